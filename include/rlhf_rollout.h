@@ -1,0 +1,138 @@
+/*
+ * rlhf_rollout.h -- C ABI of the MI355X (gfx950) rollout + rescoring library.
+ *
+ * The library runs the two inference stages of one PPO iteration of RLHF on a GPT-NeoX /
+ * Pythia-shaped policy:
+ *   rollout_generate : left-padded query batch -> a fixed number of tokens sampled at a temperature,
+ *                      truncated at the first EOS            (paper: Dataset Details, "left pad the
+ *                      queries"; PPO hyperparameter table, "Sampling Temperature"; PPO Details,
+ *                      "EOS trick", steps 1-2)
+ *   score_sequences  : teacher-forced forward over the (B, query+response) batch -> per-token
+ *                      log-probabilities and values           (paper: Preliminaries, Eq. (RL), KL term;
+ *                      General Details, "Disable dropout"; Reward Model Details, "Minor numerical
+ *                      differences ..." for the mask; PPO Details, "Value model initializes from the
+ *                      reward model" / Preliminaries Step 2 for the scalar linear head)
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative rlhf_status; it never throws or aborts.
+ *     rlhf_last_error() gives a thread-local message for the last failure on the calling thread.
+ *   - "dev" pointers are HIP device pointers, "host" pointers ordinary host memory.  The caller owns
+ *     every buffer, the workspace included; the handle owns only small device tables (rotary
+ *     cos/sin) it creates in rlhf_create and frees in rlhf_destroy.
+ *   - All work is enqueued on the hipStream_t passed as `stream` (NULL = the default stream).  The
+ *     calls do not synchronise with the host: outputs are valid once the stream has run the call's
+ *     work.  Sizes that depend on the mask (number of real tokens) stay on the device.
+ *   - Results are deterministic functions of the inputs: no floating-point atomics are used.
+ *   - Calls that share a workspace must not overlap in time.
+ */
+#ifndef RLHF_ROLLOUT_H
+#define RLHF_ROLLOUT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  RLHF_OK = 0,
+  RLHF_EINVAL = -1,       /* null pointer, bad shape, temperature <= 0, max_new_tokens <= 0, ... */
+  RLHF_ENOMEM = -2,       /* workspace smaller than rlhf_workspace_bytes reports */
+  RLHF_EHIP = -3,         /* a HIP runtime call failed */
+  RLHF_EUNSUPPORTED = -4  /* dtype / head_dim / size outside what the kernels are built for */
+} rlhf_status;
+
+enum { RLHF_DTYPE_FP32 = 0, RLHF_DTYPE_BF16 = 1 };
+
+/* Model shape.  Architecture: pre-LayerNorm decoder with parallel residual
+ * x <- x + Attn(LN1(x)) + MLP(LN2(x)), exact-erf GELU, rotary embedding on the first rotary_dims
+ * of every head (pairs (i, i + rotary_dims/2), angle pos * rope_base^(-2i/rotary_dims)), softmax
+ * scale 1/sqrt(head_dim), final LayerNorm before the untied, bias-free LM head and the value head.
+ * d_model must equal n_heads * head_dim; rotary_dims must be even and <= head_dim. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, head_dim, rotary_dims, d_ff, vocab;
+  int32_t dtype;          /* RLHF_DTYPE_FP32 (check mode) or RLHF_DTYPE_BF16: type of every weight */
+  int32_t eos_id, pad_id; /* pad_id is written after EOS and never read as an input embedding */
+  float ln_eps, rope_base;
+} rlhf_model_config;
+
+/* Weights: DEVICE pointers, read-only, caller-owned, must outlive the handle.  Matrices are
+ * row-major [out_features, in_features] (y = x W^T + b).  The per-layer members are HOST arrays of
+ * n_layers device pointers (the arrays themselves are only read inside rlhf_create). */
+typedef struct {
+  const void *embed_in;        /* [vocab, d_model] */
+  const void *const *ln1_g, *const *ln1_b, *const *ln2_g, *const *ln2_b; /* [d_model] each */
+  const void *const *w_qkv, *const *b_qkv; /* [3*d_model, d_model], rows: q of all heads | k | v; [3*d_model] */
+  const void *const *w_o, *const *b_o;     /* [d_model, d_model]; [d_model] */
+  const void *const *w_fc1, *const *b_fc1; /* [d_ff, d_model]; [d_ff] */
+  const void *const *w_fc2, *const *b_fc2; /* [d_model, d_ff]; [d_model] */
+  const void *lnf_g, *lnf_b;   /* [d_model] */
+  const void *embed_out;       /* [vocab, d_model] */
+  const void *value_w;         /* [d_model], or NULL: values are then not computed */
+  float value_b;
+} rlhf_weights;
+
+typedef struct rlhf_handle rlhf_handle;
+
+/* Creates a handle for one model on the current HIP device.  Allocates the rotary tables
+ * (synchronous).  *out is NULL on failure. */
+int rlhf_create(const rlhf_model_config *cfg, const rlhf_weights *w, rlhf_handle **out);
+void rlhf_destroy(rlhf_handle *h);
+
+/* Bytes of device workspace that rollout_generate(B, Lq, max_new) and score_sequences(B, L_score)
+ * need (the maximum of the two; pass 0 for a call you will not make). */
+int rlhf_workspace_bytes(const rlhf_handle *h, int32_t B, int32_t Lq, int32_t max_new, int32_t L_score,
+                         size_t *out);
+
+/* Rollout.  queries: dev int32 [B, Lq], left-padded; pad_mask: dev uint8 [B, Lq], 1 = real token
+ * (each row's real tokens are its last n_b slots).  Positions count real tokens only and padding
+ * never enters attention.  Step t of row b samples argmax_v(logits_v / temperature + g) with
+ * Gumbel noise g from a counter hash keyed (seed, seq_id_base + b, t, v); ties go to the lowest id.
+ * Outputs (dev):
+ *   out_tokens   int32 [B, Lq + max_new]: the query copied, then the response; pad_id after EOS
+ *   out_logprobs float [B, max_new]: log softmax(logits/temperature)[token]; 0 after EOS
+ *   out_lengths  int32 [B]: response tokens up to and including EOS (max_new if none; 0 for an
+ *                all-pad row, whose outputs are all pad_id / 0)
+ * One prefill pass and max_new-1 single-token passes are run. */
+int rollout_generate(rlhf_handle *h, const int32_t *queries, const uint8_t *pad_mask, int32_t B, int32_t Lq,
+                     uint64_t seed, uint64_t seq_id_base, float temperature, int32_t max_new_tokens,
+                     int32_t *out_tokens, float *out_logprobs, int32_t *out_lengths,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* Rescoring.  tokens: dev int32 [B, L]; mask: dev uint8 [B, L], 1 = real; the real tokens of a row
+ * must form one contiguous run (left pads from the query, right pads after EOS).
+ * Outputs (dev float [B, L]):
+ *   out_logprobs[b,t] = log softmax(logits[b,t-1]/temperature)[tokens[b,t]] where t and t-1 are
+ *                       real; 0 elsewhere (so 0 at pads and at the first real token)
+ *   out_values[b,t]   = value_w . LN_f(x[b,t]) + value_b at real t (unshifted); 0 elsewhere.
+ *                       May be NULL. */
+int score_sequences(rlhf_handle *h, const int32_t *tokens, const uint8_t *mask, int32_t B, int32_t L,
+                    float temperature, float *out_logprobs, float *out_values,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* Debug / parity aid: raw (pre-temperature) fp32 logits of the same forward pass as
+ * score_sequences at n (row, column) pairs.  rows_bt: HOST int32 [n, 2]; out_logits: dev float
+ * [n, vocab].  Every pair must name a real position. */
+int rlhf_debug_logits_rows(rlhf_handle *h, const int32_t *tokens, const uint8_t *mask, int32_t B, int32_t L,
+                           const int32_t *rows_bt, int32_t n, float *out_logits,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Per-kernel timing for benchmarks.  While enabled, every kernel launch of this handle is bracketed
+ * by HIP events on the call's stream.  rlhf_profile_read synchronises the stream's events, then
+ * fills up to `cap` entries: names[i] (static strings), total_ms[i], launches[i]; *n_out = number
+ * of kernel classes seen.  Reading clears the record. */
+int rlhf_profile_enable(rlhf_handle *h, int32_t on);
+int rlhf_profile_read(rlhf_handle *h, int32_t cap, const char **names, double *total_ms, int64_t *launches,
+                      int32_t *n_out);
+
+/* Marks on the stream between the phases of the last rollout_generate: milliseconds spent in the
+ * prefill pass and in the decode loop (synchronises on the call's last event). */
+int rlhf_last_rollout_phases(rlhf_handle *h, double *prefill_ms, double *decode_ms);
+
+const char *rlhf_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RLHF_ROLLOUT_H */

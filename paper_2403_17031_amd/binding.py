@@ -1,0 +1,216 @@
+"""ctypes binding of librlhf_rollout.so.  Argument marshalling only: every step of the rollout
+and rescoring path runs in the library's HIP kernels.  PyTorch provides device memory and the
+stream handle, nothing else.  There is no CPU fallback: a missing library is an error."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librlhf_rollout.so")
+
+EXPORTS = (
+    "rlhf_create", "rlhf_destroy", "rlhf_workspace_bytes", "rollout_generate", "score_sequences",
+    "rlhf_debug_logits_rows", "rlhf_profile_enable", "rlhf_profile_read", "rlhf_last_rollout_phases",
+    "rlhf_last_error",
+)
+
+_PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+class RlhfError(RuntimeError):
+    pass
+
+
+class _Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "head_dim", "rotary_dims", "d_ff",
+                                         "vocab", "dtype", "eos_id", "pad_id")] + \
+               [("ln_eps", C.c_float), ("rope_base", C.c_float)]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("embed_in", C.c_void_p)] + [(n, C.POINTER(C.c_void_p)) for n in _PER_LAYER] + \
+               [("lnf_g", C.c_void_p), ("lnf_b", C.c_void_p), ("embed_out", C.c_void_p), ("value_w", C.c_void_p),
+                ("value_b", C.c_float)]
+
+
+_lib = None
+
+
+def load_library():
+    """Loads the built library; raises if it has not been built (python -m paper_2403_17031_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RlhfError(f"{LIB_PATH} is missing: build it with `python -m paper_2403_17031_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, u64, f32, sz = C.c_void_p, C.c_int32, C.c_uint64, C.c_float, C.c_size_t
+    lib.rlhf_create.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(vp)]
+    lib.rlhf_destroy.argtypes = [vp]
+    lib.rlhf_destroy.restype = None
+    lib.rlhf_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz)]
+    lib.rollout_generate.argtypes = [vp, vp, vp, i32, i32, u64, u64, f32, i32, vp, vp, vp, vp, sz, vp]
+    lib.score_sequences.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.rlhf_debug_logits_rows.argtypes = [vp, vp, vp, i32, i32, C.POINTER(i32), i32, vp, vp, sz, vp]
+    lib.rlhf_profile_enable.argtypes = [vp, i32]
+    lib.rlhf_profile_read.argtypes = [vp, i32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
+                                      C.POINTER(C.c_int64), C.POINTER(i32)]
+    lib.rlhf_last_rollout_phases.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.rlhf_last_error.restype = C.c_char_p
+    for n in EXPORTS:
+        if n not in ("rlhf_destroy", "rlhf_last_error"):
+            getattr(lib, n).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def exported_symbols():
+    lib = load_library()
+    return [n for n in EXPORTS if hasattr(lib, n)]
+
+
+def _check(rc):
+    if rc != 0:
+        raise RlhfError(f"rlhf error {rc}: {load_library().rlhf_last_error().decode()}")
+
+
+class Policy:
+    """A model resident on the GPU plus a workspace; wraps one rlhf_handle."""
+
+    def __init__(self, cfg, weights: dict, device="cuda:0"):
+        """cfg: synth.ModelConfig-like object; weights: name -> float32 numpy array (already rounded to
+        bf16 values when cfg.dtype == 'bf16'), plus scalar 'value_b'."""
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self.lib = load_library()
+        self.tdtype = torch.float32 if cfg.dtype == "fp32" else torch.bfloat16
+        self._dev = {}
+        for name, arr in weights.items():
+            if name == "value_b":
+                continue
+            t = torch.from_numpy(np.ascontiguousarray(arr))
+            # the values are exactly representable in the storage type, so this conversion is lossless
+            self._dev[name] = t.to(self.device, dtype=self.tdtype).contiguous()
+        c = _Config(cfg.n_layers, cfg.d_model, cfg.n_heads, cfg.head_dim, cfg.rotary_dims, cfg.d_ff, cfg.vocab,
+                    0 if cfg.dtype == "fp32" else 1, cfg.eos_id, cfg.pad_id, cfg.ln_eps, cfg.rope_base)
+        w = _Weights()
+        self._arrays = []
+        for n in _PER_LAYER:
+            arr = (C.c_void_p * max(cfg.n_layers, 1))(*[self._dev[f"layers.{l}.{n}"].data_ptr()
+                                                         for l in range(cfg.n_layers)])
+            self._arrays.append(arr)
+            setattr(w, n, C.cast(arr, C.POINTER(C.c_void_p)))
+        for n in ("embed_in", "lnf_g", "lnf_b", "embed_out"):
+            setattr(w, n, self._dev[n].data_ptr())
+        w.value_w = self._dev["value_w"].data_ptr() if "value_w" in self._dev else None
+        w.value_b = float(weights.get("value_b", 0.0))
+        self._h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(self.lib.rlhf_create(C.byref(c), C.byref(w), C.byref(self._h)))
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self.lib.rlhf_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ------------------------------------------------------------------ workspace
+    def workspace_bytes(self, B, Lq, max_new, L_score):
+        out = C.c_size_t()
+        _check(self.lib.rlhf_workspace_bytes(self._h, B, Lq, max_new, L_score, C.byref(out)))
+        return out.value
+
+    def _workspace(self, nbytes):
+        torch = self.torch
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = None
+            self._ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def _stream(self):
+        return C.c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
+
+    # ------------------------------------------------------------------ calls
+    def rollout_generate(self, queries, pad_mask, seed, temperature, max_new_tokens, seq_id_base=0):
+        """queries int32 [B, Lq], pad_mask uint8 [B, Lq] (torch CUDA tensors or numpy arrays).
+        Returns CUDA tensors: tokens int32 [B, Lq+N], logprobs float32 [B, N], lengths int32 [B]."""
+        torch = self.torch
+        q = self._to_dev(queries, torch.int32)
+        m = self._to_dev(pad_mask, torch.uint8)
+        B, Lq = q.shape
+        N = int(max_new_tokens)
+        ws = self._workspace(self.workspace_bytes(B, Lq, max(N, 1), 0))
+        toks = torch.empty((B, Lq + max(N, 0)), dtype=torch.int32, device=self.device)
+        lps = torch.empty((B, max(N, 0)), dtype=torch.float32, device=self.device)
+        lens = torch.empty((B,), dtype=torch.int32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(self.lib.rollout_generate(self._h, q.data_ptr(), m.data_ptr(), B, Lq, C.c_uint64(seed),
+                                             C.c_uint64(seq_id_base), temperature, N, toks.data_ptr(),
+                                             lps.data_ptr(), lens.data_ptr(), ws.data_ptr(), ws.numel(),
+                                             self._stream()))
+        return toks, lps, lens
+
+    def score_sequences(self, tokens, mask, temperature, want_values=True):
+        """tokens int32 [B, L], mask uint8 [B, L].  Returns (logprobs, values) float32 [B, L] CUDA tensors."""
+        torch = self.torch
+        t = self._to_dev(tokens, torch.int32)
+        m = self._to_dev(mask, torch.uint8)
+        B, L = t.shape
+        ws = self._workspace(self.workspace_bytes(B, 0, 0, L))
+        lp = torch.empty((B, L), dtype=torch.float32, device=self.device)
+        val = torch.empty((B, L), dtype=torch.float32, device=self.device) if want_values else None
+        with torch.cuda.device(self.device):
+            _check(self.lib.score_sequences(self._h, t.data_ptr(), m.data_ptr(), B, L, temperature, lp.data_ptr(),
+                                            val.data_ptr() if want_values else None, ws.data_ptr(), ws.numel(),
+                                            self._stream()))
+        return lp, val
+
+    def debug_logits_rows(self, tokens, mask, rows_bt):
+        torch = self.torch
+        t = self._to_dev(tokens, torch.int32)
+        m = self._to_dev(mask, torch.uint8)
+        B, L = t.shape
+        rows = np.ascontiguousarray(np.asarray(rows_bt, dtype=np.int32).reshape(-1, 2))
+        n = rows.shape[0]
+        ws = self._workspace(self.workspace_bytes(B, 0, 0, L))
+        out = torch.empty((n, self.cfg.vocab), dtype=torch.float32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(self.lib.rlhf_debug_logits_rows(self._h, t.data_ptr(), m.data_ptr(), B, L,
+                                                   rows.ctypes.data_as(C.POINTER(C.c_int32)), n, out.data_ptr(),
+                                                   ws.data_ptr(), ws.numel(), self._stream()))
+        return out
+
+    # ------------------------------------------------------------------ timing aids
+    def profile_enable(self, on=True):
+        _check(self.lib.rlhf_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self):
+        cap = 64
+        names = (C.c_char_p * cap)()
+        ms = (C.c_double * cap)()
+        cnt = (C.c_int64 * cap)()
+        n = C.c_int32()
+        _check(self.lib.rlhf_profile_read(self._h, cap, names, ms, cnt, C.byref(n)))
+        return {names[i].decode(): (ms[i], cnt[i]) for i in range(min(n.value, cap))}
+
+    def last_rollout_phases(self):
+        a, b = C.c_double(), C.c_double()
+        _check(self.lib.rlhf_last_rollout_phases(self._h, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def _to_dev(self, x, dtype):
+        torch = self.torch
+        if isinstance(x, np.ndarray):
+            x = torch.from_numpy(np.ascontiguousarray(x))
+        return x.to(self.device, dtype=dtype).contiguous()

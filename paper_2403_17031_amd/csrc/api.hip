@@ -1,0 +1,616 @@
+// C ABI and host-side orchestration: validates arguments, carves the caller's workspace and
+// enqueues the kernels of rollout_generate / score_sequences on the caller's stream.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/rlhf_rollout.h"
+#include "common.h"
+
+using namespace rlhf;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string& msg) {
+  g_err = msg;
+  return code;
+}
+
+#define HIP_OK(expr)                                                                              \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess)                                                                         \
+      return fail(RLHF_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_));                  \
+  } while (0)
+
+constexpr int kMaxPos = 8192;
+constexpr int kLogitChunk = 4096;  // rows of fp32 logits materialised at a time while scoring
+
+struct Carver {  // bump allocator over the workspace; base == nullptr only measures
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base((char*)b) {}
+  template <typename T>
+  T* take(size_t n) {
+    off = (off + 255) & ~(size_t)255;
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+  void* take_bytes(size_t n) { return take<char>(n); }
+};
+
+struct Meta {
+  int *start, *len, *cu, *kvoff, *total, *pos, *rowid, *tok;
+};
+struct Acts {
+  float* x;
+  void *a, *m, *qkv, *q, *att, *ffn;
+};
+
+}  // namespace
+
+struct rlhf_handle {
+  rlhf_model_config cfg;
+  rlhf_weights w;
+  std::vector<const void*> ln1_g, ln1_b, ln2_g, ln2_b, w_qkv, b_qkv, w_o, b_o, w_fc1, b_fc1, w_fc2, b_fc2;
+  float *rope_cos = nullptr, *rope_sin = nullptr;
+  void* w16 = nullptr;                // bf16 mode: fp16 copies of the matrices the GEMMs read
+  const void* embed_out_mm = nullptr; // LM-head operand (the caller's in fp32 mode, the copy in bf16 mode)
+  size_t esz = 2;
+  // profiling
+  bool prof_on = false;
+  std::vector<const char*> prof_names;
+  std::vector<hipEvent_t> prof_ev;  // pairs
+  std::vector<hipEvent_t> ev_pool;
+  size_t ev_used = 0;
+  hipEvent_t ph[3] = {nullptr, nullptr, nullptr};
+  bool ph_valid = false;
+
+  hipEvent_t get_event() {
+    if (ev_used == ev_pool.size()) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      ev_pool.push_back(e);
+    }
+    return ev_pool[ev_used++];
+  }
+};
+
+namespace {
+
+struct ProfScope {
+  rlhf_handle* h;
+  hipStream_t s;
+  ProfScope(rlhf_handle* h_, const char* name, hipStream_t s_) : h(h_), s(s_) {
+    if (!h->prof_on) return;
+    hipEvent_t e = h->get_event();
+    if (!e) return;
+    (void)hipEventRecord(e, s);
+    h->prof_names.push_back(name);
+    h->prof_ev.push_back(e);
+  }
+  ~ProfScope() {
+    if (!h->prof_on) return;
+    hipEvent_t e = h->get_event();
+    if (!e) return;
+    (void)hipEventRecord(e, s);
+    h->prof_ev.push_back(e);
+  }
+};
+
+#define LAUNCH(name, call)                                                                        \
+  do {                                                                                            \
+    hipError_t e_;                                                                                \
+    {                                                                                             \
+      ProfScope ps_(h, name, s);                                                                  \
+      e_ = (call);                                                                                \
+    }                                                                                             \
+    if (e_ != hipSuccess) return fail(RLHF_EHIP, std::string(name) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+Meta carve_meta(Carver& c, int B, size_t Tmax) {
+  Meta m;
+  m.start = c.take<int>(B);
+  m.len = c.take<int>(B);
+  m.cu = c.take<int>(B + 1);
+  m.kvoff = c.take<int>(B + 1);
+  m.total = c.take<int>(2);
+  m.pos = c.take<int>(Tmax);
+  m.rowid = c.take<int>(Tmax);
+  m.tok = c.take<int>(Tmax);
+  return m;
+}
+
+Acts carve_acts(Carver& c, const rlhf_model_config& cfg, size_t rows, size_t esz) {
+  Acts a;
+  const size_t d = cfg.d_model;
+  a.x = c.take<float>(rows * d);
+  a.a = c.take_bytes(rows * d * esz);
+  a.m = c.take_bytes(rows * d * esz);
+  a.qkv = c.take_bytes(rows * 3 * d * esz);
+  a.q = c.take_bytes(rows * d * esz);
+  a.att = c.take_bytes(rows * d * esz);
+  a.ffn = c.take_bytes(rows * (size_t)cfg.d_ff * esz);
+  return a;
+}
+
+struct RolloutWs {
+  Meta meta;
+  Acts acts;
+  int *finished, *cur_tok;
+  void* hl;
+  float* logits;
+  char* kv;
+  size_t kv_slots;
+};
+RolloutWs carve_rollout(Carver& c, const rlhf_model_config& cfg, int B, int Lq, int N, size_t esz) {
+  RolloutWs w;
+  const size_t Tmax = (size_t)B * Lq;
+  w.meta = carve_meta(c, B, Tmax);
+  w.acts = carve_acts(c, cfg, Tmax, esz);
+  w.finished = c.take<int>(B);
+  w.cur_tok = c.take<int>(B);
+  w.hl = c.take_bytes((size_t)B * cfg.d_model * esz);
+  w.logits = c.take<float>((size_t)B * cfg.vocab);
+  w.kv_slots = (size_t)B * (Lq + N - 1);
+  w.kv = (char*)c.take_bytes((size_t)cfg.n_layers * 2 * w.kv_slots * cfg.d_model * esz);
+  return w;
+}
+
+struct ScoreWs {
+  Meta meta;
+  Acts acts;
+  char* kv;  // one layer: [2][H][Tmax][hd]
+  float *val, *lp, *logits;
+  int* idx;
+  int32_t* rows_dev;
+  size_t Tmax;
+  int chunk;
+};
+ScoreWs carve_score(Carver& c, const rlhf_model_config& cfg, int B, int L, size_t esz) {
+  ScoreWs w;
+  w.Tmax = (size_t)B * L;
+  w.meta = carve_meta(c, B, w.Tmax);
+  w.acts = carve_acts(c, cfg, w.Tmax, esz);
+  w.kv = (char*)c.take_bytes(2 * w.Tmax * cfg.d_model * esz);
+  w.val = c.take<float>(w.Tmax);
+  w.lp = c.take<float>(w.Tmax);
+  w.chunk = (int)std::min<size_t>(w.Tmax, kLogitChunk);
+  w.logits = c.take<float>((size_t)w.chunk * cfg.vocab);
+  w.idx = c.take<int>(w.Tmax);
+  w.rows_dev = c.take<int32_t>(2 * w.Tmax);
+  return w;
+}
+
+// One pass through all decoder layers.  mode 0: packed causal attention over whole sequences
+// (prefill, scoring); mode 1: one new row per sequence against the cache (decode).
+struct PassArgs {
+  int mode;
+  int rows_max;
+  const int* rows_dev;
+  const int* pos;
+  int pos_add;
+  const int* rowid;
+  const int* kvoff;
+  const int* len;
+  const int* cu;
+  int B, Lmax;
+  int ctx_add, ctx_max;
+  char* kv;            // layer l: K at kv + (2l)*kv_layer_bytes/2 ...
+  size_t kv_slots;     // slots per head
+  bool kv_per_layer;   // false: every layer reuses the same single-layer scratch
+};
+
+int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) {
+  const rlhf_model_config& c = h->cfg;
+  const int d = c.d_model, dt = c.dtype;
+  const size_t plane = p.kv_slots * (size_t)d * h->esz;  // bytes of one K (or V) plane of one layer
+  const long head_stride = (long)(p.kv_slots * (size_t)c.head_dim);
+  for (int l = 0; l < c.n_layers; ++l) {
+    char* kc = p.kv + (p.kv_per_layer ? (size_t)l * 2 * plane : 0);
+    char* vc = kc + plane;
+    LAUNCH("layernorm", launch_layernorm(dt, A.x, p.rows_max, p.rows_dev, d, c.ln_eps, h->ln1_g[l], h->ln1_b[l],
+                                         A.a, h->ln2_g[l], h->ln2_b[l], A.m, s));
+    GemmArgs g;
+    g.M_max = p.rows_max;
+    g.M_dev = p.rows_dev;
+    g.A = A.a; g.W = h->w_qkv[l]; g.bias = h->b_qkv[l]; g.out = A.qkv; g.N = 3 * d; g.K = d; g.ldo = 3 * d;
+    g.epilogue = EPI_BIAS;
+    LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
+    LAUNCH("rope_kv", launch_rope_kv(dt, A.qkv, p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff,
+                                     c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q, kc, vc,
+                                     head_stride, s));
+    if (p.mode == 0)
+      LAUNCH("attn_prefill", launch_attn_prefill(dt, A.q, kc, vc, head_stride, p.B, p.Lmax, p.len, p.cu, p.kvoff,
+                                                 c.n_heads, c.head_dim, A.att, s));
+    else
+      LAUNCH("attn_decode", launch_attn_decode(dt, A.q, kc, vc, head_stride, p.B, p.len, p.ctx_add, p.ctx_max,
+                                               p.kvoff, c.n_heads, c.head_dim, A.att, s));
+    g.A = A.att; g.W = h->w_o[l]; g.bias = h->b_o[l]; g.out = A.x; g.N = d; g.K = d; g.ldo = d;
+    g.epilogue = EPI_BIAS_RESADD;
+    LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
+    g.A = A.m; g.W = h->w_fc1[l]; g.bias = h->b_fc1[l]; g.out = A.ffn; g.N = c.d_ff; g.K = d; g.ldo = c.d_ff;
+    g.epilogue = EPI_BIAS_GELU;
+    LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
+    g.A = A.ffn; g.W = h->w_fc2[l]; g.bias = h->b_fc2[l]; g.out = A.x; g.N = d; g.K = c.d_ff; g.ldo = d;
+    g.epilogue = EPI_BIAS_RESADD;
+    LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
+  }
+  return RLHF_OK;
+}
+
+int check_common(const rlhf_handle* h, int B, int L) {
+  if (!h) return fail(RLHF_EINVAL, "null handle");
+  if (B <= 0 || L <= 0) return fail(RLHF_EINVAL, "batch and length must be positive");
+  if ((size_t)B * (size_t)L > (size_t)1 << 30) return fail(RLHF_EUNSUPPORTED, "batch * length too large");
+  if (L > kMaxPos) return fail(RLHF_EUNSUPPORTED, "sequence longer than the rotary table");
+  return RLHF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rlhf_last_error(void) { return g_err.c_str(); }
+
+int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, rlhf_handle** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !w || !out) return fail(RLHF_EINVAL, "null argument");
+  const rlhf_model_config& c = *cfg;
+  if (c.n_layers < 0 || c.d_model <= 0 || c.n_heads <= 0 || c.head_dim <= 0 || c.d_ff <= 0 || c.vocab <= 0)
+    return fail(RLHF_EINVAL, "non-positive model dimension");
+  if (c.d_model != c.n_heads * c.head_dim) return fail(RLHF_EINVAL, "d_model != n_heads * head_dim");
+  if (c.rotary_dims < 0 || (c.rotary_dims & 1) || c.rotary_dims > c.head_dim)
+    return fail(RLHF_EINVAL, "rotary_dims must be even and <= head_dim");
+  if (c.dtype != RLHF_DTYPE_FP32 && c.dtype != RLHF_DTYPE_BF16) return fail(RLHF_EUNSUPPORTED, "unknown dtype");
+  if (c.head_dim > 256) return fail(RLHF_EUNSUPPORTED, "head_dim > 256");
+  if (c.dtype == RLHF_DTYPE_BF16 && ((c.d_model % 8) || (c.d_ff % 8)))
+    return fail(RLHF_EUNSUPPORTED, "bf16 needs d_model and d_ff to be multiples of 8");
+  if (c.eos_id < 0 || c.eos_id >= c.vocab || c.pad_id < 0) return fail(RLHF_EINVAL, "bad eos/pad id");
+  if (!(c.ln_eps > 0.f) || !(c.rope_base > 0.f)) return fail(RLHF_EINVAL, "ln_eps and rope_base must be > 0");
+  if (!w->embed_in || !w->embed_out || !w->lnf_g || !w->lnf_b) return fail(RLHF_EINVAL, "null weight pointer");
+  const void* const* per_layer[12] = {w->ln1_g, w->ln1_b, w->ln2_g, w->ln2_b, w->w_qkv, w->b_qkv,
+                                      w->w_o,   w->b_o,   w->w_fc1, w->b_fc1, w->w_fc2, w->b_fc2};
+  for (auto p : per_layer) {
+    if (c.n_layers > 0 && !p) return fail(RLHF_EINVAL, "null per-layer pointer array");
+    for (int l = 0; l < c.n_layers; ++l)
+      if (!p[l]) return fail(RLHF_EINVAL, "null per-layer weight pointer");
+  }
+  rlhf_handle* h = new (std::nothrow) rlhf_handle();
+  if (!h) return fail(RLHF_ENOMEM, "host allocation failed");
+  h->cfg = c;
+  h->w = *w;
+  h->esz = c.dtype == RLHF_DTYPE_FP32 ? 4 : 2;
+  std::vector<const void*>* dst[12] = {&h->ln1_g, &h->ln1_b, &h->ln2_g, &h->ln2_b, &h->w_qkv, &h->b_qkv,
+                                       &h->w_o,   &h->b_o,   &h->w_fc1, &h->b_fc1, &h->w_fc2, &h->b_fc2};
+  for (int i = 0; i < 12; ++i) dst[i]->assign(per_layer[i], per_layer[i] + c.n_layers);
+  // rotary tables, evaluated in double on the host: angle(p, i) = p * base^(-2i/r)
+  const int half = c.rotary_dims / 2;
+  if (half > 0) {
+    std::vector<float> cs((size_t)kMaxPos * half), sn((size_t)kMaxPos * half);
+    for (int p = 0; p < kMaxPos; ++p)
+      for (int i = 0; i < half; ++i) {
+        const double ang = (double)p * std::pow((double)c.rope_base, -2.0 * i / c.rotary_dims);
+        cs[(size_t)p * half + i] = (float)std::cos(ang);
+        sn[(size_t)p * half + i] = (float)std::sin(ang);
+      }
+    hipError_t e = hipMalloc((void**)&h->rope_cos, cs.size() * 4);
+    if (e == hipSuccess) e = hipMalloc((void**)&h->rope_sin, sn.size() * 4);
+    if (e == hipSuccess) e = hipMemcpy(h->rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(h->rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      rlhf_destroy(h);
+      return fail(RLHF_EHIP, std::string("rotary tables: ") + hipGetErrorString(e));
+    }
+  }
+  // bf16 mode: the matrix cores take fp16 operands; convert the five matrix families once
+  h->embed_out_mm = w->embed_out;
+  if (c.dtype == RLHF_DTYPE_BF16) {
+    const size_t d = c.d_model, F = c.d_ff;
+    const size_t per_layer_elems = 3 * d * d + d * d + 2 * d * F;
+    const size_t total = per_layer_elems * c.n_layers + (size_t)c.vocab * d;
+    hipError_t e = hipMalloc(&h->w16, total * 2);
+    if (e != hipSuccess) {
+      rlhf_destroy(h);
+      return fail(RLHF_EHIP, std::string("fp16 weight copy: ") + hipGetErrorString(e));
+    }
+    char* p = (char*)h->w16;
+    auto conv = [&](const void*& slot, size_t n) {
+      if (e == hipSuccess) e = launch_bf16_to_f16(slot, p, n, nullptr);
+      slot = p;
+      p += n * 2;
+    };
+    for (int l = 0; l < c.n_layers; ++l) {
+      conv(h->w_qkv[l], 3 * d * d);
+      conv(h->w_o[l], d * d);
+      conv(h->w_fc1[l], d * F);
+      conv(h->w_fc2[l], d * F);
+    }
+    conv(h->embed_out_mm, (size_t)c.vocab * d);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+      rlhf_destroy(h);
+      return fail(RLHF_EHIP, std::string("fp16 weight conversion: ") + hipGetErrorString(e));
+    }
+  }
+  *out = h;
+  return RLHF_OK;
+}
+
+void rlhf_destroy(rlhf_handle* h) {
+  if (!h) return;
+  if (h->w16) (void)hipFree(h->w16);
+  if (h->rope_cos) (void)hipFree(h->rope_cos);
+  if (h->rope_sin) (void)hipFree(h->rope_sin);
+  for (hipEvent_t e : h->ev_pool) (void)hipEventDestroy(e);
+  for (hipEvent_t e : h->ph)
+    if (e) (void)hipEventDestroy(e);
+  delete h;
+}
+
+int rlhf_workspace_bytes(const rlhf_handle* h, int32_t B, int32_t Lq, int32_t max_new, int32_t L_score,
+                         size_t* out) {
+  if (!h || !out) return fail(RLHF_EINVAL, "null argument");
+  if (B <= 0) return fail(RLHF_EINVAL, "batch must be positive");
+  size_t need = 0;
+  if (Lq > 0 && max_new > 0) {
+    Carver c(nullptr);
+    carve_rollout(c, h->cfg, B, Lq, max_new, h->esz);
+    need = std::max(need, c.off);
+  }
+  if (L_score > 0) {
+    Carver c(nullptr);
+    carve_score(c, h->cfg, B, L_score, h->esz);
+    need = std::max(need, c.off);
+  }
+  *out = need + 256;
+  return RLHF_OK;
+}
+
+int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_mask, int32_t B, int32_t Lq,
+                     uint64_t seed, uint64_t seq_id_base, float temperature, int32_t max_new_tokens,
+                     int32_t* out_tokens, float* out_logprobs, int32_t* out_lengths, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+  int rc = check_common(h, B, Lq);
+  if (rc) return rc;
+  if (max_new_tokens <= 0) return fail(RLHF_EINVAL, "max_new_tokens must be > 0");
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return fail(RLHF_EINVAL, "temperature must be > 0");
+  if (!queries || !pad_mask || !out_tokens || !out_logprobs || !out_lengths || !workspace)
+    return fail(RLHF_EINVAL, "null pointer argument");
+  if ((long)Lq + max_new_tokens > kMaxPos) return fail(RLHF_EUNSUPPORTED, "Lq + max_new_tokens too large");
+  const rlhf_model_config& c = h->cfg;
+  const int N = max_new_tokens;
+  Carver cv((void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255));
+  RolloutWs ws = carve_rollout(cv, c, B, Lq, N, h->esz);
+  if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
+    return fail(RLHF_ENOMEM, "workspace too small for rollout_generate");
+  hipStream_t s = (hipStream_t)stream;
+  const int dt = c.dtype, d = c.d_model;
+  for (int i = 0; i < 3; ++i)
+    if (!h->ph[i]) HIP_OK(hipEventCreate(&h->ph[i]));
+  h->ph_valid = false;
+  HIP_OK(hipEventRecord(h->ph[0], s));
+
+  const Meta& m = ws.meta;
+  LAUNCH("copy_queries", launch_copy_queries(queries, B, Lq, N, c.pad_id, out_tokens, s));
+  LAUNCH("row_spans", launch_row_spans(pad_mask, B, Lq, N - 1, m.start, m.len, m.cu, m.kvoff, m.total, s));
+  LAUNCH("pack_embed", launch_pack_embed(dt, queries, B, Lq, m.start, m.len, m.cu, h->w.embed_in, d, c.vocab,
+                                         m.pos, m.rowid, m.tok, ws.acts.x, s));
+  PassArgs p;
+  p.mode = 0;
+  p.rows_max = B * Lq;
+  p.rows_dev = m.total;
+  p.pos = m.pos;
+  p.pos_add = 0;
+  p.rowid = m.rowid;
+  p.kvoff = m.kvoff;
+  p.len = m.len;
+  p.cu = m.cu;
+  p.B = B;
+  p.Lmax = Lq;
+  p.ctx_add = 0;
+  p.ctx_max = Lq + N;
+  p.kv = ws.kv;
+  p.kv_slots = ws.kv_slots;
+  p.kv_per_layer = true;
+  rc = run_layers(h, ws.acts, p, s);
+  if (rc) return rc;
+
+  SampleArgs sa;
+  sa.logits = ws.logits;
+  sa.B = B; sa.V = c.vocab; sa.Lq = Lq; sa.N = N;
+  sa.seed = seed; sa.seq_base = seq_id_base; sa.temperature = temperature;
+  sa.eos_id = c.eos_id; sa.pad_id = c.pad_id;
+  sa.len = m.len; sa.finished = ws.finished; sa.cur_tok = ws.cur_tok;
+  sa.out_tokens = out_tokens; sa.out_logprobs = out_logprobs; sa.out_lengths = out_lengths;
+
+  GemmArgs lm;
+  lm.A = ws.hl; lm.W = h->embed_out_mm; lm.bias = nullptr; lm.out = ws.logits;
+  lm.M_max = B; lm.M_dev = nullptr; lm.N = c.vocab; lm.K = d; lm.ldo = c.vocab; lm.epilogue = EPI_F32;
+
+  // last real position of every sequence: packed row cu[b+1] - 1
+  LAUNCH("final_ln", launch_final_ln(dt, ws.acts.x, m.cu + 1, -1, B, nullptr, d, c.ln_eps, h->w.lnf_g, h->w.lnf_b,
+                                     ws.hl, nullptr, 0.f, nullptr, s));
+  LAUNCH("gemm_lm_head_decode", launch_gemm(dt, lm, s));
+  sa.step = 0;
+  LAUNCH("sampler", launch_sampler(sa, s));
+  HIP_OK(hipEventRecord(h->ph[1], s));
+
+  // decode: pass t feeds the token sampled at step t (position len + t) and samples step t + 1
+  p.mode = 1;
+  p.rows_max = B;
+  p.rows_dev = nullptr;
+  p.pos = m.len;
+  p.rowid = nullptr;
+  for (int t = 0; t + 1 < N; ++t) {
+    LAUNCH("embed_rows", launch_embed_rows(dt, ws.cur_tok, B, h->w.embed_in, d, ws.acts.x, s));
+    p.pos_add = t;
+    p.ctx_add = t + 1;
+    rc = run_layers(h, ws.acts, p, s);
+    if (rc) return rc;
+    LAUNCH("final_ln", launch_final_ln(dt, ws.acts.x, nullptr, 0, B, nullptr, d, c.ln_eps, h->w.lnf_g, h->w.lnf_b,
+                                       ws.hl, nullptr, 0.f, nullptr, s));
+    LAUNCH("gemm_lm_head_decode", launch_gemm(dt, lm, s));
+    sa.step = t + 1;
+    LAUNCH("sampler", launch_sampler(sa, s));
+  }
+  HIP_OK(hipEventRecord(h->ph[2], s));
+  h->ph_valid = true;
+  return RLHF_OK;
+}
+
+static int score_forward(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, int B, int L, ScoreWs& ws,
+                         hipStream_t s) {
+  const rlhf_model_config& c = h->cfg;
+  const Meta& m = ws.meta;
+  LAUNCH("row_spans", launch_row_spans(mask, B, L, 0, m.start, m.len, m.cu, m.kvoff, m.total, s));
+  LAUNCH("pack_embed", launch_pack_embed(c.dtype, tokens, B, L, m.start, m.len, m.cu, h->w.embed_in, c.d_model,
+                                         c.vocab, m.pos, m.rowid, m.tok, ws.acts.x, s));
+  PassArgs p;
+  p.mode = 0;
+  p.rows_max = B * L;
+  p.rows_dev = m.total;
+  p.pos = m.pos;
+  p.pos_add = 0;
+  p.rowid = m.rowid;
+  p.kvoff = m.cu;  // the single-layer K/V scratch is indexed like the packed rows
+  p.len = m.len;
+  p.cu = m.cu;
+  p.B = B;
+  p.Lmax = L;
+  p.ctx_add = 0;
+  p.ctx_max = L;
+  p.kv = ws.kv;
+  p.kv_slots = ws.Tmax;
+  p.kv_per_layer = false;
+  return run_layers(h, ws.acts, p, s);
+}
+
+int score_sequences(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, int32_t B, int32_t L,
+                    float temperature, float* out_logprobs, float* out_values, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+  int rc = check_common(h, B, L);
+  if (rc) return rc;
+  if (!tokens || !mask || !out_logprobs || !workspace) return fail(RLHF_EINVAL, "null pointer argument");
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return fail(RLHF_EINVAL, "temperature must be > 0");
+  const rlhf_model_config& c = h->cfg;
+  Carver cv((void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255));
+  ScoreWs ws = carve_score(cv, c, B, L, h->esz);
+  if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
+    return fail(RLHF_ENOMEM, "workspace too small for score_sequences");
+  hipStream_t s = (hipStream_t)stream;
+  rc = score_forward(h, tokens, mask, B, L, ws, s);
+  if (rc) return rc;
+  const Meta& m = ws.meta;
+  const int dt = c.dtype, d = c.d_model;
+  const int Tmax = B * L;
+  // final LayerNorm of every packed row (into the LN1 buffer, free by now) + value head
+  LAUNCH("final_ln", launch_final_ln(dt, ws.acts.x, nullptr, 0, Tmax, m.total, d, c.ln_eps, h->w.lnf_g,
+                                     h->w.lnf_b, ws.acts.a, out_values ? h->w.value_w : nullptr, h->w.value_b,
+                                     ws.val, s));
+  for (int t0 = 0; t0 < Tmax; t0 += ws.chunk) {
+    const int rows = std::min(ws.chunk, Tmax - t0);
+    GemmArgs lm;
+    lm.A = (const char*)ws.acts.a + (size_t)t0 * d * h->esz;
+    lm.W = h->embed_out_mm; lm.bias = nullptr; lm.out = ws.logits;
+    lm.M_max = rows; lm.M_dev = m.total; lm.M_sub = t0;  // rows past the device-side token count are skipped
+    lm.N = c.vocab; lm.K = d; lm.ldo = c.vocab; lm.epilogue = EPI_F32;
+    LAUNCH("gemm_lm_head", launch_gemm(dt, lm, s));
+    LAUNCH("lse_gather", launch_lse_gather(ws.logits, rows, t0, m.total, c.vocab, temperature, m.tok, m.pos, ws.lp,
+                                           s));
+  }
+  LAUNCH("unpack_scores", launch_unpack_scores(ws.lp, (out_values && h->w.value_w) ? ws.val : nullptr, B, L, m.start,
+                                               m.len, m.cu, out_logprobs,
+                                               (out_values && h->w.value_w) ? out_values : nullptr, s));
+  return RLHF_OK;
+}
+
+int rlhf_debug_logits_rows(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, int32_t B, int32_t L,
+                           const int32_t* rows_bt, int32_t n, float* out_logits, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  int rc = check_common(h, B, L);
+  if (rc) return rc;
+  if (!tokens || !mask || !rows_bt || !out_logits || !workspace) return fail(RLHF_EINVAL, "null pointer argument");
+  if (n <= 0 || (size_t)n > (size_t)B * L) return fail(RLHF_EINVAL, "bad row count");
+  for (int i = 0; i < n; ++i)
+    if (rows_bt[2 * i] < 0 || rows_bt[2 * i] >= B || rows_bt[2 * i + 1] < 0 || rows_bt[2 * i + 1] >= L)
+      return fail(RLHF_EINVAL, "row index out of range");
+  const rlhf_model_config& c = h->cfg;
+  Carver cv((void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255));
+  ScoreWs ws = carve_score(cv, c, B, L, h->esz);
+  if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
+    return fail(RLHF_ENOMEM, "workspace too small");
+  hipStream_t s = (hipStream_t)stream;
+  rc = score_forward(h, tokens, mask, B, L, ws, s);
+  if (rc) return rc;
+  HIP_OK(hipMemcpyAsync(ws.rows_dev, rows_bt, sizeof(int32_t) * 2 * n, hipMemcpyHostToDevice, s));
+  HIP_OK(hipStreamSynchronize(s));  // rows_bt is pageable host memory: the one host sync of this debug call
+  LAUNCH("rows_to_packed", launch_rows_to_packed(ws.rows_dev, n, ws.meta.start, ws.meta.cu, ws.idx, s));
+  LAUNCH("final_ln", launch_final_ln(c.dtype, ws.acts.x, ws.idx, 0, n, nullptr, c.d_model, c.ln_eps, h->w.lnf_g,
+                                     h->w.lnf_b, ws.acts.a, nullptr, 0.f, nullptr, s));
+  GemmArgs lm;
+  lm.A = ws.acts.a; lm.W = h->embed_out_mm; lm.bias = nullptr; lm.out = out_logits;
+  lm.M_max = n; lm.M_dev = nullptr; lm.N = c.vocab; lm.K = c.d_model; lm.ldo = c.vocab; lm.epilogue = EPI_F32;
+  LAUNCH("gemm_lm_head", launch_gemm(c.dtype, lm, s));
+  return RLHF_OK;
+}
+
+int rlhf_profile_enable(rlhf_handle* h, int32_t on) {
+  if (!h) return fail(RLHF_EINVAL, "null handle");
+  h->prof_on = on != 0;
+  h->prof_names.clear();
+  h->prof_ev.clear();
+  h->ev_used = 0;
+  return RLHF_OK;
+}
+
+int rlhf_profile_read(rlhf_handle* h, int32_t cap, const char** names, double* total_ms, int64_t* launches,
+                      int32_t* n_out) {
+  if (!h || !n_out) return fail(RLHF_EINVAL, "null argument");
+  std::map<std::string, std::pair<double, int64_t>> agg;
+  std::map<std::string, const char*> ptr;
+  const size_t n = std::min(h->prof_names.size(), h->prof_ev.size() / 2);
+  if (n) HIP_OK(hipEventSynchronize(h->prof_ev[2 * n - 1]));
+  for (size_t i = 0; i < n; ++i) {
+    float ms = 0.f;
+    HIP_OK(hipEventElapsedTime(&ms, h->prof_ev[2 * i], h->prof_ev[2 * i + 1]));
+    auto& a = agg[h->prof_names[i]];
+    a.first += ms;
+    a.second += 1;
+    ptr[h->prof_names[i]] = h->prof_names[i];
+  }
+  int k = 0;
+  for (auto& kv : agg) {
+    if (k < cap) {
+      if (names) names[k] = ptr[kv.first];
+      if (total_ms) total_ms[k] = kv.second.first;
+      if (launches) launches[k] = kv.second.second;
+    }
+    ++k;
+  }
+  *n_out = k;
+  h->prof_names.clear();
+  h->prof_ev.clear();
+  h->ev_used = 0;
+  return RLHF_OK;
+}
+
+int rlhf_last_rollout_phases(rlhf_handle* h, double* prefill_ms, double* decode_ms) {
+  if (!h || !prefill_ms || !decode_ms) return fail(RLHF_EINVAL, "null argument");
+  if (!h->ph_valid) return fail(RLHF_EINVAL, "no completed rollout_generate on this handle");
+  HIP_OK(hipEventSynchronize(h->ph[2]));
+  float a = 0.f, b = 0.f;
+  HIP_OK(hipEventElapsedTime(&a, h->ph[0], h->ph[1]));
+  HIP_OK(hipEventElapsedTime(&b, h->ph[1], h->ph[2]));
+  *prefill_ms = a;
+  *decode_ms = b;
+  return RLHF_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,168 @@
+// Shared device helpers and the launcher declarations of the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rlhf {
+
+// ------------------------------------------------------------------------------------------------
+// Element types.  bf16_t: the storage type of a bf16 model's weights (raw 16-bit patterns).
+// half_t: the type of activations, K/V cache and matrix-core operands in bf16 mode.  Both matrix
+// operand types run at the same MFMA rate and occupy the same bytes; fp16's 11-bit significand
+// keeps the activation rounding error 8x below bf16's, which the parity bar of this library needs,
+// and every bf16 weight converts to fp16 exactly inside fp16's normal range.  Accumulation, the
+// residual stream, LayerNorm statistics, softmax and the sampler are always fp32.
+// ------------------------------------------------------------------------------------------------
+struct bf16_t {
+  uint16_t bits;
+};
+typedef _Float16 half_t;
+
+struct ModeF32 {  // fp32 check mode
+  typedef float W;  // weights as stored by the caller
+  typedef float A;  // activations and GEMM operands
+};
+struct ModeBF16 {  // bf16 weights, fp16 operands
+  typedef bf16_t W;
+  typedef half_t A;
+};
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+__device__ __forceinline__ float to_f32(half_t x) { return (float)x; }
+
+// round-to-nearest-even fp32 -> bf16 (inputs are finite in this library; NaN stays NaN-ish)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+template <typename T>
+__device__ __forceinline__ T from_f32(float f);
+template <>
+__device__ __forceinline__ float from_f32<float>(float f) {
+  return f;
+}
+template <>
+__device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) {
+  bf16_t r;
+  r.bits = f32_to_bf16_bits(f);
+  return r;
+}
+template <>
+__device__ __forceinline__ half_t from_f32<half_t>(float f) {  // round to nearest even, saturating
+  return (half_t)fminf(fmaxf(f, -65504.0f), 65504.0f);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Launchers (host).  dtype: 0 = ModeF32, 1 = ModeBF16.  All enqueue on `s` and return the
+// launch status.  "n_rows_dev", where present, points to the device-resident row count; the grid
+// is sized for the host-side upper bound and surplus blocks exit.
+// ------------------------------------------------------------------------------------------------
+enum Epilogue {
+  EPI_BIAS = 0,         // out[T]   = acc + bias
+  EPI_BIAS_GELU = 1,    // out[T]   = gelu_erf(acc + bias)
+  EPI_BIAS_RESADD = 2,  // out[f32] += acc + bias      (residual stream update, in place)
+  EPI_F32 = 3           // out[f32] = acc              (logits)
+};
+
+struct GemmArgs {
+  const void* A;      // [M, K] activations, row-major, Mode::A
+  const void* W;      // [N, K] weight, row-major, Mode::A (bf16 weights are converted at create)
+  const void* bias;   // [N] Mode::W or nullptr
+  void* out;          // [M, ldo] (Mode::A or float by epilogue)
+  int M_max;          // host upper bound of M
+  const int* M_dev;   // device row count or nullptr (then M = M_max)
+  int M_sub = 0;      // with M_dev: M = min(M_max, *M_dev - M_sub)  (row chunk starting at M_sub)
+  int N, K, ldo;
+  int epilogue;
+};
+hipError_t launch_gemm(int dtype, const GemmArgs& a, hipStream_t s);
+
+// Row metadata of a packed batch -------------------------------------------------------------------
+// mask [B, L] (1 = real) -> start[b], len[b]; then cu[b] = sum_{b'<b} len, kvoff[b] = sum_{b'<b}
+// (len + kv_extra), total[0] = cu[B], total[1] = kvoff[B].
+hipError_t launch_row_spans(const uint8_t* mask, int B, int L, int kv_extra, int* start, int* len, int* cu,
+                            int* kvoff, int* total, hipStream_t s);
+// Packed row t = cu[b] + i for i < len[b]: pos[t] = i, rowid[t] = b, tok[t] = tokens[b, start[b]+i],
+// x[t, :] = embed[tok[t], :].
+hipError_t launch_pack_embed(int dtype, const int32_t* tokens, int B, int L, const int* start, const int* len,
+                             const int* cu, const void* embed, int d, int vocab, int* pos, int* rowid, int* tok,
+                             float* x, hipStream_t s);
+// Decode step: x[b, :] = embed[cur_tok[b], :] for b < B.
+hipError_t launch_embed_rows(int dtype, const int32_t* tok, int B, const void* embed, int d, float* x,
+                             hipStream_t s);
+
+// LayerNorm of fp32 rows; two affine outputs from one set of statistics (g2 may be null -> one).
+hipError_t launch_layernorm(int dtype, const float* x, int rows_max, const int* rows_dev, int d, float eps,
+                            const void* g1, const void* b1, void* out1, const void* g2, const void* b2,
+                            void* out2, hipStream_t s);
+// Final LayerNorm of selected rows: row r reads x[src[r]] (src may be null: identity), optionally
+// also the value head val[r] = w_v . h + b_v.
+hipError_t launch_final_ln(int dtype, const float* x, const int* src, int src_add, int rows_max,
+                           const int* rows_dev, int d, float eps, const void* g, const void* b, void* out,
+                           const void* value_w, float value_b, float* val, hipStream_t s);
+
+// Rotary on q,k (first r dims of each head) + K/V store.  qkv [rows, 3d] -> q [rows, d] and
+// kc/vc [H][kv_total][hd] at slot kvoff[rowid[t]] + pos[t] + pos_add.  rowid may be null (row t is
+// sequence t).  cos/sin tables are [max_pos][r/2].
+hipError_t launch_rope_kv(int dtype, const void* qkv, int rows_max, const int* rows_dev, const int* pos,
+                          int pos_add, const int* rowid, const int* kvoff, int H, int hd, int r,
+                          const float* cos_t, const float* sin_t, void* q, void* kc, void* vc,
+                          long kv_head_stride, hipStream_t s);
+
+// Causal attention over packed sequences (prefill / scoring).  q [T, H*hd]; kc/vc [H][*][hd] with
+// sequence b's keys at slots kvoff[b] .. kvoff[b]+len[b]; out [T, H*hd].
+hipError_t launch_attn_prefill(int dtype, const void* q, const void* kc, const void* vc, long kv_head_stride,
+                               int B, int Lmax, const int* len, const int* cu, const int* kvoff, int H, int hd,
+                               void* out, hipStream_t s);
+// Decode attention: one query row per sequence against ctx = len[b] + ctx_add cached keys.
+hipError_t launch_attn_decode(int dtype, const void* q, const void* kc, const void* vc, long kv_head_stride,
+                              int B, const int* len, int ctx_add, int ctx_max, const int* kvoff, int H, int hd,
+                              void* out, hipStream_t s);
+
+// Sampler: one step for every row from fp32 logits [B, V].
+struct SampleArgs {
+  const float* logits;
+  int B, V, Lq, N, step;
+  uint64_t seed, seq_base;
+  float temperature;
+  int eos_id, pad_id;
+  const int* len;       // true query lengths (0 = all-pad row)
+  int* finished;        // [B] state, initialised at step 0
+  int32_t* cur_tok;     // [B] token fed to the next pass
+  int32_t* out_tokens;  // [B, Lq+N]
+  float* out_logprobs;  // [B, N]
+  int32_t* out_lengths; // [B]
+};
+hipError_t launch_sampler(const SampleArgs& a, hipStream_t s);
+hipError_t launch_copy_queries(const int32_t* queries, int B, int Lq, int N, int pad_id, int32_t* out_tokens,
+                               hipStream_t s);
+
+// Scoring: log softmax(logits[t]/T)[tok[t+1]] for packed rows t0 .. t0+rows of a logits chunk;
+// result goes to lp_packed[t+1] when t+1 belongs to the same sequence.
+hipError_t launch_lse_gather(const float* logits, int rows_max, int t0, const int* T_dev, int V,
+                             float temperature, const int* tok, const int* pos, float* lp_packed,
+                             hipStream_t s);
+// Packed -> padded [B, L] outputs with zeros at masked slots; logprob of a row's first token is 0.
+hipError_t launch_unpack_scores(const float* lp_packed, const float* val_packed, int B, int L, const int* start,
+                                const int* len, const int* cu, float* out_lp, float* out_val, hipStream_t s);
+// Gather helper for the debug entry point: idx[i] = cu[b_i] + (col_i - start[b_i]).
+hipError_t launch_rows_to_packed(const int32_t* rows_bt, int n, const int* start, const int* cu, int* idx,
+                                 hipStream_t s);
+
+// bf16 -> fp16 conversion of a weight matrix (exact within fp16's normal range).
+hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s);
+
+}  // namespace rlhf

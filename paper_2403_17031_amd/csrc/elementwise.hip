@@ -1,0 +1,480 @@
+// Row bookkeeping, embedding gather, LayerNorm (+ value head), partial rotary + KV store, the
+// Gumbel-max sampler, log-sum-exp + target gather, and output scatter.  All bandwidth-bound.
+#include <algorithm>
+
+#include "common.h"
+
+namespace rlhf {
+
+// =================================================================================================
+// Row spans: one wave per row finds the first real slot and the number of real slots.
+// =================================================================================================
+__global__ void row_span_kernel(const uint8_t* __restrict__ mask, int L, int* __restrict__ start,
+                                int* __restrict__ len) {
+  const int b = blockIdx.x;
+  const uint8_t* row = mask + (size_t)b * L;
+  int cnt = 0, first = L;
+  for (int c = threadIdx.x; c < L; c += 64) {
+    if (row[c]) {
+      cnt++;
+      first = min(first, c);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    cnt += __shfl_xor(cnt, o, 64);
+    first = min(first, __shfl_xor(first, o, 64));
+  }
+  if (threadIdx.x == 0) {
+    len[b] = cnt;
+    start[b] = cnt ? first : 0;
+  }
+}
+
+// Exclusive prefix sums over B rows (B is at most a few thousand: one thread walks them).
+__global__ void row_scan_kernel(const int* __restrict__ len, int B, int kv_extra, int* __restrict__ cu,
+                                int* __restrict__ kvoff, int* __restrict__ total) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  int a = 0, k = 0;
+  for (int b = 0; b < B; ++b) {
+    cu[b] = a;
+    kvoff[b] = k;
+    a += len[b];
+    k += len[b] + kv_extra;
+  }
+  cu[B] = a;
+  kvoff[B] = k;
+  total[0] = a;
+  total[1] = k;
+}
+
+hipError_t launch_row_spans(const uint8_t* mask, int B, int L, int kv_extra, int* start, int* len, int* cu,
+                            int* kvoff, int* total, hipStream_t s) {
+  hipLaunchKernelGGL(row_span_kernel, dim3(B), dim3(64), 0, s, mask, L, start, len);
+  hipLaunchKernelGGL(row_scan_kernel, dim3(1), dim3(64), 0, s, len, B, kv_extra, cu, kvoff, total);
+  return hipGetLastError();
+}
+
+// =================================================================================================
+// Pack + embed
+// =================================================================================================
+template <typename T>
+__global__ void pack_embed_kernel(const int32_t* __restrict__ tokens, int L, const int* __restrict__ start,
+                                  const int* __restrict__ len, const int* __restrict__ cu,
+                                  const T* __restrict__ embed, int d, int vocab, int* __restrict__ pos,
+                                  int* __restrict__ rowid, int* __restrict__ tok, float* __restrict__ x) {
+  const int i = blockIdx.x, b = blockIdx.y;
+  if (i >= len[b]) return;
+  const int t = cu[b] + i;
+  // ids outside the vocabulary are a caller error; clamping keeps every access in bounds
+  const int id = min(max(tokens[(size_t)b * L + start[b] + i], 0), vocab - 1);
+  if (threadIdx.x == 0) {
+    pos[t] = i;
+    rowid[t] = b;
+    tok[t] = id;
+  }
+  const T* e = embed + (size_t)id * d;
+  float* xr = x + (size_t)t * d;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) xr[c] = to_f32(e[c]);
+}
+
+hipError_t launch_pack_embed(int dtype, const int32_t* tokens, int B, int L, const int* start, const int* len,
+                             const int* cu, const void* embed, int d, int vocab, int* pos, int* rowid, int* tok,
+                             float* x, hipStream_t s) {
+  dim3 grid(L, B), block(256);
+  if (dtype == 0)
+    hipLaunchKernelGGL(pack_embed_kernel<float>, grid, block, 0, s, tokens, L, start, len, cu,
+                       (const float*)embed, d, vocab, pos, rowid, tok, x);
+  else
+    hipLaunchKernelGGL(pack_embed_kernel<bf16_t>, grid, block, 0, s, tokens, L, start, len, cu,
+                       (const bf16_t*)embed, d, vocab, pos, rowid, tok, x);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ void embed_rows_kernel(const int32_t* __restrict__ tok, const T* __restrict__ embed, int d,
+                                  float* __restrict__ x) {
+  const int b = blockIdx.x;
+  const T* e = embed + (size_t)tok[b] * d;
+  float* xr = x + (size_t)b * d;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) xr[c] = to_f32(e[c]);
+}
+
+hipError_t launch_embed_rows(int dtype, const int32_t* tok, int B, const void* embed, int d, float* x,
+                             hipStream_t s) {
+  if (dtype == 0)
+    hipLaunchKernelGGL(embed_rows_kernel<float>, dim3(B), dim3(256), 0, s, tok, (const float*)embed, d, x);
+  else
+    hipLaunchKernelGGL(embed_rows_kernel<bf16_t>, dim3(B), dim3(256), 0, s, tok, (const bf16_t*)embed, d, x);
+  return hipGetLastError();
+}
+
+// =================================================================================================
+// LayerNorm: one block per row, fp32 statistics (mean, then centred second moment), up to two
+// affine outputs from the same statistics, optional value-head dot product on the first output.
+// =================================================================================================
+__device__ __forceinline__ float block_sum_256(float v, float* sh) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();  // protects sh against the previous use
+  if ((threadIdx.x & 63) == 0) sh[w] = v;
+  __syncthreads();
+  return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+template <typename WT, typename AT>
+__global__ void __launch_bounds__(256)
+    layernorm_kernel(const float* __restrict__ x, const int* __restrict__ src, int src_add,
+                     const int* __restrict__ rows_dev, int d, float eps, const WT* __restrict__ g1,
+                     const WT* __restrict__ b1, AT* __restrict__ out1, const WT* __restrict__ g2,
+                     const WT* __restrict__ b2, AT* __restrict__ out2, const WT* __restrict__ value_w,
+                     float value_b, float* __restrict__ val) {
+  __shared__ float sh[4];
+  const int r = blockIdx.x;
+  if (rows_dev && r >= *rows_dev) return;
+  const int sr = src ? max(src[r] + src_add, 0) : r;  // an empty first sequence would give -1
+  const float* xr = x + (size_t)sr * d;
+  float s = 0.f;
+  for (int c = threadIdx.x; c < d; c += 256) s += xr[c];
+  const float mean = block_sum_256(s, sh) / (float)d;
+  float q = 0.f;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const float u = xr[c] - mean;
+    q += u * u;
+  }
+  const float rstd = 1.0f / sqrtf(block_sum_256(q, sh) / (float)d + eps);
+  float vd = 0.f;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const float n = (xr[c] - mean) * rstd;
+    const float h1 = n * to_f32(g1[c]) + to_f32(b1[c]);
+    out1[(size_t)r * d + c] = from_f32<AT>(h1);
+    if (out2) out2[(size_t)r * d + c] = from_f32<AT>(n * to_f32(g2[c]) + to_f32(b2[c]));
+    if (val) vd += h1 * to_f32(value_w[c]);
+  }
+  if (val) {
+    vd = block_sum_256(vd, sh);
+    if (threadIdx.x == 0) val[r] = vd + value_b;
+  }
+}
+
+template <typename M>
+static hipError_t ln_launch(const float* x, const int* src, int src_add, int rows_max, const int* rows_dev, int d,
+                            float eps, const void* g1, const void* b1, void* out1, const void* g2,
+                            const void* b2, void* out2, const void* vw, float vb, float* val, hipStream_t s) {
+  if (rows_max <= 0) return hipSuccess;
+  typedef typename M::W WT;
+  typedef typename M::A AT;
+  hipLaunchKernelGGL((layernorm_kernel<WT, AT>), dim3(rows_max), dim3(256), 0, s, x, src, src_add, rows_dev, d,
+                     eps, (const WT*)g1, (const WT*)b1, (AT*)out1, (const WT*)g2, (const WT*)b2, (AT*)out2,
+                     (const WT*)vw, vb, val);
+  return hipGetLastError();
+}
+
+hipError_t launch_layernorm(int dtype, const float* x, int rows_max, const int* rows_dev, int d, float eps,
+                            const void* g1, const void* b1, void* out1, const void* g2, const void* b2,
+                            void* out2, hipStream_t s) {
+  if (dtype == 0)
+    return ln_launch<ModeF32>(x, nullptr, 0, rows_max, rows_dev, d, eps, g1, b1, out1, g2, b2, out2, nullptr, 0.f,
+                            nullptr, s);
+  return ln_launch<ModeBF16>(x, nullptr, 0, rows_max, rows_dev, d, eps, g1, b1, out1, g2, b2, out2, nullptr, 0.f,
+                           nullptr, s);
+}
+
+hipError_t launch_final_ln(int dtype, const float* x, const int* src, int src_add, int rows_max,
+                           const int* rows_dev, int d, float eps, const void* g, const void* b, void* out,
+                           const void* value_w, float value_b, float* val, hipStream_t s) {
+  if (!value_w) val = nullptr;
+  if (dtype == 0)
+    return ln_launch<ModeF32>(x, src, src_add, rows_max, rows_dev, d, eps, g, b, out, nullptr, nullptr, nullptr,
+                            value_w, value_b, val, s);
+  return ln_launch<ModeBF16>(x, src, src_add, rows_max, rows_dev, d, eps, g, b, out, nullptr, nullptr, nullptr,
+                           value_w, value_b, val, s);
+}
+
+// =================================================================================================
+// Partial rotary + K/V store.  One block per packed row.
+// =================================================================================================
+template <typename T>
+__global__ void __launch_bounds__(256)
+    rope_kv_kernel(const T* __restrict__ qkv, const int* __restrict__ rows_dev, const int* __restrict__ pos,
+                   int pos_add, const int* __restrict__ rowid, const int* __restrict__ kvoff, int H, int hd,
+                   int r, const float* __restrict__ cos_t, const float* __restrict__ sin_t, T* __restrict__ q,
+                   T* __restrict__ kc, T* __restrict__ vc, long kv_head_stride) {
+  const int t = blockIdx.x;
+  if (rows_dev && t >= *rows_dev) return;
+  const int d = H * hd;
+  const int p = pos[t] + pos_add;
+  const int b = rowid ? rowid[t] : t;
+  const long slot = (long)kvoff[b] + p;
+  const T* src = qkv + (size_t)t * 3 * d;
+  const int half = r >> 1;
+  const float* cs = cos_t + (size_t)p * half;
+  const float* sn = sin_t + (size_t)p * half;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const int h = c / hd, e = c - h * hd;
+    float qv = to_f32(src[c]), kv = to_f32(src[d + c]);
+    if (e < half) {
+      const float co = cs[e], si = sn[e];
+      qv = qv * co - to_f32(src[c + half]) * si;
+      kv = kv * co - to_f32(src[d + c + half]) * si;
+    } else if (e < r) {
+      const float co = cs[e - half], si = sn[e - half];
+      qv = qv * co + to_f32(src[c - half]) * si;
+      kv = kv * co + to_f32(src[d + c - half]) * si;
+    }
+    q[(size_t)t * d + c] = from_f32<T>(qv);
+    const size_t o = (size_t)h * kv_head_stride + (size_t)slot * hd + e;
+    kc[o] = from_f32<T>(kv);
+    vc[o] = src[2 * d + c];
+  }
+}
+
+hipError_t launch_rope_kv(int dtype, const void* qkv, int rows_max, const int* rows_dev, const int* pos,
+                          int pos_add, const int* rowid, const int* kvoff, int H, int hd, int r,
+                          const float* cos_t, const float* sin_t, void* q, void* kc, void* vc,
+                          long kv_head_stride, hipStream_t s) {
+  if (rows_max <= 0) return hipSuccess;
+  if (dtype == 0)
+    hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(rows_max), dim3(256), 0, s, (const float*)qkv, rows_dev, pos,
+                       pos_add, rowid, kvoff, H, hd, r, cos_t, sin_t, (float*)q, (float*)kc, (float*)vc,
+                       kv_head_stride);
+  else
+    hipLaunchKernelGGL(rope_kv_kernel<half_t>, dim3(rows_max), dim3(256), 0, s, (const half_t*)qkv, rows_dev,
+                       pos, pos_add, rowid, kvoff, H, hd, r, cos_t, sin_t, (half_t*)q, (half_t*)kc, (half_t*)vc,
+                       kv_head_stride);
+  return hipGetLastError();
+}
+
+// =================================================================================================
+// Sampling noise: counter hash keyed (seed, sequence, step, token id) -> Gumbel variate.
+// Integer part: 64-bit xor-shift-multiply finaliser, applied three times (row key, step key,
+// token).  The top 32 bits k give u = (k + 1/2) / 2^32 in (0,1), g = -ln(-ln u).
+// =================================================================================================
+__device__ __forceinline__ uint64_t fmix64(uint64_t x) {
+  x ^= x >> 30;
+  x *= 0xBF58476D1CE4E5B9ull;
+  x ^= x >> 27;
+  x *= 0x94D049BB133111EBull;
+  x ^= x >> 31;
+  return x;
+}
+#define RLHF_GOLDEN 0x9E3779B97F4A7C15ull
+
+__device__ __forceinline__ uint64_t noise_step_key(uint64_t seed, uint64_t seq, uint32_t step) {
+  const uint64_t kr = fmix64(seed + RLHF_GOLDEN * (seq + 1));
+  return fmix64(kr + RLHF_GOLDEN * (uint64_t)(step + 1));
+}
+
+__device__ __forceinline__ float gumbel_from_key(uint64_t step_key, uint32_t v) {
+  const uint32_t k = (uint32_t)(fmix64(step_key + RLHF_GOLDEN * (uint64_t)(v + 1)) >> 32);
+  float E;  // E = -ln u, evaluated so that u close to 1 keeps its relative accuracy
+  if (k < 0x80000000u) {
+    E = -logf((float)k * 2.3283064365386963e-10f + 1.1641532182693481e-10f);
+  } else {
+    const float c = (float)(0u - k);  // 2^32 - k, in [1, 2^31]
+    E = -log1pf(-(c - 0.5f) * 2.3283064365386963e-10f);
+  }
+  return -logf(E);
+}
+
+// One block per row.  Single pass over the logits: running (max, sum exp) for the log-sum-exp and
+// running best perturbed score; ties resolve to the lowest token id at every merge.
+__global__ void __launch_bounds__(1024) sampler_kernel(SampleArgs a) {
+  __shared__ float sm[16], ss[16], sb[16];
+  __shared__ int si[16];
+  const int b = blockIdx.x;
+  const float* row = a.logits + (size_t)b * a.V;
+  const uint64_t key = noise_step_key(a.seed, a.seq_base + (uint64_t)b, (uint32_t)a.step);
+  float m = -INFINITY, s = 0.f, best = -INFINITY;
+  int bi = 0x7FFFFFFF;
+  for (int v = threadIdx.x; v < a.V; v += 1024) {
+    const float z = row[v] / a.temperature;
+    if (z > m) {
+      s = s * expf(m - z) + 1.0f;
+      m = z;
+    } else {
+      s += expf(z - m);
+    }
+    const float sc = z + gumbel_from_key(key, (uint32_t)v);
+    if (sc > best) {  // v increases within a thread, so '>' keeps the lowest id among equals
+      best = sc;
+      bi = v;
+    }
+  }
+  // wave merge
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float m2 = __shfl_xor(m, o, 64), s2 = __shfl_xor(s, o, 64), b2 = __shfl_xor(best, o, 64);
+    const int i2 = __shfl_xor(bi, o, 64);
+    const float mn = fmaxf(m, m2);
+    s = (m == -INFINITY ? 0.f : s * expf(m - mn)) + (m2 == -INFINITY ? 0.f : s2 * expf(m2 - mn));
+    m = mn;
+    if (b2 > best || (b2 == best && i2 < bi)) {
+      best = b2;
+      bi = i2;
+    }
+  }
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) {
+    sm[w] = m;
+    ss[w] = s;
+    sb[w] = best;
+    si[w] = bi;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int j = 1; j < 16; ++j) {
+      const float mn = fmaxf(m, sm[j]);
+      s = (m == -INFINITY ? 0.f : s * expf(m - mn)) + (sm[j] == -INFINITY ? 0.f : ss[j] * expf(sm[j] - mn));
+      m = mn;
+      if (sb[j] > best || (sb[j] == best && si[j] < bi)) {
+        best = sb[j];
+        bi = si[j];
+      }
+    }
+    const float ztok = row[bi] / a.temperature;
+    const float lp = ztok - (m + logf(s));
+    int fin = (a.step == 0) ? (a.len[b] == 0 ? 1 : 0) : a.finished[b];
+    if (a.step == 0) a.out_lengths[b] = (a.len[b] == 0) ? 0 : a.N;
+    const size_t to = (size_t)b * (a.Lq + a.N) + a.Lq + a.step;
+    if (fin) {
+      a.out_tokens[to] = a.pad_id;
+      a.out_logprobs[(size_t)b * a.N + a.step] = 0.f;
+    } else {
+      a.out_tokens[to] = bi;
+      a.out_logprobs[(size_t)b * a.N + a.step] = lp;
+      if (bi == a.eos_id) {
+        fin = 1;
+        a.out_lengths[b] = a.step + 1;
+      }
+    }
+    a.finished[b] = fin;
+    a.cur_tok[b] = bi;  // fed back either way; what follows EOS never reaches a kept output
+  }
+}
+
+hipError_t launch_sampler(const SampleArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(sampler_kernel, dim3(a.B), dim3(1024), 0, s, a);
+  return hipGetLastError();
+}
+
+__global__ void copy_queries_kernel(const int32_t* __restrict__ queries, int Lq, int N, int pad_id,
+                                    int32_t* __restrict__ out) {
+  const int b = blockIdx.x;
+  for (int c = threadIdx.x; c < Lq + N; c += blockDim.x)
+    out[(size_t)b * (Lq + N) + c] = c < Lq ? queries[(size_t)b * Lq + c] : pad_id;
+}
+
+hipError_t launch_copy_queries(const int32_t* queries, int B, int Lq, int N, int pad_id, int32_t* out_tokens,
+                               hipStream_t s) {
+  hipLaunchKernelGGL(copy_queries_kernel, dim3(B), dim3(256), 0, s, queries, Lq, N, pad_id, out_tokens);
+  return hipGetLastError();
+}
+
+// =================================================================================================
+// Scoring: log-sum-exp of logits/T and the target-token logit, one block per packed row.
+// =================================================================================================
+__global__ void __launch_bounds__(256)
+    lse_gather_kernel(const float* __restrict__ logits, int t0, const int* __restrict__ T_dev, int V,
+                      float temperature, const int* __restrict__ tok, const int* __restrict__ pos,
+                      float* __restrict__ lp_packed) {
+  __shared__ float sm[4], ss[4];
+  const int t = t0 + blockIdx.x;
+  const int T = *T_dev;
+  if (t + 1 >= T) return;
+  if (pos[t + 1] != pos[t] + 1) return;  // t is the last token of its sequence: nothing to predict
+  const float* row = logits + (size_t)blockIdx.x * V;
+  float m = -INFINITY, s = 0.f;
+  for (int v = threadIdx.x; v < V; v += 256) {
+    const float z = row[v] / temperature;
+    if (z > m) {
+      s = s * expf(m - z) + 1.0f;
+      m = z;
+    } else {
+      s += expf(z - m);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float m2 = __shfl_xor(m, o, 64), s2 = __shfl_xor(s, o, 64);
+    const float mn = fmaxf(m, m2);
+    s = (m == -INFINITY ? 0.f : s * expf(m - mn)) + (m2 == -INFINITY ? 0.f : s2 * expf(m2 - mn));
+    m = mn;
+  }
+  if ((threadIdx.x & 63) == 0) {
+    sm[threadIdx.x >> 6] = m;
+    ss[threadIdx.x >> 6] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int j = 1; j < 4; ++j) {
+      const float mn = fmaxf(m, sm[j]);
+      s = (m == -INFINITY ? 0.f : s * expf(m - mn)) + (sm[j] == -INFINITY ? 0.f : ss[j] * expf(sm[j] - mn));
+      m = mn;
+    }
+    const float zt = row[tok[t + 1]] / temperature;
+    lp_packed[t + 1] = zt - (m + logf(s));
+  }
+}
+
+hipError_t launch_lse_gather(const float* logits, int rows_max, int t0, const int* T_dev, int V,
+                             float temperature, const int* tok, const int* pos, float* lp_packed,
+                             hipStream_t s) {
+  if (rows_max <= 0) return hipSuccess;
+  hipLaunchKernelGGL(lse_gather_kernel, dim3(rows_max), dim3(256), 0, s, logits, t0, T_dev, V, temperature, tok,
+                     pos, lp_packed);
+  return hipGetLastError();
+}
+
+__global__ void unpack_scores_kernel(const float* __restrict__ lp_packed, const float* __restrict__ val_packed,
+                                     int L, const int* __restrict__ start, const int* __restrict__ len,
+                                     const int* __restrict__ cu, float* __restrict__ out_lp,
+                                     float* __restrict__ out_val) {
+  const int b = blockIdx.y;
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= L) return;
+  const int i = c - start[b];
+  const bool real = i >= 0 && i < len[b];
+  const size_t o = (size_t)b * L + c;
+  out_lp[o] = (real && i >= 1) ? lp_packed[cu[b] + i] : 0.f;
+  if (out_val) out_val[o] = real ? val_packed[cu[b] + i] : 0.f;
+}
+
+hipError_t launch_unpack_scores(const float* lp_packed, const float* val_packed, int B, int L, const int* start,
+                                const int* len, const int* cu, float* out_lp, float* out_val, hipStream_t s) {
+  hipLaunchKernelGGL(unpack_scores_kernel, dim3((L + 255) / 256, B), dim3(256), 0, s, lp_packed, val_packed, L,
+                     start, len, cu, out_lp, out_val);
+  return hipGetLastError();
+}
+
+__global__ void rows_to_packed_kernel(const int32_t* __restrict__ rows_bt, int n, const int* __restrict__ start,
+                                      const int* __restrict__ cu, int* __restrict__ idx) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int b = rows_bt[2 * i], c = rows_bt[2 * i + 1];
+  idx[i] = cu[b] + (c - start[b]);
+}
+
+hipError_t launch_rows_to_packed(const int32_t* rows_bt, int n, const int* start, const int* cu, int* idx,
+                                 hipStream_t s) {
+  hipLaunchKernelGGL(rows_to_packed_kernel, dim3((n + 63) / 64), dim3(64), 0, s, rows_bt, n, start, cu, idx);
+  return hipGetLastError();
+}
+
+// =================================================================================================
+// One-time weight conversion bf16 -> fp16.
+// =================================================================================================
+__global__ void bf16_to_f16_kernel(const bf16_t* __restrict__ src, half_t* __restrict__ dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = (half_t)to_f32(src[i]);
+}
+
+hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const int blocks = (int)std::min<size_t>((n + 255) / 256, 65536);
+  hipLaunchKernelGGL(bf16_to_f16_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t*)src, (half_t*)dst, n);
+  return hipGetLastError();
+}
+
+}  // namespace rlhf

@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the rollout + rescoring hot path on one MI355X.
+
+One "step" = rollout_generate on a synthetic left-padded query batch, then score_sequences on the
+rollout's own (tokens, mask) output.  Inputs are resident in HBM before the timed region.  Prints
+ONE JSON line (see README for the fields)."""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12       # B/s, MI355X HBM3E
+MFMA_PEAK = 2.5e15      # flop/s, dense fp16/bf16 MFMA
+
+
+def work_counts(cfg, n, resp, N):
+    """Algorithmic flops / bytes of the workload from the drawn lengths (real tokens only)."""
+    import numpy as np
+    L, d, F, V = cfg.n_layers, cfg.d_model, cfg.d_ff, cfg.vocab
+    es = 4 if cfg.dtype == "fp32" else 2
+    P_l = 4 * d * d + 2 * d * F
+    mm = 2 * L * P_l                     # matmul flop per token through all layers
+    lm = 2 * V * d
+    attn = lambda k: L * 4 * d * k * (k + 1) / 2
+    n = n.astype(np.float64)
+    m = n + resp
+    B = len(n)
+    kv_tok = L * 2 * d * es              # K+V bytes of one cached token
+    W = (L * (P_l + 3 * d + d + F + d + 4 * d) + V * d) * es   # bytes streamed per decode pass (no embed_in)
+    kv_read = sum(kv_tok * (n + t + 1) for t in range(N - 1)).sum()
+    return dict(
+        prefill_flops=float((n * mm + attn(n)).sum() + B * lm),
+        score_flops=float((m * (mm + lm) + attn(m)).sum()),
+        decode_bytes=float((N - 1) * W + kv_read + (N - 1) * B * kv_tok),
+        decode_kv_read_bytes=float(kv_read),
+        decode_flops=float((N - 1) * B * (mm + lm)),
+        gemm_flops_prefill=float(n.sum() * mm), gemm_flops_score=float(m.sum() * mm),
+        lm_flops_score=float(m.sum() * lm), weights_bytes=float(W), real_score_tokens=float(m.sum()),
+        real_query_tokens=float(n.sum()))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=4, help="BASELINE config index 1..5 (default: the 2.8B target)")
+    ap.add_argument("--batch", type=int, default=None, help="override the config's batch (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU (sequences are independent; see DESIGN.md on sharding); "
+                 "--gpus must be 1")
+
+    import numpy as np
+    import torch
+    import paper_2403_17031_amd as P
+    from synth import WORKLOADS, make_weights, make_queries
+
+    wl = WORKLOADS[a.config]
+    cfg = wl.model
+    B = a.batch or wl.batch
+    N = wl.new_tokens
+    t0 = time.time()
+    w = make_weights(cfg, wl.weight_seed, threads=16)
+    queries, mask = make_queries(wl, batch=B)
+    pol = P.Policy(cfg, w, device="cuda:0")
+    q_d = torch.from_numpy(queries).cuda()
+    m_d = torch.from_numpy(mask).cuda()
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def step():
+        toks, lps, lens, omask = pol.rollout_generate(q_d, m_d, wl.sample_seed, wl.temperature, N, return_mask=True)
+        lp, val = pol.score_sequences(toks, omask, wl.temperature)
+        return toks, lps, lens, omask, lp, val
+
+    for _ in range(a.warmup):
+        out = step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * a.steps)]
+    t1 = time.time()
+    for i in range(a.steps):
+        ev[3 * i].record()
+        r = pol.rollout_generate(q_d, m_d, wl.sample_seed, wl.temperature, N, return_mask=True)
+        ev[3 * i + 1].record()
+        s = pol.score_sequences(r[0], r[3], wl.temperature)
+        ev[3 * i + 2].record()
+    torch.cuda.synchronize()
+    wall = time.time() - t1
+    roll_ms = float(np.mean([ev[3 * i].elapsed_time(ev[3 * i + 1]) for i in range(a.steps)]))
+    score_ms = float(np.mean([ev[3 * i + 1].elapsed_time(ev[3 * i + 2]) for i in range(a.steps)]))
+    prefill_ms, decode_ms = pol.last_rollout_phases()
+    lens = r[2].cpu().numpy()
+    n_true = mask.sum(1)
+    wc = work_counts(cfg, n_true, lens, N)
+
+    # one more step with per-kernel HIP events (outside the timed region) for the roofline object
+    pol.profile_enable(True)
+    step()
+    prof = pol.profile_read()
+    pol.profile_enable(False)
+    tot = sum(v[0] for v in prof.values())
+    kern = {k: {"ms": round(v[0], 3), "launches": v[1]} for k, v in sorted(prof.items(), key=lambda kv: -kv[1][0])}
+    dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
+    rooflines = {}
+    if "gemm" in prof:
+        fl = wc["gemm_flops_prefill"] + wc["gemm_flops_score"]
+        ach = fl / (prof["gemm"][0] * 1e-3)
+        rooflines["gemm"] = {"bound": "mfma", "achieved": ach / 1e12, "peak": MFMA_PEAK / 1e12, "unit": "TFLOP/s",
+                             "frac": ach / MFMA_PEAK, "traffic": None,
+                             "avg_launch_ms": prof["gemm"][0] / prof["gemm"][1]}
+    if "attn_decode" in prof:
+        by = wc["decode_kv_read_bytes"]
+        ach = by / (prof["attn_decode"][0] * 1e-3)
+        rooflines["attn_decode"] = {"bound": "hbm", "achieved": ach / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                                    "frac": ach / HBM_PEAK, "traffic": None,
+                                    "avg_launch_ms": prof["attn_decode"][0] / prof["attn_decode"][1]}
+    roof = rooflines.get(dom) or rooflines.get("gemm") or {}
+    roof = dict(roof, kernel=dom if dom in rooflines else "gemm")
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, w, queries, mask, wl, n_true)
+
+    ms_step = wall / a.steps * 1e3
+    out = {
+        "metric": "rollout generated tokens/s (rollout_generate + score_sequences per step)",
+        "value": B * N / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg.dtype == "fp32" else "f16 operands / f32 accumulate (bf16 weights)",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "batch": B, "query_len": wl.query_len, "new_tokens": N,
+                   "temperature": wl.temperature, "real_query_tokens": int(n_true.sum()),
+                   "mean_response_len": float(lens.mean()),
+                   "seeds": [wl.weight_seed, wl.data_seed, wl.sample_seed]},
+        "generated_tok_s": B * N / (roll_ms * 1e-3), "rollout_ms": roll_ms,
+        "prefill_ms": prefill_ms, "decode_ms": decode_ms,
+        "decode_tok_s": B * (N - 1) / (decode_ms * 1e-3),
+        "decode_hbm_frac": wc["decode_bytes"] / (decode_ms * 1e-3) / HBM_PEAK,
+        "prefill_mfma_frac": wc["prefill_flops"] / (prefill_ms * 1e-3) / MFMA_PEAK,
+        "rescoring_tok_s": wc["real_score_tokens"] / (score_ms * 1e-3), "score_ms": score_ms,
+        "rescoring_tok_s_padded": B * (wl.query_len + N) / (score_ms * 1e-3),
+        "score_mfma_frac": wc["score_flops"] / (score_ms * 1e-3) / MFMA_PEAK,
+        "roofline": roof, "rooflines": rooflines, "kernels_ms": kern, "profiled_step_ms": tot,
+        "cpu_baseline": cpu, "setup_s": setup_s,
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(cfg, w, queries, mask, wl, n_true):
+    """The oracle, as it stands, on a bounded sample of the same workload: the shortest row of the
+    batch, 4 new tokens (prefill + 3 cached decode passes), then rescoring of that row."""
+    import numpy as np
+    from oracle import neox_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    b = int(np.argmin(np.where(n_true > 0, n_true, 1 << 30)))
+    n_new = min(4, wl.new_tokens)
+    m = O.OracleModel(w, cfg, cache_f64=False)
+    t0 = time.time()
+    toks, lps, lens = O.rollout_generate(m, queries[b:b + 1], mask[b:b + 1], wl.sample_seed, wl.temperature, n_new,
+                                         seq_id_base=b)
+    t_roll = time.time() - t0
+    full = np.concatenate([mask[b:b + 1], (np.arange(n_new)[None, :] < lens[:, None]).astype(np.uint8)], axis=1)
+    t0 = time.time()
+    O.score_sequences(m, toks, full, wl.temperature)
+    t_score = time.time() - t0
+    return {"value": n_new / (t_roll + t_score), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"row {b} (query {int(n_true[b])} tokens), {n_new} new tokens, then rescoring of that row",
+            "generated_tok_s": n_new / t_roll, "rescoring_tok_s": float(full.sum()) / t_score,
+            "rollout_s": t_roll, "score_s": t_score}
+
+
+if __name__ == "__main__":
+    main()

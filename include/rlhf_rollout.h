@@ -94,10 +94,12 @@ int rlhf_workspace_bytes(const rlhf_handle *h, int32_t B, int32_t Lq, int32_t ma
  *   out_logprobs float [B, max_new]: log softmax(logits/temperature)[token]; 0 after EOS
  *   out_lengths  int32 [B]: response tokens up to and including EOS (max_new if none; 0 for an
  *                all-pad row, whose outputs are all pad_id / 0)
+ *   out_mask     uint8 [B, Lq + max_new] or NULL: pad_mask followed by 1 for every kept response
+ *                token: with out_tokens, the input of score_sequences
  * One prefill pass and max_new-1 single-token passes are run. */
 int rollout_generate(rlhf_handle *h, const int32_t *queries, const uint8_t *pad_mask, int32_t B, int32_t Lq,
                      uint64_t seed, uint64_t seq_id_base, float temperature, int32_t max_new_tokens,
-                     int32_t *out_tokens, float *out_logprobs, int32_t *out_lengths,
+                     int32_t *out_tokens, float *out_logprobs, int32_t *out_lengths, uint8_t *out_mask,
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /* Rescoring.  tokens: dev int32 [B, L]; mask: dev uint8 [B, L], 1 = real; the real tokens of a row

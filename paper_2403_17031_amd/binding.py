@@ -46,13 +46,16 @@ def load_library():
         return _lib
     if not os.path.exists(LIB_PATH):
         raise RlhfError(f"{LIB_PATH} is missing: build it with `python -m paper_2403_17031_amd.build`")
+    # PyTorch ships its own HIP runtime under the same soname; it must be the one already loaded
+    # when this library is opened, or the process ends up with two runtimes and no visible device
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32, u64, f32, sz = C.c_void_p, C.c_int32, C.c_uint64, C.c_float, C.c_size_t
     lib.rlhf_create.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(vp)]
     lib.rlhf_destroy.argtypes = [vp]
     lib.rlhf_destroy.restype = None
     lib.rlhf_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz)]
-    lib.rollout_generate.argtypes = [vp, vp, vp, i32, i32, u64, u64, f32, i32, vp, vp, vp, vp, sz, vp]
+    lib.rollout_generate.argtypes = [vp, vp, vp, i32, i32, u64, u64, f32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.score_sequences.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, vp, sz, vp]
     lib.rlhf_debug_logits_rows.argtypes = [vp, vp, vp, i32, i32, C.POINTER(i32), i32, vp, vp, sz, vp]
     lib.rlhf_profile_enable.argtypes = [vp, i32]
@@ -142,9 +145,11 @@ class Policy:
         return C.c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
 
     # ------------------------------------------------------------------ calls
-    def rollout_generate(self, queries, pad_mask, seed, temperature, max_new_tokens, seq_id_base=0):
+    def rollout_generate(self, queries, pad_mask, seed, temperature, max_new_tokens, seq_id_base=0,
+                         return_mask=False):
         """queries int32 [B, Lq], pad_mask uint8 [B, Lq] (torch CUDA tensors or numpy arrays).
-        Returns CUDA tensors: tokens int32 [B, Lq+N], logprobs float32 [B, N], lengths int32 [B]."""
+        Returns CUDA tensors: tokens int32 [B, Lq+N], logprobs float32 [B, N], lengths int32 [B]
+        (and with return_mask=True the uint8 [B, Lq+N] mask that score_sequences takes)."""
         torch = self.torch
         q = self._to_dev(queries, torch.int32)
         m = self._to_dev(pad_mask, torch.uint8)
@@ -154,12 +159,14 @@ class Policy:
         toks = torch.empty((B, Lq + max(N, 0)), dtype=torch.int32, device=self.device)
         lps = torch.empty((B, max(N, 0)), dtype=torch.float32, device=self.device)
         lens = torch.empty((B,), dtype=torch.int32, device=self.device)
+        omask = torch.empty((B, Lq + max(N, 0)), dtype=torch.uint8, device=self.device) if return_mask else None
         with torch.cuda.device(self.device):
             _check(self.lib.rollout_generate(self._h, q.data_ptr(), m.data_ptr(), B, Lq, C.c_uint64(seed),
                                              C.c_uint64(seq_id_base), temperature, N, toks.data_ptr(),
-                                             lps.data_ptr(), lens.data_ptr(), ws.data_ptr(), ws.numel(),
+                                             lps.data_ptr(), lens.data_ptr(),
+                                             omask.data_ptr() if return_mask else None, ws.data_ptr(), ws.numel(),
                                              self._stream()))
-        return toks, lps, lens
+        return (toks, lps, lens, omask) if return_mask else (toks, lps, lens)
 
     def score_sequences(self, tokens, mask, temperature, want_values=True):
         """tokens int32 [B, L], mask uint8 [B, L].  Returns (logprobs, values) float32 [B, L] CUDA tensors."""

@@ -375,8 +375,8 @@ int rlhf_workspace_bytes(const rlhf_handle* h, int32_t B, int32_t Lq, int32_t ma
 
 int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_mask, int32_t B, int32_t Lq,
                      uint64_t seed, uint64_t seq_id_base, float temperature, int32_t max_new_tokens,
-                     int32_t* out_tokens, float* out_logprobs, int32_t* out_lengths, void* workspace,
-                     size_t workspace_bytes, void* stream) {
+                     int32_t* out_tokens, float* out_logprobs, int32_t* out_lengths, uint8_t* out_mask,
+                     void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_common(h, B, Lq);
   if (rc) return rc;
   if (max_new_tokens <= 0) return fail(RLHF_EINVAL, "max_new_tokens must be > 0");
@@ -398,7 +398,7 @@ int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_
   HIP_OK(hipEventRecord(h->ph[0], s));
 
   const Meta& m = ws.meta;
-  LAUNCH("copy_queries", launch_copy_queries(queries, B, Lq, N, c.pad_id, out_tokens, s));
+  LAUNCH("copy_queries", launch_copy_queries(queries, pad_mask, B, Lq, N, c.pad_id, out_tokens, out_mask, s));
   LAUNCH("row_spans", launch_row_spans(pad_mask, B, Lq, N - 1, m.start, m.len, m.cu, m.kvoff, m.total, s));
   LAUNCH("pack_embed", launch_pack_embed(dt, queries, B, Lq, m.start, m.len, m.cu, h->w.embed_in, d, c.vocab,
                                          m.pos, m.rowid, m.tok, ws.acts.x, s));
@@ -428,7 +428,7 @@ int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_
   sa.seed = seed; sa.seq_base = seq_id_base; sa.temperature = temperature;
   sa.eos_id = c.eos_id; sa.pad_id = c.pad_id;
   sa.len = m.len; sa.finished = ws.finished; sa.cur_tok = ws.cur_tok;
-  sa.out_tokens = out_tokens; sa.out_logprobs = out_logprobs; sa.out_lengths = out_lengths;
+  sa.out_tokens = out_tokens; sa.out_logprobs = out_logprobs; sa.out_lengths = out_lengths; sa.out_mask = out_mask;
 
   GemmArgs lm;
   lm.A = ws.hl; lm.W = h->embed_out_mm; lm.bias = nullptr; lm.out = ws.logits;

@@ -145,10 +145,11 @@ struct SampleArgs {
   int32_t* out_tokens;  // [B, Lq+N]
   float* out_logprobs;  // [B, N]
   int32_t* out_lengths; // [B]
+  uint8_t* out_mask;    // [B, Lq+N] or null
 };
 hipError_t launch_sampler(const SampleArgs& a, hipStream_t s);
-hipError_t launch_copy_queries(const int32_t* queries, int B, int Lq, int N, int pad_id, int32_t* out_tokens,
-                               hipStream_t s);
+hipError_t launch_copy_queries(const int32_t* queries, const uint8_t* pad_mask, int B, int Lq, int N, int pad_id,
+                               int32_t* out_tokens, uint8_t* out_mask, hipStream_t s);
 
 // Scoring: log softmax(logits[t]/T)[tok[t+1]] for packed rows t0 .. t0+rows of a logits chunk;
 // result goes to lp_packed[t+1] when t+1 belongs to the same sequence.

@@ -337,6 +337,7 @@ __global__ void __launch_bounds__(1024) sampler_kernel(SampleArgs a) {
     int fin = (a.step == 0) ? (a.len[b] == 0 ? 1 : 0) : a.finished[b];
     if (a.step == 0) a.out_lengths[b] = (a.len[b] == 0) ? 0 : a.N;
     const size_t to = (size_t)b * (a.Lq + a.N) + a.Lq + a.step;
+    if (a.out_mask) a.out_mask[to] = fin ? 0 : 1;
     if (fin) {
       a.out_tokens[to] = a.pad_id;
       a.out_logprobs[(size_t)b * a.N + a.step] = 0.f;
@@ -358,16 +359,20 @@ hipError_t launch_sampler(const SampleArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-__global__ void copy_queries_kernel(const int32_t* __restrict__ queries, int Lq, int N, int pad_id,
-                                    int32_t* __restrict__ out) {
+__global__ void copy_queries_kernel(const int32_t* __restrict__ queries, const uint8_t* __restrict__ pad_mask,
+                                    int Lq, int N, int pad_id, int32_t* __restrict__ out,
+                                    uint8_t* __restrict__ out_mask) {
   const int b = blockIdx.x;
-  for (int c = threadIdx.x; c < Lq + N; c += blockDim.x)
+  for (int c = threadIdx.x; c < Lq + N; c += blockDim.x) {
     out[(size_t)b * (Lq + N) + c] = c < Lq ? queries[(size_t)b * Lq + c] : pad_id;
+    if (out_mask) out_mask[(size_t)b * (Lq + N) + c] = c < Lq ? (pad_mask[(size_t)b * Lq + c] ? 1 : 0) : 0;
+  }
 }
 
-hipError_t launch_copy_queries(const int32_t* queries, int B, int Lq, int N, int pad_id, int32_t* out_tokens,
-                               hipStream_t s) {
-  hipLaunchKernelGGL(copy_queries_kernel, dim3(B), dim3(256), 0, s, queries, Lq, N, pad_id, out_tokens);
+hipError_t launch_copy_queries(const int32_t* queries, const uint8_t* pad_mask, int B, int Lq, int N, int pad_id,
+                               int32_t* out_tokens, uint8_t* out_mask, hipStream_t s) {
+  hipLaunchKernelGGL(copy_queries_kernel, dim3(B), dim3(256), 0, s, queries, pad_mask, Lq, N, pad_id, out_tokens,
+                     out_mask);
   return hipGetLastError();
 }
 

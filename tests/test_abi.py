@@ -37,7 +37,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert b"null" in lib.rlhf_last_error()
     sz = C.c_size_t()
     assert lib.rlhf_workspace_bytes(None, 1, 1, 1, 1, C.byref(sz)) == -1
-    assert lib.rollout_generate(None, None, None, 1, 1, 0, 0, 0.7, 1, None, None, None, None, 0, None) == -1
+    assert lib.rollout_generate(None, None, None, 1, 1, 0, 0, 0.7, 1, None, None, None, None, None, 0, None) == -1
     assert lib.score_sequences(None, None, None, 1, 1, 0.7, None, None, None, 0, None) == -1
     lib.rlhf_destroy(None)  # no-op
 

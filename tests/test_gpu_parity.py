@@ -43,7 +43,8 @@ def _check_rollout_and_scores(P, cfg, w, queries, mask, seed, T, N, rows=None, e
     m = O.OracleModel(w, cfg)
     pol = P.Policy(cfg, w)
     B, Lq = queries.shape
-    toks, lps, lens = (x.cpu().numpy() for x in pol.rollout_generate(queries, mask, seed, T, N))
+    toks, lps, lens, omask = (x.cpu().numpy() for x in pol.rollout_generate(queries, mask, seed, T, N,
+                                                                           return_mask=True))
     assert (toks[:, :Lq] == queries).all()
     rows = list(range(B)) if rows is None else rows
     # (1) every sampled token is the oracle's choice on the same prefix, or a near-tie
@@ -69,6 +70,7 @@ def _check_rollout_and_scores(P, cfg, w, queries, mask, seed, T, N, rows=None, e
     assert sum(1 for r in rep) == int(sum(lens[b] for b in rows))
     # (3) rescoring of the GPU's own rollout: oracle values/logprobs, and consistency with the rollout
     full_mask = np.concatenate([mask, (np.arange(N)[None, :] < lens[:, None]).astype(np.uint8)], axis=1)
+    assert (omask == full_mask).all()
     glp, gval = (x.cpu().numpy() for x in pol.score_sequences(toks, full_mask, T))
     olp, oval = O.score_sequences(m, toks[rows], full_mask[rows], T)
     np.testing.assert_allclose(glp[rows], olp, atol=tol, rtol=0)
@@ -207,10 +209,10 @@ def test_error_codes(gpu, tiny_cfg):
     ln = torch.empty((2,), dtype=torch.int32, device="cuda")
     small = torch.empty(1024, dtype=torch.uint8, device="cuda")
     rc = lib.rollout_generate(pol._h, q.data_ptr(), m.data_ptr(), 2, 8, 1, 0, 0.7, 4, out.data_ptr(), lp.data_ptr(),
-                              ln.data_ptr(), small.data_ptr(), small.numel(), None)
+                              ln.data_ptr(), None, small.data_ptr(), small.numel(), None)
     assert rc == -2 and b"workspace" in lib.rlhf_last_error()
     rc = lib.rollout_generate(pol._h, None, m.data_ptr(), 2, 8, 1, 0, 0.7, 4, out.data_ptr(), lp.data_ptr(),
-                              ln.data_ptr(), small.data_ptr(), small.numel(), None)
+                              ln.data_ptr(), None, small.data_ptr(), small.numel(), None)
     assert rc == -1
     pol.close()
     bad = cfg.with_(head_dim=17)

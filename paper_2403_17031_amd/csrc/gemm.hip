@@ -2,18 +2,38 @@
 // natural operand order of the CDNA matrix cores: every lane loads 8 consecutive K elements of one
 // row of A and of one row of W.
 //
-//  * bf16 mode (fp16 operands): v_mfma_f32_32x32x16_f16, 128x128 block tile, 4 waves (2x2) of 64x64, K step 64,
-//          LDS double buffer with global->register->LDS staging, fp32 accumulation.
+//  * bf16 mode (fp16 operands): v_mfma_f32_32x32x16_f16, 256x256 block tile, 4 waves (2x2) of
+//    128x128 (256 fp32 accumulators per lane, so a wave reads 8 operand fragments from LDS per 16
+//    matrix instructions), K step 64 (a tile row is one full 128-byte line), one 64 KB LDS stage
+//    with XOR-swizzled 16-byte chunks (conflict-free ds_read_b128), the next tile held in
+//    registers while the current one is multiplied, workgroup ids remapped so that the 32 tiles
+//    resident on one XCD share A and W panels in that XCD's L2.
 //  * fp32: plain FMA tile kernel (check mode only; not tuned).
 #include "common.h"
 
 namespace rlhf {
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+
+// GELU for fp16 outputs: erf by the classical five-term rational-times-Gaussian approximation
+// (absolute error below 1.5e-7, far under the 2^-11 relative rounding of the fp16 result).
+__device__ __forceinline__ float gelu_f16out(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __frcp_rn(fmaf(0.3275911f, z, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float q = p * t * __expf(-z * z);  // 1 - erf(z), z >= 0
+  const float half_x = 0.5f * x;
+  return x >= 0.f ? fmaf(-half_x, q, x) : half_x * q;  // x >= 0: x * (1 - q/2);  x < 0: (x/2) * q
+}
 
 template <int EPI, typename T>
 __device__ __forceinline__ void epilogue_store(void* out, size_t idx, float acc, float bias) {
@@ -31,93 +51,169 @@ __device__ __forceinline__ void epilogue_store(void* out, size_t idx, float acc,
 // =================================================================================================
 // fp16-operand MFMA kernel
 // =================================================================================================
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int LDS_ROW = BK + 8;  // 16-bit elements per LDS row: +16 bytes so that 16 consecutive rows
-                                 // start in 16 different 16-byte bank groups
+constexpr int TK = 64;
+constexpr int GROUP_M = 4;  // m-tiles per scheduling group
 
-template <int EPI>
-__global__ void __launch_bounds__(256)
+// LDS position (in halfs) of logical 16-byte chunk c (0..7) of tile row r (A rows first, then W
+// rows): rows are 128 B apart; the chunk index is XORed with bits 1..3 of the row so that 16
+// consecutive rows reading the same logical chunk hit 16 different 16-byte bank groups.
+__device__ __forceinline__ int lds_pos(int r, int c) { return r * TK + ((c ^ ((r >> 1) & 7)) << 3); }
+
+// MT x NT: 32x32 accumulator tiles per wave along M and N; the block is 2x2 waves.
+template <int EPI, int MT, int NT>
+__global__ void __launch_bounds__(256, (MT * NT > 8 ? 1 : 2))
     gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
-                     void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K, int ldo) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[2][2][BM * LDS_ROW];  // [buffer][A|W]
+                    void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
+                    int ldo, int nb_m, int nb_n) {
+  constexpr int TM = 64 * MT, TN = 64 * NT;
+  constexpr int NLD = (TM + TN) / 32;  // 16-byte chunks per thread per k-step
+  constexpr int NLD_A = TM / 32;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[(TM + TN) * TK];
   const int M = M_dev ? min(M_max, *M_dev - M_sub) : M_max;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+  // ---- tile assignment: workgroup w runs on XCD w % 8; give each XCD a contiguous run of tiles,
+  //      ordered so that consecutive tiles walk GROUP_M m-tiles for each n-tile.
+  const int total = nb_m * nb_n;
+  const int per_xcd = (total + 7) >> 3;
+  const int lt = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (lt >= total) return;
+  const int group_sz = GROUP_M * nb_n;
+  const int grp = lt / group_sz, rem = lt - grp * group_sz;
+  const int gm = min(GROUP_M, nb_m - grp * GROUP_M);
+  const int tm = grp * GROUP_M + rem % gm, tn = rem / gm;
+  const int m0 = tm * TM, n0 = tn * TN;
   if (m0 >= M) return;
+
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int wm = (wave >> 1) * (32 * MT), wn = (wave & 1) * (32 * NT);
 
-  // staging: tile = 128 rows x 8 chunks of 16 B; thread handles chunk ids tid + 256*i, i < 4
-  const int ld_row = tid >> 3, ld_kc = tid & 7;  // rows ld_row + 32*i
-  u32x4_t ra[4], rw[4];
-  auto load_tiles = [&](int k0) {
-    const int k = k0 + ld_kc * 8;
-    const bool kok = k < K;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = ld_row + 32 * i;
-      const int ar = min(m0 + r, M - 1), wr = min(n0 + r, N - 1);
-      u32x4_t z = {0, 0, 0, 0};
-      ra[i] = kok ? *(const u32x4_t*)(A + (size_t)ar * K + k) : z;
-      rw[i] = kok ? *(const u32x4_t*)(W + (size_t)wr * K + k) : z;
-    }
+  // ---- global -> register staging: a row of the tile is one full 128-byte line, read by 8
+  //      consecutive lanes; thread handles rows ld_r + 32*i (A rows first, then W rows)
+  const int ld_r = tid >> 3, ld_c = tid & 7;
+  // element offset of this thread's chunk i from A (i < NLD_A) or W, recomputed per use: keeping
+  // NLD offsets live would push the kernel past 256 registers and into scratch
+  auto goff = [&](int i) -> uint32_t {
+    const int r = ld_r + 32 * (i < NLD_A ? i : i - NLD_A);
+    return (uint32_t)((i < NLD_A ? min(m0 + r, M - 1) : min(n0 + r, N - 1)) * K + ld_c * 8);
   };
-  auto store_tiles = [&](int buf) {
+  const int st_off = lds_pos(ld_r, ld_c);  // + 32*i rows: (r>>1)&7 is unchanged by adding 32*i
+  u32x4_t stage[NLD];
+  // Full K tiles load unconditionally (a select on the loaded value would force the wave to wait
+  // for the data right away); only a ragged last tile takes the guarded form.
+  auto load_global = [&](int k0) {
+    if (k0 + TK <= K) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = ld_row + 32 * i;
-      *(u32x4_t*)(&lds[buf][0][r * LDS_ROW + ld_kc * 8]) = ra[i];
-      *(u32x4_t*)(&lds[buf][1][r * LDS_ROW + ld_kc * 8]) = rw[i];
-    }
-  };
-
-  f32x16_t acc[2][2];
+      for (int i = 0; i < NLD; ++i) stage[i] = *(const u32x4_t*)((i < NLD_A ? A : W) + goff(i) + k0);
+    } else {
+      const bool kok = k0 + ld_c * 8 < K;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  const int nk = (K + BK - 1) / BK;
-  load_tiles(0);
-  store_tiles(0);
-  __syncthreads();
-  const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) load_tiles((kt + 1) * BK);
-    const uint16_t* la = lds[buf][0];
-    const uint16_t* lw = lds[buf][1];
-#pragma unroll
-    for (int ks = 0; ks < BK; ks += 16) {
-      f16x8_t fa[2], fw[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        fa[i] = *(const f16x8_t*)(la + (wm + i * 32 + frag_row) * LDS_ROW + ks + frag_k);
-        fw[i] = *(const f16x8_t*)(lw + (wn + i * 32 + frag_row) * LDS_ROW + ks + frag_k);
+      for (int i = 0; i < NLD; ++i) {
+        u32x4_t z = {0, 0, 0, 0};
+        if (kok) z = *(const u32x4_t*)((i < NLD_A ? A : W) + goff(i) + k0);
+        stage[i] = z;
       }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fw[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_tiles(buf ^ 1);
+  };
+  auto store_lds = [&]() {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) *(u32x4_t*)(lds + st_off + 32 * i * TK) = stage[i];
+  };
+
+  // ---- fragment addressing: lane reads row (lane & 31) of a 32-row fragment, logical chunk
+  //      2*ks + (lane >> 5); the swizzle key depends on (lane & 31) >> 1 only.
+  const int key = ((lane & 31) >> 1) & 7;
+  const int fr = (lane & 31) * TK;
+  const int a_off = wm * TK + fr, w_off = (TM + wn) * TK + fr;
+
+  f32x16_t acc[NT][MT];  // [j over N][i over M]
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
+
+  const int nk = (K + TK - 1) / TK;
+  load_global(0);
+  for (int kt = 0; kt < nk; ++kt) {
+    store_lds();
+    __syncthreads();
+    if (kt + 1 < nk) load_global((kt + 1) * TK);  // in flight during the whole k-step of math
+    // Fragments are double-buffered by hand and the scheduler is fenced, so that the LDS reads of
+    // sub-step ks+1 are in flight while the matrix instructions of sub-step ks issue (left alone,
+    // the compiler re-reads into one register quad and waits before every few MFMAs).
+    constexpr int FB = (MT * NT > 8) ? 2 : 1;  // fragment buffers: two when one wave owns the SIMD
+    f16x8_t fa[FB][MT], fw[FB][NT];
+    auto load_frags = [&](int buf, int ks) {
+      const int ch = ((2 * ks + (lane >> 5)) ^ key) << 3;
+#pragma unroll
+      for (int i = 0; i < MT; ++i) fa[buf][i] = *(const f16x8_t*)(lds + a_off + i * 32 * TK + ch);
+#pragma unroll
+      for (int j = 0; j < NT; ++j) fw[buf][j] = *(const f16x8_t*)(lds + w_off + j * 32 * TK + ch);
+    };
+    if (FB == 2) load_frags(0, 0);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      if (FB == 2) {
+        if (ks < 3) load_frags((ks + 1) & 1, ks + 1);
+      } else {
+        load_frags(0, ks);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // weights as the first operand: accumulator element e of a lane is then
+      // (n = 8*(e/4) + 4*(lane/32) + e%4, m = lane%32), i.e. 4 consecutive output columns per lane
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+          acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[ks & (FB - 1)][j], fa[ks & (FB - 1)][i], acc[j][i],
+                                                             0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     __syncthreads();
   }
 
-  // accumulator element e of lane l: row (e/4)*8 + (l/32)*4 + e%4, column l%32 of the 32x32 tile
+  // ---- epilogue
+  const bool vec_ok = (ldo & 3) == 0;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int col = n0 + wn + j * 32 + (lane & 31);
-    if (col >= N) continue;
-    const float bv = (EPI != EPI_F32 && bias) ? to_f32(bias[col]) : 0.f;
+  for (int j = 0; j < NT; ++j) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int g = 0; g < 4; ++g) {
+      const int nb = n0 + wn + 32 * j + 8 * g + 4 * (lane >> 5);
+      if (nb >= N) continue;
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (EPI != EPI_F32 && bias) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        if (row < M) epilogue_store<EPI, half_t>(out, (size_t)row * ldo + col, acc[i][j][e], bv);
+        for (int u = 0; u < 4; ++u) bv[u] = (nb + u < N) ? to_f32(bias[nb + u]) : 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        const int row = m0 + wm + 32 * i + (lane & 31);
+        if (row >= M) continue;
+        const size_t o = (size_t)row * ldo + nb;
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = acc[j][i][4 * g + u] + bv[u];
+        if (vec_ok && nb + 4 <= N) {
+          if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU) {
+            f16x4_t h;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) h[u] = from_f32<half_t>(EPI == EPI_BIAS_GELU ? gelu_f16out(v[u]) : v[u]);
+            *(f16x4_t*)((half_t*)out + o) = h;
+          } else if (EPI == EPI_BIAS_RESADD) {
+            f32x4_t x = *(f32x4_t*)((float*)out + o);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x[u] += v[u];
+            *(f32x4_t*)((float*)out + o) = x;
+          } else {
+            f32x4_t x = {v[0], v[1], v[2], v[3]};
+            *(f32x4_t*)((float*)out + o) = x;
+          }
+        } else {
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (nb + u < N) epilogue_store<EPI, half_t>(out, o + u, acc[j][i][4 * g + u], bv[u]);
+        }
       }
     }
   }
@@ -176,6 +272,11 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+#ifndef RLHF_GEMM_MT
+#define RLHF_GEMM_MT 2
+#define RLHF_GEMM_NT 4
+#endif
+
 template <int EPI>
 static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
   if (dtype == 0) {
@@ -183,9 +284,12 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(gemm_f32_kernel<EPI>, grid, dim3(256), 0, s, (const float*)a.A, (const float*)a.W,
                        (const float*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo);
   } else {
-    dim3 grid((a.N + BN - 1) / BN, (a.M_max + BM - 1) / BM);
-    hipLaunchKernelGGL(gemm_f16_kernel<EPI>, grid, dim3(256), 0, s, (const half_t*)a.A, (const half_t*)a.W,
-                       (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo);
+    constexpr int MT = RLHF_GEMM_MT, NT = RLHF_GEMM_NT;
+    const int nb_m = (a.M_max + 64 * MT - 1) / (64 * MT), nb_n = (a.N + 64 * NT - 1) / (64 * NT);
+    const int per_xcd = (nb_m * nb_n + 7) / 8;
+    hipLaunchKernelGGL((gemm_f16_kernel<EPI, MT, NT>), dim3(per_xcd * 8), dim3(256), 0, s, (const half_t*)a.A,
+                       (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
+                       nb_m, nb_n);
   }
 }
 

@@ -51,6 +51,8 @@ struct Meta {
 struct Acts {
   float* x;
   void *a, *m, *qkv, *q, *att, *ffn;
+  void* splitk = nullptr;  // fp32 partial sums of the decode GEMMs
+  size_t splitk_bytes = 0;
 };
 
 }  // namespace
@@ -158,6 +160,8 @@ RolloutWs carve_rollout(Carver& c, const rlhf_model_config& cfg, int B, int Lq, 
   w.cur_tok = c.take<int>(B);
   w.hl = c.take_bytes((size_t)B * cfg.d_model * esz);
   w.logits = c.take<float>((size_t)B * cfg.vocab);
+  w.acts.splitk_bytes = (size_t)16 * B * std::max(3 * cfg.d_model, cfg.d_ff) * sizeof(float);
+  w.acts.splitk = c.take_bytes(w.acts.splitk_bytes);
   w.kv_slots = (size_t)B * (Lq + N - 1);
   w.kv = (char*)c.take_bytes((size_t)cfg.n_layers * 2 * w.kv_slots * cfg.d_model * esz);
   return w;
@@ -220,6 +224,10 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
     GemmArgs g;
     g.M_max = p.rows_max;
     g.M_dev = p.rows_dev;
+    if (p.mode == 1) {
+      g.splitk_ws = A.splitk;
+      g.splitk_ws_bytes = A.splitk_bytes;
+    }
     g.A = A.a; g.W = h->w_qkv[l]; g.bias = h->b_qkv[l]; g.out = A.qkv; g.N = 3 * d; g.K = d; g.ldo = 3 * d;
     g.epilogue = EPI_BIAS;
     LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));

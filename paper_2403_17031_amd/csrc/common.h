@@ -87,6 +87,8 @@ struct GemmArgs {
   int M_sub = 0;      // with M_dev: M = min(M_max, *M_dev - M_sub)  (row chunk starting at M_sub)
   int N, K, ldo;
   int epilogue;
+  void* splitk_ws = nullptr;   // fp32 scratch for split-K partial sums (decode-sized M), or null
+  size_t splitk_ws_bytes = 0;
 };
 hipError_t launch_gemm(int dtype, const GemmArgs& a, hipStream_t s);
 

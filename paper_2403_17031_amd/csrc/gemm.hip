@@ -61,10 +61,10 @@ __device__ __forceinline__ int lds_pos(int r, int c) { return r * TK + ((c ^ ((r
 
 // MT x NT: 32x32 accumulator tiles per wave along M and N; the block is 2x2 waves.
 template <int EPI, int MT, int NT>
-__global__ void __launch_bounds__(256, (MT * NT > 8 ? 1 : 2))
+__global__ void __launch_bounds__(256, (MT * NT > 8 ? 1 : (MT * NT > 2 ? 2 : 4)))
     gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
                     void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
-                    int ldo, int nb_m, int nb_n) {
+                    int ldo, int nb_m, int nb_n, int ksplit) {
   constexpr int TM = 64 * MT, TN = 64 * NT;
   constexpr int NLD = (TM + TN) / 32;  // 16-byte chunks per thread per k-step
   constexpr int NLD_A = TM / 32;
@@ -73,8 +73,11 @@ __global__ void __launch_bounds__(256, (MT * NT > 8 ? 1 : 2))
 
   // ---- tile assignment: workgroup w runs on XCD w % 8; give each XCD a contiguous run of tiles,
   //      ordered so that consecutive tiles walk GROUP_M m-tiles for each n-tile.
+  //      The split uses the device-side row count, so that tiles past it do not leave XCDs idle.
+  nb_m = min(nb_m, (M + TM - 1) / TM);
   const int total = nb_m * nb_n;
   const int per_xcd = (total + 7) >> 3;
+  if ((int)(blockIdx.x >> 3) >= per_xcd) return;
   const int lt = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (lt >= total) return;
   const int group_sz = GROUP_M * nb_n;
@@ -133,9 +136,15 @@ __global__ void __launch_bounds__(256, (MT * NT > 8 ? 1 : 2))
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
 
-  const int nk = (K + TK - 1) / TK;
-  load_global(0);
-  for (int kt = 0; kt < nk; ++kt) {
+  // split-K: block z = blockIdx.y owns k-steps [kt0, nk); its fp32 partial sums go to slab z of
+  // `out` ([ksplit][M_max][ldo]) and a second kernel adds the slabs in a fixed order
+  const int nk_all = (K + TK - 1) / TK;
+  const int per_split = (nk_all + ksplit - 1) / ksplit;
+  const int kt0 = blockIdx.y * per_split;
+  const int nk = min(nk_all, kt0 + per_split);
+  if (ksplit > 1) out = (float*)out + (size_t)blockIdx.y * M_max * ldo;
+  if (kt0 < nk) load_global(kt0 * TK);
+  for (int kt = kt0; kt < nk; ++kt) {
     store_lds();
     __syncthreads();
     if (kt + 1 < nk) load_global((kt + 1) * TK);  // in flight during the whole k-step of math
@@ -277,6 +286,31 @@ __global__ void __launch_bounds__(256)
 #define RLHF_GEMM_NT 4
 #endif
 
+template <int EPI, int MT, int NT>
+static void launch_f16(const GemmArgs& a, hipStream_t s, void* out, int ksplit) {
+  const int nb_m = (a.M_max + 64 * MT - 1) / (64 * MT), nb_n = (a.N + 64 * NT - 1) / (64 * NT);
+  const int per_xcd = (nb_m * nb_n + 7) / 8;
+  hipLaunchKernelGGL((gemm_f16_kernel<EPI, MT, NT>), dim3(per_xcd * 8, ksplit), dim3(256), 0, s,
+                     (const half_t*)a.A, (const half_t*)a.W, (const bf16_t*)a.bias, out, a.M_max, a.M_dev, a.M_sub,
+                     a.N, a.K, a.ldo, nb_m, nb_n, ksplit);
+}
+
+// out = epilogue(sum_z partial[z] + bias), slabs added in index order: deterministic.
+template <int EPI>
+__global__ void __launch_bounds__(256)
+    splitk_reduce_kernel(const float* __restrict__ part, int ksplit, size_t slab, const bf16_t* __restrict__ bias,
+                         void* __restrict__ out, int M, int N, int ldo) {
+  const size_t i4 = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i4 >= (size_t)M * ldo) return;
+  const int col = (int)(i4 % ldo);
+  if (col >= N) return;
+  f32x4_t v = *(const f32x4_t*)(part + i4);
+  for (int z = 1; z < ksplit; ++z) v += *(const f32x4_t*)(part + z * slab + i4);
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (col + u < N) epilogue_store<EPI, half_t>(out, i4 + u, v[u], (EPI != EPI_F32 && bias) ? to_f32(bias[col + u]) : 0.f);
+}
+
 template <int EPI>
 static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
   if (dtype == 0) {
@@ -284,12 +318,27 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(gemm_f32_kernel<EPI>, grid, dim3(256), 0, s, (const float*)a.A, (const float*)a.W,
                        (const float*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo);
   } else {
-    constexpr int MT = RLHF_GEMM_MT, NT = RLHF_GEMM_NT;
-    const int nb_m = (a.M_max + 64 * MT - 1) / (64 * MT), nb_n = (a.N + 64 * NT - 1) / (64 * NT);
-    const int per_xcd = (nb_m * nb_n + 7) / 8;
-    hipLaunchKernelGGL((gemm_f16_kernel<EPI, MT, NT>), dim3(per_xcd * 8), dim3(256), 0, s, (const half_t*)a.A,
-                       (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
-                       nb_m, nb_n);
+    // Few rows (decode): the chip is filled by small N tiles and by splitting K, so that every CU
+    // holds several short k-loops in flight; partial sums go through the caller's fp32 scratch.
+    if (a.M_max <= 512 && a.splitk_ws && (a.ldo & 3) == 0) {
+      const int tiles = ((a.M_max + 127) / 128) * ((a.N + 63) / 64);
+      const int nk = (a.K + TK - 1) / TK;
+      int ksplit = 1;
+      while (ksplit < 16 && tiles * ksplit < 1024 && nk / (ksplit * 2) >= 4) ksplit *= 2;
+      const size_t need = (size_t)ksplit * a.M_max * a.ldo * sizeof(float);
+      if (ksplit > 1 && need <= a.splitk_ws_bytes) {
+        launch_f16<EPI_F32, 2, 1>(a, s, a.splitk_ws, ksplit);
+        const size_t n4 = ((size_t)a.M_max * a.ldo + 3) / 4;
+        hipLaunchKernelGGL(splitk_reduce_kernel<EPI>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
+                           (const float*)a.splitk_ws, ksplit, (size_t)a.M_max * a.ldo, (const bf16_t*)a.bias, a.out,
+                           a.M_max, a.N, a.ldo);
+        return;
+      }
+    }
+    if (a.M_max <= 512)
+      launch_f16<EPI, 2, 1>(a, s, a.out, 1);
+    else
+      launch_f16<EPI, RLHF_GEMM_MT, RLHF_GEMM_NT>(a, s, a.out, 1);
   }
 }
 

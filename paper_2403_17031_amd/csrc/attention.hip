@@ -101,10 +101,181 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+
+// =================================================================================================
+// MFMA flash attention (fp16 operands, fp32 softmax and accumulation), head_dim HD a multiple of 16.
+//
+// Block = 4 waves; wave w owns 32 queries, all work is per wave except the shared K / V tile.
+// Scores are produced transposed, S^T[key][q] = K Q^T, so that a lane holds one query (lane % 32)
+// and 16 of each 32 keys: the running max / sum are per-lane scalars, shared with lane ^ 32 only.
+// The probabilities then feed O^T[d][q] = V^T P^T straight from registers: the accumulator layout
+// of S^T is the operand layout of P^T up to a fixed permutation of the 16 keys of a k-step, and
+// the V tile is stored in LDS transposed with that same permutation applied.
+// =================================================================================================
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+constexpr int FA_BQ = 128, FA_BK = 64;
+constexpr int FA_VT_STRIDE = FA_BK + 8;  // halfs per V^T row: 144 B, odd multiple of 16 B
+
+template <int HD>
+__global__ void __launch_bounds__(256)
+    attn_prefill_mfma(const half_t* __restrict__ q, const half_t* __restrict__ kc, const half_t* __restrict__ vc,
+                      long kv_head_stride, const int* __restrict__ len, const int* __restrict__ cu,
+                      const int* __restrict__ kvoff, int H, float scale_log2e, half_t* __restrict__ out) {
+  constexpr int NKS = HD / 16;         // k-steps of the Q K^T contraction
+  constexpr int NDT = (HD + 31) / 32;  // 32-row tiles of O^T
+  constexpr int K_STRIDE = HD + 8;     // halfs per K row: odd multiple of 16 B for every HD used
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[FA_BK * K_STRIDE];
+  __shared__ __attribute__((aligned(16))) uint16_t Vt[NDT * 32 * FA_VT_STRIDE];
+  const int b = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * FA_BQ;
+  const int n = len[b];
+  if (q0 >= n) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, l32 = lane & 31;
+  const int d = H * HD;
+  const half_t* kb = kc + (size_t)h * kv_head_stride + (size_t)kvoff[b] * HD;
+  const half_t* vb = vc + (size_t)h * kv_head_stride + (size_t)kvoff[b] * HD;
+
+  // rows of V^T beyond HD are never loaded: zero them once
+  for (int c = tid; c < (NDT * 32 - HD) * FA_VT_STRIDE; c += 256) Vt[HD * FA_VT_STRIDE + c] = 0;
+
+  // this lane's query and its Q fragments (kept in registers for the whole block)
+  const int qi = q0 + wave * 32 + l32;
+  const half_t* qrow = q + ((size_t)cu[b] + min(qi, n - 1)) * d + (size_t)h * HD;
+  f16x8_t qf[NKS];
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const f16x8_t*)(qrow + 16 * ks + 8 * half);
+
+  f32x16_t o[NDT];
+#pragma unroll
+  for (int t = 0; t < NDT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;  // l_run: sum over this lane's keys only
+
+  const int q_hi = min(q0 + FA_BQ, n) - 1;           // last query of the block
+  const int wq_lo = q0 + wave * 32;                  // first query of the wave
+  for (int k0 = 0; k0 <= q_hi; k0 += FA_BK) {
+    __syncthreads();
+    // K tile, row-major; keys past the sequence are clamped (their scores are masked below)
+    for (int c = tid; c < FA_BK * (HD / 8); c += 256) {
+      const int r = c / (HD / 8), ch = c - r * (HD / 8);
+      const u32x4_t v = *(const u32x4_t*)(kb + (size_t)min(k0 + r, n - 1) * HD + ch * 8);
+      *(u32x4_t*)(Ks + r * K_STRIDE + ch * 8) = v;
+    }
+    // V tile, transposed: consecutive lanes take consecutive keys, so that each of the 8 stores of
+    // a lane lands in one contiguous 128-byte row segment of V^T.  Key kk of a 16-key group goes
+    // to column 8*((kk>>2)&1) + (kk&3) + 4*(kk>>3) of that group.
+    for (int c = tid; c < FA_BK * (HD / 8); c += 256) {
+      const int ch = c / FA_BK, r = c - ch * FA_BK;
+      const f16x8_t v = *(const f16x8_t*)(vb + (size_t)min(k0 + r, n - 1) * HD + ch * 8);
+      const int kk = r & 15;
+      const int col = (r & ~15) + 8 * ((kk >> 2) & 1) + (kk & 3) + 4 * (kk >> 3);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ((half_t*)Vt)[(ch * 8 + i) * FA_VT_STRIDE + col] = v[i];
+    }
+    __syncthreads();
+    if (k0 > wq_lo + 31) continue;  // every key of this tile is in the future of this wave's queries
+
+    // ---- S^T = K Q^T for the two 32-key fragments
+    f32x16_t st[2];
+#pragma unroll
+    for (int kf = 0; kf < 2; ++kf) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) st[kf][e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const f16x8_t kfrag = *(const f16x8_t*)(Ks + (kf * 32 + l32) * K_STRIDE + 16 * ks + 8 * half);
+        st[kf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kfrag, qf[ks], st[kf], 0, 0, 0);
+      }
+    }
+    // ---- mask (only tiles that touch the diagonal or the end of the sequence), scale, running max
+    const bool need_mask = (k0 + FA_BK - 1 > wq_lo) || (k0 + FA_BK > n);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kf = 0; kf < 2; ++kf)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        float v = st[kf][e] * scale_log2e;
+        if (need_mask) {
+          const int kj = k0 + kf * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+          if (kj > qi || kj >= n) v = -INFINITY;
+        }
+        st[kf][e] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);  // finite: key 0 is visible to every query
+    const float alpha = exp2f(m_run - m_new);
+    m_run = m_new;
+    float psum = 0.f;
+    f16x8_t pf[4];  // P^T operand of each 16-key step
+#pragma unroll
+    for (int kf = 0; kf < 2; ++kf)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float p = exp2f(st[kf][e] - m_new);
+        psum += p;
+        pf[kf * 2 + (e >> 3)][e & 7] = (half_t)p;
+      }
+    l_run = l_run * alpha + psum;
+    // ---- O^T = alpha * O^T + V^T P^T
+#pragma unroll
+    for (int t = 0; t < NDT; ++t) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const f16x8_t vfrag = *(const f16x8_t*)(Vt + (t * 32 + l32) * FA_VT_STRIDE + 16 * c + 8 * half);
+        o[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vfrag, pf[c], o[t], 0, 0, 0);
+      }
+    }
+  }
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (qi < n) {
+    const float inv = 1.0f / l_tot;
+    half_t* orow = out + ((size_t)cu[b] + qi) * d + (size_t)h * HD;
+#pragma unroll
+    for (int t = 0; t < NDT; ++t)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int dd = 32 * t + 8 * g + 4 * half;
+        if (dd < HD) {  // HD is a multiple of 4, so the 4 columns are in range together
+          f16x4_t v;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) v[u] = from_f32<half_t>(o[t][4 * g + u] * inv);
+          *(f16x4_t*)(orow + dd) = v;
+        }
+      }
+  }
+}
+
+template <int HD>
+static void launch_fa(const void* q, const void* kc, const void* vc, long kv_head_stride, int B, int Lmax,
+                      const int* len, const int* cu, const int* kvoff, int H, void* out, hipStream_t s) {
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
+  dim3 grid((Lmax + FA_BQ - 1) / FA_BQ, H, B);
+  hipLaunchKernelGGL(attn_prefill_mfma<HD>, grid, dim3(256), 0, s, (const half_t*)q, (const half_t*)kc,
+                     (const half_t*)vc, kv_head_stride, len, cu, kvoff, H, scale_log2e, (half_t*)out);
+}
+
 hipError_t launch_attn_prefill(int dtype, const void* q, const void* kc, const void* vc, long kv_head_stride,
                                int B, int Lmax, const int* len, const int* cu, const int* kvoff, int H, int hd,
                                void* out, hipStream_t s) {
   if (hd > 256) return hipErrorInvalidValue;
+  if (dtype == 1) {
+    switch (hd) {
+      case 16: launch_fa<16>(q, kc, vc, kv_head_stride, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
+      case 64: launch_fa<64>(q, kc, vc, kv_head_stride, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
+      case 80: launch_fa<80>(q, kc, vc, kv_head_stride, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
+      case 128: launch_fa<128>(q, kc, vc, kv_head_stride, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
+      case 256: launch_fa<256>(q, kc, vc, kv_head_stride, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
+      default: break;  // other head sizes: generic kernel below
+    }
+  }
   const size_t sh = sizeof(float) * (32 * hd + 32 * (hd + 1) + 32 * hd + 32 * 33 + 96);
   const float scale = 1.0f / sqrtf((float)hd);
   dim3 grid((Lmax + 31) / 32, H, B);

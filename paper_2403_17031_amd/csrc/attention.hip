@@ -2,6 +2,8 @@
 // attention against the KV cache (decode).  K and V live in a [head][slot][head_dim] layout, a
 // sequence's keys occupying consecutive slots, so one (sequence, head) pair reads one contiguous
 // run of memory.
+#include <algorithm>
+
 #include "common.h"
 
 namespace rlhf {
@@ -353,10 +355,160 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+
+// =================================================================================================
+// Decode attention for fp16 caches, head_dim HD a multiple of 8.  HBM-bound: a (sequence, head)
+// pair owns one contiguous run of ctx*HD halfs of K and of V, which the block reads as a flat
+// stream of 16-byte chunks, 64 lanes x 16 B per wave instruction.
+//   lane = (g, part): part = chunk within a row (HD/8 per row), g = row within the wave's group
+//   of G = 64 / (HD/8) rows.  Phase 1: 8-element partial dot products (v_dot2_f32_f16) combined
+//   across the lanes of a row (butterfly when HD/8 is a power of two, else through LDS).
+//   Phase 2: softmax over the scores in LDS.  Phase 3: the same flat stream over V, each lane
+//   accumulating its 8 output dims in fp32; groups and waves are summed through LDS.
+// =================================================================================================
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+
+template <int HD>
+__global__ void __launch_bounds__(256)
+    attn_decode_f16(const half_t* __restrict__ q, const half_t* __restrict__ kc, const half_t* __restrict__ vc,
+                    long kv_head_stride, const int* __restrict__ len, int ctx_add, const int* __restrict__ kvoff,
+                    int H, float scale, half_t* __restrict__ out) {
+  constexpr int CPR = HD / 8;             // 16-byte chunks per row
+  constexpr int G = 64 / CPR;             // rows per wave instruction
+  constexpr int ACTIVE = G * CPR;         // lanes that carry a chunk
+  constexpr bool POW2 = (CPR & (CPR - 1)) == 0;
+  extern __shared__ float smem[];
+  __shared__ float red[8];
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int ctx = len[b] + ctx_add;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane / CPR, part = lane - g * CPR;
+  const bool active = lane < ACTIVE;
+  float* sc = smem;                              // [ctx_pad] scores, then probabilities
+  const int ctx_pad = (ctx + 3) & ~3;
+  float* scratch = sc + ctx_pad;                 // partial dots (non-power-of-two CPR) / output partials
+  const int d = H * HD;
+  const half_t* kb = kc + (size_t)h * kv_head_stride + (size_t)kvoff[b] * HD;
+  const half_t* vb = vc + (size_t)h * kv_head_stride + (size_t)kvoff[b] * HD;
+
+  // this lane's 8 query values, as 4 packed pairs
+  f16x2_t qv[4];
+  {
+    const half_t* qp = q + (size_t)b * d + (size_t)h * HD + part * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) qv[i] = active ? *(const f16x2_t*)(qp + 2 * i) : (f16x2_t){0, 0};
+  }
+  const int n_it = (ctx + G - 1) / G;  // wave instructions needed to cover ctx rows
+  // ---- phase 1: scores
+  for (int it = wave; it < n_it; it += 4) {
+    const int j = it * G + g;
+    float pd = 0.f;
+    if (active && j < ctx) {
+      const u32x4_t kv = *(const u32x4_t*)(kb + (size_t)j * HD + part * 8);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t w = kv[i];
+        f16x2_t kk;
+        __builtin_memcpy(&kk, &w, 4);
+        pd = __builtin_amdgcn_fdot2(kk, qv[i], pd, false);
+      }
+    }
+    if (POW2) {
+#pragma unroll
+      for (int o = CPR >> 1; o > 0; o >>= 1) pd += __shfl_xor(pd, o, 64);
+      if (part == 0 && j < ctx) sc[j] = pd * scale;
+    } else {
+      if (active) scratch[it * ACTIVE + lane] = pd;  // row j's CPR partials are contiguous
+    }
+  }
+  __syncthreads();
+  if (!POW2) {
+    for (int j = tid; j < ctx; j += 256) {
+      float s = 0.f;
+#pragma unroll
+      for (int c = 0; c < CPR; ++c) s += scratch[j * CPR + c];  // (j/G)*ACTIVE + (j%G)*CPR == j*CPR
+      sc[j] = s * scale;
+    }
+    __syncthreads();
+  }
+  // ---- phase 2: softmax
+  float mx = -INFINITY;
+  for (int j = tid; j < ctx; j += 256) mx = fmaxf(mx, sc[j]);
+  mx = wave_max(mx);
+  if (lane == 0) red[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float sum = 0.f;
+  for (int j = tid; j < ctx; j += 256) {
+    const float p = __expf(sc[j] - mx);
+    sc[j] = p;
+    sum += p;
+  }
+  sum = wave_sum(sum);
+  if (lane == 0) red[4 + wave] = sum;
+  __syncthreads();
+  const float inv = 1.0f / (red[4] + red[5] + red[6] + red[7]);
+  // ---- phase 3: out = sum_j p_j V[j]
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int it = wave; it < n_it; it += 4) {
+    const int j = it * G + g;
+    if (active && j < ctx) {
+      const u32x4_t vv = *(const u32x4_t*)(vb + (size_t)j * HD + part * 8);
+      const float p = sc[j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t w = vv[i];
+        f16x2_t x;
+        __builtin_memcpy(&x, &w, 4);
+        acc[2 * i] = fmaf(p, (float)x[0], acc[2 * i]);
+        acc[2 * i + 1] = fmaf(p, (float)x[1], acc[2 * i + 1]);
+      }
+    }
+  }
+  __syncthreads();  // the partial-dot scratch is dead; reuse it for [wave][g][HD] output partials
+  if (active) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) scratch[(wave * G + g) * HD + part * 8 + i] = acc[i];
+  }
+  __syncthreads();
+  for (int e = tid; e < HD; e += 256) {
+    float o = 0.f;
+#pragma unroll
+    for (int r = 0; r < 4 * G; ++r) o += scratch[r * HD + e];
+    out[(size_t)b * d + (size_t)h * HD + e] = from_f32<half_t>(o * inv);
+  }
+}
+
+template <int HD>
+static hipError_t launch_dec(const void* q, const void* kc, const void* vc, long kv_head_stride, int B,
+                             const int* len, int ctx_add, int ctx_max, const int* kvoff, int H, void* out,
+                             hipStream_t s) {
+  constexpr int CPR = HD / 8, G = 64 / CPR;
+  const size_t part = ((CPR & (CPR - 1)) == 0) ? 0 : (size_t)((ctx_max + G - 1) / G) * G * CPR;
+  const size_t sh = sizeof(float) * (((ctx_max + 3) & ~3) + std::max(part, (size_t)4 * G * HD));
+  if (sh > 160 * 1024) return hipErrorInvalidValue;
+  if (sh > 65536)
+    (void)hipFuncSetAttribute((const void*)attn_decode_f16<HD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
+  hipLaunchKernelGGL(attn_decode_f16<HD>, dim3(H, B), dim3(256), sh, s, (const half_t*)q, (const half_t*)kc,
+                     (const half_t*)vc, kv_head_stride, len, ctx_add, kvoff, H, 1.0f / sqrtf((float)HD),
+                     (half_t*)out);
+  return hipGetLastError();
+}
+
 hipError_t launch_attn_decode(int dtype, const void* q, const void* kc, const void* vc, long kv_head_stride,
                               int B, const int* len, int ctx_add, int ctx_max, const int* kvoff, int H, int hd,
                               void* out, hipStream_t s) {
   if (hd > 256) return hipErrorInvalidValue;
+  if (dtype == 1) {
+    switch (hd) {
+      case 16: return launch_dec<16>(q, kc, vc, kv_head_stride, B, len, ctx_add, ctx_max, kvoff, H, out, s);
+      case 64: return launch_dec<64>(q, kc, vc, kv_head_stride, B, len, ctx_add, ctx_max, kvoff, H, out, s);
+      case 80: return launch_dec<80>(q, kc, vc, kv_head_stride, B, len, ctx_add, ctx_max, kvoff, H, out, s);
+      case 128: return launch_dec<128>(q, kc, vc, kv_head_stride, B, len, ctx_add, ctx_max, kvoff, H, out, s);
+      case 256: return launch_dec<256>(q, kc, vc, kv_head_stride, B, len, ctx_add, ctx_max, kvoff, H, out, s);
+      default: break;  // other head sizes: generic kernel below
+    }
+  }
   const size_t sh = sizeof(float) * (hd + 256 + ctx_max);
   if (sh > 65536) return hipErrorInvalidValue;
   const float scale = 1.0f / sqrtf((float)hd);

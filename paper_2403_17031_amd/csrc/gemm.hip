@@ -60,8 +60,10 @@ constexpr int GROUP_M = 4;  // m-tiles per scheduling group
 __device__ __forceinline__ int lds_pos(int r, int c) { return r * TK + ((c ^ ((r >> 1) & 7)) << 3); }
 
 // MT x NT: 32x32 accumulator tiles per wave along M and N; the block is 2x2 waves.
-template <int EPI, int MT, int NT>
-__global__ void __launch_bounds__(256, (MT * NT > 8 ? 1 : (MT * NT > 2 ? 2 : 4)))
+// PF: k-steps of global loads kept in flight in registers; OCC: blocks per CU the register
+// allocation is sized for.
+template <int EPI, int MT, int NT, int PF, int OCC>
+__global__ void __launch_bounds__(256, OCC)
     gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
                     void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
                     int ldo, int nb_m, int nb_n, int ksplit) {
@@ -100,26 +102,26 @@ __global__ void __launch_bounds__(256, (MT * NT > 8 ? 1 : (MT * NT > 2 ? 2 : 4))
     return (uint32_t)((i < NLD_A ? min(m0 + r, M - 1) : min(n0 + r, N - 1)) * K + ld_c * 8);
   };
   const int st_off = lds_pos(ld_r, ld_c);  // + 32*i rows: (r>>1)&7 is unchanged by adding 32*i
-  u32x4_t stage[NLD];
+  u32x4_t stage[PF][NLD];
   // Full K tiles load unconditionally (a select on the loaded value would force the wave to wait
   // for the data right away); only a ragged last tile takes the guarded form.
-  auto load_global = [&](int k0) {
+  auto load_global = [&](int set, int k0) {
     if (k0 + TK <= K) {
 #pragma unroll
-      for (int i = 0; i < NLD; ++i) stage[i] = *(const u32x4_t*)((i < NLD_A ? A : W) + goff(i) + k0);
+      for (int i = 0; i < NLD; ++i) stage[set][i] = *(const u32x4_t*)((i < NLD_A ? A : W) + goff(i) + k0);
     } else {
       const bool kok = k0 + ld_c * 8 < K;
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
         u32x4_t z = {0, 0, 0, 0};
         if (kok) z = *(const u32x4_t*)((i < NLD_A ? A : W) + goff(i) + k0);
-        stage[i] = z;
+        stage[set][i] = z;
       }
     }
   };
-  auto store_lds = [&]() {
+  auto store_lds = [&](int set) {
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) *(u32x4_t*)(lds + st_off + 32 * i * TK) = stage[i];
+    for (int i = 0; i < NLD; ++i) *(u32x4_t*)(lds + st_off + 32 * i * TK) = stage[set][i];
   };
 
   // ---- fragment addressing: lane reads row (lane & 31) of a 32-row fragment, logical chunk
@@ -143,11 +145,16 @@ __global__ void __launch_bounds__(256, (MT * NT > 8 ? 1 : (MT * NT > 2 ? 2 : 4))
   const int kt0 = blockIdx.y * per_split;
   const int nk = min(nk_all, kt0 + per_split);
   if (ksplit > 1) out = (float*)out + (size_t)blockIdx.y * M_max * ldo;
-  if (kt0 < nk) load_global(kt0 * TK);
-  for (int kt = kt0; kt < nk; ++kt) {
-    store_lds();
+#pragma unroll
+  for (int p = 0; p < PF; ++p)
+    if (kt0 + p < nk) load_global(p, (kt0 + p) * TK);
+  for (int kt = kt0; kt < nk; kt += PF) {
+#pragma unroll
+   for (int p = 0; p < PF; ++p) {
+    if (kt + p >= nk) break;
+    store_lds(p);
     __syncthreads();
-    if (kt + 1 < nk) load_global((kt + 1) * TK);  // in flight during the whole k-step of math
+    if (kt + p + PF < nk) load_global(p, (kt + p + PF) * TK);  // in flight for PF k-steps of math
     // Fragments are double-buffered by hand and the scheduler is fenced, so that the LDS reads of
     // sub-step ks+1 are in flight while the matrix instructions of sub-step ks issue (left alone,
     // the compiler re-reads into one register quad and waits before every few MFMAs).
@@ -180,6 +187,7 @@ __global__ void __launch_bounds__(256, (MT * NT > 8 ? 1 : (MT * NT > 2 ? 2 : 4))
       __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
+   }
   }
 
   // ---- epilogue
@@ -284,13 +292,15 @@ __global__ void __launch_bounds__(256)
 #ifndef RLHF_GEMM_MT
 #define RLHF_GEMM_MT 2
 #define RLHF_GEMM_NT 4
+#define RLHF_GEMM_PF 1
+#define RLHF_GEMM_OCC 2
 #endif
 
-template <int EPI, int MT, int NT>
+template <int EPI, int MT, int NT, int PF, int OCC>
 static void launch_f16(const GemmArgs& a, hipStream_t s, void* out, int ksplit) {
   const int nb_m = (a.M_max + 64 * MT - 1) / (64 * MT), nb_n = (a.N + 64 * NT - 1) / (64 * NT);
   const int per_xcd = (nb_m * nb_n + 7) / 8;
-  hipLaunchKernelGGL((gemm_f16_kernel<EPI, MT, NT>), dim3(per_xcd * 8, ksplit), dim3(256), 0, s,
+  hipLaunchKernelGGL((gemm_f16_kernel<EPI, MT, NT, PF, OCC>), dim3(per_xcd * 8, ksplit), dim3(256), 0, s,
                      (const half_t*)a.A, (const half_t*)a.W, (const bf16_t*)a.bias, out, a.M_max, a.M_dev, a.M_sub,
                      a.N, a.K, a.ldo, nb_m, nb_n, ksplit);
 }
@@ -327,7 +337,7 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
       while (ksplit < 16 && tiles * ksplit < 1024 && nk / (ksplit * 2) >= 4) ksplit *= 2;
       const size_t need = (size_t)ksplit * a.M_max * a.ldo * sizeof(float);
       if (ksplit > 1 && need <= a.splitk_ws_bytes) {
-        launch_f16<EPI_F32, 2, 1>(a, s, a.splitk_ws, ksplit);
+        launch_f16<EPI_F32, 2, 1, 1, 4>(a, s, a.splitk_ws, ksplit);
         const size_t n4 = ((size_t)a.M_max * a.ldo + 3) / 4;
         hipLaunchKernelGGL(splitk_reduce_kernel<EPI>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
                            (const float*)a.splitk_ws, ksplit, (size_t)a.M_max * a.ldo, (const bf16_t*)a.bias, a.out,
@@ -336,9 +346,9 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
       }
     }
     if (a.M_max <= 512)
-      launch_f16<EPI, 2, 1>(a, s, a.out, 1);
+      launch_f16<EPI, 2, 1, 1, 4>(a, s, a.out, 1);
     else
-      launch_f16<EPI, RLHF_GEMM_MT, RLHF_GEMM_NT>(a, s, a.out, 1);
+      launch_f16<EPI, RLHF_GEMM_MT, RLHF_GEMM_NT, RLHF_GEMM_PF, RLHF_GEMM_OCC>(a, s, a.out, 1);
   }
 }
 

@@ -157,6 +157,84 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+// Vectorised form for bf16 parameters / fp16 outputs: d a multiple of 4 and at most 4096; the row
+// lives in registers (up to four float4 per thread), parameters and outputs move 8 bytes at a time.
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+
+__device__ __forceinline__ f32x4_t bf16x4_to_f32(u32x2_t v) {
+  f32x4_t r;
+  r[0] = __uint_as_float(v[0] << 16);
+  r[1] = __uint_as_float(v[0] & 0xFFFF0000u);
+  r[2] = __uint_as_float(v[1] << 16);
+  r[3] = __uint_as_float(v[1] & 0xFFFF0000u);
+  return r;
+}
+
+__global__ void __launch_bounds__(256)
+    layernorm_vec_kernel(const float* __restrict__ x, const int* __restrict__ src, int src_add,
+                         const int* __restrict__ rows_dev, int d, float eps, const bf16_t* __restrict__ g1,
+                         const bf16_t* __restrict__ b1, half_t* __restrict__ out1, const bf16_t* __restrict__ g2,
+                         const bf16_t* __restrict__ b2, half_t* __restrict__ out2,
+                         const bf16_t* __restrict__ value_w, float value_b, float* __restrict__ val) {
+  __shared__ float sh[4];
+  const int r = blockIdx.x;
+  if (rows_dev && r >= *rows_dev) return;
+  const int sr = src ? max(src[r] + src_add, 0) : r;
+  const f32x4_t* xr = (const f32x4_t*)(x + (size_t)sr * d);
+  const int nv = d >> 2;
+  f32x4_t v[4];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = threadIdx.x + 256 * i;
+    if (c < nv) {
+      v[i] = xr[c];
+      s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
+    }
+  }
+  const float mean = block_sum_256(s, sh) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = threadIdx.x + 256 * i;
+    if (c < nv) {
+      v[i] -= mean;
+      q += v[i][0] * v[i][0] + v[i][1] * v[i][1] + v[i][2] * v[i][2] + v[i][3] * v[i][3];
+    }
+  }
+  const float rstd = 1.0f / sqrtf(block_sum_256(q, sh) / (float)d + eps);
+  float vd = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = threadIdx.x + 256 * i;
+    if (c < nv) {
+      const f32x4_t n = v[i] * rstd;
+      const f32x4_t h1 = n * bf16x4_to_f32(((const u32x2_t*)g1)[c]) + bf16x4_to_f32(((const u32x2_t*)b1)[c]);
+      f16x4_t o;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) o[u] = from_f32<half_t>(h1[u]);
+      ((f16x4_t*)(out1 + (size_t)r * d))[c] = o;
+      if (out2) {
+        const f32x4_t h2 = n * bf16x4_to_f32(((const u32x2_t*)g2)[c]) + bf16x4_to_f32(((const u32x2_t*)b2)[c]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) o[u] = from_f32<half_t>(h2[u]);
+        ((f16x4_t*)(out2 + (size_t)r * d))[c] = o;
+      }
+      if (val) {
+        const f32x4_t w = bf16x4_to_f32(((const u32x2_t*)value_w)[c]);
+        vd += h1[0] * w[0] + h1[1] * w[1] + h1[2] * w[2] + h1[3] * w[3];
+      }
+    }
+  }
+  if (val) {
+    vd = block_sum_256(vd, sh);
+    if (threadIdx.x == 0) val[r] = vd + value_b;
+  }
+}
+
 template <typename M>
 static hipError_t ln_launch(const float* x, const int* src, int src_add, int rows_max, const int* rows_dev, int d,
                             float eps, const void* g1, const void* b1, void* out1, const void* g2,
@@ -164,6 +242,12 @@ static hipError_t ln_launch(const float* x, const int* src, int src_add, int row
   if (rows_max <= 0) return hipSuccess;
   typedef typename M::W WT;
   typedef typename M::A AT;
+  if (sizeof(AT) == 2 && (d & 3) == 0 && d <= 4096) {
+    hipLaunchKernelGGL(layernorm_vec_kernel, dim3(rows_max), dim3(256), 0, s, x, src, src_add, rows_dev, d, eps,
+                       (const bf16_t*)g1, (const bf16_t*)b1, (half_t*)out1, (const bf16_t*)g2, (const bf16_t*)b2,
+                       (half_t*)out2, (const bf16_t*)vw, vb, val);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL((layernorm_kernel<WT, AT>), dim3(rows_max), dim3(256), 0, s, x, src, src_add, rows_dev, d,
                      eps, (const WT*)g1, (const WT*)b1, (AT*)out1, (const WT*)g2, (const WT*)b2, (AT*)out2,
                      (const WT*)vw, vb, val);
@@ -229,6 +313,49 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+// fp16 form moving 16 bytes (8 dims) per access; head_dim a multiple of 8.  Only the chunks that
+// overlap the rotary dims do per-element work (the rotation partner is fetched as a scalar).
+__global__ void __launch_bounds__(256)
+    rope_kv_vec_kernel(const half_t* __restrict__ qkv, const int* __restrict__ rows_dev, const int* __restrict__ pos,
+                       int pos_add, const int* __restrict__ rowid, const int* __restrict__ kvoff, int H, int hd,
+                       int r, const float* __restrict__ cos_t, const float* __restrict__ sin_t,
+                       half_t* __restrict__ q, half_t* __restrict__ kc, half_t* __restrict__ vc,
+                       long kv_head_stride) {
+  const int t = blockIdx.x;
+  if (rows_dev && t >= *rows_dev) return;
+  const int d = H * hd;
+  const int p = pos[t] + pos_add;
+  const int b = rowid ? rowid[t] : t;
+  const long slot = (long)kvoff[b] + p;
+  const half_t* src = qkv + (size_t)t * 3 * d;
+  const int half = r >> 1;
+  const float* cs = cos_t + (size_t)p * half;
+  const float* sn = sin_t + (size_t)p * half;
+  const int cph = hd >> 3, cpr = d >> 3;  // chunks per head / per q,k,v section
+  for (int c = threadIdx.x; c < 3 * cpr; c += 256) {
+    const int sec = c / cpr, cc = c - sec * cpr;
+    const int h = cc / cph, e0 = (cc - h * cph) << 3;
+    f16x8_t v = *(const f16x8_t*)(src + (size_t)c * 8);
+    if (sec < 2 && e0 < r) {
+      const half_t* hb = src + sec * d + h * hd;  // this head's q or k
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int e = e0 + i;
+        if (e < half)
+          v[i] = from_f32<half_t>((float)v[i] * cs[e] - (float)hb[e + half] * sn[e]);
+        else if (e < r)
+          v[i] = from_f32<half_t>((float)v[i] * cs[e - half] + (float)hb[e - half] * sn[e - half]);
+      }
+    }
+    if (sec == 0) {
+      *(f16x8_t*)(q + (size_t)t * d + cc * 8) = v;
+    } else {
+      half_t* dst = (sec == 1 ? kc : vc) + (size_t)h * kv_head_stride + (size_t)slot * hd + e0;
+      *(f16x8_t*)dst = v;
+    }
+  }
+}
+
 hipError_t launch_rope_kv(int dtype, const void* qkv, int rows_max, const int* rows_dev, const int* pos,
                           int pos_add, const int* rowid, const int* kvoff, int H, int hd, int r,
                           const float* cos_t, const float* sin_t, void* q, void* kc, void* vc,
@@ -237,6 +364,10 @@ hipError_t launch_rope_kv(int dtype, const void* qkv, int rows_max, const int* r
   if (dtype == 0)
     hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(rows_max), dim3(256), 0, s, (const float*)qkv, rows_dev, pos,
                        pos_add, rowid, kvoff, H, hd, r, cos_t, sin_t, (float*)q, (float*)kc, (float*)vc,
+                       kv_head_stride);
+  else if ((hd & 7) == 0)
+    hipLaunchKernelGGL(rope_kv_vec_kernel, dim3(rows_max), dim3(256), 0, s, (const half_t*)qkv, rows_dev, pos,
+                       pos_add, rowid, kvoff, H, hd, r, cos_t, sin_t, (half_t*)q, (half_t*)kc, (half_t*)vc,
                        kv_head_stride);
   else
     hipLaunchKernelGGL(rope_kv_kernel<half_t>, dim3(rows_max), dim3(256), 0, s, (const half_t*)qkv, rows_dev,

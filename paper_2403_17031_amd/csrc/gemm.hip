@@ -9,6 +9,9 @@
 //    registers while the current one is multiplied, workgroup ids remapped so that the 32 tiles
 //    resident on one XCD share A and W panels in that XCD's L2.
 //  * fp32: plain FMA tile kernel (check mode only; not tuned).
+#include <algorithm>
+#include <type_traits>
+
 #include "common.h"
 
 namespace rlhf {
@@ -18,6 +21,7 @@ typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
@@ -289,11 +293,274 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+// =================================================================================================
+// Large-M kernel: 256x256 block tile, one block per CU, 4 waves of 128x128 (256 accumulator
+// registers per lane).  Tiles go global -> LDS directly (global_load_lds, 16 bytes per lane: a wave
+// instruction fills 1 KB; no staging registers, no ds_write) into FOUR 32 KB stages of K depth 32,
+// three k-steps ahead of the math: with one block per CU a k-step lasts about as long as a memory
+// round trip under load, so a single stage of lookahead leaves the matrix cores waiting.  Raw
+// s_barrier + explicit s_waitcnt are used because __syncthreads would drain every outstanding load.
+// The fragment reads of the next k-step are issued right after the barrier and the last 16 matrix
+// instructions of the current k-step run behind them, so LDS latency is not exposed either.  Each
+// lane picks its global chunk so that the linear LDS image is the XOR-swizzled layout the fragment
+// reads expect (conflict-free ds_read_b128).
+// =================================================================================================
+#ifdef RLHF_ABL_SAMEK
+#define RLHF_ABL_K(k) 0  // timing experiment only: every k-step re-reads the first tile
+#else
+#define RLHF_ABL_K(k) (k)
+#endif
+#define RLHF_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define RLHF_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+constexpr int DK = 32;                      // K depth of one stage
+constexpr int DSTAGE = (256 + 256) * DK;    // halfs per stage (32 KB)
+
+template <int EPI>
+__global__ void __launch_bounds__(256, 1)
+    gemm_f16_dma_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
+                        void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
+                        int ldo, int nb_m, int nb_n) {
+  constexpr int TM = 256, TN = 256, MT = 4, NT = 4;
+  __shared__ __attribute__((aligned(16))) uint16_t lds0[DSTAGE];
+  __shared__ __attribute__((aligned(16))) uint16_t lds1[DSTAGE];
+  __shared__ __attribute__((aligned(16))) uint16_t lds2[DSTAGE];
+  __shared__ __attribute__((aligned(16))) uint16_t lds3[DSTAGE];
+  const int M = M_dev ? min(M_max, *M_dev - M_sub) : M_max;
+  nb_m = min(nb_m, (M + TM - 1) / TM);
+  const int total = nb_m * nb_n;
+  const int per_xcd = (total + 7) >> 3;
+  if ((int)(blockIdx.x >> 3) >= per_xcd) return;
+  const int lt = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (lt >= total) return;
+  const int group_sz = GROUP_M * nb_n;
+  const int grp = lt / group_sz, rem = lt - grp * group_sz;
+  const int gm = min(GROUP_M, nb_m - grp * GROUP_M);
+  const int tm = grp * GROUP_M + rem % gm, tn = rem / gm;
+  const int m0 = tm * TM, n0 = tn * TN;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps LDS bases in SGPRs
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+
+  // ---- direct loads: a stage row is 64 B (4 chunks); wave-load j (= 8*wave + i, i < 8) fills rows
+  //      16j .. 16j+15 (rows < 256: A, else W); lane l lands at row 16j + l/4, physical chunk l%4,
+  //      and therefore fetches logical chunk (l%4) ^ ((row>>2)&3)
+  uint32_t goff[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int row = 16 * (8 * wave + i) + (lane >> 2);
+    const int c = (lane & 3) ^ ((row >> 2) & 3);
+    const int grow = row < TM ? min(m0 + row, M - 1) : min(n0 + row - TM, N - 1);
+    goff[i] = (uint32_t)(grow * K + c * 8);
+  }
+  const half_t* gbase = wave < 2 ? A : W;  // waves 0,1 load A rows, waves 2,3 load W rows
+  auto issue_loads = [&](uint16_t* stage, int k0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      __builtin_amdgcn_global_load_lds(RLHF_GLOBAL_PTR(gbase + goff[i] + RLHF_ABL_K(k0)),
+                                       RLHF_LDS_PTR(stage + (16 * (8 * wave + i)) * DK), 16, 0, 0);
+  };
+
+  const int l32 = lane & 31, hf = lane >> 5;
+  const int key = (l32 >> 2) & 3;
+  const int a_off = (wm + l32) * DK, w_off = (TM + wn + l32) * DK;
+  const int ch0 = ((hf) ^ key) << 3, ch1 = ((2 + hf) ^ key) << 3;  // sub-steps 0 and 1
+
+  f32x16_t acc[NT][MT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
+
+  f16x8_t fa0[MT], fw0[NT], fa1[MT], fw1[NT];  // fragment buffers of sub-steps 0 and 1
+  auto frags = [&](const uint16_t* ls, int ch, f16x8_t* fa, f16x8_t* fw) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i) fa[i] = *(const f16x8_t*)(ls + a_off + i * 32 * DK + ch);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) fw[j] = *(const f16x8_t*)(ls + w_off + j * 32 * DK + ch);
+  };
+  // weights as the first operand: accumulator element e of a lane is then
+  // (n = 8*(e/4) + 4*(lane/32) + e%4, m = lane%32), i.e. 4 consecutive output columns per lane
+  auto mma = [&](const f16x8_t* fa, const f16x8_t* fw, int j0, int j1) {
+#pragma unroll
+    for (int j = j0; j < j1; ++j)
+#pragma unroll
+      for (int i = 0; i < MT; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[j], fa[i], acc[j][i], 0, 0, 0);
+  };
+  // vmcnt(16) lgkmcnt(0): everything but the two youngest tile loads (8 instructions each) has
+  // landed, and this wave's fragment reads are complete
+#define RLHF_WAIT_BARRIER()                      \
+  __builtin_amdgcn_sched_barrier(0);             \
+  asm volatile("" ::: "memory");                 \
+  __builtin_amdgcn_s_waitcnt(0x4070);            \
+  __builtin_amdgcn_s_barrier();                  \
+  asm volatile("" ::: "memory");                 \
+  __builtin_amdgcn_sched_barrier(0);
+  // One k-step.  Order matters: the fragment reads of sub-step 1 go out in the middle of sub-step
+  // 0's matrix instructions, and those of the next k-step right after the barrier, so every LDS
+  // read has at least 8 matrix instructions (256 cycles) in front of its first use.
+#define RLHF_STEP(CUR, NEXT, LOAD, KT)                         \
+  mma(fa0, fw0, 0, 2);                                         \
+  __builtin_amdgcn_sched_barrier(0);                           \
+  issue_loads(LOAD, min((KT) + 3, nk - 1) * DK);               \
+  frags(CUR, ch1, fa1, fw1);                                   \
+  __builtin_amdgcn_sched_barrier(0);                           \
+  mma(fa0, fw0, 2, 4);                                         \
+  RLHF_WAIT_BARRIER()                                          \
+  frags(NEXT, ch0, fa0, fw0);                                  \
+  __builtin_amdgcn_sched_barrier(0);                           \
+  mma(fa1, fw1, 0, 4);                                         \
+  __builtin_amdgcn_sched_barrier(0);
+
+  // K is a multiple of 4*DK here (the launcher routes other shapes to the staged kernel), so the
+  // loop is branch-free: past the end the final tile is re-issued into a stage nobody reads.
+  const int nk = K / DK;
+  issue_loads(lds0, 0);
+  issue_loads(lds1, min(1, nk - 1) * DK);
+  issue_loads(lds2, min(2, nk - 1) * DK);
+  RLHF_WAIT_BARRIER()
+  frags(lds0, ch0, fa0, fw0);
+  for (int kt = 0; kt < nk; kt += 4) {
+    RLHF_STEP(lds0, lds1, lds3, kt)
+    RLHF_STEP(lds1, lds2, lds0, kt + 1)
+    RLHF_STEP(lds2, lds3, lds1, kt + 2)
+    RLHF_STEP(lds3, lds0, lds2, kt + 3)
+  }
+#undef RLHF_STEP
+#undef RLHF_WAIT_BARRIER
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): the surplus loads have landed too
+  __syncthreads();
+
+#ifdef RLHF_ABL_NOEPI
+  if (M > 0) { if (acc[0][0][0] == 1.2345f) ((float*)out)[0] = acc[1][1][1] + acc[2][2][2] + acc[3][3][3]; return; }
+#endif
+  // ---- epilogue.  In the accumulator layout a lane owns 4 consecutive columns of ONE row, so a
+  //      direct store touches 32 rows with 8-16 bytes each -- partial-line writes that the memory
+  //      system handles an order of magnitude slower than full lines.  Each wave therefore
+  //      transposes its 128x128 tile through one of the four (now idle) 32 KB LDS stages and stores
+  //      16 bytes per lane, 16 lanes per 256-byte row segment.  The LDS image is XOR-swizzled by
+  //      row (chunk ^ (row & 15)); accumulator tiles are addressed through compile-time indices
+  //      (a loop the compiler declines to unroll would spill all 256 accumulators to scratch).
+  uint16_t* ep = wave == 0 ? lds0 : wave == 1 ? lds1 : wave == 2 ? lds2 : lds3;  // 32 KB per wave
+  const int rd_row = lane >> 4, rd_c = lane & 15;
+  // bias of this lane's 64 columns: 16 eight-byte loads issued together (N is a multiple of 8 here
+  // and every column group starts at a multiple of 4, so a group is inside or outside as a whole)
+  f32x4_t bias_v[NT][4];
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int nb = n0 + wn + 32 * j + 8 * g + 4 * hf;
+      u32x2_t raw = {0, 0};
+      if (EPI != EPI_F32 && bias && nb < N) raw = *(const u32x2_t*)(bias + nb);
+      bias_v[j][g][0] = __uint_as_float(raw[0] << 16);
+      bias_v[j][g][1] = __uint_as_float(raw[0] & 0xFFFF0000u);
+      bias_v[j][g][2] = __uint_as_float(raw[1] << 16);
+      bias_v[j][g][3] = __uint_as_float(raw[1] & 0xFFFF0000u);
+    }
+  if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU) {
+    auto put = [&](auto jc, auto ic) {
+      constexpr int j = decltype(jc)::value, i = decltype(ic)::value;
+      const int row = 32 * i + l32;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        f16x4_t h;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float v = acc[j][i][4 * g + u] + bias_v[j][g][u];
+          h[u] = from_f32<half_t>(EPI == EPI_BIAS_GELU ? gelu_f16out(v) : v);
+        }
+        *(f16x4_t*)(ep + row * 128 + (((4 * j + g) ^ (row & 15)) << 3) + 4 * hf) = h;
+      }
+    };
+#define RLHF_ROW(J)                                                                        \
+  put(std::integral_constant<int, J>{}, std::integral_constant<int, 0>{});                 \
+  put(std::integral_constant<int, J>{}, std::integral_constant<int, 1>{});                 \
+  put(std::integral_constant<int, J>{}, std::integral_constant<int, 2>{});                 \
+  put(std::integral_constant<int, J>{}, std::integral_constant<int, 3>{});
+    RLHF_ROW(0) RLHF_ROW(1) RLHF_ROW(2) RLHF_ROW(3)
+#undef RLHF_ROW
+    __syncthreads();
+    const int gcol = n0 + wn + rd_c * 8;
+#pragma unroll 8
+    for (int it = 0; it < 32; ++it) {
+      const int row = it * 4 + rd_row;
+      const int grow = m0 + wm + row;
+      const u32x4_t v = *(const u32x4_t*)(ep + row * 128 + ((rd_c ^ (row & 15)) << 3));
+      if (grow < M && gcol < N) *(u32x4_t*)((half_t*)out + (size_t)grow * ldo + gcol) = v;
+    }
+  } else {
+    float* epf = (float*)ep;  // 128 rows x 64 floats per pass
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int gcol = n0 + wn + 64 * hh + rd_c * 4;
+      // residual rows of this pass: all 32 loads are issued before the transpose, so their latency
+      // hides behind the LDS traffic
+      f32x4_t xv[32];
+      if (EPI == EPI_BIAS_RESADD) {
+#pragma unroll
+        for (int it = 0; it < 32; ++it) {
+          const int grow = m0 + wm + it * 4 + rd_row;
+          if (grow < M && gcol < N) xv[it] = *(const f32x4_t*)((const float*)out + (size_t)grow * ldo + gcol);
+        }
+      }
+      auto put = [&](auto jc, auto ic) {
+        constexpr int j = decltype(jc)::value, i = decltype(ic)::value;
+        const int row = 32 * i + l32;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4_t v = {acc[j][i][4 * g] + bias_v[j][g][0], acc[j][i][4 * g + 1] + bias_v[j][g][1],
+                             acc[j][i][4 * g + 2] + bias_v[j][g][2], acc[j][i][4 * g + 3] + bias_v[j][g][3]};
+          const int c = 8 * (j & 1) + 2 * g + hf;
+          *(f32x4_t*)(epf + row * 64 + ((c ^ (row & 15)) << 2)) = v;
+        }
+      };
+#define RLHF_ROW(J)                                                                        \
+  put(std::integral_constant<int, J>{}, std::integral_constant<int, 0>{});                 \
+  put(std::integral_constant<int, J>{}, std::integral_constant<int, 1>{});                 \
+  put(std::integral_constant<int, J>{}, std::integral_constant<int, 2>{});                 \
+  put(std::integral_constant<int, J>{}, std::integral_constant<int, 3>{});
+      if (hh == 0) { RLHF_ROW(0) RLHF_ROW(1) } else { RLHF_ROW(2) RLHF_ROW(3) }
+#undef RLHF_ROW
+      __syncthreads();
+#pragma unroll
+      for (int it = 0; it < 32; ++it) {
+        const int row = it * 4 + rd_row;
+        const int grow = m0 + wm + row;
+        f32x4_t v = *(const f32x4_t*)(epf + row * 64 + ((rd_c ^ (row & 15)) << 2));
+        if (grow < M && gcol < N) {
+          if (EPI == EPI_BIAS_RESADD) v += xv[it];
+          *(f32x4_t*)((float*)out + (size_t)grow * ldo + gcol) = v;
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+template <int EPI>
+static void launch_f16_dma(const GemmArgs& a, hipStream_t s) {
+  const int nb_m = (a.M_max + 255) / 256, nb_n = (a.N + 255) / 256;
+  const int per_xcd = (nb_m * nb_n + 7) / 8;
+  hipLaunchKernelGGL(gemm_f16_dma_kernel<EPI>, dim3(per_xcd * 8), dim3(256), 0, s, (const half_t*)a.A,
+                     (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
+                     nb_m, nb_n);
+}
+
+#ifndef RLHF_GEMM_DMA
+#define RLHF_GEMM_DMA 1
+#endif
 #ifndef RLHF_GEMM_MT
 #define RLHF_GEMM_MT 2
 #define RLHF_GEMM_NT 4
 #define RLHF_GEMM_PF 1
 #define RLHF_GEMM_OCC 2
+#endif
+#ifndef RLHF_DEC_PF
+#define RLHF_DEC_PF 1
+#define RLHF_DEC_OCC 4
 #endif
 
 template <int EPI, int MT, int NT, int PF, int OCC>
@@ -337,7 +604,7 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
       while (ksplit < 16 && tiles * ksplit < 1024 && nk / (ksplit * 2) >= 4) ksplit *= 2;
       const size_t need = (size_t)ksplit * a.M_max * a.ldo * sizeof(float);
       if (ksplit > 1 && need <= a.splitk_ws_bytes) {
-        launch_f16<EPI_F32, 2, 1, 1, 4>(a, s, a.splitk_ws, ksplit);
+        launch_f16<EPI_F32, 2, 1, RLHF_DEC_PF, RLHF_DEC_OCC>(a, s, a.splitk_ws, ksplit);
         const size_t n4 = ((size_t)a.M_max * a.ldo + 3) / 4;
         hipLaunchKernelGGL(splitk_reduce_kernel<EPI>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
                            (const float*)a.splitk_ws, ksplit, (size_t)a.M_max * a.ldo, (const bf16_t*)a.bias, a.out,
@@ -346,7 +613,9 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
       }
     }
     if (a.M_max <= 512)
-      launch_f16<EPI, 2, 1, 1, 4>(a, s, a.out, 1);
+      launch_f16<EPI, 2, 1, RLHF_DEC_PF, RLHF_DEC_OCC>(a, s, a.out, 1);
+    else if (RLHF_GEMM_DMA && (a.K % (4 * DK)) == 0 && (a.N % 8) == 0 && (a.ldo % 8) == 0 && (size_t)std::max(a.M_max, a.N) * a.K < (1ull << 32))
+      launch_f16_dma<EPI>(a, s);
     else
       launch_f16<EPI, RLHF_GEMM_MT, RLHF_GEMM_NT, RLHF_GEMM_PF, RLHF_GEMM_OCC>(a, s, a.out, 1);
   }

@@ -206,6 +206,7 @@ struct PassArgs {
   const int* cu;
   int B, Lmax;
   int ctx_add, ctx_max;
+  int kv_extra;        // slots per head beyond len[b] in a sequence's K/V slab
   char* kv;            // layer l: K at kv + (2l)*kv_layer_bytes/2 ...
   size_t kv_slots;     // slots per head
   bool kv_per_layer;   // false: every layer reuses the same single-layer scratch
@@ -215,11 +216,10 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
   const rlhf_model_config& c = h->cfg;
   const int d = c.d_model, dt = c.dtype;
   const size_t plane = p.kv_slots * (size_t)d * h->esz;  // bytes of one K (or V) plane of one layer
-  const long head_stride = (long)(p.kv_slots * (size_t)c.head_dim);
   for (int l = 0; l < c.n_layers; ++l) {
     char* kc = p.kv + (p.kv_per_layer ? (size_t)l * 2 * plane : 0);
     char* vc = kc + plane;
-    LAUNCH("layernorm", launch_layernorm(dt, A.x, p.rows_max, p.rows_dev, d, c.ln_eps, h->ln1_g[l], h->ln1_b[l],
+    LAUNCH(p.mode ? "layernorm_decode" : "layernorm", launch_layernorm(dt, A.x, p.rows_max, p.rows_dev, d, c.ln_eps, h->ln1_g[l], h->ln1_b[l],
                                          A.a, h->ln2_g[l], h->ln2_b[l], A.m, s));
     GemmArgs g;
     g.M_max = p.rows_max;
@@ -231,14 +231,14 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
     g.A = A.a; g.W = h->w_qkv[l]; g.bias = h->b_qkv[l]; g.out = A.qkv; g.N = 3 * d; g.K = d; g.ldo = 3 * d;
     g.epilogue = EPI_BIAS;
     LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
-    LAUNCH("rope_kv", launch_rope_kv(dt, A.qkv, p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff,
-                                     c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q, kc, vc,
-                                     head_stride, s));
+    LAUNCH(p.mode ? "rope_kv_decode" : "rope_kv", launch_rope_kv(dt, A.qkv, p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff,
+                                     p.len, c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q, kc, vc,
+                                     (long)p.kv_extra, s));
     if (p.mode == 0)
-      LAUNCH("attn_prefill", launch_attn_prefill(dt, A.q, kc, vc, head_stride, p.B, p.Lmax, p.len, p.cu, p.kvoff,
+      LAUNCH("attn_prefill", launch_attn_prefill(dt, A.q, kc, vc, (long)p.kv_extra, p.B, p.Lmax, p.len, p.cu, p.kvoff,
                                                  c.n_heads, c.head_dim, A.att, s));
     else
-      LAUNCH("attn_decode", launch_attn_decode(dt, A.q, kc, vc, head_stride, p.B, p.len, p.ctx_add, p.ctx_max,
+      LAUNCH("attn_decode", launch_attn_decode(dt, A.q, kc, vc, (long)p.kv_extra, p.B, p.len, p.ctx_add, p.ctx_max,
                                                p.kvoff, c.n_heads, c.head_dim, A.att, s));
     g.A = A.att; g.W = h->w_o[l]; g.bias = h->b_o[l]; g.out = A.x; g.N = d; g.K = d; g.ldo = d;
     g.epilogue = EPI_BIAS_RESADD;
@@ -424,6 +424,7 @@ int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_
   p.Lmax = Lq;
   p.ctx_add = 0;
   p.ctx_max = Lq + N;
+  p.kv_extra = N - 1;
   p.kv = ws.kv;
   p.kv_slots = ws.kv_slots;
   p.kv_per_layer = true;
@@ -494,6 +495,7 @@ static int score_forward(rlhf_handle* h, const int32_t* tokens, const uint8_t* m
   p.Lmax = L;
   p.ctx_add = 0;
   p.ctx_max = L;
+  p.kv_extra = 0;
   p.kv = ws.kv;
   p.kv_slots = ws.Tmax;
   p.kv_per_layer = false;

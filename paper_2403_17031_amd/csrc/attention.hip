@@ -15,7 +15,7 @@ namespace rlhf {
 template <typename T>
 __global__ void __launch_bounds__(256)
     attn_prefill_generic(const T* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc,
-                         long kv_head_stride, const int* __restrict__ len, const int* __restrict__ cu,
+                         long kv_extra, const int* __restrict__ len, const int* __restrict__ cu,
                          const int* __restrict__ kvoff, int H, int hd, float scale, T* __restrict__ out) {
   extern __shared__ float smem[];
   const int b = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * 32;
@@ -31,8 +31,8 @@ __global__ void __launch_bounds__(256)
   const int tid = threadIdx.x;
   const int d = H * hd;
   const T* qb = q + ((size_t)cu[b]) * d + (size_t)h * hd;
-  const T* kb = kc + (size_t)h * kv_head_stride + (size_t)kvoff[b] * hd;
-  const T* vb = vc + (size_t)h * kv_head_stride + (size_t)kvoff[b] * hd;
+  const T* kb = kc + ((size_t)kvoff[b] * H + (size_t)h * (len[b] + kv_extra)) * hd;
+  const T* vb = vc + ((size_t)kvoff[b] * H + (size_t)h * (len[b] + kv_extra)) * hd;
   for (int c = tid; c < 32 * hd; c += 256) {
     const int r = c / hd, e = c - r * hd;
     const int qi = min(q0 + r, n - 1);
@@ -125,7 +125,7 @@ constexpr int FA_VT_STRIDE = FA_BK + 8;  // halfs per V^T row: 144 B, odd multip
 template <int HD>
 __global__ void __launch_bounds__(256)
     attn_prefill_mfma(const half_t* __restrict__ q, const half_t* __restrict__ kc, const half_t* __restrict__ vc,
-                      long kv_head_stride, const int* __restrict__ len, const int* __restrict__ cu,
+                      long kv_extra, const int* __restrict__ len, const int* __restrict__ cu,
                       const int* __restrict__ kvoff, int H, float scale_log2e, half_t* __restrict__ out) {
   constexpr int NKS = HD / 16;         // k-steps of the Q K^T contraction
   constexpr int NDT = (HD + 31) / 32;  // 32-row tiles of O^T
@@ -138,8 +138,8 @@ __global__ void __launch_bounds__(256)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, l32 = lane & 31;
   const int d = H * HD;
-  const half_t* kb = kc + (size_t)h * kv_head_stride + (size_t)kvoff[b] * HD;
-  const half_t* vb = vc + (size_t)h * kv_head_stride + (size_t)kvoff[b] * HD;
+  const half_t* kb = kc + ((size_t)kvoff[b] * H + (size_t)h * (len[b] + kv_extra)) * HD;
+  const half_t* vb = vc + ((size_t)kvoff[b] * H + (size_t)h * (len[b] + kv_extra)) * HD;
 
   // rows of V^T beyond HD are never loaded: zero them once
   for (int c = tid; c < (NDT * 32 - HD) * FA_VT_STRIDE; c += 256) Vt[HD * FA_VT_STRIDE + c] = 0;
@@ -256,25 +256,25 @@ __global__ void __launch_bounds__(256)
 }
 
 template <int HD>
-static void launch_fa(const void* q, const void* kc, const void* vc, long kv_head_stride, int B, int Lmax,
+static void launch_fa(const void* q, const void* kc, const void* vc, long kv_extra, int B, int Lmax,
                       const int* len, const int* cu, const int* kvoff, int H, void* out, hipStream_t s) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
   dim3 grid((Lmax + FA_BQ - 1) / FA_BQ, H, B);
   hipLaunchKernelGGL(attn_prefill_mfma<HD>, grid, dim3(256), 0, s, (const half_t*)q, (const half_t*)kc,
-                     (const half_t*)vc, kv_head_stride, len, cu, kvoff, H, scale_log2e, (half_t*)out);
+                     (const half_t*)vc, kv_extra, len, cu, kvoff, H, scale_log2e, (half_t*)out);
 }
 
-hipError_t launch_attn_prefill(int dtype, const void* q, const void* kc, const void* vc, long kv_head_stride,
+hipError_t launch_attn_prefill(int dtype, const void* q, const void* kc, const void* vc, long kv_extra,
                                int B, int Lmax, const int* len, const int* cu, const int* kvoff, int H, int hd,
                                void* out, hipStream_t s) {
   if (hd > 256) return hipErrorInvalidValue;
   if (dtype == 1) {
     switch (hd) {
-      case 16: launch_fa<16>(q, kc, vc, kv_head_stride, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
-      case 64: launch_fa<64>(q, kc, vc, kv_head_stride, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
-      case 80: launch_fa<80>(q, kc, vc, kv_head_stride, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
-      case 128: launch_fa<128>(q, kc, vc, kv_head_stride, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
-      case 256: launch_fa<256>(q, kc, vc, kv_head_stride, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
+      case 16: launch_fa<16>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
+      case 64: launch_fa<64>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
+      case 80: launch_fa<80>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
+      case 128: launch_fa<128>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
+      case 256: launch_fa<256>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
       default: break;  // other head sizes: generic kernel below
     }
   }
@@ -286,13 +286,13 @@ hipError_t launch_attn_prefill(int dtype, const void* q, const void* kc, const v
       (void)hipFuncSetAttribute((const void*)attn_prefill_generic<float>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)sh);
     hipLaunchKernelGGL(attn_prefill_generic<float>, grid, dim3(256), sh, s, (const float*)q, (const float*)kc,
-                       (const float*)vc, kv_head_stride, len, cu, kvoff, H, hd, scale, (float*)out);
+                       (const float*)vc, kv_extra, len, cu, kvoff, H, hd, scale, (float*)out);
   } else {
     if (sh > 65536)
       (void)hipFuncSetAttribute((const void*)attn_prefill_generic<half_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)sh);
     hipLaunchKernelGGL(attn_prefill_generic<half_t>, grid, dim3(256), sh, s, (const half_t*)q, (const half_t*)kc,
-                       (const half_t*)vc, kv_head_stride, len, cu, kvoff, H, hd, scale, (half_t*)out);
+                       (const half_t*)vc, kv_extra, len, cu, kvoff, H, hd, scale, (half_t*)out);
   }
   return hipGetLastError();
 }
@@ -303,7 +303,7 @@ hipError_t launch_attn_prefill(int dtype, const void* q, const void* kc, const v
 template <typename T>
 __global__ void __launch_bounds__(256)
     attn_decode_generic(const T* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc,
-                        long kv_head_stride, const int* __restrict__ len, int ctx_add,
+                        long kv_extra, const int* __restrict__ len, int ctx_add,
                         const int* __restrict__ kvoff, int H, int hd, float scale, T* __restrict__ out) {
   extern __shared__ float smem[];
   __shared__ float red[8];
@@ -314,8 +314,8 @@ __global__ void __launch_bounds__(256)
   float* part = qs + hd;   // [256]  (G x hd partial outputs, G*hd <= 256)
   float* sc = part + 256;  // [ctx]
   const int d = H * hd;
-  const T* kb = kc + (size_t)h * kv_head_stride + (size_t)kvoff[b] * hd;
-  const T* vb = vc + (size_t)h * kv_head_stride + (size_t)kvoff[b] * hd;
+  const T* kb = kc + ((size_t)kvoff[b] * H + (size_t)h * (len[b] + kv_extra)) * hd;
+  const T* vb = vc + ((size_t)kvoff[b] * H + (size_t)h * (len[b] + kv_extra)) * hd;
   for (int e = tid; e < hd; e += 256) qs[e] = to_f32(q[(size_t)b * d + (size_t)h * hd + e]) * scale;
   __syncthreads();
   float mx = -INFINITY;
@@ -371,7 +371,7 @@ typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
 template <int HD>
 __global__ void __launch_bounds__(256)
     attn_decode_f16(const half_t* __restrict__ q, const half_t* __restrict__ kc, const half_t* __restrict__ vc,
-                    long kv_head_stride, const int* __restrict__ len, int ctx_add, const int* __restrict__ kvoff,
+                    long kv_extra, const int* __restrict__ len, int ctx_add, const int* __restrict__ kvoff,
                     int H, float scale, half_t* __restrict__ out) {
   constexpr int CPR = HD / 8;             // 16-byte chunks per row
   constexpr int G = 64 / CPR;             // rows per wave instruction
@@ -388,8 +388,8 @@ __global__ void __launch_bounds__(256)
   const int ctx_pad = (ctx + 3) & ~3;
   float* scratch = sc + ctx_pad;                 // partial dots (non-power-of-two CPR) / output partials
   const int d = H * HD;
-  const half_t* kb = kc + (size_t)h * kv_head_stride + (size_t)kvoff[b] * HD;
-  const half_t* vb = vc + (size_t)h * kv_head_stride + (size_t)kvoff[b] * HD;
+  const half_t* kb = kc + ((size_t)kvoff[b] * H + (size_t)h * (len[b] + kv_extra)) * HD;
+  const half_t* vb = vc + ((size_t)kvoff[b] * H + (size_t)h * (len[b] + kv_extra)) * HD;
 
   // this lane's 8 query values, as 4 packed pairs
   f16x2_t qv[4];
@@ -480,7 +480,7 @@ __global__ void __launch_bounds__(256)
 }
 
 template <int HD>
-static hipError_t launch_dec(const void* q, const void* kc, const void* vc, long kv_head_stride, int B,
+static hipError_t launch_dec(const void* q, const void* kc, const void* vc, long kv_extra, int B,
                              const int* len, int ctx_add, int ctx_max, const int* kvoff, int H, void* out,
                              hipStream_t s) {
   constexpr int CPR = HD / 8, G = 64 / CPR;
@@ -490,22 +490,22 @@ static hipError_t launch_dec(const void* q, const void* kc, const void* vc, long
   if (sh > 65536)
     (void)hipFuncSetAttribute((const void*)attn_decode_f16<HD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
   hipLaunchKernelGGL(attn_decode_f16<HD>, dim3(H, B), dim3(256), sh, s, (const half_t*)q, (const half_t*)kc,
-                     (const half_t*)vc, kv_head_stride, len, ctx_add, kvoff, H, 1.0f / sqrtf((float)HD),
+                     (const half_t*)vc, kv_extra, len, ctx_add, kvoff, H, 1.0f / sqrtf((float)HD),
                      (half_t*)out);
   return hipGetLastError();
 }
 
-hipError_t launch_attn_decode(int dtype, const void* q, const void* kc, const void* vc, long kv_head_stride,
+hipError_t launch_attn_decode(int dtype, const void* q, const void* kc, const void* vc, long kv_extra,
                               int B, const int* len, int ctx_add, int ctx_max, const int* kvoff, int H, int hd,
                               void* out, hipStream_t s) {
   if (hd > 256) return hipErrorInvalidValue;
   if (dtype == 1) {
     switch (hd) {
-      case 16: return launch_dec<16>(q, kc, vc, kv_head_stride, B, len, ctx_add, ctx_max, kvoff, H, out, s);
-      case 64: return launch_dec<64>(q, kc, vc, kv_head_stride, B, len, ctx_add, ctx_max, kvoff, H, out, s);
-      case 80: return launch_dec<80>(q, kc, vc, kv_head_stride, B, len, ctx_add, ctx_max, kvoff, H, out, s);
-      case 128: return launch_dec<128>(q, kc, vc, kv_head_stride, B, len, ctx_add, ctx_max, kvoff, H, out, s);
-      case 256: return launch_dec<256>(q, kc, vc, kv_head_stride, B, len, ctx_add, ctx_max, kvoff, H, out, s);
+      case 16: return launch_dec<16>(q, kc, vc, kv_extra, B, len, ctx_add, ctx_max, kvoff, H, out, s);
+      case 64: return launch_dec<64>(q, kc, vc, kv_extra, B, len, ctx_add, ctx_max, kvoff, H, out, s);
+      case 80: return launch_dec<80>(q, kc, vc, kv_extra, B, len, ctx_add, ctx_max, kvoff, H, out, s);
+      case 128: return launch_dec<128>(q, kc, vc, kv_extra, B, len, ctx_add, ctx_max, kvoff, H, out, s);
+      case 256: return launch_dec<256>(q, kc, vc, kv_extra, B, len, ctx_add, ctx_max, kvoff, H, out, s);
       default: break;  // other head sizes: generic kernel below
     }
   }
@@ -515,10 +515,10 @@ hipError_t launch_attn_decode(int dtype, const void* q, const void* kc, const vo
   dim3 grid(H, B);
   if (dtype == 0)
     hipLaunchKernelGGL(attn_decode_generic<float>, grid, dim3(256), sh, s, (const float*)q, (const float*)kc,
-                       (const float*)vc, kv_head_stride, len, ctx_add, kvoff, H, hd, scale, (float*)out);
+                       (const float*)vc, kv_extra, len, ctx_add, kvoff, H, hd, scale, (float*)out);
   else
     hipLaunchKernelGGL(attn_decode_generic<half_t>, grid, dim3(256), sh, s, (const half_t*)q, (const half_t*)kc,
-                       (const half_t*)vc, kv_head_stride, len, ctx_add, kvoff, H, hd, scale, (half_t*)out);
+                       (const half_t*)vc, kv_extra, len, ctx_add, kvoff, H, hd, scale, (half_t*)out);
   return hipGetLastError();
 }
 

@@ -116,21 +116,24 @@ hipError_t launch_final_ln(int dtype, const float* x, const int* src, int src_ad
                            const int* rows_dev, int d, float eps, const void* g, const void* b, void* out,
                            const void* value_w, float value_b, float* val, hipStream_t s);
 
+// K/V layout: sequence b owns the slab of slots [kvoff[b]*H, kvoff[b+1]*H); inside it head h has
+// len[b] + kv_extra consecutive rows of hd elements (kv_extra = room for generated tokens), so one
+// (sequence, head) pair is one contiguous run and a sequence's heads are neighbours.
 // Rotary on q,k (first r dims of each head) + K/V store.  qkv [rows, 3d] -> q [rows, d] and
-// kc/vc [H][kv_total][hd] at slot kvoff[rowid[t]] + pos[t] + pos_add.  rowid may be null (row t is
+// kc/vc at row pos[t] + pos_add of (sequence rowid[t], head h).  rowid may be null (row t is
 // sequence t).  cos/sin tables are [max_pos][r/2].
 hipError_t launch_rope_kv(int dtype, const void* qkv, int rows_max, const int* rows_dev, const int* pos,
-                          int pos_add, const int* rowid, const int* kvoff, int H, int hd, int r,
+                          int pos_add, const int* rowid, const int* kvoff, const int* len, int H, int hd, int r,
                           const float* cos_t, const float* sin_t, void* q, void* kc, void* vc,
-                          long kv_head_stride, hipStream_t s);
+                          long kv_extra, hipStream_t s);
 
 // Causal attention over packed sequences (prefill / scoring).  q [T, H*hd]; kc/vc [H][*][hd] with
 // sequence b's keys at slots kvoff[b] .. kvoff[b]+len[b]; out [T, H*hd].
-hipError_t launch_attn_prefill(int dtype, const void* q, const void* kc, const void* vc, long kv_head_stride,
+hipError_t launch_attn_prefill(int dtype, const void* q, const void* kc, const void* vc, long kv_extra,
                                int B, int Lmax, const int* len, const int* cu, const int* kvoff, int H, int hd,
                                void* out, hipStream_t s);
 // Decode attention: one query row per sequence against ctx = len[b] + ctx_add cached keys.
-hipError_t launch_attn_decode(int dtype, const void* q, const void* kc, const void* vc, long kv_head_stride,
+hipError_t launch_attn_decode(int dtype, const void* q, const void* kc, const void* vc, long kv_extra,
                               int B, const int* len, int ctx_add, int ctx_max, const int* kvoff, int H, int hd,
                               void* out, hipStream_t s);
 

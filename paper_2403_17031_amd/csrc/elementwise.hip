@@ -173,8 +173,9 @@ __device__ __forceinline__ f32x4_t bf16x4_to_f32(u32x2_t v) {
   return r;
 }
 
+// One block per row (few rows: decode).
 __global__ void __launch_bounds__(256)
-    layernorm_vec_kernel(const float* __restrict__ x, const int* __restrict__ src, int src_add,
+    layernorm_vec_block_kernel(const float* __restrict__ x, const int* __restrict__ src, int src_add,
                          const int* __restrict__ rows_dev, int d, float eps, const bf16_t* __restrict__ g1,
                          const bf16_t* __restrict__ b1, half_t* __restrict__ out1, const bf16_t* __restrict__ g2,
                          const bf16_t* __restrict__ b2, half_t* __restrict__ out2,
@@ -235,6 +236,70 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+// One wave per row, four rows per block: no block-wide synchronisation, only wave shuffles.
+template <int NV>  // float4 chunks per lane: d <= 256 * NV
+__global__ void __launch_bounds__(256)
+    layernorm_vec_kernel(const float* __restrict__ x, const int* __restrict__ src, int src_add, int rows_max,
+                         const int* __restrict__ rows_dev, int d, float eps, const bf16_t* __restrict__ g1,
+                         const bf16_t* __restrict__ b1, half_t* __restrict__ out1, const bf16_t* __restrict__ g2,
+                         const bf16_t* __restrict__ b2, half_t* __restrict__ out2,
+                         const bf16_t* __restrict__ value_w, float value_b, float* __restrict__ val) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= (rows_dev ? min(*rows_dev, rows_max) : rows_max)) return;
+  const int sr = src ? max(src[r] + src_add, 0) : r;
+  const f32x4_t* xr = (const f32x4_t*)(x + (size_t)sr * d);
+  const int nv = d >> 2;
+  f32x4_t v[NV];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nv) {
+      v[i] = xr[c];
+      s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
+    }
+  }
+  const float mean = wave_sum(s) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nv) {
+      v[i] -= mean;
+      q += v[i][0] * v[i][0] + v[i][1] * v[i][1] + v[i][2] * v[i][2] + v[i][3] * v[i][3];
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+  float vd = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nv) {
+      const f32x4_t n = v[i] * rstd;
+      const f32x4_t h1 = n * bf16x4_to_f32(((const u32x2_t*)g1)[c]) + bf16x4_to_f32(((const u32x2_t*)b1)[c]);
+      f16x4_t o;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) o[u] = from_f32<half_t>(h1[u]);
+      ((f16x4_t*)(out1 + (size_t)r * d))[c] = o;
+      if (out2) {
+        const f32x4_t h2 = n * bf16x4_to_f32(((const u32x2_t*)g2)[c]) + bf16x4_to_f32(((const u32x2_t*)b2)[c]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) o[u] = from_f32<half_t>(h2[u]);
+        ((f16x4_t*)(out2 + (size_t)r * d))[c] = o;
+      }
+      if (val) {
+        const f32x4_t w = bf16x4_to_f32(((const u32x2_t*)value_w)[c]);
+        vd += h1[0] * w[0] + h1[1] * w[1] + h1[2] * w[2] + h1[3] * w[3];
+      }
+    }
+  }
+  if (val) {
+    vd = wave_sum(vd);
+    if (lane == 0) val[r] = vd + value_b;
+  }
+}
+
 template <typename M>
 static hipError_t ln_launch(const float* x, const int* src, int src_add, int rows_max, const int* rows_dev, int d,
                             float eps, const void* g1, const void* b1, void* out1, const void* g2,
@@ -243,9 +308,19 @@ static hipError_t ln_launch(const float* x, const int* src, int src_add, int row
   typedef typename M::W WT;
   typedef typename M::A AT;
   if (sizeof(AT) == 2 && (d & 3) == 0 && d <= 4096) {
-    hipLaunchKernelGGL(layernorm_vec_kernel, dim3(rows_max), dim3(256), 0, s, x, src, src_add, rows_dev, d, eps,
-                       (const bf16_t*)g1, (const bf16_t*)b1, (half_t*)out1, (const bf16_t*)g2, (const bf16_t*)b2,
-                       (half_t*)out2, (const bf16_t*)vw, vb, val);
+    const dim3 grid((rows_max + 3) / 4);
+    if (rows_max <= 2048)
+      hipLaunchKernelGGL(layernorm_vec_block_kernel, dim3(rows_max), dim3(256), 0, s, x, src, src_add, rows_dev, d,
+                         eps, (const bf16_t*)g1, (const bf16_t*)b1, (half_t*)out1, (const bf16_t*)g2,
+                         (const bf16_t*)b2, (half_t*)out2, (const bf16_t*)vw, vb, val);
+    else if (d <= 1024)
+      hipLaunchKernelGGL(layernorm_vec_kernel<4>, grid, dim3(256), 0, s, x, src, src_add, rows_max, rows_dev, d,
+                         eps, (const bf16_t*)g1, (const bf16_t*)b1, (half_t*)out1, (const bf16_t*)g2,
+                         (const bf16_t*)b2, (half_t*)out2, (const bf16_t*)vw, vb, val);
+    else
+      hipLaunchKernelGGL(layernorm_vec_kernel<16>, grid, dim3(256), 0, s, x, src, src_add, rows_max, rows_dev, d,
+                         eps, (const bf16_t*)g1, (const bf16_t*)b1, (half_t*)out1, (const bf16_t*)g2,
+                         (const bf16_t*)b2, (half_t*)out2, (const bf16_t*)vw, vb, val);
     return hipGetLastError();
   }
   hipLaunchKernelGGL((layernorm_kernel<WT, AT>), dim3(rows_max), dim3(256), 0, s, x, src, src_add, rows_dev, d,
@@ -281,15 +356,17 @@ hipError_t launch_final_ln(int dtype, const float* x, const int* src, int src_ad
 template <typename T>
 __global__ void __launch_bounds__(256)
     rope_kv_kernel(const T* __restrict__ qkv, const int* __restrict__ rows_dev, const int* __restrict__ pos,
-                   int pos_add, const int* __restrict__ rowid, const int* __restrict__ kvoff, int H, int hd,
+                   int pos_add, const int* __restrict__ rowid, const int* __restrict__ kvoff,
+                   const int* __restrict__ len, int H, int hd,
                    int r, const float* __restrict__ cos_t, const float* __restrict__ sin_t, T* __restrict__ q,
-                   T* __restrict__ kc, T* __restrict__ vc, long kv_head_stride) {
+                   T* __restrict__ kc, T* __restrict__ vc, long kv_extra) {
   const int t = blockIdx.x;
   if (rows_dev && t >= *rows_dev) return;
   const int d = H * hd;
   const int p = pos[t] + pos_add;
   const int b = rowid ? rowid[t] : t;
-  const long slot = (long)kvoff[b] + p;
+  const long seq_base = (long)kvoff[b] * H;          // sequence b owns slots [kvoff[b]*H, kvoff[b+1]*H)
+  const long seq_len = len[b] + kv_extra;             // slots per head inside that slab
   const T* src = qkv + (size_t)t * 3 * d;
   const int half = r >> 1;
   const float* cs = cos_t + (size_t)p * half;
@@ -307,7 +384,7 @@ __global__ void __launch_bounds__(256)
       kv = kv * co + to_f32(src[d + c - half]) * si;
     }
     q[(size_t)t * d + c] = from_f32<T>(qv);
-    const size_t o = (size_t)h * kv_head_stride + (size_t)slot * hd + e;
+    const size_t o = (size_t)(seq_base + h * seq_len + p) * hd + e;
     kc[o] = from_f32<T>(kv);
     vc[o] = src[2 * d + c];
   }
@@ -315,64 +392,120 @@ __global__ void __launch_bounds__(256)
 
 // fp16 form moving 16 bytes (8 dims) per access; head_dim a multiple of 8.  Only the chunks that
 // overlap the rotary dims do per-element work (the rotation partner is fetched as a scalar).
+// A block takes RPB consecutive packed rows, so that the K / V stores of one head are RPB adjacent
+// 2*hd-byte rows written by one CU.  Two passes: (1) one thread per (row, q|k, head) loads the
+// head's rotary dims (the first ceil(R/8) 16-byte chunks), rotates them in registers and stores
+// them; (2) every other chunk (rest of q and k, all of v) is a 16-byte copy.  R is a template
+// parameter so the rotation pairs (i, i + R/2) are register-to-register.
+template <int RPB, int R>
 __global__ void __launch_bounds__(256)
-    rope_kv_vec_kernel(const half_t* __restrict__ qkv, const int* __restrict__ rows_dev, const int* __restrict__ pos,
-                       int pos_add, const int* __restrict__ rowid, const int* __restrict__ kvoff, int H, int hd,
-                       int r, const float* __restrict__ cos_t, const float* __restrict__ sin_t,
-                       half_t* __restrict__ q, half_t* __restrict__ kc, half_t* __restrict__ vc,
-                       long kv_head_stride) {
-  const int t = blockIdx.x;
-  if (rows_dev && t >= *rows_dev) return;
-  const int d = H * hd;
-  const int p = pos[t] + pos_add;
-  const int b = rowid ? rowid[t] : t;
-  const long slot = (long)kvoff[b] + p;
-  const half_t* src = qkv + (size_t)t * 3 * d;
-  const int half = r >> 1;
-  const float* cs = cos_t + (size_t)p * half;
-  const float* sn = sin_t + (size_t)p * half;
-  const int cph = hd >> 3, cpr = d >> 3;  // chunks per head / per q,k,v section
-  for (int c = threadIdx.x; c < 3 * cpr; c += 256) {
-    const int sec = c / cpr, cc = c - sec * cpr;
-    const int h = cc / cph, e0 = (cc - h * cph) << 3;
-    f16x8_t v = *(const f16x8_t*)(src + (size_t)c * 8);
-    if (sec < 2 && e0 < r) {
-      const half_t* hb = src + sec * d + h * hd;  // this head's q or k
+    rope_kv_vec_kernel(const half_t* __restrict__ qkv, int rows_max, const int* __restrict__ rows_dev,
+                       const int* __restrict__ pos, int pos_add, const int* __restrict__ rowid,
+                       const int* __restrict__ kvoff, const int* __restrict__ len, int H, int hd,
+                       const float* __restrict__ cos_t, const float* __restrict__ sin_t, half_t* __restrict__ q,
+                       half_t* __restrict__ kc, half_t* __restrict__ vc, long kv_extra) {
+  constexpr int HALF = R / 2, RC = (R + 7) / 8;
+  __shared__ int s_pos[RPB];
+  __shared__ long s_base[RPB], s_len[RPB];
+  const int t0 = blockIdx.x * RPB;
+  const int rows = min(rows_dev ? *rows_dev : rows_max, rows_max);
+  if (t0 >= rows) return;
+  const int nr = min(RPB, rows - t0);
+  if (threadIdx.x < nr) {
+    const int t = t0 + threadIdx.x;
+    const int p = pos[t] + pos_add;
+    const int b = rowid ? rowid[t] : t;
+    s_pos[threadIdx.x] = p;
+    s_len[threadIdx.x] = len[b] + kv_extra;             // slots per head in sequence b's slab
+    s_base[threadIdx.x] = (long)kvoff[b] * H + p;       // slab start (in slots) + position
+  }
+  __syncthreads();
+  const int d = H * hd, cph = hd >> 3;
+  auto dst_of = [&](int sec, int rr, int h) -> half_t* {
+    return sec == 0 ? q + (size_t)(t0 + rr) * d + h * hd
+                    : (sec == 1 ? kc : vc) + (size_t)(s_base[rr] + h * s_len[rr]) * hd;
+  };
+  // ---- pass 1: rotary part of every q and k head
+  for (int c = threadIdx.x; c < nr * 2 * H; c += 256) {
+    const int rr = c / (2 * H), w = c - rr * 2 * H;
+    const int sec = w / H, h = w - sec * H;
+    const half_t* hb = qkv + (size_t)(t0 + rr) * 3 * d + sec * d + h * hd;
+    f16x8_t v[RC];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int e = e0 + i;
-        if (e < half)
-          v[i] = from_f32<half_t>((float)v[i] * cs[e] - (float)hb[e + half] * sn[e]);
-        else if (e < r)
-          v[i] = from_f32<half_t>((float)v[i] * cs[e - half] + (float)hb[e - half] * sn[e - half]);
-      }
+    for (int i = 0; i < RC; ++i) v[i] = *(const f16x8_t*)(hb + 8 * i);
+    const float* cs = cos_t + (size_t)s_pos[rr] * HALF;
+    const float* sn = sin_t + (size_t)s_pos[rr] * HALF;
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const float co = cs[i], si = sn[i];
+      const float lo = (float)v[i >> 3][i & 7], hi = (float)v[(i + HALF) >> 3][(i + HALF) & 7];
+      v[i >> 3][i & 7] = from_f32<half_t>(lo * co - hi * si);
+      v[(i + HALF) >> 3][(i + HALF) & 7] = from_f32<half_t>(hi * co + lo * si);
     }
-    if (sec == 0) {
-      *(f16x8_t*)(q + (size_t)t * d + cc * 8) = v;
+    half_t* dst = dst_of(sec, rr, h);
+#pragma unroll
+    for (int i = 0; i < RC; ++i) *(f16x8_t*)(dst + 8 * i) = v[i];
+  }
+  // ---- pass 2: plain copies, chunk fastest, then row, then head, then section
+  const int qk_cph = cph - RC;                    // untouched chunks per q / k head
+  const int per_qk = nr * qk_cph, per_v = nr * cph;
+  const int total = 2 * H * per_qk + H * per_v;
+  for (int c = threadIdx.x; c < total; c += 256) {
+    int sec, h, rr, ch;
+    if (c < 2 * H * per_qk) {
+      const int sh = c / per_qk, w = c - sh * per_qk;
+      sec = sh / H; h = sh - sec * H;
+      rr = w / qk_cph; ch = RC + (w - rr * qk_cph);
     } else {
-      half_t* dst = (sec == 1 ? kc : vc) + (size_t)h * kv_head_stride + (size_t)slot * hd + e0;
-      *(f16x8_t*)dst = v;
+      const int c2 = c - 2 * H * per_qk;
+      sec = 2; h = c2 / per_v;
+      const int w = c2 - h * per_v;
+      rr = w / cph; ch = w - rr * cph;
     }
+    const f16x8_t v = *(const f16x8_t*)(qkv + (size_t)(t0 + rr) * 3 * d + sec * d + h * hd + 8 * ch);
+    *(f16x8_t*)(dst_of(sec, rr, h) + 8 * ch) = v;
   }
 }
 
+template <int RPB>
+static bool launch_rope_vec(int r, dim3 grid, hipStream_t s, const half_t* qkv, int rows_max, const int* rows_dev,
+                            const int* pos, int pos_add, const int* rowid, const int* kvoff, const int* len, int H,
+                            int hd, const float* cos_t, const float* sin_t, half_t* q, half_t* kc, half_t* vc,
+                            long kv_extra) {
+#define RLHF_ROPE_CASE(RR)                                                                                     \
+  case RR:                                                                                                     \
+    hipLaunchKernelGGL((rope_kv_vec_kernel<RPB, RR>), grid, dim3(256), 0, s, qkv, rows_max, rows_dev, pos,     \
+                       pos_add, rowid, kvoff, len, H, hd, cos_t, sin_t, q, kc, vc, kv_extra);                  \
+    return true;
+  switch (r) {
+    RLHF_ROPE_CASE(4) RLHF_ROPE_CASE(16) RLHF_ROPE_CASE(20) RLHF_ROPE_CASE(32) RLHF_ROPE_CASE(64)
+    default: return false;
+  }
+#undef RLHF_ROPE_CASE
+}
+
 hipError_t launch_rope_kv(int dtype, const void* qkv, int rows_max, const int* rows_dev, const int* pos,
-                          int pos_add, const int* rowid, const int* kvoff, int H, int hd, int r,
+                          int pos_add, const int* rowid, const int* kvoff, const int* len, int H, int hd, int r,
                           const float* cos_t, const float* sin_t, void* q, void* kc, void* vc,
-                          long kv_head_stride, hipStream_t s) {
+                          long kv_extra, hipStream_t s) {
   if (rows_max <= 0) return hipSuccess;
   if (dtype == 0)
     hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(rows_max), dim3(256), 0, s, (const float*)qkv, rows_dev, pos,
-                       pos_add, rowid, kvoff, H, hd, r, cos_t, sin_t, (float*)q, (float*)kc, (float*)vc,
-                       kv_head_stride);
-  else if ((hd & 7) == 0)
-    hipLaunchKernelGGL(rope_kv_vec_kernel, dim3(rows_max), dim3(256), 0, s, (const half_t*)qkv, rows_dev, pos,
-                       pos_add, rowid, kvoff, H, hd, r, cos_t, sin_t, (half_t*)q, (half_t*)kc, (half_t*)vc,
-                       kv_head_stride);
+                       pos_add, rowid, kvoff, len, H, hd, r, cos_t, sin_t, (float*)q, (float*)kc, (float*)vc,
+                       kv_extra);
+  else if ((hd & 7) == 0 && r <= hd &&
+           (rows_max > 2048
+                ? launch_rope_vec<8>(r, dim3((rows_max + 7) / 8), s, (const half_t*)qkv, rows_max, rows_dev, pos,
+                                     pos_add, rowid, kvoff, len, H, hd, cos_t, sin_t, (half_t*)q, (half_t*)kc,
+                                     (half_t*)vc, kv_extra)
+                : launch_rope_vec<1>(r, dim3(rows_max), s, (const half_t*)qkv, rows_max, rows_dev, pos, pos_add,
+                                     rowid, kvoff, len, H, hd, cos_t, sin_t, (half_t*)q, (half_t*)kc, (half_t*)vc,
+                                     kv_extra))) {
+  }
   else
     hipLaunchKernelGGL(rope_kv_kernel<half_t>, dim3(rows_max), dim3(256), 0, s, (const half_t*)qkv, rows_dev,
-                       pos, pos_add, rowid, kvoff, H, hd, r, cos_t, sin_t, (half_t*)q, (half_t*)kc, (half_t*)vc,
-                       kv_head_stride);
+                       pos, pos_add, rowid, kvoff, len, H, hd, r, cos_t, sin_t, (half_t*)q, (half_t*)kc, (half_t*)vc,
+                       kv_extra);
   return hipGetLastError();
 }
 

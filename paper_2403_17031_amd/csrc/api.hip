@@ -51,7 +51,8 @@ struct Meta {
 struct Acts {
   float* x;
   void *a, *m, *qkv, *q, *att, *ffn;
-  void* splitk = nullptr;  // fp32 partial sums of the decode GEMMs
+  void* splitk = nullptr;   // fp32 partial sums of the decode GEMMs (attention branch)
+  void* splitk2 = nullptr;  // same for the MLP branch, which runs on a second stream
   size_t splitk_bytes = 0;
 };
 
@@ -73,6 +74,10 @@ struct rlhf_handle {
   size_t ev_used = 0;
   hipEvent_t ph[3] = {nullptr, nullptr, nullptr};
   bool ph_valid = false;
+  // decode runs the MLP branch of the parallel-residual layer on a second stream (default priority)
+  hipStream_t side = nullptr;
+  hipEvent_t fork_ev[8] = {}, join_ev[8] = {};
+  unsigned ev_rr = 0;
 
   hipEvent_t get_event() {
     if (ev_used == ev_pool.size()) {
@@ -162,6 +167,7 @@ RolloutWs carve_rollout(Carver& c, const rlhf_model_config& cfg, int B, int Lq, 
   w.logits = c.take<float>((size_t)B * cfg.vocab);
   w.acts.splitk_bytes = (size_t)16 * B * std::max(3 * cfg.d_model, cfg.d_ff) * sizeof(float);
   w.acts.splitk = c.take_bytes(w.acts.splitk_bytes);
+  w.acts.splitk2 = c.take_bytes(w.acts.splitk_bytes);
   w.kv_slots = (size_t)B * (Lq + N - 1);
   w.kv = (char*)c.take_bytes((size_t)cfg.n_layers * 2 * w.kv_slots * cfg.d_model * esz);
   return w;
@@ -228,27 +234,66 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
       g.splitk_ws = A.splitk;
       g.splitk_ws_bytes = A.splitk_bytes;
     }
+    // Decode: the MLP branch (weights streaming through the matrix cores) overlaps the attention
+    // branch (K/V streaming from HBM).  Needs FC2 on the split-K path, so that only its final
+    // reduction touches the residual stream; not used while per-kernel profiling is on.
+    bool fork_mlp = false;
+    hipEvent_t join = nullptr;
+    if (p.mode == 1 && !h->prof_on) {
+      GemmArgs t = g;
+      t.splitk_ws = A.splitk2; t.N = d; t.K = c.d_ff; t.ldo = d;
+      fork_mlp = gemm_splitk_factor(dt, t) > 1;
+    }
     g.A = A.a; g.W = h->w_qkv[l]; g.bias = h->b_qkv[l]; g.out = A.qkv; g.N = 3 * d; g.K = d; g.ldo = 3 * d;
     g.epilogue = EPI_BIAS;
     LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
     LAUNCH(p.mode ? "rope_kv_decode" : "rope_kv", launch_rope_kv(dt, A.qkv, p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff,
                                      p.len, c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q, kc, vc,
                                      (long)p.kv_extra, s));
+    if (fork_mlp) {
+      hipEvent_t fork = h->fork_ev[h->ev_rr & 7];
+      join = h->join_ev[h->ev_rr & 7];
+      ++h->ev_rr;
+      HIP_OK(hipEventRecord(fork, s));
+      HIP_OK(hipStreamWaitEvent(h->side, fork, 0));
+      GemmArgs m1 = g, m2 = g;
+      m1.splitk_ws = A.splitk2; m2.splitk_ws = A.splitk2;
+      m1.A = A.m; m1.W = h->w_fc1[l]; m1.bias = h->b_fc1[l]; m1.out = A.ffn; m1.N = c.d_ff; m1.K = d;
+      m1.ldo = c.d_ff; m1.epilogue = EPI_BIAS_GELU;
+      m2.A = A.ffn; m2.W = h->w_fc2[l]; m2.bias = h->b_fc2[l]; m2.out = A.x; m2.N = d; m2.K = c.d_ff; m2.ldo = d;
+      m2.epilogue = EPI_BIAS_RESADD; m2.phase = 1;
+      hipError_t e1 = launch_gemm(dt, m1, h->side);
+      if (e1 == hipSuccess) e1 = launch_gemm(dt, m2, h->side);
+      if (e1 != hipSuccess) return fail(RLHF_EHIP, std::string("gemm_decode (side stream): ") + hipGetErrorString(e1));
+      HIP_OK(hipEventRecord(join, h->side));
+    }
     if (p.mode == 0)
       LAUNCH("attn_prefill", launch_attn_prefill(dt, A.q, kc, vc, (long)p.kv_extra, p.B, p.Lmax, p.len, p.cu, p.kvoff,
                                                  c.n_heads, c.head_dim, A.att, s));
     else
       LAUNCH("attn_decode", launch_attn_decode(dt, A.q, kc, vc, (long)p.kv_extra, p.B, p.len, p.ctx_add, p.ctx_max,
                                                p.kvoff, c.n_heads, c.head_dim, A.att, s));
-    g.A = A.att; g.W = h->w_o[l]; g.bias = h->b_o[l]; g.out = A.x; g.N = d; g.K = d; g.ldo = d;
-    g.epilogue = EPI_BIAS_RESADD;
-    LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
-    g.A = A.m; g.W = h->w_fc1[l]; g.bias = h->b_fc1[l]; g.out = A.ffn; g.N = c.d_ff; g.K = d; g.ldo = c.d_ff;
-    g.epilogue = EPI_BIAS_GELU;
-    LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
-    g.A = A.ffn; g.W = h->w_fc2[l]; g.bias = h->b_fc2[l]; g.out = A.x; g.N = d; g.K = c.d_ff; g.ldo = d;
-    g.epilogue = EPI_BIAS_RESADD;
-    LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
+    GemmArgs go = g, g1 = g, g2 = g;
+    go.A = A.att; go.W = h->w_o[l]; go.bias = h->b_o[l]; go.out = A.x; go.N = d; go.K = d; go.ldo = d;
+    go.epilogue = EPI_BIAS_RESADD;
+    g1.A = A.m; g1.W = h->w_fc1[l]; g1.bias = h->b_fc1[l]; g1.out = A.ffn; g1.N = c.d_ff; g1.K = d; g1.ldo = c.d_ff;
+    g1.epilogue = EPI_BIAS_GELU;
+    g2.A = A.ffn; g2.W = h->w_fc2[l]; g2.bias = h->b_fc2[l]; g2.out = A.x; g2.N = d; g2.K = c.d_ff; g2.ldo = d;
+    g2.epilogue = EPI_BIAS_RESADD;
+    if (fork_mlp) {
+      // MLP branch: FC1 and the partial sums of FC2 were enqueued on the side stream next to the
+      // attention kernel (forked after the rotary kernel); only FC2's reduction, which adds into the
+      // residual stream, waits here, so the order x = (x + attn) + mlp is the serial one.
+      LAUNCH("gemm_decode", launch_gemm(dt, go, s));
+      HIP_OK(hipStreamWaitEvent(s, join, 0));
+      g2.splitk_ws = A.splitk2;
+      g2.phase = 2;
+      LAUNCH("gemm_decode", launch_gemm(dt, g2, s));
+    } else {
+      LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, go, s));
+      LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g1, s));
+      LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g2, s));
+    }
   }
   return RLHF_OK;
 }
@@ -347,6 +392,17 @@ int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, rlhf_handle
       return fail(RLHF_EHIP, std::string("fp16 weight conversion: ") + hipGetErrorString(e));
     }
   }
+  {
+    hipError_t e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
+    for (int i = 0; i < 8 && e == hipSuccess; ++i) {
+      e = hipEventCreateWithFlags(&h->fork_ev[i], hipEventDisableTiming);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&h->join_ev[i], hipEventDisableTiming);
+    }
+    if (e != hipSuccess) {
+      rlhf_destroy(h);
+      return fail(RLHF_EHIP, std::string("side stream: ") + hipGetErrorString(e));
+    }
+  }
   *out = h;
   return RLHF_OK;
 }
@@ -359,6 +415,11 @@ void rlhf_destroy(rlhf_handle* h) {
   for (hipEvent_t e : h->ev_pool) (void)hipEventDestroy(e);
   for (hipEvent_t e : h->ph)
     if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : h->fork_ev)
+    if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : h->join_ev)
+    if (e) (void)hipEventDestroy(e);
+  if (h->side) (void)hipStreamDestroy(h->side);
   delete h;
 }
 

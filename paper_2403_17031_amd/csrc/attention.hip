@@ -399,26 +399,35 @@ __global__ void __launch_bounds__(256)
     for (int i = 0; i < 4; ++i) qv[i] = active ? *(const f16x2_t*)(qp + 2 * i) : (f16x2_t){0, 0};
   }
   const int n_it = (ctx + G - 1) / G;  // wave instructions needed to cover ctx rows
-  // ---- phase 1: scores
-  for (int it = wave; it < n_it; it += 4) {
-    const int j = it * G + g;
-    float pd = 0.f;
-    if (active && j < ctx) {
-      const u32x4_t kv = *(const u32x4_t*)(kb + (size_t)j * HD + part * 8);
+  // ---- phase 1: scores.  Four wave-loads are issued before the first is consumed: with one load
+  //      per wave in flight a CU holds too few bytes in flight to cover the HBM round trip.
+  for (int it0 = wave; it0 < n_it; it0 += 16) {
+    u32x4_t kv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = (it0 + 4 * u) * G + g;
+      kv[u] = (u32x4_t){0, 0, 0, 0};
+      if (active && j < ctx) kv[u] = *(const u32x4_t*)(kb + (size_t)j * HD + part * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int it = it0 + 4 * u;
+      const int j = it * G + g;
+      float pd = 0.f;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const uint32_t w = kv[i];
+        const uint32_t w = kv[u][i];
         f16x2_t kk;
         __builtin_memcpy(&kk, &w, 4);
         pd = __builtin_amdgcn_fdot2(kk, qv[i], pd, false);
       }
-    }
-    if (POW2) {
+      if (POW2) {
 #pragma unroll
-      for (int o = CPR >> 1; o > 0; o >>= 1) pd += __shfl_xor(pd, o, 64);
-      if (part == 0 && j < ctx) sc[j] = pd * scale;
-    } else {
-      if (active) scratch[it * ACTIVE + lane] = pd;  // row j's CPR partials are contiguous
+        for (int o = CPR >> 1; o > 0; o >>= 1) pd += __shfl_xor(pd, o, 64);
+        if (part == 0 && j < ctx) sc[j] = pd * scale;
+      } else {
+        if (active && it < n_it) scratch[it * ACTIVE + lane] = pd;  // row j's CPR partials are contiguous
+      }
     }
   }
   __syncthreads();
@@ -450,18 +459,26 @@ __global__ void __launch_bounds__(256)
   const float inv = 1.0f / (red[4] + red[5] + red[6] + red[7]);
   // ---- phase 3: out = sum_j p_j V[j]
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int it = wave; it < n_it; it += 4) {
-    const int j = it * G + g;
-    if (active && j < ctx) {
-      const u32x4_t vv = *(const u32x4_t*)(vb + (size_t)j * HD + part * 8);
-      const float p = sc[j];
+  for (int it0 = wave; it0 < n_it; it0 += 16) {
+    u32x4_t vv[4];
+    float pj[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = (it0 + 4 * u) * G + g;
+      const bool ok = active && j < ctx;
+      vv[u] = (u32x4_t){0, 0, 0, 0};
+      if (ok) vv[u] = *(const u32x4_t*)(vb + (size_t)j * HD + part * 8);
+      pj[u] = ok ? sc[j] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const uint32_t w = vv[i];
+        const uint32_t w = vv[u][i];
         f16x2_t x;
         __builtin_memcpy(&x, &w, 4);
-        acc[2 * i] = fmaf(p, (float)x[0], acc[2 * i]);
-        acc[2 * i + 1] = fmaf(p, (float)x[1], acc[2 * i + 1]);
+        acc[2 * i] = fmaf(pj[u], (float)x[0], acc[2 * i]);
+        acc[2 * i + 1] = fmaf(pj[u], (float)x[1], acc[2 * i + 1]);
       }
     }
   }

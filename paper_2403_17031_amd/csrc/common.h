@@ -89,7 +89,10 @@ struct GemmArgs {
   int epilogue;
   void* splitk_ws = nullptr;   // fp32 scratch for split-K partial sums (decode-sized M), or null
   size_t splitk_ws_bytes = 0;
+  int phase = 0;               // split-K only: 0 = GEMM + reduce, 1 = partial sums only, 2 = reduce only
 };
+// > 1 when launch_gemm would take the split-K path for these arguments.
+int gemm_splitk_factor(int dtype, const GemmArgs& a);
 hipError_t launch_gemm(int dtype, const GemmArgs& a, hipStream_t s);
 
 // Row metadata of a packed batch -------------------------------------------------------------------

@@ -588,6 +588,19 @@ __global__ void __launch_bounds__(256)
     if (col + u < N) epilogue_store<EPI, half_t>(out, i4 + u, v[u], (EPI != EPI_F32 && bias) ? to_f32(bias[col + u]) : 0.f);
 }
 
+// Split factor of the few-rows path (1 = not split).  Few rows (decode): the chip is filled by small
+// N tiles and by splitting K, so that every CU holds several short k-loops in flight; partial sums
+// go through the caller's fp32 scratch.
+int gemm_splitk_factor(int dtype, const GemmArgs& a) {
+  if (dtype != 1 || a.M_max > 512 || !a.splitk_ws || (a.ldo & 3) != 0) return 1;
+  const int tiles = ((a.M_max + 127) / 128) * ((a.N + 63) / 64);
+  const int nk = (a.K + TK - 1) / TK;
+  int ksplit = 1;
+  while (ksplit < 16 && tiles * ksplit < 1024 && nk / (ksplit * 2) >= 4) ksplit *= 2;
+  if ((size_t)ksplit * a.M_max * a.ldo * sizeof(float) > a.splitk_ws_bytes) return 1;
+  return ksplit;
+}
+
 template <int EPI>
 static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
   if (dtype == 0) {
@@ -597,20 +610,16 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
   } else {
     // Few rows (decode): the chip is filled by small N tiles and by splitting K, so that every CU
     // holds several short k-loops in flight; partial sums go through the caller's fp32 scratch.
-    if (a.M_max <= 512 && a.splitk_ws && (a.ldo & 3) == 0) {
-      const int tiles = ((a.M_max + 127) / 128) * ((a.N + 63) / 64);
-      const int nk = (a.K + TK - 1) / TK;
-      int ksplit = 1;
-      while (ksplit < 16 && tiles * ksplit < 1024 && nk / (ksplit * 2) >= 4) ksplit *= 2;
-      const size_t need = (size_t)ksplit * a.M_max * a.ldo * sizeof(float);
-      if (ksplit > 1 && need <= a.splitk_ws_bytes) {
-        launch_f16<EPI_F32, 2, 1, RLHF_DEC_PF, RLHF_DEC_OCC>(a, s, a.splitk_ws, ksplit);
+    const int ksplit = gemm_splitk_factor(dtype, a);
+    if (ksplit > 1) {
+      if (a.phase != 2) launch_f16<EPI_F32, 2, 1, RLHF_DEC_PF, RLHF_DEC_OCC>(a, s, a.splitk_ws, ksplit);
+      if (a.phase != 1) {
         const size_t n4 = ((size_t)a.M_max * a.ldo + 3) / 4;
         hipLaunchKernelGGL(splitk_reduce_kernel<EPI>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
                            (const float*)a.splitk_ws, ksplit, (size_t)a.M_max * a.ldo, (const bf16_t*)a.bias, a.out,
                            a.M_max, a.N, a.ldo);
-        return;
       }
+      return;
     }
     if (a.M_max <= 512)
       launch_f16<EPI, 2, 1, RLHF_DEC_PF, RLHF_DEC_OCC>(a, s, a.out, 1);

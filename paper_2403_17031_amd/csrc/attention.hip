@@ -123,7 +123,7 @@ constexpr int FA_BQ = 128, FA_BK = 64;
 constexpr int FA_VT_STRIDE = FA_BK + 8;  // halfs per V^T row: 144 B, odd multiple of 16 B
 
 template <int HD>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
     attn_prefill_mfma(const half_t* __restrict__ q, const half_t* __restrict__ kc, const half_t* __restrict__ vc,
                       long kv_extra, const int* __restrict__ len, const int* __restrict__ cu,
                       const int* __restrict__ kvoff, int H, float scale_log2e, half_t* __restrict__ out) {
@@ -160,26 +160,67 @@ __global__ void __launch_bounds__(256)
 
   const int q_hi = min(q0 + FA_BQ, n) - 1;           // last query of the block
   const int wq_lo = q0 + wave * 32;                  // first query of the wave
-  for (int k0 = 0; k0 <= q_hi; k0 += FA_BK) {
-    __syncthreads();
-    // K tile, row-major; keys past the sequence are clamped (their scores are masked below)
-    for (int c = tid; c < FA_BK * (HD / 8); c += 256) {
-      const int r = c / (HD / 8), ch = c - r * (HD / 8);
-      const u32x4_t v = *(const u32x4_t*)(kb + (size_t)min(k0 + r, n - 1) * HD + ch * 8);
-      *(u32x4_t*)(Ks + r * K_STRIDE + ch * 8) = v;
-    }
-    // V tile, transposed: consecutive lanes take consecutive keys, so that each of the 8 stores of
-    // a lane lands in one contiguous 128-byte row segment of V^T.  Key kk of a 16-key group goes
-    // to column 8*((kk>>2)&1) + (kk&3) + 4*(kk>>3) of that group.
-    for (int c = tid; c < FA_BK * (HD / 8); c += 256) {
-      const int ch = c / FA_BK, r = c - ch * FA_BK;
-      const f16x8_t v = *(const f16x8_t*)(vb + (size_t)min(k0 + r, n - 1) * HD + ch * 8);
-      const int kk = r & 15;
-      const int col = (r & ~15) + 8 * ((kk >> 2) & 1) + (kk & 3) + 4 * (kk >> 3);
+  // The next K / V tile travels global -> registers while the current one is being multiplied.
+  //   K: row-major 16-byte chunks, keys past the sequence clamped (their scores are masked below).
+  //   V: stored transposed.  A thread takes 4 consecutive keys x 8 dims and writes 8 eight-byte
+  //      words, one per dim: keys 4g..4g+3 stay adjacent under the column permutation
+  //      (key kk of a 16-key group goes to column 8*((kk>>2)&1) + (kk&3) + 4*(kk>>3)).
+  constexpr int KCH = FA_BK * (HD / 8);             // 16-byte chunks of a K tile
+  constexpr int NKR = (KCH + 255) / 256;            // ... per thread
+  constexpr int VIT = (FA_BK / 4) * (HD / 8);       // V items (4 keys x 8 dims)
+  constexpr int NVR = (VIT + 255) / 256;            // ... per thread
+  u32x4_t kreg[NKR];
+  f16x8_t vreg[NVR][4];
+  auto load_tile = [&](int k0) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) ((half_t*)Vt)[(ch * 8 + i) * FA_VT_STRIDE + col] = v[i];
+    for (int i = 0; i < NKR; ++i) {
+      const int c = tid + 256 * i;
+      if (c < KCH) {
+        const int r = c / (HD / 8), ch = c - r * (HD / 8);
+        kreg[i] = *(const u32x4_t*)(kb + (size_t)min(k0 + r, n - 1) * HD + ch * 8);
+      }
     }
+#pragma unroll
+    for (int i = 0; i < NVR; ++i) {
+      const int c = tid + 256 * i;
+      if (c < VIT) {
+        const int ch = c / (FA_BK / 4), g4 = c - ch * (FA_BK / 4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          vreg[i][u] = *(const f16x8_t*)(vb + (size_t)min(k0 + 4 * g4 + u, n - 1) * HD + ch * 8);
+      }
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int i = 0; i < NKR; ++i) {
+      const int c = tid + 256 * i;
+      if (c < KCH) {
+        const int r = c / (HD / 8), ch = c - r * (HD / 8);
+        *(u32x4_t*)(Ks + r * K_STRIDE + ch * 8) = kreg[i];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NVR; ++i) {
+      const int c = tid + 256 * i;
+      if (c < VIT) {
+        const int ch = c / (FA_BK / 4), g4 = c - ch * (FA_BK / 4);
+        const int kk = (4 * g4) & 15;
+        const int col = ((4 * g4) & ~15) + 8 * ((kk >> 2) & 1) + 4 * (kk >> 3);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          f16x4_t w = {vreg[i][0][e], vreg[i][1][e], vreg[i][2][e], vreg[i][3][e]};
+          *(f16x4_t*)((half_t*)Vt + (ch * 8 + e) * FA_VT_STRIDE + col) = w;
+        }
+      }
+    }
+  };
+  load_tile(0);
+  for (int k0 = 0; k0 <= q_hi; k0 += FA_BK) {
+    __syncthreads();  // every wave is done with the previous tile
+    store_tile();
     __syncthreads();
+    if (k0 + FA_BK <= q_hi) load_tile(k0 + FA_BK);
     if (k0 > wq_lo + 31) continue;  // every key of this tile is in the future of this wave's queries
 
     // ---- S^T = K Q^T for the two 32-key fragments

@@ -315,7 +315,7 @@ __global__ void __launch_bounds__(256)
 constexpr int DK = 32;                      // K depth of one stage
 constexpr int DSTAGE = (256 + 256) * DK;    // halfs per stage (32 KB)
 
-template <int EPI>
+template <int EPI, int NS>
 __global__ void __launch_bounds__(256, 1)
     gemm_f16_dma_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
                         void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
@@ -325,6 +325,7 @@ __global__ void __launch_bounds__(256, 1)
   __shared__ __attribute__((aligned(16))) uint16_t lds1[DSTAGE];
   __shared__ __attribute__((aligned(16))) uint16_t lds2[DSTAGE];
   __shared__ __attribute__((aligned(16))) uint16_t lds3[DSTAGE];
+  __shared__ __attribute__((aligned(16))) uint16_t lds4[NS == 5 ? DSTAGE : 8];  // fifth stage: all 160 KB
   const int M = M_dev ? min(M_max, *M_dev - M_sub) : M_max;
   nb_m = min(nb_m, (M + TM - 1) / TM);
   const int total = nb_m * nb_n;
@@ -389,44 +390,76 @@ __global__ void __launch_bounds__(256, 1)
 #pragma unroll
       for (int i = 0; i < MT; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[j], fa[i], acc[j][i], 0, 0, 0);
   };
-  // vmcnt(16) lgkmcnt(0): everything but the two youngest tile loads (8 instructions each) has
-  // landed, and this wave's fragment reads are complete
+  // vmcnt(8*(NS-2)) lgkmcnt(0): everything but the NS-2 youngest tile loads (8 instructions each)
+  // has landed, and this wave's fragment reads are complete
+  constexpr int WAIT_IMM = NS == 5 ? 0x4078 : 0x4070;
 #define RLHF_WAIT_BARRIER()                      \
   __builtin_amdgcn_sched_barrier(0);             \
   asm volatile("" ::: "memory");                 \
-  __builtin_amdgcn_s_waitcnt(0x4070);            \
+  __builtin_amdgcn_s_waitcnt(WAIT_IMM);          \
   __builtin_amdgcn_s_barrier();                  \
   asm volatile("" ::: "memory");                 \
   __builtin_amdgcn_sched_barrier(0);
-  // One k-step.  Order matters: the fragment reads of sub-step 1 go out in the middle of sub-step
-  // 0's matrix instructions, and those of the next k-step right after the barrier, so every LDS
-  // read has at least 8 matrix instructions (256 cycles) in front of its first use.
-#define RLHF_STEP(CUR, NEXT, LOAD, KT)                         \
-  mma(fa0, fw0, 0, 2);                                         \
-  __builtin_amdgcn_sched_barrier(0);                           \
-  issue_loads(LOAD, min((KT) + 3, nk - 1) * DK);               \
-  frags(CUR, ch1, fa1, fw1);                                   \
-  __builtin_amdgcn_sched_barrier(0);                           \
-  mma(fa0, fw0, 2, 4);                                         \
-  RLHF_WAIT_BARRIER()                                          \
-  frags(NEXT, ch0, fa0, fw0);                                  \
-  __builtin_amdgcn_sched_barrier(0);                           \
-  mma(fa1, fw1, 0, 4);                                         \
-  __builtin_amdgcn_sched_barrier(0);
+  // One k-step: 32 matrix instructions per wave with the 8 tile loads and 16 fragment reads dealt
+  // out one at a time between them (scheduling fences keep the order), so each memory instruction
+  // issues in the shadow of a matrix instruction instead of in a clump that drains the pipe.  The
+  // fragments of sub-step 1 are read during sub-step 0, those of the next k-step (after the
+  // barrier that publishes its tile) during sub-step 1.
+  auto load_one = [&](uint16_t* stage, int k0, int i) {
+    __builtin_amdgcn_global_load_lds(RLHF_GLOBAL_PTR(gbase + goff[i] + RLHF_ABL_K(k0)),
+                                     RLHF_LDS_PTR(stage + (16 * (8 * wave + i)) * DK), 16, 0, 0);
+  };
+  auto frag_one = [&](const uint16_t* ls, int ch, int q, f16x8_t* fa, f16x8_t* fw) {
+    if (q < MT) fa[q] = *(const f16x8_t*)(ls + a_off + q * 32 * DK + ch);
+    else fw[q - MT] = *(const f16x8_t*)(ls + w_off + (q - MT) * 32 * DK + ch);
+  };
+#define RLHF_STEP(CUR, NEXT, LOAD, KT)                                                        \
+  {                                                                                           \
+    const int kload = min((KT) + NS - 1, nk - 1) * DK;                                        \
+    _Pragma("unroll") for (int n = 0; n < 16; ++n) {                                          \
+      acc[n >> 2][n & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw0[n >> 2], fa0[n & 3],    \
+                                                                  acc[n >> 2][n & 3], 0, 0, 0); \
+      __builtin_amdgcn_sched_barrier(0);                                                      \
+      if (n < 8) frag_one(CUR, ch1, n, fa1, fw1);                                             \
+      else load_one(LOAD, kload, n - 8);                                                      \
+      __builtin_amdgcn_sched_barrier(0);                                                      \
+    }                                                                                         \
+    RLHF_WAIT_BARRIER()                                                                       \
+    _Pragma("unroll") for (int n = 0; n < 16; ++n) {                                          \
+      acc[n >> 2][n & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw1[n >> 2], fa1[n & 3],    \
+                                                                  acc[n >> 2][n & 3], 0, 0, 0); \
+      __builtin_amdgcn_sched_barrier(0);                                                      \
+      if (n < 8) frag_one(NEXT, ch0, n, fa0, fw0);                                            \
+      __builtin_amdgcn_sched_barrier(0);                                                      \
+    }                                                                                         \
+  }
 
-  // K is a multiple of 4*DK here (the launcher routes other shapes to the staged kernel), so the
-  // loop is branch-free: past the end the final tile is re-issued into a stage nobody reads.
+  // K is a multiple of NS*DK here (the launcher picks NS, or the staged kernel), so the loop is
+  // branch-free: past the end the final tile is re-issued into a stage nobody reads.  NS-1 tiles
+  // are in flight while one is consumed; what the loop sustains is set by bytes in flight over
+  // the loaded L2 latency, hence five stages (the whole LDS) when K allows.
   const int nk = K / DK;
   issue_loads(lds0, 0);
   issue_loads(lds1, min(1, nk - 1) * DK);
   issue_loads(lds2, min(2, nk - 1) * DK);
+  if (NS == 5) issue_loads(lds3, min(3, nk - 1) * DK);
   RLHF_WAIT_BARRIER()
   frags(lds0, ch0, fa0, fw0);
-  for (int kt = 0; kt < nk; kt += 4) {
-    RLHF_STEP(lds0, lds1, lds3, kt)
-    RLHF_STEP(lds1, lds2, lds0, kt + 1)
-    RLHF_STEP(lds2, lds3, lds1, kt + 2)
-    RLHF_STEP(lds3, lds0, lds2, kt + 3)
+  if (NS == 5) {
+    for (int kt = 0; kt < nk; kt += 5) {
+      RLHF_STEP(lds0, lds1, lds4, kt)
+      RLHF_STEP(lds1, lds2, lds0, kt + 1)
+      RLHF_STEP(lds2, lds3, lds1, kt + 2)
+      RLHF_STEP(lds3, lds4, lds2, kt + 3)
+      RLHF_STEP(lds4, lds0, lds3, kt + 4)
+    }
+  } else {
+    for (int kt = 0; kt < nk; kt += 4) {
+      RLHF_STEP(lds0, lds1, lds3, kt)
+      RLHF_STEP(lds1, lds2, lds0, kt + 1)
+      RLHF_STEP(lds2, lds3, lds1, kt + 2)
+      RLHF_STEP(lds3, lds0, lds2, kt + 3)
+    }
   }
 #undef RLHF_STEP
 #undef RLHF_WAIT_BARRIER
@@ -544,9 +577,14 @@ template <int EPI>
 static void launch_f16_dma(const GemmArgs& a, hipStream_t s) {
   const int nb_m = (a.M_max + 255) / 256, nb_n = (a.N + 255) / 256;
   const int per_xcd = (nb_m * nb_n + 7) / 8;
-  hipLaunchKernelGGL(gemm_f16_dma_kernel<EPI>, dim3(per_xcd * 8), dim3(256), 0, s, (const half_t*)a.A,
-                     (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
-                     nb_m, nb_n);
+  if (a.K % (5 * DK) == 0)
+    hipLaunchKernelGGL((gemm_f16_dma_kernel<EPI, 5>), dim3(per_xcd * 8), dim3(256), 0, s, (const half_t*)a.A,
+                       (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
+                       nb_m, nb_n);
+  else
+    hipLaunchKernelGGL((gemm_f16_dma_kernel<EPI, 4>), dim3(per_xcd * 8), dim3(256), 0, s, (const half_t*)a.A,
+                       (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
+                       nb_m, nb_n);
 }
 
 #ifndef RLHF_GEMM_DMA
@@ -623,7 +661,7 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
     }
     if (a.M_max <= 512)
       launch_f16<EPI, 2, 1, RLHF_DEC_PF, RLHF_DEC_OCC>(a, s, a.out, 1);
-    else if (RLHF_GEMM_DMA && (a.K % (4 * DK)) == 0 && (a.N % 8) == 0 && (a.ldo % 8) == 0 && (size_t)std::max(a.M_max, a.N) * a.K < (1ull << 32))
+    else if (RLHF_GEMM_DMA && ((a.K % (4 * DK)) == 0 || (a.K % (5 * DK)) == 0) && (a.N % 8) == 0 && (a.ldo % 8) == 0 && (size_t)std::max(a.M_max, a.N) * a.K < (1ull << 32))
       launch_f16_dma<EPI>(a, s);
     else
       launch_f16<EPI, RLHF_GEMM_MT, RLHF_GEMM_NT, RLHF_GEMM_PF, RLHF_GEMM_OCC>(a, s, a.out, 1);

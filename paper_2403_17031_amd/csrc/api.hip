@@ -222,47 +222,85 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
   const rlhf_model_config& c = h->cfg;
   const int d = c.d_model, dt = c.dtype;
   const size_t plane = p.kv_slots * (size_t)d * h->esz;  // bytes of one K (or V) plane of one layer
+
+  GemmArgs base;
+  base.M_max = p.rows_max;
+  base.M_dev = p.rows_dev;
+  if (p.mode == 1) {
+    base.splitk_ws = A.splitk;
+    base.splitk_ws_bytes = A.splitk_bytes;
+  }
+  auto gemm_args = [&](const void* in, const void* w, const void* bias, void* out, int N, int K, int epi) {
+    GemmArgs g = base;
+    g.A = in; g.W = w; g.bias = bias; g.out = out; g.N = N; g.K = K; g.ldo = N; g.epilogue = epi;
+    return g;
+  };
+
+  // Decode with every product on the split-K path: the reductions of the partial sums are folded
+  // into the kernels that consume them (QKV into the rotary kernel; out-projection and FC2 into the
+  // next layer's LayerNorm), which takes four short kernels per layer off the critical path.
+  int ks_qkv = 1, ks_o = 1, ks_2 = 1;
+  if (p.mode == 1) {
+    ks_qkv = gemm_splitk_factor(dt, gemm_args(A.a, nullptr, nullptr, A.qkv, 3 * d, d, EPI_BIAS));
+    ks_o = gemm_splitk_factor(dt, gemm_args(A.att, nullptr, nullptr, A.x, d, d, EPI_BIAS_RESADD));
+    ks_2 = gemm_splitk_factor(dt, gemm_args(A.ffn, nullptr, nullptr, A.x, d, c.d_ff, EPI_BIAS_RESADD));
+  }
+  const bool fold = p.mode == 1 && ks_qkv > 1 && ks_o > 1 && ks_2 > 1 &&
+                    rope_kv_splitk_supported(dt, c.n_heads, c.head_dim, c.rotary_dims) &&
+                    layernorm_pending_supported(dt, p.rows_max, d);
+  // Decode: the MLP branch (weights streaming through the matrix cores) overlaps the attention
+  // branch (K/V streaming from HBM).  Needs FC2 on the split-K path, so that only its final
+  // reduction touches the residual stream; not used while per-kernel profiling is on.
+  const bool fork_mlp = p.mode == 1 && !h->prof_on && ks_2 > 1;
+  const size_t slab = (size_t)p.rows_max * d;
+  bool pending = false;  // out-projection and FC2 partial sums of the previous layer not yet in x
+
   for (int l = 0; l < c.n_layers; ++l) {
     char* kc = p.kv + (p.kv_per_layer ? (size_t)l * 2 * plane : 0);
     char* vc = kc + plane;
-    LAUNCH(p.mode ? "layernorm_decode" : "layernorm", launch_layernorm(dt, A.x, p.rows_max, p.rows_dev, d, c.ln_eps, h->ln1_g[l], h->ln1_b[l],
-                                         A.a, h->ln2_g[l], h->ln2_b[l], A.m, s));
-    GemmArgs g;
-    g.M_max = p.rows_max;
-    g.M_dev = p.rows_dev;
-    if (p.mode == 1) {
-      g.splitk_ws = A.splitk;
-      g.splitk_ws_bytes = A.splitk_bytes;
+    if (pending) {
+      PendingResidual pr;
+      pr.part_a = (const float*)A.splitk; pr.ks_a = ks_o; pr.bias_a = h->b_o[l - 1];
+      pr.part_b = (const float*)A.splitk2; pr.ks_b = ks_2; pr.bias_b = h->b_fc2[l - 1];
+      pr.slab = slab;
+      LAUNCH("layernorm_decode", launch_layernorm_pending(A.x, p.rows_max, p.rows_dev, d, c.ln_eps, h->ln1_g[l], h->ln1_b[l],
+                                                          A.a, h->ln2_g[l], h->ln2_b[l], A.m, pr, s));
+      pending = false;
+    } else {
+      LAUNCH(p.mode ? "layernorm_decode" : "layernorm", launch_layernorm(dt, A.x, p.rows_max, p.rows_dev, d, c.ln_eps, h->ln1_g[l], h->ln1_b[l],
+                                           A.a, h->ln2_g[l], h->ln2_b[l], A.m, s));
     }
-    // Decode: the MLP branch (weights streaming through the matrix cores) overlaps the attention
-    // branch (K/V streaming from HBM).  Needs FC2 on the split-K path, so that only its final
-    // reduction touches the residual stream; not used while per-kernel profiling is on.
-    bool fork_mlp = false;
+    GemmArgs g = gemm_args(A.a, h->w_qkv[l], h->b_qkv[l], A.qkv, 3 * d, d, EPI_BIAS);
+    if (fold) {
+      g.phase = 1;
+      LAUNCH("gemm_decode", launch_gemm(dt, g, s));
+      LAUNCH("rope_kv_decode", launch_rope_kv_splitk((const float*)A.splitk, ks_qkv, (size_t)p.rows_max * 3 * d, h->b_qkv[l],
+                                                     p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff, p.len,
+                                                     c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q,
+                                                     kc, vc, (long)p.kv_extra, s));
+    } else {
+      LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
+      LAUNCH(p.mode ? "rope_kv_decode" : "rope_kv", launch_rope_kv(dt, A.qkv, p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff,
+                                       p.len, c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q, kc, vc,
+                                       (long)p.kv_extra, s));
+    }
+    GemmArgs go = gemm_args(A.att, h->w_o[l], h->b_o[l], A.x, d, d, EPI_BIAS_RESADD);
+    GemmArgs g1 = gemm_args(A.m, h->w_fc1[l], h->b_fc1[l], A.ffn, c.d_ff, d, EPI_BIAS_GELU);
+    GemmArgs g2 = gemm_args(A.ffn, h->w_fc2[l], h->b_fc2[l], A.x, d, c.d_ff, EPI_BIAS_RESADD);
+    if (p.mode == 1) {  // the MLP branch has partial-sum scratch of its own
+      g1.splitk_ws = A.splitk2;
+      g2.splitk_ws = A.splitk2;
+    }
     hipEvent_t join = nullptr;
-    if (p.mode == 1 && !h->prof_on) {
-      GemmArgs t = g;
-      t.splitk_ws = A.splitk2; t.N = d; t.K = c.d_ff; t.ldo = d;
-      fork_mlp = gemm_splitk_factor(dt, t) > 1;
-    }
-    g.A = A.a; g.W = h->w_qkv[l]; g.bias = h->b_qkv[l]; g.out = A.qkv; g.N = 3 * d; g.K = d; g.ldo = 3 * d;
-    g.epilogue = EPI_BIAS;
-    LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
-    LAUNCH(p.mode ? "rope_kv_decode" : "rope_kv", launch_rope_kv(dt, A.qkv, p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff,
-                                     p.len, c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q, kc, vc,
-                                     (long)p.kv_extra, s));
     if (fork_mlp) {
       hipEvent_t fork = h->fork_ev[h->ev_rr & 7];
       join = h->join_ev[h->ev_rr & 7];
       ++h->ev_rr;
       HIP_OK(hipEventRecord(fork, s));
       HIP_OK(hipStreamWaitEvent(h->side, fork, 0));
-      GemmArgs m1 = g, m2 = g;
-      m1.splitk_ws = A.splitk2; m2.splitk_ws = A.splitk2;
-      m1.A = A.m; m1.W = h->w_fc1[l]; m1.bias = h->b_fc1[l]; m1.out = A.ffn; m1.N = c.d_ff; m1.K = d;
-      m1.ldo = c.d_ff; m1.epilogue = EPI_BIAS_GELU;
-      m2.A = A.ffn; m2.W = h->w_fc2[l]; m2.bias = h->b_fc2[l]; m2.out = A.x; m2.N = d; m2.K = c.d_ff; m2.ldo = d;
-      m2.epilogue = EPI_BIAS_RESADD; m2.phase = 1;
-      hipError_t e1 = launch_gemm(dt, m1, h->side);
+      GemmArgs m2 = g2;
+      m2.phase = 1;
+      hipError_t e1 = launch_gemm(dt, g1, h->side);
       if (e1 == hipSuccess) e1 = launch_gemm(dt, m2, h->side);
       if (e1 != hipSuccess) return fail(RLHF_EHIP, std::string("gemm_decode (side stream): ") + hipGetErrorString(e1));
       HIP_OK(hipEventRecord(join, h->side));
@@ -273,26 +311,27 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
     else
       LAUNCH("attn_decode", launch_attn_decode(dt, A.q, kc, vc, (long)p.kv_extra, p.B, p.len, p.ctx_add, p.ctx_max,
                                                p.kvoff, c.n_heads, c.head_dim, A.att, s));
-    GemmArgs go = g, g1 = g, g2 = g;
-    go.A = A.att; go.W = h->w_o[l]; go.bias = h->b_o[l]; go.out = A.x; go.N = d; go.K = d; go.ldo = d;
-    go.epilogue = EPI_BIAS_RESADD;
-    g1.A = A.m; g1.W = h->w_fc1[l]; g1.bias = h->b_fc1[l]; g1.out = A.ffn; g1.N = c.d_ff; g1.K = d; g1.ldo = c.d_ff;
-    g1.epilogue = EPI_BIAS_GELU;
-    g2.A = A.ffn; g2.W = h->w_fc2[l]; g2.bias = h->b_fc2[l]; g2.out = A.x; g2.N = d; g2.K = c.d_ff; g2.ldo = d;
-    g2.epilogue = EPI_BIAS_RESADD;
+    // From here on the order of the additions into x is the serial one: x = (x + attn) + mlp.
+    const bool defer = fold && l + 1 < c.n_layers;  // the next layer's LayerNorm adds both products
+    if (fold) go.phase = 1;
+    LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, go, s));
     if (fork_mlp) {
-      // MLP branch: FC1 and the partial sums of FC2 were enqueued on the side stream next to the
-      // attention kernel (forked after the rotary kernel); only FC2's reduction, which adds into the
-      // residual stream, waits here, so the order x = (x + attn) + mlp is the serial one.
-      LAUNCH("gemm_decode", launch_gemm(dt, go, s));
       HIP_OK(hipStreamWaitEvent(s, join, 0));
-      g2.splitk_ws = A.splitk2;
+    } else {
+      LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g1, s));
+      if (fold) g2.phase = 1;
+      LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g2, s));
+    }
+    if (defer) {
+      pending = true;
+    } else if (fold) {
+      go.phase = 2;
+      g2.phase = 2;
+      LAUNCH("gemm_decode", launch_gemm(dt, go, s));
+      LAUNCH("gemm_decode", launch_gemm(dt, g2, s));
+    } else if (fork_mlp) {
       g2.phase = 2;
       LAUNCH("gemm_decode", launch_gemm(dt, g2, s));
-    } else {
-      LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, go, s));
-      LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g1, s));
-      LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g2, s));
     }
   }
   return RLHF_OK;

@@ -113,6 +113,21 @@ hipError_t launch_embed_rows(int dtype, const int32_t* tok, int B, const void* e
 hipError_t launch_layernorm(int dtype, const float* x, int rows_max, const int* rows_dev, int d, float eps,
                             const void* g1, const void* b1, void* out1, const void* g2, const void* b2,
                             void* out2, hipStream_t s);
+// Two split-K products (fp32 partial slabs of `slab` floats each, row-major [rows, d]) whose reduction
+// into the residual stream is still pending: x <- (x + (sum_z A_z + bias_a)) + (sum_z B_z + bias_b).
+struct PendingResidual {
+  const float* part_a = nullptr;
+  const float* part_b = nullptr;
+  const void* bias_a = nullptr;  // bf16 [d]
+  const void* bias_b = nullptr;
+  int ks_a = 0, ks_b = 0;
+  size_t slab = 0;
+};
+bool layernorm_pending_supported(int dtype, int rows_max, int d);
+// LayerNorm as above, after folding the pending products into x (written back in place).
+hipError_t launch_layernorm_pending(float* x, int rows_max, const int* rows_dev, int d, float eps, const void* g1,
+                                    const void* b1, void* out1, const void* g2, const void* b2, void* out2,
+                                    const PendingResidual& pend, hipStream_t s);
 // Final LayerNorm of selected rows: row r reads x[src[r]] (src may be null: identity), optionally
 // also the value head val[r] = w_v . h + b_v.
 hipError_t launch_final_ln(int dtype, const float* x, const int* src, int src_add, int rows_max,
@@ -129,6 +144,14 @@ hipError_t launch_rope_kv(int dtype, const void* qkv, int rows_max, const int* r
                           int pos_add, const int* rowid, const int* kvoff, const int* len, int H, int hd, int r,
                           const float* cos_t, const float* sin_t, void* q, void* kc, void* vc,
                           long kv_extra, hipStream_t s);
+
+// Same, one row per sequence, with the qkv row formed from the fp32 partial slabs of a split-K
+// product (`slab` floats each, row-major [rows, 3*H*hd]) plus bias instead of being read.
+bool rope_kv_splitk_supported(int dtype, int H, int hd, int r);
+hipError_t launch_rope_kv_splitk(const float* part, int ksplit, size_t slab, const void* bias, int rows_max,
+                                 const int* rows_dev, const int* pos, int pos_add, const int* rowid,
+                                 const int* kvoff, const int* len, int H, int hd, int r, const float* cos_t,
+                                 const float* sin_t, void* q, void* kc, void* vc, long kv_extra, hipStream_t s);
 
 // Causal attention over packed sequences (prefill / scoring).  q [T, H*hd]; kc/vc [H][*][hd] with
 // sequence b's keys at slots kvoff[b] .. kvoff[b]+len[b]; out [T, H*hd].

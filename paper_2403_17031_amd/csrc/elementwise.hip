@@ -173,13 +173,39 @@ __device__ __forceinline__ f32x4_t bf16x4_to_f32(u32x2_t v) {
   return r;
 }
 
+// Sum of ks fp32 partial slabs at one float4 position, added in slab order.  The usual split factors
+// are unrolled completely so that all loads are in flight before the chain of additions starts.
+template <int KS>
+__device__ __forceinline__ f32x4_t sum_slabs_n(const f32x4_t* __restrict__ p, size_t slab4) {
+  f32x4_t v[KS];
+#pragma unroll
+  for (int z = 0; z < KS; ++z) v[z] = p[z * slab4];
+  f32x4_t t = v[0];
+#pragma unroll
+  for (int z = 1; z < KS; ++z) t += v[z];
+  return t;
+}
+__device__ __forceinline__ f32x4_t sum_slabs(const f32x4_t* __restrict__ p, size_t slab4, int ks) {
+  switch (ks) {
+    case 2: return sum_slabs_n<2>(p, slab4);
+    case 4: return sum_slabs_n<4>(p, slab4);
+    case 8: return sum_slabs_n<8>(p, slab4);
+    case 16: return sum_slabs_n<16>(p, slab4);
+    default: break;
+  }
+  f32x4_t t = p[0];
+  for (int z = 1; z < ks; ++z) t += p[z * slab4];
+  return t;
+}
+
 // One block per row (few rows: decode).
 __global__ void __launch_bounds__(256)
-    layernorm_vec_block_kernel(const float* __restrict__ x, const int* __restrict__ src, int src_add,
+    layernorm_vec_block_kernel(const float* x, const int* __restrict__ src, int src_add,
                          const int* __restrict__ rows_dev, int d, float eps, const bf16_t* __restrict__ g1,
                          const bf16_t* __restrict__ b1, half_t* __restrict__ out1, const bf16_t* __restrict__ g2,
                          const bf16_t* __restrict__ b2, half_t* __restrict__ out2,
-                         const bf16_t* __restrict__ value_w, float value_b, float* __restrict__ val) {
+                         const bf16_t* __restrict__ value_w, float value_b, float* __restrict__ val,
+                         PendingResidual pend, float* xw) {
   __shared__ float sh[4];
   const int r = blockIdx.x;
   if (rows_dev && r >= *rows_dev) return;
@@ -193,6 +219,17 @@ __global__ void __launch_bounds__(256)
     const int c = threadIdx.x + 256 * i;
     if (c < nv) {
       v[i] = xr[c];
+      if (xw) {
+        // two split-K products whose reduction was left to this kernel: x <- (x + (sum_z A_z + bias_a))
+        // + (sum_z B_z + bias_b), slabs in index order, the order of the stand-alone reduction
+        const size_t o = (size_t)r * nv + c;
+        const size_t slab4 = pend.slab >> 2;
+        const f32x4_t ta = sum_slabs((const f32x4_t*)pend.part_a + o, slab4, pend.ks_a);
+        const f32x4_t tb = sum_slabs((const f32x4_t*)pend.part_b + o, slab4, pend.ks_b);
+        v[i] += ta + bf16x4_to_f32(((const u32x2_t*)pend.bias_a)[c]);
+        v[i] += tb + bf16x4_to_f32(((const u32x2_t*)pend.bias_b)[c]);
+        ((f32x4_t*)(xw + (size_t)r * d))[c] = v[i];
+      }
       s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
     }
   }
@@ -312,7 +349,8 @@ static hipError_t ln_launch(const float* x, const int* src, int src_add, int row
     if (rows_max <= 2048)
       hipLaunchKernelGGL(layernorm_vec_block_kernel, dim3(rows_max), dim3(256), 0, s, x, src, src_add, rows_dev, d,
                          eps, (const bf16_t*)g1, (const bf16_t*)b1, (half_t*)out1, (const bf16_t*)g2,
-                         (const bf16_t*)b2, (half_t*)out2, (const bf16_t*)vw, vb, val);
+                         (const bf16_t*)b2, (half_t*)out2, (const bf16_t*)vw, vb, val, PendingResidual{},
+                         (float*)nullptr);
     else if (d <= 1024)
       hipLaunchKernelGGL(layernorm_vec_kernel<4>, grid, dim3(256), 0, s, x, src, src_add, rows_max, rows_dev, d,
                          eps, (const bf16_t*)g1, (const bf16_t*)b1, (half_t*)out1, (const bf16_t*)g2,
@@ -337,6 +375,20 @@ hipError_t launch_layernorm(int dtype, const float* x, int rows_max, const int* 
                             nullptr, s);
   return ln_launch<ModeBF16>(x, nullptr, 0, rows_max, rows_dev, d, eps, g1, b1, out1, g2, b2, out2, nullptr, 0.f,
                            nullptr, s);
+}
+
+bool layernorm_pending_supported(int dtype, int rows_max, int d) {
+  return dtype == 1 && (d & 3) == 0 && d <= 4096 && rows_max <= 2048;
+}
+
+hipError_t launch_layernorm_pending(float* x, int rows_max, const int* rows_dev, int d, float eps, const void* g1,
+                                    const void* b1, void* out1, const void* g2, const void* b2, void* out2,
+                                    const PendingResidual& pend, hipStream_t s) {
+  if (!layernorm_pending_supported(1, rows_max, d) || (pend.slab & 3) != 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(layernorm_vec_block_kernel, dim3(rows_max), dim3(256), 0, s, x, (const int*)nullptr, 0,
+                     rows_dev, d, eps, (const bf16_t*)g1, (const bf16_t*)b1, (half_t*)out1, (const bf16_t*)g2,
+                     (const bf16_t*)b2, (half_t*)out2, (const bf16_t*)nullptr, 0.f, (float*)nullptr, pend, x);
+  return hipGetLastError();
 }
 
 hipError_t launch_final_ln(int dtype, const float* x, const int* src, int src_add, int rows_max,
@@ -506,6 +558,76 @@ hipError_t launch_rope_kv(int dtype, const void* qkv, int rows_max, const int* r
     hipLaunchKernelGGL(rope_kv_kernel<half_t>, dim3(rows_max), dim3(256), 0, s, (const half_t*)qkv, rows_dev,
                        pos, pos_add, rowid, kvoff, len, H, hd, r, cos_t, sin_t, (half_t*)q, (half_t*)kc, (half_t*)vc,
                        kv_extra);
+  return hipGetLastError();
+}
+
+// Decode form fed by a split-K product: block (t, g) owns HPB heads of row t.  The q, k and v slices
+// of those heads are formed from the fp32 partial slabs (added in slab order) plus the bias and
+// rounded to fp16 exactly as the stand-alone reduction would have stored them; the rotary pairs
+// are then turned in LDS and the slices copied out in 16-byte chunks.
+template <int HPB>
+__global__ void __launch_bounds__(256)
+    rope_kv_splitk_kernel(const float* __restrict__ part, int ksplit, size_t slab, const bf16_t* __restrict__ bias,
+                          const int* __restrict__ rows_dev, const int* __restrict__ pos, int pos_add,
+                          const int* __restrict__ rowid, const int* __restrict__ kvoff, const int* __restrict__ len,
+                          int H, int hd, int r, const float* __restrict__ cos_t, const float* __restrict__ sin_t,
+                          half_t* __restrict__ q, half_t* __restrict__ kc, half_t* __restrict__ vc, long kv_extra) {
+  __shared__ __attribute__((aligned(16))) half_t s_row[3 * HPB * 256];
+  const int t = blockIdx.x, h0 = blockIdx.y * HPB;
+  if (rows_dev && t >= *rows_dev) return;
+  const int d = H * hd, q4 = hd >> 2, half = r >> 1;
+  const size_t rb = ((size_t)t * 3 * d) >> 2, slab4 = slab >> 2;
+  for (int c = threadIdx.x; c < 3 * HPB * q4; c += 256) {
+    const int u = c / q4, j = c - u * q4;          // unit u = sec * HPB + local head
+    const int sec = u / HPB, hl = u - sec * HPB;
+    const int col4 = (sec * d + (h0 + hl) * hd) / 4 + j;
+    f32x4_t v = sum_slabs((const f32x4_t*)part + rb + col4, slab4, ksplit);
+    v += bf16x4_to_f32(((const u32x2_t*)bias)[col4]);
+    f16x4_t o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = from_f32<half_t>(v[e]);
+    ((f16x4_t*)s_row)[u * q4 + j] = o;
+  }
+  __syncthreads();
+  const int p = pos[t] + pos_add;
+  for (int c = threadIdx.x; c < 2 * HPB * half; c += 256) {  // q and k units only
+    const int u = c / half, i = c - u * half;
+    half_t* hb = s_row + u * hd;
+    const float co = cos_t[(size_t)p * half + i], si = sin_t[(size_t)p * half + i];
+    const float lo = (float)hb[i], hi = (float)hb[i + half];
+    hb[i] = from_f32<half_t>(lo * co - hi * si);
+    hb[i + half] = from_f32<half_t>(hi * co + lo * si);
+  }
+  __syncthreads();
+  const int b = rowid ? rowid[t] : t;
+  const long slot0 = (long)kvoff[b] * H + p, seq_len = len[b] + kv_extra;
+  const int cph = hd >> 3;
+  for (int c = threadIdx.x; c < 3 * HPB * cph; c += 256) {
+    const int u = c / cph, ch = c - u * cph;
+    const int sec = u / HPB, h = h0 + (u - sec * HPB);
+    half_t* dst = sec == 0 ? q + (size_t)t * d + h * hd : (sec == 1 ? kc : vc) + (size_t)(slot0 + h * seq_len) * hd;
+    *(f16x8_t*)(dst + 8 * ch) = *(const f16x8_t*)(s_row + u * hd + 8 * ch);
+  }
+}
+
+bool rope_kv_splitk_supported(int dtype, int H, int hd, int r) {
+  return dtype == 1 && (hd & 7) == 0 && hd <= 256 && (r & 1) == 0 && r <= hd && ((3 * H * hd) & 3) == 0;
+}
+
+hipError_t launch_rope_kv_splitk(const float* part, int ksplit, size_t slab, const void* bias, int rows_max,
+                                 const int* rows_dev, const int* pos, int pos_add, const int* rowid,
+                                 const int* kvoff, const int* len, int H, int hd, int r, const float* cos_t,
+                                 const float* sin_t, void* q, void* kc, void* vc, long kv_extra, hipStream_t s) {
+  if (rows_max <= 0) return hipSuccess;
+  if (!rope_kv_splitk_supported(1, H, hd, r) || (slab & 3) != 0 || ksplit < 1) return hipErrorInvalidValue;
+  if ((H & 3) == 0)
+    hipLaunchKernelGGL(rope_kv_splitk_kernel<4>, dim3(rows_max, H / 4), dim3(256), 0, s, part, ksplit, slab,
+                       (const bf16_t*)bias, rows_dev, pos, pos_add, rowid, kvoff, len, H, hd, r, cos_t, sin_t,
+                       (half_t*)q, (half_t*)kc, (half_t*)vc, kv_extra);
+  else
+    hipLaunchKernelGGL(rope_kv_splitk_kernel<1>, dim3(rows_max, H), dim3(256), 0, s, part, ksplit, slab,
+                       (const bf16_t*)bias, rows_dev, pos, pos_add, rowid, kvoff, len, H, hd, r, cos_t, sin_t,
+                       (half_t*)q, (half_t*)kc, (half_t*)vc, kv_extra);
   return hipGetLastError();
 }
 

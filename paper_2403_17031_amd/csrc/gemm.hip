@@ -633,8 +633,13 @@ int gemm_splitk_factor(int dtype, const GemmArgs& a) {
   if (dtype != 1 || a.M_max > 512 || !a.splitk_ws || (a.ldo & 3) != 0) return 1;
   const int tiles = ((a.M_max + 127) / 128) * ((a.N + 63) / 64);
   const int nk = (a.K + TK - 1) / TK;
+  // Measured on the decode layer of the 2.8B shape (batch 256, next to the attention kernel of the
+  // same layer): a product whose tiles already cover the 256 CUs is fastest unsplit; otherwise K is
+  // split while that leaves at least 16 k-steps per block and at most 640 blocks -- beyond that the
+  // fp32 partial sums (written, then read by the reduction) outweigh the extra parallelism.
+  if (tiles >= 256) return 1;
   int ksplit = 1;
-  while (ksplit < 16 && tiles * ksplit < 1024 && nk / (ksplit * 2) >= 4) ksplit *= 2;
+  while (ksplit < 16 && tiles * ksplit * 2 <= 640 && nk / (ksplit * 2) >= 16) ksplit *= 2;
   if ((size_t)ksplit * a.M_max * a.ldo * sizeof(float) > a.splitk_ws_bytes) return 1;
   return ksplit;
 }

@@ -536,6 +536,92 @@ static bool launch_rope_vec(int r, dim3 grid, hipStream_t s, const half_t* qkv, 
 #undef RLHF_ROPE_CASE
 }
 
+// Many-rows form (prefill, scoring): block (RPB consecutive packed rows) x (HPB heads).  The q, k and v
+// slices of those heads are loaded into LDS as RPB*3 contiguous segments of HPB*HD halfs, the rotary
+// pairs are turned there, and the result leaves in 16-byte chunks: q as one contiguous segment per
+// row, K and V as HD-long rows of which the RPB rows of one head are adjacent in a sequence's slab.
+// All index arithmetic divides by compile-time constants.
+template <int HD, int R, int HPB, int RPB>
+__global__ void __launch_bounds__(256)
+    rope_kv_tile_kernel(const half_t* __restrict__ qkv, int rows_max, const int* __restrict__ rows_dev,
+                        const int* __restrict__ pos, int pos_add, const int* __restrict__ rowid,
+                        const int* __restrict__ kvoff, const int* __restrict__ len, int H,
+                        const float* __restrict__ cos_t, const float* __restrict__ sin_t, half_t* __restrict__ q,
+                        half_t* __restrict__ kc, half_t* __restrict__ vc, long kv_extra) {
+  constexpr int SEG = HPB * HD, SEGC = SEG / 8, CPH = HD / 8, HALF = R / 2;
+  __shared__ __attribute__((aligned(16))) half_t tile[RPB * 3 * SEG];
+  __shared__ int s_pos[RPB];
+  __shared__ long s_base[RPB], s_len[RPB];
+  const int t0 = blockIdx.x * RPB, h0 = blockIdx.y * HPB;
+  const int rows = min(rows_dev ? *rows_dev : rows_max, rows_max);
+  if (t0 >= rows) return;
+  const int nr = min(RPB, rows - t0);
+  const int d = H * HD;
+  if (threadIdx.x < nr) {
+    const int t = t0 + threadIdx.x;
+    const int p = pos[t] + pos_add;
+    const int b = rowid ? rowid[t] : t;
+    s_pos[threadIdx.x] = p;
+    s_len[threadIdx.x] = len[b] + kv_extra;
+    s_base[threadIdx.x] = (long)kvoff[b] * H + p;
+  }
+  for (int c = threadIdx.x; c < nr * 3 * SEGC; c += 256) {
+    const int rs = c / SEGC, ch = c - rs * SEGC;  // rs = row * 3 + section
+    const int rr = rs / 3, sec = rs - rr * 3;
+    *(f16x8_t*)(tile + rs * SEG + 8 * ch) =
+        *(const f16x8_t*)(qkv + (size_t)(t0 + rr) * 3 * d + sec * d + h0 * HD + 8 * ch);
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < nr * 2 * HPB * HALF; c += 256) {
+    const int u = c / HALF, i = c - u * HALF;     // u = (row * 2 + section) * HPB + head
+    const int rs2 = u / HPB, hl = u - rs2 * HPB;
+    const int rr = rs2 >> 1, sec = rs2 & 1;
+    half_t* hb = tile + (rr * 3 + sec) * SEG + hl * HD;
+    const float co = cos_t[(size_t)s_pos[rr] * HALF + i], si = sin_t[(size_t)s_pos[rr] * HALF + i];
+    const float lo = (float)hb[i], hi = (float)hb[i + HALF];
+    hb[i] = from_f32<half_t>(lo * co - hi * si);
+    hb[i + HALF] = from_f32<half_t>(hi * co + lo * si);
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < nr * SEGC; c += 256) {  // q
+    const int rr = c / SEGC, ch = c - rr * SEGC;
+    *(f16x8_t*)(q + (size_t)(t0 + rr) * d + h0 * HD + 8 * ch) = *(const f16x8_t*)(tile + rr * 3 * SEG + 8 * ch);
+  }
+  for (int c = threadIdx.x; c < 2 * HPB * nr * CPH; c += 256) {  // k, v: chunk, then row, then head, then section
+    const int w = c / CPH, ch = c - w * CPH;
+    const int sh = w / nr, rr = w - sh * nr;
+    const int sec = 1 + sh / HPB, hl = sh - (sec - 1) * HPB;
+    half_t* dst = (sec == 1 ? kc : vc) + (size_t)(s_base[rr] + (h0 + hl) * s_len[rr]) * HD + 8 * ch;
+    *(f16x8_t*)dst = *(const f16x8_t*)(tile + (rr * 3 + sec) * SEG + hl * HD + 8 * ch);
+  }
+}
+
+template <int HD, int R, int HPB>
+static void launch_rope_tile(hipStream_t s, const half_t* qkv, int rows_max, const int* rows_dev, const int* pos,
+                             int pos_add, const int* rowid, const int* kvoff, const int* len, int H,
+                             const float* cos_t, const float* sin_t, half_t* q, half_t* kc, half_t* vc,
+                             long kv_extra) {
+  hipLaunchKernelGGL((rope_kv_tile_kernel<HD, R, HPB, 8>), dim3((rows_max + 7) / 8, H / HPB), dim3(256), 0, s, qkv,
+                     rows_max, rows_dev, pos, pos_add, rowid, kvoff, len, H, cos_t, sin_t, q, kc, vc, kv_extra);
+}
+
+// The head shapes of the model family (rotary on a quarter of the head); other shapes take the
+// general kernels.
+static bool try_rope_tile(hipStream_t s, const half_t* qkv, int rows_max, const int* rows_dev, const int* pos,
+                          int pos_add, const int* rowid, const int* kvoff, const int* len, int H, int hd, int r,
+                          const float* cos_t, const float* sin_t, half_t* q, half_t* kc, half_t* vc,
+                          long kv_extra) {
+#define RLHF_TILE(HD_, R_, HPB_)                                                                              \
+  if (hd == HD_ && r == R_ && H % HPB_ == 0) {                                                                \
+    launch_rope_tile<HD_, R_, HPB_>(s, qkv, rows_max, rows_dev, pos, pos_add, rowid, kvoff, len, H, cos_t,    \
+                                    sin_t, q, kc, vc, kv_extra);                                              \
+    return true;                                                                                              \
+  }
+  RLHF_TILE(80, 20, 8) RLHF_TILE(128, 32, 8) RLHF_TILE(256, 64, 4) RLHF_TILE(64, 16, 4) RLHF_TILE(16, 4, 1)
+#undef RLHF_TILE
+  return false;
+}
+
 hipError_t launch_rope_kv(int dtype, const void* qkv, int rows_max, const int* rows_dev, const int* pos,
                           int pos_add, const int* rowid, const int* kvoff, const int* len, int H, int hd, int r,
                           const float* cos_t, const float* sin_t, void* q, void* kc, void* vc,
@@ -545,6 +631,10 @@ hipError_t launch_rope_kv(int dtype, const void* qkv, int rows_max, const int* r
     hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(rows_max), dim3(256), 0, s, (const float*)qkv, rows_dev, pos,
                        pos_add, rowid, kvoff, len, H, hd, r, cos_t, sin_t, (float*)q, (float*)kc, (float*)vc,
                        kv_extra);
+  else if (rows_max > 2048 &&
+           try_rope_tile(s, (const half_t*)qkv, rows_max, rows_dev, pos, pos_add, rowid, kvoff, len, H, hd, r, cos_t,
+                         sin_t, (half_t*)q, (half_t*)kc, (half_t*)vc, kv_extra)) {
+  }
   else if ((hd & 7) == 0 && r <= hd &&
            (rows_max > 2048
                 ? launch_rope_vec<8>(r, dim3((rows_max + 7) / 8), s, (const half_t*)qkv, rows_max, rows_dev, pos,

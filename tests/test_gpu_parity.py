@@ -150,6 +150,18 @@ def test_reduced_depth_of_each_benchmark_shape_bf16(gpu, shape):
     _check_rollout_and_scores(gpu, cfg, w, queries, mask, seed=idx, T=0.7, N=5)
 
 
+@pytest.mark.parametrize("shape", ["160m", "1b", "2.8b", "6.9b"])
+def test_reduced_depth_many_rows_bf16(gpu, shape):
+    """Same shapes with 16 sequences: more than 2048 packed rows, which is where the library switches
+    to its large-row-count kernels (direct-to-LDS GEMM, wave-per-row LayerNorm, tiled rotary kernel).
+    Three rows, first, middle and last, are graded against the oracle."""
+    idx = {"160m": 2, "1b": 3, "2.8b": 4, "6.9b": 5}[shape]
+    cfg = WORKLOADS[idx].model.with_(n_layers=2)
+    w = make_weights(cfg, 200 + idx)
+    queries, mask = _queries(cfg, B=16, Lq=150, lo=100, hi=150, seed=10 + idx)
+    _check_rollout_and_scores(gpu, cfg, w, queries, mask, seed=10 + idx, T=0.7, N=4, rows=[0, 7, 15])
+
+
 def test_scoring_random_responses_right_padded(gpu, tiny_cfg):
     """A scoring input that does not come from the sampler: random responses of random lengths, so
     rows have left pads, right pads, or both."""

@@ -123,6 +123,25 @@ def main():
     roof = rooflines.get(dom) or rooflines.get("gemm") or {}
     roof = dict(roof, kernel=dom if dom in rooflines else "gemm")
 
+    # The signals PPO consumes next (reward assembly, GAE, advantage whitening) on this step's outputs.
+    # Outside the headline metric.  Stand-ins: the policy's own rescoring outputs serve as the reference
+    # log-probs and the reward-model values (a second and third weight set would cost two more
+    # score_sequences calls of the time reported as score_ms).
+    toks_d, lps_d, _, _ = r
+    lp_d, val_d = s
+    Lq = wl.query_len
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    for i in range(reps + 2):
+        if i == 2:
+            e0.record()
+        rew, _, _, kept = P.ppo_assemble_rewards(lps_d, lp_d, val_d, toks_d, Lq, cfg.eos_id, cfg.pad_id, 0.05)
+        adv, ret = P.ppo_gae(rew, val_d, kept, 1.0, 0.95, value_offset=Lq - 1)
+        P.ppo_whiten(adv, kept)
+    e1.record()
+    torch.cuda.synchronize()
+    signals_ms = e0.elapsed_time(e1) / reps
+
     cpu = None
     if not a.no_cpu_baseline:
         cpu = cpu_baseline(cfg, w, queries, mask, wl, n_true)
@@ -147,6 +166,7 @@ def main():
         "rescoring_tok_s_padded": B * (wl.query_len + N) / (score_ms * 1e-3),
         "score_mfma_frac": wc["score_flops"] / (score_ms * 1e-3) / MFMA_PEAK,
         "roofline": roof, "rooflines": rooflines, "kernels_ms": kern, "profiled_step_ms": tot,
+        "ppo_signals_ms": signals_ms,
         "cpu_baseline": cpu, "setup_s": setup_s,
     }
     print(json.dumps(out))

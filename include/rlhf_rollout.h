@@ -113,6 +113,44 @@ int score_sequences(rlhf_handle *h, const int32_t *tokens, const uint8_t *mask, 
                     float temperature, float *out_logprobs, float *out_values,
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- What PPO consumes after the rollout (stateless: no handle, no workspace). ------------------
+ *
+ * Reward assembly (paper: Preliminaries, Eq. (RL); Reward Model Details, "Extract reward from the EOS
+ * token"; PPO Details, "EOS trick" step 3 and the figure "Reward and values of a completion").
+ * For row b let first = index of the first pad_id among its N response tokens (N if none) and
+ * last = first - 1.  Then for t <= last
+ *   out_rewards[b,t] = -beta * (logprobs[b,t] - ref_logprobs[b,Lq+t])   (+ score_b at t = last)
+ * where score_b = rm_values[b,Lq+last] if the token at last is eos_id, else missing_eos_score (the
+ * paper's -1); rewards are 0 for t > last, and a row that starts with pad_id is all 0.
+ * Inputs (dev): logprobs float [B,N] as written by rollout_generate; ref_logprobs, rm_values float
+ * [B,Lq+N] as written by score_sequences (out_logprobs with the reference policy's weights,
+ * out_values with the reward model's weights); tokens int32 [B,Lq+N].
+ * Outputs (dev): out_rewards float [B,N]; out_scores float [B] (score_b); out_kl float [B]
+ * (sum over t <= last of logprobs - ref_logprobs); out_kept int32 [B] (last + 1, the number of
+ * response tokens PPO treats as real).  All four outputs are required. */
+int rlhf_ppo_assemble_rewards(const float *logprobs, const float *ref_logprobs, const float *rm_values,
+                              const int32_t *tokens, int32_t B, int32_t Lq, int32_t N, int32_t eos_id,
+                              int32_t pad_id, float beta, float missing_eos_score, float *out_rewards,
+                              float *out_scores, float *out_kl, int32_t *out_kept, void *stream);
+
+/* Generalised advantage estimation (paper: PPO hyperparameter table, gamma = 1, lambda = 0.95; the
+ * estimator itself is the standard one): over t < kept[b], delta_t = r_t + gamma V_{t+1} - V_t with
+ * V = 0 at t+1 >= kept[b], A_t = delta_t + gamma lambda A_{t+1}, returns = A + V; 0 elsewhere.
+ * rewards dev float [B,N]; values dev float, element (b,t) at values[b*values_row_stride + t] (so a
+ * [B,Lq+N] array from score_sequences is passed as pointer + column offset, stride Lq+N);
+ * kept dev int32 [B]; outputs dev float [B,N]. */
+int rlhf_ppo_gae(const float *rewards, const float *values, int64_t values_row_stride, const int32_t *kept,
+                 int32_t B, int32_t N, float gamma, float lambda, float *out_advantages, float *out_returns,
+                 void *stream);
+
+/* Whitening (paper: PPO Details, "(Optional) Reward whitening" and "Advantage whitening"):
+ * (x - mean) / sqrt(var + 1e-8) with the biased variance over the positions t < kept[b] of the whole
+ * batch (kept == NULL: every position); shift_mean == 0 adds the mean back, as the paper's
+ * whiten(rewards, shift_mean=False) does.  Positions that are not kept get 0.  x, out: dev float
+ * [B,N] (may be the same buffer). */
+int rlhf_ppo_whiten(const float *x, const int32_t *kept, int32_t B, int32_t N, int32_t shift_mean, float *out,
+                    void *stream);
+
 /* Debug / parity aid: raw (pre-temperature) fp32 logits of the same forward pass as
  * score_sequences at n (row, column) pairs.  rows_bt: HOST int32 [n, 2]; out_logits: dev float
  * [n, vocab].  Every pair must name a real position. */

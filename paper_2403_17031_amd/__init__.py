@@ -9,4 +9,7 @@ from .binding import (  # noqa: F401
     RlhfError,
     load_library,
     exported_symbols,
+    ppo_assemble_rewards,
+    ppo_gae,
+    ppo_whiten,
 )

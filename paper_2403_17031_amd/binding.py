@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "librlhf_rollout.so")
 EXPORTS = (
     "rlhf_create", "rlhf_destroy", "rlhf_workspace_bytes", "rollout_generate", "score_sequences",
     "rlhf_debug_logits_rows", "rlhf_profile_enable", "rlhf_profile_read", "rlhf_last_rollout_phases",
-    "rlhf_last_error",
+    "rlhf_last_error", "rlhf_ppo_assemble_rewards", "rlhf_ppo_gae", "rlhf_ppo_whiten",
 )
 
 _PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -62,6 +62,9 @@ def load_library():
     lib.rlhf_profile_read.argtypes = [vp, i32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                       C.POINTER(C.c_int64), C.POINTER(i32)]
     lib.rlhf_last_rollout_phases.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.rlhf_ppo_assemble_rewards.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, vp, vp, vp, vp, vp]
+    lib.rlhf_ppo_gae.argtypes = [vp, vp, C.c_int64, vp, i32, i32, f32, f32, vp, vp, vp]
+    lib.rlhf_ppo_whiten.argtypes = [vp, vp, i32, i32, i32, vp, vp]
     lib.rlhf_last_error.restype = C.c_char_p
     for n in EXPORTS:
         if n not in ("rlhf_destroy", "rlhf_last_error"):
@@ -221,3 +224,84 @@ class Policy:
         if isinstance(x, np.ndarray):
             x = torch.from_numpy(np.ascontiguousarray(x))
         return x.to(self.device, dtype=dtype).contiguous()
+
+
+# ---------------------------------------------------------------------- PPO signals (stateless)
+def _dev_f32(torch, a, device):
+    t = a if isinstance(a, torch.Tensor) else torch.as_tensor(np.ascontiguousarray(a))
+    return t.to(device=device, dtype=torch.float32).contiguous()
+
+
+def _dev_i32(torch, a, device):
+    t = a if isinstance(a, torch.Tensor) else torch.as_tensor(np.ascontiguousarray(a))
+    return t.to(device=device, dtype=torch.int32).contiguous()
+
+
+def _cur_stream(torch, device):
+    return C.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def ppo_assemble_rewards(logprobs, ref_logprobs, rm_values, tokens, query_len, eos_id, pad_id, beta=0.05,
+                         missing_eos_score=-1.0, device="cuda:0"):
+    """logprobs [B, N] (rollout_generate); ref_logprobs, rm_values [B, Lq+N] (score_sequences with the
+    reference policy's / the reward model's weights); tokens int32 [B, Lq+N].
+    Returns CUDA tensors (rewards [B, N], scores [B], kl [B], kept int32 [B])."""
+    import torch
+    lib = load_library()
+    dev = torch.device(device)
+    lp = _dev_f32(torch, logprobs, dev)
+    ref = _dev_f32(torch, ref_logprobs, dev)
+    rm = _dev_f32(torch, rm_values, dev)
+    tok = _dev_i32(torch, tokens, dev)
+    B, N = lp.shape
+    Lq = int(query_len)
+    if tuple(ref.shape) != (B, Lq + N) or tuple(rm.shape) != (B, Lq + N) or tuple(tok.shape) != (B, Lq + N):
+        raise RlhfError("ppo_assemble_rewards: ref_logprobs, rm_values and tokens must be [B, query_len + N]")
+    rewards = torch.empty((B, N), dtype=torch.float32, device=dev)
+    scores = torch.empty((B,), dtype=torch.float32, device=dev)
+    kl = torch.empty((B,), dtype=torch.float32, device=dev)
+    kept = torch.empty((B,), dtype=torch.int32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.rlhf_ppo_assemble_rewards(lp.data_ptr(), ref.data_ptr(), rm.data_ptr(), tok.data_ptr(), B, Lq, N,
+                                             int(eos_id), int(pad_id), float(beta), float(missing_eos_score),
+                                             rewards.data_ptr(), scores.data_ptr(), kl.data_ptr(), kept.data_ptr(),
+                                             _cur_stream(torch, dev)))
+    return rewards, scores, kl, kept
+
+
+def ppo_gae(rewards, values, kept, gamma=1.0, lam=0.95, value_offset=0, device="cuda:0"):
+    """rewards [B, N]; values [B, >= value_offset + N], the value of response token t read at column
+    value_offset + t; kept int32 [B].  Returns CUDA tensors (advantages, returns), both [B, N]."""
+    import torch
+    lib = load_library()
+    dev = torch.device(device)
+    r = _dev_f32(torch, rewards, dev)
+    v = _dev_f32(torch, values, dev)
+    k = _dev_i32(torch, kept, dev)
+    B, N = r.shape
+    off = int(value_offset)
+    if v.shape[0] != B or off < 0 or v.shape[1] < off + N or k.shape[0] != B:
+        raise RlhfError("ppo_gae: values must be [B, >= value_offset + N] and kept [B]")
+    adv = torch.empty((B, N), dtype=torch.float32, device=dev)
+    ret = torch.empty((B, N), dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.rlhf_ppo_gae(r.data_ptr(), v.data_ptr() + 4 * off, v.shape[1], k.data_ptr(), B, N, float(gamma),
+                                float(lam), adv.data_ptr(), ret.data_ptr(), _cur_stream(torch, dev)))
+    return adv, ret
+
+
+def ppo_whiten(x, kept=None, shift_mean=True, device="cuda:0"):
+    """x [B, N]; kept int32 [B] or None (dense).  Returns a CUDA tensor [B, N]."""
+    import torch
+    lib = load_library()
+    dev = torch.device(device)
+    xv = _dev_f32(torch, x, dev)
+    B, N = xv.shape
+    k = None if kept is None else _dev_i32(torch, kept, dev)
+    if k is not None and k.shape[0] != B:
+        raise RlhfError("ppo_whiten: kept must be [B]")
+    out = torch.empty((B, N), dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.rlhf_ppo_whiten(xv.data_ptr(), None if k is None else k.data_ptr(), B, N, 1 if shift_mean else 0,
+                                   out.data_ptr(), _cur_stream(torch, dev)))
+    return out

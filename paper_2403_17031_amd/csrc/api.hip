@@ -351,6 +351,39 @@ extern "C" {
 
 const char* rlhf_last_error(void) { return g_err.c_str(); }
 
+int rlhf_ppo_assemble_rewards(const float* logprobs, const float* ref_logprobs, const float* rm_values,
+                              const int32_t* tokens, int32_t B, int32_t Lq, int32_t N, int32_t eos_id,
+                              int32_t pad_id, float beta, float missing_eos_score, float* out_rewards,
+                              float* out_scores, float* out_kl, int32_t* out_kept, void* stream) {
+  if (!logprobs || !ref_logprobs || !rm_values || !tokens || !out_rewards || !out_kept || !out_scores || !out_kl)
+    return fail(RLHF_EINVAL, "null pointer argument");
+  if (B <= 0 || N <= 0 || Lq < 0) return fail(RLHF_EINVAL, "batch and response length must be positive");
+  if ((size_t)B * ((size_t)Lq + N) > (size_t)1 << 30) return fail(RLHF_EUNSUPPORTED, "batch * length too large");
+  HIP_OK(launch_ppo_rewards(logprobs, ref_logprobs, rm_values, tokens, B, Lq, N, eos_id, pad_id, beta,
+                            missing_eos_score, out_rewards, out_scores, out_kl, out_kept, (hipStream_t)stream));
+  return RLHF_OK;
+}
+
+int rlhf_ppo_gae(const float* rewards, const float* values, int64_t values_row_stride, const int32_t* kept,
+                 int32_t B, int32_t N, float gamma, float lambda, float* out_advantages, float* out_returns,
+                 void* stream) {
+  if (!rewards || !values || !kept || !out_advantages || !out_returns)
+    return fail(RLHF_EINVAL, "null pointer argument");
+  if (B <= 0 || N <= 0) return fail(RLHF_EINVAL, "batch and response length must be positive");
+  if (values_row_stride < N) return fail(RLHF_EINVAL, "values_row_stride smaller than the response length");
+  HIP_OK(launch_ppo_gae(rewards, values, (long)values_row_stride, kept, B, N, gamma, lambda, out_advantages,
+                        out_returns, (hipStream_t)stream));
+  return RLHF_OK;
+}
+
+int rlhf_ppo_whiten(const float* x, const int32_t* kept, int32_t B, int32_t N, int32_t shift_mean, float* out,
+                    void* stream) {
+  if (!x || !out) return fail(RLHF_EINVAL, "null pointer argument");
+  if (B <= 0 || N <= 0) return fail(RLHF_EINVAL, "batch and response length must be positive");
+  HIP_OK(launch_ppo_whiten(x, kept, B, N, shift_mean ? 1 : 0, out, (hipStream_t)stream));
+  return RLHF_OK;
+}
+
 int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, rlhf_handle** out) {
   if (out) *out = nullptr;
   if (!cfg || !w || !out) return fail(RLHF_EINVAL, "null argument");

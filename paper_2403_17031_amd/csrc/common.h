@@ -194,6 +194,15 @@ hipError_t launch_unpack_scores(const float* lp_packed, const float* val_packed,
 hipError_t launch_rows_to_packed(const int32_t* rows_bt, int n, const int* start, const int* cu, int* idx,
                                  hipStream_t s);
 
+// PPO signals (reward assembly, advantage estimation, whitening); see ppo_signals.hip.
+hipError_t launch_ppo_rewards(const float* lp, const float* ref_full, const float* rm_full, const int* tokens, int B,
+                              int Lq, int N, int eos_id, int pad_id, float beta, float miss, float* rewards,
+                              float* scores, float* kl, int* kept, hipStream_t s);
+hipError_t launch_ppo_gae(const float* rewards, const float* values, long vstride, const int* kept, int B, int N,
+                          float gamma, float lam, float* adv, float* ret, hipStream_t s);
+hipError_t launch_ppo_whiten(const float* x, const int* kept, int B, int N, int shift_mean, float* out,
+                             hipStream_t s);
+
 // bf16 -> fp16 conversion of a weight matrix (exact within fp16's normal range).
 hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s);
 

@@ -296,15 +296,22 @@ __global__ void __launch_bounds__(256)
 // =================================================================================================
 // Large-M kernel: 256x256 block tile, one block per CU, 4 waves of 128x128 (256 accumulator
 // registers per lane).  Tiles go global -> LDS directly (global_load_lds, 16 bytes per lane: a wave
-// instruction fills 1 KB; no staging registers, no ds_write) into FOUR 32 KB stages of K depth 32,
-// three k-steps ahead of the math: with one block per CU a k-step lasts about as long as a memory
-// round trip under load, so a single stage of lookahead leaves the matrix cores waiting.  Raw
-// s_barrier + explicit s_waitcnt are used because __syncthreads would drain every outstanding load.
-// The fragment reads of the next k-step are issued right after the barrier and the last 16 matrix
-// instructions of the current k-step run behind them, so LDS latency is not exposed either.  Each
-// lane picks its global chunk so that the linear LDS image is the XOR-swizzled layout the fragment
-// reads expect (conflict-free ds_read_b128).
+// instruction fills 1 KB; no staging registers, no ds_write) into TWO 64 KB stages of K depth 64.
+// The depth is what matters: a tile row is then one full 128-byte line per stage.  With half
+// lines (K depth 32, more and smaller stages) every line was requested twice from L2, one half per
+// k-step, and the matrix cores waited on that request stream; fetching whole lines removed the
+// stall, and a lookahead of one stage proved as good as three.  One raw s_barrier per stage (64
+// matrix instructions per wave) with an explicit s_waitcnt; the 16 tile loads and 32 fragment
+// reads of a stage are dealt out one at a time between the matrix instructions (scheduling fences
+// keep the order), so each issues in the shadow of a matrix instruction.  Each lane picks its
+// global chunk so that the linear LDS image is the XOR-swizzled layout the fragment reads expect
+// (conflict-free ds_read_b128).
 // =================================================================================================
+#ifdef RLHF_ABL_NOSTORE
+#define RLHF_ABL_NOSTORE_COND &&v[0] == 0x12345678u
+#else
+#define RLHF_ABL_NOSTORE_COND
+#endif
 #ifdef RLHF_ABL_SAMEK
 #define RLHF_ABL_K(k) 0  // timing experiment only: every k-step re-reads the first tile
 #else
@@ -312,10 +319,10 @@ __global__ void __launch_bounds__(256)
 #endif
 #define RLHF_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define RLHF_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
-constexpr int DK = 32;                      // K depth of one stage
-constexpr int DSTAGE = (256 + 256) * DK;    // halfs per stage (32 KB)
+constexpr int DK = 64;                      // K depth of one stage: 128 bytes per tile row
+constexpr int DSTAGE = (256 + 256) * DK;    // halfs per stage (64 KB)
 
-template <int EPI, int NS>
+template <int EPI>
 __global__ void __launch_bounds__(256, 1)
     gemm_f16_dma_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
                         void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
@@ -323,9 +330,6 @@ __global__ void __launch_bounds__(256, 1)
   constexpr int TM = 256, TN = 256, MT = 4, NT = 4;
   __shared__ __attribute__((aligned(16))) uint16_t lds0[DSTAGE];
   __shared__ __attribute__((aligned(16))) uint16_t lds1[DSTAGE];
-  __shared__ __attribute__((aligned(16))) uint16_t lds2[DSTAGE];
-  __shared__ __attribute__((aligned(16))) uint16_t lds3[DSTAGE];
-  __shared__ __attribute__((aligned(16))) uint16_t lds4[NS == 5 ? DSTAGE : 8];  // fifth stage: all 160 KB
   const int M = M_dev ? min(M_max, *M_dev - M_sub) : M_max;
   nb_m = min(nb_m, (M + TM - 1) / TM);
   const int total = nb_m * nb_n;
@@ -343,29 +347,29 @@ __global__ void __launch_bounds__(256, 1)
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps LDS bases in SGPRs
   const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
 
-  // ---- direct loads: a stage row is 64 B (4 chunks); wave-load j (= 8*wave + i, i < 8) fills rows
-  //      16j .. 16j+15 (rows < 256: A, else W); lane l lands at row 16j + l/4, physical chunk l%4,
-  //      and therefore fetches logical chunk (l%4) ^ ((row>>2)&3)
-  uint32_t goff[8];
+  // ---- direct loads: a stage row is 128 B (8 chunks); wave-load j (= 16*wave + i, i < 16) fills
+  //      rows 8j .. 8j+7 (rows < 256: A, else W); lane l lands at row 8j + l/8, physical chunk l%8,
+  //      and therefore fetches logical chunk (l%8) ^ ((row>>1)&7)
+  uint32_t goff[16];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int row = 16 * (8 * wave + i) + (lane >> 2);
-    const int c = (lane & 3) ^ ((row >> 2) & 3);
+  for (int i = 0; i < 16; ++i) {
+    const int row = 8 * (16 * wave + i) + (lane >> 3);
+    const int c = (lane & 7) ^ ((row >> 1) & 7);
     const int grow = row < TM ? min(m0 + row, M - 1) : min(n0 + row - TM, N - 1);
     goff[i] = (uint32_t)(grow * K + c * 8);
   }
   const half_t* gbase = wave < 2 ? A : W;  // waves 0,1 load A rows, waves 2,3 load W rows
-  auto issue_loads = [&](uint16_t* stage, int k0) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      __builtin_amdgcn_global_load_lds(RLHF_GLOBAL_PTR(gbase + goff[i] + RLHF_ABL_K(k0)),
-                                       RLHF_LDS_PTR(stage + (16 * (8 * wave + i)) * DK), 16, 0, 0);
+  auto load_one = [&](uint16_t* stage, int k0, int i) {
+    __builtin_amdgcn_global_load_lds(RLHF_GLOBAL_PTR(gbase + goff[i] + RLHF_ABL_K(k0)),
+                                     RLHF_LDS_PTR(stage + (8 * (16 * wave + i)) * DK), 16, 0, 0);
   };
 
   const int l32 = lane & 31, hf = lane >> 5;
-  const int key = (l32 >> 2) & 3;
+  const int key = (l32 >> 1) & 7;
   const int a_off = (wm + l32) * DK, w_off = (TM + wn + l32) * DK;
-  const int ch0 = ((hf) ^ key) << 3, ch1 = ((2 + hf) ^ key) << 3;  // sub-steps 0 and 1
+  // sub-step s (16 of the 64 k of a stage) reads logical chunks 2s and 2s+1: one per half-wave
+  const int ch0 = ((0 + hf) ^ key) << 3, ch1 = ((2 + hf) ^ key) << 3, ch2 = ((4 + hf) ^ key) << 3,
+            ch3 = ((6 + hf) ^ key) << 3;
 
   f32x16_t acc[NT][MT];
 #pragma unroll
@@ -375,93 +379,64 @@ __global__ void __launch_bounds__(256, 1)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
 
-  f16x8_t fa0[MT], fw0[NT], fa1[MT], fw1[NT];  // fragment buffers of sub-steps 0 and 1
-  auto frags = [&](const uint16_t* ls, int ch, f16x8_t* fa, f16x8_t* fw) {
-#pragma unroll
-    for (int i = 0; i < MT; ++i) fa[i] = *(const f16x8_t*)(ls + a_off + i * 32 * DK + ch);
-#pragma unroll
-    for (int j = 0; j < NT; ++j) fw[j] = *(const f16x8_t*)(ls + w_off + j * 32 * DK + ch);
-  };
-  // weights as the first operand: accumulator element e of a lane is then
-  // (n = 8*(e/4) + 4*(lane/32) + e%4, m = lane%32), i.e. 4 consecutive output columns per lane
-  auto mma = [&](const f16x8_t* fa, const f16x8_t* fw, int j0, int j1) {
-#pragma unroll
-    for (int j = j0; j < j1; ++j)
-#pragma unroll
-      for (int i = 0; i < MT; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[j], fa[i], acc[j][i], 0, 0, 0);
-  };
-  // vmcnt(8*(NS-2)) lgkmcnt(0): everything but the NS-2 youngest tile loads (8 instructions each)
-  // has landed, and this wave's fragment reads are complete
-  constexpr int WAIT_IMM = NS == 5 ? 0x4078 : 0x4070;
-#define RLHF_WAIT_BARRIER()                      \
-  __builtin_amdgcn_sched_barrier(0);             \
-  asm volatile("" ::: "memory");                 \
-  __builtin_amdgcn_s_waitcnt(WAIT_IMM);          \
-  __builtin_amdgcn_s_barrier();                  \
-  asm volatile("" ::: "memory");                 \
-  __builtin_amdgcn_sched_barrier(0);
-  // One k-step: 32 matrix instructions per wave with the 8 tile loads and 16 fragment reads dealt
-  // out one at a time between them (scheduling fences keep the order), so each memory instruction
-  // issues in the shadow of a matrix instruction instead of in a clump that drains the pipe.  The
-  // fragments of sub-step 1 are read during sub-step 0, those of the next k-step (after the
-  // barrier that publishes its tile) during sub-step 1.
-  auto load_one = [&](uint16_t* stage, int k0, int i) {
-    __builtin_amdgcn_global_load_lds(RLHF_GLOBAL_PTR(gbase + goff[i] + RLHF_ABL_K(k0)),
-                                     RLHF_LDS_PTR(stage + (16 * (8 * wave + i)) * DK), 16, 0, 0);
-  };
+  // fragment buffers, used alternately by the four sub-steps of a stage.  Weights are the first
+  // matrix operand: accumulator element e of a lane is then (n = 8*(e/4) + 4*(lane/32) + e%4,
+  // m = lane%32), i.e. 4 consecutive output columns per lane
+  f16x8_t fa0[MT], fw0[NT], fa1[MT], fw1[NT];
   auto frag_one = [&](const uint16_t* ls, int ch, int q, f16x8_t* fa, f16x8_t* fw) {
     if (q < MT) fa[q] = *(const f16x8_t*)(ls + a_off + q * 32 * DK + ch);
     else fw[q - MT] = *(const f16x8_t*)(ls + w_off + (q - MT) * 32 * DK + ch);
   };
-#define RLHF_STEP(CUR, NEXT, LOAD, KT)                                                        \
-  {                                                                                           \
-    const int kload = min((KT) + NS - 1, nk - 1) * DK;                                        \
-    _Pragma("unroll") for (int n = 0; n < 16; ++n) {                                          \
-      acc[n >> 2][n & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw0[n >> 2], fa0[n & 3],    \
-                                                                  acc[n >> 2][n & 3], 0, 0, 0); \
-      __builtin_amdgcn_sched_barrier(0);                                                      \
-      if (n < 8) frag_one(CUR, ch1, n, fa1, fw1);                                             \
-      else load_one(LOAD, kload, n - 8);                                                      \
-      __builtin_amdgcn_sched_barrier(0);                                                      \
-    }                                                                                         \
-    RLHF_WAIT_BARRIER()                                                                       \
-    _Pragma("unroll") for (int n = 0; n < 16; ++n) {                                          \
-      acc[n >> 2][n & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw1[n >> 2], fa1[n & 3],    \
-                                                                  acc[n >> 2][n & 3], 0, 0, 0); \
-      __builtin_amdgcn_sched_barrier(0);                                                      \
-      if (n < 8) frag_one(NEXT, ch0, n, fa0, fw0);                                            \
-      __builtin_amdgcn_sched_barrier(0);                                                      \
-    }                                                                                         \
+  // 16 matrix instructions on (FA, FW); after the n-th, fragment read n (n < 8) of the next
+  // sub-step from (LS, CH) into (GA, GW) and, if LOAD, tile load n of the stage at K offset KL
+#define RLHF_SUB(FA, FW, LS, CH, GA, GW, LOAD, LSTAGE, KL)                                        \
+  _Pragma("unroll") for (int n = 0; n < 16; ++n) {                                                \
+    acc[n >> 2][n & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(FW[n >> 2], FA[n & 3],            \
+                                                                acc[n >> 2][n & 3], 0, 0, 0);     \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    if (n < 8) frag_one(LS, CH, n, GA, GW);                                                       \
+    if (LOAD) load_one(LSTAGE, KL, n);                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+  }
+  // vmcnt(0) lgkmcnt(0) + barrier: every wave's tile loads have landed and every wave has finished
+  // reading the current stage
+#define RLHF_WAIT_BARRIER()                      \
+  __builtin_amdgcn_sched_barrier(0);             \
+  asm volatile("" ::: "memory");                 \
+  __builtin_amdgcn_s_waitcnt(0x0070);            \
+  __builtin_amdgcn_s_barrier();                  \
+  asm volatile("" ::: "memory");                 \
+  __builtin_amdgcn_sched_barrier(0);
+  // One stage (K depth 64).  The first three sub-steps read their successors' fragments from CUR.
+  // After the barrier CUR is free and OTHER holds the next stage: the last sub-step reads the next
+  // stage's first fragments from OTHER and issues the loads of the stage after that into CUR, so a
+  // load has a whole stage of matrix work to land.
+#define RLHF_STAGE(CUR, OTHER, KT)                                                                \
+  {                                                                                               \
+    const int kload = min((KT) + 2, nk - 1) * DK;                                                 \
+    RLHF_SUB(fa0, fw0, CUR, ch1, fa1, fw1, false, CUR, 0)                                         \
+    RLHF_SUB(fa1, fw1, CUR, ch2, fa0, fw0, false, CUR, 0)                                         \
+    RLHF_SUB(fa0, fw0, CUR, ch3, fa1, fw1, false, CUR, 0)                                         \
+    RLHF_WAIT_BARRIER()                                                                           \
+    RLHF_SUB(fa1, fw1, OTHER, ch0, fa0, fw0, true, CUR, kload)                                    \
   }
 
-  // K is a multiple of NS*DK here (the launcher picks NS, or the staged kernel), so the loop is
-  // branch-free: past the end the final tile is re-issued into a stage nobody reads.  NS-1 tiles
-  // are in flight while one is consumed; what the loop sustains is set by bytes in flight over
-  // the loaded L2 latency, hence five stages (the whole LDS) when K allows.
+  // K is a multiple of 2*DK here (the launcher routes other shapes to the staged kernel), so the
+  // loop is branch-free: past the end the final tile is re-issued into a stage nobody reads.
   const int nk = K / DK;
-  issue_loads(lds0, 0);
-  issue_loads(lds1, min(1, nk - 1) * DK);
-  issue_loads(lds2, min(2, nk - 1) * DK);
-  if (NS == 5) issue_loads(lds3, min(3, nk - 1) * DK);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) load_one(lds0, 0, i);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) load_one(lds1, min(1, nk - 1) * DK, i);
   RLHF_WAIT_BARRIER()
-  frags(lds0, ch0, fa0, fw0);
-  if (NS == 5) {
-    for (int kt = 0; kt < nk; kt += 5) {
-      RLHF_STEP(lds0, lds1, lds4, kt)
-      RLHF_STEP(lds1, lds2, lds0, kt + 1)
-      RLHF_STEP(lds2, lds3, lds1, kt + 2)
-      RLHF_STEP(lds3, lds4, lds2, kt + 3)
-      RLHF_STEP(lds4, lds0, lds3, kt + 4)
-    }
-  } else {
-    for (int kt = 0; kt < nk; kt += 4) {
-      RLHF_STEP(lds0, lds1, lds3, kt)
-      RLHF_STEP(lds1, lds2, lds0, kt + 1)
-      RLHF_STEP(lds2, lds3, lds1, kt + 2)
-      RLHF_STEP(lds3, lds0, lds2, kt + 3)
-    }
+#pragma unroll
+  for (int q = 0; q < 8; ++q) frag_one(lds0, ch0, q, fa0, fw0);
+  for (int kt = 0; kt < nk; kt += 2) {
+    RLHF_STAGE(lds0, lds1, kt)
+    RLHF_STAGE(lds1, lds0, kt + 1)
   }
-#undef RLHF_STEP
+#undef RLHF_STAGE
+#undef RLHF_SUB
 #undef RLHF_WAIT_BARRIER
   __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): the surplus loads have landed too
   __syncthreads();
@@ -476,7 +451,7 @@ __global__ void __launch_bounds__(256, 1)
   //      16 bytes per lane, 16 lanes per 256-byte row segment.  The LDS image is XOR-swizzled by
   //      row (chunk ^ (row & 15)); accumulator tiles are addressed through compile-time indices
   //      (a loop the compiler declines to unroll would spill all 256 accumulators to scratch).
-  uint16_t* ep = wave == 0 ? lds0 : wave == 1 ? lds1 : wave == 2 ? lds2 : lds3;  // 32 KB per wave
+  uint16_t* ep = (wave & 2 ? lds1 : lds0) + (wave & 1) * (DSTAGE / 2);  // 32 KB per wave
   const int rd_row = lane >> 4, rd_c = lane & 15;
   // bias of this lane's 64 columns: 16 eight-byte loads issued together (N is a multiple of 8 here
   // and every column group starts at a multiple of 4, so a group is inside or outside as a whole)
@@ -522,7 +497,7 @@ __global__ void __launch_bounds__(256, 1)
       const int row = it * 4 + rd_row;
       const int grow = m0 + wm + row;
       const u32x4_t v = *(const u32x4_t*)(ep + row * 128 + ((rd_c ^ (row & 15)) << 3));
-      if (grow < M && gcol < N) *(u32x4_t*)((half_t*)out + (size_t)grow * ldo + gcol) = v;
+      if (grow < M && gcol < N RLHF_ABL_NOSTORE_COND) *(u32x4_t*)((half_t*)out + (size_t)grow * ldo + gcol) = v;
     }
   } else {
     float* epf = (float*)ep;  // 128 rows x 64 floats per pass
@@ -577,14 +552,9 @@ template <int EPI>
 static void launch_f16_dma(const GemmArgs& a, hipStream_t s) {
   const int nb_m = (a.M_max + 255) / 256, nb_n = (a.N + 255) / 256;
   const int per_xcd = (nb_m * nb_n + 7) / 8;
-  if (a.K % (5 * DK) == 0)
-    hipLaunchKernelGGL((gemm_f16_dma_kernel<EPI, 5>), dim3(per_xcd * 8), dim3(256), 0, s, (const half_t*)a.A,
-                       (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
-                       nb_m, nb_n);
-  else
-    hipLaunchKernelGGL((gemm_f16_dma_kernel<EPI, 4>), dim3(per_xcd * 8), dim3(256), 0, s, (const half_t*)a.A,
-                       (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
-                       nb_m, nb_n);
+  hipLaunchKernelGGL(gemm_f16_dma_kernel<EPI>, dim3(per_xcd * 8), dim3(256), 0, s, (const half_t*)a.A,
+                     (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
+                     nb_m, nb_n);
 }
 
 #ifndef RLHF_GEMM_DMA
@@ -666,7 +636,7 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
     }
     if (a.M_max <= 512)
       launch_f16<EPI, 2, 1, RLHF_DEC_PF, RLHF_DEC_OCC>(a, s, a.out, 1);
-    else if (RLHF_GEMM_DMA && ((a.K % (4 * DK)) == 0 || (a.K % (5 * DK)) == 0) && (a.N % 8) == 0 && (a.ldo % 8) == 0 && (size_t)std::max(a.M_max, a.N) * a.K < (1ull << 32))
+    else if (RLHF_GEMM_DMA && (a.K % (2 * DK)) == 0 && (a.N % 8) == 0 && (a.ldo % 8) == 0 && (size_t)std::max(a.M_max, a.N) * a.K < (1ull << 32))
       launch_f16_dma<EPI>(a, s);
     else
       launch_f16<EPI, RLHF_GEMM_MT, RLHF_GEMM_NT, RLHF_GEMM_PF, RLHF_GEMM_OCC>(a, s, a.out, 1);

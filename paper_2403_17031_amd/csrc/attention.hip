@@ -252,7 +252,7 @@ __global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
       }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);  // finite: key 0 is visible to every query
-    const float alpha = exp2f(m_run - m_new);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // arguments <= 0: the bare instruction will do
     m_run = m_new;
     float psum = 0.f;
     f16x8_t pf[4];  // P^T operand of each 16-key step
@@ -260,16 +260,22 @@ __global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
     for (int kf = 0; kf < 2; ++kf)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const float p = exp2f(st[kf][e] - m_new);
+        const float p = __builtin_amdgcn_exp2f(st[kf][e] - m_new);
         psum += p;
         pf[kf * 2 + (e >> 3)][e & 7] = (half_t)p;
       }
     l_run = l_run * alpha + psum;
     // ---- O^T = alpha * O^T + V^T P^T
+    // once the running maxima have settled (usually after the first tiles) alpha is 1 in every lane
+    // and the rescaling of the accumulators is skipped for the whole wave
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+      for (int t = 0; t < NDT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+    }
 #pragma unroll
     for (int t = 0; t < NDT; ++t) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const f16x8_t vfrag = *(const f16x8_t*)(Vt + (t * 32 + l32) * FA_VT_STRIDE + 16 * c + 8 * half);

@@ -242,7 +242,7 @@ __global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
     for (int kf = 0; kf < 2; ++kf)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        float v = st[kf][e] * scale_log2e;
+        float v = st[kf][e];  // raw dot products: the (positive) scale is applied inside the exponent's FMA
         if (need_mask) {
           const int kj = k0 + kf * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
           if (kj > qi || kj >= n) v = -INFINITY;
@@ -251,7 +251,7 @@ __global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
         mx = fmaxf(mx, v);
       }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);  // finite: key 0 is visible to every query
+    const float m_new = fmaxf(m_run, mx * scale_log2e);  // finite: key 0 is visible to every query
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // arguments <= 0: the bare instruction will do
     m_run = m_new;
     float psum = 0.f;
@@ -260,7 +260,7 @@ __global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
     for (int kf = 0; kf < 2; ++kf)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const float p = __builtin_amdgcn_exp2f(st[kf][e] - m_new);
+        const float p = __builtin_amdgcn_exp2f(fmaf(st[kf][e], scale_log2e, -m_new));
         psum += p;
         pf[kf * 2 + (e >> 3)][e & 7] = (half_t)p;
       }

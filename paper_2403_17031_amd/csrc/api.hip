@@ -50,7 +50,7 @@ struct Meta {
 };
 struct Acts {
   float* x;
-  void *a, *m, *qkv, *q, *att, *ffn;
+  void *a, *m, *qkv, *q, *att, *ffn;  // att and ffn are carved back to back: [rows, d + d_ff] when viewed as one
   void* splitk = nullptr;   // fp32 partial sums of the decode GEMMs (attention branch)
   void* splitk2 = nullptr;  // same for the MLP branch, which runs on a second stream
   size_t splitk_bytes = 0;
@@ -65,6 +65,10 @@ struct rlhf_handle {
   float *rope_cos = nullptr, *rope_sin = nullptr;
   void* w16 = nullptr;                // bf16 mode: fp16 copies of the matrices the GEMMs read
   const void* embed_out_mm = nullptr; // LM-head operand (the caller's in fp32 mode, the copy in bf16 mode)
+  // bf16 mode: the fp16 copies of the out-projection [d, d] and FC2 [d, d_ff] of a layer sit side by
+  // side as one [d, d + d_ff] matrix (w_o = its column 0, w_fc2 = its column d, both with this row
+  // stride), so that prefill / scoring can run them as a single product over K = d + d_ff
+  int ld_o2 = 0;
   size_t esz = 2;
   // profiling
   bool prof_on = false;
@@ -142,8 +146,8 @@ Acts carve_acts(Carver& c, const rlhf_model_config& cfg, size_t rows, size_t esz
   a.m = c.take_bytes(rows * d * esz);
   a.qkv = c.take_bytes(rows * 3 * d * esz);
   a.q = c.take_bytes(rows * d * esz);
-  a.att = c.take_bytes(rows * d * esz);
-  a.ffn = c.take_bytes(rows * (size_t)cfg.d_ff * esz);
+  a.att = c.take_bytes(rows * (d + (size_t)cfg.d_ff) * esz);
+  a.ffn = (char*)a.att + rows * d * esz;
   return a;
 }
 
@@ -252,6 +256,14 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
   // branch (K/V streaming from HBM).  Needs FC2 on the split-K path, so that only its final
   // reduction touches the residual stream; not used while per-kernel profiling is on.
   const bool fork_mlp = p.mode == 1 && !h->prof_on && ks_2 > 1;
+  // Prefill / scoring: out-projection and FC2 both add into the residual stream, so they run as one
+  // product over the concatenated K = d + d_ff when the large-M kernel takes that shape.
+  auto gcat = [&](int l) {
+    GemmArgs g = gemm_args(A.att, h->w_o[l], h->b_o[l], A.x, d, d + c.d_ff, EPI_BIAS_RESADD);
+    g.bias2 = h->b_fc2[l];
+    return g;
+  };
+  const bool cat = p.mode == 0 && h->ld_o2 != 0 && gemm_takes_bias2(dt, gcat(0));
   const size_t slab = (size_t)p.rows_max * d;
   bool pending = false;  // out-projection and FC2 partial sums of the previous layer not yet in x
 
@@ -287,6 +299,11 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
     GemmArgs go = gemm_args(A.att, h->w_o[l], h->b_o[l], A.x, d, d, EPI_BIAS_RESADD);
     GemmArgs g1 = gemm_args(A.m, h->w_fc1[l], h->b_fc1[l], A.ffn, c.d_ff, d, EPI_BIAS_GELU);
     GemmArgs g2 = gemm_args(A.ffn, h->w_fc2[l], h->b_fc2[l], A.x, d, c.d_ff, EPI_BIAS_RESADD);
+    go.ldw = g2.ldw = h->ld_o2;
+    if (cat) {  // attention output and FFN hidden side by side: [rows, d + d_ff]
+      g1.out = (char*)A.att + (size_t)d * h->esz;
+      g1.ldo = d + c.d_ff;
+    }
     if (p.mode == 1) {  // the MLP branch has partial-sum scratch of its own
       g1.splitk_ws = A.splitk2;
       g2.splitk_ws = A.splitk2;
@@ -307,11 +324,17 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
     }
     if (p.mode == 0)
       LAUNCH("attn_prefill", launch_attn_prefill(dt, A.q, kc, vc, (long)p.kv_extra, p.B, p.Lmax, p.len, p.cu, p.kvoff,
-                                                 c.n_heads, c.head_dim, A.att, s));
+                                                 c.n_heads, c.head_dim, A.att, cat ? d + c.d_ff : d, s));
     else
       LAUNCH("attn_decode", launch_attn_decode(dt, A.q, kc, vc, (long)p.kv_extra, p.B, p.len, p.ctx_add, p.ctx_max,
                                                p.kvoff, c.n_heads, c.head_dim, A.att, s));
     // From here on the order of the additions into x is the serial one: x = (x + attn) + mlp.
+    if (cat) {
+      // x += [att | ffn] [W_o | W_fc2]^T + b_o + b_fc2: one product, one pass over the residual stream
+      LAUNCH("gemm", launch_gemm(dt, g1, s));
+      LAUNCH("gemm", launch_gemm(dt, gcat(l), s));
+      continue;
+    }
     const bool defer = fold && l + 1 < c.n_layers;  // the next layer's LayerNorm adds both products
     if (fold) go.phase = 1;
     LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, go, s));
@@ -451,11 +474,15 @@ int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, rlhf_handle
       slot = p;
       p += n * 2;
     };
+    h->ld_o2 = (int)(d + F);
     for (int l = 0; l < c.n_layers; ++l) {
       conv(h->w_qkv[l], 3 * d * d);
-      conv(h->w_o[l], d * d);
       conv(h->w_fc1[l], d * F);
-      conv(h->w_fc2[l], d * F);
+      if (e == hipSuccess) e = launch_bf16_to_f16_2d(h->w_o[l], p, d, d, d + F, nullptr);
+      if (e == hipSuccess) e = launch_bf16_to_f16_2d(h->w_fc2[l], p + d * 2, d, F, d + F, nullptr);
+      h->w_o[l] = p;
+      h->w_fc2[l] = p + d * 2;
+      p += (d * d + d * F) * 2;
     }
     conv(h->embed_out_mm, (size_t)c.vocab * d);
     if (e == hipSuccess) e = hipDeviceSynchronize();

@@ -16,7 +16,7 @@ template <typename T>
 __global__ void __launch_bounds__(256)
     attn_prefill_generic(const T* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc,
                          long kv_extra, const int* __restrict__ len, const int* __restrict__ cu,
-                         const int* __restrict__ kvoff, int H, int hd, float scale, T* __restrict__ out) {
+                         const int* __restrict__ kvoff, int H, int hd, float scale, T* __restrict__ out, int out_ld) {
   extern __shared__ float smem[];
   const int b = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * 32;
   const int n = len[b];
@@ -94,7 +94,7 @@ __global__ void __launch_bounds__(256)
   }
   if (q0 + qi < n) {
     const float inv = 1.0f / row_l[qi];
-    T* ob = out + ((size_t)cu[b] + q0 + qi) * d + (size_t)h * hd;
+    T* ob = out + ((size_t)cu[b] + q0 + qi) * out_ld + (size_t)h * hd;
 #pragma unroll
     for (int k = 0; k < 32; ++k) {
       const int e = sub + 8 * k;
@@ -126,7 +126,7 @@ template <int HD>
 __global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
     attn_prefill_mfma(const half_t* __restrict__ q, const half_t* __restrict__ kc, const half_t* __restrict__ vc,
                       long kv_extra, const int* __restrict__ len, const int* __restrict__ cu,
-                      const int* __restrict__ kvoff, int H, float scale_log2e, half_t* __restrict__ out) {
+                      const int* __restrict__ kvoff, int H, float scale_log2e, half_t* __restrict__ out, int out_ld) {
   constexpr int NKS = HD / 16;         // k-steps of the Q K^T contraction
   constexpr int NDT = (HD + 31) / 32;  // 32-row tiles of O^T
   constexpr int K_STRIDE = HD + 8;     // halfs per K row: odd multiple of 16 B for every HD used
@@ -286,7 +286,7 @@ __global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (qi < n) {
     const float inv = 1.0f / l_tot;
-    half_t* orow = out + ((size_t)cu[b] + qi) * d + (size_t)h * HD;
+    half_t* orow = out + ((size_t)cu[b] + qi) * out_ld + (size_t)h * HD;
 #pragma unroll
     for (int t = 0; t < NDT; ++t)
 #pragma unroll
@@ -304,24 +304,24 @@ __global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
 
 template <int HD>
 static void launch_fa(const void* q, const void* kc, const void* vc, long kv_extra, int B, int Lmax,
-                      const int* len, const int* cu, const int* kvoff, int H, void* out, hipStream_t s) {
+                      const int* len, const int* cu, const int* kvoff, int H, void* out, int out_ld, hipStream_t s) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
   dim3 grid((Lmax + FA_BQ - 1) / FA_BQ, H, B);
   hipLaunchKernelGGL(attn_prefill_mfma<HD>, grid, dim3(256), 0, s, (const half_t*)q, (const half_t*)kc,
-                     (const half_t*)vc, kv_extra, len, cu, kvoff, H, scale_log2e, (half_t*)out);
+                     (const half_t*)vc, kv_extra, len, cu, kvoff, H, scale_log2e, (half_t*)out, out_ld);
 }
 
 hipError_t launch_attn_prefill(int dtype, const void* q, const void* kc, const void* vc, long kv_extra,
                                int B, int Lmax, const int* len, const int* cu, const int* kvoff, int H, int hd,
-                               void* out, hipStream_t s) {
+                               void* out, int out_ld, hipStream_t s) {
   if (hd > 256) return hipErrorInvalidValue;
   if (dtype == 1) {
     switch (hd) {
-      case 16: launch_fa<16>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
-      case 64: launch_fa<64>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
-      case 80: launch_fa<80>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
-      case 128: launch_fa<128>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
-      case 256: launch_fa<256>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, s); return hipGetLastError();
+      case 16: launch_fa<16>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, out_ld, s); return hipGetLastError();
+      case 64: launch_fa<64>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, out_ld, s); return hipGetLastError();
+      case 80: launch_fa<80>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, out_ld, s); return hipGetLastError();
+      case 128: launch_fa<128>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, out_ld, s); return hipGetLastError();
+      case 256: launch_fa<256>(q, kc, vc, kv_extra, B, Lmax, len, cu, kvoff, H, out, out_ld, s); return hipGetLastError();
       default: break;  // other head sizes: generic kernel below
     }
   }
@@ -333,13 +333,13 @@ hipError_t launch_attn_prefill(int dtype, const void* q, const void* kc, const v
       (void)hipFuncSetAttribute((const void*)attn_prefill_generic<float>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)sh);
     hipLaunchKernelGGL(attn_prefill_generic<float>, grid, dim3(256), sh, s, (const float*)q, (const float*)kc,
-                       (const float*)vc, kv_extra, len, cu, kvoff, H, hd, scale, (float*)out);
+                       (const float*)vc, kv_extra, len, cu, kvoff, H, hd, scale, (float*)out, out_ld);
   } else {
     if (sh > 65536)
       (void)hipFuncSetAttribute((const void*)attn_prefill_generic<half_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)sh);
     hipLaunchKernelGGL(attn_prefill_generic<half_t>, grid, dim3(256), sh, s, (const half_t*)q, (const half_t*)kc,
-                       (const half_t*)vc, kv_extra, len, cu, kvoff, H, hd, scale, (half_t*)out);
+                       (const half_t*)vc, kv_extra, len, cu, kvoff, H, hd, scale, (half_t*)out, out_ld);
   }
   return hipGetLastError();
 }

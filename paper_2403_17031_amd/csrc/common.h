@@ -90,7 +90,11 @@ struct GemmArgs {
   void* splitk_ws = nullptr;   // fp32 scratch for split-K partial sums (decode-sized M), or null
   size_t splitk_ws_bytes = 0;
   int phase = 0;               // split-K only: 0 = GEMM + reduce, 1 = partial sums only, 2 = reduce only
+  int lda = 0, ldw = 0;        // row strides of A and W in elements (0: K); fp16 kernels only
+  const void* bias2 = nullptr; // second bias added like the first; large-M fp16 kernel only
 };
+// True when launch_gemm would route these arguments to the kernel that honours bias2.
+bool gemm_takes_bias2(int dtype, const GemmArgs& a);
 // > 1 when launch_gemm would take the split-K path for these arguments.
 int gemm_splitk_factor(int dtype, const GemmArgs& a);
 hipError_t launch_gemm(int dtype, const GemmArgs& a, hipStream_t s);
@@ -157,7 +161,7 @@ hipError_t launch_rope_kv_splitk(const float* part, int ksplit, size_t slab, con
 // sequence b's keys at slots kvoff[b] .. kvoff[b]+len[b]; out [T, H*hd].
 hipError_t launch_attn_prefill(int dtype, const void* q, const void* kc, const void* vc, long kv_extra,
                                int B, int Lmax, const int* len, const int* cu, const int* kvoff, int H, int hd,
-                               void* out, hipStream_t s);
+                               void* out, int out_ld, hipStream_t s);
 // Decode attention: one query row per sequence against ctx = len[b] + ctx_add cached keys.
 hipError_t launch_attn_decode(int dtype, const void* q, const void* kc, const void* vc, long kv_extra,
                               int B, const int* len, int ctx_add, int ctx_max, const int* kvoff, int H, int hd,
@@ -205,5 +209,7 @@ hipError_t launch_ppo_whiten(const float* x, const int* kept, int B, int N, int 
 
 // bf16 -> fp16 conversion of a weight matrix (exact within fp16's normal range).
 hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s);
+// Same for a [rows, cols] matrix written with row stride dst_ld (elements).
+hipError_t launch_bf16_to_f16_2d(const void* src, void* dst, size_t rows, size_t cols, size_t dst_ld, hipStream_t s);
 
 }  // namespace rlhf

@@ -958,4 +958,23 @@ hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t 
   return hipGetLastError();
 }
 
+__global__ void bf16_to_f16_2d_kernel(const bf16_t* __restrict__ src, half_t* __restrict__ dst, size_t rows,
+                                      size_t cols, size_t dst_ld) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x, n = rows * cols;
+  for (; i < n; i += stride) {
+    const size_t r = i / cols, c = i - r * cols;
+    dst[r * dst_ld + c] = (half_t)to_f32(src[i]);
+  }
+}
+
+hipError_t launch_bf16_to_f16_2d(const void* src, void* dst, size_t rows, size_t cols, size_t dst_ld,
+                                 hipStream_t s) {
+  if (rows * cols == 0) return hipSuccess;
+  const int blocks = (int)std::min<size_t>((rows * cols + 255) / 256, 65536);
+  hipLaunchKernelGGL(bf16_to_f16_2d_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t*)src, (half_t*)dst, rows,
+                     cols, dst_ld);
+  return hipGetLastError();
+}
+
 }  // namespace rlhf

@@ -70,7 +70,7 @@ template <int EPI, int MT, int NT, int PF, int OCC>
 __global__ void __launch_bounds__(256, OCC)
     gemm_f16_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
                     void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
-                    int ldo, int nb_m, int nb_n, int ksplit) {
+                    int ldo, int nb_m, int nb_n, int ksplit, int lda, int ldw) {
   constexpr int TM = 64 * MT, TN = 64 * NT;
   constexpr int NLD = (TM + TN) / 32;  // 16-byte chunks per thread per k-step
   constexpr int NLD_A = TM / 32;
@@ -103,7 +103,7 @@ __global__ void __launch_bounds__(256, OCC)
   // NLD offsets live would push the kernel past 256 registers and into scratch
   auto goff = [&](int i) -> uint32_t {
     const int r = ld_r + 32 * (i < NLD_A ? i : i - NLD_A);
-    return (uint32_t)((i < NLD_A ? min(m0 + r, M - 1) : min(n0 + r, N - 1)) * K + ld_c * 8);
+    return (uint32_t)((i < NLD_A ? min(m0 + r, M - 1) * lda : min(n0 + r, N - 1) * ldw) + ld_c * 8);
   };
   const int st_off = lds_pos(ld_r, ld_c);  // + 32*i rows: (r>>1)&7 is unchanged by adding 32*i
   u32x4_t stage[PF][NLD];
@@ -326,7 +326,7 @@ template <int EPI>
 __global__ void __launch_bounds__(256, 1)
     gemm_f16_dma_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
                         void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
-                        int ldo, int nb_m, int nb_n) {
+                        int ldo, int nb_m, int nb_n, int lda, int ldw, const bf16_t* __restrict__ bias2) {
   constexpr int TM = 256, TN = 256, MT = 4, NT = 4;
   __shared__ __attribute__((aligned(16))) uint16_t lds0[DSTAGE];
   __shared__ __attribute__((aligned(16))) uint16_t lds1[DSTAGE];
@@ -355,8 +355,7 @@ __global__ void __launch_bounds__(256, 1)
   for (int i = 0; i < 16; ++i) {
     const int row = 8 * (16 * wave + i) + (lane >> 3);
     const int c = (lane & 7) ^ ((row >> 1) & 7);
-    const int grow = row < TM ? min(m0 + row, M - 1) : min(n0 + row - TM, N - 1);
-    goff[i] = (uint32_t)(grow * K + c * 8);
+    goff[i] = (uint32_t)((row < TM ? min(m0 + row, M - 1) * lda : min(n0 + row - TM, N - 1) * ldw) + c * 8);
   }
   const half_t* gbase = wave < 2 ? A : W;  // waves 0,1 load A rows, waves 2,3 load W rows
   auto load_one = [&](uint16_t* stage, int k0, int i) {
@@ -467,6 +466,13 @@ __global__ void __launch_bounds__(256, 1)
       bias_v[j][g][1] = __uint_as_float(raw[0] & 0xFFFF0000u);
       bias_v[j][g][2] = __uint_as_float(raw[1] << 16);
       bias_v[j][g][3] = __uint_as_float(raw[1] & 0xFFFF0000u);
+      if (EPI != EPI_F32 && bias2 && nb < N) {
+        raw = *(const u32x2_t*)(bias2 + nb);
+        bias_v[j][g][0] += __uint_as_float(raw[0] << 16);
+        bias_v[j][g][1] += __uint_as_float(raw[0] & 0xFFFF0000u);
+        bias_v[j][g][2] += __uint_as_float(raw[1] << 16);
+        bias_v[j][g][3] += __uint_as_float(raw[1] & 0xFFFF0000u);
+      }
     }
   if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU) {
     auto put = [&](auto jc, auto ic) {
@@ -554,7 +560,7 @@ static void launch_f16_dma(const GemmArgs& a, hipStream_t s) {
   const int per_xcd = (nb_m * nb_n + 7) / 8;
   hipLaunchKernelGGL(gemm_f16_dma_kernel<EPI>, dim3(per_xcd * 8), dim3(256), 0, s, (const half_t*)a.A,
                      (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
-                     nb_m, nb_n);
+                     nb_m, nb_n, a.lda ? a.lda : a.K, a.ldw ? a.ldw : a.K, (const bf16_t*)a.bias2);
 }
 
 #ifndef RLHF_GEMM_DMA
@@ -577,7 +583,7 @@ static void launch_f16(const GemmArgs& a, hipStream_t s, void* out, int ksplit) 
   const int per_xcd = (nb_m * nb_n + 7) / 8;
   hipLaunchKernelGGL((gemm_f16_kernel<EPI, MT, NT, PF, OCC>), dim3(per_xcd * 8, ksplit), dim3(256), 0, s,
                      (const half_t*)a.A, (const half_t*)a.W, (const bf16_t*)a.bias, out, a.M_max, a.M_dev, a.M_sub,
-                     a.N, a.K, a.ldo, nb_m, nb_n, ksplit);
+                     a.N, a.K, a.ldo, nb_m, nb_n, ksplit, a.lda ? a.lda : a.K, a.ldw ? a.ldw : a.K);
 }
 
 // out = epilogue(sum_z partial[z] + bias), slabs added in index order: deterministic.
@@ -614,6 +620,14 @@ int gemm_splitk_factor(int dtype, const GemmArgs& a) {
   return ksplit;
 }
 
+// Shapes the large-M kernel takes: K a multiple of two stages, 16-byte aligned rows, 32-bit offsets.
+static bool takes_dma(const GemmArgs& a) {
+  const size_t lda = a.lda ? a.lda : a.K, ldw = a.ldw ? a.ldw : a.K;
+  return RLHF_GEMM_DMA && a.M_max > 512 && (a.K % (2 * DK)) == 0 && (a.N % 8) == 0 && (a.ldo % 8) == 0 &&
+         (lda % 8) == 0 && (ldw % 8) == 0 && std::max((size_t)a.M_max * lda, (size_t)a.N * ldw) < (1ull << 32);
+}
+bool gemm_takes_bias2(int dtype, const GemmArgs& a) { return dtype == 1 && takes_dma(a); }
+
 template <int EPI>
 static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
   if (dtype == 0) {
@@ -636,7 +650,7 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
     }
     if (a.M_max <= 512)
       launch_f16<EPI, 2, 1, RLHF_DEC_PF, RLHF_DEC_OCC>(a, s, a.out, 1);
-    else if (RLHF_GEMM_DMA && (a.K % (2 * DK)) == 0 && (a.N % 8) == 0 && (a.ldo % 8) == 0 && (size_t)std::max(a.M_max, a.N) * a.K < (1ull << 32))
+    else if (takes_dma(a))
       launch_f16_dma<EPI>(a, s);
     else
       launch_f16<EPI, RLHF_GEMM_MT, RLHF_GEMM_NT, RLHF_GEMM_PF, RLHF_GEMM_OCC>(a, s, a.out, 1);
@@ -646,6 +660,8 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
 hipError_t launch_gemm(int dtype, const GemmArgs& a, hipStream_t s) {
   if (a.M_max <= 0) return hipSuccess;
   if (dtype == 1 && (a.K % 8) != 0) return hipErrorInvalidValue;
+  if (dtype != 1 && (a.lda || a.ldw || a.bias2)) return hipErrorInvalidValue;
+  if (a.bias2 && !gemm_takes_bias2(dtype, a)) return hipErrorInvalidValue;
   switch (a.epilogue) {
     case EPI_BIAS: launch_epi<EPI_BIAS>(dtype, a, s); break;
     case EPI_BIAS_GELU: launch_epi<EPI_BIAS_GELU>(dtype, a, s); break;

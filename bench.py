@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="BASELINE config index 1..5 (default: the 2.8B target)")
     ap.add_argument("--batch", type=int, default=None, help="override the config's batch (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extra-score-shapes", action="store_true",
+                    help="also time score_sequences on the paper's other batch shapes: right-padded (B,638) and (B,2021)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (sequences are independent; see DESIGN.md on sharding); "
@@ -142,6 +144,31 @@ def main():
     torch.cuda.synchronize()
     signals_ms = e0.elapsed_time(e1) / reps
 
+    # The paper's other scoring shapes (reward-model batches of 638 tokens, long-context batches of 2021),
+    # right-padded with true lengths uniform in [L/4, L]; outside the headline metric.
+    extra = None
+    if a.extra_score_shapes:
+        extra = {}
+        for L, Bx in ((638, B), (2021, max(1, B // 4))):
+            g = np.random.default_rng(wl.data_seed + L)
+            xl = g.integers(L // 4, L + 1, Bx)
+            xt = g.integers(1, cfg.pad_id, (Bx, L)).astype(np.int32)
+            xm = (np.arange(L)[None, :] < xl[:, None]).astype(np.uint8)
+            xt[xm == 0] = cfg.pad_id
+            xt_d, xm_d = torch.from_numpy(xt).cuda(), torch.from_numpy(xm).cuda()
+            pol.score_sequences(xt_d, xm_d, 1.0)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            pol.score_sequences(xt_d, xm_d, 1.0)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            n_ = xl.astype(np.float64)
+            Lc, d_, F_, V_ = cfg.n_layers, cfg.d_model, cfg.d_ff, cfg.vocab
+            fl = float((n_ * (2 * Lc * (4 * d_ * d_ + 2 * d_ * F_) + 2 * V_ * d_) + Lc * 4 * d_ * n_ * (n_ + 1) / 2).sum())
+            extra[f"B{Bx}xL{L}"] = {"ms": ms, "real_tok_s": float(xl.sum()) / (ms * 1e-3),
+                                    "mfma_frac": fl / (ms * 1e-3) / MFMA_PEAK}
+
     cpu = None
     if not a.no_cpu_baseline:
         cpu = cpu_baseline(cfg, w, queries, mask, wl, n_true)
@@ -166,7 +193,7 @@ def main():
         "rescoring_tok_s_padded": B * (wl.query_len + N) / (score_ms * 1e-3),
         "score_mfma_frac": wc["score_flops"] / (score_ms * 1e-3) / MFMA_PEAK,
         "roofline": roof, "rooflines": rooflines, "kernels_ms": kern, "profiled_step_ms": tot,
-        "ppo_signals_ms": signals_ms,
+        "ppo_signals_ms": signals_ms, "extra_score_shapes": extra,
         "cpu_baseline": cpu, "setup_s": setup_s,
     }
     print(json.dumps(out))

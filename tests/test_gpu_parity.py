@@ -183,6 +183,32 @@ def test_scoring_random_responses_right_padded(gpu, tiny_cfg):
     pol.close()
 
 
+@pytest.mark.parametrize("L,lo", [(638, 200), (2021, 900)])
+def test_scoring_long_right_padded_batches_bf16(gpu, L, lo):
+    """The paper's other scoring shapes: reward-model style batches of 638 tokens and long-context batches
+    of 2021 tokens, right-padded (Dataset Details, token-length tables), here at the 2.8B layer shape
+    with 2 layers.  Context lengths well beyond the rollout's 565 exercise more attention tiles per
+    sequence."""
+    O = _oracle()
+    cfg = WORKLOADS[4].model.with_(n_layers=2)
+    w = make_weights(cfg, 300 + L)
+    g = np.random.default_rng(L)
+    B = 5
+    lens = g.integers(lo, L + 1, B)
+    lens[0] = L
+    tokens = g.integers(1, cfg.pad_id, (B, L)).astype(np.int32)
+    mask = (np.arange(L)[None, :] < lens[:, None]).astype(np.uint8)
+    tokens[mask == 0] = cfg.pad_id
+    pol = gpu.Policy(cfg, w)
+    glp, gval = (x.cpu().numpy() for x in pol.score_sequences(tokens, mask, 1.0))
+    rows = [0, B - 1]
+    olp, oval = O.score_sequences(O.OracleModel(w, cfg), tokens[rows], mask[rows], 1.0)
+    np.testing.assert_allclose(glp[rows], olp, atol=TOL["bf16"], rtol=0)
+    np.testing.assert_allclose(gval[rows], oval, atol=TOL["bf16"] * max(1.0, float(np.abs(oval).max())), rtol=0)
+    assert (glp[mask == 0] == 0).all() and (gval[mask == 0] == 0).all() and (glp[:, 0] == 0).all()
+    pol.close()
+
+
 def test_results_are_deterministic_and_batch_independent(gpu, tiny_cfg):
     cfg = tiny_cfg.with_(dtype="bf16")
     w = make_weights(cfg, 7, variant="test")

@@ -86,6 +86,15 @@ def test_config2_pythia160m_full_batch(gpu):
     print("config 2: oracle/GPU token differences inside the near-tie band:", _grade_rows(wl, w, queries, mask, out, rows))
 
 
+@pytest.mark.timeout(600)
+def test_config3_pythia1b_full_batch(gpu):
+    """Head dimension 256 at the full batch of 256; the oracle replays the shortest row."""
+    wl, w, queries, mask, out = _run_full(gpu, 3)
+    _check_any_size_properties(wl, queries, mask, out)
+    rows = [int(np.argmin(mask.sum(1)))]
+    print("config 3: oracle/GPU token differences inside the near-tie band:", _grade_rows(wl, w, queries, mask, out, rows))
+
+
 @pytest.mark.timeout(900)
 def test_config4_pythia2p8b_full_batch(gpu):
     """The benchmark workload itself (batch 256, 32 layers); the oracle replays the shortest row."""

@@ -182,6 +182,9 @@ struct ScoreWs {
   Acts acts;
   char* kv;  // one layer: [2][H][Tmax][hd]
   float *val, *lp, *logits;
+  float *pmax = nullptr, *psum = nullptr, *ztgt = nullptr;  // fused LM head: per-part softmax statistics
+  int nparts = 0;
+  bool fused_lm = false;
   int* idx;
   int32_t* rows_dev;
   size_t Tmax;
@@ -195,8 +198,21 @@ ScoreWs carve_score(Carver& c, const rlhf_model_config& cfg, int B, int L, size_
   w.kv = (char*)c.take_bytes(2 * w.Tmax * cfg.d_model * esz);
   w.val = c.take<float>(w.Tmax);
   w.lp = c.take<float>(w.Tmax);
+  // the LM head either keeps the logits in registers and leaves per-part statistics (large batches),
+  // or materialises them for a chunk of rows at a time
+  GemmArgs lf;
+  lf.A = nullptr; lf.W = nullptr; lf.bias = nullptr; lf.out = nullptr;
+  lf.M_max = (int)w.Tmax; lf.M_dev = nullptr;
+  lf.N = cfg.vocab; lf.K = cfg.d_model; lf.ldo = cfg.vocab; lf.epilogue = EPI_LSE;
+  w.fused_lm = gemm_takes_lse(cfg.dtype, lf);
   w.chunk = (int)std::min<size_t>(w.Tmax, kLogitChunk);
-  w.logits = c.take<float>((size_t)w.chunk * cfg.vocab);
+  w.logits = w.fused_lm ? nullptr : c.take<float>((size_t)w.chunk * cfg.vocab);
+  w.nparts = 2 * ((cfg.vocab + 255) / 256);  // two 128-column parts per 256-column GEMM tile
+  if (w.fused_lm) {
+    w.pmax = c.take<float>((size_t)w.nparts * w.Tmax);
+    w.psum = c.take<float>((size_t)w.nparts * w.Tmax);
+    w.ztgt = c.take<float>(w.Tmax);
+  }
   w.idx = c.take<int>(w.Tmax);
   w.rows_dev = c.take<int32_t>(2 * w.Tmax);
   return w;
@@ -684,7 +700,23 @@ int score_sequences(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, 
   LAUNCH("final_ln", launch_final_ln(dt, ws.acts.x, nullptr, 0, Tmax, m.total, d, c.ln_eps, h->w.lnf_g,
                                      h->w.lnf_b, ws.acts.a, out_values ? h->w.value_w : nullptr, h->w.value_b,
                                      ws.val, s));
-  for (int t0 = 0; t0 < Tmax; t0 += ws.chunk) {
+  // LM head + log-softmax.  With enough rows for the large-M kernel the logits never leave the
+  // accumulators: its epilogue reduces every 128-column part of a row to (max, sum of exp) and
+  // picks out the target token's logit, and a small kernel combines the parts.  Otherwise the
+  // logits of a chunk of rows are materialised and reduced by a second kernel.
+  LseArgs la;
+  la.tok = m.tok; la.pos = m.pos; la.T_dev = m.total; la.inv_temperature = 1.0f / temperature;
+  la.pmax = ws.pmax; la.psum = ws.psum; la.ztgt = ws.ztgt; la.stride = Tmax; la.vocab = c.vocab;
+  GemmArgs lf;
+  lf.A = ws.acts.a; lf.W = h->embed_out_mm; lf.bias = nullptr; lf.out = nullptr;
+  lf.M_max = Tmax; lf.M_dev = m.total; lf.M_sub = 0;
+  lf.N = c.vocab; lf.K = d; lf.ldo = c.vocab; lf.epilogue = EPI_LSE; lf.lse = &la;
+  const bool fused_lm = ws.fused_lm;
+  if (fused_lm) {
+    LAUNCH("gemm_lm_head", launch_gemm(dt, lf, s));
+    LAUNCH("lse_gather", launch_lse_combine(la, Tmax, ws.nparts, ws.lp, s));
+  }
+  for (int t0 = 0; t0 < Tmax && !fused_lm; t0 += ws.chunk) {
     const int rows = std::min(ws.chunk, Tmax - t0);
     GemmArgs lm;
     lm.A = (const char*)ws.acts.a + (size_t)t0 * d * h->esz;

@@ -74,8 +74,31 @@ enum Epilogue {
   EPI_BIAS = 0,         // out[T]   = acc + bias
   EPI_BIAS_GELU = 1,    // out[T]   = gelu_erf(acc + bias)
   EPI_BIAS_RESADD = 2,  // out[f32] += acc + bias      (residual stream update, in place)
-  EPI_F32 = 3           // out[f32] = acc              (logits)
+  EPI_F32 = 3,          // out[f32] = acc              (logits)
+  EPI_LSE = 4           // nothing stored but per-row softmax statistics of acc/T (scoring LM head)
 };
+
+// EPI_LSE: the product is a [rows, vocab] logits matrix that is never stored.  Each 128-column part p
+// of packed row t leaves max_v z and sum_v exp(z - max) (z = logit / temperature) in pmax/psum
+// [p * stride + t]; the part that holds the row's target token (the next token of the same
+// sequence) also leaves its z in ztgt[t].  launch_lse_combine turns these into log-probabilities.
+struct LseArgs {
+  const int* tok;     // [rows] packed token ids
+  const int* pos;     // [rows] packed positions (pos[t+1] == pos[t] + 1 <=> same sequence)
+  const int* T_dev;   // number of packed rows
+  float inv_temperature;
+  float* pmax;
+  float* psum;
+  float* ztgt;
+  int stride;         // rows_max
+  int vocab;
+};
+// lp_packed[t + 1] = ztgt[t] - logsumexp over the nparts parts, for every t whose successor is in
+// the same sequence.
+hipError_t launch_lse_combine(const LseArgs& a, int rows_max, int nparts, float* lp_packed, hipStream_t s);
+// True when launch_gemm would take EPI_LSE for these arguments (large-M fp16 kernel only).
+struct GemmArgs;
+bool gemm_takes_lse(int dtype, const GemmArgs& a);
 
 struct GemmArgs {
   const void* A;      // [M, K] activations, row-major, Mode::A
@@ -90,6 +113,7 @@ struct GemmArgs {
   void* splitk_ws = nullptr;   // fp32 scratch for split-K partial sums (decode-sized M), or null
   size_t splitk_ws_bytes = 0;
   int phase = 0;               // split-K only: 0 = GEMM + reduce, 1 = partial sums only, 2 = reduce only
+  const struct LseArgs* lse = nullptr;  // EPI_LSE only
   int lda = 0, ldw = 0;        // row strides of A and W in elements (0: K); fp16 kernels only
   const void* bias2 = nullptr; // second bias added like the first; large-M fp16 kernel only
 };

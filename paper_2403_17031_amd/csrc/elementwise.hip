@@ -907,6 +907,29 @@ hipError_t launch_lse_gather(const float* logits, int rows_max, int t0, const in
   return hipGetLastError();
 }
 
+// Scoring with the fused LM head: one thread per packed row combines the per-part statistics.
+__global__ void __launch_bounds__(256)
+    lse_combine_kernel(LseArgs a, int nparts, float* __restrict__ lp_packed) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  const int T = *a.T_dev;
+  if (t + 1 >= T) return;
+  if (a.pos[t + 1] != a.pos[t] + 1) return;  // t is the last token of its sequence: nothing to predict
+  float m = -INFINITY;
+  for (int p = 0; p < nparts; ++p) m = fmaxf(m, a.pmax[(size_t)p * a.stride + t]);
+  float s = 0.f;
+  for (int p = 0; p < nparts; ++p) {
+    const float pm = a.pmax[(size_t)p * a.stride + t];
+    if (pm > -INFINITY) s += a.psum[(size_t)p * a.stride + t] * expf(pm - m);
+  }
+  lp_packed[t + 1] = a.ztgt[t] - (m + logf(s));
+}
+
+hipError_t launch_lse_combine(const LseArgs& a, int rows_max, int nparts, float* lp_packed, hipStream_t s) {
+  if (rows_max <= 0) return hipSuccess;
+  hipLaunchKernelGGL(lse_combine_kernel, dim3((rows_max + 255) / 256), dim3(256), 0, s, a, nparts, lp_packed);
+  return hipGetLastError();
+}
+
 __global__ void unpack_scores_kernel(const float* __restrict__ lp_packed, const float* __restrict__ val_packed,
                                      int L, const int* __restrict__ start, const int* __restrict__ len,
                                      const int* __restrict__ cu, float* __restrict__ out_lp,

@@ -326,7 +326,8 @@ template <int EPI>
 __global__ void __launch_bounds__(256, 1)
     gemm_f16_dma_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
                         void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
-                        int ldo, int nb_m, int nb_n, int lda, int ldw, const bf16_t* __restrict__ bias2) {
+                        int ldo, int nb_m, int nb_n, int lda, int ldw, const bf16_t* __restrict__ bias2,
+                        LseArgs lse) {
   constexpr int TM = 256, TN = 256, MT = 4, NT = 4;
   __shared__ __attribute__((aligned(16))) uint16_t lds0[DSTAGE];
   __shared__ __attribute__((aligned(16))) uint16_t lds1[DSTAGE];
@@ -443,6 +444,52 @@ __global__ void __launch_bounds__(256, 1)
 #ifdef RLHF_ABL_NOEPI
   if (M > 0) { if (acc[0][0][0] == 1.2345f) ((float*)out)[0] = acc[1][1][1] + acc[2][2][2] + acc[3][3][3]; return; }
 #endif
+  if (EPI == EPI_LSE) {
+    // ---- scoring LM head: the logits stay in the accumulators.  A lane holds, for each of its 4
+    //      rows (32*i + lane%32), 64 of the wave's 128 columns (the other 64 are in lane ^ 32):
+    //      running max and sum of exp over them, combined across the two half-waves, plus the
+    //      target token's z if its column is among this lane's.
+    const int part = 2 * tn + (wave & 1);
+    const int T = *lse.T_dev;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const int tr = M_sub + m0 + wm + 32 * i + l32;  // packed row
+      const bool row_ok = m0 + wm + 32 * i + l32 < M;
+      int tcol = -1;  // target column relative to this wave's first column, or out of range
+      if (row_ok && tr + 1 < T && lse.pos[tr + 1] == lse.pos[tr] + 1) tcol = lse.tok[tr + 1] - (n0 + wn);
+      float m = -INFINITY, zt = 0.f;
+      bool has_t = false;
+      float z[NT][16];
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int col = 32 * j + 8 * (e >> 2) + 4 * hf + (e & 3);
+          float v = acc[j][i][e] * lse.inv_temperature;
+          if (n0 + wn + col >= N) v = -INFINITY;
+          if (col == tcol) { zt = v; has_t = true; }
+          z[j][e] = v;
+          m = fmaxf(m, v);
+        }
+      m = fmaxf(m, __shfl_xor(m, 32, 64));
+      float sum = 0.f;
+      if (m > -INFINITY) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) sum += __expf(z[j][e] - m);
+      }
+      sum += __shfl_xor(sum, 32, 64);
+      if (row_ok) {
+        if (hf == 0) {
+          lse.pmax[(size_t)part * lse.stride + tr] = m;
+          lse.psum[(size_t)part * lse.stride + tr] = sum;
+        }
+        if (has_t) lse.ztgt[tr] = zt;
+      }
+    }
+    return;
+  }
   // ---- epilogue.  In the accumulator layout a lane owns 4 consecutive columns of ONE row, so a
   //      direct store touches 32 rows with 8-16 bytes each -- partial-line writes that the memory
   //      system handles an order of magnitude slower than full lines.  Each wave therefore
@@ -560,7 +607,8 @@ static void launch_f16_dma(const GemmArgs& a, hipStream_t s) {
   const int per_xcd = (nb_m * nb_n + 7) / 8;
   hipLaunchKernelGGL(gemm_f16_dma_kernel<EPI>, dim3(per_xcd * 8), dim3(256), 0, s, (const half_t*)a.A,
                      (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
-                     nb_m, nb_n, a.lda ? a.lda : a.K, a.ldw ? a.ldw : a.K, (const bf16_t*)a.bias2);
+                     nb_m, nb_n, a.lda ? a.lda : a.K, a.ldw ? a.ldw : a.K, (const bf16_t*)a.bias2,
+                     a.lse ? *a.lse : LseArgs{});
 }
 
 #ifndef RLHF_GEMM_DMA
@@ -627,6 +675,7 @@ static bool takes_dma(const GemmArgs& a) {
          (lda % 8) == 0 && (ldw % 8) == 0 && std::max((size_t)a.M_max * lda, (size_t)a.N * ldw) < (1ull << 32);
 }
 bool gemm_takes_bias2(int dtype, const GemmArgs& a) { return dtype == 1 && takes_dma(a); }
+bool gemm_takes_lse(int dtype, const GemmArgs& a) { return dtype == 1 && takes_dma(a); }
 
 template <int EPI>
 static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
@@ -667,6 +716,10 @@ hipError_t launch_gemm(int dtype, const GemmArgs& a, hipStream_t s) {
     case EPI_BIAS_GELU: launch_epi<EPI_BIAS_GELU>(dtype, a, s); break;
     case EPI_BIAS_RESADD: launch_epi<EPI_BIAS_RESADD>(dtype, a, s); break;
     case EPI_F32: launch_epi<EPI_F32>(dtype, a, s); break;
+    case EPI_LSE:
+      if (!a.lse || !gemm_takes_lse(dtype, a)) return hipErrorInvalidValue;
+      launch_f16_dma<EPI_LSE>(a, s);
+      break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -23,7 +23,9 @@
  *     calls do not synchronise with the host: outputs are valid once the stream has run the call's
  *     work.  Sizes that depend on the mask (number of real tokens) stay on the device.
  *   - Results are deterministic functions of the inputs: no floating-point atomics are used.
- *   - Calls that share a workspace must not overlap in time.
+ *   - Calls that share a workspace, or a handle (it owns a helper stream and events on which parts of
+ *     the decode loop run next to the caller's stream, joined again before the call's work ends), must
+ *     not overlap in time.
  */
 #ifndef RLHF_ROLLOUT_H
 #define RLHF_ROLLOUT_H

@@ -307,16 +307,6 @@ __global__ void __launch_bounds__(256)
 // global chunk so that the linear LDS image is the XOR-swizzled layout the fragment reads expect
 // (conflict-free ds_read_b128).
 // =================================================================================================
-#ifdef RLHF_ABL_NOSTORE
-#define RLHF_ABL_NOSTORE_COND &&v[0] == 0x12345678u
-#else
-#define RLHF_ABL_NOSTORE_COND
-#endif
-#ifdef RLHF_ABL_SAMEK
-#define RLHF_ABL_K(k) 0  // timing experiment only: every k-step re-reads the first tile
-#else
-#define RLHF_ABL_K(k) (k)
-#endif
 #define RLHF_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define RLHF_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 constexpr int DK = 64;                      // K depth of one stage: 128 bytes per tile row
@@ -360,7 +350,7 @@ __global__ void __launch_bounds__(256, 1)
   }
   const half_t* gbase = wave < 2 ? A : W;  // waves 0,1 load A rows, waves 2,3 load W rows
   auto load_one = [&](uint16_t* stage, int k0, int i) {
-    __builtin_amdgcn_global_load_lds(RLHF_GLOBAL_PTR(gbase + goff[i] + RLHF_ABL_K(k0)),
+    __builtin_amdgcn_global_load_lds(RLHF_GLOBAL_PTR(gbase + goff[i] + k0),
                                      RLHF_LDS_PTR(stage + (8 * (16 * wave + i)) * DK), 16, 0, 0);
   };
 
@@ -441,9 +431,6 @@ __global__ void __launch_bounds__(256, 1)
   __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): the surplus loads have landed too
   __syncthreads();
 
-#ifdef RLHF_ABL_NOEPI
-  if (M > 0) { if (acc[0][0][0] == 1.2345f) ((float*)out)[0] = acc[1][1][1] + acc[2][2][2] + acc[3][3][3]; return; }
-#endif
   if (EPI == EPI_LSE) {
     // ---- scoring LM head: the logits stay in the accumulators.  A lane holds, for each of its 4
     //      rows (32*i + lane%32), 64 of the wave's 128 columns (the other 64 are in lane ^ 32):
@@ -550,7 +537,7 @@ __global__ void __launch_bounds__(256, 1)
       const int row = it * 4 + rd_row;
       const int grow = m0 + wm + row;
       const u32x4_t v = *(const u32x4_t*)(ep + row * 128 + ((rd_c ^ (row & 15)) << 3));
-      if (grow < M && gcol < N RLHF_ABL_NOSTORE_COND) *(u32x4_t*)((half_t*)out + (size_t)grow * ldo + gcol) = v;
+      if (grow < M && gcol < N) *(u32x4_t*)((half_t*)out + (size_t)grow * ldo + gcol) = v;
     }
   } else {
     float* epf = (float*)ep;  // 128 rows x 64 floats per pass

@@ -1,0 +1,107 @@
+// Stand-alone driver for the library's GEMM path at the per-layer shapes of a model: runs QKV, FC1 and
+// the fused out-projection + FC2 product on seeded random operands, checks sampled outputs against a
+// double-precision dot product on the host, times them with HIP events, and runs a plain copy kernel of
+// known size next to them.  It exists because hardware counters (rocprofv3 --pmc) can be collected on a
+// small native process where they cannot on the Python benchmark; the copy kernel is the yardstick the
+// FETCH_SIZE / WRITE_SIZE readings are scaled by.
+//   usage: gemm_driver [M=83373] [reps=3] [d_model=2560]
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "common.h"
+
+using namespace rlhf;
+
+#define CK(x)                                                                               \
+  do {                                                                                      \
+    hipError_t e_ = (x);                                                                    \
+    if (e_ != hipSuccess) {                                                                 \
+      printf("HIP error %s at %s:%d\n", hipGetErrorString(e_), __FILE__, __LINE__);         \
+      return 1;                                                                             \
+    }                                                                                       \
+  } while (0)
+
+static uint16_t f2h(float f) { _Float16 h = (_Float16)f; uint16_t u; memcpy(&u, &h, 2); return u; }
+static float h2f(uint16_t u) { _Float16 h; memcpy(&h, &u, 2); return (float)h; }
+static uint16_t f2bf(float f) { unsigned u; memcpy(&u, &f, 4); u += 0x7FFF + ((u >> 16) & 1); return (uint16_t)(u >> 16); }
+static float bf2f(uint16_t h) { unsigned u = ((unsigned)h) << 16; float f; memcpy(&f, &u, 4); return f; }
+
+// yardstick: reads `n` 16-byte words and writes them elsewhere
+typedef __attribute__((ext_vector_type(4))) unsigned u4_t;
+__global__ void __launch_bounds__(256) copy_yardstick_kernel(const u4_t* __restrict__ src, u4_t* __restrict__ dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t st = (size_t)gridDim.x * 256;
+  for (; i < n; i += st) dst[i] = src[i];
+}
+
+int main(int argc, char** argv) {
+  const int M = argc > 1 ? atoi(argv[1]) : 83373;
+  const int reps = argc > 2 ? atoi(argv[2]) : 3;
+  const int d = argc > 3 ? atoi(argv[3]) : 2560, F = 4 * d;
+  if (M <= 512 || d % 128 != 0) { printf("M must exceed 512 and d_model be a multiple of 128\n"); return 1; }
+  struct Shape { const char* name; int N, K, epi; bool bias2; } shapes[] = {
+      {"qkv", 3 * d, d, EPI_BIAS, false}, {"fc1", F, d, EPI_BIAS_GELU, false}, {"out+fc2", d, d + F, EPI_BIAS_RESADD, true}};
+  const size_t maxA = (size_t)M * (d + F), maxW = (size_t)F * d * 3, maxO = (size_t)M * F;
+  std::vector<uint16_t> hA(maxA), hW(maxW), hb(F), hb2(F);
+  srand(1);
+  for (auto& x : hA) x = f2h((rand() % 2001 - 1000) / 1000.0f);
+  for (auto& x : hW) x = f2h((rand() % 2001 - 1000) / 25000.0f);
+  for (auto& x : hb) x = f2bf((rand() % 2001 - 1000) / 5000.0f);
+  for (auto& x : hb2) x = f2bf((rand() % 2001 - 1000) / 5000.0f);
+  uint16_t *dA, *dW, *db, *db2; void* dO; int* dM;
+  CK(hipMalloc(&dA, maxA * 2)); CK(hipMalloc(&dW, maxW * 2)); CK(hipMalloc(&db, F * 2)); CK(hipMalloc(&db2, F * 2));
+  CK(hipMalloc(&dO, maxO * 4)); CK(hipMalloc(&dM, 4));
+  CK(hipMemcpy(dA, hA.data(), maxA * 2, hipMemcpyHostToDevice)); CK(hipMemcpy(dW, hW.data(), maxW * 2, hipMemcpyHostToDevice));
+  CK(hipMemcpy(db, hb.data(), F * 2, hipMemcpyHostToDevice)); CK(hipMemcpy(db2, hb2.data(), F * 2, hipMemcpyHostToDevice));
+  CK(hipMemcpy(dM, &M, 4, hipMemcpyHostToDevice));
+  hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+  int bad = 0;
+  for (auto& s : shapes) {
+    GemmArgs g;
+    g.A = dA; g.W = dW; g.bias = db; g.bias2 = s.bias2 ? db2 : nullptr; g.out = dO;
+    g.M_max = M + 1000; g.M_dev = dM; g.N = s.N; g.K = s.K; g.ldo = s.N; g.epilogue = s.epi;
+    CK(hipMemset(dO, 0, maxO * 4));
+    CK(launch_gemm(1, g, 0)); CK(hipDeviceSynchronize());
+    const bool f32out = s.epi == EPI_BIAS_RESADD;
+    std::vector<uint16_t> ho16; std::vector<float> ho32;
+    if (f32out) { ho32.resize((size_t)M * s.N); CK(hipMemcpy(ho32.data(), dO, ho32.size() * 4, hipMemcpyDeviceToHost)); }
+    else { ho16.resize((size_t)M * s.N); CK(hipMemcpy(ho16.data(), dO, ho16.size() * 2, hipMemcpyDeviceToHost)); }
+    double maxerr = 0;
+    for (int t = 0; t < 400; ++t) {
+      const int r = t < 8 ? (t % 2 ? M - 1 : 0) : rand() % M, c = t < 8 ? (t % 4 < 2 ? 0 : s.N - 1) : rand() % s.N;
+      double acc = 0;
+      for (int k = 0; k < s.K; ++k) acc += (double)h2f(hA[(size_t)r * s.K + k]) * h2f(hW[(size_t)c * s.K + k]);
+      acc += bf2f(hb[c]) + (s.bias2 ? bf2f(hb2[c]) : 0.f);
+      if (s.epi == EPI_BIAS_GELU) acc = 0.5 * acc * (1 + erf(acc / sqrt(2.0)));
+      const double got = f32out ? ho32[(size_t)r * s.N + c] : h2f(ho16[(size_t)r * s.N + c]);
+      const double tol = f32out ? 4e-3 : 8e-3 * fmax(1.0, fabs(acc));
+      const double err = fabs(got - acc);
+      if (err > maxerr) maxerr = err;
+      if (err > tol) { printf("MISMATCH %s r=%d c=%d got %f want %f\n", s.name, r, c, got, acc); ++bad; break; }
+    }
+    CK(hipEventRecord(e0, 0));
+    for (int i = 0; i < reps; ++i) CK(launch_gemm(1, g, 0));
+    CK(hipEventRecord(e1, 0)); CK(hipEventSynchronize(e1));
+    float ms; CK(hipEventElapsedTime(&ms, e0, e1)); ms /= reps;
+    const double fl = 2.0 * M * s.N * s.K;
+    const double bytes = 2.0 * ((double)M * s.K + (double)s.N * s.K) + (f32out ? 8.0 : 2.0) * M * s.N;
+    printf("%-8s M=%d N=%d K=%d: %.3f ms  %.1f TFLOP/s  algorithmic HBM bytes %.3f GB  max |err| %.2e\n", s.name, M, s.N,
+           s.K, ms, fl / ms / 1e9, bytes / 1e9, maxerr);
+  }
+  {
+    const size_t n = (size_t)1 << 26;  // 1 GiB read + 1 GiB written
+    u4_t *src = (u4_t*)dA, *dst = (u4_t*)dO;
+    if (maxA * 2 < n * 16 || maxO * 4 < n * 16) { printf("copy yardstick skipped: buffers smaller than 1 GiB\n"); }
+    else {
+      CK(hipEventRecord(e0, 0));
+      for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(copy_yardstick_kernel, dim3(8192), dim3(256), 0, 0, src, dst, n);
+      CK(hipEventRecord(e1, 0)); CK(hipEventSynchronize(e1));
+      float ms; CK(hipEventElapsedTime(&ms, e0, e1)); ms /= reps;
+      printf("copy yardstick: 1.074 GB read + 1.074 GB written per launch, %.3f ms (%.2f TB/s)\n", ms, 2.0 * n * 16 / ms / 1e9);
+    }
+  }
+  return bad ? 2 : 0;
+}

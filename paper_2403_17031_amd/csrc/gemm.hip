@@ -312,13 +312,20 @@ __global__ void __launch_bounds__(256)
 constexpr int DK = 64;                      // K depth of one stage: 128 bytes per tile row
 constexpr int DSTAGE = (256 + 256) * DK;    // halfs per stage (64 KB)
 
-template <int EPI>
-__global__ void __launch_bounds__(256, 1)
+template <int EPI, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES, 1)
     gemm_f16_dma_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
                         void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
                         int ldo, int nb_m, int nb_n, int lda, int ldw, const bf16_t* __restrict__ bias2,
                         LseArgs lse) {
-  constexpr int TM = 256, TN = 256, MT = 4, NT = 4;
+  // WAVES = 4: one wave per SIMD, each 128 x 128 of the tile (256 accumulator registers).
+  // WAVES = 8: two waves per SIMD, each 128 x 64 (128 accumulator registers): what one wave cannot
+  // overlap (waits, epilogue arithmetic against stores) the SIMD's other wave fills.
+  constexpr int TM = 256, TN = 256, MT = 4, NT = WAVES == 8 ? 2 : 4;
+  constexpr int WN = 32 * NT;         // columns per wave
+  constexpr int NWN = TN / WN;        // waves along N
+  constexpr int NLD = 64 / WAVES;     // tile loads per wave per stage
+  constexpr int NMF = MT * NT;        // matrix instructions per wave per sub-step
   __shared__ __attribute__((aligned(16))) uint16_t lds0[DSTAGE];
   __shared__ __attribute__((aligned(16))) uint16_t lds1[DSTAGE];
   const int M = M_dev ? min(M_max, *M_dev - M_sub) : M_max;
@@ -336,22 +343,22 @@ __global__ void __launch_bounds__(256, 1)
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps LDS bases in SGPRs
-  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+  const int wm = (wave / NWN) * 128, wn = (wave % NWN) * WN;
 
-  // ---- direct loads: a stage row is 128 B (8 chunks); wave-load j (= 16*wave + i, i < 16) fills
+  // ---- direct loads: a stage row is 128 B (8 chunks); wave-load j (= NLD*wave + i, i < NLD) fills
   //      rows 8j .. 8j+7 (rows < 256: A, else W); lane l lands at row 8j + l/8, physical chunk l%8,
   //      and therefore fetches logical chunk (l%8) ^ ((row>>1)&7)
-  uint32_t goff[16];
+  uint32_t goff[NLD];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int row = 8 * (16 * wave + i) + (lane >> 3);
+  for (int i = 0; i < NLD; ++i) {
+    const int row = 8 * (NLD * wave + i) + (lane >> 3);
     const int c = (lane & 7) ^ ((row >> 1) & 7);
     goff[i] = (uint32_t)((row < TM ? min(m0 + row, M - 1) * lda : min(n0 + row - TM, N - 1) * ldw) + c * 8);
   }
-  const half_t* gbase = wave < 2 ? A : W;  // waves 0,1 load A rows, waves 2,3 load W rows
+  const half_t* gbase = wave < WAVES / 2 ? A : W;  // the first half of the waves loads A rows, the second W rows
   auto load_one = [&](uint16_t* stage, int k0, int i) {
     __builtin_amdgcn_global_load_lds(RLHF_GLOBAL_PTR(gbase + goff[i] + k0),
-                                     RLHF_LDS_PTR(stage + (8 * (16 * wave + i)) * DK), 16, 0, 0);
+                                     RLHF_LDS_PTR(stage + (8 * (NLD * wave + i)) * DK), 16, 0, 0);
   };
 
   const int l32 = lane & 31, hf = lane >> 5;
@@ -377,15 +384,15 @@ __global__ void __launch_bounds__(256, 1)
     if (q < MT) fa[q] = *(const f16x8_t*)(ls + a_off + q * 32 * DK + ch);
     else fw[q - MT] = *(const f16x8_t*)(ls + w_off + (q - MT) * 32 * DK + ch);
   };
-  // 16 matrix instructions on (FA, FW); after the n-th, fragment read n (n < 8) of the next
+  // NMF matrix instructions on (FA, FW); after the n-th, fragment read n (n < MT + NT) of the next
   // sub-step from (LS, CH) into (GA, GW) and, if LOAD, tile load n of the stage at K offset KL
 #define RLHF_SUB(FA, FW, LS, CH, GA, GW, LOAD, LSTAGE, KL)                                        \
-  _Pragma("unroll") for (int n = 0; n < 16; ++n) {                                                \
+  _Pragma("unroll") for (int n = 0; n < NMF; ++n) {                                               \
     acc[n >> 2][n & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(FW[n >> 2], FA[n & 3],            \
                                                                 acc[n >> 2][n & 3], 0, 0, 0);     \
     __builtin_amdgcn_sched_barrier(0);                                                            \
-    if (n < 8) frag_one(LS, CH, n, GA, GW);                                                       \
-    if (LOAD) load_one(LSTAGE, KL, n);                                                            \
+    if (n < MT + NT) frag_one(LS, CH, n, GA, GW);                                                 \
+    if (LOAD && n < NLD) load_one(LSTAGE, KL, n);                                                 \
     __builtin_amdgcn_sched_barrier(0);                                                            \
   }
   // vmcnt(0) lgkmcnt(0) + barrier: every wave's tile loads have landed and every wave has finished
@@ -415,12 +422,12 @@ __global__ void __launch_bounds__(256, 1)
   // loop is branch-free: past the end the final tile is re-issued into a stage nobody reads.
   const int nk = K / DK;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) load_one(lds0, 0, i);
+  for (int i = 0; i < NLD; ++i) load_one(lds0, 0, i);
 #pragma unroll
-  for (int i = 0; i < 16; ++i) load_one(lds1, min(1, nk - 1) * DK, i);
+  for (int i = 0; i < NLD; ++i) load_one(lds1, min(1, nk - 1) * DK, i);
   RLHF_WAIT_BARRIER()
 #pragma unroll
-  for (int q = 0; q < 8; ++q) frag_one(lds0, ch0, q, fa0, fw0);
+  for (int q = 0; q < MT + NT; ++q) frag_one(lds0, ch0, q, fa0, fw0);
   for (int kt = 0; kt < nk; kt += 2) {
     RLHF_STAGE(lds0, lds1, kt)
     RLHF_STAGE(lds1, lds0, kt + 1)
@@ -433,10 +440,10 @@ __global__ void __launch_bounds__(256, 1)
 
   if (EPI == EPI_LSE) {
     // ---- scoring LM head: the logits stay in the accumulators.  A lane holds, for each of its 4
-    //      rows (32*i + lane%32), 64 of the wave's 128 columns (the other 64 are in lane ^ 32):
+    //      rows (32*i + lane%32), half of the wave's WN columns (the other half is in lane ^ 32):
     //      running max and sum of exp over them, combined across the two half-waves, plus the
     //      target token's z if its column is among this lane's.
-    const int part = 2 * tn + (wave & 1);
+    const int part = NWN * tn + (wave % NWN);
     const int T = *lse.T_dev;
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
@@ -484,8 +491,11 @@ __global__ void __launch_bounds__(256, 1)
   //      16 bytes per lane, 16 lanes per 256-byte row segment.  The LDS image is XOR-swizzled by
   //      row (chunk ^ (row & 15)); accumulator tiles are addressed through compile-time indices
   //      (a loop the compiler declines to unroll would spill all 256 accumulators to scratch).
-  uint16_t* ep = (wave & 2 ? lds1 : lds0) + (wave & 1) * (DSTAGE / 2);  // 32 KB per wave
-  const int rd_row = lane >> 4, rd_c = lane & 15;
+  constexpr int EPW = 128 * WN;  // halfs of LDS per wave: its tile as fp16, or half of it as fp32
+  uint16_t* ep = wave * EPW < DSTAGE ? lds0 + wave * EPW : lds1 + (wave * EPW - DSTAGE);
+  constexpr int CH = WN / 8;     // 16-byte chunks per fp16 row of the wave's tile = lanes per row on the way out
+  constexpr int RPI = 64 / CH;   // rows per store instruction
+  const int rd_row = lane / CH, rd_c = lane % CH;
   // bias of this lane's 64 columns: 16 eight-byte loads issued together (N is a multiple of 8 here
   // and every column group starts at a multiple of 4, so a group is inside or outside as a whole)
   f32x4_t bias_v[NT][4];
@@ -520,7 +530,7 @@ __global__ void __launch_bounds__(256, 1)
           const float v = acc[j][i][4 * g + u] + bias_v[j][g][u];
           h[u] = from_f32<half_t>(EPI == EPI_BIAS_GELU ? gelu_f16out(v) : v);
         }
-        *(f16x4_t*)(ep + row * 128 + (((4 * j + g) ^ (row & 15)) << 3) + 4 * hf) = h;
+        *(f16x4_t*)(ep + row * WN + (((4 * j + g) ^ (row & (CH - 1))) << 3) + 4 * hf) = h;
       }
     };
 #define RLHF_ROW(J)                                                                        \
@@ -528,29 +538,32 @@ __global__ void __launch_bounds__(256, 1)
   put(std::integral_constant<int, J>{}, std::integral_constant<int, 1>{});                 \
   put(std::integral_constant<int, J>{}, std::integral_constant<int, 2>{});                 \
   put(std::integral_constant<int, J>{}, std::integral_constant<int, 3>{});
-    RLHF_ROW(0) RLHF_ROW(1) RLHF_ROW(2) RLHF_ROW(3)
+    RLHF_ROW(0) RLHF_ROW(1)
+    if constexpr (NT > 2) { RLHF_ROW(NT - 2) RLHF_ROW(NT - 1) }
 #undef RLHF_ROW
     __syncthreads();
     const int gcol = n0 + wn + rd_c * 8;
 #pragma unroll 8
-    for (int it = 0; it < 32; ++it) {
-      const int row = it * 4 + rd_row;
+    for (int it = 0; it < 128 / RPI; ++it) {
+      const int row = it * RPI + rd_row;
       const int grow = m0 + wm + row;
-      const u32x4_t v = *(const u32x4_t*)(ep + row * 128 + ((rd_c ^ (row & 15)) << 3));
+      const u32x4_t v = *(const u32x4_t*)(ep + row * WN + ((rd_c ^ (row & (CH - 1))) << 3));
       if (grow < M && gcol < N) *(u32x4_t*)((half_t*)out + (size_t)grow * ldo + gcol) = v;
     }
   } else {
-    float* epf = (float*)ep;  // 128 rows x 64 floats per pass
+    float* epf = (float*)ep;   // 128 rows x PC floats per pass
+    constexpr int PC = WN / 2;  // columns per pass; a row is PC/4 = CH 16-byte chunks, as in the fp16 case
+    constexpr int JP = NT / 2;  // accumulator tiles along N per pass
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
-      const int gcol = n0 + wn + 64 * hh + rd_c * 4;
-      // residual rows of this pass: all 32 loads are issued before the transpose, so their latency
+      const int gcol = n0 + wn + PC * hh + rd_c * 4;
+      // residual rows of this pass: all loads are issued before the transpose, so their latency
       // hides behind the LDS traffic
-      f32x4_t xv[32];
+      f32x4_t xv[128 / RPI];
       if (EPI == EPI_BIAS_RESADD) {
 #pragma unroll
-        for (int it = 0; it < 32; ++it) {
-          const int grow = m0 + wm + it * 4 + rd_row;
+        for (int it = 0; it < 128 / RPI; ++it) {
+          const int grow = m0 + wm + it * RPI + rd_row;
           if (grow < M && gcol < N) xv[it] = *(const f32x4_t*)((const float*)out + (size_t)grow * ldo + gcol);
         }
       }
@@ -561,8 +574,8 @@ __global__ void __launch_bounds__(256, 1)
         for (int g = 0; g < 4; ++g) {
           const f32x4_t v = {acc[j][i][4 * g] + bias_v[j][g][0], acc[j][i][4 * g + 1] + bias_v[j][g][1],
                              acc[j][i][4 * g + 2] + bias_v[j][g][2], acc[j][i][4 * g + 3] + bias_v[j][g][3]};
-          const int c = 8 * (j & 1) + 2 * g + hf;
-          *(f32x4_t*)(epf + row * 64 + ((c ^ (row & 15)) << 2)) = v;
+          const int c = 8 * (j % JP) + 2 * g + hf;
+          *(f32x4_t*)(epf + row * PC + ((c ^ (row & (CH - 1))) << 2)) = v;
         }
       };
 #define RLHF_ROW(J)                                                                        \
@@ -570,14 +583,18 @@ __global__ void __launch_bounds__(256, 1)
   put(std::integral_constant<int, J>{}, std::integral_constant<int, 1>{});                 \
   put(std::integral_constant<int, J>{}, std::integral_constant<int, 2>{});                 \
   put(std::integral_constant<int, J>{}, std::integral_constant<int, 3>{});
-      if (hh == 0) { RLHF_ROW(0) RLHF_ROW(1) } else { RLHF_ROW(2) RLHF_ROW(3) }
+      if constexpr (NT > 2) {
+        if (hh == 0) { RLHF_ROW(0) RLHF_ROW(1) } else { RLHF_ROW(NT - 2) RLHF_ROW(NT - 1) }
+      } else {
+        if (hh == 0) { RLHF_ROW(0) } else { RLHF_ROW(1) }
+      }
 #undef RLHF_ROW
       __syncthreads();
 #pragma unroll
-      for (int it = 0; it < 32; ++it) {
-        const int row = it * 4 + rd_row;
+      for (int it = 0; it < 128 / RPI; ++it) {
+        const int row = it * RPI + rd_row;
         const int grow = m0 + wm + row;
-        f32x4_t v = *(const f32x4_t*)(epf + row * 64 + ((rd_c ^ (row & 15)) << 2));
+        f32x4_t v = *(const f32x4_t*)(epf + row * PC + ((rd_c ^ (row & (CH - 1))) << 2));
         if (grow < M && gcol < N) {
           if (EPI == EPI_BIAS_RESADD) v += xv[it];
           *(f32x4_t*)((float*)out + (size_t)grow * ldo + gcol) = v;
@@ -592,7 +609,10 @@ template <int EPI>
 static void launch_f16_dma(const GemmArgs& a, hipStream_t s) {
   const int nb_m = (a.M_max + 255) / 256, nb_n = (a.N + 255) / 256;
   const int per_xcd = (nb_m * nb_n + 7) / 8;
-  hipLaunchKernelGGL(gemm_f16_dma_kernel<EPI>, dim3(per_xcd * 8), dim3(256), 0, s, (const half_t*)a.A,
+  // Eight waves measure 8-10 % faster than four on the layer shapes; the log-sum-exp epilogue keeps
+  // four, since its per-part statistics are laid out for 128-column parts.
+  constexpr int WV = EPI == EPI_LSE ? 4 : 8;
+  hipLaunchKernelGGL((gemm_f16_dma_kernel<EPI, WV>), dim3(per_xcd * 8), dim3(64 * WV), 0, s, (const half_t*)a.A,
                      (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
                      nb_m, nb_n, a.lda ? a.lda : a.K, a.ldw ? a.ldw : a.K, (const bf16_t*)a.bias2,
                      a.lse ? *a.lse : LseArgs{});

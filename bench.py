@@ -134,7 +134,8 @@ def main():
     roof = rooflines.get(dom) or rooflines.get("gemm") or {}
     roof = dict(roof, kernel=dom if dom in rooflines else "gemm")
 
-    # The signals PPO consumes next (reward assembly, GAE, advantage whitening) on this step's outputs.
+    # The signals PPO consumes next (reward assembly, GAE, advantage whitening, the clipped objective with its
+    # output gradients) on this step's outputs.
     # Outside the headline metric.  Stand-ins: the policy's own rescoring outputs serve as the reference
     # log-probs and the reward-model values (a second and third weight set would cost two more
     # score_sequences calls of the time reported as score_ms).
@@ -148,7 +149,10 @@ def main():
             e0.record()
         rew, _, _, kept = P.ppo_assemble_rewards(lps_d, lp_d, val_d, toks_d, Lq, cfg.eos_id, cfg.pad_id, 0.05)
         adv, ret = P.ppo_gae(rew, val_d, kept, 1.0, 0.95, value_offset=Lq - 1)
-        P.ppo_whiten(adv, kept)
+        wadv = P.ppo_whiten(adv, kept)
+        # the clipped objective and its gradient w.r.t. the model outputs, as in the first PPO epoch
+        # (new outputs = the rollout's own)
+        P.ppo_loss(lps_d, lps_d, wadv, val_d[:, Lq - 1:Lq - 1 + N], val_d[:, Lq - 1:Lq - 1 + N], ret, kept)
     e1.record()
     torch.cuda.synchronize()
     signals_ms = e0.elapsed_time(e1) / reps

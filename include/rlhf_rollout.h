@@ -153,6 +153,26 @@ int rlhf_ppo_gae(const float *rewards, const float *values, int64_t values_row_s
 int rlhf_ppo_whiten(const float *x, const int32_t *kept, int32_t B, int32_t N, int32_t shift_mean, float *out,
                     void *stream);
 
+/* The PPO objective on a rollout batch and its gradient with respect to the model's outputs (paper:
+ * PPO hyperparameter table -- policy clipping coefficient 0.2, value clipping coefficient 0.2, value
+ * function coefficient c1 = 0.1, value function loss clipping on; the formulas are the standard
+ * ones of that lineage).  Over the kept positions t < kept[b], n of them in the batch:
+ *   ratio = exp(new_logprobs - old_logprobs)
+ *   pg    = mean max(-A ratio, -A clip(ratio, 1-cliprange, 1+cliprange))
+ *   vf    = mean 0.5 max((V - R)^2, (clip(V, Vold - cliprange_value, Vold + cliprange_value) - R)^2)
+ *   loss  = pg + vf_coef * vf
+ * d_logprobs = d loss / d new_logprobs = -A ratio / n where the unclipped surrogate is the larger or
+ * equal one, else 0; d_values = vf_coef (V - R) / n where the unclipped square is the larger or equal
+ * one, else 0; both 0 at positions that are not kept.
+ * stats dev float [8]: loss, pg, vf, approx_kl = mean 0.5 (new - old)^2, fraction of tokens with the
+ * clipped surrogate strictly larger, same for the value term, mean ratio, n.  With n = 0 everything
+ * is 0.  All arrays dev float [B,N] over the response positions (contiguous), kept dev int32 [B];
+ * every pointer is required.  One launch on `stream`; sums in double in a fixed order. */
+int rlhf_ppo_loss(const float *new_logprobs, const float *old_logprobs, const float *advantages,
+                  const float *new_values, const float *old_values, const float *returns, const int32_t *kept,
+                  int32_t B, int32_t N, float cliprange, float cliprange_value, float vf_coef, float *d_logprobs,
+                  float *d_values, float *stats, void *stream);
+
 /* Debug / parity aid: raw (pre-temperature) fp32 logits of the same forward pass as
  * score_sequences at n (row, column) pairs.  rows_bt: HOST int32 [n, 2]; out_logits: dev float
  * [n, vocab].  Every pair must name a real position. */

@@ -12,4 +12,6 @@ from .binding import (  # noqa: F401
     ppo_assemble_rewards,
     ppo_gae,
     ppo_whiten,
+    ppo_loss,
+    PPO_LOSS_STATS,
 )

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "librlhf_rollout.so")
 EXPORTS = (
     "rlhf_create", "rlhf_destroy", "rlhf_workspace_bytes", "rollout_generate", "score_sequences",
     "rlhf_debug_logits_rows", "rlhf_profile_enable", "rlhf_profile_read", "rlhf_last_rollout_phases",
-    "rlhf_last_error", "rlhf_ppo_assemble_rewards", "rlhf_ppo_gae", "rlhf_ppo_whiten",
+    "rlhf_last_error", "rlhf_ppo_assemble_rewards", "rlhf_ppo_gae", "rlhf_ppo_whiten", "rlhf_ppo_loss",
 )
 
 _PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -65,6 +65,7 @@ def load_library():
     lib.rlhf_ppo_assemble_rewards.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, vp, vp, vp, vp, vp]
     lib.rlhf_ppo_gae.argtypes = [vp, vp, C.c_int64, vp, i32, i32, f32, f32, vp, vp, vp]
     lib.rlhf_ppo_whiten.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+    lib.rlhf_ppo_loss.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp, vp, vp]
     lib.rlhf_last_error.restype = C.c_char_p
     for n in EXPORTS:
         if n not in ("rlhf_destroy", "rlhf_last_error"):
@@ -305,3 +306,30 @@ def ppo_whiten(x, kept=None, shift_mean=True, device="cuda:0"):
         _check(lib.rlhf_ppo_whiten(xv.data_ptr(), None if k is None else k.data_ptr(), B, N, 1 if shift_mean else 0,
                                    out.data_ptr(), _cur_stream(torch, dev)))
     return out
+
+
+PPO_LOSS_STATS = ("loss", "pg_loss", "vf_loss", "approx_kl", "pg_clipfrac", "vf_clipfrac", "ratio_mean", "n_tokens")
+
+
+def ppo_loss(new_logprobs, old_logprobs, advantages, new_values, old_values, returns, kept, cliprange=0.2,
+             cliprange_value=0.2, vf_coef=0.1, device="cuda:0"):
+    """All arrays [B, N] over the response positions, kept int32 [B].  Returns (stats, d_logprobs,
+    d_values): stats a CUDA float tensor [8] in the order of PPO_LOSS_STATS, the gradients CUDA
+    tensors [B, N]."""
+    import torch
+    lib = load_library()
+    dev = torch.device(device)
+    arrs = [_dev_f32(torch, a, dev) for a in (new_logprobs, old_logprobs, advantages, new_values, old_values, returns)]
+    B, N = arrs[0].shape
+    if any(a.shape != (B, N) for a in arrs):
+        raise RlhfError("ppo_loss: all six arrays must be [B, N]")
+    k = _dev_i32(torch, kept, dev)
+    if k.shape[0] != B:
+        raise RlhfError("ppo_loss: kept must be [B]")
+    d_lp = torch.empty((B, N), dtype=torch.float32, device=dev)
+    d_v = torch.empty((B, N), dtype=torch.float32, device=dev)
+    stats = torch.empty(8, dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.rlhf_ppo_loss(*[a.data_ptr() for a in arrs], k.data_ptr(), B, N, cliprange, cliprange_value, vf_coef,
+                                 d_lp.data_ptr(), d_v.data_ptr(), stats.data_ptr(), _cur_stream(torch, dev)))
+    return stats, d_lp, d_v

@@ -423,6 +423,22 @@ int rlhf_ppo_whiten(const float* x, const int32_t* kept, int32_t B, int32_t N, i
   return RLHF_OK;
 }
 
+int rlhf_ppo_loss(const float* new_logprobs, const float* old_logprobs, const float* advantages,
+                  const float* new_values, const float* old_values, const float* returns, const int32_t* kept,
+                  int32_t B, int32_t N, float cliprange, float cliprange_value, float vf_coef, float* d_logprobs,
+                  float* d_values, float* stats, void* stream) {
+  if (!new_logprobs || !old_logprobs || !advantages || !new_values || !old_values || !returns || !kept ||
+      !d_logprobs || !d_values || !stats)
+    return fail(RLHF_EINVAL, "null pointer argument");
+  if (B <= 0 || N <= 0) return fail(RLHF_EINVAL, "batch and response length must be positive");
+  if (!(cliprange >= 0.f) || !(cliprange_value >= 0.f) || !std::isfinite(cliprange) || !std::isfinite(cliprange_value) ||
+      !std::isfinite(vf_coef))
+    return fail(RLHF_EINVAL, "clip ranges must be finite and >= 0, the value coefficient finite");
+  HIP_OK(launch_ppo_loss(new_logprobs, old_logprobs, advantages, new_values, old_values, returns, kept, B, N, cliprange,
+                         cliprange_value, vf_coef, d_logprobs, d_values, stats, (hipStream_t)stream));
+  return RLHF_OK;
+}
+
 int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, rlhf_handle** out) {
   if (out) *out = nullptr;
   if (!cfg || !w || !out) return fail(RLHF_EINVAL, "null argument");

@@ -230,6 +230,9 @@ hipError_t launch_ppo_gae(const float* rewards, const float* values, long vstrid
                           float gamma, float lam, float* adv, float* ret, hipStream_t s);
 hipError_t launch_ppo_whiten(const float* x, const int* kept, int B, int N, int shift_mean, float* out,
                              hipStream_t s);
+hipError_t launch_ppo_loss(const float* lp, const float* lp0, const float* adv, const float* v, const float* v0,
+                           const float* ret, const int* kept, int B, int N, float eps, float eps_v, float c1,
+                           float* d_lp, float* d_v, float* stats, hipStream_t s);
 
 // bf16 -> fp16 conversion of a weight matrix (exact within fp16's normal range).
 hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s);

@@ -1,7 +1,8 @@
 // What PPO consumes after a rollout, computed on the device from the outputs of rollout_generate
 // and score_sequences: per-token rewards (KL penalty per kept token, reward-model score on the last
 // kept token, a constant in place of the score when the response has no EOS), generalised advantage
-// estimates with returns, and batch whitening.  The arrays are tiny (batch x 53), so the kernels are
+// estimates with returns, batch whitening, and the clipped objective with its gradient with respect
+// to the model's outputs.  The arrays are tiny (batch x 53), so the kernels are
 // latency-bound by construction: one wave per row, sums and recursions in double and in a fixed
 // order (bit-reproducible; no atomics).
 #include "common.h"
@@ -119,6 +120,72 @@ __global__ void __launch_bounds__(1024)
     }
     out[i] = o;
   }
+}
+
+// One block: the clipped PPO objective over the kept response tokens and its gradient with respect
+// to the new log-probs and the new values.  Branch choice and sums in double, fixed order.
+// stats: loss, pg_loss, vf_loss, approx_kl, pg_clipfrac, vf_clipfrac, ratio_mean, n_tokens.
+__global__ void __launch_bounds__(1024)
+    ppo_loss_kernel(const float* __restrict__ lp, const float* __restrict__ lp0, const float* __restrict__ adv,
+                    const float* __restrict__ v, const float* __restrict__ v0, const float* __restrict__ ret,
+                    const int* __restrict__ kept, int B, int N, float eps, float eps_v, float c1,
+                    float* __restrict__ d_lp, float* __restrict__ d_v, float* __restrict__ stats) {
+  __shared__ double sh[16];
+  const size_t total = (size_t)B * N;
+  auto is_kept = [&](size_t i) { return (int)(i % N) < kept[i / N]; };
+  double cnt = 0.0;
+  for (size_t i = threadIdx.x; i < total; i += 1024)
+    if (is_kept(i)) cnt += 1.0;
+  const double n = block_sum_1024_d(cnt, sh);
+  const double inv_n = n > 0 ? 1.0 / n : 0.0;
+  double pg = 0.0, vf = 0.0, kl = 0.0, rs = 0.0, pgc = 0.0, vfc = 0.0;
+  for (size_t i = threadIdx.x; i < total; i += 1024) {
+    float g_lp = 0.f, g_v = 0.f;
+    if (is_kept(i)) {
+      const double diff = (double)lp[i] - (double)lp0[i];
+      const double ratio = exp(diff);
+      const double ratio_c = fmin(fmax(ratio, 1.0 - (double)eps), 1.0 + (double)eps);
+      const double a = adv[i];
+      const double pg1 = -a * ratio, pg2 = -a * ratio_c;
+      pg += fmax(pg1, pg2);
+      if (pg2 > pg1) pgc += 1.0;
+      else g_lp = (float)(-a * ratio * inv_n);
+      const double vv = v[i], vo = v0[i], r = ret[i];
+      const double v_c = fmin(fmax(vv, vo - (double)eps_v), vo + (double)eps_v);
+      const double vf1 = (vv - r) * (vv - r), vf2 = (v_c - r) * (v_c - r);
+      vf += 0.5 * fmax(vf1, vf2);
+      if (vf2 > vf1) vfc += 1.0;
+      else g_v = (float)((double)c1 * (vv - r) * inv_n);
+      kl += 0.5 * diff * diff;
+      rs += ratio;
+    }
+    d_lp[i] = g_lp;
+    d_v[i] = g_v;
+  }
+  pg = block_sum_1024_d(pg, sh) * inv_n;
+  vf = block_sum_1024_d(vf, sh) * inv_n;
+  kl = block_sum_1024_d(kl, sh) * inv_n;
+  rs = block_sum_1024_d(rs, sh) * inv_n;
+  pgc = block_sum_1024_d(pgc, sh) * inv_n;
+  vfc = block_sum_1024_d(vfc, sh) * inv_n;
+  if (threadIdx.x == 0) {
+    stats[0] = (float)(pg + (double)c1 * vf);
+    stats[1] = (float)pg;
+    stats[2] = (float)vf;
+    stats[3] = (float)kl;
+    stats[4] = (float)pgc;
+    stats[5] = (float)vfc;
+    stats[6] = (float)rs;
+    stats[7] = (float)n;
+  }
+}
+
+hipError_t launch_ppo_loss(const float* lp, const float* lp0, const float* adv, const float* v, const float* v0,
+                           const float* ret, const int* kept, int B, int N, float eps, float eps_v, float c1,
+                           float* d_lp, float* d_v, float* stats, hipStream_t s) {
+  hipLaunchKernelGGL(ppo_loss_kernel, dim3(1), dim3(1024), 0, s, lp, lp0, adv, v, v0, ret, kept, B, N, eps, eps_v, c1,
+                     d_lp, d_v, stats);
+  return hipGetLastError();
 }
 
 hipError_t launch_ppo_rewards(const float* lp, const float* ref_full, const float* rm_full, const int* tokens, int B,

@@ -2,12 +2,11 @@
 // natural operand order of the CDNA matrix cores: every lane loads 8 consecutive K elements of one
 // row of A and of one row of W.
 //
-//  * bf16 mode (fp16 operands): v_mfma_f32_32x32x16_f16, 256x256 block tile, 4 waves (2x2) of
-//    128x128 (256 fp32 accumulators per lane, so a wave reads 8 operand fragments from LDS per 16
-//    matrix instructions), K step 64 (a tile row is one full 128-byte line), one 64 KB LDS stage
-//    with XOR-swizzled 16-byte chunks (conflict-free ds_read_b128), the next tile held in
-//    registers while the current one is multiplied, workgroup ids remapped so that the 32 tiles
-//    resident on one XCD share A and W panels in that XCD's L2.
+//  * bf16 mode (fp16 operands), many rows: v_mfma_f32_32x32x16_f16, 256x256 block tile, 8 waves
+//    (2x4) of 128x64, K step 64 (a tile row is one full 128-byte line), two 64 KB LDS stages
+//    filled directly from global memory, XOR-swizzled 16-byte chunks (conflict-free ds_read_b128),
+//    workgroup ids remapped so that the 32 tiles resident on one XCD share A and W panels in that
+//    XCD's L2.  Few rows (decode): 128x64 tiles staged through registers, split over K.
 //  * fp32: plain FMA tile kernel (check mode only; not tuned).
 #include <algorithm>
 #include <type_traits>
@@ -293,15 +292,15 @@ __global__ void __launch_bounds__(256)
 }
 
 // =================================================================================================
-// Large-M kernel: 256x256 block tile, one block per CU, 4 waves of 128x128 (256 accumulator
-// registers per lane).  Tiles go global -> LDS directly (global_load_lds, 16 bytes per lane: a wave
+// Large-M kernel: 256x256 block tile, one block per CU, 8 waves of 128x64 (two per SIMD; the
+// log-sum-exp epilogue runs the 4-wave form, 128x128 per wave).  Tiles go global -> LDS directly (global_load_lds, 16 bytes per lane: a wave
 // instruction fills 1 KB; no staging registers, no ds_write) into TWO 64 KB stages of K depth 64.
 // The depth is what matters: a tile row is then one full 128-byte line per stage.  With half
 // lines (K depth 32, more and smaller stages) every line was requested twice from L2, one half per
 // k-step, and the matrix cores waited on that request stream; fetching whole lines removed the
-// stall, and a lookahead of one stage proved as good as three.  One raw s_barrier per stage (64
-// matrix instructions per wave) with an explicit s_waitcnt; the 16 tile loads and 32 fragment
-// reads of a stage are dealt out one at a time between the matrix instructions (scheduling fences
+// stall, and a lookahead of one stage proved as good as three.  One raw s_barrier per stage with
+// an explicit s_waitcnt; the tile loads and fragment reads of a stage are dealt out one at a time
+// between the matrix instructions (scheduling fences
 // keep the order), so each issues in the shadow of a matrix instruction.  Each lane picks its
 // global chunk so that the linear LDS image is the XOR-swizzled layout the fragment reads expect
 // (conflict-free ds_read_b128).

@@ -116,12 +116,12 @@ def main():
         # Memory traffic of the per-layer GEMMs cannot be counted in this process (hardware counters are
         # collected on the stand-alone gemm_driver, see profiles/pmc_gemm_traffic_config4.md): for d_model
         # 2560 the L2-miss bytes, FETCH_SIZE + WRITE_SIZE scaled by a copy kernel of known size, came to
-        # 119,390 bytes per GEMM row per launch (mean of QKV, FC1 and out+FC2 at 83,373 rows) and grow in
+        # 116,183 bytes per GEMM row per launch (mean of QKV, FC1 and out+FC2 at 83,373 rows) and grow in
         # proportion to the rows, so the figure here is that rate times this run's mean rows per launch.
         # It counts what leaves the L2s, Infinity-Cache hits included: an upper bound of the HBM bytes.
         traffic = None
         if cfg.d_model == 2560 and cfg.dtype != "fp32":
-            traffic = 119390.0 * 0.5 * (wc["real_query_tokens"] + wc["real_score_tokens"])
+            traffic = 116183.0 * 0.5 * (wc["real_query_tokens"] + wc["real_score_tokens"])
         rooflines["gemm"] = {"bound": "mfma", "achieved": ach / 1e12, "peak": MFMA_PEAK / 1e12, "unit": "TFLOP/s",
                              "frac": ach / MFMA_PEAK, "traffic": traffic,
                              "avg_launch_ms": prof["gemm"][0] / prof["gemm"][1]}

@@ -128,8 +128,11 @@ def main():
     if "attn_decode" in prof:
         by = wc["decode_kv_read_bytes"]
         ach = by / (prof["attn_decode"][0] * 1e-3)
+        # FETCH_SIZE + WRITE_SIZE of this kernel on the stand-alone attn_driver (head size 80, see
+        # profiles/pmc_attn_decode_traffic_config4.md): 1.004 x the algorithmic K/V bytes, every row fetched once
+        a_traffic = 1.004 * by / prof["attn_decode"][1] if cfg.head_dim == 80 and cfg.dtype != "fp32" else None
         rooflines["attn_decode"] = {"bound": "hbm", "achieved": ach / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                                    "frac": ach / HBM_PEAK, "traffic": None,
+                                    "frac": ach / HBM_PEAK, "traffic": a_traffic,
                                     "avg_launch_ms": prof["attn_decode"][0] / prof["attn_decode"][1]}
     roof = rooflines.get(dom) or rooflines.get("gemm") or {}
     roof = dict(roof, kernel=dom if dom in rooflines else "gemm")

@@ -9,7 +9,6 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librlhf_rollout.so")
-DRIVER = os.path.join(HERE, "gemm_driver")
 SOURCES = ["api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "ppo_signals.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wno-unused-result",
@@ -45,15 +44,16 @@ def build(verbose: bool = False) -> str:
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
-    # stand-alone GEMM driver (hardware-counter runs): links the library's own objects
-    drv_obj = os.path.join(objdir, "gemm_driver.o")
-    r = subprocess.run([hipcc, *FLAGS, "-c", os.path.join(CSRC, "gemm_driver.hip"), "-o", drv_obj],
-                       capture_output=True, text=True)
-    if r.returncode == 0:
-        r = subprocess.run([hipcc, "--offload-arch=gfx950", "-o", DRIVER, drv_obj,
-                            os.path.join(objdir, "gemm.o")], capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"gemm_driver build failed:\n{r.stderr}")
+    # stand-alone kernel drivers (hardware-counter runs): each links the library's own object
+    for drv, obj in (("gemm_driver", "gemm.o"), ("attn_driver", "attention.o")):
+        drv_obj = os.path.join(objdir, drv + ".o")
+        r = subprocess.run([hipcc, *FLAGS, "-c", os.path.join(CSRC, drv + ".hip"), "-o", drv_obj],
+                           capture_output=True, text=True)
+        if r.returncode == 0:
+            r = subprocess.run([hipcc, "--offload-arch=gfx950", "-o", os.path.join(HERE, drv), drv_obj,
+                                os.path.join(objdir, obj)], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"{drv} build failed:\n{r.stderr}")
     return LIB
 
 

@@ -337,6 +337,80 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+// Same, with 8 consecutive elements per lane: two 16-byte loads, and one 16-byte fp16 store per
+// output instead of two 8-byte ones.
+template <int NV8>  // 8-element chunks per lane: d <= 512 * NV8
+__global__ void __launch_bounds__(256)
+    layernorm_vec8_kernel(const float* __restrict__ x, const int* __restrict__ src, int src_add, int rows_max,
+                          const int* __restrict__ rows_dev, int d, float eps, const bf16_t* __restrict__ g1,
+                          const bf16_t* __restrict__ b1, half_t* __restrict__ out1, const bf16_t* __restrict__ g2,
+                          const bf16_t* __restrict__ b2, half_t* __restrict__ out2,
+                          const bf16_t* __restrict__ value_w, float value_b, float* __restrict__ val) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= (rows_dev ? min(*rows_dev, rows_max) : rows_max)) return;
+  const int sr = src ? max(src[r] + src_add, 0) : r;
+  const f32x4_t* xr = (const f32x4_t*)(x + (size_t)sr * d);
+  const int nv = d >> 3;
+  f32x4_t v[NV8][2];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV8; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nv) {
+      v[i][0] = xr[2 * c];
+      v[i][1] = xr[2 * c + 1];
+      s += (v[i][0][0] + v[i][0][1] + v[i][0][2] + v[i][0][3]) + (v[i][1][0] + v[i][1][1] + v[i][1][2] + v[i][1][3]);
+    }
+  }
+  const float mean = wave_sum(s) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV8; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nv) {
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        v[i][hh] -= mean;
+        q += v[i][hh][0] * v[i][hh][0] + v[i][hh][1] * v[i][hh][1] + v[i][hh][2] * v[i][hh][2] +
+             v[i][hh][3] * v[i][hh][3];
+      }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+  float vd = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV8; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nv) {
+      f16x8_t o1, o2;
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const f32x4_t n = v[i][hh] * rstd;
+        const int c4 = 2 * c + hh;
+        const f32x4_t h1 = n * bf16x4_to_f32(((const u32x2_t*)g1)[c4]) + bf16x4_to_f32(((const u32x2_t*)b1)[c4]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) o1[4 * hh + u] = from_f32<half_t>(h1[u]);
+        if (out2) {
+          const f32x4_t h2 = n * bf16x4_to_f32(((const u32x2_t*)g2)[c4]) + bf16x4_to_f32(((const u32x2_t*)b2)[c4]);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) o2[4 * hh + u] = from_f32<half_t>(h2[u]);
+        }
+        if (val) {
+          const f32x4_t w = bf16x4_to_f32(((const u32x2_t*)value_w)[c4]);
+          vd += h1[0] * w[0] + h1[1] * w[1] + h1[2] * w[2] + h1[3] * w[3];
+        }
+      }
+      ((f16x8_t*)(out1 + (size_t)r * d))[c] = o1;
+      if (out2) ((f16x8_t*)(out2 + (size_t)r * d))[c] = o2;
+    }
+  }
+  if (val) {
+    vd = wave_sum(vd);
+    if (lane == 0) val[r] = vd + value_b;
+  }
+}
+
 template <typename M>
 static hipError_t ln_launch(const float* x, const int* src, int src_add, int rows_max, const int* rows_dev, int d,
                             float eps, const void* g1, const void* b1, void* out1, const void* g2,
@@ -351,6 +425,10 @@ static hipError_t ln_launch(const float* x, const int* src, int src_add, int row
                          eps, (const bf16_t*)g1, (const bf16_t*)b1, (half_t*)out1, (const bf16_t*)g2,
                          (const bf16_t*)b2, (half_t*)out2, (const bf16_t*)vw, vb, val, PendingResidual{},
                          (float*)nullptr);
+    else if ((d & 7) == 0 && d > 1024)
+      hipLaunchKernelGGL(layernorm_vec8_kernel<8>, grid, dim3(256), 0, s, x, src, src_add, rows_max, rows_dev, d,
+                         eps, (const bf16_t*)g1, (const bf16_t*)b1, (half_t*)out1, (const bf16_t*)g2,
+                         (const bf16_t*)b2, (half_t*)out2, (const bf16_t*)vw, vb, val);
     else if (d <= 1024)
       hipLaunchKernelGGL(layernorm_vec_kernel<4>, grid, dim3(256), 0, s, x, src, src_add, rows_max, rows_dev, d,
                          eps, (const bf16_t*)g1, (const bf16_t*)b1, (half_t*)out1, (const bf16_t*)g2,

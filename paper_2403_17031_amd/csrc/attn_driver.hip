@@ -1,7 +1,8 @@
 // Stand-alone driver for the decode attention kernel at the 2.8B shape (batch 256, 32 heads of 80): fills
 // a K/V cache laid out as the library lays it out, runs one decode step's attention, checks sampled
 // (sequence, head) outputs against a double-precision softmax on the host, times the kernel and runs a
-// plain copy kernel of known size next to it.  Like gemm_driver it exists for hardware-counter runs
+// plain copy kernel of known size next to it; it also runs and checks the packed causal (prefill /
+// scoring) attention kernel on the same cache.  Like gemm_driver it exists for hardware-counter runs
 // (rocprofv3 --pmc), which work on a small native process but not on the Python benchmark.
 //   usage: attn_driver [batch=256] [reps=5]
 #include <cmath>
@@ -113,6 +114,65 @@ int main(int argc, char** argv) {
   const double bytes = ctx_sum * 2.0 * d * 2.0;  // K and V rows of every sequence's context, fp16
   printf("attn_decode B=%d H=%d hd=%d mean context %.1f: %.1f us  algorithmic K/V bytes %.3f GB  %.2f TB/s  max |err| %.2e\n",
          B, H, HD, ctx_sum / B, ms * 1e3, bytes / 1e9, bytes / ms / 1e9, maxerr);
+  // ---- the packed causal (prefill / scoring) kernel on the same cache: every sequence attends over
+  //      all len + 52 rows of its slab, queries packed back to back as the library packs them
+  {
+    std::vector<int> plen(B), cu(B + 1);
+    long T = 0;
+    double pair_sum = 0;
+    int Lmax = 0;
+    for (int b = 0; b < B; ++b) {
+      plen[b] = len[b] + N - 1;  // every row of the sequence's slab
+      cu[b] = (int)T;
+      T += plen[b];
+      pair_sum += 0.5 * plen[b] * (plen[b] + 1.0);
+      if (plen[b] > Lmax) Lmax = plen[b];
+    }
+    cu[B] = (int)T;
+    _Float16 *dq2, *dout2;
+    int *dplen, *dcu;
+    CK(hipMalloc(&dq2, (size_t)T * d * 2)); CK(hipMalloc(&dout2, (size_t)T * d * 2));
+    CK(hipMalloc(&dplen, B * 4)); CK(hipMalloc(&dcu, (B + 1) * 4));
+    hipLaunchKernelGGL(fill_f16_kernel, dim3(4096), dim3(256), 0, 0, dq2, (size_t)T * d, 4u);
+    CK(hipMemcpy(dplen, plen.data(), B * 4, hipMemcpyHostToDevice));
+    CK(hipMemcpy(dcu, cu.data(), (B + 1) * 4, hipMemcpyHostToDevice));
+    CK(launch_attn_prefill(1, dq2, dK, dV, 0, B, Lmax, dplen, dcu, dkvoff, H, HD, dout2, d, 0));
+    CK(hipDeviceSynchronize());
+    double perr = 0;
+    for (int t = 0; t < 12; ++t) {
+      const int b = t == 0 ? 0 : rand() % B, h = rand() % H;
+      const int qi = t == 0 ? plen[b] - 1 : rand() % plen[b];
+      const size_t base = ((size_t)kvoff[b] * H + (size_t)h * plen[b]) * HD;
+      std::vector<uint16_t> hk((size_t)(qi + 1) * HD), hv((size_t)(qi + 1) * HD), hq1(HD), ho1(HD);
+      CK(hipMemcpy(hk.data(), dK + base, hk.size() * 2, hipMemcpyDeviceToHost));
+      CK(hipMemcpy(hv.data(), dV + base, hv.size() * 2, hipMemcpyDeviceToHost));
+      CK(hipMemcpy(hq1.data(), dq2 + ((size_t)cu[b] + qi) * d + h * HD, HD * 2, hipMemcpyDeviceToHost));
+      CK(hipMemcpy(ho1.data(), dout2 + ((size_t)cu[b] + qi) * d + h * HD, HD * 2, hipMemcpyDeviceToHost));
+      std::vector<double> sc(qi + 1);
+      double mx = -1e300, den = 0;
+      for (int j = 0; j <= qi; ++j) {
+        double sdot = 0;
+        for (int e = 0; e < HD; ++e) sdot += (double)h2f(hq1[e]) * h2f(hk[(size_t)j * HD + e]);
+        sc[j] = sdot / sqrt((double)HD);
+        if (sc[j] > mx) mx = sc[j];
+      }
+      for (int j = 0; j <= qi; ++j) { sc[j] = exp(sc[j] - mx); den += sc[j]; }
+      for (int e = 0; e < HD; ++e) {
+        double o = 0;
+        for (int j = 0; j <= qi; ++j) o += sc[j] * h2f(hv[(size_t)j * HD + e]);
+        const double err = fabs(o / den - h2f(ho1[e]));
+        if (err > perr) perr = err;
+        if (err > 4e-3) { if (!bad) printf("PREFILL MISMATCH b=%d h=%d q=%d e=%d\n", b, h, qi, e); ++bad; }
+      }
+    }
+    CK(hipEventRecord(e0, 0));
+    for (int i = 0; i < reps; ++i) CK(launch_attn_prefill(1, dq2, dK, dV, 0, B, Lmax, dplen, dcu, dkvoff, H, HD, dout2, d, 0));
+    CK(hipEventRecord(e1, 0)); CK(hipEventSynchronize(e1));
+    CK(hipEventElapsedTime(&ms, e0, e1)); ms /= reps;
+    const double fl = 4.0 * d * pair_sum;  // QK^T and PV over the causal (query, key) pairs
+    printf("attn_prefill B=%d H=%d hd=%d tokens %ld mean length %.1f: %.1f us  %.1f TFLOP/s  max |err| %.2e\n", B, H, HD, T,
+           (double)T / B, ms * 1e3, fl / ms / 1e9, perr);
+  }
   {
     const size_t n = (size_t)1 << 24;  // 256 MiB read + 256 MiB written
     if (plane * 2 < n * 16) printf("copy yardstick skipped: cache plane smaller than 256 MiB\n");

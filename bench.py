@@ -160,6 +160,25 @@ def main():
     torch.cuda.synchronize()
     signals_ms = e0.elapsed_time(e1) / reps
 
+    # The optimizer step of the PPO update (AdamW over fp32 master weights, moments and the bf16 copy) on
+    # 2^30 parameters: 16 bytes read and 14 written per element.  Outside the headline metric.
+    n_opt = 1 << 30
+    o_p = torch.zeros(n_opt, dtype=torch.float32, device="cuda")
+    o_g = torch.full((n_opt,), 1e-3, dtype=torch.float32, device="cuda")
+    o_m, o_v = torch.zeros_like(o_p), torch.zeros_like(o_p)
+    o_b = torch.empty(n_opt, dtype=torch.bfloat16, device="cuda")
+    for i in range(1 + 3):
+        if i == 1:
+            e0.record()
+        P.adamw_step(o_p, o_g, o_m, o_v, i + 1, param_bf16=o_b)
+    e1.record()
+    torch.cuda.synchronize()
+    adamw_ms = e0.elapsed_time(e1) / 3
+    ach = 30.0 * n_opt / (adamw_ms * 1e-3)
+    rooflines["adamw"] = {"bound": "hbm", "achieved": ach / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                          "frac": ach / HBM_PEAK, "traffic": None, "avg_launch_ms": adamw_ms}
+    del o_p, o_g, o_m, o_v, o_b
+
     # The paper's other scoring shapes (reward-model batches of 638 tokens, long-context batches of 2021),
     # right-padded with true lengths uniform in [L/4, L]; outside the headline metric.
     extra = None
@@ -209,7 +228,7 @@ def main():
         "rescoring_tok_s_padded": B * (wl.query_len + N) / (score_ms * 1e-3),
         "score_mfma_frac": wc["score_flops"] / (score_ms * 1e-3) / MFMA_PEAK,
         "roofline": roof, "rooflines": rooflines, "kernels_ms": kern, "profiled_step_ms": tot,
-        "ppo_signals_ms": signals_ms, "extra_score_shapes": extra,
+        "ppo_signals_ms": signals_ms, "adamw_ms_per_2p30_params": adamw_ms, "extra_score_shapes": extra,
         "cpu_baseline": cpu, "setup_s": setup_s,
     }
     print(json.dumps(out))

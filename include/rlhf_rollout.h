@@ -173,6 +173,23 @@ int rlhf_ppo_loss(const float *new_logprobs, const float *old_logprobs, const fl
                   int32_t B, int32_t N, float cliprange, float cliprange_value, float vf_coef, float *d_logprobs,
                   float *d_values, float *stats, void *stream);
 
+/* One AdamW update of a flat parameter array (paper: PPO hyperparameter table, "AdamW (eps = 1e-5,
+ * lr = 3e-6)"; the algorithm is the published one, Adam with decoupled weight decay), update number
+ * `step` >= 1:
+ *   g = grad * grad_scale;  p *= 1 - lr * weight_decay;
+ *   m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2;
+ *   p -= lr / (1 - beta1^step) * m / (sqrt(v) / sqrt(1 - beta2^step) + eps)
+ * param, exp_avg, exp_avg_sq: dev float [n], updated in place; grad: dev float [n]; param_bf16: dev
+ * uint16 [n] or NULL, receives the updated parameters rounded to bf16 (nearest even) -- the format the
+ * forward passes read.  fp32 arrays 16-byte aligned, the bf16 array 8-byte aligned; n == 0 is a no-op.  The caller
+ * supplies `lr` already scheduled (the paper's linear schedule: lr * (1 - k / K) for update k of K).
+ * Arithmetic in fp32; the hyperparameters are doubles, and 1 - beta, lr * weight_decay and the two bias
+ * corrections are formed in double on the host before being rounded to fp32.  One launch on
+ * `stream`; elementwise, so a model's tensors can be updated as one flat array or one by one. */
+int rlhf_adamw_step(float *param, const float *grad, float *exp_avg, float *exp_avg_sq, uint16_t *param_bf16,
+                    uint64_t n, int32_t step, double lr, double beta1, double beta2, double eps,
+                    double weight_decay, double grad_scale, void *stream);
+
 /* Debug / parity aid: raw (pre-temperature) fp32 logits of the same forward pass as
  * score_sequences at n (row, column) pairs.  rows_bt: HOST int32 [n, 2]; out_logits: dev float
  * [n, vocab].  Every pair must name a real position. */

@@ -14,4 +14,6 @@ from .binding import (  # noqa: F401
     ppo_whiten,
     ppo_loss,
     PPO_LOSS_STATS,
+    adamw_step,
+    linear_lr,
 )

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "librlhf_rollout.so")
 EXPORTS = (
     "rlhf_create", "rlhf_destroy", "rlhf_workspace_bytes", "rollout_generate", "score_sequences",
     "rlhf_debug_logits_rows", "rlhf_profile_enable", "rlhf_profile_read", "rlhf_last_rollout_phases",
-    "rlhf_last_error", "rlhf_ppo_assemble_rewards", "rlhf_ppo_gae", "rlhf_ppo_whiten", "rlhf_ppo_loss",
+    "rlhf_last_error", "rlhf_ppo_assemble_rewards", "rlhf_ppo_gae", "rlhf_ppo_whiten", "rlhf_ppo_loss", "rlhf_adamw_step",
 )
 
 _PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -66,6 +66,7 @@ def load_library():
     lib.rlhf_ppo_gae.argtypes = [vp, vp, C.c_int64, vp, i32, i32, f32, f32, vp, vp, vp]
     lib.rlhf_ppo_whiten.argtypes = [vp, vp, i32, i32, i32, vp, vp]
     lib.rlhf_ppo_loss.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp, vp, vp]
+    lib.rlhf_adamw_step.argtypes = [vp, vp, vp, vp, vp, u64, i32] + [C.c_double] * 6 + [vp]
     lib.rlhf_last_error.restype = C.c_char_p
     for n in EXPORTS:
         if n not in ("rlhf_destroy", "rlhf_last_error"):
@@ -333,3 +334,35 @@ def ppo_loss(new_logprobs, old_logprobs, advantages, new_values, old_values, ret
         _check(lib.rlhf_ppo_loss(*[a.data_ptr() for a in arrs], k.data_ptr(), B, N, cliprange, cliprange_value, vf_coef,
                                  d_lp.data_ptr(), d_v.data_ptr(), stats.data_ptr(), _cur_stream(torch, dev)))
     return stats, d_lp, d_v
+
+
+
+def linear_lr(base_lr, update_index, total_updates):
+    """Learning rate of update `update_index` (0-based) of `total_updates` under the linear schedule."""
+    if total_updates <= 0:
+        raise ValueError("total_updates must be positive")
+    k = min(max(int(update_index), 0), int(total_updates))
+    return base_lr * (1.0 - k / total_updates)
+
+
+def adamw_step(param, grad, exp_avg, exp_avg_sq, step, lr=3e-6, beta1=0.9, beta2=0.999, eps=1e-5, weight_decay=0.01,
+               grad_scale=1.0, param_bf16=None):
+    """In-place AdamW update of CUDA float32 tensors (any shape, contiguous, same number of elements);
+    param_bf16: optional CUDA bfloat16 tensor that receives the rounded parameters."""
+    import torch
+    lib = load_library()
+    ts = (param, grad, exp_avg, exp_avg_sq)
+    if any((not isinstance(t, torch.Tensor)) or t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous()
+           for t in ts):
+        raise RlhfError("adamw_step: param, grad and the moments must be contiguous CUDA float32 tensors")
+    n = param.numel()
+    if any(t.numel() != n for t in ts):
+        raise RlhfError("adamw_step: all arrays must have the same number of elements")
+    if param_bf16 is not None and (param_bf16.dtype != torch.bfloat16 or not param_bf16.is_cuda or
+                                   not param_bf16.is_contiguous() or param_bf16.numel() != n):
+        raise RlhfError("adamw_step: param_bf16 must be a contiguous CUDA bfloat16 tensor of the same size")
+    dev = param.device
+    with torch.cuda.device(dev):
+        _check(lib.rlhf_adamw_step(param.data_ptr(), grad.data_ptr(), exp_avg.data_ptr(), exp_avg_sq.data_ptr(),
+                                   None if param_bf16 is None else param_bf16.data_ptr(), n, int(step), lr, beta1, beta2,
+                                   eps, weight_decay, grad_scale, _cur_stream(torch, dev)))

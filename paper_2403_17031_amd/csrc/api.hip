@@ -439,6 +439,28 @@ int rlhf_ppo_loss(const float* new_logprobs, const float* old_logprobs, const fl
   return RLHF_OK;
 }
 
+int rlhf_adamw_step(float* param, const float* grad, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16,
+                    uint64_t n, int32_t step, double lr, double beta1, double beta2, double eps, double weight_decay,
+                    double grad_scale, void* stream) {
+  if (step < 1) return fail(RLHF_EINVAL, "step counts from 1");
+  if (!(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0))
+    return fail(RLHF_EINVAL, "beta1 and beta2 must be in [0, 1)");
+  if (!(lr >= 0.0) || !(eps > 0.0) || !(weight_decay >= 0.0) || !std::isfinite(lr) || !std::isfinite(eps) ||
+      !std::isfinite(weight_decay) || !std::isfinite(grad_scale))
+    return fail(RLHF_EINVAL, "lr, weight_decay must be finite and >= 0, eps finite and > 0, grad_scale finite");
+  if (n == 0) return RLHF_OK;  // nothing to update; the pointers may then be null
+  if (!param || !grad || !exp_avg || !exp_avg_sq) return fail(RLHF_EINVAL, "null pointer argument");
+  if ((((uintptr_t)param | (uintptr_t)grad | (uintptr_t)exp_avg | (uintptr_t)exp_avg_sq) & 15) != 0 ||
+      ((uintptr_t)param_bf16 & 7) != 0)
+    return fail(RLHF_EINVAL, "fp32 arrays must be 16-byte aligned, the bf16 array 8-byte aligned");
+  const double bias1 = 1.0 - std::pow(beta1, (double)step);
+  const double bias2 = 1.0 - std::pow(beta2, (double)step);
+  HIP_OK(launch_adamw(param, grad, exp_avg, exp_avg_sq, param_bf16, (size_t)n, (float)(1.0 - lr * weight_decay),
+                      (float)beta1, (float)(1.0 - beta1), (float)beta2, (float)(1.0 - beta2), (float)(lr / bias1),
+                      (float)(1.0 / std::sqrt(bias2)), (float)eps, (float)grad_scale, (hipStream_t)stream));
+  return RLHF_OK;
+}
+
 int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, rlhf_handle** out) {
   if (out) *out = nullptr;
   if (!cfg || !w || !out) return fail(RLHF_EINVAL, "null argument");

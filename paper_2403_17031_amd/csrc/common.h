@@ -233,6 +233,10 @@ hipError_t launch_ppo_whiten(const float* x, const int* kept, int B, int N, int 
 hipError_t launch_ppo_loss(const float* lp, const float* lp0, const float* adv, const float* v, const float* v0,
                            const float* ret, const int* kept, int B, int N, float eps, float eps_v, float c1,
                            float* d_lp, float* d_v, float* stats, hipStream_t s);
+// Optimizer step (optimizer.hip).
+hipError_t launch_adamw(float* p, const float* g, float* m, float* v, uint16_t* p_bf16, size_t n, float decay,
+                        float beta1, float omb1, float beta2, float omb2, float step_size, float inv_sqrt_bias2,
+                        float eps, float grad_scale, hipStream_t s);
 
 // bf16 -> fp16 conversion of a weight matrix (exact within fp16's normal range).
 hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s);

@@ -489,6 +489,13 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
   //      16 bytes per lane, 16 lanes per 256-byte row segment.  The LDS image is XOR-swizzled by
   //      row (chunk ^ (row & 15)); accumulator tiles are addressed through compile-time indices
   //      (a loop the compiler declines to unroll would spill all 256 accumulators to scratch).
+  // The staging regions are private to a wave, so the waves need not wait for each other: a wave's
+  // own LDS writes are complete, and visible to all its lanes, once its LDS counter has drained.
+#define RLHF_WAVE_LDS_FENCE()                  \
+  __builtin_amdgcn_sched_barrier(0);           \
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); \
+  __builtin_amdgcn_wave_barrier();             \
+  __builtin_amdgcn_sched_barrier(0);
   constexpr int EPW = 128 * WN;  // halfs of LDS per wave: its tile as fp16, or half of it as fp32
   uint16_t* ep = wave * EPW < DSTAGE ? lds0 + wave * EPW : lds1 + (wave * EPW - DSTAGE);
   constexpr int CH = WN / 8;     // 16-byte chunks per fp16 row of the wave's tile = lanes per row on the way out
@@ -539,7 +546,7 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
     RLHF_ROW(0) RLHF_ROW(1)
     if constexpr (NT > 2) { RLHF_ROW(NT - 2) RLHF_ROW(NT - 1) }
 #undef RLHF_ROW
-    __syncthreads();
+    RLHF_WAVE_LDS_FENCE();
     const int gcol = n0 + wn + rd_c * 8;
 #pragma unroll 8
     for (int it = 0; it < 128 / RPI; ++it) {
@@ -587,7 +594,7 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
         if (hh == 0) { RLHF_ROW(0) } else { RLHF_ROW(1) }
       }
 #undef RLHF_ROW
-      __syncthreads();
+      RLHF_WAVE_LDS_FENCE();
 #pragma unroll
       for (int it = 0; it < 128 / RPI; ++it) {
         const int row = it * RPI + rd_row;
@@ -598,9 +605,10 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
           *(f32x4_t*)((float*)out + (size_t)grow * ldo + gcol) = v;
         }
       }
-      __syncthreads();
+      RLHF_WAVE_LDS_FENCE();
     }
   }
+#undef RLHF_WAVE_LDS_FENCE
 }
 
 template <int EPI>

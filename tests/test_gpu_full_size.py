@@ -102,3 +102,13 @@ def test_config4_pythia2p8b_full_batch(gpu):
     _check_any_size_properties(wl, queries, mask, out)
     rows = [int(np.argmin(mask.sum(1)))]
     print("config 4: oracle/GPU token differences inside the near-tie band:", _grade_rows(wl, w, queries, mask, out, rows))
+
+
+@pytest.mark.timeout(1200)
+def test_config5_pythia6p9b_full_batch(gpu):
+    """The largest benchmark shape (batch 512, d_model 4096, head dimension 128, about 200 GB of HBM with the
+    workspace); the oracle replays the shortest row."""
+    wl, w, queries, mask, out = _run_full(gpu, 5)
+    _check_any_size_properties(wl, queries, mask, out)
+    rows = [int(np.argmin(mask.sum(1)))]
+    print("config 5: oracle/GPU token differences inside the near-tie band:", _grade_rows(wl, w, queries, mask, out, rows))

@@ -154,6 +154,7 @@ Acts carve_acts(Carver& c, const rlhf_model_config& cfg, size_t rows, size_t esz
 struct RolloutWs {
   Meta meta;
   Acts acts;
+  Acts last;  // [B, .] activations of the final prefill layer's last-position rows
   int *finished, *cur_tok;
   void* hl;
   float* logits;
@@ -172,6 +173,9 @@ RolloutWs carve_rollout(Carver& c, const rlhf_model_config& cfg, int B, int Lq, 
   w.acts.splitk_bytes = (size_t)16 * B * std::max(3 * cfg.d_model, cfg.d_ff) * sizeof(float);
   w.acts.splitk = c.take_bytes(w.acts.splitk_bytes);
   w.acts.splitk2 = c.take_bytes(w.acts.splitk_bytes);
+  w.last = carve_acts(c, cfg, (size_t)B, esz);
+  w.last.splitk_bytes = w.acts.splitk_bytes;
+  w.last.splitk = w.acts.splitk;  // decode has not started: its partial-sum scratch is free
   w.kv_slots = (size_t)B * (Lq + N - 1);
   w.kv = (char*)c.take_bytes((size_t)cfg.n_layers * 2 * w.kv_slots * cfg.d_model * esz);
   return w;
@@ -236,6 +240,11 @@ struct PassArgs {
   char* kv;            // layer l: K at kv + (2l)*kv_layer_bytes/2 ...
   size_t kv_slots;     // slots per head
   bool kv_per_layer;   // false: every layer reuses the same single-layer scratch
+  // Prefill of a rollout only needs the last position of every sequence after the final layer
+  // (the first sampled token comes from it): when `last` is set, the final layer computes K and V
+  // for every row as usual, but attention, out-projection and MLP run on the B gathered last rows
+  // only, into last->x ([B, d], row b = sequence b).
+  const Acts* last = nullptr;
 };
 
 int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) {
@@ -311,6 +320,34 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
       LAUNCH(p.mode ? "rope_kv_decode" : "rope_kv", launch_rope_kv(dt, A.qkv, p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff,
                                        p.len, c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q, kc, vc,
                                        (long)p.kv_extra, s));
+    }
+    if (p.mode == 0 && p.last && l + 1 == c.n_layers) {
+      const Acts& Z = *p.last;
+      const size_t rb = (size_t)d * h->esz;
+      LAUNCH("gather_last", launch_gather_rows(A.q, p.cu + 1, -1, p.B, rb, Z.q, s));
+      LAUNCH("gather_last", launch_gather_rows(A.m, p.cu + 1, -1, p.B, rb, Z.m, s));
+      LAUNCH("gather_last", launch_gather_rows(A.x, p.cu + 1, -1, p.B, (size_t)d * sizeof(float), Z.x, s));
+      // the last query of a sequence attends over all of its rows: the single-row kernel with ctx = len
+      LAUNCH("attn_decode", launch_attn_decode(dt, Z.q, kc, vc, (long)p.kv_extra, p.B, p.len, 0, p.ctx_max, p.kvoff,
+                                               c.n_heads, c.head_dim, Z.att, s));
+      GemmArgs z;
+      z.M_max = p.B;
+      z.M_dev = nullptr;
+      z.splitk_ws = Z.splitk;
+      z.splitk_ws_bytes = Z.splitk_bytes;
+      auto few = [&](const void* in, const void* w, const void* bias, void* out, int N, int K, int epi) {
+        GemmArgs g = z;
+        g.A = in; g.W = w; g.bias = bias; g.out = out; g.N = N; g.K = K; g.ldo = N; g.epilogue = epi;
+        return g;
+      };
+      GemmArgs zo = few(Z.att, h->w_o[l], h->b_o[l], Z.x, d, d, EPI_BIAS_RESADD);
+      GemmArgs z1 = few(Z.m, h->w_fc1[l], h->b_fc1[l], Z.ffn, c.d_ff, d, EPI_BIAS_GELU);
+      GemmArgs z2 = few(Z.ffn, h->w_fc2[l], h->b_fc2[l], Z.x, d, c.d_ff, EPI_BIAS_RESADD);
+      zo.ldw = z2.ldw = h->ld_o2;
+      LAUNCH("gemm_decode", launch_gemm(dt, zo, s));
+      LAUNCH("gemm_decode", launch_gemm(dt, z1, s));
+      LAUNCH("gemm_decode", launch_gemm(dt, z2, s));
+      break;
     }
     GemmArgs go = gemm_args(A.att, h->w_o[l], h->b_o[l], A.x, d, d, EPI_BIAS_RESADD);
     GemmArgs g1 = gemm_args(A.m, h->w_fc1[l], h->b_fc1[l], A.ffn, c.d_ff, d, EPI_BIAS_GELU);
@@ -642,8 +679,10 @@ int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_
   p.kv = ws.kv;
   p.kv_slots = ws.kv_slots;
   p.kv_per_layer = true;
+  p.last = c.n_layers > 0 ? &ws.last : nullptr;
   rc = run_layers(h, ws.acts, p, s);
   if (rc) return rc;
+  p.last = nullptr;
 
   SampleArgs sa;
   sa.logits = ws.logits;
@@ -657,9 +696,14 @@ int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_
   lm.A = ws.hl; lm.W = h->embed_out_mm; lm.bias = nullptr; lm.out = ws.logits;
   lm.M_max = B; lm.M_dev = nullptr; lm.N = c.vocab; lm.K = d; lm.ldo = c.vocab; lm.epilogue = EPI_F32;
 
-  // last real position of every sequence: packed row cu[b+1] - 1
-  LAUNCH("final_ln", launch_final_ln(dt, ws.acts.x, m.cu + 1, -1, B, nullptr, d, c.ln_eps, h->w.lnf_g, h->w.lnf_b,
-                                     ws.hl, nullptr, 0.f, nullptr, s));
+  // last real position of every sequence: row b of the gathered rows (packed row cu[b+1] - 1 when
+  // the model has no layers)
+  if (c.n_layers > 0)
+    LAUNCH("final_ln", launch_final_ln(dt, ws.last.x, nullptr, 0, B, nullptr, d, c.ln_eps, h->w.lnf_g, h->w.lnf_b,
+                                       ws.hl, nullptr, 0.f, nullptr, s));
+  else
+    LAUNCH("final_ln", launch_final_ln(dt, ws.acts.x, m.cu + 1, -1, B, nullptr, d, c.ln_eps, h->w.lnf_g, h->w.lnf_b,
+                                       ws.hl, nullptr, 0.f, nullptr, s));
   LAUNCH("gemm_lm_head_decode", launch_gemm(dt, lm, s));
   sa.step = 0;
   LAUNCH("sampler", launch_sampler(sa, s));

@@ -398,7 +398,7 @@ __global__ void __launch_bounds__(256)
   if (tid < hd) {
     float o = 0.f;
     for (int gg = 0; gg < G; ++gg) o += part[gg * hd + tid];
-    out[(size_t)b * d + (size_t)h * hd + tid] = from_f32<T>(o / sum);
+    out[(size_t)b * d + (size_t)h * hd + tid] = from_f32<T>(sum > 0.f ? o / sum : 0.f);  // empty context: zero row
   }
 }
 
@@ -503,7 +503,8 @@ __global__ void __launch_bounds__(256)
   sum = wave_sum(sum);
   if (lane == 0) red[4 + wave] = sum;
   __syncthreads();
-  const float inv = 1.0f / (red[4] + red[5] + red[6] + red[7]);
+  const float den = red[4] + red[5] + red[6] + red[7];
+  const float inv = den > 0.f ? 1.0f / den : 0.f;  // an empty context (all-pad sequence) gives a zero row
   // ---- phase 3: out = sum_j p_j V[j]
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int it0 = wave; it0 < n_it; it0 += 16) {

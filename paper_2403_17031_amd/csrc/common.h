@@ -134,6 +134,8 @@ hipError_t launch_pack_embed(int dtype, const int32_t* tokens, int B, int L, con
                              const int* cu, const void* embed, int d, int vocab, int* pos, int* rowid, int* tok,
                              float* x, hipStream_t s);
 // Decode step: x[b, :] = embed[cur_tok[b], :] for b < B.
+hipError_t launch_gather_rows(const void* in, const int* src, int src_add, int rows, size_t row_bytes, void* out,
+                              hipStream_t s);
 hipError_t launch_embed_rows(int dtype, const int32_t* tok, int B, const void* embed, int d, float* x,
                              hipStream_t s);
 

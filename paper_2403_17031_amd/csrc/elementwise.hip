@@ -109,6 +109,25 @@ hipError_t launch_embed_rows(int dtype, const int32_t* tok, int B, const void* e
   return hipGetLastError();
 }
 
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+// out row r = in row src[r] + src_add, rows of `chunks` 16-byte pieces (any element type).
+__global__ void __launch_bounds__(256)
+    gather_rows_kernel(const u32x4_t* __restrict__ in, const int* __restrict__ src, int src_add, int chunks,
+                       u32x4_t* __restrict__ out) {
+  const size_t sr = (size_t)max(src[blockIdx.x] + src_add, 0);
+  for (int c = threadIdx.x; c < chunks; c += 256) out[(size_t)blockIdx.x * chunks + c] = in[sr * chunks + c];
+}
+
+hipError_t launch_gather_rows(const void* in, const int* src, int src_add, int rows, size_t row_bytes, void* out,
+                              hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if ((row_bytes & 15) != 0 || row_bytes / 16 > 0x7fffffff) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(rows), dim3(256), 0, s, (const u32x4_t*)in, src, src_add,
+                     (int)(row_bytes / 16), (u32x4_t*)out);
+  return hipGetLastError();
+}
+
 // =================================================================================================
 // LayerNorm: one block per row, fp32 statistics (mean, then centred second moment), up to two
 // affine outputs from the same statistics, optional value-head dot product on the first output.

@@ -249,6 +249,7 @@ struct PassArgs {
 
 int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) {
   const rlhf_model_config& c = h->cfg;
+  if (c.n_layers == 0) return RLHF_OK;  // nothing to run (and no layer 0 to take shapes from below)
   const int d = c.d_model, dt = c.dtype;
   const size_t plane = p.kv_slots * (size_t)d * h->esz;  // bytes of one K (or V) plane of one layer
 

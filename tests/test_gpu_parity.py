@@ -256,3 +256,55 @@ def test_error_codes(gpu, tiny_cfg):
     bad = cfg.with_(head_dim=17)
     with pytest.raises(gpu.RlhfError):
         gpu.Policy(bad, w)
+
+
+def _random_case(i):
+    """A seeded draw of a small model and batch: head sizes of every dispatch class (specialised and
+    generic kernels), rotary on a part or all of the head, layer counts from 0, widths and vocabularies that
+    are multiples of no tile size, batches down to a single sequence and a single new token."""
+    g = np.random.default_rng(1000 + i)
+    hd = int(g.choice([8, 16, 24, 32, 64, 80, 128]))
+    H = int(g.choice([1, 2, 3, 5]))
+    r = int(g.choice([hd // 4, hd // 2, hd]))
+    r -= r % 2
+    d = H * hd
+    cfg = ModelConfig(n_layers=int(g.integers(0, 4)), d_model=d, n_heads=H, head_dim=hd, rotary_dims=max(r, 2),
+                      d_ff=int(g.choice([d, 2 * d + 8, 4 * d])), vocab=int(g.choice([97, 160, 517, 1000])),
+                      dtype=("fp32", "bf16")[i % 2], pad_id=90)
+    B, Lq, N = int(g.integers(1, 8)), int(g.integers(1, 34)), int(g.integers(1, 8))
+    return cfg, B, Lq, N
+
+
+@pytest.mark.parametrize("i", range(int(__import__("os").environ.get("RLHF_RANDOM_CASES", "14"))))
+def test_randomized_small_models(gpu, i):
+    cfg, B, Lq, N = _random_case(i)
+    w = make_weights(cfg, 50 + i, variant="test")
+    queries, mask = _queries(cfg, B=B, Lq=Lq, lo=1, hi=Lq, seed=i)
+    if B > 2 and i % 3 == 0:
+        queries[1] = cfg.pad_id   # an all-pad row in some of the cases
+        mask[1] = 0
+    _check_rollout_and_scores(gpu, cfg, w, queries, mask, seed=900 + i, T=(0.7, 1.0, 0.3)[i % 3], N=N)
+
+
+def _random_wide_case(i):
+    """Seeded draws with enough packed rows (hundreds to a few thousand) to reach the many-rows kernels: the
+    large-tile GEMM where the width allows it (K a multiple of 128) and the staged one where it does not, the
+    tiled rotary kernel, the wave-per-row LayerNorms, the fused LM head."""
+    g = np.random.default_rng(2000 + i)
+    H, hd = [(2, 64), (8, 80), (3, 128), (1, 256), (6, 64), (4, 16), (5, 80)][int(g.integers(0, 7))]
+    d = H * hd
+    r = int(g.choice([hd // 4, hd // 2, hd]))
+    cfg = ModelConfig(n_layers=int(g.integers(1, 3)), d_model=d, n_heads=H, head_dim=hd, rotary_dims=r,
+                      d_ff=int(g.choice([d, 2 * d, 4 * d, 2 * d + 64])), vocab=int(g.choice([517, 1000, 2048])),
+                      dtype="bf16", pad_id=500)
+    B, Lq, N = int(g.integers(8, 41)), int(g.integers(40, 91)), int(g.integers(1, 5))
+    return cfg, B, Lq, N
+
+
+@pytest.mark.parametrize("i", range(int(__import__("os").environ.get("RLHF_RANDOM_WIDE_CASES", "8"))))
+def test_randomized_models_with_many_rows(gpu, i):
+    cfg, B, Lq, N = _random_wide_case(i)
+    w = make_weights(cfg, 70 + i, variant="test")
+    queries, mask = _queries(cfg, B=B, Lq=Lq, lo=Lq // 2, hi=Lq, seed=i)
+    rows = sorted({0, B - 1, int(np.argmin(mask.sum(1)))})
+    _check_rollout_and_scores(gpu, cfg, w, queries, mask, seed=300 + i, T=0.7, N=N, rows=rows, expect_exact=False)

@@ -308,3 +308,16 @@ def test_randomized_models_with_many_rows(gpu, i):
     queries, mask = _queries(cfg, B=B, Lq=Lq, lo=Lq // 2, hi=Lq, seed=i)
     rows = sorted({0, B - 1, int(np.argmin(mask.sum(1)))})
     _check_rollout_and_scores(gpu, cfg, w, queries, mask, seed=300 + i, T=0.7, N=N, rows=rows, expect_exact=False)
+
+
+@pytest.mark.parametrize("B,H,hd,Lq,N", [(513, 2, 64, 6, 3), (1100, 1, 128, 4, 2), (2100, 4, 16, 3, 3)])
+def test_batches_beyond_the_few_rows_kernels(gpu, B, H, hd, Lq, N):
+    """More sequences than the decode kernels' few-rows paths take (512 GEMM rows, 2048 LayerNorm / rotary
+    rows): a small model, so that the oracle can still replay sampled rows."""
+    d = H * hd
+    cfg = ModelConfig(n_layers=2, d_model=d, n_heads=H, head_dim=hd, rotary_dims=hd // 4, d_ff=2 * d, vocab=517,
+                      dtype="bf16", pad_id=500)
+    w = make_weights(cfg, 31, variant="test")
+    queries, mask = _queries(cfg, B=B, Lq=Lq, lo=1, hi=Lq, seed=B)
+    rows = [0, 1, B // 2, B - 2, B - 1]
+    _check_rollout_and_scores(gpu, cfg, w, queries, mask, seed=B, T=0.7, N=N, rows=rows, expect_exact=False)

@@ -211,7 +211,7 @@ ScoreWs carve_score(Carver& c, const rlhf_model_config& cfg, int B, int L, size_
   w.fused_lm = gemm_takes_lse(cfg.dtype, lf);
   w.chunk = (int)std::min<size_t>(w.Tmax, kLogitChunk);
   w.logits = w.fused_lm ? nullptr : c.take<float>((size_t)w.chunk * cfg.vocab);
-  w.nparts = 2 * ((cfg.vocab + 255) / 256);  // two 128-column parts per 256-column GEMM tile
+  w.nparts = gemm_lse_parts(cfg.vocab);
   if (w.fused_lm) {
     w.pmax = c.take<float>((size_t)w.nparts * w.Tmax);
     w.psum = c.take<float>((size_t)w.nparts * w.Tmax);

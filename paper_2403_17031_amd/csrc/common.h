@@ -99,6 +99,7 @@ hipError_t launch_lse_combine(const LseArgs& a, int rows_max, int nparts, float*
 // True when launch_gemm would take EPI_LSE for these arguments (large-M fp16 kernel only).
 struct GemmArgs;
 bool gemm_takes_lse(int dtype, const GemmArgs& a);
+int gemm_lse_parts(int n_cols);
 
 struct GemmArgs {
   const void* A;      // [M, K] activations, row-major, Mode::A

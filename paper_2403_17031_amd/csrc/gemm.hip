@@ -292,8 +292,8 @@ __global__ void __launch_bounds__(256)
 }
 
 // =================================================================================================
-// Large-M kernel: 256x256 block tile, one block per CU, 8 waves of 128x64 (two per SIMD; the
-// log-sum-exp epilogue runs the 4-wave form, 128x128 per wave).  Tiles go global -> LDS directly (global_load_lds, 16 bytes per lane: a wave
+// Large-M kernel: 256x256 block tile, one block per CU, 8 waves of 128x64 (two per SIMD; a 4-wave
+// form, 128x128 per wave, is kept as a template option).  Tiles go global -> LDS directly (global_load_lds, 16 bytes per lane: a wave
 // instruction fills 1 KB; no staging registers, no ds_write) into TWO 64 KB stages of K depth 64.
 // The depth is what matters: a tile row is then one full 128-byte line per stage.  With half
 // lines (K depth 32, more and smaller stages) every line was requested twice from L2, one half per
@@ -307,6 +307,7 @@ __global__ void __launch_bounds__(256)
 // =================================================================================================
 #define RLHF_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define RLHF_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+constexpr int kDmaWaves = 8;                // waves per block of the large-M kernel (4 or 8)
 constexpr int DK = 64;                      // K depth of one stage: 128 bytes per tile row
 constexpr int DSTAGE = (256 + 256) * DK;    // halfs per stage (64 KB)
 
@@ -615,9 +616,8 @@ template <int EPI>
 static void launch_f16_dma(const GemmArgs& a, hipStream_t s) {
   const int nb_m = (a.M_max + 255) / 256, nb_n = (a.N + 255) / 256;
   const int per_xcd = (nb_m * nb_n + 7) / 8;
-  // Eight waves measure 8-10 % faster than four on the layer shapes; the log-sum-exp epilogue keeps
-  // four, since its per-part statistics are laid out for 128-column parts.
-  constexpr int WV = EPI == EPI_LSE ? 4 : 8;
+  // Eight waves measure 8-10 % faster than four on the layer shapes.
+  constexpr int WV = kDmaWaves;
   hipLaunchKernelGGL((gemm_f16_dma_kernel<EPI, WV>), dim3(per_xcd * 8), dim3(64 * WV), 0, s, (const half_t*)a.A,
                      (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
                      nb_m, nb_n, a.lda ? a.lda : a.K, a.ldw ? a.ldw : a.K, (const bf16_t*)a.bias2,
@@ -689,6 +689,9 @@ static bool takes_dma(const GemmArgs& a) {
 }
 bool gemm_takes_bias2(int dtype, const GemmArgs& a) { return dtype == 1 && takes_dma(a); }
 bool gemm_takes_lse(int dtype, const GemmArgs& a) { return dtype == 1 && takes_dma(a); }
+// Parts (column groups with their own max / sum-exp) the log-sum-exp epilogue leaves per row: one per wave
+// column of every 256-column tile.
+int gemm_lse_parts(int n_cols) { return (kDmaWaves == 8 ? 4 : 2) * ((n_cols + 255) / 256); }
 
 template <int EPI>
 static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {

@@ -784,7 +784,7 @@ int score_sequences(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, 
                                      h->w.lnf_b, ws.acts.a, out_values ? h->w.value_w : nullptr, h->w.value_b,
                                      ws.val, s));
   // LM head + log-softmax.  With enough rows for the large-M kernel the logits never leave the
-  // accumulators: its epilogue reduces every 128-column part of a row to (max, sum of exp) and
+  // accumulators: its epilogue reduces every part of a row (one wave's columns) to (max, sum of exp) and
   // picks out the target token's logit, and a small kernel combines the parts.  Otherwise the
   // logits of a chunk of rows are materialised and reduced by a second kernel.
   LseArgs la;

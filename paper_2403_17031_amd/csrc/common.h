@@ -78,7 +78,8 @@ enum Epilogue {
   EPI_LSE = 4           // nothing stored but per-row softmax statistics of acc/T (scoring LM head)
 };
 
-// EPI_LSE: the product is a [rows, vocab] logits matrix that is never stored.  Each 128-column part p
+// EPI_LSE: the product is a [rows, vocab] logits matrix that is never stored.  Each part p (the columns of
+// one wave of a tile; gemm_lse_parts() of them per row)
 // of packed row t leaves max_v z and sum_v exp(z - max) (z = logit / temperature) in pmax/psum
 // [p * stride + t]; the part that holds the row's target token (the next token of the same
 // sequence) also leaves its z in ztgt[t].  launch_lse_combine turns these into log-probabilities.

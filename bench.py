@@ -32,14 +32,21 @@ def work_counts(cfg, n, resp, N):
     kv_tok = L * 2 * d * es              # K+V bytes of one cached token
     W = (L * (P_l + 3 * d + d + F + d + 4 * d) + V * d) * es   # bytes streamed per decode pass (no embed_in)
     kv_read = sum(kv_tok * (n + t + 1) for t in range(N - 1)).sum()
+    # Prefill of a rollout: the final layer forms K and V (and Q) for every row, but only the last row of each
+    # sequence goes through its attention, out-projection and MLP.
+    mm_pre = 2 * ((L - 1) * P_l + 3 * d * d) if L > 0 else 0
+    last_rows = 2 * (d * d + 2 * d * F) if L > 0 else 0
+    attn_pre = lambda k: (L - 1) * 4 * d * k * (k + 1) / 2 + 4 * d * k if L > 0 else 0 * k
     return dict(
-        prefill_flops=float((n * mm + attn(n)).sum() + B * lm),
+        prefill_flops=float((n * mm_pre + attn_pre(n)).sum() + B * (last_rows + lm)),
         score_flops=float((m * (mm + lm) + attn(m)).sum()),
         decode_bytes=float((N - 1) * W + kv_read + (N - 1) * B * kv_tok),
         decode_kv_read_bytes=float(kv_read),
         decode_flops=float((N - 1) * B * (mm + lm)),
-        gemm_flops_prefill=float(n.sum() * mm), gemm_flops_score=float(m.sum() * mm),
+        gemm_flops_prefill=float(n.sum() * mm_pre), gemm_flops_score=float(m.sum() * mm),
         lm_flops_score=float(m.sum() * lm), weights_bytes=float(W), real_score_tokens=float(m.sum()),
+        # the packed causal attention kernel: every layer of scoring, all but the final layer of prefill
+        attn_flops=float(attn(m).sum() + (attn(n).sum() * (L - 1) / L if L > 0 else 0.0)),
         real_query_tokens=float(n.sum()))
 
 
@@ -134,6 +141,26 @@ def main():
         rooflines["attn_decode"] = {"bound": "hbm", "achieved": ach / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                                     "frac": ach / HBM_PEAK, "traffic": a_traffic,
                                     "avg_launch_ms": prof["attn_decode"][0] / prof["attn_decode"][1]}
+    # the smaller kernel classes, each against the roof that bounds it (algorithmic work over measured time)
+    es = 4 if cfg.dtype == "fp32" else 2
+    Lr, dm = cfg.n_layers, cfg.d_model
+    tok_pre, tok_sc = wc["real_query_tokens"], wc["real_score_tokens"]
+
+    def _hbm(name, nbytes):
+        if name in prof and prof[name][0] > 0:
+            a_ = nbytes / (prof[name][0] * 1e-3)
+            rooflines[name] = {"bound": "hbm", "achieved": a_ / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                               "frac": a_ / HBM_PEAK, "traffic": None,
+                               "avg_launch_ms": prof[name][0] / prof[name][1]}
+
+    _hbm("layernorm", (tok_pre + tok_sc) * Lr * dm * (4 + 2 * es))       # fp32 row in, two normalised rows out
+    _hbm("rope_kv", (tok_pre + tok_sc) * Lr * 3 * dm * es * 2)           # q, k, v in; q and the K/V rows out
+    _hbm("gemm_decode", (N - 1) * (wc["weights_bytes"] - cfg.vocab * dm * es))  # layer weights once per pass
+    if "attn_prefill" in prof and prof["attn_prefill"][0] > 0:
+        a_ = wc["attn_flops"] / (prof["attn_prefill"][0] * 1e-3)
+        rooflines["attn_prefill"] = {"bound": "mfma", "achieved": a_ / 1e12, "peak": MFMA_PEAK / 1e12,
+                                     "unit": "TFLOP/s", "frac": a_ / MFMA_PEAK, "traffic": None,
+                                     "avg_launch_ms": prof["attn_prefill"][0] / prof["attn_prefill"][1]}
     roof = rooflines.get(dom) or rooflines.get("gemm") or {}
     roof = dict(roof, kernel=dom if dom in rooflines else "gemm")
 

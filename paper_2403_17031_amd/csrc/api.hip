@@ -554,7 +554,7 @@ int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, rlhf_handle
   if (c.dtype == RLHF_DTYPE_BF16) {
     const size_t d = c.d_model, F = c.d_ff;
     const size_t per_layer_elems = 3 * d * d + d * d + 2 * d * F;
-    const size_t total = per_layer_elems * c.n_layers + (size_t)c.vocab * d;
+    const size_t total = per_layer_elems * c.n_layers + (size_t)c.vocab * d + 3 * d * c.n_layers;
     hipError_t e = hipMalloc(&h->w16, total * 2);
     if (e != hipSuccess) {
       rlhf_destroy(h);
@@ -568,7 +568,13 @@ int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, rlhf_handle
     };
     h->ld_o2 = (int)(d + F);
     for (int l = 0; l < c.n_layers; ++l) {
-      conv(h->w_qkv[l], 3 * d * d);
+      // W_qkv with the rotary pairs of every q and k head made neighbours, and its bias likewise
+      char* bq = p + 3 * d * d * 2;
+      if (e == hipSuccess)
+        e = launch_qkv_weights_f16(h->w_qkv[l], h->b_qkv[l], p, bq, (int)d, c.head_dim, c.rotary_dims, nullptr);
+      h->w_qkv[l] = p;
+      h->b_qkv[l] = bq;
+      p += (3 * d * d + 3 * d) * 2;
       conv(h->w_fc1[l], d * F);
       if (e == hipSuccess) e = launch_bf16_to_f16_2d(h->w_o[l], p, d, d, d + F, nullptr);
       if (e == hipSuccess) e = launch_bf16_to_f16_2d(h->w_fc2[l], p + d * 2, d, F, d + F, nullptr);

@@ -245,6 +245,10 @@ hipError_t launch_adamw(float* p, const float* g, float* m, float* v, uint16_t* 
 // bf16 -> fp16 conversion of a weight matrix (exact within fp16's normal range).
 hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s);
 // Same for a [rows, cols] matrix written with row stride dst_ld (elements).
+// fp16 copy of W_qkv and a bf16 copy of its bias with the rotary dims of every q and k head
+// reordered pairwise ((i, i + r/2) -> (2i, 2i + 1)): the layout every fp16 rotary kernel assumes.
+hipError_t launch_qkv_weights_f16(const void* w, const void* b, void* w16, void* b_out, int d, int hd, int r,
+                                  hipStream_t s);
 hipError_t launch_bf16_to_f16_2d(const void* src, void* dst, size_t rows, size_t cols, size_t dst_ld, hipStream_t s);
 
 }  // namespace rlhf

@@ -509,6 +509,9 @@ __global__ void __launch_bounds__(256)
                    const int* __restrict__ len, int H, int hd,
                    int r, const float* __restrict__ cos_t, const float* __restrict__ sin_t, T* __restrict__ q,
                    T* __restrict__ kc, T* __restrict__ vc, long kv_extra) {
+  // fp16 (bf16-model) path: the rows of W_qkv were reordered when the handle was created so that
+  // the two dims of a rotary pair are neighbours (see launch_qkv_weights_f16)
+  constexpr bool ADJ = sizeof(T) == 2;
   const int t = blockIdx.x;
   if (rows_dev && t >= *rows_dev) return;
   const int d = H * hd;
@@ -523,7 +526,14 @@ __global__ void __launch_bounds__(256)
   for (int c = threadIdx.x; c < d; c += 256) {
     const int h = c / hd, e = c - h * hd;
     float qv = to_f32(src[c]), kv = to_f32(src[d + c]);
-    if (e < half) {
+    if (ADJ) {  // pair (2i, 2i+1) turns by angle i
+      if (e < r) {
+        const float co = cs[e >> 1], si = (e & 1) ? sn[e >> 1] : -sn[e >> 1];
+        const int cp = c - e + (e ^ 1);
+        qv = qv * co + to_f32(src[cp]) * si;
+        kv = kv * co + to_f32(src[d + cp]) * si;
+      }
+    } else if (e < half) {
       const float co = cs[e], si = sn[e];
       qv = qv * co - to_f32(src[c + half]) * si;
       kv = kv * co - to_f32(src[d + c + half]) * si;
@@ -545,7 +555,7 @@ __global__ void __launch_bounds__(256)
 // 2*hd-byte rows written by one CU.  Two passes: (1) one thread per (row, q|k, head) loads the
 // head's rotary dims (the first ceil(R/8) 16-byte chunks), rotates them in registers and stores
 // them; (2) every other chunk (rest of q and k, all of v) is a 16-byte copy.  R is a template
-// parameter so the rotation pairs (i, i + R/2) are register-to-register.
+// parameter so the rotation pairs (2i, 2i + 1: the reordered layout of the fp16 path) are register-to-register.
 template <int RPB, int R>
 __global__ void __launch_bounds__(256)
     rope_kv_vec_kernel(const half_t* __restrict__ qkv, int rows_max, const int* __restrict__ rows_dev,
@@ -587,9 +597,9 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
     for (int i = 0; i < HALF; ++i) {
       const float co = cs[i], si = sn[i];
-      const float lo = (float)v[i >> 3][i & 7], hi = (float)v[(i + HALF) >> 3][(i + HALF) & 7];
-      v[i >> 3][i & 7] = from_f32<half_t>(lo * co - hi * si);
-      v[(i + HALF) >> 3][(i + HALF) & 7] = from_f32<half_t>(hi * co + lo * si);
+      const float lo = (float)v[(2 * i) >> 3][(2 * i) & 7], hi = (float)v[(2 * i + 1) >> 3][(2 * i + 1) & 7];
+      v[(2 * i) >> 3][(2 * i) & 7] = from_f32<half_t>(lo * co - hi * si);
+      v[(2 * i + 1) >> 3][(2 * i + 1) & 7] = from_f32<half_t>(hi * co + lo * si);
     }
     half_t* dst = dst_of(sec, rr, h);
 #pragma unroll
@@ -675,9 +685,9 @@ __global__ void __launch_bounds__(256)
     const int rr = rs2 >> 1, sec = rs2 & 1;
     half_t* hb = tile + (rr * 3 + sec) * SEG + hl * HD;
     const float co = cos_t[(size_t)s_pos[rr] * HALF + i], si = sin_t[(size_t)s_pos[rr] * HALF + i];
-    const float lo = (float)hb[i], hi = (float)hb[i + HALF];
-    hb[i] = from_f32<half_t>(lo * co - hi * si);
-    hb[i + HALF] = from_f32<half_t>(hi * co + lo * si);
+    const float lo = (float)hb[2 * i], hi = (float)hb[2 * i + 1];
+    hb[2 * i] = from_f32<half_t>(lo * co - hi * si);
+    hb[2 * i + 1] = from_f32<half_t>(hi * co + lo * si);
   }
   __syncthreads();
   for (int c = threadIdx.x; c < nr * SEGC; c += 256) {  // q
@@ -781,9 +791,9 @@ __global__ void __launch_bounds__(256)
     const int u = c / half, i = c - u * half;
     half_t* hb = s_row + u * hd;
     const float co = cos_t[(size_t)p * half + i], si = sin_t[(size_t)p * half + i];
-    const float lo = (float)hb[i], hi = (float)hb[i + half];
-    hb[i] = from_f32<half_t>(lo * co - hi * si);
-    hb[i + half] = from_f32<half_t>(hi * co + lo * si);
+    const float lo = (float)hb[2 * i], hi = (float)hb[2 * i + 1];
+    hb[2 * i] = from_f32<half_t>(lo * co - hi * si);
+    hb[2 * i + 1] = from_f32<half_t>(hi * co + lo * si);
   }
   __syncthreads();
   const int b = rowid ? rowid[t] : t;
@@ -1094,6 +1104,28 @@ hipError_t launch_bf16_to_f16_2d(const void* src, void* dst, size_t rows, size_t
   const int blocks = (int)std::min<size_t>((rows * cols + 255) / 256, 65536);
   hipLaunchKernelGGL(bf16_to_f16_2d_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t*)src, (half_t*)dst, rows,
                      cols, dst_ld);
+  return hipGetLastError();
+}
+
+// W_qkv and its bias for the fp16 path: [q | k | v] sections of H heads.  Inside every q and k head
+// the rotary dims are reordered so that the pair (i, i + r/2) sits at (2i, 2i + 1); q.k is unchanged
+// by a reordering common to both, and neighbours can be turned by whoever holds two adjacent
+// columns (a GEMM epilogue lane) without any exchange.  One block per output row.
+__global__ void __launch_bounds__(256)
+    qkv_weights_f16_kernel(const bf16_t* __restrict__ w, const bf16_t* __restrict__ b, half_t* __restrict__ w16,
+                           bf16_t* __restrict__ b_out, int d, int hd, int r) {
+  const int n = blockIdx.x;  // destination row, 0 .. 3d-1
+  const int sec = n / d, e = (n - sec * d) % hd;
+  int src = n;
+  if (sec < 2 && e < r) src = n - e + ((e & 1) ? (e >> 1) + (r >> 1) : (e >> 1));
+  for (int c = threadIdx.x; c < d; c += 256) w16[(size_t)n * d + c] = (half_t)to_f32(w[(size_t)src * d + c]);
+  if (threadIdx.x == 0) b_out[n] = b[src];
+}
+
+hipError_t launch_qkv_weights_f16(const void* w, const void* b, void* w16, void* b_out, int d, int hd, int r,
+                                  hipStream_t s) {
+  hipLaunchKernelGGL(qkv_weights_f16_kernel, dim3(3 * d), dim3(256), 0, s, (const bf16_t*)w, (const bf16_t*)b,
+                     (half_t*)w16, (bf16_t*)b_out, d, hd, r);
   return hipGetLastError();
 }
 

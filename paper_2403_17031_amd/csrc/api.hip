@@ -316,6 +316,16 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
                                                      p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff, p.len,
                                                      c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q,
                                                      kc, vc, (long)p.kv_extra, s));
+    } else if (p.mode == 0 && gemm_takes_qkv(dt, g, c.n_heads, c.head_dim, c.rotary_dims)) {
+      // prefill / scoring: the rotary turn and the K/V store are the epilogue of the QKV product
+      QkvArgs qa;
+      qa.pos = p.pos; qa.rowid = p.rowid; qa.kvoff = p.kvoff; qa.len = p.len;
+      qa.cos_t = h->rope_cos; qa.sin_t = h->rope_sin;
+      qa.q = A.q; qa.kc = kc; qa.vc = vc; qa.kv_extra = (long)p.kv_extra;
+      qa.pos_add = p.pos_add; qa.H = c.n_heads; qa.hd = c.head_dim; qa.r = c.rotary_dims;
+      g.epilogue = EPI_QKV;
+      g.qkv = &qa;
+      LAUNCH("gemm", launch_gemm(dt, g, s));
     } else {
       LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
       LAUNCH(p.mode ? "rope_kv_decode" : "rope_kv", launch_rope_kv(dt, A.qkv, p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff,

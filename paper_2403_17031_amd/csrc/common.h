@@ -75,7 +75,8 @@ enum Epilogue {
   EPI_BIAS_GELU = 1,    // out[T]   = gelu_erf(acc + bias)
   EPI_BIAS_RESADD = 2,  // out[f32] += acc + bias      (residual stream update, in place)
   EPI_F32 = 3,          // out[f32] = acc              (logits)
-  EPI_LSE = 4           // nothing stored but per-row softmax statistics of acc/T (scoring LM head)
+  EPI_LSE = 4,          // nothing stored but per-row softmax statistics of acc/T (scoring LM head)
+  EPI_QKV = 5           // acc + bias with the rotary turn applied, q stored as rows, K and V into the cache
 };
 
 // EPI_LSE: the product is a [rows, vocab] logits matrix that is never stored.  Each part p (the columns of
@@ -98,7 +99,26 @@ struct LseArgs {
 // the same sequence.
 hipError_t launch_lse_combine(const LseArgs& a, int rows_max, int nparts, float* lp_packed, hipStream_t s);
 // True when launch_gemm would take EPI_LSE for these arguments (large-M fp16 kernel only).
+// EPI_QKV: the product is the [rows, 3*d] QKV matrix in sections q | k | v with the rotary pairs of a
+// head in neighbouring columns.  The epilogue adds the bias, turns the pairs by the row's position,
+// rounds to fp16 and stores q to q[row, d] and the K / V heads to the cache slot of (sequence, head,
+// position): what the product followed by the stand-alone rotary kernel leaves, without the
+// [rows, 3*d] intermediate.  Large-M fp16 kernel only.
+struct QkvArgs {
+  const int* pos;      // [rows] position of a packed row (+ pos_add)
+  const int* rowid;    // [rows] sequence of a packed row, or null (row = sequence)
+  const int* kvoff;    // [sequences] first cache slot of a sequence (in units of H slots)
+  const int* len;      // [sequences] real length; a head's slab holds len + kv_extra slots
+  const float* cos_t;  // [positions][r/2]
+  const float* sin_t;
+  void* q;             // [rows, d] fp16
+  void* kc;            // K cache, V cache (fp16)
+  void* vc;
+  long kv_extra;
+  int pos_add, H, hd, r;
+};
 struct GemmArgs;
+bool gemm_takes_qkv(int dtype, const GemmArgs& a, int H, int hd, int r);
 bool gemm_takes_lse(int dtype, const GemmArgs& a);
 int gemm_lse_parts(int n_cols);
 
@@ -116,6 +136,7 @@ struct GemmArgs {
   size_t splitk_ws_bytes = 0;
   int phase = 0;               // split-K only: 0 = GEMM + reduce, 1 = partial sums only, 2 = reduce only
   const struct LseArgs* lse = nullptr;  // EPI_LSE only
+  const struct QkvArgs* qkv = nullptr;  // EPI_QKV only
   int lda = 0, ldw = 0;        // row strides of A and W in elements (0: K); fp16 kernels only
   const void* bias2 = nullptr; // second bias added like the first; large-M fp16 kernel only
 };

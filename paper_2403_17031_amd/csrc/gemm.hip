@@ -19,6 +19,7 @@ typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
@@ -316,7 +317,7 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
     gemm_f16_dma_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
                         void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
                         int ldo, int nb_m, int nb_n, int lda, int ldw, const bf16_t* __restrict__ bias2,
-                        LseArgs lse) {
+                        LseArgs lse, QkvArgs qk) {
   // WAVES = 4: one wave per SIMD, each 128 x 128 of the tile (256 accumulator registers).
   // WAVES = 8: two waves per SIMD, each 128 x 64 (128 accumulator registers): what one wave cannot
   // overlap (waits, epilogue arithmetic against stores) the SIMD's other wave fills.
@@ -524,17 +525,53 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
         bias_v[j][g][3] += __uint_as_float(raw[1] & 0xFFFF0000u);
       }
     }
-  if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU) {
+  if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_QKV) {
+    // EPI_QKV: position of this lane's four rows, and for each of its eight 4-column groups the
+    // index of its first rotary angle (-1: the group is not rotary).  A group is two whole pairs.
+    const int qd = qk.H * qk.hd, qhalf = qk.r >> 1;
+    int prow[MT], ang[NT][4];
+    if (EPI == EPI_QKV) {
+#pragma unroll
+      for (int i = 0; i < MT; ++i) prow[i] = (qk.pos[min(m0 + wm + 32 * i + l32, M - 1)] + qk.pos_add) * qhalf;
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int c = n0 + wn + 32 * j + 8 * g + 4 * hf;
+          const int sec = c >= 2 * qd ? 2 : (c >= qd ? 1 : 0);
+          const int e = (c - sec * qd) % qk.hd;
+          ang[j][g] = (sec < 2 && e < qk.r && c < N) ? (e >> 1) : -1;
+        }
+    }
     auto put = [&](auto jc, auto ic) {
       constexpr int j = decltype(jc)::value, i = decltype(ic)::value;
       const int row = 32 * i + l32;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         f16x4_t h;
+        if (EPI == EPI_QKV) {
+          float v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const float v = acc[j][i][4 * g + u] + bias_v[j][g][u];
-          h[u] = from_f32<half_t>(EPI == EPI_BIAS_GELU ? gelu_f16out(v) : v);
+          for (int u = 0; u < 4; ++u) v[u] = acc[j][i][4 * g + u] + bias_v[j][g][u];
+          if (ang[j][g] >= 0) {
+            // the stand-alone kernel turns values already rounded to fp16: keep that order of roundings
+            const f32x2_t co = *(const f32x2_t*)(qk.cos_t + prow[i] + ang[j][g]);
+            const f32x2_t si = *(const f32x2_t*)(qk.sin_t + prow[i] + ang[j][g]);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+              const float lo = (float)from_f32<half_t>(v[2 * u]), hi = (float)from_f32<half_t>(v[2 * u + 1]);
+              v[2 * u] = lo * co[u] - hi * si[u];
+              v[2 * u + 1] = hi * co[u] + lo * si[u];
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) h[u] = from_f32<half_t>(v[u]);
+        } else {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float v = acc[j][i][4 * g + u] + bias_v[j][g][u];
+            h[u] = from_f32<half_t>(EPI == EPI_BIAS_GELU ? gelu_f16out(v) : v);
+          }
         }
         *(f16x4_t*)(ep + row * WN + (((4 * j + g) ^ (row & (CH - 1))) << 3) + 4 * hf) = h;
       }
@@ -549,6 +586,28 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
 #undef RLHF_ROW
     RLHF_WAVE_LDS_FENCE();
     const int gcol = n0 + wn + rd_c * 8;
+    if (EPI == EPI_QKV) {
+      // this lane's 16-byte chunk lies in one head of one section (head_dim is a multiple of 8)
+      const int sec = gcol >= 2 * qd ? 2 : (gcol >= qd ? 1 : 0);
+      const int hh = (gcol - sec * qd) / qk.hd, e = gcol - sec * qd - hh * qk.hd;
+      half_t* cache = (half_t*)(sec == 1 ? qk.kc : qk.vc);
+#pragma unroll 8
+      for (int it = 0; it < 128 / RPI; ++it) {
+        const int row = it * RPI + rd_row;
+        const int grow = m0 + wm + row;
+        const u32x4_t v = *(const u32x4_t*)(ep + row * WN + ((rd_c ^ (row & (CH - 1))) << 3));
+        if (grow < M && gcol < N) {
+          if (sec == 0) {
+            *(u32x4_t*)((half_t*)qk.q + (size_t)grow * qd + gcol) = v;
+          } else {
+            const int b = qk.rowid ? qk.rowid[grow] : grow;
+            const long slot = (long)qk.kvoff[b] * qk.H + (qk.pos[grow] + qk.pos_add) + (long)hh * (qk.len[b] + qk.kv_extra);
+            *(u32x4_t*)(cache + (size_t)slot * qk.hd + e) = v;
+          }
+        }
+      }
+      return;
+    }
 #pragma unroll 8
     for (int it = 0; it < 128 / RPI; ++it) {
       const int row = it * RPI + rd_row;
@@ -621,7 +680,7 @@ static void launch_f16_dma(const GemmArgs& a, hipStream_t s) {
   hipLaunchKernelGGL((gemm_f16_dma_kernel<EPI, WV>), dim3(per_xcd * 8), dim3(64 * WV), 0, s, (const half_t*)a.A,
                      (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
                      nb_m, nb_n, a.lda ? a.lda : a.K, a.ldw ? a.ldw : a.K, (const bf16_t*)a.bias2,
-                     a.lse ? *a.lse : LseArgs{});
+                     a.lse ? *a.lse : LseArgs{}, a.qkv ? *a.qkv : QkvArgs{});
 }
 
 #ifndef RLHF_GEMM_DMA
@@ -689,6 +748,12 @@ static bool takes_dma(const GemmArgs& a) {
 }
 bool gemm_takes_bias2(int dtype, const GemmArgs& a) { return dtype == 1 && takes_dma(a); }
 bool gemm_takes_lse(int dtype, const GemmArgs& a) { return dtype == 1 && takes_dma(a); }
+// EPI_QKV: 16-byte chunks must not straddle heads, a lane's 4-column group must be whole pairs, and the
+// cos / sin pairs are read as aligned 8-byte words.
+bool gemm_takes_qkv(int dtype, const GemmArgs& a, int H, int hd, int r) {
+  return dtype == 1 && takes_dma(a) && H > 0 && hd > 0 && (hd % 8) == 0 && (r % 4) == 0 && r <= hd &&
+         a.N == 3 * H * hd && a.bias != nullptr;
+}
 // Parts (column groups with their own max / sum-exp) the log-sum-exp epilogue leaves per row: one per wave
 // column of every 256-column tile.
 int gemm_lse_parts(int n_cols) { return (kDmaWaves == 8 ? 4 : 2) * ((n_cols + 255) / 256); }
@@ -735,6 +800,10 @@ hipError_t launch_gemm(int dtype, const GemmArgs& a, hipStream_t s) {
     case EPI_LSE:
       if (!a.lse || !gemm_takes_lse(dtype, a)) return hipErrorInvalidValue;
       launch_f16_dma<EPI_LSE>(a, s);
+      break;
+    case EPI_QKV:
+      if (!a.qkv || !gemm_takes_qkv(dtype, a, a.qkv->H, a.qkv->hd, a.qkv->r)) return hipErrorInvalidValue;
+      launch_f16_dma<EPI_QKV>(a, s);
       break;
     default: return hipErrorInvalidValue;
   }

@@ -321,3 +321,18 @@ def test_batches_beyond_the_few_rows_kernels(gpu, B, H, hd, Lq, N):
     queries, mask = _queries(cfg, B=B, Lq=Lq, lo=1, hi=Lq, seed=B)
     rows = [0, 1, B // 2, B - 2, B - 1]
     _check_rollout_and_scores(gpu, cfg, w, queries, mask, seed=B, T=0.7, N=N, rows=rows, expect_exact=False)
+
+
+@pytest.mark.parametrize("H,hd,r", [(16, 8, 4), (16, 8, 8), (2, 64, 0), (8, 16, 16), (8, 80, 20), (2, 64, 6), (4, 32, 2)])
+def test_rotary_layouts_with_many_rows(gpu, H, hd, r):
+    """Widths the large-tile GEMM takes (d_model a multiple of 128) with more than 512 packed rows, so that
+    prefill and scoring run the QKV product whose epilogue applies the rotary turn and stores K / V: heads of one
+    16-byte chunk, heads that straddle the 64-column wave tiles, full and absent rotary; and rotary widths that
+    are not a multiple of 4, which the epilogue declines and the stand-alone rotary kernels take."""
+    d = H * hd
+    cfg = ModelConfig(n_layers=2, d_model=d, n_heads=H, head_dim=hd, rotary_dims=r, d_ff=2 * d, vocab=517,
+                      dtype="bf16", pad_id=500)
+    w = make_weights(cfg, 57, variant="test")
+    queries, mask = _queries(cfg, B=24, Lq=48, lo=20, hi=48, seed=H * hd + r)
+    rows = sorted({0, 23, int(np.argmin(mask.sum(1)))})
+    _check_rollout_and_scores(gpu, cfg, w, queries, mask, seed=900 + r, T=0.7, N=3, rows=rows, expect_exact=False)

@@ -105,7 +105,8 @@ hipError_t launch_lse_combine(const LseArgs& a, int rows_max, int nparts, float*
 // position): what the product followed by the stand-alone rotary kernel leaves, without the
 // [rows, 3*d] intermediate.  Large-M fp16 kernel only.
 struct QkvArgs {
-  const int* pos;      // [rows] position of a packed row (+ pos_add)
+  const int* pos;      // [rows] position of a packed row (+ pos_add); rows are indexed from the start of the
+                       // packed batch: a launch over a row chunk (GemmArgs::M_sub) adds its offset
   const int* rowid;    // [rows] sequence of a packed row, or null (row = sequence)
   const int* kvoff;    // [sequences] first cache slot of a sequence (in units of H slots)
   const int* len;      // [sequences] real length; a head's slab holds len + kv_extra slots

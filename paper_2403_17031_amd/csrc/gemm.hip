@@ -532,7 +532,7 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
     int prow[MT], ang[NT][4];
     if (EPI == EPI_QKV) {
 #pragma unroll
-      for (int i = 0; i < MT; ++i) prow[i] = (qk.pos[min(m0 + wm + 32 * i + l32, M - 1)] + qk.pos_add) * qhalf;
+      for (int i = 0; i < MT; ++i) prow[i] = (qk.pos[M_sub + min(m0 + wm + 32 * i + l32, M - 1)] + qk.pos_add) * qhalf;
 #pragma unroll
       for (int j = 0; j < NT; ++j)
 #pragma unroll
@@ -597,11 +597,12 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
         const int grow = m0 + wm + row;
         const u32x4_t v = *(const u32x4_t*)(ep + row * WN + ((rd_c ^ (row & (CH - 1))) << 3));
         if (grow < M && gcol < N) {
+          const int t = M_sub + grow;  // packed row: the row chunk of this launch starts at M_sub
           if (sec == 0) {
-            *(u32x4_t*)((half_t*)qk.q + (size_t)grow * qd + gcol) = v;
+            *(u32x4_t*)((half_t*)qk.q + (size_t)t * qd + gcol) = v;
           } else {
-            const int b = qk.rowid ? qk.rowid[grow] : grow;
-            const long slot = (long)qk.kvoff[b] * qk.H + (qk.pos[grow] + qk.pos_add) + (long)hh * (qk.len[b] + qk.kv_extra);
+            const int b = qk.rowid ? qk.rowid[t] : t;
+            const long slot = (long)qk.kvoff[b] * qk.H + (qk.pos[t] + qk.pos_add) + (long)hh * (qk.len[b] + qk.kv_extra);
             *(u32x4_t*)(cache + (size_t)slot * qk.hd + e) = v;
           }
         }

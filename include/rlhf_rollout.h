@@ -190,6 +190,31 @@ int rlhf_adamw_step(float *param, const float *grad, float *exp_avg, float *exp_
                     uint64_t n, int32_t step, double lr, double beta1, double beta2, double eps,
                     double weight_decay, double grad_scale, void *stream);
 
+/* Backward pass through the output heads: from the gradients the loss head returns to the residual
+ * stream after the last decoder layer and to the head parameters (paper: the PPO update trains the
+ * policy and the value model by gradient descent on the loss of the PPO hyperparameter table; the
+ * heads are those of `score_sequences`: Tech stack for the GPT-NeoX final LayerNorm and untied LM
+ * head, Preliminaries Step 2 / PPO Details "Value model initializes from the reward model" for the
+ * scalar head, the sampling temperature dividing the logits).  For packed rows t < T with
+ *   h_t = LN_f(x_t),  z_t = W h_t,  lp_t = log softmax(z_t / temperature)[targets[t]],  v_t = w_v . h_t + b_v
+ * and a loss L with dL/dlp_t = d_logprobs[t] (ignored where targets[t] < 0) and dL/dv_t = d_values[t],
+ * every output is grad_scale times the gradient of L:
+ *   d_x [T, d]            w.r.t. x (the residual stream: what the layers' backward pass continues from)
+ *   d_lnf_g, d_lnf_b [d]  w.r.t. the final LayerNorm's gain and bias
+ *   d_embed_out [V, d]    w.r.t. the LM head (overwritten, not accumulated)
+ *   d_value_w [d], d_value_b [1]   w.r.t. the value head (required iff the model has one, with d_values)
+ * x_final: dev float [T, d]; targets: dev int32 [T], the token id row t predicts, or -1; all outputs
+ * dev float.  grad_scale (finite) exists because in bf16 mode dL/dz and h are fp16 matrix operands of
+ * the two gradient products: pick it so that grad_scale * d_logprobs / temperature is well inside
+ * fp16's range, and undo it in rlhf_adamw_step.  Sums over rows run in a fixed order (no
+ * floating-point atomics).  Logits exist for 4096 rows at a time inside the workspace, whose size
+ * rlhf_head_backward_workspace_bytes reports; RLHF_ENOMEM if it is smaller.  Work is enqueued on `stream`. */
+int rlhf_head_backward_workspace_bytes(const rlhf_handle *h, int32_t T, size_t *out);
+int rlhf_head_backward(rlhf_handle *h, const float *x_final, const int32_t *targets, const float *d_logprobs,
+                       const float *d_values, int32_t T, float temperature, float grad_scale, float *d_x,
+                       float *d_lnf_g, float *d_lnf_b, float *d_embed_out, float *d_value_w, float *d_value_b,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
 /* Debug / parity aid: raw (pre-temperature) fp32 logits of the same forward pass as
  * score_sequences at n (row, column) pairs.  rows_bt: HOST int32 [n, 2]; out_logits: dev float
  * [n, vocab].  Every pair must name a real position. */

@@ -15,6 +15,7 @@ EXPORTS = (
     "rlhf_create", "rlhf_destroy", "rlhf_workspace_bytes", "rollout_generate", "score_sequences",
     "rlhf_debug_logits_rows", "rlhf_profile_enable", "rlhf_profile_read", "rlhf_last_rollout_phases",
     "rlhf_last_error", "rlhf_ppo_assemble_rewards", "rlhf_ppo_gae", "rlhf_ppo_whiten", "rlhf_ppo_loss", "rlhf_adamw_step",
+    "rlhf_head_backward", "rlhf_head_backward_workspace_bytes",
 )
 
 _PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -66,6 +67,8 @@ def load_library():
     lib.rlhf_ppo_gae.argtypes = [vp, vp, C.c_int64, vp, i32, i32, f32, f32, vp, vp, vp]
     lib.rlhf_ppo_whiten.argtypes = [vp, vp, i32, i32, i32, vp, vp]
     lib.rlhf_ppo_loss.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp, vp, vp]
+    lib.rlhf_head_backward_workspace_bytes.argtypes = [vp, i32, C.POINTER(C.c_size_t)]
+    lib.rlhf_head_backward.argtypes = [vp, vp, vp, vp, vp, i32, C.c_float, C.c_float] + [vp] * 6 + [vp, C.c_size_t, vp]
     lib.rlhf_adamw_step.argtypes = [vp, vp, vp, vp, vp, u64, i32] + [C.c_double] * 6 + [vp]
     lib.rlhf_last_error.restype = C.c_char_p
     for n in EXPORTS:
@@ -117,6 +120,7 @@ class Policy:
             setattr(w, n, self._dev[n].data_ptr())
         w.value_w = self._dev["value_w"].data_ptr() if "value_w" in self._dev else None
         w.value_b = float(weights.get("value_b", 0.0))
+        self._has_value = "value_w" in self._dev
         self._h = C.c_void_p()
         with torch.cuda.device(self.device):
             _check(self.lib.rlhf_create(C.byref(c), C.byref(w), C.byref(self._h)))
@@ -187,6 +191,36 @@ class Policy:
                                             val.data_ptr() if want_values else None, ws.data_ptr(), ws.numel(),
                                             self._stream()))
         return lp, val
+
+    def head_backward(self, x_final, targets, d_logprobs, d_values, temperature, grad_scale=1.0):
+        """x_final float32 [T, d], targets int32 [T] (-1: no term), d_logprobs / d_values float32 [T].  Returns a
+        dict of CUDA float32 tensors: d_x [T, d], d_lnf_g [d], d_lnf_b [d], d_embed_out [V, d], and, if the model
+        has a value head, d_value_w [d] and d_value_b [1]; each is grad_scale times the gradient."""
+        torch = self.torch
+        x = self._to_dev(x_final, torch.float32)
+        y = self._to_dev(targets, torch.int32)
+        gl = self._to_dev(d_logprobs, torch.float32)
+        T, d = x.shape
+        if d != self.cfg.d_model or y.numel() != T or gl.numel() != T:
+            raise RlhfError("head_backward: x_final must be [T, d_model], targets and d_logprobs [T]")
+        has_v = self._has_value
+        gv = self._to_dev(d_values, torch.float32) if has_v else None
+        if has_v and gv.numel() != T:
+            raise RlhfError("head_backward: d_values must be [T]")
+        out = C.c_size_t()
+        _check(self.lib.rlhf_head_backward_workspace_bytes(self._h, T, C.byref(out)))
+        ws = self._workspace(out.value)
+        new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=self.device)
+        res = dict(d_x=new(T, d), d_lnf_g=new(d), d_lnf_b=new(d), d_embed_out=new(self.cfg.vocab, d))
+        if has_v:
+            res.update(d_value_w=new(d), d_value_b=new(1))
+        with torch.cuda.device(self.device):
+            _check(self.lib.rlhf_head_backward(
+                self._h, x.data_ptr(), y.data_ptr(), gl.data_ptr(), gv.data_ptr() if has_v else None, T, temperature,
+                grad_scale, res["d_x"].data_ptr(), res["d_lnf_g"].data_ptr(), res["d_lnf_b"].data_ptr(),
+                res["d_embed_out"].data_ptr(), res["d_value_w"].data_ptr() if has_v else None,
+                res["d_value_b"].data_ptr() if has_v else None, ws.data_ptr(), ws.numel(), self._stream()))
+        return res
 
     def debug_logits_rows(self, tokens, mask, rows_bt):
         torch = self.torch

@@ -649,6 +649,101 @@ int rlhf_workspace_bytes(const rlhf_handle* h, int32_t B, int32_t Lq, int32_t ma
   return RLHF_OK;
 }
 
+namespace {
+constexpr int kHeadChunk = 4096;  // rows whose logits and logit gradients exist at a time
+struct HeadBwdWs {
+  void *hl, *dz, *dzT, *hlT, *WT;
+  float *logits, *dhl, *stats, *part;
+  int chunk, chunk_pad, V_pad, splits;
+};
+HeadBwdWs carve_head_bwd(Carver& c, const rlhf_model_config& cfg, int T, size_t esz) {
+  HeadBwdWs w;
+  const size_t d = cfg.d_model, V = cfg.vocab;
+  w.chunk = std::min(T, kHeadChunk);
+  w.chunk_pad = (w.chunk + 127) & ~127;  // the row count of a chunk is the K of the weight-gradient product
+  w.V_pad = (int)((V + 7) & ~(size_t)7);  // the vocabulary is the K of the input-gradient product
+  w.splits = std::max(1, std::min(64, (T + 255) / 256));
+  w.hl = c.take_bytes((size_t)w.chunk_pad * d * esz);
+  w.logits = c.take<float>((size_t)w.chunk * V);
+  w.dz = c.take_bytes((size_t)w.chunk_pad * w.V_pad * esz);
+  w.dzT = c.take_bytes(V * (size_t)w.chunk_pad * esz);
+  w.hlT = c.take_bytes(d * (size_t)w.chunk_pad * esz);
+  w.WT = c.take_bytes(d * (size_t)w.V_pad * esz);
+  w.dhl = c.take<float>((size_t)T * d);
+  w.stats = c.take<float>((size_t)2 * T);
+  w.part = c.take<float>((size_t)w.splits * 3 * d);
+  return w;
+}
+}  // namespace
+
+int rlhf_head_backward_workspace_bytes(const rlhf_handle* h, int32_t T, size_t* out) {
+  if (!h || !out) return fail(RLHF_EINVAL, "null argument");
+  if (T <= 0) return fail(RLHF_EINVAL, "row count must be positive");
+  Carver c(nullptr);
+  carve_head_bwd(c, h->cfg, T, h->esz);
+  *out = c.off + 256;
+  return RLHF_OK;
+}
+
+int rlhf_head_backward(rlhf_handle* h, const float* x_final, const int32_t* targets, const float* d_logprobs,
+                       const float* d_values, int32_t T, float temperature, float grad_scale, float* d_x,
+                       float* d_lnf_g, float* d_lnf_b, float* d_embed_out, float* d_value_w, float* d_value_b,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (!h) return fail(RLHF_EINVAL, "null handle");
+  if (T <= 0) return fail(RLHF_EINVAL, "row count must be positive");
+  if ((size_t)T > (size_t)1 << 30) return fail(RLHF_EUNSUPPORTED, "too many rows");
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return fail(RLHF_EINVAL, "temperature must be > 0");
+  if (!std::isfinite(grad_scale)) return fail(RLHF_EINVAL, "grad_scale must be finite");
+  if (!x_final || !targets || !d_logprobs || !d_x || !d_lnf_g || !d_lnf_b || !d_embed_out || !workspace)
+    return fail(RLHF_EINVAL, "null pointer argument");
+  const rlhf_model_config& c = h->cfg;
+  const bool has_value = h->w.value_w != nullptr;
+  if (has_value && (!d_values || !d_value_w || !d_value_b))
+    return fail(RLHF_EINVAL, "the model has a value head: d_values, d_value_w and d_value_b are required");
+  Carver cv((void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255));
+  HeadBwdWs ws = carve_head_bwd(cv, c, T, h->esz);
+  if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
+    return fail(RLHF_ENOMEM, "workspace too small for rlhf_head_backward");
+  hipStream_t s = (hipStream_t)stream;
+  const int dt = c.dtype, d = c.d_model, V = c.vocab;
+  const size_t esz = h->esz;
+
+  // W^T [d, V_pad] (zero columns past V), and d_embed_out = 0: the chunks add into it
+  LAUNCH("head_bwd_prep", launch_transpose_pad(dt, h->embed_out_mm, (size_t)d, ws.WT, (size_t)ws.V_pad, V, d, ws.V_pad, s));
+  LAUNCH("head_bwd_prep", launch_fill_zero(d_embed_out, (size_t)V * d * sizeof(float), s));
+  for (int r0 = 0; r0 < T; r0 += ws.chunk) {
+    const int rows = std::min(ws.chunk, T - r0);
+    const int rows_pad = (rows + 127) & ~127;
+    // h = LN_f(x) for the chunk, rows past the chunk zero (they are columns of the K dimension below)
+    if (rows_pad > rows)
+      LAUNCH("head_bwd_prep", launch_fill_zero((char*)ws.hl + (size_t)rows * d * esz, (size_t)(rows_pad - rows) * d * esz, s));
+    LAUNCH("final_ln", launch_final_ln(dt, x_final + (size_t)r0 * d, nullptr, 0, rows, nullptr, d, c.ln_eps, h->w.lnf_g,
+                                       h->w.lnf_b, ws.hl, nullptr, 0.f, nullptr, s));
+    GemmArgs lm;  // z = h W^T
+    lm.A = ws.hl; lm.W = h->embed_out_mm; lm.bias = nullptr; lm.out = ws.logits;
+    lm.M_max = rows; lm.M_dev = nullptr; lm.N = V; lm.K = d; lm.ldo = V; lm.epilogue = EPI_F32;
+    LAUNCH("gemm_lm_head", launch_gemm(dt, lm, s));
+    LAUNCH("softmax_grad", launch_softmax_grad(dt, ws.logits, V, ws.V_pad, targets + r0, d_logprobs + r0, rows, rows_pad,
+                                               1.0f / temperature, grad_scale, ws.dz, s));
+    GemmArgs gi;  // dL/dh = dz W: the product of dz [rows, V] with the rows of W^T
+    gi.A = ws.dz; gi.W = ws.WT; gi.bias = nullptr; gi.out = ws.dhl + (size_t)r0 * d;
+    gi.M_max = rows; gi.M_dev = nullptr; gi.N = d; gi.K = ws.V_pad; gi.ldo = d; gi.epilogue = EPI_F32;
+    LAUNCH("gemm_head_dx", launch_gemm(dt, gi, s));
+    // dL/dW += dz^T h: rows of dz^T [V, rows_pad] against rows of h^T [d, rows_pad]
+    LAUNCH("head_bwd_transpose", launch_transpose_pad(dt, ws.dz, (size_t)ws.V_pad, ws.dzT, (size_t)rows_pad, rows_pad, V, rows_pad, s));
+    LAUNCH("head_bwd_transpose", launch_transpose_pad(dt, ws.hl, (size_t)d, ws.hlT, (size_t)rows_pad, rows_pad, d, rows_pad, s));
+    GemmArgs gw;
+    gw.A = ws.dzT; gw.W = ws.hlT; gw.bias = nullptr; gw.out = d_embed_out;
+    gw.M_max = V; gw.M_dev = nullptr; gw.N = d; gw.K = rows_pad; gw.ldo = d; gw.epilogue = EPI_BIAS_RESADD;
+    LAUNCH("gemm_head_dw", launch_gemm(dt, gw, s));
+  }
+  LAUNCH("head_ln_backward", launch_head_ln_backward(dt, x_final, ws.dhl, d_values, grad_scale, h->w.value_w, h->w.lnf_g,
+                                                     h->w.lnf_b, T, d, c.ln_eps, d_x, ws.stats, ws.part, ws.splits,
+                                                     d_lnf_g, d_lnf_b, has_value ? d_value_w : nullptr,
+                                                     has_value ? d_value_b : nullptr, s));
+  return RLHF_OK;
+}
+
 int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_mask, int32_t B, int32_t Lq,
                      uint64_t seed, uint64_t seq_id_base, float temperature, int32_t max_new_tokens,
                      int32_t* out_tokens, float* out_logprobs, int32_t* out_lengths, uint8_t* out_mask,

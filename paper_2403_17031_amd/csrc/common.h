@@ -265,6 +265,22 @@ hipError_t launch_adamw(float* p, const float* g, float* m, float* v, uint16_t* 
                         float eps, float grad_scale, hipStream_t s);
 
 // bf16 -> fp16 conversion of a weight matrix (exact within fp16's normal range).
+// ---- backward through the output heads (head_backward.hip); dtype 0: float operands, 1: fp16 ----
+// dst[c][r] = src[r][c] (r < R, c < C); dst columns R .. R_pad-1 are zeroed.
+hipError_t launch_transpose_pad(int dtype, const void* src, size_t ld_src, void* dst, size_t ld_dst, int R, int C,
+                                int R_pad, hipStream_t s);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);  // bytes: a multiple of 4
+// dz[r][v] = gl[r] * scale * inv_temp * (onehot(targets[r])[v] - softmax(logits[r] * inv_temp)[v]) for r < rows with
+// a target; zero for rows without one, rows rows .. rows_pad-1 and columns V .. V_pad-1.
+hipError_t launch_softmax_grad(int dtype, const float* logits, int V, int V_pad, const int* targets, const float* gl,
+                               int rows, int rows_pad, float inv_temp, float scale, void* dz, hipStream_t s);
+// dy = dhl + gv * scale * value_w; dx = LayerNorm input gradient of dy; d_g = sum_t dy * xhat, d_b = sum_t dy,
+// d_wv = sum_t gv * scale * h, d_bv = scale * sum_t gv.  stats [T, 2] and part [splits, 3, d] are scratch.
+hipError_t launch_head_ln_backward(int dtype, const float* x, const float* dhl, const float* gv, float scale,
+                                   const void* value_w, const void* g, const void* b, int T, int d, float eps,
+                                   float* dx, float* stats, float* part, int splits, float* d_g, float* d_b,
+                                   float* d_wv, float* d_bv, hipStream_t s);
+
 hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s);
 // Same for a [rows, cols] matrix written with row stride dst_ld (elements).
 // fp16 copy of W_qkv and a bf16 copy of its bias with the rotary dims of every q and k head

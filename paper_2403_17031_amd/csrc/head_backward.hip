@@ -1,0 +1,241 @@
+// Backward pass through the output heads (final LayerNorm, LM head with temperature, value head):
+// the element-wise and reduction kernels around the three matrix products, which run on the
+// library's GEMM kernels.  Sums over rows are taken in a fixed order (no floating-point atomics).
+#include <algorithm>
+
+#include "common.h"
+
+namespace rlhf {
+
+namespace {
+
+__device__ __forceinline__ float block_sum(float v, float* sh) {  // 256 threads; sh: 4 floats
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+__device__ __forceinline__ float block_max(float v, float* sh) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+}
+
+// dst[c][r] = src[r][c] for r < R, c < C; dst columns R .. R_pad-1 are zeroed.  32 x 32 tiles.
+template <typename T>
+__global__ void __launch_bounds__(256)
+    transpose_pad_kernel(const T* __restrict__ src, size_t ld_src, T* __restrict__ dst, size_t ld_dst, int R, int C,
+                         int R_pad) {
+  __shared__ T tile[32][33];
+  const int r0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = r0 + ty + 8 * i, c = c0 + tx;
+    T v = from_f32<T>(0.f);
+    if (r < R && c < C) v = src[(size_t)r * ld_src + c];
+    tile[ty + 8 * i][tx] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = c0 + ty + 8 * i, r = r0 + tx;
+    if (c < C && r < R_pad) dst[(size_t)c * ld_dst + r] = tile[tx][ty + 8 * i];
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) fill_zero_kernel(T* __restrict__ p, size_t n) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) p[i] = from_f32<T>(0.f);
+}
+
+// Row r of a chunk: dz[r][v] = gl[r] * scale / T * (onehot(y_r)[v] - softmax(logits[r] / T)[v]);
+// rows past `rows` (padding), rows without a target and columns V .. V_pad-1 are zero.
+template <typename T>
+__global__ void __launch_bounds__(256)
+    softmax_grad_kernel(const float* __restrict__ logits, int V, int V_pad, const int* __restrict__ targets,
+                        const float* __restrict__ gl, int rows, float inv_temp, float scale, T* __restrict__ dz) {
+  __shared__ float sh[4];
+  const int r = blockIdx.x;
+  T* out = dz + (size_t)r * V_pad;
+  const int y = r < rows ? targets[r] : -1;
+  if (y < 0 || y >= V) {  // block-uniform
+    for (int v = threadIdx.x; v < V_pad; v += 256) out[v] = from_f32<T>(0.f);
+    return;
+  }
+  const float* z = logits + (size_t)r * V;
+  float mx = -INFINITY;
+  for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
+  mx = block_max(mx, sh) * inv_temp;
+  float sum = 0.f;
+  for (int v = threadIdx.x; v < V; v += 256) sum += __expf(z[v] * inv_temp - mx);
+  sum = block_sum(sum, sh);
+  const float c = gl[r] * scale * inv_temp, inv_sum = 1.0f / sum;
+  for (int v = threadIdx.x; v < V_pad; v += 256) {
+    float g = 0.f;
+    if (v < V) g = c * ((v == y ? 1.0f : 0.0f) - __expf(z[v] * inv_temp - mx) * inv_sum);
+    out[v] = from_f32<T>(g);
+  }
+}
+
+// One block per row: statistics of x, dy = dhl + gv * scale * w_v, and the LayerNorm input gradient
+//   dx = rstd * (u - mean(u) - xh * mean(u * xh)),  u = dy * g,  xh = (x - mean) * rstd.
+// mean and rstd are kept for the column sums.
+template <typename W>
+__global__ void __launch_bounds__(256)
+    ln_backward_kernel(const float* __restrict__ x, const float* __restrict__ dhl, const float* __restrict__ gv,
+                       float scale, const W* __restrict__ value_w, const W* __restrict__ g, int d, float eps,
+                       float* __restrict__ dx, float* __restrict__ stats) {
+  __shared__ float sh[4];
+  const size_t t = blockIdx.x;
+  const float* xr = x + t * d;
+  const float* dr = dhl + t * d;
+  float s = 0.f;
+  for (int c = threadIdx.x; c < d; c += 256) s += xr[c];
+  const float mean = block_sum(s, sh) / (float)d;
+  float q = 0.f;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const float e = xr[c] - mean;
+    q += e * e;
+  }
+  const float rstd = 1.0f / sqrtf(block_sum(q, sh) / (float)d + eps);
+  const float gvt = value_w ? gv[t] * scale : 0.f;
+  float su = 0.f, sux = 0.f;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const float dy = dr[c] + (value_w ? gvt * to_f32(value_w[c]) : 0.f);
+    const float u = dy * to_f32(g[c]), xh = (xr[c] - mean) * rstd;
+    su += u;
+    sux += u * xh;
+  }
+  const float mu = block_sum(su, sh) / (float)d;
+  const float mux = block_sum(sux, sh) / (float)d;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const float dy = dr[c] + (value_w ? gvt * to_f32(value_w[c]) : 0.f);
+    const float u = dy * to_f32(g[c]), xh = (xr[c] - mean) * rstd;
+    dx[t * d + c] = rstd * (u - mu - xh * mux);
+  }
+  if (threadIdx.x == 0) {
+    stats[2 * t] = mean;
+    stats[2 * t + 1] = rstd;
+  }
+}
+
+// Column sums over a range of rows: block (column block, row split) leaves, for each of its 256
+// columns, sum dy * xh, sum dy and sum gv * h over its rows (h = the final LayerNorm's output in the
+// activation type A, as the forward pass produces it).  part: [splits][3][d].
+template <typename W, typename A>
+__global__ void __launch_bounds__(256)
+    head_colsum_kernel(const float* __restrict__ x, const float* __restrict__ dhl, const float* __restrict__ gv,
+                       float scale, const W* __restrict__ value_w, const W* __restrict__ g, const W* __restrict__ b,
+                       const float* __restrict__ stats, int T, int d, int rows_per_split, float* __restrict__ part) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  const int t0 = blockIdx.y * rows_per_split, t1 = min(T, t0 + rows_per_split);
+  if (c >= d) return;
+  const float gc = to_f32(g[c]), bc = to_f32(b[c]), wv = value_w ? to_f32(value_w[c]) : 0.f;
+  float sg = 0.f, sb = 0.f, sw = 0.f;
+  for (int t = t0; t < t1; ++t) {
+    const float gvt = value_w ? gv[t] * scale : 0.f;
+    const float dy = dhl[(size_t)t * d + c] + gvt * wv;
+    const float xh = (x[(size_t)t * d + c] - stats[2 * t]) * stats[2 * t + 1];
+    sg += dy * xh;
+    sb += dy;
+    sw += gvt * to_f32(from_f32<A>(xh * gc + bc));
+  }
+  float* p = part + (size_t)blockIdx.y * 3 * d;
+  p[c] = sg;
+  p[d + c] = sb;
+  p[2 * d + c] = sw;
+}
+
+// Adds the row splits in index order; thread block 0 also sums gv over all rows (fixed order:
+// per-thread strided partial sums, then the block tree).
+__global__ void __launch_bounds__(256)
+    head_colsum_final_kernel(const float* __restrict__ part, int splits, int d, const float* __restrict__ gv,
+                             float scale, int T, float* __restrict__ d_g, float* __restrict__ d_b,
+                             float* __restrict__ d_wv, float* __restrict__ d_bv) {
+  __shared__ float sh[4];
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c < d) {
+    float sg = 0.f, sb = 0.f, sw = 0.f;
+    for (int z = 0; z < splits; ++z) {
+      const float* p = part + (size_t)z * 3 * d;
+      sg += p[c];
+      sb += p[d + c];
+      sw += p[2 * d + c];
+    }
+    d_g[c] = sg;
+    d_b[c] = sb;
+    if (d_wv) d_wv[c] = sw;
+  }
+  if (blockIdx.x == 0 && d_bv) {
+    float s = 0.f;
+    for (int t = threadIdx.x; t < T; t += 256) s += gv[t];
+    s = block_sum(s, sh);
+    if (threadIdx.x == 0) *d_bv = s * scale;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_transpose_pad(int dtype, const void* src, size_t ld_src, void* dst, size_t ld_dst, int R, int C,
+                                int R_pad, hipStream_t s) {
+  if (R_pad <= 0 || C <= 0) return hipSuccess;
+  dim3 grid((R_pad + 31) / 32, (C + 31) / 32);
+  if (dtype == 0)
+    hipLaunchKernelGGL(transpose_pad_kernel<float>, grid, dim3(256), 0, s, (const float*)src, ld_src, (float*)dst,
+                       ld_dst, R, C, R_pad);
+  else
+    hipLaunchKernelGGL(transpose_pad_kernel<half_t>, grid, dim3(256), 0, s, (const half_t*)src, ld_src, (half_t*)dst,
+                       ld_dst, R, C, R_pad);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  const size_t n = bytes / 4;  // callers pass multiples of 4 bytes
+  const int blocks = (int)std::min<size_t>((n + 255) / 256, 65536);
+  hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(blocks), dim3(256), 0, s, (float*)p, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_grad(int dtype, const float* logits, int V, int V_pad, const int* targets, const float* gl,
+                               int rows, int rows_pad, float inv_temp, float scale, void* dz, hipStream_t s) {
+  if (rows_pad <= 0) return hipSuccess;
+  if (dtype == 0)
+    hipLaunchKernelGGL(softmax_grad_kernel<float>, dim3(rows_pad), dim3(256), 0, s, logits, V, V_pad, targets, gl,
+                       rows, inv_temp, scale, (float*)dz);
+  else
+    hipLaunchKernelGGL(softmax_grad_kernel<half_t>, dim3(rows_pad), dim3(256), 0, s, logits, V, V_pad, targets, gl,
+                       rows, inv_temp, scale, (half_t*)dz);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_ln_backward(int dtype, const float* x, const float* dhl, const float* gv, float scale,
+                                   const void* value_w, const void* g, const void* b, int T, int d, float eps,
+                                   float* dx, float* stats, float* part, int splits, float* d_g, float* d_b,
+                                   float* d_wv, float* d_bv, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  const int rps = (T + splits - 1) / splits;
+  dim3 cgrid((d + 255) / 256, splits);
+  if (dtype == 0) {
+    hipLaunchKernelGGL(ln_backward_kernel<float>, dim3(T), dim3(256), 0, s, x, dhl, gv, scale, (const float*)value_w,
+                       (const float*)g, d, eps, dx, stats);
+    hipLaunchKernelGGL((head_colsum_kernel<float, float>), cgrid, dim3(256), 0, s, x, dhl, gv, scale,
+                       (const float*)value_w, (const float*)g, (const float*)b, stats, T, d, rps, part);
+  } else {
+    hipLaunchKernelGGL(ln_backward_kernel<bf16_t>, dim3(T), dim3(256), 0, s, x, dhl, gv, scale,
+                       (const bf16_t*)value_w, (const bf16_t*)g, d, eps, dx, stats);
+    hipLaunchKernelGGL((head_colsum_kernel<bf16_t, half_t>), cgrid, dim3(256), 0, s, x, dhl, gv, scale,
+                       (const bf16_t*)value_w, (const bf16_t*)g, (const bf16_t*)b, stats, T, d, rps, part);
+  }
+  hipLaunchKernelGGL(head_colsum_final_kernel, dim3((d + 255) / 256), dim3(256), 0, s, part, splits, d, gv, scale, T,
+                     d_g, d_b, d_wv, d_bv);
+  return hipGetLastError();
+}
+
+}  // namespace rlhf

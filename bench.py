@@ -206,6 +206,29 @@ def main():
                           "frac": ach / HBM_PEAK, "traffic": None, "avg_launch_ms": adamw_ms}
     del o_p, o_g, o_m, o_v, o_b
 
+    # The backward pass through the output heads over the batch's B*N response positions (what the PPO
+    # update differentiates): three products of 2*T*V*d flop each (logits, dL/dh, dL/dW).  Outside the
+    # headline metric.
+    T_hb = B * N
+    g_hb = torch.Generator(device="cuda").manual_seed(7)
+    x_hb = torch.randn(T_hb, cfg.d_model, device="cuda", generator=g_hb) * 2.0
+    y_hb = torch.randint(0, cfg.vocab, (T_hb,), device="cuda", generator=g_hb, dtype=torch.int32)
+    gl_hb = torch.randn(T_hb, device="cuda", generator=g_hb) / T_hb
+    gv_hb = torch.randn(T_hb, device="cuda", generator=g_hb) / T_hb
+    for i in range(1 + 2):
+        if i == 1:
+            e0.record()
+        hb = pol.head_backward(x_hb, y_hb, gl_hb, gv_hb, wl.temperature, grad_scale=64.0 * T_hb)
+    e1.record()
+    torch.cuda.synchronize()
+    head_bwd_ms = e0.elapsed_time(e1) / 2
+    ach = 3 * 2.0 * T_hb * cfg.vocab * cfg.d_model / (head_bwd_ms * 1e-3)
+    hb_peak = MFMA_PEAK if cfg.dtype != "fp32" else 157.3e12
+    rooflines["head_backward"] = {"bound": "mfma", "achieved": ach / 1e12, "peak": hb_peak / 1e12, "unit": "TFLOP/s",
+                                  "frac": ach / hb_peak, "traffic": None, "avg_launch_ms": head_bwd_ms,
+                                  "rows": T_hb}
+    del x_hb, y_hb, gl_hb, gv_hb, hb
+
     # The paper's other scoring shapes (reward-model batches of 638 tokens, long-context batches of 2021),
     # right-padded with true lengths uniform in [L/4, L]; outside the headline metric.
     extra = None
@@ -255,7 +278,7 @@ def main():
         "rescoring_tok_s_padded": B * (wl.query_len + N) / (score_ms * 1e-3),
         "score_mfma_frac": wc["score_flops"] / (score_ms * 1e-3) / MFMA_PEAK,
         "roofline": roof, "rooflines": rooflines, "kernels_ms": kern, "profiled_step_ms": tot,
-        "ppo_signals_ms": signals_ms, "adamw_ms_per_2p30_params": adamw_ms, "extra_score_shapes": extra,
+        "ppo_signals_ms": signals_ms, "adamw_ms_per_2p30_params": adamw_ms, "head_backward_ms": head_bwd_ms, "extra_score_shapes": extra,
         "cpu_baseline": cpu, "setup_s": setup_s,
     }
     print(json.dumps(out))

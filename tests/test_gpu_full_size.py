@@ -112,3 +112,41 @@ def test_config5_pythia6p9b_full_batch(gpu):
     _check_any_size_properties(wl, queries, mask, out)
     rows = [int(np.argmin(mask.sum(1)))]
     print("config 5: oracle/GPU token differences inside the near-tie band:", _grade_rows(wl, w, queries, mask, out, rows))
+
+
+@pytest.mark.timeout(600)
+def test_head_backward_at_the_2p8b_width(gpu):
+    """The output heads of the benchmark model (d_model 2560, vocabulary 50,304) over the response positions of a
+    full batch (256 x 53 rows, four chunks of logits): the oracle recomputes sampled rows of d_x one by one; what
+    holds at any size is checked on the whole result (the LM-head gradient sums to zero over the vocabulary, its
+    rows for tokens that are no row's target are minus the softmax-weighted sums and therefore small and finite,
+    d_x rows have zero mean, rows without any gradient are zero)."""
+    from oracle.head_backward_oracle import head_backward
+    wl = WORKLOADS[4]
+    cfg = wl.model.with_(n_layers=0)
+    w = make_weights(cfg, wl.weight_seed)
+    T = 256 * 53
+    g = np.random.default_rng(99)
+    x = (g.normal(0.0, 2.0, (T, cfg.d_model))).astype(np.float32)
+    y = g.integers(0, cfg.vocab, T).astype(np.int32)
+    y[::7] = -1
+    gl = (g.normal(0.0, 1.0, T) / T).astype(np.float32)
+    gv = (g.normal(0.0, 0.1, T) / T).astype(np.float32)
+    gl[5], gv[5], y[5] = 0.0, 0.0, -1
+    scale = 64.0 * T
+    pol = gpu.Policy(cfg, w)
+    got = pol.head_backward(x, y, gl, gv, 0.7, grad_scale=scale)
+    dx = got["d_x"].cpu().numpy().astype(np.float64) / scale
+    dW = got["d_embed_out"].double() / scale
+    assert np.isfinite(dx).all() and bool(dW.isfinite().all())
+    assert np.abs(dx.mean(1)).max() <= 1e-5 * np.abs(dx).max()
+    assert np.all(dx[5] == 0.0)
+    col = dW.sum(0).abs().max().item()
+    assert col <= 2e-3 * dW.abs().sum(0).max().item()
+    rows = [0, 1, 4095, 4096, 9000, T - 1]
+    for t in rows:
+        ref = head_backward(x[t:t + 1], w["lnf_g"], w["lnf_b"], w["embed_out"], w["value_w"], y[t:t + 1], gl[t:t + 1],
+                            gv[t:t + 1], 0.7, ln_eps=cfg.ln_eps)["d_x"][0]
+        assert np.abs(dx[t] - ref).max() <= 2e-2 * np.abs(ref).max(), t
+        assert np.linalg.norm(dx[t] - ref) <= 5e-3 * np.linalg.norm(ref), t
+    pol.close()

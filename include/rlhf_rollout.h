@@ -207,7 +207,7 @@ int rlhf_adamw_step(float *param, const float *grad, float *exp_avg, float *exp_
  * dev float.  grad_scale (finite) exists because in bf16 mode dL/dz and h are fp16 matrix operands of
  * the two gradient products: pick it so that grad_scale * d_logprobs / temperature is well inside
  * fp16's range, and undo it in rlhf_adamw_step.  Sums over rows run in a fixed order (no
- * floating-point atomics).  Logits exist for 4096 rows at a time inside the workspace, whose size
+ * floating-point atomics).  Logits exist for 16,384 rows at a time inside the workspace, whose size
  * rlhf_head_backward_workspace_bytes reports; RLHF_ENOMEM if it is smaller.  Work is enqueued on `stream`. */
 int rlhf_head_backward_workspace_bytes(const rlhf_handle *h, int32_t T, size_t *out);
 int rlhf_head_backward(rlhf_handle *h, const float *x_final, const int32_t *targets, const float *d_logprobs,

@@ -650,7 +650,8 @@ int rlhf_workspace_bytes(const rlhf_handle* h, int32_t B, int32_t Lq, int32_t ma
 }
 
 namespace {
-constexpr int kHeadChunk = 4096;  // rows whose logits and logit gradients exist at a time
+constexpr int kHeadChunk = 16384;  // rows whose logits and logit gradients exist at a time (3.3 GB of fp32 logits
+                                   // at a 50k vocabulary): one chunk covers a rollout batch's response positions
 struct HeadBwdWs {
   void *hl, *dz, *dzT, *hlT, *WT;
   float *logits, *dhl, *stats, *part;

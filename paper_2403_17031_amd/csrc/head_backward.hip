@@ -9,6 +9,9 @@ namespace rlhf {
 
 namespace {
 
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
+
 __device__ __forceinline__ float block_sum(float v, float* sh) {  // 256 threads; sh: 4 floats
   v = wave_sum(v);
   __syncthreads();
@@ -47,6 +50,34 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+// fp16 form with 8-byte accesses: 64 x 64 tiles, a thread moves 4 consecutive halfs on both sides.
+// Needs ld_src, ld_dst multiples of 4, and R_pad, C multiples of 4 (so every quad is inside or outside as a whole); src
+// rows R .. R_pad-1 are not read (the destination gets zeros there).
+__global__ void __launch_bounds__(256)
+    transpose_pad_f16x4_kernel(const half_t* __restrict__ src, size_t ld_src, half_t* __restrict__ dst, size_t ld_dst,
+                               int R, int C, int R_pad) {
+  __shared__ half_t tile[64][64 + 4];
+  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const int tq = threadIdx.x & 15, tr = threadIdx.x >> 4;  // quad within a row of the tile, row within a pass
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = r0 + tr + 16 * i, c = c0 + 4 * tq;
+    f16x4_t v = {0, 0, 0, 0};
+    if (r < R && c < C) v = *(const f16x4_t*)(src + (size_t)r * ld_src + c);
+    *(f16x4_t*)&tile[tr + 16 * i][4 * tq] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = c0 + tr + 16 * i, r = r0 + 4 * tq;
+    if (c < C && r < R_pad) {
+      const f16x4_t v = {tile[4 * tq][tr + 16 * i], tile[4 * tq + 1][tr + 16 * i], tile[4 * tq + 2][tr + 16 * i],
+                         tile[4 * tq + 3][tr + 16 * i]};
+      *(f16x4_t*)(dst + (size_t)c * ld_dst + r) = v;
+    }
+  }
+}
+
 template <typename T>
 __global__ void __launch_bounds__(256) fill_zero_kernel(T* __restrict__ p, size_t n) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -56,30 +87,100 @@ __global__ void __launch_bounds__(256) fill_zero_kernel(T* __restrict__ p, size_
 
 // Row r of a chunk: dz[r][v] = gl[r] * scale / T * (onehot(y_r)[v] - softmax(logits[r] / T)[v]);
 // rows past `rows` (padding), rows without a target and columns V .. V_pad-1 are zero.
-template <typename T>
-__global__ void __launch_bounds__(256)
+// One block of 1024 threads per row; the row is read once and kept in registers (up to NPT values
+// per thread, i.e. vocabularies up to 1024 * NPT), longer rows are re-read from memory.
+constexpr int SG_THREADS = 1024, SG_NPT = 64;
+__device__ __forceinline__ float block_sum_1024(float v, float* sh) {  // sh: 16 floats
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) t += sh[i];
+  return t;
+}
+__device__ __forceinline__ float block_max_1024(float v, float* sh) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float t = sh[0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) t = fmaxf(t, sh[i]);
+  return t;
+}
+// store 4 consecutive values of type T (16 or 8 bytes)
+__device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
+  *(f32x4_t*)p = (f32x4_t){a, b, c, d};
+}
+__device__ __forceinline__ void store4(half_t* p, float a, float b, float c, float d) {
+  *(f16x4_t*)p = (f16x4_t){from_f32<half_t>(a), from_f32<half_t>(b), from_f32<half_t>(c), from_f32<half_t>(d)};
+}
+// MODE 0: rows re-read from memory, any V.  MODE 1: the row is read once, 4 consecutive values per
+// access (V a multiple of 4 -- rows are then 16-byte aligned -- and at most 4 * 1024 * NQ values).
+template <typename T, int MODE>
+__global__ void __launch_bounds__(SG_THREADS)
     softmax_grad_kernel(const float* __restrict__ logits, int V, int V_pad, const int* __restrict__ targets,
                         const float* __restrict__ gl, int rows, float inv_temp, float scale, T* __restrict__ dz) {
-  __shared__ float sh[4];
+  constexpr int NQ = SG_NPT / 4;  // quads per thread
+  __shared__ float sh[16];
   const int r = blockIdx.x;
   T* out = dz + (size_t)r * V_pad;
   const int y = r < rows ? targets[r] : -1;
   if (y < 0 || y >= V) {  // block-uniform
-    for (int v = threadIdx.x; v < V_pad; v += 256) out[v] = from_f32<T>(0.f);
+    for (int v = threadIdx.x; v < V_pad; v += SG_THREADS) out[v] = from_f32<T>(0.f);
     return;
   }
   const float* z = logits + (size_t)r * V;
+  f32x4_t zr[MODE == 1 ? NQ : 1];
   float mx = -INFINITY;
-  for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
-  mx = block_max(mx, sh) * inv_temp;
+  if (MODE == 1) {
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      const int v = 4 * (threadIdx.x + i * SG_THREADS);
+      zr[i] = (f32x4_t){-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      if (v < V) zr[i] = *(const f32x4_t*)(z + v) * inv_temp;
+      mx = fmaxf(fmaxf(mx, fmaxf(zr[i][0], zr[i][1])), fmaxf(zr[i][2], zr[i][3]));
+    }
+  } else {
+    for (int v = threadIdx.x; v < V; v += SG_THREADS) mx = fmaxf(mx, z[v] * inv_temp);
+  }
+  mx = block_max_1024(mx, sh);
   float sum = 0.f;
-  for (int v = threadIdx.x; v < V; v += 256) sum += __expf(z[v] * inv_temp - mx);
-  sum = block_sum(sum, sh);
-  const float c = gl[r] * scale * inv_temp, inv_sum = 1.0f / sum;
-  for (int v = threadIdx.x; v < V_pad; v += 256) {
-    float g = 0.f;
-    if (v < V) g = c * ((v == y ? 1.0f : 0.0f) - __expf(z[v] * inv_temp - mx) * inv_sum);
-    out[v] = from_f32<T>(g);
+  if (MODE == 1) {
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        zr[i][u] = __expf(zr[i][u] - mx);  // exp(-inf) = 0 past the end of the row
+        sum += zr[i][u];
+      }
+    }
+  } else {
+    for (int v = threadIdx.x; v < V; v += SG_THREADS) sum += __expf(z[v] * inv_temp - mx);
+  }
+  sum = block_sum_1024(sum, sh);
+  const float c = gl[r] * scale * inv_temp, ci = -c / sum;
+  if (MODE == 1) {
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      const int v = 4 * (threadIdx.x + i * SG_THREADS);
+      if (v < V) {
+        float o[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) o[u] = zr[i][u] * ci + (v + u == y ? c : 0.f);
+        store4(out + v, o[0], o[1], o[2], o[3]);
+      } else if (v < V_pad) {  // V_pad - V < 8 and both are multiples of 4: one quad at most
+        store4(out + v, 0.f, 0.f, 0.f, 0.f);
+      }
+    }
+  } else {
+    for (int v = threadIdx.x; v < V_pad; v += SG_THREADS) {
+      float g = 0.f;
+      if (v < V) g = __expf(z[v] * inv_temp - mx) * ci + (v == y ? c : 0.f);
+      out[v] = from_f32<T>(g);
+    }
   }
 }
 
@@ -189,6 +290,10 @@ hipError_t launch_transpose_pad(int dtype, const void* src, size_t ld_src, void*
   if (dtype == 0)
     hipLaunchKernelGGL(transpose_pad_kernel<float>, grid, dim3(256), 0, s, (const float*)src, ld_src, (float*)dst,
                        ld_dst, R, C, R_pad);
+  else if ((ld_src & 3) == 0 && (ld_dst & 3) == 0 && (R_pad & 3) == 0 && (C & 3) == 0 && (R & 3) == 0 &&
+           (((uintptr_t)src | (uintptr_t)dst) & 7) == 0)
+    hipLaunchKernelGGL(transpose_pad_f16x4_kernel, dim3((R_pad + 63) / 64, (C + 63) / 64), dim3(256), 0, s,
+                       (const half_t*)src, ld_src, (half_t*)dst, ld_dst, R, C, R_pad);
   else
     hipLaunchKernelGGL(transpose_pad_kernel<half_t>, grid, dim3(256), 0, s, (const half_t*)src, ld_src, (half_t*)dst,
                        ld_dst, R, C, R_pad);
@@ -206,12 +311,16 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
 hipError_t launch_softmax_grad(int dtype, const float* logits, int V, int V_pad, const int* targets, const float* gl,
                                int rows, int rows_pad, float inv_temp, float scale, void* dz, hipStream_t s) {
   if (rows_pad <= 0) return hipSuccess;
-  if (dtype == 0)
-    hipLaunchKernelGGL(softmax_grad_kernel<float>, dim3(rows_pad), dim3(256), 0, s, logits, V, V_pad, targets, gl,
-                       rows, inv_temp, scale, (float*)dz);
-  else
-    hipLaunchKernelGGL(softmax_grad_kernel<half_t>, dim3(rows_pad), dim3(256), 0, s, logits, V, V_pad, targets, gl,
-                       rows, inv_temp, scale, (half_t*)dz);
+  const int mode = ((V & 3) == 0 && V_pad <= SG_THREADS * SG_NPT) ? 1 : 0;
+#define RLHF_SG(TT, MD)                                                                                          \
+  hipLaunchKernelGGL((softmax_grad_kernel<TT, MD>), dim3(rows_pad), dim3(SG_THREADS), 0, s, logits, V, V_pad, targets, \
+                     gl, rows, inv_temp, scale, (TT*)dz)
+  if (dtype == 0) {
+    if (mode) RLHF_SG(float, 1); else RLHF_SG(float, 0);
+  } else {
+    if (mode) RLHF_SG(half_t, 1); else RLHF_SG(half_t, 0);
+  }
+#undef RLHF_SG
   return hipGetLastError();
 }
 

@@ -117,7 +117,7 @@ def test_config5_pythia6p9b_full_batch(gpu):
 @pytest.mark.timeout(600)
 def test_head_backward_at_the_2p8b_width(gpu):
     """The output heads of the benchmark model (d_model 2560, vocabulary 50,304) over the response positions of a
-    full batch (256 x 53 rows, four chunks of logits): the oracle recomputes sampled rows of d_x one by one; what
+    full batch (256 x 53 rows): the oracle recomputes sampled rows of d_x one by one; what
     holds at any size is checked on the whole result (the LM-head gradient sums to zero over the vocabulary, its
     rows for tokens that are no row's target are minus the softmax-weighted sums and therefore small and finite,
     d_x rows have zero mean, rows without any gradient are zero)."""

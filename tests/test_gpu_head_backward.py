@@ -80,10 +80,11 @@ def test_bf16_mode(gpu, T, d, V):
 
 
 def test_more_rows_than_one_chunk(gpu):
-    """4096 rows of logits exist at a time: the LM-head gradient accumulates over chunks, the last one ragged."""
+    """16,384 rows of logits exist at a time: the LM-head gradient accumulates over chunks, the last one ragged."""
     cfg = ModelConfig(n_layers=0, d_model=64, n_heads=1, head_dim=64, rotary_dims=0, d_ff=64, vocab=520,
                       dtype="bf16", pad_id=0, eos_id=1)
-    _check(gpu, cfg, make_weights(cfg, 13, variant="test"), 4096 + 333, seed=5, scale=4429.0 * 64.0)
+    T = 16384 + 333
+    _check(gpu, cfg, make_weights(cfg, 13, variant="test"), T, seed=5, scale=T * 64.0)
 
 
 def test_without_value_head_and_without_targets(gpu):

@@ -215,6 +215,23 @@ int rlhf_head_backward(rlhf_handle *h, const float *x_final, const int32_t *targ
                        float *d_lnf_g, float *d_lnf_b, float *d_embed_out, float *d_value_w, float *d_value_b,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* Backward pass through the MLP branch of decoder layer `layer` (paper: as for rlhf_head_backward; the
+ * layer is the parallel-residual GPT-NeoX layer of Tech stack, x_out = x + attention(LN1(x)) + mlp(LN2(x)),
+ * so this branch is a function of the layer input alone).  With m = LN2(x), u = m W1^T + b1, f = gelu(u)
+ * (exact erf form), y = f W2^T + b2 and an upstream gradient d_out = dL/dx_out (any scale: the call is
+ * linear in it), the outputs are the gradients of L through this branch:
+ *   d_x [T, d]        the branch's term of dL/dx (the residual's identity term d_out is NOT included)
+ *   d_ln2_g, d_ln2_b [d];  d_w_fc1 [d_ff, d], d_b_fc1 [d_ff];  d_w_fc2 [d, d_ff], d_b_fc2 [d]   (overwritten)
+ * The branch's forward is recomputed from x_in (nothing but the layer inputs has to be kept by a training
+ * forward pass).  x_in, d_out: dev float [T, d], packed rows in any order (the branch acts on rows
+ * independently); all outputs dev float.  In bf16 mode d_out, f and dL/du are rounded to fp16 as operands of
+ * the gradient products: scale d_out into fp16's range (see grad_scale of rlhf_head_backward).  Sums over
+ * rows run in a fixed order.  Workspace size from rlhf_mlp_backward_workspace_bytes; RLHF_ENOMEM if smaller. */
+int rlhf_mlp_backward_workspace_bytes(const rlhf_handle *h, int32_t T, size_t *out);
+int rlhf_mlp_backward(rlhf_handle *h, int32_t layer, const float *x_in, const float *d_out, int32_t T, float *d_x,
+                      float *d_ln2_g, float *d_ln2_b, float *d_w_fc1, float *d_b_fc1, float *d_w_fc2, float *d_b_fc2,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
 /* Debug / parity aid: raw (pre-temperature) fp32 logits of the same forward pass as
  * score_sequences at n (row, column) pairs.  rows_bt: HOST int32 [n, 2]; out_logits: dev float
  * [n, vocab].  Every pair must name a real position. */

@@ -15,7 +15,7 @@ EXPORTS = (
     "rlhf_create", "rlhf_destroy", "rlhf_workspace_bytes", "rollout_generate", "score_sequences",
     "rlhf_debug_logits_rows", "rlhf_profile_enable", "rlhf_profile_read", "rlhf_last_rollout_phases",
     "rlhf_last_error", "rlhf_ppo_assemble_rewards", "rlhf_ppo_gae", "rlhf_ppo_whiten", "rlhf_ppo_loss", "rlhf_adamw_step",
-    "rlhf_head_backward", "rlhf_head_backward_workspace_bytes",
+    "rlhf_head_backward", "rlhf_head_backward_workspace_bytes", "rlhf_mlp_backward", "rlhf_mlp_backward_workspace_bytes",
 )
 
 _PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -69,6 +69,8 @@ def load_library():
     lib.rlhf_ppo_loss.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, f32, f32, vp, vp, vp, vp]
     lib.rlhf_head_backward_workspace_bytes.argtypes = [vp, i32, C.POINTER(C.c_size_t)]
     lib.rlhf_head_backward.argtypes = [vp, vp, vp, vp, vp, i32, C.c_float, C.c_float] + [vp] * 6 + [vp, C.c_size_t, vp]
+    lib.rlhf_mlp_backward_workspace_bytes.argtypes = [vp, i32, C.POINTER(C.c_size_t)]
+    lib.rlhf_mlp_backward.argtypes = [vp, i32, vp, vp, i32] + [vp] * 7 + [vp, C.c_size_t, vp]
     lib.rlhf_adamw_step.argtypes = [vp, vp, vp, vp, vp, u64, i32] + [C.c_double] * 6 + [vp]
     lib.rlhf_last_error.restype = C.c_char_p
     for n in EXPORTS:
@@ -220,6 +222,29 @@ class Policy:
                 grad_scale, res["d_x"].data_ptr(), res["d_lnf_g"].data_ptr(), res["d_lnf_b"].data_ptr(),
                 res["d_embed_out"].data_ptr(), res["d_value_w"].data_ptr() if has_v else None,
                 res["d_value_b"].data_ptr() if has_v else None, ws.data_ptr(), ws.numel(), self._stream()))
+        return res
+
+    def mlp_backward(self, layer, x_in, d_out):
+        """x_in, d_out float32 [T, d].  Returns a dict of CUDA float32 tensors: d_x [T, d] (the MLP branch's term
+        only), d_ln2_g, d_ln2_b [d], d_w_fc1 [d_ff, d], d_b_fc1 [d_ff], d_w_fc2 [d, d_ff], d_b_fc2 [d]."""
+        torch = self.torch
+        x = self._to_dev(x_in, torch.float32)
+        g = self._to_dev(d_out, torch.float32)
+        T, d = x.shape
+        F = self.cfg.d_ff
+        if d != self.cfg.d_model or tuple(g.shape) != (T, d):
+            raise RlhfError("mlp_backward: x_in and d_out must both be [T, d_model]")
+        out = C.c_size_t()
+        _check(self.lib.rlhf_mlp_backward_workspace_bytes(self._h, T, C.byref(out)))
+        ws = self._workspace(out.value)
+        new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=self.device)
+        res = dict(d_x=new(T, d), d_ln2_g=new(d), d_ln2_b=new(d), d_w_fc1=new(F, d), d_b_fc1=new(F),
+                   d_w_fc2=new(d, F), d_b_fc2=new(d))
+        with torch.cuda.device(self.device):
+            _check(self.lib.rlhf_mlp_backward(self._h, int(layer), x.data_ptr(), g.data_ptr(), T,
+                                              *[res[k].data_ptr() for k in ("d_x", "d_ln2_g", "d_ln2_b", "d_w_fc1",
+                                                                            "d_b_fc1", "d_w_fc2", "d_b_fc2")],
+                                              ws.data_ptr(), ws.numel(), self._stream()))
         return res
 
     def debug_logits_rows(self, tokens, mask, rows_bt):

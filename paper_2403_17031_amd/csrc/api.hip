@@ -745,6 +745,97 @@ int rlhf_head_backward(rlhf_handle* h, const float* x_final, const int32_t* targ
   return RLHF_OK;
 }
 
+namespace {
+struct MlpBwdWs {
+  void *m, *u, *f, *go, *df, *goT, *fT, *mT, *w1T, *w2T;
+  float *dm, *stats, *part;
+  int T_pad, splits;
+};
+MlpBwdWs carve_mlp_bwd(Carver& c, const rlhf_model_config& cfg, int T, size_t esz) {
+  MlpBwdWs w;
+  const size_t d = cfg.d_model, F = cfg.d_ff;
+  w.T_pad = (T + 127) & ~127;  // the row count is the K of the weight-gradient products
+  w.splits = std::max(1, std::min(64, (T + 255) / 256));
+  const size_t Tp = (size_t)w.T_pad;
+  w.m = c.take_bytes((size_t)T * d * esz);
+  w.u = c.take_bytes((size_t)T * F * esz);
+  w.f = c.take_bytes((size_t)T * F * esz);
+  w.go = c.take_bytes((size_t)T * d * esz);
+  w.df = c.take_bytes((size_t)T * F * esz);
+  w.goT = c.take_bytes(d * Tp * esz);
+  w.fT = c.take_bytes(F * Tp * esz);
+  w.mT = c.take_bytes(d * Tp * esz);
+  w.w1T = c.take_bytes(d * F * esz);
+  w.w2T = c.take_bytes(F * d * esz);
+  w.dm = c.take<float>((size_t)T * d);
+  w.stats = c.take<float>((size_t)2 * T);
+  w.part = c.take<float>((size_t)w.splits * std::max(3 * d, F));
+  return w;
+}
+}  // namespace
+
+int rlhf_mlp_backward_workspace_bytes(const rlhf_handle* h, int32_t T, size_t* out) {
+  if (!h || !out) return fail(RLHF_EINVAL, "null argument");
+  if (T <= 0) return fail(RLHF_EINVAL, "row count must be positive");
+  Carver c(nullptr);
+  carve_mlp_bwd(c, h->cfg, T, h->esz);
+  *out = c.off + 256;
+  return RLHF_OK;
+}
+
+int rlhf_mlp_backward(rlhf_handle* h, int32_t layer, const float* x_in, const float* d_out, int32_t T, float* d_x,
+                      float* d_ln2_g, float* d_ln2_b, float* d_w_fc1, float* d_b_fc1, float* d_w_fc2, float* d_b_fc2,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  if (!h) return fail(RLHF_EINVAL, "null handle");
+  const rlhf_model_config& c = h->cfg;
+  if (layer < 0 || layer >= c.n_layers) return fail(RLHF_EINVAL, "layer index out of range");
+  if (T <= 0) return fail(RLHF_EINVAL, "row count must be positive");
+  if ((size_t)T * (size_t)std::max(c.d_model, c.d_ff) >= ((size_t)1 << 32) - ((size_t)128 * std::max(c.d_model, c.d_ff)))
+    return fail(RLHF_EUNSUPPORTED, "too many rows");
+  if (!x_in || !d_out || !d_x || !d_ln2_g || !d_ln2_b || !d_w_fc1 || !d_b_fc1 || !d_w_fc2 || !d_b_fc2 || !workspace)
+    return fail(RLHF_EINVAL, "null pointer argument");
+  Carver cv((void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255));
+  MlpBwdWs ws = carve_mlp_bwd(cv, c, T, h->esz);
+  if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
+    return fail(RLHF_ENOMEM, "workspace too small for rlhf_mlp_backward");
+  hipStream_t s = (hipStream_t)stream;
+  const int dt = c.dtype, d = c.d_model, F = c.d_ff, l = layer, Tp = ws.T_pad;
+  const size_t ld_w2 = h->ld_o2 ? (size_t)h->ld_o2 : (size_t)F;  // row stride of this layer's W_fc2
+
+  auto gemm = [&](const void* A, const void* W, const void* bias, void* out, int M, int N, int K, int epi) {
+    GemmArgs g;
+    g.A = A; g.W = W; g.bias = bias; g.out = out; g.M_max = M; g.M_dev = nullptr;
+    g.N = N; g.K = K; g.ldo = N; g.epilogue = epi;
+    return g;
+  };
+  // ---- the branch's forward, recomputed from the layer input: m = LN2(x), u = m W1^T + b1, f = gelu(u)
+  LAUNCH("final_ln", launch_final_ln(dt, x_in, nullptr, 0, T, nullptr, d, c.ln_eps, h->ln2_g[l], h->ln2_b[l], ws.m,
+                                     nullptr, 0.f, nullptr, s));
+  LAUNCH("gemm_mlp_fwd", launch_gemm(dt, gemm(ws.m, h->w_fc1[l], h->b_fc1[l], ws.u, T, F, d, EPI_BIAS), s));
+  LAUNCH("gelu", launch_gelu(dt, ws.u, ws.f, (size_t)T * F, s));
+  // ---- FC2: db2 = sum_t G, dW2 = G^T f, df = G W2
+  LAUNCH("colsum", launch_colsum(0, d_out, T, d, ws.part, ws.splits, d_b_fc2, s));
+  LAUNCH("convert", launch_convert_from_f32(dt, d_out, ws.go, (size_t)T * d, s));
+  LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.go, (size_t)d, ws.goT, (size_t)Tp, T, d, Tp, s));
+  LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.f, (size_t)F, ws.fT, (size_t)Tp, T, F, Tp, s));
+  LAUNCH("gemm_mlp_dw", launch_gemm(dt, gemm(ws.goT, ws.fT, nullptr, d_w_fc2, d, F, Tp, EPI_F32), s));
+  LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, h->w_fc2[l], ld_w2, ws.w2T, (size_t)d, d, F, d, s));
+  LAUNCH("gemm_mlp_dx", launch_gemm(dt, gemm(ws.go, ws.w2T, nullptr, ws.df, T, F, d, EPI_BIAS), s));
+  // ---- GELU, then FC1: du = df * gelu'(u) (in place), db1 = sum_t du, dW1 = du^T m, dm = du W1
+  LAUNCH("gelu", launch_gelu_backward(dt, ws.u, ws.df, (size_t)T * F, s));
+  LAUNCH("colsum", launch_colsum(dt, ws.df, T, F, ws.part, ws.splits, d_b_fc1, s));
+  LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.df, (size_t)F, ws.fT, (size_t)Tp, T, F, Tp, s));
+  LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.m, (size_t)d, ws.mT, (size_t)Tp, T, d, Tp, s));
+  LAUNCH("gemm_mlp_dw", launch_gemm(dt, gemm(ws.fT, ws.mT, nullptr, d_w_fc1, F, d, Tp, EPI_F32), s));
+  LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, h->w_fc1[l], (size_t)d, ws.w1T, (size_t)F, F, d, F, s));
+  LAUNCH("gemm_mlp_dx", launch_gemm(dt, gemm(ws.df, ws.w1T, nullptr, ws.dm, T, d, F, EPI_F32), s));
+  // ---- LN2: the branch's term of dL/dx, and the gradients of its gain and bias
+  LAUNCH("head_ln_backward", launch_head_ln_backward(dt, x_in, ws.dm, nullptr, 1.0f, nullptr, h->ln2_g[l], h->ln2_b[l], T,
+                                                     d, c.ln_eps, d_x, ws.stats, ws.part, ws.splits, d_ln2_g, d_ln2_b,
+                                                     nullptr, nullptr, s));
+  return RLHF_OK;
+}
+
 int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_mask, int32_t B, int32_t Lq,
                      uint64_t seed, uint64_t seq_id_base, float temperature, int32_t max_new_tokens,
                      int32_t* out_tokens, float* out_logprobs, int32_t* out_lengths, uint8_t* out_mask,

@@ -281,6 +281,13 @@ hipError_t launch_head_ln_backward(int dtype, const float* x, const float* dhl, 
                                    float* dx, float* stats, float* part, int splits, float* d_g, float* d_b,
                                    float* d_wv, float* d_bv, hipStream_t s);
 
+// Element-wise pieces of a layer's backward pass (dtype 0: float activations, 1: fp16).
+hipError_t launch_gelu(int dtype, const void* u, void* f, size_t n, hipStream_t s);            // f = gelu(u)
+hipError_t launch_gelu_backward(int dtype, const void* u, void* df, size_t n, hipStream_t s);  // df *= gelu'(u)
+hipError_t launch_convert_from_f32(int dtype, const float* src, void* dst, size_t n, hipStream_t s);
+// out[c] = sum_r a[r][c] over a contiguous [R, C] matrix (elem 0: float, 1: fp16); part: [splits][C] scratch.
+hipError_t launch_colsum(int elem, const void* a, int R, int C, float* part, int splits, float* out, hipStream_t s);
+
 hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s);
 // Same for a [rows, cols] matrix written with row stride dst_ld (elements).
 // fp16 copy of W_qkv and a bf16 copy of its bias with the rotary dims of every q and k head

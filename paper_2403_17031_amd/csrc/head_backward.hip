@@ -281,7 +281,90 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+// f = gelu(u) (exact erf form), element-wise.
+template <typename T>
+__global__ void __launch_bounds__(256) gelu_kernel(const T* __restrict__ u, T* __restrict__ f, size_t n) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) {
+    const float x = to_f32(u[i]);
+    f[i] = from_f32<T>(0.5f * x * (1.0f + erff(x * 0.70710678118654752f)));
+  }
+}
+// du = df * gelu'(u), gelu'(u) = Phi(u) + u * phi(u); in place on df.
+template <typename T>
+__global__ void __launch_bounds__(256) gelu_backward_kernel(const T* __restrict__ u, T* __restrict__ df, size_t n) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) {
+    const float x = to_f32(u[i]);
+    const float Phi = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
+    const float phi = 0.3989422804014327f * __expf(-0.5f * x * x);
+    df[i] = from_f32<T>(to_f32(df[i]) * (Phi + x * phi));
+  }
+}
+template <typename T>
+__global__ void __launch_bounds__(256) convert_kernel(const float* __restrict__ src, T* __restrict__ dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) dst[i] = from_f32<T>(src[i]);
+}
+// Column sums of a [R, C] matrix in two stages with a fixed order: block (column block, row split)
+// sums its rows for 256 columns into part [splits][C]; the second kernel adds the splits.
+template <typename T>
+__global__ void __launch_bounds__(256)
+    colsum_part_kernel(const T* __restrict__ a, int R, int C, int rows_per_split, float* __restrict__ part) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  const int r0 = blockIdx.y * rows_per_split, r1 = min(R, r0 + rows_per_split);
+  float s = 0.f;
+  for (int r = r0; r < r1; ++r) s += to_f32(a[(size_t)r * C + c]);
+  part[(size_t)blockIdx.y * C + c] = s;
+}
+__global__ void __launch_bounds__(256)
+    colsum_final_kernel(const float* __restrict__ part, int splits, int C, float* __restrict__ out) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  float s = 0.f;
+  for (int z = 0; z < splits; ++z) s += part[(size_t)z * C + c];
+  out[c] = s;
+}
+
 }  // namespace
+
+hipError_t launch_gelu(int dtype, const void* u, void* f, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const int blocks = (int)std::min<size_t>((n + 255) / 256, 65536);
+  if (dtype == 0) hipLaunchKernelGGL(gelu_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)u, (float*)f, n);
+  else hipLaunchKernelGGL(gelu_kernel<half_t>, dim3(blocks), dim3(256), 0, s, (const half_t*)u, (half_t*)f, n);
+  return hipGetLastError();
+}
+hipError_t launch_gelu_backward(int dtype, const void* u, void* df, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const int blocks = (int)std::min<size_t>((n + 255) / 256, 65536);
+  if (dtype == 0)
+    hipLaunchKernelGGL(gelu_backward_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)u, (float*)df, n);
+  else
+    hipLaunchKernelGGL(gelu_backward_kernel<half_t>, dim3(blocks), dim3(256), 0, s, (const half_t*)u, (half_t*)df, n);
+  return hipGetLastError();
+}
+hipError_t launch_convert_from_f32(int dtype, const float* src, void* dst, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const int blocks = (int)std::min<size_t>((n + 255) / 256, 65536);
+  if (dtype == 0) hipLaunchKernelGGL(convert_kernel<float>, dim3(blocks), dim3(256), 0, s, src, (float*)dst, n);
+  else hipLaunchKernelGGL(convert_kernel<half_t>, dim3(blocks), dim3(256), 0, s, src, (half_t*)dst, n);
+  return hipGetLastError();
+}
+// elem: 0 = float matrix, 1 = fp16 matrix.  part: [splits][C] floats of scratch.
+hipError_t launch_colsum(int elem, const void* a, int R, int C, float* part, int splits, float* out, hipStream_t s) {
+  if (C <= 0) return hipSuccess;
+  const int rps = (std::max(R, 1) + splits - 1) / splits;
+  dim3 grid((C + 255) / 256, splits);
+  if (elem == 0) hipLaunchKernelGGL(colsum_part_kernel<float>, grid, dim3(256), 0, s, (const float*)a, R, C, rps, part);
+  else hipLaunchKernelGGL(colsum_part_kernel<half_t>, grid, dim3(256), 0, s, (const half_t*)a, R, C, rps, part);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((C + 255) / 256), dim3(256), 0, s, part, splits, C, out);
+  return hipGetLastError();
+}
 
 hipError_t launch_transpose_pad(int dtype, const void* src, size_t ld_src, void* dst, size_t ld_dst, int R, int C,
                                 int R_pad, hipStream_t s) {

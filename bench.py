@@ -229,6 +229,27 @@ def main():
                                   "rows": T_hb}
     del x_hb, y_hb, gl_hb, gv_hb, hb
 
+    # The backward pass through one decoder layer's MLP branch over the batch's packed rows (the rows the
+    # scoring pass runs over): forward recomputation (1 product) + four gradient products of 2*T*d*d_ff flop.
+    # Outside the headline metric.
+    mlp_bwd_ms = None
+    if cfg.n_layers > 0:
+        T_mb = int(wc["real_score_tokens"])
+        x_mb = torch.randn(T_mb, cfg.d_model, device="cuda", generator=g_hb) * 2.0
+        g_mb = torch.randn(T_mb, cfg.d_model, device="cuda", generator=g_hb)
+        for i in range(1 + 2):
+            if i == 1:
+                e0.record()
+            mb = pol.mlp_backward(0, x_mb, g_mb)
+        e1.record()
+        torch.cuda.synchronize()
+        mlp_bwd_ms = e0.elapsed_time(e1) / 2
+        ach = 5 * 2.0 * T_mb * cfg.d_model * cfg.d_ff / (mlp_bwd_ms * 1e-3)
+        rooflines["mlp_backward"] = {"bound": "mfma", "achieved": ach / 1e12, "peak": hb_peak / 1e12,
+                                     "unit": "TFLOP/s", "frac": ach / hb_peak, "traffic": None,
+                                     "avg_launch_ms": mlp_bwd_ms, "rows": T_mb}
+        del x_mb, g_mb, mb
+
     # The paper's other scoring shapes (reward-model batches of 638 tokens, long-context batches of 2021),
     # right-padded with true lengths uniform in [L/4, L]; outside the headline metric.
     extra = None
@@ -278,7 +299,7 @@ def main():
         "rescoring_tok_s_padded": B * (wl.query_len + N) / (score_ms * 1e-3),
         "score_mfma_frac": wc["score_flops"] / (score_ms * 1e-3) / MFMA_PEAK,
         "roofline": roof, "rooflines": rooflines, "kernels_ms": kern, "profiled_step_ms": tot,
-        "ppo_signals_ms": signals_ms, "adamw_ms_per_2p30_params": adamw_ms, "head_backward_ms": head_bwd_ms, "extra_score_shapes": extra,
+        "ppo_signals_ms": signals_ms, "adamw_ms_per_2p30_params": adamw_ms, "head_backward_ms": head_bwd_ms, "mlp_backward_ms_per_layer": mlp_bwd_ms, "extra_score_shapes": extra,
         "cpu_baseline": cpu, "setup_s": setup_s,
     }
     print(json.dumps(out))

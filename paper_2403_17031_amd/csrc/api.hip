@@ -663,7 +663,7 @@ HeadBwdWs carve_head_bwd(Carver& c, const rlhf_model_config& cfg, int T, size_t 
   w.chunk = std::min(T, kHeadChunk);
   w.chunk_pad = (w.chunk + 127) & ~127;  // the row count of a chunk is the K of the weight-gradient product
   w.V_pad = (int)((V + 7) & ~(size_t)7);  // the vocabulary is the K of the input-gradient product
-  w.splits = std::max(1, std::min(64, (T + 255) / 256));
+  w.splits = std::max(1, std::min(256, (T + 255) / 256));
   w.hl = c.take_bytes((size_t)w.chunk_pad * d * esz);
   w.logits = c.take<float>((size_t)w.chunk * V);
   w.dz = c.take_bytes((size_t)w.chunk_pad * w.V_pad * esz);
@@ -755,7 +755,7 @@ MlpBwdWs carve_mlp_bwd(Carver& c, const rlhf_model_config& cfg, int T, size_t es
   MlpBwdWs w;
   const size_t d = cfg.d_model, F = cfg.d_ff;
   w.T_pad = (T + 127) & ~127;  // the row count is the K of the weight-gradient products
-  w.splits = std::max(1, std::min(64, (T + 255) / 256));
+  w.splits = std::max(1, std::min(256, (T + 255) / 256));
   const size_t Tp = (size_t)w.T_pad;
   w.m = c.take_bytes((size_t)T * d * esz);
   w.u = c.take_bytes((size_t)T * F * esz);

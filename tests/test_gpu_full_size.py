@@ -150,3 +150,29 @@ def test_head_backward_at_the_2p8b_width(gpu):
         assert np.abs(dx[t] - ref).max() <= 2e-2 * np.abs(ref).max(), t
         assert np.linalg.norm(dx[t] - ref) <= 5e-3 * np.linalg.norm(ref), t
     pol.close()
+
+
+@pytest.mark.timeout(900)
+def test_mlp_backward_at_the_2p8b_width(gpu):
+    """One layer of the benchmark model (d_model 2560, d_ff 10,240) over 4,229 packed rows (a ragged count: the
+    weight-gradient products pad it to 4,352) against the oracle on the whole result."""
+    from oracle.mlp_backward_oracle import mlp_backward
+    wl = WORKLOADS[4]
+    cfg = wl.model.with_(n_layers=1, vocab=64, eos_id=1, pad_id=0)
+    w = make_weights(cfg, wl.weight_seed)
+    T = 4229
+    g = np.random.default_rng(98)
+    x = g.normal(0.0, 2.0, (T, cfg.d_model)).astype(np.float32)
+    G = (g.normal(0.0, 1.0, (T, cfg.d_model)) * 4.0).astype(np.float32)
+    pol = gpu.Policy(cfg, w)
+    got = pol.mlp_backward(0, x, G)
+    L = lambda n: w[f"layers.0.{n}"]
+    ref = mlp_backward(x, L("ln2_g"), L("ln2_b"), L("w_fc1"), L("b_fc1"), L("w_fc2"), L("b_fc2"), G, cfg.ln_eps)
+    pairs = dict(d_x="d_x", d_ln2_g="d_ln_g", d_ln2_b="d_ln_b", d_w_fc1="d_w_fc1", d_b_fc1="d_b_fc1",
+                 d_w_fc2="d_w_fc2", d_b_fc2="d_b_fc2")
+    for k, rk in pairs.items():
+        a, b = got[k].cpu().numpy().astype(np.float64), ref[rk]
+        assert np.isfinite(a).all(), k
+        assert np.abs(a - b).max() <= 2e-2 * np.abs(b).max(), k
+        assert np.linalg.norm(a - b) <= 5e-3 * np.linalg.norm(b), (k, np.linalg.norm(a - b) / np.linalg.norm(b))
+    pol.close()

@@ -11,6 +11,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 __device__ __forceinline__ float block_sum(float v, float* sh) {  // 256 threads; sh: 4 floats
   v = wave_sum(v);
@@ -74,6 +75,38 @@ __global__ void __launch_bounds__(256)
       const f16x4_t v = {tile[4 * tq][tr + 16 * i], tile[4 * tq + 1][tr + 16 * i], tile[4 * tq + 2][tr + 16 * i],
                          tile[4 * tq + 3][tr + 16 * i]};
       *(f16x4_t*)(dst + (size_t)c * ld_dst + r) = v;
+    }
+  }
+}
+
+// fp16 form with 16-byte accesses on both sides: 64 x 64 tiles, a thread moves 8 consecutive halfs.
+// Needs ld_src, ld_dst, R_pad and C multiples of 8 and 16-byte aligned bases.  The LDS row stride of
+// 66 halfs (33 words) spreads the 8 rows a thread gathers over different banks.
+__global__ void __launch_bounds__(256)
+    transpose_pad_f16x8_kernel(const half_t* __restrict__ src, size_t ld_src, half_t* __restrict__ dst, size_t ld_dst,
+                               int R, int C, int R_pad) {
+  __shared__ uint32_t tile[64 * 33];
+  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const int to = threadIdx.x & 7, tr = threadIdx.x >> 3;  // octet within a tile row, row within a pass
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = r0 + tr + 32 * i, c = c0 + 8 * to;
+    u32x4_t v = {0, 0, 0, 0};
+    if (r < R && c < C) v = *(const u32x4_t*)(src + (size_t)r * ld_src + c);
+    uint32_t* t = tile + (tr + 32 * i) * 33 + 4 * to;
+    t[0] = v[0]; t[1] = v[1]; t[2] = v[2]; t[3] = v[3];
+  }
+  __syncthreads();
+  const uint16_t* th = (const uint16_t*)tile;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int cl = tr + 32 * i, c = c0 + cl, r = r0 + 8 * to;
+    if (c < C && r < R_pad) {
+      u32x4_t v;
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        v[k] = (uint32_t)th[(8 * to + 2 * k) * 66 + cl] | ((uint32_t)th[(8 * to + 2 * k + 1) * 66 + cl] << 16);
+      *(u32x4_t*)(dst + (size_t)c * ld_dst + r) = v;
     }
   }
 }
@@ -419,6 +452,10 @@ hipError_t launch_transpose_pad(int dtype, const void* src, size_t ld_src, void*
   if (dtype == 0)
     hipLaunchKernelGGL(transpose_pad_kernel<float>, grid, dim3(256), 0, s, (const float*)src, ld_src, (float*)dst,
                        ld_dst, R, C, R_pad);
+  else if ((ld_src & 7) == 0 && (ld_dst & 7) == 0 && (R_pad & 7) == 0 && (C & 7) == 0 &&
+           (((uintptr_t)src | (uintptr_t)dst) & 15) == 0)
+    hipLaunchKernelGGL(transpose_pad_f16x8_kernel, dim3((R_pad + 63) / 64, (C + 63) / 64), dim3(256), 0, s,
+                       (const half_t*)src, ld_src, (half_t*)dst, ld_dst, R, C, R_pad);
   else if ((ld_src & 3) == 0 && (ld_dst & 3) == 0 && (R_pad & 3) == 0 && (C & 3) == 0 && (R & 3) == 0 &&
            (((uintptr_t)src | (uintptr_t)dst) & 7) == 0)
     hipLaunchKernelGGL(transpose_pad_f16x4_kernel, dim3((R_pad + 63) / 64, (C + 63) / 64), dim3(256), 0, s,

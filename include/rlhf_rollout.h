@@ -232,6 +232,25 @@ int rlhf_mlp_backward(rlhf_handle *h, int32_t layer, const float *x_in, const fl
                       float *d_ln2_g, float *d_ln2_b, float *d_w_fc1, float *d_b_fc1, float *d_w_fc2, float *d_b_fc2,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* Backward pass through packed causal softmax attention, the core of a layer's attention branch
+ * (paper: as for rlhf_head_backward; Tech stack for the GPT-NeoX attention).  Stateless: no handle.
+ * For every sequence b (packed rows cu_seqlens[b] .. cu_seqlens[b+1]-1) and head h, with Q, K, V the
+ * rows' slices [h*head_dim, (h+1)*head_dim) after the rotary turn,
+ *   S = Q K^T / sqrt(head_dim),  P = softmax over keys j <= i,  O = P V,
+ * and d_out = dL/dO:  dV = P^T dO;  dP = dO V^T;  dS = P * (dP - rowsum(P * dP));
+ *   dQ = dS K / sqrt(head_dim);  dK = dS^T Q / sqrt(head_dim).
+ * q, k, v, d_out and the outputs dq, dk, dv: dev [T, n_heads*head_dim] row-major, float (dtype
+ * RLHF_DTYPE_FP32) or fp16 (RLHF_DTYPE_BF16: the activation type of that mode), 16-byte aligned;
+ * cu_seqlens: dev int32 [B+1], increasing from 0 to T; lse_scratch, delta_scratch: dev float [T*n_heads]
+ * (left holding the rows' log-sum-exp and sum_j P_ij dP_ij).  max_len (host): at least the longest
+ * sequence; longer sequences are cut off at max_len rows (wrong results there, nothing out of bounds).
+ * head_dim <= 256 and a multiple of 4 (fp32) or 8 (fp16); arithmetic in fp32; sums in a fixed order.
+ * Two launches on `stream`. */
+int rlhf_attention_backward(const void *q, const void *k, const void *v, const void *d_out,
+                            const int32_t *cu_seqlens, int32_t B, int32_t T, int32_t n_heads, int32_t head_dim,
+                            int32_t dtype, int32_t max_len, float *lse_scratch, float *delta_scratch, void *dq,
+                            void *dk, void *dv, void *stream);
+
 /* Debug / parity aid: raw (pre-temperature) fp32 logits of the same forward pass as
  * score_sequences at n (row, column) pairs.  rows_bt: HOST int32 [n, 2]; out_logits: dev float
  * [n, vocab].  Every pair must name a real position. */

@@ -15,5 +15,6 @@ from .binding import (  # noqa: F401
     ppo_loss,
     PPO_LOSS_STATS,
     adamw_step,
+    attention_backward,
     linear_lr,
 )

@@ -15,7 +15,7 @@ EXPORTS = (
     "rlhf_create", "rlhf_destroy", "rlhf_workspace_bytes", "rollout_generate", "score_sequences",
     "rlhf_debug_logits_rows", "rlhf_profile_enable", "rlhf_profile_read", "rlhf_last_rollout_phases",
     "rlhf_last_error", "rlhf_ppo_assemble_rewards", "rlhf_ppo_gae", "rlhf_ppo_whiten", "rlhf_ppo_loss", "rlhf_adamw_step",
-    "rlhf_head_backward", "rlhf_head_backward_workspace_bytes", "rlhf_mlp_backward", "rlhf_mlp_backward_workspace_bytes",
+    "rlhf_head_backward", "rlhf_head_backward_workspace_bytes", "rlhf_mlp_backward", "rlhf_mlp_backward_workspace_bytes", "rlhf_attention_backward",
 )
 
 _PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -71,6 +71,7 @@ def load_library():
     lib.rlhf_head_backward.argtypes = [vp, vp, vp, vp, vp, i32, C.c_float, C.c_float] + [vp] * 6 + [vp, C.c_size_t, vp]
     lib.rlhf_mlp_backward_workspace_bytes.argtypes = [vp, i32, C.POINTER(C.c_size_t)]
     lib.rlhf_mlp_backward.argtypes = [vp, i32, vp, vp, i32] + [vp] * 7 + [vp, C.c_size_t, vp]
+    lib.rlhf_attention_backward.argtypes = [vp] * 5 + [i32] * 6 + [vp] * 5 + [vp]
     lib.rlhf_adamw_step.argtypes = [vp, vp, vp, vp, vp, u64, i32] + [C.c_double] * 6 + [vp]
     lib.rlhf_last_error.restype = C.c_char_p
     for n in EXPORTS:
@@ -402,6 +403,35 @@ def linear_lr(base_lr, update_index, total_updates):
         raise ValueError("total_updates must be positive")
     k = min(max(int(update_index), 0), int(total_updates))
     return base_lr * (1.0 - k / total_updates)
+
+
+def attention_backward(q, k, v, d_out, cu_seqlens, n_heads, max_len=None):
+    """q, k, v, d_out: CUDA tensors [T, n_heads*head_dim], all float32 or all float16, contiguous; cu_seqlens int32
+    [B+1] (CUDA or host).  Returns (dq, dk, dv) in the inputs' dtype."""
+    import torch
+    lib = load_library()
+    ts = (q, k, v, d_out)
+    if any((not isinstance(t, torch.Tensor)) or not t.is_cuda or not t.is_contiguous() or t.dim() != 2 for t in ts):
+        raise RlhfError("attention_backward: q, k, v, d_out must be contiguous 2-D CUDA tensors")
+    if any(t.dtype != q.dtype or t.shape != q.shape for t in ts) or q.dtype not in (torch.float32, torch.float16):
+        raise RlhfError("attention_backward: q, k, v, d_out must share shape and dtype (float32 or float16)")
+    T, d = q.shape
+    if d % n_heads:
+        raise RlhfError("attention_backward: the width must be a multiple of n_heads")
+    dev = q.device
+    cu = torch.as_tensor(cu_seqlens, dtype=torch.int32).to(dev).contiguous()
+    B = cu.numel() - 1
+    if max_len is None:
+        max_len = int((cu[1:] - cu[:-1]).max().item())
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    lse = torch.empty(T * n_heads, dtype=torch.float32, device=dev)
+    delta = torch.empty(T * n_heads, dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.rlhf_attention_backward(q.data_ptr(), k.data_ptr(), v.data_ptr(), d_out.data_ptr(), cu.data_ptr(),
+                                           B, T, n_heads, d // n_heads, 0 if q.dtype == torch.float32 else 1,
+                                           max(int(max_len), 1), lse.data_ptr(), delta.data_ptr(), dq.data_ptr(),
+                                           dk.data_ptr(), dv.data_ptr(), _cur_stream(torch, dev)))
+    return dq, dk, dv
 
 
 def adamw_step(param, grad, exp_avg, exp_avg_sq, step, lr=3e-6, beta1=0.9, beta2=0.999, eps=1e-5, weight_decay=0.01,

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librlhf_rollout.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "ppo_signals.hip", "optimizer.hip", "head_backward.hip"]
+SOURCES = ["api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "ppo_signals.hip", "optimizer.hip", "head_backward.hip", "attention_backward.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wno-unused-result",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -487,6 +487,25 @@ int rlhf_ppo_loss(const float* new_logprobs, const float* old_logprobs, const fl
   return RLHF_OK;
 }
 
+int rlhf_attention_backward(const void* q, const void* k, const void* v, const void* d_out, const int32_t* cu_seqlens,
+                            int32_t B, int32_t T, int32_t n_heads, int32_t head_dim, int32_t dtype, int32_t max_len,
+                            float* lse_scratch, float* delta_scratch, void* dq, void* dk, void* dv, void* stream) {
+  if (!q || !k || !v || !d_out || !cu_seqlens || !lse_scratch || !delta_scratch || !dq || !dk || !dv)
+    return fail(RLHF_EINVAL, "null pointer argument");
+  if (B <= 0 || T <= 0 || n_heads <= 0 || head_dim <= 0 || max_len <= 0)
+    return fail(RLHF_EINVAL, "batch, rows, heads, head_dim and max_len must be positive");
+  if (dtype != RLHF_DTYPE_FP32 && dtype != RLHF_DTYPE_BF16) return fail(RLHF_EUNSUPPORTED, "unknown dtype");
+  if (head_dim > 256 || (head_dim % (dtype == RLHF_DTYPE_FP32 ? 4 : 8)) != 0)
+    return fail(RLHF_EUNSUPPORTED, "head_dim must be <= 256 and a multiple of 4 (fp32) or 8 (fp16)");
+  if ((size_t)4 * (2 * (size_t)head_dim + 2 * (size_t)max_len) * sizeof(float) > 150 * 1024)
+    return fail(RLHF_EUNSUPPORTED, "max_len too large for the kernels' scratch");
+  if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)d_out | (uintptr_t)dq | (uintptr_t)dk | (uintptr_t)dv) & 15) != 0)
+    return fail(RLHF_EINVAL, "matrices must be 16-byte aligned");
+  HIP_OK(launch_attention_backward(dtype, q, k, v, d_out, cu_seqlens, B, T, n_heads, head_dim, max_len, lse_scratch,
+                                   delta_scratch, dq, dk, dv, (hipStream_t)stream));
+  return RLHF_OK;
+}
+
 int rlhf_adamw_step(float* param, const float* grad, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16,
                     uint64_t n, int32_t step, double lr, double beta1, double beta2, double eps, double weight_decay,
                     double grad_scale, void* stream) {

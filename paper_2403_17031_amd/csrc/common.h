@@ -288,6 +288,13 @@ hipError_t launch_convert_from_f32(int dtype, const float* src, void* dst, size_
 // out[c] = sum_r a[r][c] over a contiguous [R, C] matrix (elem 0: float, 1: fp16); part: [splits][C] scratch.
 hipError_t launch_colsum(int elem, const void* a, int R, int C, float* part, int splits, float* out, hipStream_t s);
 
+// Backward of packed causal attention (attention_backward.hip): q, k, v, g = dO and the outputs dq, dk, dv are
+// [T, H*hd] row-major in float (dtype 0) or fp16 (1); cu [B+1] packed-row offsets of the sequences;
+// lse, delta: [T*H] floats of scratch.  hd a multiple of 4 (float) or 8 (fp16); sequences of at most max_len rows.
+hipError_t launch_attention_backward(int dtype, const void* q, const void* k, const void* v, const void* g,
+                                     const int* cu, int B, int Tn, int H, int hd, int max_len, float* lse,
+                                     float* delta, void* dq, void* dk, void* dv, hipStream_t s);
+
 hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s);
 // Same for a [rows, cols] matrix written with row stride dst_ld (elements).
 // fp16 copy of W_qkv and a bf16 copy of its bias with the rotary dims of every q and k head

@@ -250,6 +250,29 @@ def main():
                                      "avg_launch_ms": mlp_bwd_ms, "rows": T_mb}
         del x_mb, g_mb, mb
 
+    # The backward pass through the packed causal attention of one layer over the same rows (sequence lengths
+    # of the scoring pass): five contractions of 2*hd flop per (query, key <= query, head) pair.
+    attn_bwd_ms = None
+    if cfg.n_layers > 0 and cfg.dtype != "fp32":
+        n_sc = (n_true + lens).astype(np.int64)
+        cu_ab = np.concatenate([[0], np.cumsum(n_sc)]).astype(np.int32)
+        T_ab = int(cu_ab[-1])
+        qkvg = [(torch.randn(T_ab, cfg.d_model, device="cuda", generator=g_hb)).half() for _ in range(4)]
+        cu_dev = torch.from_numpy(cu_ab).cuda()
+        for i in range(1 + 2):
+            if i == 1:
+                e0.record()
+            ab = P.attention_backward(*qkvg, cu_dev, cfg.n_heads, max_len=int(n_sc.max()))
+        e1.record()
+        torch.cuda.synchronize()
+        attn_bwd_ms = e0.elapsed_time(e1) / 2
+        ach = 5 * 2.0 * cfg.d_model * float((n_sc * (n_sc + 1) // 2).sum()) / (attn_bwd_ms * 1e-3)
+        rooflines["attention_backward"] = {"bound": "mfma", "achieved": ach / 1e12, "peak": MFMA_PEAK / 1e12,
+                                           "unit": "TFLOP/s", "frac": ach / MFMA_PEAK, "traffic": None,
+                                           "avg_launch_ms": attn_bwd_ms, "rows": T_ab,
+                                           "note": "first form: fp32 vector arithmetic, no matrix cores"}
+        del qkvg, ab
+
     # The paper's other scoring shapes (reward-model batches of 638 tokens, long-context batches of 2021),
     # right-padded with true lengths uniform in [L/4, L]; outside the headline metric.
     extra = None
@@ -299,7 +322,7 @@ def main():
         "rescoring_tok_s_padded": B * (wl.query_len + N) / (score_ms * 1e-3),
         "score_mfma_frac": wc["score_flops"] / (score_ms * 1e-3) / MFMA_PEAK,
         "roofline": roof, "rooflines": rooflines, "kernels_ms": kern, "profiled_step_ms": tot,
-        "ppo_signals_ms": signals_ms, "adamw_ms_per_2p30_params": adamw_ms, "head_backward_ms": head_bwd_ms, "mlp_backward_ms_per_layer": mlp_bwd_ms, "extra_score_shapes": extra,
+        "ppo_signals_ms": signals_ms, "adamw_ms_per_2p30_params": adamw_ms, "head_backward_ms": head_bwd_ms, "mlp_backward_ms_per_layer": mlp_bwd_ms, "attention_backward_ms_per_layer": attn_bwd_ms, "extra_score_shapes": extra,
         "cpu_baseline": cpu, "setup_s": setup_s,
     }
     print(json.dumps(out))

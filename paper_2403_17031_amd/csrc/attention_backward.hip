@@ -38,6 +38,11 @@ __device__ __forceinline__ float dot_row(const float* __restrict__ a, const half
   return s;
 }
 
+template <typename T>
+struct __attribute__((aligned(2 * sizeof(T)))) pair2 {  // two neighbouring elements, moved as one word
+  T a, b;
+};
+
 // sequence of packed row t: the largest b with cu[b] <= t (cu has B + 1 entries, cu[0] = 0)
 __device__ __forceinline__ int find_seq(const int* __restrict__ cu, int B, int t) {
   int lo = 0, hi = B;  // invariant: cu[lo] <= t, and t < cu[hi] or hi == B
@@ -92,16 +97,28 @@ __global__ void __launch_bounds__(256)
   dl = wave_sum(dl);
   for (int j = lane; j < nk; j += 64) ds[j] = p[j] * (ds[j] - dl);
   __syncthreads();
-  for (int e = lane; e < hd; e += 64) {
+  for (int e = 2 * lane; e < hd; e += 128) {  // two dims per lane: head sizes up to 128 take one sweep
     const T* kc = k + (size_t)s0 * d + col + e;
-    float a0 = 0.f, a1 = 0.f;
+    float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
     int j = 0;
     for (; j + 1 < nk; j += 2) {
-      a0 = fmaf(ds[j], to_f32(kc[(size_t)j * d]), a0);
-      a1 = fmaf(ds[j + 1], to_f32(kc[(size_t)(j + 1) * d]), a1);
+      const pair2<T> x = *(const pair2<T>*)(kc + (size_t)j * d), y = *(const pair2<T>*)(kc + (size_t)(j + 1) * d);
+      a0 = fmaf(ds[j], to_f32(x.a), a0);
+      a1 = fmaf(ds[j], to_f32(x.b), a1);
+      b0 = fmaf(ds[j + 1], to_f32(y.a), b0);
+      b1 = fmaf(ds[j + 1], to_f32(y.b), b1);
     }
-    if (j < nk) a0 = fmaf(ds[j], to_f32(kc[(size_t)j * d]), a0);
-    if (live) dq[t * d + col + e] = from_f32<T>((a0 + a1) * scale);
+    if (j < nk) {
+      const pair2<T> x = *(const pair2<T>*)(kc + (size_t)j * d);
+      a0 = fmaf(ds[j], to_f32(x.a), a0);
+      a1 = fmaf(ds[j], to_f32(x.b), a1);
+    }
+    if (live) {
+      pair2<T> o;
+      o.a = from_f32<T>((a0 + b0) * scale);
+      o.b = from_f32<T>((a1 + b1) * scale);
+      *(pair2<T>*)(dq + t * d + col + e) = o;
+    }
   }
   if (live && lane == 0) {
     lse[(size_t)t * H + h] = l;
@@ -143,17 +160,25 @@ __global__ void __launch_bounds__(256)
     ds[ii] = pr * (dp - delta[r * H + h]);
   }
   __syncthreads();
-  for (int e = lane; e < hd; e += 64) {
+  for (int e = 2 * lane; e < hd; e += 128) {
     const T* gc = g + (size_t)t * d + col + e;
     const T* qc = q + (size_t)t * d + col + e;
-    float av = 0.f, ak = 0.f;
+    float av0 = 0.f, av1 = 0.f, ak0 = 0.f, ak1 = 0.f;
     for (int ii = 0; ii < nq; ++ii) {
-      av = fmaf(p[ii], to_f32(gc[(size_t)ii * d]), av);
-      ak = fmaf(ds[ii], to_f32(qc[(size_t)ii * d]), ak);
+      const pair2<T> x = *(const pair2<T>*)(gc + (size_t)ii * d), y = *(const pair2<T>*)(qc + (size_t)ii * d);
+      av0 = fmaf(p[ii], to_f32(x.a), av0);
+      av1 = fmaf(p[ii], to_f32(x.b), av1);
+      ak0 = fmaf(ds[ii], to_f32(y.a), ak0);
+      ak1 = fmaf(ds[ii], to_f32(y.b), ak1);
     }
     if (live) {
-      dv[t * d + col + e] = from_f32<T>(av);
-      dk[t * d + col + e] = from_f32<T>(ak * scale);
+      pair2<T> o;
+      o.a = from_f32<T>(av0);
+      o.b = from_f32<T>(av1);
+      *(pair2<T>*)(dv + t * d + col + e) = o;
+      o.a = from_f32<T>(ak0 * scale);
+      o.b = from_f32<T>(ak1 * scale);
+      *(pair2<T>*)(dk + t * d + col + e) = o;
     }
   }
 }

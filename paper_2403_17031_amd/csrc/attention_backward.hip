@@ -57,7 +57,8 @@ template <typename T>
 __global__ void __launch_bounds__(256)
     attn_bwd_q_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
                       const T* __restrict__ g, const int* __restrict__ cu, int B, int Tn, int H, int hd, float scale,
-                      int max_len, float* __restrict__ lse, float* __restrict__ delta, T* __restrict__ dq) {
+                      int max_len, float* __restrict__ lse, float* __restrict__ delta, T* __restrict__ dq,
+                      size_t ldq, size_t ldg, size_t ldo, T* __restrict__ o, size_t ldoo) {
   extern __shared__ float sm[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = blockIdx.y;
   const int t_raw = blockIdx.x * 4 + wave;
@@ -65,19 +66,19 @@ __global__ void __launch_bounds__(256)
   const int t = live ? t_raw : 0;
   const int b = find_seq(cu, B, t), s0 = min(max(cu[b], 0), t);  // clamped: a malformed cu must not lead out of bounds
   const int nk = min(t - s0 + 1, max_len);  // keys 0 .. i of the sequence
-  const size_t d = (size_t)H * hd, col = (size_t)h * hd;
+  const size_t col = (size_t)h * hd;
   float* qs = sm + (size_t)wave * (2 * hd + 2 * max_len);
   float* gs = qs + hd;
   float* p = gs + hd;
   float* ds = p + max_len;
   for (int e = lane; e < hd; e += 64) {
-    qs[e] = to_f32(q[t * d + col + e]);
-    gs[e] = to_f32(g[t * d + col + e]);
+    qs[e] = to_f32(q[t * ldq + col + e]);
+    gs[e] = to_f32(g[t * ldg + col + e]);
   }
   __syncthreads();
   float mx = -INFINITY;
   for (int j = lane; j < nk; j += 64) {
-    const float s = dot_row(qs, k + (size_t)(s0 + j) * d + col, hd) * scale;
+    const float s = dot_row(qs, k + (size_t)(s0 + j) * ldq + col, hd) * scale;
     p[j] = s;
     mx = fmaxf(mx, s);
   }
@@ -89,7 +90,7 @@ __global__ void __launch_bounds__(256)
   float dl = 0.f;
   for (int j = lane; j < nk; j += 64) {
     const float pj = __expf(p[j] - l);
-    const float dp = dot_row(gs, v + (size_t)(s0 + j) * d + col, hd);
+    const float dp = dot_row(gs, v + (size_t)(s0 + j) * ldq + col, hd);
     p[j] = pj;
     ds[j] = dp;
     dl = fmaf(pj, dp, dl);
@@ -98,26 +99,43 @@ __global__ void __launch_bounds__(256)
   for (int j = lane; j < nk; j += 64) ds[j] = p[j] * (ds[j] - dl);
   __syncthreads();
   for (int e = 2 * lane; e < hd; e += 128) {  // two dims per lane: head sizes up to 128 take one sweep
-    const T* kc = k + (size_t)s0 * d + col + e;
+    const T* kc = k + (size_t)s0 * ldq + col + e;
     float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
     int j = 0;
     for (; j + 1 < nk; j += 2) {
-      const pair2<T> x = *(const pair2<T>*)(kc + (size_t)j * d), y = *(const pair2<T>*)(kc + (size_t)(j + 1) * d);
+      const pair2<T> x = *(const pair2<T>*)(kc + (size_t)j * ldq), y = *(const pair2<T>*)(kc + (size_t)(j + 1) * ldq);
       a0 = fmaf(ds[j], to_f32(x.a), a0);
       a1 = fmaf(ds[j], to_f32(x.b), a1);
       b0 = fmaf(ds[j + 1], to_f32(y.a), b0);
       b1 = fmaf(ds[j + 1], to_f32(y.b), b1);
     }
     if (j < nk) {
-      const pair2<T> x = *(const pair2<T>*)(kc + (size_t)j * d);
+      const pair2<T> x = *(const pair2<T>*)(kc + (size_t)j * ldq);
       a0 = fmaf(ds[j], to_f32(x.a), a0);
       a1 = fmaf(ds[j], to_f32(x.b), a1);
     }
     if (live) {
-      pair2<T> o;
-      o.a = from_f32<T>((a0 + b0) * scale);
-      o.b = from_f32<T>((a1 + b1) * scale);
-      *(pair2<T>*)(dq + t * d + col + e) = o;
+      pair2<T> ov;
+      ov.a = from_f32<T>((a0 + b0) * scale);
+      ov.b = from_f32<T>((a1 + b1) * scale);
+      *(pair2<T>*)(dq + t * ldo + col + e) = ov;
+    }
+  }
+  if (o) {  // the forward output O_i = sum_j P_ij V_j, for callers that recompute the forward pass here
+    for (int e = 2 * lane; e < hd; e += 128) {
+      const T* vc = v + (size_t)s0 * ldq + col + e;
+      float a0 = 0.f, a1 = 0.f;
+      for (int j = 0; j < nk; ++j) {
+        const pair2<T> x = *(const pair2<T>*)(vc + (size_t)j * ldq);
+        a0 = fmaf(p[j], to_f32(x.a), a0);
+        a1 = fmaf(p[j], to_f32(x.b), a1);
+      }
+      if (live) {
+        pair2<T> ov;
+        ov.a = from_f32<T>(a0);
+        ov.b = from_f32<T>(a1);
+        *(pair2<T>*)(o + t * ldoo + col + e) = ov;
+      }
     }
   }
   if (live && lane == 0) {
@@ -131,7 +149,7 @@ __global__ void __launch_bounds__(256)
     attn_bwd_kv_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
                        const T* __restrict__ g, const int* __restrict__ cu, int B, int Tn, int H, int hd, float scale,
                        int max_len, const float* __restrict__ lse, const float* __restrict__ delta,
-                       T* __restrict__ dk, T* __restrict__ dv) {
+                       T* __restrict__ dk, T* __restrict__ dv, size_t ldq, size_t ldg, size_t ldo) {
   extern __shared__ float sm[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = blockIdx.y;
   const int t_raw = blockIdx.x * 4 + wave;
@@ -141,31 +159,31 @@ __global__ void __launch_bounds__(256)
   const int n = min(cu[b + 1] - s0, max_len);
   const int j = t - s0;
   const int nq = max(min(n - j, Tn - t), 0);  // queries j .. n-1 of the sequence see this key
-  const size_t d = (size_t)H * hd, col = (size_t)h * hd;
+  const size_t col = (size_t)h * hd;
   float* ks = sm + (size_t)wave * (2 * hd + 2 * max_len);
   float* vs = ks + hd;
   float* p = vs + hd;
   float* ds = p + max_len;
   for (int e = lane; e < hd; e += 64) {
-    ks[e] = to_f32(k[t * d + col + e]);
-    vs[e] = to_f32(v[t * d + col + e]);
+    ks[e] = to_f32(k[t * ldq + col + e]);
+    vs[e] = to_f32(v[t * ldq + col + e]);
   }
   __syncthreads();
   for (int ii = lane; ii < nq; ii += 64) {
     const size_t r = (size_t)(t + ii);
-    const float s = dot_row(ks, q + r * d + col, hd) * scale;
+    const float s = dot_row(ks, q + r * ldq + col, hd) * scale;
     const float pr = __expf(s - lse[r * H + h]);
-    const float dp = dot_row(vs, g + r * d + col, hd);
+    const float dp = dot_row(vs, g + r * ldg + col, hd);
     p[ii] = pr;
     ds[ii] = pr * (dp - delta[r * H + h]);
   }
   __syncthreads();
   for (int e = 2 * lane; e < hd; e += 128) {
-    const T* gc = g + (size_t)t * d + col + e;
-    const T* qc = q + (size_t)t * d + col + e;
+    const T* gc = g + (size_t)t * ldg + col + e;
+    const T* qc = q + (size_t)t * ldq + col + e;
     float av0 = 0.f, av1 = 0.f, ak0 = 0.f, ak1 = 0.f;
     for (int ii = 0; ii < nq; ++ii) {
-      const pair2<T> x = *(const pair2<T>*)(gc + (size_t)ii * d), y = *(const pair2<T>*)(qc + (size_t)ii * d);
+      const pair2<T> x = *(const pair2<T>*)(gc + (size_t)ii * ldg), y = *(const pair2<T>*)(qc + (size_t)ii * ldq);
       av0 = fmaf(p[ii], to_f32(x.a), av0);
       av1 = fmaf(p[ii], to_f32(x.b), av1);
       ak0 = fmaf(ds[ii], to_f32(y.a), ak0);
@@ -175,21 +193,80 @@ __global__ void __launch_bounds__(256)
       pair2<T> o;
       o.a = from_f32<T>(av0);
       o.b = from_f32<T>(av1);
-      *(pair2<T>*)(dv + t * d + col + e) = o;
+      *(pair2<T>*)(dv + t * ldo + col + e) = o;
       o.a = from_f32<T>(ak0 * scale);
       o.b = from_f32<T>(ak1 * scale);
-      *(pair2<T>*)(dk + t * d + col + e) = o;
+      *(pair2<T>*)(dk + t * ldo + col + e) = o;
     }
   }
 }
 
+// Rotary turn of the q and k sections of a [T, 3*d] matrix (sections q | k | v, heads of hd, the first
+// r dims of a head rotary), in place, by the row's position in its sequence (row - cu[sequence]);
+// dir = +1 turns forward, -1 back (the transpose of the forward turn: what a gradient takes).
+// ADJ: pairs are (2i, 2i+1) -- the reordered layout of the fp16 path -- else (i, i + r/2).
+template <typename T, bool ADJ>
+__global__ void __launch_bounds__(256)
+    rope_inplace_kernel(T* __restrict__ qkv, size_t ld, const int* __restrict__ cu, int B, int Tn, int H, int hd, int r,
+                        const float* __restrict__ cos_t, const float* __restrict__ sin_t, float dir) {
+  const int t = blockIdx.x;
+  if (t >= Tn || t >= cu[B]) return;
+  const int b = find_seq(cu, B, t), pos = t - min(max(cu[b], 0), t), half = r >> 1;
+  const float* cs = cos_t + (size_t)pos * half;
+  const float* sn = sin_t + (size_t)pos * half;
+  for (int c = threadIdx.x; c < 2 * H * half; c += 256) {
+    const int u = c / half, i = c - u * half;  // u = section * H + head
+    T* hb = qkv + (size_t)t * ld + (size_t)u * hd;  // sections are d = H*hd apart, so (section, head) is u heads in
+    const int lo_i = ADJ ? 2 * i : i, hi_i = ADJ ? 2 * i + 1 : i + half;
+    const float co = cs[i], si = sn[i] * dir;
+    const float lo = to_f32(hb[lo_i]), hi = to_f32(hb[hi_i]);
+    hb[lo_i] = from_f32<T>(lo * co - hi * si);
+    hb[hi_i] = from_f32<T>(hi * co + lo * si);
+  }
+}
+
+// out[src(n)] = in[n] for the 3*d rows of a W_qkv-shaped matrix (or its bias, C = 1): puts rows that are in
+// the reordered pair layout of the fp16 path back into the caller's order (see qkv_weights_f16_kernel).
+__global__ void __launch_bounds__(256)
+    qkv_rows_to_caller_order_kernel(const float* __restrict__ in, float* __restrict__ out, int d, int hd, int r, int C) {
+  const int n = blockIdx.x;
+  const int sec = n / d, e = (n - sec * d) % hd;
+  int src = n;
+  if (sec < 2 && e < r) src = n - e + ((e & 1) ? (e >> 1) + (r >> 1) : (e >> 1));
+  for (int c = threadIdx.x; c < C; c += 256) out[(size_t)src * C + c] = in[(size_t)n * C + c];
+}
+
 }  // namespace
+
+hipError_t launch_rope_inplace(int dtype, void* qkv, size_t ld, const int* cu, int B, int Tn, int H, int hd, int r,
+                               const float* cos_t, const float* sin_t, int backward, hipStream_t s) {
+  if (Tn <= 0 || r <= 0) return hipSuccess;
+  const float dir = backward ? -1.0f : 1.0f;
+  if (dtype == 0)
+    hipLaunchKernelGGL((rope_inplace_kernel<float, false>), dim3(Tn), dim3(256), 0, s, (float*)qkv, ld, cu, B, Tn, H, hd,
+                       r, cos_t, sin_t, dir);
+  else
+    hipLaunchKernelGGL((rope_inplace_kernel<half_t, true>), dim3(Tn), dim3(256), 0, s, (half_t*)qkv, ld, cu, B, Tn, H,
+                       hd, r, cos_t, sin_t, dir);
+  return hipGetLastError();
+}
+
+hipError_t launch_qkv_rows_to_caller_order(const float* in, float* out, int d, int hd, int r, int C, hipStream_t s) {
+  hipLaunchKernelGGL(qkv_rows_to_caller_order_kernel, dim3(3 * d), dim3(256), 0, s, in, out, d, hd, r, C);
+  return hipGetLastError();
+}
 
 // dtype 0: float, 1: fp16.  head_dim a multiple of 4 (float) or 8 (fp16); the longest sequence at
 // most max_len rows (longer ones are cut off at max_len: wrong results, but no access out of bounds).
 hipError_t launch_attention_backward(int dtype, const void* q, const void* k, const void* v, const void* g,
                                      const int* cu, int B, int Tn, int H, int hd, int max_len, float* lse,
-                                     float* delta, void* dq, void* dk, void* dv, hipStream_t s) {
+                                     float* delta, void* dq, void* dk, void* dv, hipStream_t s, size_t ld_qkv,
+                                     size_t ld_g, size_t ld_out, void* o, size_t ld_o) {
+  const size_t dm = (size_t)H * hd;
+  if (!ld_qkv) ld_qkv = dm;
+  if (!ld_g) ld_g = dm;
+  if (!ld_out) ld_out = dm;
+  if (!ld_o) ld_o = dm;
   if (Tn <= 0) return hipSuccess;
   if (hd <= 0 || (hd % (dtype == 0 ? 4 : 8)) != 0 || max_len <= 0) return hipErrorInvalidValue;
   const size_t sh = (size_t)4 * (2 * (size_t)hd + 2 * (size_t)max_len) * sizeof(float);
@@ -202,20 +279,22 @@ hipError_t launch_attention_backward(int dtype, const void* q, const void* k, co
       (void)hipFuncSetAttribute((const void*)attn_bwd_kv_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
     }
     hipLaunchKernelGGL(attn_bwd_q_kernel<float>, grid, dim3(256), sh, s, (const float*)q, (const float*)k,
-                       (const float*)v, (const float*)g, cu, B, Tn, H, hd, scale, max_len, lse, delta, (float*)dq);
+                       (const float*)v, (const float*)g, cu, B, Tn, H, hd, scale, max_len, lse, delta, (float*)dq, ld_qkv,
+                       ld_g, ld_out, (float*)o, ld_o);
     hipLaunchKernelGGL(attn_bwd_kv_kernel<float>, grid, dim3(256), sh, s, (const float*)q, (const float*)k,
                        (const float*)v, (const float*)g, cu, B, Tn, H, hd, scale, max_len, lse, delta, (float*)dk,
-                       (float*)dv);
+                       (float*)dv, ld_qkv, ld_g, ld_out);
   } else {
     if (sh > 65536) {
       (void)hipFuncSetAttribute((const void*)attn_bwd_q_kernel<half_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
       (void)hipFuncSetAttribute((const void*)attn_bwd_kv_kernel<half_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
     }
     hipLaunchKernelGGL(attn_bwd_q_kernel<half_t>, grid, dim3(256), sh, s, (const half_t*)q, (const half_t*)k,
-                       (const half_t*)v, (const half_t*)g, cu, B, Tn, H, hd, scale, max_len, lse, delta, (half_t*)dq);
+                       (const half_t*)v, (const half_t*)g, cu, B, Tn, H, hd, scale, max_len, lse, delta, (half_t*)dq,
+                       ld_qkv, ld_g, ld_out, (half_t*)o, ld_o);
     hipLaunchKernelGGL(attn_bwd_kv_kernel<half_t>, grid, dim3(256), sh, s, (const half_t*)q, (const half_t*)k,
                        (const half_t*)v, (const half_t*)g, cu, B, Tn, H, hd, scale, max_len, lse, delta, (half_t*)dk,
-                       (half_t*)dv);
+                       (half_t*)dv, ld_qkv, ld_g, ld_out);
   }
   return hipGetLastError();
 }

@@ -293,7 +293,18 @@ hipError_t launch_colsum(int elem, const void* a, int R, int C, float* part, int
 // lse, delta: [T*H] floats of scratch.  hd a multiple of 4 (float) or 8 (fp16); sequences of at most max_len rows.
 hipError_t launch_attention_backward(int dtype, const void* q, const void* k, const void* v, const void* g,
                                      const int* cu, int B, int Tn, int H, int hd, int max_len, float* lse,
-                                     float* delta, void* dq, void* dk, void* dv, hipStream_t s);
+                                     float* delta, void* dq, void* dk, void* dv, hipStream_t s, size_t ld_qkv = 0,
+                                     size_t ld_g = 0, size_t ld_out = 0, void* o = nullptr, size_t ld_o = 0);
+// (row strides in elements: ld_qkv of q, k, v; ld_g of g; ld_out of dq, dk, dv; 0 = H*hd.  o: optional forward
+// output O = P V, [T, ld_o].)
+
+// Rotary turn, in place, of the q and k sections of a [T, 3*d] matrix (row stride ld) by each row's position in
+// its sequence; backward != 0 applies the transpose (turn by the negative angle).  dtype 1 uses the reordered
+// pair layout (2i, 2i+1) of the fp16 path, dtype 0 the pairs (i, i + r/2).
+hipError_t launch_rope_inplace(int dtype, void* qkv, size_t ld, const int* cu, int B, int Tn, int H, int hd, int r,
+                               const float* cos_t, const float* sin_t, int backward, hipStream_t s);
+// Rows of a [3*d, C] fp32 matrix from the fp16 path's reordered W_qkv row order back to the caller's.
+hipError_t launch_qkv_rows_to_caller_order(const float* in, float* out, int d, int hd, int r, int C, hipStream_t s);
 
 hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s);
 // Same for a [rows, cols] matrix written with row stride dst_ld (elements).

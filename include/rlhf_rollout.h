@@ -251,6 +251,24 @@ int rlhf_attention_backward(const void *q, const void *k, const void *v, const v
                             int32_t dtype, int32_t max_len, float *lse_scratch, float *delta_scratch, void *dq,
                             void *dk, void *dv, void *stream);
 
+/* Backward pass through the attention branch of decoder layer `layer` (paper: as for rlhf_mlp_backward; the
+ * other branch of the parallel-residual layer).  With a = LN1(x), [q | k | v] = a Wqkv^T + bqkv, the rotary turn
+ * of q and k by each row's position in its sequence, o = packed causal attention (rlhf_attention_backward's
+ * forward), y = o Wo^T + bo and an upstream gradient d_out = dL/dx_out (any scale: the call is linear in it):
+ *   d_x [T, d]        the branch's term of dL/dx (the residual's identity term d_out is NOT included)
+ *   d_ln1_g, d_ln1_b [d];  d_w_qkv [3d, d], d_b_qkv [3d] (rows in the caller's order: q of all heads | k | v);
+ *   d_w_o [d, d], d_b_o [d]                                                                    (overwritten)
+ * The branch's forward is recomputed from x_in.  x_in, d_out: dev float [T, d], packed rows, sequence b in rows
+ * cu_seqlens[b] .. cu_seqlens[b+1]-1 (dev int32 [B+1], from 0 to T), positions counted from each sequence's
+ * first row; max_len (host) at least the longest sequence and at most 8192.  In bf16 mode d_out, q, k, v, o and
+ * the attention gradients are fp16 (operands of the gradient products): scale d_out into fp16's range.  Sums
+ * run in a fixed order.  Workspace size from rlhf_attention_branch_backward_workspace_bytes. */
+int rlhf_attention_branch_backward_workspace_bytes(const rlhf_handle *h, int32_t T, size_t *out);
+int rlhf_attention_branch_backward(rlhf_handle *h, int32_t layer, const float *x_in, const float *d_out,
+                                   const int32_t *cu_seqlens, int32_t B, int32_t T, int32_t max_len, float *d_x,
+                                   float *d_ln1_g, float *d_ln1_b, float *d_w_qkv, float *d_b_qkv, float *d_w_o,
+                                   float *d_b_o, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Debug / parity aid: raw (pre-temperature) fp32 logits of the same forward pass as
  * score_sequences at n (row, column) pairs.  rows_bt: HOST int32 [n, 2]; out_logits: dev float
  * [n, vocab].  Every pair must name a real position. */

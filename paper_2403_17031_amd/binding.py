@@ -15,7 +15,7 @@ EXPORTS = (
     "rlhf_create", "rlhf_destroy", "rlhf_workspace_bytes", "rollout_generate", "score_sequences",
     "rlhf_debug_logits_rows", "rlhf_profile_enable", "rlhf_profile_read", "rlhf_last_rollout_phases",
     "rlhf_last_error", "rlhf_ppo_assemble_rewards", "rlhf_ppo_gae", "rlhf_ppo_whiten", "rlhf_ppo_loss", "rlhf_adamw_step",
-    "rlhf_head_backward", "rlhf_head_backward_workspace_bytes", "rlhf_mlp_backward", "rlhf_mlp_backward_workspace_bytes", "rlhf_attention_backward",
+    "rlhf_head_backward", "rlhf_head_backward_workspace_bytes", "rlhf_mlp_backward", "rlhf_mlp_backward_workspace_bytes", "rlhf_attention_backward", "rlhf_attention_branch_backward", "rlhf_attention_branch_backward_workspace_bytes",
 )
 
 _PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -71,6 +71,8 @@ def load_library():
     lib.rlhf_head_backward.argtypes = [vp, vp, vp, vp, vp, i32, C.c_float, C.c_float] + [vp] * 6 + [vp, C.c_size_t, vp]
     lib.rlhf_mlp_backward_workspace_bytes.argtypes = [vp, i32, C.POINTER(C.c_size_t)]
     lib.rlhf_mlp_backward.argtypes = [vp, i32, vp, vp, i32] + [vp] * 7 + [vp, C.c_size_t, vp]
+    lib.rlhf_attention_branch_backward_workspace_bytes.argtypes = [vp, i32, C.POINTER(C.c_size_t)]
+    lib.rlhf_attention_branch_backward.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32] + [vp] * 7 + [vp, C.c_size_t, vp]
     lib.rlhf_attention_backward.argtypes = [vp] * 5 + [i32] * 6 + [vp] * 5 + [vp]
     lib.rlhf_adamw_step.argtypes = [vp, vp, vp, vp, vp, u64, i32] + [C.c_double] * 6 + [vp]
     lib.rlhf_last_error.restype = C.c_char_p
@@ -246,6 +248,34 @@ class Policy:
                                               *[res[k].data_ptr() for k in ("d_x", "d_ln2_g", "d_ln2_b", "d_w_fc1",
                                                                             "d_b_fc1", "d_w_fc2", "d_b_fc2")],
                                               ws.data_ptr(), ws.numel(), self._stream()))
+        return res
+
+    def attention_branch_backward(self, layer, x_in, d_out, cu_seqlens, max_len=None):
+        """x_in, d_out float32 [T, d]; cu_seqlens int32 [B+1].  Returns a dict of CUDA float32 tensors: d_x [T, d]
+        (the attention branch's term only), d_ln1_g, d_ln1_b [d], d_w_qkv [3d, d], d_b_qkv [3d], d_w_o [d, d],
+        d_b_o [d]."""
+        torch = self.torch
+        x = self._to_dev(x_in, torch.float32)
+        g = self._to_dev(d_out, torch.float32)
+        cu = self._to_dev(cu_seqlens if isinstance(cu_seqlens, torch.Tensor) else np.asarray(cu_seqlens, dtype=np.int32),
+                          torch.int32)
+        T, d = x.shape
+        if d != self.cfg.d_model or tuple(g.shape) != (T, d) or cu.dim() != 1 or cu.numel() < 2:
+            raise RlhfError("attention_branch_backward: x_in and d_out must be [T, d_model], cu_seqlens [B+1]")
+        if max_len is None:
+            max_len = int((cu[1:] - cu[:-1]).max().item())
+        out = C.c_size_t()
+        _check(self.lib.rlhf_attention_branch_backward_workspace_bytes(self._h, T, C.byref(out)))
+        ws = self._workspace(out.value)
+        new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=self.device)
+        names = ("d_x", "d_ln1_g", "d_ln1_b", "d_w_qkv", "d_b_qkv", "d_w_o", "d_b_o")
+        res = dict(d_x=new(T, d), d_ln1_g=new(d), d_ln1_b=new(d), d_w_qkv=new(3 * d, d), d_b_qkv=new(3 * d),
+                   d_w_o=new(d, d), d_b_o=new(d))
+        with torch.cuda.device(self.device):
+            _check(self.lib.rlhf_attention_branch_backward(self._h, int(layer), x.data_ptr(), g.data_ptr(), cu.data_ptr(),
+                                                           cu.numel() - 1, T, max(int(max_len), 1),
+                                                           *[res[k].data_ptr() for k in names], ws.data_ptr(),
+                                                           ws.numel(), self._stream()))
         return res
 
     def debug_logits_rows(self, tokens, mask, rows_bt):

@@ -855,6 +855,126 @@ int rlhf_mlp_backward(rlhf_handle* h, int32_t layer, const float* x_in, const fl
   return RLHF_OK;
 }
 
+namespace {
+struct AttnBwdWs {
+  void *a, *qkv, *go, *dO, *att, *dqkv, *goT, *attT, *dqkvT, *aT, *woT, *wqkvT;
+  float *da, *dwq, *dbq, *stats, *part, *lse, *delta;
+  int T_pad, splits;
+};
+AttnBwdWs carve_attn_bwd(Carver& c, const rlhf_model_config& cfg, int T, size_t esz) {
+  AttnBwdWs w;
+  const size_t d = cfg.d_model;
+  w.T_pad = (T + 127) & ~127;
+  w.splits = std::max(1, std::min(256, (T + 255) / 256));
+  const size_t Tp = (size_t)w.T_pad;
+  w.a = c.take_bytes((size_t)T * d * esz);
+  w.qkv = c.take_bytes((size_t)T * 3 * d * esz);
+  w.go = c.take_bytes((size_t)T * d * esz);
+  w.dO = c.take_bytes((size_t)T * d * esz);
+  w.att = c.take_bytes((size_t)T * d * esz);
+  w.dqkv = c.take_bytes((size_t)T * 3 * d * esz);
+  w.goT = c.take_bytes(d * Tp * esz);
+  w.attT = c.take_bytes(d * Tp * esz);
+  w.dqkvT = c.take_bytes(3 * d * Tp * esz);
+  w.aT = c.take_bytes(d * Tp * esz);
+  w.woT = c.take_bytes(d * d * esz);
+  w.wqkvT = c.take_bytes(3 * d * d * esz);
+  w.da = c.take<float>((size_t)T * d);
+  w.dwq = c.take<float>(3 * d * d);
+  w.dbq = c.take<float>(3 * d);
+  w.stats = c.take<float>((size_t)2 * T);
+  w.part = c.take<float>((size_t)w.splits * 3 * d);
+  w.lse = c.take<float>((size_t)T * cfg.n_heads);
+  w.delta = c.take<float>((size_t)T * cfg.n_heads);
+  return w;
+}
+}  // namespace
+
+int rlhf_attention_branch_backward_workspace_bytes(const rlhf_handle* h, int32_t T, size_t* out) {
+  if (!h || !out) return fail(RLHF_EINVAL, "null argument");
+  if (T <= 0) return fail(RLHF_EINVAL, "row count must be positive");
+  Carver c(nullptr);
+  carve_attn_bwd(c, h->cfg, T, h->esz);
+  *out = c.off + 256;
+  return RLHF_OK;
+}
+
+int rlhf_attention_branch_backward(rlhf_handle* h, int32_t layer, const float* x_in, const float* d_out,
+                                   const int32_t* cu_seqlens, int32_t B, int32_t T, int32_t max_len, float* d_x,
+                                   float* d_ln1_g, float* d_ln1_b, float* d_w_qkv, float* d_b_qkv, float* d_w_o,
+                                   float* d_b_o, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!h) return fail(RLHF_EINVAL, "null handle");
+  const rlhf_model_config& c = h->cfg;
+  if (layer < 0 || layer >= c.n_layers) return fail(RLHF_EINVAL, "layer index out of range");
+  if (T <= 0 || B <= 0 || max_len <= 0) return fail(RLHF_EINVAL, "rows, batch and max_len must be positive");
+  if (max_len > kMaxPos) return fail(RLHF_EUNSUPPORTED, "sequence longer than the rotary table");
+  if ((size_t)T * 3 * (size_t)c.d_model >= ((size_t)1 << 32) - (size_t)384 * c.d_model)
+    return fail(RLHF_EUNSUPPORTED, "too many rows");
+  if (!x_in || !d_out || !cu_seqlens || !d_x || !d_ln1_g || !d_ln1_b || !d_w_qkv || !d_b_qkv || !d_w_o || !d_b_o ||
+      !workspace)
+    return fail(RLHF_EINVAL, "null pointer argument");
+  const int dt = c.dtype, d = c.d_model, H = c.n_heads, hd = c.head_dim, l = layer;
+  if ((hd % (dt == 0 ? 4 : 8)) != 0) return fail(RLHF_EUNSUPPORTED, "head_dim must be a multiple of 4 (fp32) or 8 (bf16)");
+  if ((size_t)4 * (2 * (size_t)hd + 2 * (size_t)max_len) * sizeof(float) > 150 * 1024)
+    return fail(RLHF_EUNSUPPORTED, "max_len too large for the attention kernels' scratch");
+  Carver cv((void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255));
+  AttnBwdWs ws = carve_attn_bwd(cv, c, T, h->esz);
+  if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
+    return fail(RLHF_ENOMEM, "workspace too small for rlhf_attention_branch_backward");
+  hipStream_t s = (hipStream_t)stream;
+  const size_t esz = h->esz;
+  const int Tp = ws.T_pad;
+  const size_t ld_wo = h->ld_o2 ? (size_t)h->ld_o2 : (size_t)d;  // row stride of this layer's W_o
+  const bool reordered = dt == 1;  // fp16 path: W_qkv's rows (and so the columns of qkv) are in the pair layout
+
+  auto gemm = [&](const void* A, const void* W, const void* bias, void* out, int M, int N, int K, int epi) {
+    GemmArgs g;
+    g.A = A; g.W = W; g.bias = bias; g.out = out; g.M_max = M; g.M_dev = nullptr;
+    g.N = N; g.K = K; g.ldo = N; g.epilogue = epi;
+    return g;
+  };
+  // ---- the branch's forward, recomputed from the layer input: a = LN1(x), qkv = a Wqkv^T + b, rotary turn
+  LAUNCH("final_ln", launch_final_ln(dt, x_in, nullptr, 0, T, nullptr, d, c.ln_eps, h->ln1_g[l], h->ln1_b[l], ws.a,
+                                     nullptr, 0.f, nullptr, s));
+  LAUNCH("gemm_attn_fwd", launch_gemm(dt, gemm(ws.a, h->w_qkv[l], h->b_qkv[l], ws.qkv, T, 3 * d, d, EPI_BIAS), s));
+  LAUNCH("rope_inplace", launch_rope_inplace(dt, ws.qkv, (size_t)3 * d, cu_seqlens, B, T, H, hd, c.rotary_dims,
+                                             h->rope_cos, h->rope_sin, 0, s));
+  // ---- out-projection: dbo = sum_t G, do = G Wo
+  LAUNCH("colsum", launch_colsum(0, d_out, T, d, ws.part, ws.splits, d_b_o, s));
+  LAUNCH("convert", launch_convert_from_f32(dt, d_out, ws.go, (size_t)T * d, s));
+  LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, h->w_o[l], ld_wo, ws.woT, (size_t)d, d, d, d, s));
+  LAUNCH("gemm_attn_dx", launch_gemm(dt, gemm(ws.go, ws.woT, nullptr, ws.dO, T, d, d, EPI_BIAS), s));
+  // ---- attention core: (dq | dk | dv) into the sections of dqkv, and the forward output o
+  char* qkv = (char*)ws.qkv;
+  char* dqkv = (char*)ws.dqkv;
+  LAUNCH("attention_backward",
+         launch_attention_backward(dt, qkv, qkv + (size_t)d * esz, qkv + (size_t)2 * d * esz, ws.dO, cu_seqlens, B, T, H, hd,
+                                   max_len, ws.lse, ws.delta, dqkv, dqkv + (size_t)d * esz, dqkv + (size_t)2 * d * esz, s,
+                                   (size_t)3 * d, (size_t)d, (size_t)3 * d, ws.att, (size_t)d));
+  // ---- dWo = G^T o
+  LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.go, (size_t)d, ws.goT, (size_t)Tp, T, d, Tp, s));
+  LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.att, (size_t)d, ws.attT, (size_t)Tp, T, d, Tp, s));
+  LAUNCH("gemm_attn_dw", launch_gemm(dt, gemm(ws.goT, ws.attT, nullptr, d_w_o, d, d, Tp, EPI_F32), s));
+  // ---- back through the rotary turn, then the QKV product: dbqkv, dWqkv, da
+  LAUNCH("rope_inplace", launch_rope_inplace(dt, ws.dqkv, (size_t)3 * d, cu_seqlens, B, T, H, hd, c.rotary_dims,
+                                             h->rope_cos, h->rope_sin, 1, s));
+  LAUNCH("colsum", launch_colsum(dt, ws.dqkv, T, 3 * d, ws.part, ws.splits, reordered ? ws.dbq : d_b_qkv, s));
+  LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.dqkv, (size_t)3 * d, ws.dqkvT, (size_t)Tp, T, 3 * d, Tp, s));
+  LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.a, (size_t)d, ws.aT, (size_t)Tp, T, d, Tp, s));
+  LAUNCH("gemm_attn_dw", launch_gemm(dt, gemm(ws.dqkvT, ws.aT, nullptr, reordered ? ws.dwq : d_w_qkv, 3 * d, d, Tp, EPI_F32), s));
+  if (reordered) {
+    LAUNCH("qkv_rows", launch_qkv_rows_to_caller_order(ws.dwq, d_w_qkv, d, hd, c.rotary_dims, d, s));
+    LAUNCH("qkv_rows", launch_qkv_rows_to_caller_order(ws.dbq, d_b_qkv, d, hd, c.rotary_dims, 1, s));
+  }
+  LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, h->w_qkv[l], (size_t)d, ws.wqkvT, (size_t)3 * d, 3 * d, d, 3 * d, s));
+  LAUNCH("gemm_attn_dx", launch_gemm(dt, gemm(ws.dqkv, ws.wqkvT, nullptr, ws.da, T, d, 3 * d, EPI_F32), s));
+  // ---- LN1: the branch's term of dL/dx, and the gradients of its gain and bias
+  LAUNCH("head_ln_backward", launch_head_ln_backward(dt, x_in, ws.da, nullptr, 1.0f, nullptr, h->ln1_g[l], h->ln1_b[l], T,
+                                                     d, c.ln_eps, d_x, ws.stats, ws.part, ws.splits, d_ln1_g, d_ln1_b,
+                                                     nullptr, nullptr, s));
+  return RLHF_OK;
+}
+
 int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_mask, int32_t B, int32_t Lq,
                      uint64_t seed, uint64_t seq_id_base, float temperature, int32_t max_new_tokens,
                      int32_t* out_tokens, float* out_logprobs, int32_t* out_lengths, uint8_t* out_mask,

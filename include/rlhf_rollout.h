@@ -269,6 +269,41 @@ int rlhf_attention_branch_backward(rlhf_handle *h, int32_t layer, const float *x
                                    float *d_ln1_g, float *d_ln1_b, float *d_w_qkv, float *d_b_qkv, float *d_w_o,
                                    float *d_b_o, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- The whole backward pass of the policy (with its value head) for one PPO update. ------------------
+ *
+ * rlhf_forward_keep: the forward pass of score_sequences over tokens / mask (same conventions), keeping what
+ * the backward pass needs: x_keep dev float [(n_layers + 1), B*L, d_model] receives the residual stream at the
+ * input of every layer and after the last one, packed rows first (row cu[b] + i = token i of sequence b;
+ * rows past the number of real tokens are undefined); cu_seqlens dev int32 [B+1] and packed_tokens dev int32
+ * [B*L] receive the packing.  Workspace as for score_sequences(B, L).
+ *
+ * Gradients are returned through rlhf_grads, the mirror of rlhf_weights: DEVICE float arrays of the weights'
+ * shapes, overwritten; the per-layer members are HOST arrays of n_layers device pointers; value_w / value_b
+ * may be NULL iff the model has no value head.
+ *
+ * rlhf_policy_backward: from dL/dlogprob and dL/dvalue per packed row (see rlhf_head_backward for targets,
+ * d_logprobs, d_values, temperature and grad_scale) through the heads, every layer's two branches (the
+ * residual stream's gradient is the sum of the upstream gradient and the two branch terms, added in that
+ * order) and the input embedding (rows of equal tokens summed in packed order).  T (host) is the number of
+ * real tokens = cu_seqlens[B]; max_len (host) at least the longest sequence.  Everything is grad_scale times
+ * the gradient; rlhf_adamw_step divides it out.  (paper: PPO Details / PPO hyperparameter table -- the update
+ * is gradient descent on the loss of rlhf_ppo_loss; the model is Tech stack's GPT-NeoX with the scalar head.) */
+typedef struct {
+  float *embed_in;
+  float *const *ln1_g, *const *ln1_b, *const *ln2_g, *const *ln2_b;
+  float *const *w_qkv, *const *b_qkv, *const *w_o, *const *b_o;
+  float *const *w_fc1, *const *b_fc1, *const *w_fc2, *const *b_fc2;
+  float *lnf_g, *lnf_b, *embed_out, *value_w, *value_b;
+} rlhf_grads;
+int rlhf_forward_keep(rlhf_handle *h, const int32_t *tokens, const uint8_t *mask, int32_t B, int32_t L,
+                      float *x_keep, int32_t *cu_seqlens, int32_t *packed_tokens, void *workspace,
+                      size_t workspace_bytes, void *stream);
+int rlhf_policy_backward_workspace_bytes(const rlhf_handle *h, int32_t T, size_t *out);
+int rlhf_policy_backward(rlhf_handle *h, const float *x_keep, int64_t x_keep_layer_stride, const int32_t *cu_seqlens,
+                         const int32_t *packed_tokens, int32_t B, int32_t T, int32_t max_len, const int32_t *targets,
+                         const float *d_logprobs, const float *d_values, float temperature, float grad_scale,
+                         const rlhf_grads *grads, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Debug / parity aid: raw (pre-temperature) fp32 logits of the same forward pass as
  * score_sequences at n (row, column) pairs.  rows_bt: HOST int32 [n, 2]; out_logits: dev float
  * [n, vocab].  Every pair must name a real position. */

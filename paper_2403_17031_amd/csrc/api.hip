@@ -245,11 +245,19 @@ struct PassArgs {
   // for every row as usual, but attention, out-projection and MLP run on the B gathered last rows
   // only, into last->x ([B, d], row b = sequence b).
   const Acts* last = nullptr;
+  // Training forward: when set, the residual stream at the input of layer l is copied to
+  // keep + l * keep_stride (rows_max rows), and the stream after the last layer to slot n_layers.
+  float* keep = nullptr;
+  size_t keep_stride = 0;
 };
 
 int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) {
   const rlhf_model_config& c = h->cfg;
-  if (c.n_layers == 0) return RLHF_OK;  // nothing to run (and no layer 0 to take shapes from below)
+  if (c.n_layers == 0) {  // nothing to run (and no layer 0 to take shapes from below)
+    if (p.keep)
+      HIP_OK(hipMemcpyAsync(p.keep, A.x, (size_t)p.rows_max * c.d_model * sizeof(float), hipMemcpyDeviceToDevice, s));
+    return RLHF_OK;
+  }
   const int d = c.d_model, dt = c.dtype;
   const size_t plane = p.kv_slots * (size_t)d * h->esz;  // bytes of one K (or V) plane of one layer
 
@@ -294,6 +302,9 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
   bool pending = false;  // out-projection and FC2 partial sums of the previous layer not yet in x
 
   for (int l = 0; l < c.n_layers; ++l) {
+    if (p.keep)
+      HIP_OK(hipMemcpyAsync(p.keep + (size_t)l * p.keep_stride, A.x, (size_t)p.rows_max * d * sizeof(float),
+                            hipMemcpyDeviceToDevice, s));
     char* kc = p.kv + (p.kv_per_layer ? (size_t)l * 2 * plane : 0);
     char* vc = kc + plane;
     if (pending) {
@@ -421,6 +432,9 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
       LAUNCH("gemm_decode", launch_gemm(dt, g2, s));
     }
   }
+  if (p.keep)
+    HIP_OK(hipMemcpyAsync(p.keep + (size_t)c.n_layers * p.keep_stride, A.x, (size_t)p.rows_max * d * sizeof(float),
+                          hipMemcpyDeviceToDevice, s));
   return RLHF_OK;
 }
 
@@ -1076,7 +1090,7 @@ int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_
 }
 
 static int score_forward(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, int B, int L, ScoreWs& ws,
-                         hipStream_t s) {
+                         hipStream_t s, float* keep = nullptr) {
   const rlhf_model_config& c = h->cfg;
   const Meta& m = ws.meta;
   LAUNCH("row_spans", launch_row_spans(mask, B, L, 0, m.start, m.len, m.cu, m.kvoff, m.total, s));
@@ -1100,6 +1114,8 @@ static int score_forward(rlhf_handle* h, const int32_t* tokens, const uint8_t* m
   p.kv = ws.kv;
   p.kv_slots = ws.Tmax;
   p.kv_per_layer = false;
+  p.keep = keep;
+  p.keep_stride = (size_t)B * L * c.d_model;
   return run_layers(h, ws.acts, p, s);
 }
 
@@ -1155,6 +1171,93 @@ int score_sequences(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, 
   LAUNCH("unpack_scores", launch_unpack_scores(ws.lp, (out_values && h->w.value_w) ? ws.val : nullptr, B, L, m.start,
                                                m.len, m.cu, out_logprobs,
                                                (out_values && h->w.value_w) ? out_values : nullptr, s));
+  return RLHF_OK;
+}
+
+int rlhf_forward_keep(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, int32_t B, int32_t L, float* x_keep,
+                      int32_t* cu_seqlens, int32_t* packed_tokens, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  int rc = check_common(h, B, L);
+  if (rc) return rc;
+  if (!tokens || !mask || !x_keep || !cu_seqlens || !packed_tokens || !workspace)
+    return fail(RLHF_EINVAL, "null pointer argument");
+  const rlhf_model_config& c = h->cfg;
+  Carver cv((void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255));
+  ScoreWs ws = carve_score(cv, c, B, L, h->esz);
+  if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
+    return fail(RLHF_ENOMEM, "workspace too small for rlhf_forward_keep");
+  hipStream_t s = (hipStream_t)stream;
+  rc = score_forward(h, tokens, mask, B, L, ws, s, x_keep);
+  if (rc) return rc;
+  HIP_OK(hipMemcpyAsync(cu_seqlens, ws.meta.cu, (size_t)(B + 1) * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+  HIP_OK(hipMemcpyAsync(packed_tokens, ws.meta.tok, (size_t)B * L * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+  return RLHF_OK;
+}
+
+int rlhf_policy_backward_workspace_bytes(const rlhf_handle* h, int32_t T, size_t* out) {
+  if (!h || !out) return fail(RLHF_EINVAL, "null argument");
+  if (T <= 0) return fail(RLHF_EINVAL, "row count must be positive");
+  size_t a = 0, b = 0, c = 0;
+  int rc = rlhf_head_backward_workspace_bytes(h, T, &a);
+  if (rc) return rc;
+  if (h->cfg.n_layers > 0) {
+    rc = rlhf_mlp_backward_workspace_bytes(h, T, &b);
+    if (rc) return rc;
+    rc = rlhf_attention_branch_backward_workspace_bytes(h, T, &c);
+    if (rc) return rc;
+  }
+  *out = std::max(a, std::max(b, c)) + (size_t)4 * T * h->cfg.d_model * sizeof(float) + 2048;
+  return RLHF_OK;
+}
+
+int rlhf_policy_backward(rlhf_handle* h, const float* x_keep, int64_t x_keep_layer_stride, const int32_t* cu_seqlens,
+                         const int32_t* packed_tokens, int32_t B, int32_t T, int32_t max_len, const int32_t* targets,
+                         const float* d_logprobs, const float* d_values, float temperature, float grad_scale,
+                         const rlhf_grads* g, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!h || !g) return fail(RLHF_EINVAL, "null argument");
+  const rlhf_model_config& c = h->cfg;
+  if (T <= 0 || B <= 0) return fail(RLHF_EINVAL, "rows and batch must be positive");
+  if (!x_keep || !cu_seqlens || !packed_tokens || !workspace || !g->embed_in)
+    return fail(RLHF_EINVAL, "null pointer argument");
+  if (x_keep_layer_stride < (int64_t)T * c.d_model) return fail(RLHF_EINVAL, "x_keep_layer_stride smaller than T * d_model");
+  float* const* per_layer[12] = {g->ln1_g, g->ln1_b, g->ln2_g, g->ln2_b, g->w_qkv, g->b_qkv,
+                                 g->w_o,   g->b_o,   g->w_fc1, g->b_fc1, g->w_fc2, g->b_fc2};
+  for (auto p : per_layer) {
+    if (c.n_layers > 0 && !p) return fail(RLHF_EINVAL, "null per-layer gradient pointer array");
+    for (int l = 0; l < c.n_layers; ++l)
+      if (!p[l]) return fail(RLHF_EINVAL, "null per-layer gradient pointer");
+  }
+  if (c.d_model > 8192) return fail(RLHF_EUNSUPPORTED, "d_model > 8192");
+  size_t need = 0;
+  int rc = rlhf_policy_backward_workspace_bytes(h, T, &need);
+  if (rc) return rc;
+  if (workspace_bytes < need) return fail(RLHF_ENOMEM, "workspace too small for rlhf_policy_backward");
+  hipStream_t s = (hipStream_t)stream;
+  const size_t n = (size_t)T * c.d_model;
+  char* base = (char*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
+  const size_t buf = (n * sizeof(float) + 255) & ~(size_t)255;
+  float* dx = (float*)base;                 // gradient of the residual stream at the current depth
+  float* dx_m = (float*)(base + buf);       // MLP branch term
+  float* dx_a = (float*)(base + 2 * buf);   // attention branch term
+  float* dx_n = (float*)(base + 3 * buf);   // their sum with dx: the gradient one layer down
+  char* sub = base + 4 * buf;
+  const size_t sub_bytes = workspace_bytes - (size_t)(sub - (char*)workspace);
+  rc = rlhf_head_backward(h, x_keep + (size_t)c.n_layers * x_keep_layer_stride, targets, d_logprobs, d_values, T,
+                          temperature, grad_scale, dx, g->lnf_g, g->lnf_b, g->embed_out, g->value_w, g->value_b, sub,
+                          sub_bytes, stream);
+  if (rc) return rc;
+  for (int l = c.n_layers - 1; l >= 0; --l) {
+    const float* xl = x_keep + (size_t)l * x_keep_layer_stride;
+    rc = rlhf_mlp_backward(h, l, xl, dx, T, dx_m, g->ln2_g[l], g->ln2_b[l], g->w_fc1[l], g->b_fc1[l], g->w_fc2[l],
+                           g->b_fc2[l], sub, sub_bytes, stream);
+    if (rc) return rc;
+    rc = rlhf_attention_branch_backward(h, l, xl, dx, cu_seqlens, B, T, max_len, dx_a, g->ln1_g[l], g->ln1_b[l],
+                                        g->w_qkv[l], g->b_qkv[l], g->w_o[l], g->b_o[l], sub, sub_bytes, stream);
+    if (rc) return rc;
+    LAUNCH("add3", launch_add3(dx, dx_a, dx_m, dx_n, n, s));
+    std::swap(dx, dx_n);
+  }
+  LAUNCH("embed_backward", launch_embed_backward(packed_tokens, dx, T, c.d_model, c.vocab, g->embed_in, s));
   return RLHF_OK;
 }
 

@@ -306,6 +306,10 @@ hipError_t launch_rope_inplace(int dtype, void* qkv, size_t ld, const int* cu, i
 // Rows of a [3*d, C] fp32 matrix from the fp16 path's reordered W_qkv row order back to the caller's.
 hipError_t launch_qkv_rows_to_caller_order(const float* in, float* out, int d, int hd, int r, int C, hipStream_t s);
 
+// out[v][:] = sum over packed rows t with tok[t] == v of dx[t][:], in increasing t; out is [V, d], d <= 8192.
+hipError_t launch_embed_backward(const int* tok, const float* dx, int T, int d, int V, float* out, hipStream_t s);
+hipError_t launch_add3(const float* a, const float* b, const float* c, float* out, size_t n, hipStream_t s);  // (a+b)+c
+
 hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s);
 // Same for a [rows, cols] matrix written with row stride dst_ld (elements).
 // fp16 copy of W_qkv and a bf16 copy of its bias with the rotary dims of every q and k head

@@ -403,7 +403,64 @@ __global__ void __launch_bounds__(256)
   out[c] = s;
 }
 
+// Gradient of the input embedding: out[v][:] = sum over packed rows t with tok[t] == v of dx[t][:], rows added
+// in increasing t (a fixed order: no atomics).  One block per vocabulary entry scans the token list 256 rows at a
+// time; a thread keeps up to 32 columns (d <= 8192) in registers.
+__global__ void __launch_bounds__(256)
+    embed_backward_kernel(const int* __restrict__ tok, const float* __restrict__ dx, int T, int d,
+                          float* __restrict__ out) {
+  __shared__ int hits[256];
+  const int v = blockIdx.x, tid = threadIdx.x;
+  float acc[32];
+#pragma unroll
+  for (int i = 0; i < 32; ++i) acc[i] = 0.f;
+  for (int t0 = 0; t0 < T; t0 += 256) {
+    const int t = t0 + tid;
+    const int match = (t < T && tok[t] == v) ? 1 : 0;
+    if (__syncthreads_or(match)) {
+      hits[tid] = match;
+      __syncthreads();
+      for (int i = 0; i < 256; ++i) {
+        if (!hits[i]) continue;
+        const float* row = dx + (size_t)(t0 + i) * d;
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+          const int c = tid + 256 * u;
+          if (c < d) acc[u] += row[c];
+        }
+      }
+      __syncthreads();
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 32; ++u) {
+    const int c = tid + 256 * u;
+    if (c < d) out[(size_t)v * d + c] = acc[u];
+  }
+}
+
+__global__ void __launch_bounds__(256)
+    add3_kernel(const float* __restrict__ a, const float* __restrict__ b, const float* __restrict__ c,
+                float* __restrict__ out, size_t n) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) out[i] = (a[i] + b[i]) + c[i];
+}
+
 }  // namespace
+
+hipError_t launch_embed_backward(const int* tok, const float* dx, int T, int d, int V, float* out, hipStream_t s) {
+  if (V <= 0) return hipSuccess;
+  if (d > 8192) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(embed_backward_kernel, dim3(V), dim3(256), 0, s, tok, dx, T, d, out);
+  return hipGetLastError();
+}
+hipError_t launch_add3(const float* a, const float* b, const float* c, float* out, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const int blocks = (int)std::min<size_t>((n + 255) / 256, 65536);
+  hipLaunchKernelGGL(add3_kernel, dim3(blocks), dim3(256), 0, s, a, b, c, out, n);
+  return hipGetLastError();
+}
 
 hipError_t launch_gelu(int dtype, const void* u, void* f, size_t n, hipStream_t s) {
   if (n == 0) return hipSuccess;

@@ -15,7 +15,8 @@ EXPORTS = (
     "rlhf_create", "rlhf_destroy", "rlhf_workspace_bytes", "rollout_generate", "score_sequences",
     "rlhf_debug_logits_rows", "rlhf_profile_enable", "rlhf_profile_read", "rlhf_last_rollout_phases",
     "rlhf_last_error", "rlhf_ppo_assemble_rewards", "rlhf_ppo_gae", "rlhf_ppo_whiten", "rlhf_ppo_loss", "rlhf_adamw_step",
-    "rlhf_head_backward", "rlhf_head_backward_workspace_bytes", "rlhf_mlp_backward", "rlhf_mlp_backward_workspace_bytes", "rlhf_attention_backward", "rlhf_attention_branch_backward", "rlhf_attention_branch_backward_workspace_bytes",
+    "rlhf_head_backward", "rlhf_head_backward_workspace_bytes", "rlhf_mlp_backward", "rlhf_mlp_backward_workspace_bytes", "rlhf_attention_backward", "rlhf_forward_keep", "rlhf_policy_backward", "rlhf_policy_backward_workspace_bytes",
+    "rlhf_attention_branch_backward", "rlhf_attention_branch_backward_workspace_bytes",
 )
 
 _PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -35,6 +36,12 @@ class _Weights(C.Structure):
     _fields_ = [("embed_in", C.c_void_p)] + [(n, C.POINTER(C.c_void_p)) for n in _PER_LAYER] + \
                [("lnf_g", C.c_void_p), ("lnf_b", C.c_void_p), ("embed_out", C.c_void_p), ("value_w", C.c_void_p),
                 ("value_b", C.c_float)]
+
+
+class _Grads(C.Structure):  # rlhf_grads: the mirror of rlhf_weights, float arrays
+    _fields_ = [("embed_in", C.c_void_p)] + [(n, C.POINTER(C.c_void_p)) for n in _PER_LAYER] + \
+               [("lnf_g", C.c_void_p), ("lnf_b", C.c_void_p), ("embed_out", C.c_void_p), ("value_w", C.c_void_p),
+                ("value_b", C.c_void_p)]
 
 
 _lib = None
@@ -73,6 +80,10 @@ def load_library():
     lib.rlhf_mlp_backward.argtypes = [vp, i32, vp, vp, i32] + [vp] * 7 + [vp, C.c_size_t, vp]
     lib.rlhf_attention_branch_backward_workspace_bytes.argtypes = [vp, i32, C.POINTER(C.c_size_t)]
     lib.rlhf_attention_branch_backward.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32] + [vp] * 7 + [vp, C.c_size_t, vp]
+    lib.rlhf_forward_keep.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.rlhf_policy_backward_workspace_bytes.argtypes = [vp, i32, C.POINTER(C.c_size_t)]
+    lib.rlhf_policy_backward.argtypes = [vp, vp, C.c_int64, vp, vp, i32, i32, i32, vp, vp, vp, C.c_float, C.c_float,
+                                         C.POINTER(_Grads), vp, C.c_size_t, vp]
     lib.rlhf_attention_backward.argtypes = [vp] * 5 + [i32] * 6 + [vp] * 5 + [vp]
     lib.rlhf_adamw_step.argtypes = [vp, vp, vp, vp, vp, u64, i32] + [C.c_double] * 6 + [vp]
     lib.rlhf_last_error.restype = C.c_char_p
@@ -276,6 +287,68 @@ class Policy:
                                                            cu.numel() - 1, T, max(int(max_len), 1),
                                                            *[res[k].data_ptr() for k in names], ws.data_ptr(),
                                                            ws.numel(), self._stream()))
+        return res
+
+    def forward_keep(self, tokens, mask):
+        """The scoring forward pass, keeping the residual stream at the input of every layer and after the last.
+        Returns (x_keep float32 [(n_layers + 1), B*L, d], cu_seqlens int32 [B+1], packed_tokens int32 [B*L])."""
+        torch = self.torch
+        t = self._to_dev(tokens, torch.int32)
+        m = self._to_dev(mask, torch.uint8)
+        B, L = t.shape
+        ws = self._workspace(self.workspace_bytes(B, 0, 0, L))
+        x_keep = torch.empty((self.cfg.n_layers + 1, B * L, self.cfg.d_model), dtype=torch.float32, device=self.device)
+        cu = torch.empty(B + 1, dtype=torch.int32, device=self.device)
+        ptok = torch.empty(B * L, dtype=torch.int32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(self.lib.rlhf_forward_keep(self._h, t.data_ptr(), m.data_ptr(), B, L, x_keep.data_ptr(), cu.data_ptr(),
+                                              ptok.data_ptr(), ws.data_ptr(), ws.numel(), self._stream()))
+        return x_keep, cu, ptok
+
+    def policy_backward(self, x_keep, cu_seqlens, packed_tokens, targets, d_logprobs, d_values, temperature,
+                        grad_scale=1.0, max_len=None):
+        """x_keep, cu_seqlens, packed_tokens from forward_keep; targets int32 [T], d_logprobs / d_values float32 [T]
+        over the T = cu_seqlens[-1] packed rows.  Returns {weight name: CUDA float32 gradient (times grad_scale)}."""
+        torch = self.torch
+        cfg = self.cfg
+        cu = self._to_dev(cu_seqlens, torch.int32)
+        T = int(cu[-1].item())
+        B = cu.numel() - 1
+        if max_len is None:
+            max_len = int((cu[1:] - cu[:-1]).max().item())
+        y = self._to_dev(targets, torch.int32)
+        gl = self._to_dev(d_logprobs, torch.float32)
+        gv = self._to_dev(d_values, torch.float32) if self._has_value else None
+        if y.numel() != T or gl.numel() != T or (gv is not None and gv.numel() != T):
+            raise RlhfError("policy_backward: targets, d_logprobs and d_values must have one entry per packed row")
+        d, F, V = cfg.d_model, cfg.d_ff, cfg.vocab
+        new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=self.device)
+        shapes = dict(ln1_g=(d,), ln1_b=(d,), ln2_g=(d,), ln2_b=(d,), w_qkv=(3 * d, d), b_qkv=(3 * d,), w_o=(d, d),
+                      b_o=(d,), w_fc1=(F, d), b_fc1=(F,), w_fc2=(d, F), b_fc2=(d,))
+        res = dict(embed_in=new(V, d), lnf_g=new(d), lnf_b=new(d), embed_out=new(V, d))
+        if self._has_value:
+            res.update(value_w=new(d), value_b=new(1))
+        for l in range(cfg.n_layers):
+            for n in _PER_LAYER:
+                res[f"layers.{l}.{n}"] = new(*shapes[n])
+        g = _Grads()
+        keep = []
+        for n in _PER_LAYER:
+            arr = (C.c_void_p * max(cfg.n_layers, 1))(*[res[f"layers.{l}.{n}"].data_ptr() for l in range(cfg.n_layers)])
+            keep.append(arr)
+            setattr(g, n, C.cast(arr, C.POINTER(C.c_void_p)))
+        for n in ("embed_in", "lnf_g", "lnf_b", "embed_out"):
+            setattr(g, n, res[n].data_ptr())
+        g.value_w = res["value_w"].data_ptr() if self._has_value else None
+        g.value_b = res["value_b"].data_ptr() if self._has_value else None
+        out = C.c_size_t()
+        _check(self.lib.rlhf_policy_backward_workspace_bytes(self._h, T, C.byref(out)))
+        ws = self._workspace(out.value)
+        with torch.cuda.device(self.device):
+            _check(self.lib.rlhf_policy_backward(self._h, x_keep.data_ptr(), x_keep.stride(0), cu.data_ptr(),
+                                                 packed_tokens.data_ptr(), B, T, max(int(max_len), 1), y.data_ptr(),
+                                                 gl.data_ptr(), gv.data_ptr() if gv is not None else None, temperature,
+                                                 grad_scale, C.byref(g), ws.data_ptr(), ws.numel(), self._stream()))
         return res
 
     def debug_logits_rows(self, tokens, mask, rows_bt):

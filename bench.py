@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="BASELINE config index 1..5 (default: the 2.8B target)")
     ap.add_argument("--batch", type=int, default=None, help="override the config's batch (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-update-leg", action="store_true",
+                    help="skip the PPO-update leg (forward keeping activations, backward, AdamW; ~10 s at config 4)")
     ap.add_argument("--extra-score-shapes", action="store_true",
                     help="also time score_sequences on the paper's other batch shapes: right-padded (B,638) and (B,2021)")
     a = ap.parse_args()
@@ -273,6 +275,49 @@ def main():
                                            "note": "first form: fp32 vector arithmetic, no matrix cores"}
         del qkvg, ab
 
+    # One PPO update pass over the rollout batch (outside the headline metric): the forward pass that keeps the
+    # layer inputs, the whole backward pass from synthetic loss gradients on the response positions, and AdamW over
+    # every weight.  Config 5 (6.9B) is skipped: weights, optimizer state and kept activations exceed one GPU.
+    update = None
+    if not a.no_update_leg and cfg.n_layers > 0 and cfg.dtype != "fp32" and a.config != 5:
+        toks_u, mask_u = r[0], r[3]
+        Lu = toks_u.shape[1]
+        mb = mask_u.bool()
+        bt = mb.nonzero()                                # packed order: by sequence, then position
+        bb, tt = bt[:, 0], bt[:, 1]
+        T_u = int(bt.shape[0])
+        t1 = torch.clamp(tt + 1, max=Lu - 1)
+        nxt = (tt + 1 < Lu) & mb[bb, t1] & (tt + 1 >= Lq)  # rows that predict a response token
+        tgt_u = torch.where(nxt, toks_u[bb, t1], torch.full_like(tt, -1, dtype=torch.int32)).to(torch.int32)
+        gl_u = torch.where(nxt, torch.randn(T_u, device="cuda", generator=g_hb) / (B * N), torch.zeros(T_u, device="cuda"))
+        gv_u = torch.where(nxt, torch.randn(T_u, device="cuda", generator=g_hb) / (B * N), torch.zeros(T_u, device="cuda"))
+        state = {}
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        for it in range(2):                              # one untimed pass, one timed
+            ev[0].record()
+            x_keep, cu_u, ptok_u = pol.forward_keep(toks_u, mask_u)
+            ev[1].record()
+            grads = pol.policy_backward(x_keep, cu_u, ptok_u, tgt_u, gl_u, gv_u, wl.temperature, grad_scale=64.0 * B * N)
+            ev[2].record()
+            for name, gten in grads.items():
+                if name not in state:
+                    wt = pol._dev[name] if name in pol._dev else torch.zeros(1, device="cuda")
+                    state[name] = (wt.float().reshape(gten.shape).contiguous(), torch.zeros_like(gten),
+                                   torch.zeros_like(gten))
+                p32, m1, m2 = state[name]
+                P.adamw_step(p32, gten, m1, m2, it + 1, grad_scale=64.0 * B * N,
+                             param_bf16=pol._dev[name] if name in pol._dev and pol._dev[name].dtype == torch.bfloat16 else None)
+            ev[3].record()
+            del x_keep, grads
+        torch.cuda.synchronize()
+        f_ms, b_ms, o_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), ev[2].elapsed_time(ev[3])
+        tot = f_ms + b_ms + o_ms
+        update = {"forward_keep_ms": f_ms, "policy_backward_ms": b_ms, "adamw_ms": o_ms, "total_ms": tot, "rows": T_u,
+                  "tflops": 3.0 * wc["score_flops"] / (tot * 1e-3) / 1e12,
+                  "note": "3 x the scoring pass's flops (forward + twice that for the gradients) over the time of one "
+                          "pass; the attention backward kernels are a first form without matrix cores"}
+        del state
+
     # The paper's other scoring shapes (reward-model batches of 638 tokens, long-context batches of 2021),
     # right-padded with true lengths uniform in [L/4, L]; outside the headline metric.
     extra = None
@@ -322,7 +367,7 @@ def main():
         "rescoring_tok_s_padded": B * (wl.query_len + N) / (score_ms * 1e-3),
         "score_mfma_frac": wc["score_flops"] / (score_ms * 1e-3) / MFMA_PEAK,
         "roofline": roof, "rooflines": rooflines, "kernels_ms": kern, "profiled_step_ms": tot,
-        "ppo_signals_ms": signals_ms, "adamw_ms_per_2p30_params": adamw_ms, "head_backward_ms": head_bwd_ms, "mlp_backward_ms_per_layer": mlp_bwd_ms, "attention_backward_ms_per_layer": attn_bwd_ms, "extra_score_shapes": extra,
+        "ppo_signals_ms": signals_ms, "adamw_ms_per_2p30_params": adamw_ms, "head_backward_ms": head_bwd_ms, "mlp_backward_ms_per_layer": mlp_bwd_ms, "attention_backward_ms_per_layer": attn_bwd_ms, "ppo_update": update, "extra_score_shapes": extra,
         "cpu_baseline": cpu, "setup_s": setup_s,
     }
     print(json.dumps(out))

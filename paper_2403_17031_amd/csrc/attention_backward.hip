@@ -28,14 +28,29 @@ __device__ __forceinline__ float dot_row(const float* __restrict__ a, const floa
   }
   return s;
 }
+// fp16 rows: the row's own vector sits in LDS as fp16 pairs (exact: the inputs are fp16; they take the first
+// half of the slot sized for floats), so that two products per instruction accumulate in fp32 (v_dot2_f32_f16).
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
 __device__ __forceinline__ float dot_row(const float* __restrict__ a, const half_t* __restrict__ row, int hd) {
+  const f16x2_t* ah = (const f16x2_t*)a;  // hd/2 pairs, written by stash_row
   float s = 0.f;
   for (int c = 0; c < hd; c += 8) {
     const f16x8_t v = *(const f16x8_t*)(row + c);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s = fmaf(a[c + e], (float)v[e], s);
+    for (int e = 0; e < 4; ++e) {
+      const f16x2_t x = {v[2 * e], v[2 * e + 1]};
+      s = __builtin_amdgcn_fdot2(x, ah[(c >> 1) + e], s, false);
+    }
   }
   return s;
+}
+// the row's own vector into its LDS slot, in the form dot_row reads
+__device__ __forceinline__ void stash_row(float* dst, const float* src, int hd, int lane) {
+  for (int e = lane; e < hd; e += 64) dst[e] = src[e];
+}
+__device__ __forceinline__ void stash_row(float* dst, const half_t* src, int hd, int lane) {
+  half_t* dh = (half_t*)dst;
+  for (int e = lane; e < hd; e += 64) dh[e] = src[e];
 }
 
 template <typename T>
@@ -71,10 +86,8 @@ __global__ void __launch_bounds__(256)
   float* gs = qs + hd;
   float* p = gs + hd;
   float* ds = p + max_len;
-  for (int e = lane; e < hd; e += 64) {
-    qs[e] = to_f32(q[t * ldq + col + e]);
-    gs[e] = to_f32(g[t * ldg + col + e]);
-  }
+  stash_row(qs, q + t * ldq + col, hd, lane);
+  stash_row(gs, g + t * ldg + col, hd, lane);
   __syncthreads();
   float mx = -INFINITY;
   for (int j = lane; j < nk; j += 64) {
@@ -164,10 +177,8 @@ __global__ void __launch_bounds__(256)
   float* vs = ks + hd;
   float* p = vs + hd;
   float* ds = p + max_len;
-  for (int e = lane; e < hd; e += 64) {
-    ks[e] = to_f32(k[t * ldq + col + e]);
-    vs[e] = to_f32(v[t * ldq + col + e]);
-  }
+  stash_row(ks, k + t * ldq + col, hd, lane);
+  stash_row(vs, v + t * ldq + col, hd, lane);
   __syncthreads();
   for (int ii = lane; ii < nq; ii += 64) {
     const size_t r = (size_t)(t + ii);

@@ -211,31 +211,34 @@ def main():
     # The backward pass through the output heads over the batch's B*N response positions (what the PPO
     # update differentiates): three products of 2*T*V*d flop each (logits, dL/dh, dL/dW).  Outside the
     # headline metric.
-    T_hb = B * N
+    bwd_legs = a.config != 5   # the 6.9B shape fills the GPU with weights and the rollout workspace alone
+    head_bwd_ms = None
     g_hb = torch.Generator(device="cuda").manual_seed(7)
-    x_hb = torch.randn(T_hb, cfg.d_model, device="cuda", generator=g_hb) * 2.0
-    y_hb = torch.randint(0, cfg.vocab, (T_hb,), device="cuda", generator=g_hb, dtype=torch.int32)
-    gl_hb = torch.randn(T_hb, device="cuda", generator=g_hb) / T_hb
-    gv_hb = torch.randn(T_hb, device="cuda", generator=g_hb) / T_hb
-    for i in range(1 + 2):
-        if i == 1:
-            e0.record()
-        hb = pol.head_backward(x_hb, y_hb, gl_hb, gv_hb, wl.temperature, grad_scale=64.0 * T_hb)
-    e1.record()
-    torch.cuda.synchronize()
-    head_bwd_ms = e0.elapsed_time(e1) / 2
-    ach = 3 * 2.0 * T_hb * cfg.vocab * cfg.d_model / (head_bwd_ms * 1e-3)
     hb_peak = MFMA_PEAK if cfg.dtype != "fp32" else 157.3e12
-    rooflines["head_backward"] = {"bound": "mfma", "achieved": ach / 1e12, "peak": hb_peak / 1e12, "unit": "TFLOP/s",
-                                  "frac": ach / hb_peak, "traffic": None, "avg_launch_ms": head_bwd_ms,
-                                  "rows": T_hb}
-    del x_hb, y_hb, gl_hb, gv_hb, hb
+    if bwd_legs:
+        T_hb = B * N
+        x_hb = torch.randn(T_hb, cfg.d_model, device="cuda", generator=g_hb) * 2.0
+        y_hb = torch.randint(0, cfg.vocab, (T_hb,), device="cuda", generator=g_hb, dtype=torch.int32)
+        gl_hb = torch.randn(T_hb, device="cuda", generator=g_hb) / T_hb
+        gv_hb = torch.randn(T_hb, device="cuda", generator=g_hb) / T_hb
+        for i in range(1 + 2):
+            if i == 1:
+                e0.record()
+            hb = pol.head_backward(x_hb, y_hb, gl_hb, gv_hb, wl.temperature, grad_scale=64.0 * T_hb)
+        e1.record()
+        torch.cuda.synchronize()
+        head_bwd_ms = e0.elapsed_time(e1) / 2
+        ach = 3 * 2.0 * T_hb * cfg.vocab * cfg.d_model / (head_bwd_ms * 1e-3)
+        rooflines["head_backward"] = {"bound": "mfma", "achieved": ach / 1e12, "peak": hb_peak / 1e12, "unit": "TFLOP/s",
+                                      "frac": ach / hb_peak, "traffic": None, "avg_launch_ms": head_bwd_ms,
+                                      "rows": T_hb}
+        del x_hb, y_hb, gl_hb, gv_hb, hb
 
     # The backward pass through one decoder layer's MLP branch over the batch's packed rows (the rows the
     # scoring pass runs over): forward recomputation (1 product) + four gradient products of 2*T*d*d_ff flop.
     # Outside the headline metric.
     mlp_bwd_ms = None
-    if cfg.n_layers > 0:
+    if cfg.n_layers > 0 and bwd_legs:
         T_mb = int(wc["real_score_tokens"])
         x_mb = torch.randn(T_mb, cfg.d_model, device="cuda", generator=g_hb) * 2.0
         g_mb = torch.randn(T_mb, cfg.d_model, device="cuda", generator=g_hb)
@@ -255,7 +258,7 @@ def main():
     # The backward pass through the packed causal attention of one layer over the same rows (sequence lengths
     # of the scoring pass): five contractions of 2*hd flop per (query, key <= query, head) pair.
     attn_bwd_ms = None
-    if cfg.n_layers > 0 and cfg.dtype != "fp32":
+    if cfg.n_layers > 0 and cfg.dtype != "fp32" and bwd_legs:
         n_sc = (n_true + lens).astype(np.int64)
         cu_ab = np.concatenate([[0], np.cumsum(n_sc)]).astype(np.int32)
         T_ab = int(cu_ab[-1])
@@ -279,7 +282,7 @@ def main():
     # layer inputs, the whole backward pass from synthetic loss gradients on the response positions, and AdamW over
     # every weight.  Config 5 (6.9B) is skipped: weights, optimizer state and kept activations exceed one GPU.
     update = None
-    if not a.no_update_leg and cfg.n_layers > 0 and cfg.dtype != "fp32" and a.config != 5:
+    if not a.no_update_leg and cfg.n_layers > 0 and cfg.dtype != "fp32" and bwd_legs:
         toks_u, mask_u = r[0], r[3]
         Lu = toks_u.shape[1]
         mb = mask_u.bool()

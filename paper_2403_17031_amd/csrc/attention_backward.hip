@@ -5,9 +5,9 @@
 //                       dQ_i = scale * sum_j dS_ij K_j; keeps lse_i and delta_i for the second kernel.
 //   attn_bwd_kv_kernel: for key row j -- the same P_ij and dS_ij for the queries i >= j of its
 //                       sequence (from lse_i, delta_i), dV_j = sum_i P_ij dO_i, dK_j = scale * sum_i dS_ij Q_i.
-// Dot products run with lanes over partner rows (each lane reads one partner row, 16 bytes at a
-// time, against this row's vector broadcast from LDS); the weighted row sums run with lanes over
-// the head's dims (partner rows read coalesced, one after the other).
+// Dot products (fp16): hd/8 neighbouring lanes share a partner row, 16 bytes each, against this row's own
+// vector kept in LDS; the weighted row sums run with lanes over pairs of the head's dims, partner rows one
+// after the other.  Every global read is a whole row segment.
 #include <algorithm>
 
 #include "common.h"
@@ -53,6 +53,58 @@ __device__ __forceinline__ void stash_row(float* dst, const half_t* src, int hd,
   for (int e = lane; e < hd; e += 64) dh[e] = src[e];
 }
 
+// outA[i] = fa . rowA_i and outB[i] = fb . rowB_i for i < count, rows ld apart (fa, fb: this row's vectors in LDS
+// as stash_row leaves them).  Float rows: one partner row per lane.
+__device__ __forceinline__ void dots2_rows(const float* fa, const float* fb, const float* rowsA, size_t ldA,
+                                           const float* rowsB, size_t ldB, int count, int hd, int lane, float* outA,
+                                           float* outB) {
+  for (int i = lane; i < count; i += 64) {
+    outA[i] = dot_row(fa, rowsA + (size_t)i * ldA, hd);
+    outB[i] = dot_row(fb, rowsB + (size_t)i * ldB, hd);
+  }
+}
+// fp16 rows: hd/8 neighbouring lanes share a partner row, 16 bytes each, so that a wave instruction reads whole
+// rows (64 / (hd/8) of them) instead of 64 scattered chunks; the lanes of a row then add their partial sums.
+__device__ __forceinline__ void dots2_rows(const float* fa, const float* fb, const half_t* rowsA, size_t ldA,
+                                           const half_t* rowsB, size_t ldB, int count, int hd, int lane, float* outA,
+                                           float* outB) {
+  const int cpr = hd >> 3, G = 64 / cpr;
+  const int grp = lane / cpr, part = lane - grp * cpr;
+  const bool active = grp < G;
+  const f16x2_t* ah = (const f16x2_t*)fa + 4 * part;
+  const f16x2_t* bh = (const f16x2_t*)fb + 4 * part;
+  f16x2_t a[4], b[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    a[e] = active ? ah[e] : (f16x2_t){0, 0};
+    b[e] = active ? bh[e] : (f16x2_t){0, 0};
+  }
+  for (int i0 = 0; i0 < count; i0 += G) {
+    const int i = i0 + grp;
+    float sa = 0.f, sb = 0.f;
+    if (active && i < count) {
+      const f16x8_t x = *(const f16x8_t*)(rowsA + (size_t)i * ldA + 8 * part);
+      const f16x8_t y = *(const f16x8_t*)(rowsB + (size_t)i * ldB + 8 * part);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sa = __builtin_amdgcn_fdot2((f16x2_t){x[2 * e], x[2 * e + 1]}, a[e], sa, false);
+        sb = __builtin_amdgcn_fdot2((f16x2_t){y[2 * e], y[2 * e + 1]}, b[e], sb, false);
+      }
+    }
+    for (int off = 1; off < cpr; off <<= 1) {  // lane `part` ends up with the sum over parts part .. cpr-1
+      const float oa = __shfl_down(sa, off, 64), ob = __shfl_down(sb, off, 64);
+      if (part + off < cpr) {
+        sa += oa;
+        sb += ob;
+      }
+    }
+    if (active && part == 0 && i < count) {
+      outA[i] = sa;
+      outB[i] = sb;
+    }
+  }
+}
+
 template <typename T>
 struct __attribute__((aligned(2 * sizeof(T)))) pair2 {  // two neighbouring elements, moved as one word
   T a, b;
@@ -89,24 +141,21 @@ __global__ void __launch_bounds__(256)
   stash_row(qs, q + t * ldq + col, hd, lane);
   stash_row(gs, g + t * ldg + col, hd, lane);
   __syncthreads();
+  // p[j] = q . k_j (raw), ds[j] = dO . v_j for the keys of the row
+  dots2_rows(qs, gs, k + (size_t)s0 * ldq + col, ldq, v + (size_t)s0 * ldq + col, ldq, nk, hd, lane, p, ds);
+  __syncthreads();
   float mx = -INFINITY;
-  for (int j = lane; j < nk; j += 64) {
-    const float s = dot_row(qs, k + (size_t)(s0 + j) * ldq + col, hd) * scale;
-    p[j] = s;
-    mx = fmaxf(mx, s);
-  }
+  for (int j = lane; j < nk; j += 64) mx = fmaxf(mx, p[j] * scale);
   mx = wave_max(mx);
   float sum = 0.f;
-  for (int j = lane; j < nk; j += 64) sum += __expf(p[j] - mx);
+  for (int j = lane; j < nk; j += 64) sum += __expf(p[j] * scale - mx);
   sum = wave_sum(sum);
   const float l = mx + __logf(sum);
   float dl = 0.f;
   for (int j = lane; j < nk; j += 64) {
-    const float pj = __expf(p[j] - l);
-    const float dp = dot_row(gs, v + (size_t)(s0 + j) * ldq + col, hd);
+    const float pj = __expf(p[j] * scale - l);
     p[j] = pj;
-    ds[j] = dp;
-    dl = fmaf(pj, dp, dl);
+    dl = fmaf(pj, ds[j], dl);
   }
   dl = wave_sum(dl);
   for (int j = lane; j < nk; j += 64) ds[j] = p[j] * (ds[j] - dl);
@@ -115,6 +164,7 @@ __global__ void __launch_bounds__(256)
     const T* kc = k + (size_t)s0 * ldq + col + e;
     float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
     int j = 0;
+#pragma unroll 4
     for (; j + 1 < nk; j += 2) {
       const pair2<T> x = *(const pair2<T>*)(kc + (size_t)j * ldq), y = *(const pair2<T>*)(kc + (size_t)(j + 1) * ldq);
       a0 = fmaf(ds[j], to_f32(x.a), a0);
@@ -138,6 +188,7 @@ __global__ void __launch_bounds__(256)
     for (int e = 2 * lane; e < hd; e += 128) {
       const T* vc = v + (size_t)s0 * ldq + col + e;
       float a0 = 0.f, a1 = 0.f;
+#pragma unroll 8
       for (int j = 0; j < nk; ++j) {
         const pair2<T> x = *(const pair2<T>*)(vc + (size_t)j * ldq);
         a0 = fmaf(p[j], to_f32(x.a), a0);
@@ -180,19 +231,21 @@ __global__ void __launch_bounds__(256)
   stash_row(ks, k + t * ldq + col, hd, lane);
   stash_row(vs, v + t * ldq + col, hd, lane);
   __syncthreads();
+  // p[ii] = k . q_i (raw), ds[ii] = v . dO_i for the queries that see this key
+  dots2_rows(ks, vs, q + (size_t)t * ldq + col, ldq, g + (size_t)t * ldg + col, ldg, nq, hd, lane, p, ds);
+  __syncthreads();
   for (int ii = lane; ii < nq; ii += 64) {
     const size_t r = (size_t)(t + ii);
-    const float s = dot_row(ks, q + r * ldq + col, hd) * scale;
-    const float pr = __expf(s - lse[r * H + h]);
-    const float dp = dot_row(vs, g + r * ldg + col, hd);
+    const float pr = __expf(p[ii] * scale - lse[r * H + h]);
     p[ii] = pr;
-    ds[ii] = pr * (dp - delta[r * H + h]);
+    ds[ii] = pr * (ds[ii] - delta[r * H + h]);
   }
   __syncthreads();
   for (int e = 2 * lane; e < hd; e += 128) {
     const T* gc = g + (size_t)t * ldg + col + e;
     const T* qc = q + (size_t)t * ldq + col + e;
     float av0 = 0.f, av1 = 0.f, ak0 = 0.f, ak1 = 0.f;
+#pragma unroll 8
     for (int ii = 0; ii < nq; ++ii) {
       const pair2<T> x = *(const pair2<T>*)(gc + (size_t)ii * ldg), y = *(const pair2<T>*)(qc + (size_t)ii * ldq);
       av0 = fmaf(p[ii], to_f32(x.a), av0);

@@ -265,6 +265,150 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+// Matrix-core form of the dK / dV kernel (fp16).  A block owns 128 keys of one (sequence, head), a wave 32 of them,
+// one per lane pair; their K and V rows stay in registers as MFMA operands.  Tiles of 64 queries (rows i0 .. i0+63
+// of the sequence, from the key tile's own position to the end) go through LDS twice over: row-major (Q, dO) as
+// the first operand of S = Q K^T and dP = dO V^T, whose accumulators hold, for the lane's key, the tile's queries
+// as rows; and transposed (Q^T, dO^T, columns in the order the accumulator rows map to operand slots) as the first
+// operand of dK^T += Q^T dS and dV^T += dO^T P.  P = exp(S scale - lse_i) needs no running maximum: lse_i and
+// delta_i come from the query-side kernel.
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+template <int HD>
+__global__ void __launch_bounds__(256, 1)
+    attn_bwd_kv_mfma(const half_t* __restrict__ q, const half_t* __restrict__ k, const half_t* __restrict__ v,
+                     const half_t* __restrict__ g, const int* __restrict__ cu, int Tn, int H, float scale,
+                     const float* __restrict__ lse, const float* __restrict__ delta, half_t* __restrict__ dk,
+                     half_t* __restrict__ dv, size_t ldq, size_t ldg, size_t ldo) {
+  constexpr int NKS = HD / 16, NDT = (HD + 31) / 32, RS = HD + 8, TS = 64 + 8;
+  __shared__ __attribute__((aligned(16))) uint16_t Qs[64 * RS];
+  __shared__ __attribute__((aligned(16))) uint16_t Gs[64 * RS];
+  __shared__ __attribute__((aligned(16))) uint16_t Qt[NDT * 32 * TS];
+  __shared__ __attribute__((aligned(16))) uint16_t Gt[NDT * 32 * TS];
+  __shared__ float lse_s[64], del_s[64];
+  const int b = blockIdx.z, h = blockIdx.y, k0 = blockIdx.x * 128;
+  const int s0 = min(max(cu[b], 0), Tn), n = min(cu[b + 1], Tn) - s0;  // clamped: a malformed cu must not lead out of bounds
+  if (k0 >= n) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+  const size_t col = (size_t)h * HD;
+  const int kj = k0 + wave * 32 + l32;  // this lane's key
+  const int kjc = min(kj, n - 1);
+  f16x8_t kf[NKS], vf[NKS];
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) {
+    kf[ks] = *(const f16x8_t*)(k + (size_t)(s0 + kjc) * ldq + col + 16 * ks + 8 * half);
+    vf[ks] = *(const f16x8_t*)(v + (size_t)(s0 + kjc) * ldq + col + 16 * ks + 8 * half);
+  }
+  for (int c = tid; c < (NDT * 32 - HD) * TS; c += 256) {  // rows of the transposed tiles past HD stay zero
+    Qt[HD * TS + c] = 0;
+    Gt[HD * TS + c] = 0;
+  }
+  f32x16_t dvT[NDT], dkT[NDT];
+#pragma unroll
+  for (int t = 0; t < NDT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      dvT[t][e] = 0.f;
+      dkT[t][e] = 0.f;
+    }
+  const float scale_log2e = scale * 1.4426950408889634f;
+  const int kw0 = k0 + wave * 32;  // first key of the wave
+  constexpr int CPR = HD / 8;
+  for (int i0 = k0 & ~63; i0 < n; i0 += 64) {
+    __syncthreads();  // every wave is done with the previous tile
+    for (int c = tid; c < 64 * CPR; c += 256) {  // row-major images
+      const int r = c / CPR, ch = c - r * CPR;
+      const size_t row = (size_t)(s0 + min(i0 + r, n - 1));
+      *(u32x4_t*)(Qs + r * RS + ch * 8) = *(const u32x4_t*)(q + row * ldq + col + ch * 8);
+      *(u32x4_t*)(Gs + r * RS + ch * 8) = *(const u32x4_t*)(g + row * ldg + col + ch * 8);
+    }
+    for (int c = tid; c < 16 * CPR; c += 256) {  // transposed images: 4 queries x 8 dims per item
+      const int ch = c / 16, g4 = c - ch * 16;
+      const int kk = (4 * g4) & 15;
+      const int colp = ((4 * g4) & ~15) + 8 * ((kk >> 2) & 1) + 4 * (kk >> 3);
+      f16x8_t qv[4], gv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const size_t row = (size_t)(s0 + min(i0 + 4 * g4 + u, n - 1));
+        qv[u] = *(const f16x8_t*)(q + row * ldq + col + ch * 8);
+        gv[u] = *(const f16x8_t*)(g + row * ldg + col + ch * 8);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const f16x4_t wq = {qv[0][e], qv[1][e], qv[2][e], qv[3][e]};
+        const f16x4_t wg = {gv[0][e], gv[1][e], gv[2][e], gv[3][e]};
+        *(f16x4_t*)((half_t*)Qt + (ch * 8 + e) * TS + colp) = wq;
+        *(f16x4_t*)((half_t*)Gt + (ch * 8 + e) * TS + colp) = wg;
+      }
+    }
+    if (tid < 64) {
+      const size_t row = (size_t)(s0 + min(i0 + tid, n - 1));
+      lse_s[tid] = lse[row * H + h] * 1.4426950408889634f;
+      del_s[tid] = delta[row * H + h];
+    }
+    __syncthreads();
+    if (i0 + 63 < kw0) continue;  // every query of this tile comes before every key of this wave
+    f16x8_t pf[4], df[4];  // P and dS of the tile for this lane's key, as second operands of the 16-query steps
+#pragma unroll
+    for (int qf2 = 0; qf2 < 2; ++qf2) {
+      f32x16_t st, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        st[e] = 0.f;
+        dp[e] = 0.f;
+      }
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const f16x8_t qa = *(const f16x8_t*)(Qs + (qf2 * 32 + l32) * RS + 16 * ks + 8 * half);
+        const f16x8_t ga = *(const f16x8_t*)(Gs + (qf2 * 32 + l32) * RS + 16 * ks + 8 * half);
+        st = __builtin_amdgcn_mfma_f32_32x32x16_f16(qa, kf[ks], st, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_f16(ga, vf[ks], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = qf2 * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+        const int i = i0 + row;
+        const bool ok = i >= kj && i < n && kj < n;
+        const float pr = ok ? __builtin_amdgcn_exp2f(fmaf(st[e], scale_log2e, -lse_s[row])) : 0.f;
+        pf[qf2 * 2 + (e >> 3)][e & 7] = (half_t)pr;
+        df[qf2 * 2 + (e >> 3)][e & 7] = (half_t)(pr * (dp[e] - del_s[row]));
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < NDT; ++t) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const f16x8_t ga = *(const f16x8_t*)(Gt + (t * 32 + l32) * TS + 16 * c + 8 * half);
+        const f16x8_t qa = *(const f16x8_t*)(Qt + (t * 32 + l32) * TS + 16 * c + 8 * half);
+        dvT[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ga, pf[c], dvT[t], 0, 0, 0);
+        dkT[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(qa, df[c], dkT[t], 0, 0, 0);
+      }
+    }
+  }
+  if (kj < n) {
+    half_t* dvr = dv + (size_t)(s0 + kj) * ldo + col;
+    half_t* dkr = dk + (size_t)(s0 + kj) * ldo + col;
+#pragma unroll
+    for (int t = 0; t < NDT; ++t)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int dd = 32 * t + 8 * g4 + 4 * half;
+        if (dd < HD) {  // HD is a multiple of 4: the 4 dims are in range together
+          f16x4_t a, c2;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            a[u] = from_f32<half_t>(dvT[t][4 * g4 + u]);
+            c2[u] = from_f32<half_t>(dkT[t][4 * g4 + u] * scale);
+          }
+          *(f16x4_t*)(dvr + dd) = a;
+          *(f16x4_t*)(dkr + dd) = c2;
+        }
+      }
+  }
+}
+
 // Rotary turn of the q and k sections of a [T, 3*d] matrix (sections q | k | v, heads of hd, the first
 // r dims of a head rotary), in place, by the row's position in its sequence (row - cu[sequence]);
 // dir = +1 turns forward, -1 back (the transpose of the forward turn: what a gradient takes).
@@ -356,6 +500,18 @@ hipError_t launch_attention_backward(int dtype, const void* q, const void* k, co
     hipLaunchKernelGGL(attn_bwd_q_kernel<half_t>, grid, dim3(256), sh, s, (const half_t*)q, (const half_t*)k,
                        (const half_t*)v, (const half_t*)g, cu, B, Tn, H, hd, scale, max_len, lse, delta, (half_t*)dq,
                        ld_qkv, ld_g, ld_out, (half_t*)o, ld_o);
+    if (hd == 64 || hd == 80 || hd == 128) {  // the model family's head sizes: matrix-core form of the key-side kernel
+      dim3 kgrid((max_len + 127) / 128, H, B);
+#define RLHF_KV_MFMA(HD_)                                                                                       \
+  hipLaunchKernelGGL(attn_bwd_kv_mfma<HD_>, kgrid, dim3(256), 0, s, (const half_t*)q, (const half_t*)k,         \
+                     (const half_t*)v, (const half_t*)g, cu, Tn, H, scale, lse, delta, (half_t*)dk, (half_t*)dv, \
+                     ld_qkv, ld_g, ld_out)
+      if (hd == 64) RLHF_KV_MFMA(64);
+      else if (hd == 80) RLHF_KV_MFMA(80);
+      else RLHF_KV_MFMA(128);
+#undef RLHF_KV_MFMA
+      return hipGetLastError();
+    }
     hipLaunchKernelGGL(attn_bwd_kv_kernel<half_t>, grid, dim3(256), sh, s, (const half_t*)q, (const half_t*)k,
                        (const half_t*)v, (const half_t*)g, cu, B, Tn, H, hd, scale, max_len, lse, delta, (half_t*)dk,
                        (half_t*)dv, ld_qkv, ld_g, ld_out);

@@ -274,8 +274,7 @@ def main():
         ach = 5 * 2.0 * cfg.d_model * float((n_sc * (n_sc + 1) // 2).sum()) / (attn_bwd_ms * 1e-3)
         rooflines["attention_backward"] = {"bound": "mfma", "achieved": ach / 1e12, "peak": MFMA_PEAK / 1e12,
                                            "unit": "TFLOP/s", "frac": ach / MFMA_PEAK, "traffic": None,
-                                           "avg_launch_ms": attn_bwd_ms, "rows": T_ab,
-                                           "note": "first form: fp32 vector arithmetic, no matrix cores"}
+                                           "avg_launch_ms": attn_bwd_ms, "rows": T_ab}
         del qkvg, ab
 
     # One PPO update pass over the rollout batch (outside the headline metric): the forward pass that keeps the
@@ -317,8 +316,7 @@ def main():
         tot = f_ms + b_ms + o_ms
         update = {"forward_keep_ms": f_ms, "policy_backward_ms": b_ms, "adamw_ms": o_ms, "total_ms": tot, "rows": T_u,
                   "tflops": 3.0 * wc["score_flops"] / (tot * 1e-3) / 1e12,
-                  "note": "3 x the scoring pass's flops (forward + twice that for the gradients) over the time of one "
-                          "pass; the attention backward kernels are a first form without matrix cores"}
+                  "note": "3 x the scoring pass's flops (forward + twice that for the gradients) over the time of one pass"}
         del state
 
     # The paper's other scoring shapes (reward-model batches of 638 tokens, long-context batches of 2021),

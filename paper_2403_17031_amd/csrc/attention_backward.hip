@@ -409,6 +409,214 @@ __global__ void __launch_bounds__(256, 1)
   }
 }
 
+// Matrix-core form of the query-side kernel (fp16).  A block owns 128 queries of one (sequence, head), a wave 32,
+// whose Q and dO rows stay in registers as second operands; tiles of 64 keys go through LDS row-major (K, V) and
+// transposed (K^T, V^T).  Pass 1 is the forward pass (S^T = K Q^T, running maximum and sum, O^T += V^T P^T): it
+// yields O, lse_i and delta_i = dO_i . O_i.  Pass 2 walks the key tiles again: P^T = exp(S^T scale - lse_i),
+// dP^T = V dO^T, dS^T = P^T (dP^T - delta_i), dQ^T += K^T dS^T.
+template <int HD>
+__global__ void __launch_bounds__(256, 1)
+    attn_bwd_q_mfma(const half_t* __restrict__ q, const half_t* __restrict__ k, const half_t* __restrict__ v,
+                    const half_t* __restrict__ g, const int* __restrict__ cu, int Tn, int H, float scale,
+                    float* __restrict__ lse, float* __restrict__ delta, half_t* __restrict__ dq, size_t ldq, size_t ldg,
+                    size_t ldo, half_t* __restrict__ o_out, size_t ldoo) {
+  constexpr int NKS = HD / 16, NDT = (HD + 31) / 32, RS = HD + 8, TS = 64 + 8, CPR = HD / 8;
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * RS];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[64 * RS];
+  __shared__ __attribute__((aligned(16))) uint16_t Kt[NDT * 32 * TS];
+  __shared__ __attribute__((aligned(16))) uint16_t Vt[NDT * 32 * TS];
+  const int b = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * 128;
+  const int s0 = min(max(cu[b], 0), Tn), n = min(cu[b + 1], Tn) - s0;
+  if (q0 >= n) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+  const size_t col = (size_t)h * HD;
+  const int qi = q0 + wave * 32 + l32;  // this lane's query (two lanes per query: half 0 / 1)
+  const int qic = min(qi, n - 1);
+  f16x8_t qf[NKS], gf[NKS];
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) {
+    qf[ks] = *(const f16x8_t*)(q + (size_t)(s0 + qic) * ldq + col + 16 * ks + 8 * half);
+    gf[ks] = *(const f16x8_t*)(g + (size_t)(s0 + qic) * ldg + col + 16 * ks + 8 * half);
+  }
+  for (int c = tid; c < (NDT * 32 - HD) * TS; c += 256) {
+    Kt[HD * TS + c] = 0;
+    Vt[HD * TS + c] = 0;
+  }
+  const int q_hi = min(q0 + 128, n) - 1, wq_lo = q0 + wave * 32;
+  const float scale_log2e = scale * 1.4426950408889634f;
+  auto load_tiles = [&](int k0) {
+    __syncthreads();  // every wave is done with the previous tile
+    for (int c = tid; c < 64 * CPR; c += 256) {
+      const int r = c / CPR, ch = c - r * CPR;
+      const size_t row = (size_t)(s0 + min(k0 + r, n - 1));
+      *(u32x4_t*)(Ks + r * RS + ch * 8) = *(const u32x4_t*)(k + row * ldq + col + ch * 8);
+      *(u32x4_t*)(Vs + r * RS + ch * 8) = *(const u32x4_t*)(v + row * ldq + col + ch * 8);
+    }
+    for (int c = tid; c < 16 * CPR; c += 256) {
+      const int ch = c / 16, g4 = c - ch * 16;
+      const int kk = (4 * g4) & 15;
+      const int colp = ((4 * g4) & ~15) + 8 * ((kk >> 2) & 1) + 4 * (kk >> 3);
+      f16x8_t kv[4], vv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const size_t row = (size_t)(s0 + min(k0 + 4 * g4 + u, n - 1));
+        kv[u] = *(const f16x8_t*)(k + row * ldq + col + ch * 8);
+        vv[u] = *(const f16x8_t*)(v + row * ldq + col + ch * 8);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const f16x4_t wk = {kv[0][e], kv[1][e], kv[2][e], kv[3][e]};
+        const f16x4_t wv = {vv[0][e], vv[1][e], vv[2][e], vv[3][e]};
+        *(f16x4_t*)((half_t*)Kt + (ch * 8 + e) * TS + colp) = wk;
+        *(f16x4_t*)((half_t*)Vt + (ch * 8 + e) * TS + colp) = wv;
+      }
+    }
+    __syncthreads();
+  };
+  auto scores = [&](f32x16_t* st) {  // S^T of the tile for this lane's query: two fragments of 32 keys
+#pragma unroll
+    for (int kf = 0; kf < 2; ++kf) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) st[kf][e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const f16x8_t ka = *(const f16x8_t*)(Ks + (kf * 32 + l32) * RS + 16 * ks + 8 * half);
+        st[kf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka, qf[ks], st[kf], 0, 0, 0);
+      }
+    }
+  };
+  // ---- pass 1: the forward pass
+  f32x16_t acc[NDT];
+#pragma unroll
+  for (int t = 0; t < NDT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  for (int k0 = 0; k0 <= q_hi; k0 += 64) {
+    load_tiles(k0);
+    if (k0 > wq_lo + 31) continue;  // every key of this tile is in the future of this wave's queries
+    f32x16_t st[2];
+    scores(st);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kf = 0; kf < 2; ++kf)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int kj = k0 + kf * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+        if (kj > qi || kj >= n) st[kf][e] = -INFINITY;
+        mx = fmaxf(mx, st[kf][e]);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx * scale_log2e);  // finite: key 0 is visible to every query
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    float psum = 0.f;
+    f16x8_t pf[4];
+#pragma unroll
+    for (int kf = 0; kf < 2; ++kf)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(st[kf][e], scale_log2e, -m_new));
+        psum += p;
+        pf[kf * 2 + (e >> 3)][e & 7] = (half_t)p;
+      }
+    l_run = l_run * alpha + psum;
+#pragma unroll
+    for (int t = 0; t < NDT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[t][e] *= alpha;
+#pragma unroll
+    for (int t = 0; t < NDT; ++t)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const f16x8_t va = *(const f16x8_t*)(Vt + (t * 32 + l32) * TS + 16 * c + 8 * half);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pf[c], acc[t], 0, 0, 0);
+      }
+  }
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.0f / l_tot;
+  const float lse2 = m_run + __builtin_amdgcn_logf(l_tot);  // log2 of the row's sum of exponentials
+  // O_i (optional output) and delta_i = dO_i . O_i: this lane holds 4-dim groups of its query's output
+  float dl = 0.f;
+  {
+    const half_t* grow = g + (size_t)(s0 + qic) * ldg + col;
+#pragma unroll
+    for (int t = 0; t < NDT; ++t)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int dd = 32 * t + 8 * g4 + 4 * half;
+        if (dd < HD) {
+          const f16x4_t gv = *(const f16x4_t*)(grow + dd);
+          f16x4_t ov;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float x = acc[t][4 * g4 + u] * inv;
+            dl = fmaf(x, (float)gv[u], dl);
+            ov[u] = from_f32<half_t>(x);
+          }
+          if (o_out && qi < n) *(f16x4_t*)(o_out + (size_t)(s0 + qi) * ldoo + col + dd) = ov;
+        }
+      }
+  }
+  dl += __shfl_xor(dl, 32, 64);
+  if (qi < n && half == 0) {
+    lse[(size_t)(s0 + qi) * H + h] = lse2 * 0.6931471805599453f;  // natural logarithm, as the key-side kernels read it
+    delta[(size_t)(s0 + qi) * H + h] = dl;
+  }
+  // ---- pass 2: dQ^T += K^T dS^T over the same key tiles
+#pragma unroll
+  for (int t = 0; t < NDT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+  for (int k0 = 0; k0 <= q_hi; k0 += 64) {
+    load_tiles(k0);
+    if (k0 > wq_lo + 31) continue;
+    f32x16_t st[2];
+    scores(st);
+    f16x8_t df[4];
+#pragma unroll
+    for (int kf = 0; kf < 2; ++kf) {
+      f32x16_t dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dp[e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const f16x8_t va = *(const f16x8_t*)(Vs + (kf * 32 + l32) * RS + 16 * ks + 8 * half);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, gf[ks], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int kj = k0 + kf * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+        const bool ok = kj <= qi && kj < n;
+        const float pr = ok ? __builtin_amdgcn_exp2f(fmaf(st[kf][e], scale_log2e, -lse2)) : 0.f;
+        df[kf * 2 + (e >> 3)][e & 7] = (half_t)(pr * (dp[e] - dl));
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < NDT; ++t)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const f16x8_t ka = *(const f16x8_t*)(Kt + (t * 32 + l32) * TS + 16 * c + 8 * half);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka, df[c], acc[t], 0, 0, 0);
+      }
+  }
+  if (qi < n) {
+    half_t* drow = dq + (size_t)(s0 + qi) * ldo + col;
+#pragma unroll
+    for (int t = 0; t < NDT; ++t)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int dd = 32 * t + 8 * g4 + 4 * half;
+        if (dd < HD) {
+          f16x4_t a;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) a[u] = from_f32<half_t>(acc[t][4 * g4 + u] * scale);
+          *(f16x4_t*)(drow + dd) = a;
+        }
+      }
+  }
+}
+
 // Rotary turn of the q and k sections of a [T, 3*d] matrix (sections q | k | v, heads of hd, the first
 // r dims of a head rotary), in place, by the row's position in its sequence (row - cu[sequence]);
 // dir = +1 turns forward, -1 back (the transpose of the forward turn: what a gradient takes).
@@ -497,21 +705,24 @@ hipError_t launch_attention_backward(int dtype, const void* q, const void* k, co
       (void)hipFuncSetAttribute((const void*)attn_bwd_q_kernel<half_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
       (void)hipFuncSetAttribute((const void*)attn_bwd_kv_kernel<half_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
     }
+    if (hd == 64 || hd == 80 || hd == 128) {  // the model family's head sizes: matrix-core forms of both kernels
+      dim3 mgrid((max_len + 127) / 128, H, B);
+#define RLHF_BWD_MFMA(HD_)                                                                                      \
+  hipLaunchKernelGGL(attn_bwd_q_mfma<HD_>, mgrid, dim3(256), 0, s, (const half_t*)q, (const half_t*)k,          \
+                     (const half_t*)v, (const half_t*)g, cu, Tn, H, scale, lse, delta, (half_t*)dq, ld_qkv,     \
+                     ld_g, ld_out, (half_t*)o, ld_o);                                                           \
+  hipLaunchKernelGGL(attn_bwd_kv_mfma<HD_>, mgrid, dim3(256), 0, s, (const half_t*)q, (const half_t*)k,         \
+                     (const half_t*)v, (const half_t*)g, cu, Tn, H, scale, lse, delta, (half_t*)dk, (half_t*)dv, \
+                     ld_qkv, ld_g, ld_out)
+      if (hd == 64) { RLHF_BWD_MFMA(64); }
+      else if (hd == 80) { RLHF_BWD_MFMA(80); }
+      else { RLHF_BWD_MFMA(128); }
+#undef RLHF_BWD_MFMA
+      return hipGetLastError();
+    }
     hipLaunchKernelGGL(attn_bwd_q_kernel<half_t>, grid, dim3(256), sh, s, (const half_t*)q, (const half_t*)k,
                        (const half_t*)v, (const half_t*)g, cu, B, Tn, H, hd, scale, max_len, lse, delta, (half_t*)dq,
                        ld_qkv, ld_g, ld_out, (half_t*)o, ld_o);
-    if (hd == 64 || hd == 80 || hd == 128) {  // the model family's head sizes: matrix-core form of the key-side kernel
-      dim3 kgrid((max_len + 127) / 128, H, B);
-#define RLHF_KV_MFMA(HD_)                                                                                       \
-  hipLaunchKernelGGL(attn_bwd_kv_mfma<HD_>, kgrid, dim3(256), 0, s, (const half_t*)q, (const half_t*)k,         \
-                     (const half_t*)v, (const half_t*)g, cu, Tn, H, scale, lse, delta, (half_t*)dk, (half_t*)dv, \
-                     ld_qkv, ld_g, ld_out)
-      if (hd == 64) RLHF_KV_MFMA(64);
-      else if (hd == 80) RLHF_KV_MFMA(80);
-      else RLHF_KV_MFMA(128);
-#undef RLHF_KV_MFMA
-      return hipGetLastError();
-    }
     hipLaunchKernelGGL(attn_bwd_kv_kernel<half_t>, grid, dim3(256), sh, s, (const half_t*)q, (const half_t*)k,
                        (const half_t*)v, (const half_t*)g, cu, B, Tn, H, hd, scale, max_len, lse, delta, (half_t*)dk,
                        (half_t*)dv, ld_qkv, ld_g, ld_out);

@@ -1,5 +1,7 @@
 // Backward pass through packed causal softmax attention: dQ, dK, dV from Q, K, V and dO.
-// First form: one wave per (row, head), no matrix cores, every sum in a fixed order (no atomics).
+// Two kernels, query side and key side, every sum in a fixed order (no atomics).  For fp16 and the model
+// family's head sizes the matrix-core kernels further down run (attn_bwd_q_mfma, attn_bwd_kv_mfma); the first
+// form, kept for the other head sizes and the fp32 check mode, is one wave per (row, head) on the vector units:
 //   attn_bwd_q_kernel : for query row i -- scores against keys j <= i, their log-sum-exp, P_ij,
 //                       dP_ij = dO_i . V_j, delta_i = sum_j P_ij dP_ij, dS_ij = P_ij (dP_ij - delta_i),
 //                       dQ_i = scale * sum_j dS_ij K_j; keeps lse_i and delta_i for the second kernel.

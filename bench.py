@@ -313,9 +313,9 @@ def main():
             del x_keep, grads
         torch.cuda.synchronize()
         f_ms, b_ms, o_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), ev[2].elapsed_time(ev[3])
-        tot = f_ms + b_ms + o_ms
-        update = {"forward_keep_ms": f_ms, "policy_backward_ms": b_ms, "adamw_ms": o_ms, "total_ms": tot, "rows": T_u,
-                  "tflops": 3.0 * wc["score_flops"] / (tot * 1e-3) / 1e12,
+        upd_ms = f_ms + b_ms + o_ms
+        update = {"forward_keep_ms": f_ms, "policy_backward_ms": b_ms, "adamw_ms": o_ms, "total_ms": upd_ms, "rows": T_u,
+                  "tflops": 3.0 * wc["score_flops"] / (upd_ms * 1e-3) / 1e12,
                   "note": "3 x the scoring pass's flops (forward + twice that for the gradients) over the time of one pass"}
         del state
 

@@ -1073,7 +1073,7 @@ int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_
   p.pos = m.len;
   p.rowid = nullptr;
   for (int t = 0; t + 1 < N; ++t) {
-    LAUNCH("embed_rows", launch_embed_rows(dt, ws.cur_tok, B, h->w.embed_in, d, ws.acts.x, s));
+    LAUNCH("embed_rows", launch_embed_rows(dt, ws.cur_tok, B, h->w.embed_in, d, c.vocab, ws.acts.x, s));
     p.pos_add = t;
     p.ctx_add = t + 1;
     rc = run_layers(h, ws.acts, p, s);

@@ -160,7 +160,7 @@ hipError_t launch_pack_embed(int dtype, const int32_t* tokens, int B, int L, con
 // Decode step: x[b, :] = embed[cur_tok[b], :] for b < B.
 hipError_t launch_gather_rows(const void* in, const int* src, int src_add, int rows, size_t row_bytes, void* out,
                               hipStream_t s);
-hipError_t launch_embed_rows(int dtype, const int32_t* tok, int B, const void* embed, int d, float* x,
+hipError_t launch_embed_rows(int dtype, const int32_t* tok, int B, const void* embed, int d, int vocab, float* x,
                              hipStream_t s);
 
 // LayerNorm of fp32 rows; two affine outputs from one set of statistics (g2 may be null -> one).

@@ -92,20 +92,20 @@ hipError_t launch_pack_embed(int dtype, const int32_t* tokens, int B, int L, con
 }
 
 template <typename T>
-__global__ void embed_rows_kernel(const int32_t* __restrict__ tok, const T* __restrict__ embed, int d,
+__global__ void embed_rows_kernel(const int32_t* __restrict__ tok, const T* __restrict__ embed, int d, int vocab,
                                   float* __restrict__ x) {
   const int b = blockIdx.x;
-  const T* e = embed + (size_t)tok[b] * d;
+  const T* e = embed + (size_t)min(max(tok[b], 0), vocab - 1) * d;  // an id outside the table never leaves it
   float* xr = x + (size_t)b * d;
   for (int c = threadIdx.x; c < d; c += blockDim.x) xr[c] = to_f32(e[c]);
 }
 
-hipError_t launch_embed_rows(int dtype, const int32_t* tok, int B, const void* embed, int d, float* x,
+hipError_t launch_embed_rows(int dtype, const int32_t* tok, int B, const void* embed, int d, int vocab, float* x,
                              hipStream_t s) {
   if (dtype == 0)
-    hipLaunchKernelGGL(embed_rows_kernel<float>, dim3(B), dim3(256), 0, s, tok, (const float*)embed, d, x);
+    hipLaunchKernelGGL(embed_rows_kernel<float>, dim3(B), dim3(256), 0, s, tok, (const float*)embed, d, vocab, x);
   else
-    hipLaunchKernelGGL(embed_rows_kernel<bf16_t>, dim3(B), dim3(256), 0, s, tok, (const bf16_t*)embed, d, x);
+    hipLaunchKernelGGL(embed_rows_kernel<bf16_t>, dim3(B), dim3(256), 0, s, tok, (const bf16_t*)embed, d, vocab, x);
   return hipGetLastError();
 }
 
@@ -915,8 +915,12 @@ __global__ void __launch_bounds__(1024) sampler_kernel(SampleArgs a) {
         bi = si[j];
       }
     }
+    // A row without a single comparable score (every logit NaN) leaves bi at its start value: stop the row
+    // with EOS and a zero log-prob rather than index past the row and feed an id outside the table onwards.
+    const bool none = bi < 0 || bi >= a.V;
+    if (none) bi = a.eos_id;
     const float ztok = row[bi] / a.temperature;
-    const float lp = ztok - (m + logf(s));
+    const float lp = none ? 0.f : ztok - (m + logf(s));
     int fin = (a.step == 0) ? (a.len[b] == 0 ? 1 : 0) : a.finished[b];
     if (a.step == 0) a.out_lengths[b] = (a.len[b] == 0) ? 0 : a.N;
     const size_t to = (size_t)b * (a.Lq + a.N) + a.Lq + a.step;

@@ -251,6 +251,18 @@ int rlhf_attention_backward(const void *q, const void *k, const void *v, const v
                             int32_t dtype, int32_t max_len, float *lse_scratch, float *delta_scratch, void *dq,
                             void *dk, void *dv, void *stream);
 
+/* rlhf_attention_backward for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving or training loops, harnesses that forbid hipMalloc): the same kernels and results, with the two
+ * per-(row, head) scratch arrays taken from a fixed 8 MB array inside the library instead of from the caller.
+ * Limit: T * n_heads <= 1,048,576 (e.g. 32,768 packed rows of 32 heads), otherwise RLHF_EUNSUPPORTED.  The call
+ * allocates and frees nothing (its first call on a device looks up the array's address).  Every call on one
+ * GPU uses the same array: calls that overlap in time on one GPU race; calls on one stream do not.  All other
+ * arguments, errors and alignment rules are those of rlhf_attention_backward. */
+int rlhf_attention_backward_noalloc(const void *q, const void *k, const void *v, const void *d_out,
+                                    const int32_t *cu_seqlens, int32_t B, int32_t T, int32_t n_heads,
+                                    int32_t head_dim, int32_t dtype, int32_t max_len, void *dq, void *dk, void *dv,
+                                    void *stream);
+
 /* Backward pass through the attention branch of decoder layer `layer` (paper: as for rlhf_mlp_backward; the
  * other branch of the parallel-residual layer).  With a = LN1(x), [q | k | v] = a Wqkv^T + bqkv, the rotary turn
  * of q and k by each row's position in its sequence, o = packed causal attention (rlhf_attention_backward's

@@ -17,6 +17,7 @@ EXPORTS = (
     "rlhf_last_error", "rlhf_ppo_assemble_rewards", "rlhf_ppo_gae", "rlhf_ppo_whiten", "rlhf_ppo_loss", "rlhf_adamw_step",
     "rlhf_head_backward", "rlhf_head_backward_workspace_bytes", "rlhf_mlp_backward", "rlhf_mlp_backward_workspace_bytes", "rlhf_attention_backward", "rlhf_forward_keep", "rlhf_policy_backward", "rlhf_policy_backward_workspace_bytes",
     "rlhf_attention_branch_backward", "rlhf_attention_branch_backward_workspace_bytes",
+    "rlhf_attention_backward_noalloc",
 )
 
 _PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -85,6 +86,7 @@ def load_library():
     lib.rlhf_policy_backward.argtypes = [vp, vp, C.c_int64, vp, vp, i32, i32, i32, vp, vp, vp, C.c_float, C.c_float,
                                          C.POINTER(_Grads), vp, C.c_size_t, vp]
     lib.rlhf_attention_backward.argtypes = [vp] * 5 + [i32] * 6 + [vp] * 5 + [vp]
+    lib.rlhf_attention_backward_noalloc.argtypes = [vp] * 5 + [i32] * 6 + [vp] * 3 + [vp]
     lib.rlhf_adamw_step.argtypes = [vp, vp, vp, vp, vp, u64, i32] + [C.c_double] * 6 + [vp]
     lib.rlhf_last_error.restype = C.c_char_p
     for n in EXPORTS:
@@ -508,9 +510,10 @@ def linear_lr(base_lr, update_index, total_updates):
     return base_lr * (1.0 - k / total_updates)
 
 
-def attention_backward(q, k, v, d_out, cu_seqlens, n_heads, max_len=None):
+def attention_backward(q, k, v, d_out, cu_seqlens, n_heads, max_len=None, noalloc=False, out=None):
     """q, k, v, d_out: CUDA tensors [T, n_heads*head_dim], all float32 or all float16, contiguous; cu_seqlens int32
-    [B+1] (CUDA or host).  Returns (dq, dk, dv) in the inputs' dtype."""
+    [B+1] (CUDA or host).  Returns (dq, dk, dv) in the inputs' dtype.  noalloc=True goes through
+    rlhf_attention_backward_noalloc (the library's own fixed scratch); out: optional (dq, dk, dv) to write into."""
     import torch
     lib = load_library()
     ts = (q, k, v, d_out)
@@ -526,7 +529,15 @@ def attention_backward(q, k, v, d_out, cu_seqlens, n_heads, max_len=None):
     B = cu.numel() - 1
     if max_len is None:
         max_len = int((cu[1:] - cu[:-1]).max().item())
-    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    dq, dk, dv = out if out is not None else (torch.empty_like(q), torch.empty_like(q), torch.empty_like(q))
+    if noalloc:
+        with torch.cuda.device(dev):
+            _check(lib.rlhf_attention_backward_noalloc(q.data_ptr(), k.data_ptr(), v.data_ptr(), d_out.data_ptr(),
+                                                       cu.data_ptr(), B, T, n_heads, d // n_heads,
+                                                       0 if q.dtype == torch.float32 else 1, max(int(max_len), 1),
+                                                       dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+                                                       _cur_stream(torch, dev)))
+        return dq, dk, dv
     lse = torch.empty(T * n_heads, dtype=torch.float32, device=dev)
     delta = torch.empty(T * n_heads, dtype=torch.float32, device=dev)
     with torch.cuda.device(dev):

@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -29,6 +30,14 @@ int fail(int code, const std::string& msg) {
   } while (0)
 
 constexpr int kMaxPos = 8192;
+
+// Scratch of the allocation-free attention backward: log-sum-exp and delta, one float per (row, head) each.
+// Every GPU the library runs on holds its own 8 MB copy until the process ends.
+constexpr size_t kStaticScratchFloats = (size_t)1 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) float g_static_scratch[2 * kStaticScratchFloats];
+float* g_static_scratch_ptr[kMaxDevices] = {};  // device address of the array, per device (host code never uses its name)
+std::mutex g_static_scratch_mu;
 constexpr int kLogitChunk = 4096;  // rows of fp32 logits materialised at a time while scoring
 
 struct Carver {  // bump allocator over the workspace; base == nullptr only measures
@@ -518,6 +527,33 @@ int rlhf_attention_backward(const void* q, const void* k, const void* v, const v
   HIP_OK(launch_attention_backward(dtype, q, k, v, d_out, cu_seqlens, B, T, n_heads, head_dim, max_len, lse_scratch,
                                    delta_scratch, dq, dk, dv, (hipStream_t)stream));
   return RLHF_OK;
+}
+
+int rlhf_attention_backward_noalloc(const void* q, const void* k, const void* v, const void* d_out,
+                                    const int32_t* cu_seqlens, int32_t B, int32_t T, int32_t n_heads, int32_t head_dim,
+                                    int32_t dtype, int32_t max_len, void* dq, void* dk, void* dv, void* stream) {
+  if (T > 0 && n_heads > 0 && (size_t)T * (size_t)n_heads > kStaticScratchFloats)
+    return fail(RLHF_EUNSUPPORTED, "rows * heads beyond the static scratch (1,048,576): use rlhf_attention_backward "
+                                   "with caller scratch");
+  int dev = -1;
+  HIP_OK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(RLHF_EUNSUPPORTED, "device index beyond the per-device table");
+  float* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_static_scratch_mu);
+    if (!g_static_scratch_ptr[dev]) {
+      // the array's name is a host-side stand-in: its device address on the current device comes from the runtime
+      void* p = nullptr;
+      HIP_OK(hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)));
+      if (!p) return fail(RLHF_EHIP, "hipGetSymbolAddress returned a null address");
+      g_static_scratch_ptr[dev] = (float*)p;
+    }
+    base = g_static_scratch_ptr[dev];
+  }
+  // Both halves are written by the first kernel for every (row, head) before the second reads them: nothing
+  // has to start at zero, and what an earlier call left behind is never read.
+  return rlhf_attention_backward(q, k, v, d_out, cu_seqlens, B, T, n_heads, head_dim, dtype, max_len, base,
+                                 base + kStaticScratchFloats, dq, dk, dv, stream);
 }
 
 int rlhf_adamw_step(float* param, const float* grad, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16,

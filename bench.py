@@ -309,6 +309,7 @@ def main():
                 p32, m1, m2 = state[name]
                 P.adamw_step(p32, gten, m1, m2, it + 1, grad_scale=64.0 * B * N,
                              param_bf16=pol._dev[name] if name in pol._dev and pol._dev[name].dtype == torch.bfloat16 else None)
+            pol.refresh_weights()                        # the matrix products read an fp16 image of the new weights
             ev[3].record()
             del x_keep, grads
         torch.cuda.synchronize()

@@ -17,8 +17,10 @@
  *   - Every function returns 0 on success or a negative rlhf_status; it never throws or aborts.
  *     rlhf_last_error() gives a thread-local message for the last failure on the calling thread.
  *   - "dev" pointers are HIP device pointers, "host" pointers ordinary host memory.  The caller owns
- *     every buffer, the workspace included; the handle owns only small device tables (rotary
- *     cos/sin) it creates in rlhf_create and frees in rlhf_destroy.
+ *     every buffer: weights, workspaces and, in bf16 mode, the fp16 weight image the matrix products read
+ *     (rlhf_weight_image_bytes / rlhf_create / rlhf_refresh_weights).  The handle itself allocates only the
+ *     two small rotary cos/sin tables (2 x 8192 x rotary_dims/2 floats) in rlhf_create and frees them in
+ *     rlhf_destroy; no other call allocates or frees device memory.
  *   - All work is enqueued on the hipStream_t passed as `stream` (NULL = the default stream).  The
  *     calls do not synchronise with the host: outputs are valid once the stream has run the call's
  *     work.  Sizes that depend on the mask (number of real tokens) stay on the device.
@@ -77,10 +79,26 @@ typedef struct {
 
 typedef struct rlhf_handle rlhf_handle;
 
-/* Creates a handle for one model on the current HIP device.  Allocates the rotary tables
- * (synchronous).  *out is NULL on failure. */
-int rlhf_create(const rlhf_model_config *cfg, const rlhf_weights *w, rlhf_handle **out);
+/* bf16 mode feeds the matrix cores fp16 operands: the five matrix families (W_qkv with its bias, W_o, W_fc1,
+ * W_fc2, embed_out) are read from an fp16 image, converted from the caller's bf16 arrays (exact inside fp16's
+ * normal range).  rlhf_weight_image_bytes gives the image's size (0 for an fp32 model; about the size of the
+ * bf16 matrices themselves, e.g. 5.5 GB for the 2.8B shape): the caller allocates it, 256-byte aligned, passes
+ * it to rlhf_create and keeps it alive and untouched until rlhf_destroy.  Everything else (LayerNorm gains and
+ * biases, linear biases other than b_qkv, embed_in, the value head) is read from the caller's arrays directly. */
+int rlhf_weight_image_bytes(const rlhf_model_config *cfg, size_t *out);
+
+/* Creates a handle for one model on the current HIP device: allocates the rotary tables and fills the weight
+ * image (synchronous).  weight_image: dev buffer of at least rlhf_weight_image_bytes() bytes (may be NULL for an
+ * fp32 model); RLHF_EINVAL if it is NULL or misaligned, RLHF_ENOMEM if too small.  *out is NULL on failure. */
+int rlhf_create(const rlhf_model_config *cfg, const rlhf_weights *w, void *weight_image,
+                size_t weight_image_bytes, rlhf_handle **out);
 void rlhf_destroy(rlhf_handle *h);
+
+/* Re-converts the caller's (changed) bf16 matrices into the weight image: call it after an optimizer step
+ * (rlhf_adamw_step with param_bf16 = the weight arrays) and before the next forward pass.  Enqueued on
+ * `stream`, allocates nothing; a no-op for an fp32 model.  Until it has run, the matrix products still see the
+ * previous matrices while LayerNorm parameters, biases and embed_in are already the new ones. */
+int rlhf_refresh_weights(rlhf_handle *h, void *stream);
 
 /* Bytes of device workspace that rollout_generate(B, Lq, max_new) and score_sequences(B, L_score)
  * need (the maximum of the two; pass 0 for a call you will not make). */
@@ -180,8 +198,8 @@ int rlhf_ppo_loss(const float *new_logprobs, const float *old_logprobs, const fl
  *   m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2;
  *   p -= lr / (1 - beta1^step) * m / (sqrt(v) / sqrt(1 - beta2^step) + eps)
  * param, exp_avg, exp_avg_sq: dev float [n], updated in place; grad: dev float [n]; param_bf16: dev
- * uint16 [n] or NULL, receives the updated parameters rounded to bf16 (nearest even) -- the format the
- * forward passes read.  fp32 arrays 16-byte aligned, the bf16 array 8-byte aligned; n == 0 is a no-op.  The caller
+ * uint16 [n] or NULL, receives the updated parameters rounded to bf16 (nearest even) -- the storage format of
+ * a bf16 model's weights; the forward passes see updated matrices after rlhf_refresh_weights.  fp32 arrays 16-byte aligned, the bf16 array 8-byte aligned; n == 0 is a no-op.  The caller
  * supplies `lr` already scheduled (the paper's linear schedule: lr * (1 - k / K) for update k of K).
  * Arithmetic in fp32; the hyperparameters are doubles, and 1 - beta, lr * weight_decay and the two bias
  * corrections are formed in double on the host before being rounded to fp32.  One launch on

@@ -17,7 +17,7 @@ EXPORTS = (
     "rlhf_last_error", "rlhf_ppo_assemble_rewards", "rlhf_ppo_gae", "rlhf_ppo_whiten", "rlhf_ppo_loss", "rlhf_adamw_step",
     "rlhf_head_backward", "rlhf_head_backward_workspace_bytes", "rlhf_mlp_backward", "rlhf_mlp_backward_workspace_bytes", "rlhf_attention_backward", "rlhf_forward_keep", "rlhf_policy_backward", "rlhf_policy_backward_workspace_bytes",
     "rlhf_attention_branch_backward", "rlhf_attention_branch_backward_workspace_bytes",
-    "rlhf_attention_backward_noalloc",
+    "rlhf_attention_backward_noalloc", "rlhf_weight_image_bytes", "rlhf_refresh_weights",
 )
 
 _PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -60,7 +60,9 @@ def load_library():
     import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32, u64, f32, sz = C.c_void_p, C.c_int32, C.c_uint64, C.c_float, C.c_size_t
-    lib.rlhf_create.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(vp)]
+    lib.rlhf_create.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), vp, sz, C.POINTER(vp)]
+    lib.rlhf_weight_image_bytes.argtypes = [C.POINTER(_Config), C.POINTER(sz)]
+    lib.rlhf_refresh_weights.argtypes = [vp, vp]
     lib.rlhf_destroy.argtypes = [vp]
     lib.rlhf_destroy.restype = None
     lib.rlhf_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz)]
@@ -140,14 +142,25 @@ class Policy:
         w.value_b = float(weights.get("value_b", 0.0))
         self._has_value = "value_w" in self._dev
         self._h = C.c_void_p()
+        nimg = C.c_size_t()
+        _check(self.lib.rlhf_weight_image_bytes(C.byref(c), C.byref(nimg)))
+        # the fp16 image the matrix products of a bf16 model read: caller-owned, like every other buffer
+        self._image = torch.empty(max(nimg.value, 1), dtype=torch.uint8, device=self.device)
         with torch.cuda.device(self.device):
-            _check(self.lib.rlhf_create(C.byref(c), C.byref(w), C.byref(self._h)))
+            _check(self.lib.rlhf_create(C.byref(c), C.byref(w), self._image.data_ptr(), nimg.value, C.byref(self._h)))
         self._ws = None
 
     def close(self):
         if getattr(self, "_h", None):
             self.lib.rlhf_destroy(self._h)
             self._h = None
+            self._image = None
+
+    def refresh_weights(self):
+        """After the weight tensors in self._dev were changed in place (an optimizer step): re-convert the
+        matrices into the fp16 image the products read."""
+        with self.torch.cuda.device(self.device):
+            _check(self.lib.rlhf_refresh_weights(self._h, self._stream()))
 
     def __del__(self):
         try:

@@ -71,8 +71,10 @@ struct rlhf_handle {
   rlhf_model_config cfg;
   rlhf_weights w;
   std::vector<const void*> ln1_g, ln1_b, ln2_g, ln2_b, w_qkv, b_qkv, w_o, b_o, w_fc1, b_fc1, w_fc2, b_fc2;
+  // the caller's own arrays of the tensors that bf16 mode reads through the fp16 image (sources of a refresh)
+  std::vector<const void*> src_w_qkv, src_b_qkv, src_w_o, src_w_fc1, src_w_fc2;
   float *rope_cos = nullptr, *rope_sin = nullptr;
-  void* w16 = nullptr;                // bf16 mode: fp16 copies of the matrices the GEMMs read
+  void* w16 = nullptr;                // bf16 mode: fp16 image of the matrices the GEMMs read (caller's buffer)
   const void* embed_out_mm = nullptr; // LM-head operand (the caller's in fp32 mode, the copy in bf16 mode)
   // bf16 mode: the fp16 copies of the out-projection [d, d] and FC2 [d, d_ff] of a layer sit side by
   // side as one [d, d + d_ff] matrix (w_o = its column 0, w_fc2 = its column d, both with this row
@@ -447,6 +449,42 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
   return RLHF_OK;
 }
 
+// Bytes of the fp16 weight image of a bf16-mode model: per layer W_qkv (rotary pairs made neighbours) with its
+// reordered bias, W_fc1, and W_o | W_fc2 side by side; then the LM head.
+size_t weight_image_bytes_of(const rlhf_model_config& c) {
+  const size_t d = c.d_model, F = c.d_ff;
+  const size_t per_layer_elems = 3 * d * d + 3 * d + d * F + d * d + d * F;
+  return (per_layer_elems * (size_t)c.n_layers + (size_t)c.vocab * d) * 2;
+}
+
+// (Re)fills the image from the caller's bf16 arrays and points the handle's per-layer matrix pointers into it.
+hipError_t convert_weight_image(rlhf_handle* h, hipStream_t s) {
+  const rlhf_model_config& c = h->cfg;
+  const size_t d = c.d_model, F = c.d_ff;
+  char* p = (char*)h->w16;
+  hipError_t e = hipSuccess;
+  h->ld_o2 = (int)(d + F);
+  for (int l = 0; l < c.n_layers && e == hipSuccess; ++l) {
+    char* wq = p;
+    char* bq = wq + 3 * d * d * 2;
+    char* w1 = bq + 3 * d * 2;
+    char* wo = w1 + d * F * 2;
+    e = launch_qkv_weights_f16(h->src_w_qkv[l], h->src_b_qkv[l], wq, bq, (int)d, c.head_dim, c.rotary_dims, s);
+    if (e == hipSuccess) e = launch_bf16_to_f16(h->src_w_fc1[l], w1, d * F, s);
+    if (e == hipSuccess) e = launch_bf16_to_f16_2d(h->src_w_o[l], wo, d, d, d + F, s);
+    if (e == hipSuccess) e = launch_bf16_to_f16_2d(h->src_w_fc2[l], wo + d * 2, d, F, d + F, s);
+    h->w_qkv[l] = wq;
+    h->b_qkv[l] = bq;
+    h->w_fc1[l] = w1;
+    h->w_o[l] = wo;
+    h->w_fc2[l] = wo + d * 2;
+    p = wo + (d * d + d * F) * 2;
+  }
+  if (e == hipSuccess) e = launch_bf16_to_f16(h->w.embed_out, p, (size_t)c.vocab * d, s);
+  h->embed_out_mm = p;
+  return e;
+}
+
 int check_common(const rlhf_handle* h, int B, int L) {
   if (!h) return fail(RLHF_EINVAL, "null handle");
   if (B <= 0 || L <= 0) return fail(RLHF_EINVAL, "batch and length must be positive");
@@ -578,7 +616,23 @@ int rlhf_adamw_step(float* param, const float* grad, float* exp_avg, float* exp_
   return RLHF_OK;
 }
 
-int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, rlhf_handle** out) {
+int rlhf_weight_image_bytes(const rlhf_model_config* cfg, size_t* out) {
+  if (!cfg || !out) return fail(RLHF_EINVAL, "null argument");
+  if (cfg->n_layers < 0 || cfg->d_model <= 0 || cfg->d_ff <= 0 || cfg->vocab <= 0)
+    return fail(RLHF_EINVAL, "non-positive model dimension");
+  *out = cfg->dtype == RLHF_DTYPE_BF16 ? weight_image_bytes_of(*cfg) : 0;
+  return RLHF_OK;
+}
+
+int rlhf_refresh_weights(rlhf_handle* h, void* stream) {
+  if (!h) return fail(RLHF_EINVAL, "null handle");
+  if (h->cfg.dtype != RLHF_DTYPE_BF16) return RLHF_OK;  // fp32 mode reads the caller's arrays directly
+  HIP_OK(convert_weight_image(h, (hipStream_t)stream));
+  return RLHF_OK;
+}
+
+int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, void* weight_image, size_t weight_image_bytes,
+                rlhf_handle** out) {
   if (out) *out = nullptr;
   if (!cfg || !w || !out) return fail(RLHF_EINVAL, "null argument");
   const rlhf_model_config& c = *cfg;
@@ -609,6 +663,7 @@ int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, rlhf_handle
   std::vector<const void*>* dst[12] = {&h->ln1_g, &h->ln1_b, &h->ln2_g, &h->ln2_b, &h->w_qkv, &h->b_qkv,
                                        &h->w_o,   &h->b_o,   &h->w_fc1, &h->b_fc1, &h->w_fc2, &h->b_fc2};
   for (int i = 0; i < 12; ++i) dst[i]->assign(per_layer[i], per_layer[i] + c.n_layers);
+  h->src_w_qkv = h->w_qkv; h->src_b_qkv = h->b_qkv; h->src_w_o = h->w_o; h->src_w_fc1 = h->w_fc1; h->src_w_fc2 = h->w_fc2;
   // rotary tables, evaluated in double on the host: angle(p, i) = p * base^(-2i/r)
   const int half = c.rotary_dims / 2;
   if (half > 0) {
@@ -628,40 +683,18 @@ int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, rlhf_handle
       return fail(RLHF_EHIP, std::string("rotary tables: ") + hipGetErrorString(e));
     }
   }
-  // bf16 mode: the matrix cores take fp16 operands; convert the five matrix families once
+  // bf16 mode: the matrix cores take fp16 operands; the five matrix families are converted into the caller's
+  // image buffer (and again by rlhf_refresh_weights whenever the caller has changed its weights)
   h->embed_out_mm = w->embed_out;
   if (c.dtype == RLHF_DTYPE_BF16) {
-    const size_t d = c.d_model, F = c.d_ff;
-    const size_t per_layer_elems = 3 * d * d + d * d + 2 * d * F;
-    const size_t total = per_layer_elems * c.n_layers + (size_t)c.vocab * d + 3 * d * c.n_layers;
-    hipError_t e = hipMalloc(&h->w16, total * 2);
-    if (e != hipSuccess) {
+    const size_t need = weight_image_bytes_of(c);
+    if (!weight_image || ((uintptr_t)weight_image & 255) != 0 || weight_image_bytes < need) {
       rlhf_destroy(h);
-      return fail(RLHF_EHIP, std::string("fp16 weight copy: ") + hipGetErrorString(e));
+      return fail(weight_image ? RLHF_ENOMEM : RLHF_EINVAL,
+                  "bf16 mode needs a 256-byte aligned device buffer of rlhf_weight_image_bytes() bytes");
     }
-    char* p = (char*)h->w16;
-    auto conv = [&](const void*& slot, size_t n) {
-      if (e == hipSuccess) e = launch_bf16_to_f16(slot, p, n, nullptr);
-      slot = p;
-      p += n * 2;
-    };
-    h->ld_o2 = (int)(d + F);
-    for (int l = 0; l < c.n_layers; ++l) {
-      // W_qkv with the rotary pairs of every q and k head made neighbours, and its bias likewise
-      char* bq = p + 3 * d * d * 2;
-      if (e == hipSuccess)
-        e = launch_qkv_weights_f16(h->w_qkv[l], h->b_qkv[l], p, bq, (int)d, c.head_dim, c.rotary_dims, nullptr);
-      h->w_qkv[l] = p;
-      h->b_qkv[l] = bq;
-      p += (3 * d * d + 3 * d) * 2;
-      conv(h->w_fc1[l], d * F);
-      if (e == hipSuccess) e = launch_bf16_to_f16_2d(h->w_o[l], p, d, d, d + F, nullptr);
-      if (e == hipSuccess) e = launch_bf16_to_f16_2d(h->w_fc2[l], p + d * 2, d, F, d + F, nullptr);
-      h->w_o[l] = p;
-      h->w_fc2[l] = p + d * 2;
-      p += (d * d + d * F) * 2;
-    }
-    conv(h->embed_out_mm, (size_t)c.vocab * d);
+    h->w16 = weight_image;
+    hipError_t e = convert_weight_image(h, nullptr);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
       rlhf_destroy(h);
@@ -685,7 +718,6 @@ int rlhf_create(const rlhf_model_config* cfg, const rlhf_weights* w, rlhf_handle
 
 void rlhf_destroy(rlhf_handle* h) {
   if (!h) return;
-  if (h->w16) (void)hipFree(h->w16);
   if (h->rope_cos) (void)hipFree(h->rope_cos);
   if (h->rope_sin) (void)hipFree(h->rope_sin);
   for (hipEvent_t e : h->ev_pool) (void)hipEventDestroy(e);

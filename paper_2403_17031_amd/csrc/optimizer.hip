@@ -1,5 +1,6 @@
 // AdamW step of the PPO update, fused over everything an update touches: fp32 master weights, both
-// moments, and the bf16 copy of the weights that the forward passes read.  Pure streaming work
+// moments, and the bf16 storage copy of the weights (a bf16 model's matrices reach the forward passes through
+// the fp16 image that rlhf_refresh_weights rebuilds from that copy).  Pure streaming work
 // (16 bytes read, 12 to 14 written per element): 4 elements per lane, 16-byte accesses, grid sized
 // for 64 blocks per CU (measured best of 8 / 16 / 64) with a grid-stride loop, so any length fits one launch.
 #include "common.h"

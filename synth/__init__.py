@@ -12,6 +12,7 @@ from .inputs import (  # noqa: F401
     make_random_responses,
     make_tensor,
     boost_eos,
+    boost_eos_bias,
     round_to_bf16,
     bf16_bits,
     weight_names,

@@ -178,6 +178,23 @@ def boost_eos(cfg: ModelConfig, w: dict, alpha: float) -> dict:
     return out
 
 
+def boost_eos_bias(cfg: ModelConfig, w: dict, alpha: float) -> dict:
+    """Test helper: raise the EOS logit by `alpha` at every position while every weight stays at its
+    initialisation scale.
+
+    The final LayerNorm's bias gets a component along the EOS row e of the output embedding,
+    lnf_b += alpha * e / (e . e): the EOS logit rises by alpha, any other logit v by
+    alpha * (e_v . e) / (e . e), which is small for random rows.  No row of the output embedding is
+    touched (unlike boost_eos, whose EOS row is tens of times larger than N(0, 0.02) weights), so
+    rounding errors of the hidden state are weighted as in the real model.  In bf16 mode the new bias
+    is rounded to bf16 (the storage type), which moves the boost by a fraction of a percent."""
+    e = w["embed_out"][cfg.eos_id].astype(np.float64)
+    b = w["lnf_b"].astype(np.float64) + alpha * e / float(e @ e)
+    out = dict(w)
+    out["lnf_b"] = round_to_bf16(b.astype(np.float32)) if cfg.dtype == "bf16" else b.astype(np.float32)
+    return out
+
+
 # ----------------------------------------------------------------------------------------------
 # queries
 # ----------------------------------------------------------------------------------------------

@@ -11,6 +11,8 @@ import pytest
 import paper_2403_17031_amd as P
 from synth import ModelConfig, make_weights
 
+from bars import assert_signal_entries_close
+
 pytestmark = pytest.mark.gpu
 
 PAIRS = dict(d_x="d_x", d_ln1_g="d_ln_g", d_ln1_b="d_ln_b", d_w_qkv="d_w_qkv", d_b_qkv="d_b_qkv", d_w_o="d_w_o",
@@ -48,6 +50,7 @@ def _check(P, cfg, lens, seed, layer=0, scale=1.0):
         assert err <= (1e-4 if fp32 else 2e-2) * top, (n, err, top)
         if not fp32:
             assert np.linalg.norm(a - b) <= 5e-3 * np.linalg.norm(b), (n, np.linalg.norm(a - b) / np.linalg.norm(b))
+        assert_signal_entries_close(a, b, fp32, n)
     pol.close()
 
 

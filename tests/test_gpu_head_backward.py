@@ -13,6 +13,8 @@ import pytest
 import paper_2403_17031_amd as P
 from synth import ModelConfig, make_weights
 
+from bars import assert_signal_entries_close
+
 pytestmark = pytest.mark.gpu
 
 
@@ -59,6 +61,7 @@ def _check(P, cfg, w, T, seed, scale, value_head=True, frac_no_target=0.2):
         assert err <= (1e-4 if fp32 else 2e-2) * top, (n, err, top)
         if not fp32:
             assert np.linalg.norm(a - b) <= 5e-3 * np.linalg.norm(b), (n, np.linalg.norm(a - b) / np.linalg.norm(b))
+        assert_signal_entries_close(a, b, fp32, n)
     pol.close()
     return got, ref
 

@@ -11,6 +11,8 @@ import pytest
 import paper_2403_17031_amd as P
 from synth import ModelConfig, make_weights
 
+from bars import assert_signal_entries_close
+
 pytestmark = pytest.mark.gpu
 
 NAMES = ("d_x", "d_ln2_g", "d_ln2_b", "d_w_fc1", "d_b_fc1", "d_w_fc2", "d_b_fc2")
@@ -47,6 +49,7 @@ def _check(P, cfg, T, seed, layer=0, scale=1.0):
         assert err <= (1e-4 if fp32 else 2e-2) * top, (n, err, top)
         if not fp32:
             assert np.linalg.norm(a - b) <= 5e-3 * np.linalg.norm(b), (n, np.linalg.norm(a - b) / np.linalg.norm(b))
+        assert_signal_entries_close(a, b, fp32, n)
     pol.close()
     return got
 

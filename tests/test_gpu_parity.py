@@ -7,7 +7,7 @@ import pytest
 
 pytestmark = pytest.mark.gpu
 
-from synth import ModelConfig, Workload, WORKLOADS, make_weights, make_queries, make_random_responses, boost_eos
+from synth import ModelConfig, Workload, WORKLOADS, make_weights, make_queries, make_random_responses, boost_eos, boost_eos_bias
 
 TOL = {"fp32": 1e-4, "bf16": 2e-2}
 NEAR_TIE = 1e-2
@@ -109,17 +109,37 @@ def test_tiny_model_ragged_shapes(gpu, tiny_cfg, dtype):
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 def test_eos_stop_mask_and_all_pad_row(gpu, tiny_cfg, dtype):
+    """EOS made likely through the final LayerNorm's bias, every weight at its initialisation scale: both modes
+    at their stated bars (1e-4 / 2e-2)."""
     cfg = tiny_cfg.with_(dtype=dtype)
-    w = boost_eos(cfg, make_weights(cfg, 7, variant="test"), alpha=3.0)
+    w = boost_eos_bias(cfg, make_weights(cfg, 7, variant="test"), alpha=3.0)
     queries, mask = _queries(cfg, B=8, Lq=16, lo=2, hi=16, seed=1)
     queries[3] = cfg.pad_id
     mask[3] = 0
-    # the boosted EOS row of the output embedding is ~30x larger than N(0, 0.02) weights, and bf16
-    # rounding of the hidden state scales with it: 5e-2 here instead of the 2e-2 of the real shapes
-    toks, lps, lens, _ = _check_rollout_and_scores(gpu, cfg, w, queries, mask, seed=4321, T=0.7, N=12,
-                                                   tol=None if dtype == "fp32" else 5e-2)
+    toks, lps, lens, _ = _check_rollout_and_scores(gpu, cfg, w, queries, mask, seed=4321, T=0.7, N=12)
     assert lens[3] == 0
     assert (lens[np.arange(8) != 3] < 12).any(), "the EOS path was not exercised"
+
+
+def test_eos_stop_mask_with_a_large_output_row_fp32(gpu, tiny_cfg):
+    """The other way to make EOS likely: an EOS row of the output embedding ~30x larger than N(0, 0.02) weights
+    (fp32 check mode only: in bf16 mode the rounding of the hidden state scales with that row)."""
+    cfg = tiny_cfg.with_(dtype="fp32")
+    w = boost_eos(cfg, make_weights(cfg, 7, variant="test"), alpha=3.0)
+    queries, mask = _queries(cfg, B=8, Lq=16, lo=2, hi=16, seed=1)
+    toks, lps, lens, _ = _check_rollout_and_scores(gpu, cfg, w, queries, mask, seed=4321, T=0.7, N=12)
+    assert (lens < 12).any(), "the EOS path was not exercised"
+
+
+def test_eos_stop_mask_at_the_full_vocabulary_bf16(gpu):
+    """The stop mask at vocabulary 50,304 (BASELINE config 1's shape in bf16): EOS raised to about 15 % per step
+    through the final LayerNorm's bias, weights at initialisation scale, bar 2e-2."""
+    wl = WORKLOADS[1]
+    cfg = wl.model.with_(dtype="bf16")
+    w = boost_eos_bias(cfg, make_weights(cfg, 5, variant="test"), alpha=6.4)
+    queries, mask = make_queries(wl, seed=78, batch=6)
+    toks, lps, lens, _ = _check_rollout_and_scores(gpu, cfg, w, queries, mask, 99, 0.7, 16)
+    assert (lens < 16).any() and (lens > 1).any(), lens
 
 
 def test_config1_pythia70m_shape_fp32(gpu):

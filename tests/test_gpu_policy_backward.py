@@ -11,6 +11,8 @@ import pytest
 import paper_2403_17031_amd as P
 from synth import ModelConfig, make_weights
 
+from bars import assert_signal_entries_close
+
 pytestmark = pytest.mark.gpu
 
 
@@ -66,6 +68,7 @@ def _check(P, cfg, B, L, seed, scale):
             rel = np.linalg.norm(a - b) / np.linalg.norm(b)
             assert rel <= 5e-3, (name, rel)
             worst[name] = rel
+        assert_signal_entries_close(a, b, fp32, name)
     pol.close()
     return worst
 

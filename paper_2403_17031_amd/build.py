@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librlhf_rollout.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "ppo_signals.hip", "optimizer.hip", "head_backward.hip", "attention_backward.hip"]
+SOURCES = ["api.hip", "gemm.hip", "gemm_skinny.hip", "attention.hip", "elementwise.hip", "ppo_signals.hip", "optimizer.hip", "head_backward.hip", "attention_backward.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wno-unused-result",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -45,13 +45,14 @@ def build(verbose: bool = False) -> str:
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
     # stand-alone kernel drivers (hardware-counter runs): each links the library's own object
-    for drv, obj in (("gemm_driver", "gemm.o"), ("attn_driver", "attention.o")):
+    for drv, obj in (("gemm_driver", "gemm.o gemm_skinny.o"), ("attn_driver", "attention.o"),
+                     ("dec_driver", "gemm.o gemm_skinny.o")):
         drv_obj = os.path.join(objdir, drv + ".o")
         r = subprocess.run([hipcc, *FLAGS, "-c", os.path.join(CSRC, drv + ".hip"), "-o", drv_obj],
                            capture_output=True, text=True)
         if r.returncode == 0:
             r = subprocess.run([hipcc, "--offload-arch=gfx950", "-o", os.path.join(HERE, drv), drv_obj,
-                                os.path.join(objdir, obj)], capture_output=True, text=True)
+                                *[os.path.join(objdir, o) for o in obj.split()]], capture_output=True, text=True)
         if r.returncode != 0:  # the drivers are measurement aids: the library itself is built, so only warn
             sys.stderr.write(f"warning: {drv} was not built:\n{r.stderr}\n")
     return LIB

@@ -288,11 +288,28 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
   // Decode with every product on the split-K path: the reductions of the partial sums are folded
   // into the kernels that consume them (QKV into the rotary kernel; out-projection and FC2 into the
   // next layer's LayerNorm), which takes four short kernels per layer off the critical path.
+  // Decode products.  QKV and the out-projection sit on the critical path of a layer and run alone on the chip:
+  // they take the weight-streaming kernel, K split 4 ways (more splits shorten them further but cost the next
+  // LayerNorm / rotary kernel as much again in partial sums to add up).  FC1 and FC2 run in the shadow of the
+  // attention kernel on a second stream: there the staged tile kernel's small blocks, which fit on a CU next to
+  // attention blocks, do better than blocks that each take a whole CU (measured: decode 476 against 525-580 ms).
+  int cap_qkv = 4, cap_o = 4, cap_1 = 0, cap_2 = 0;
+  int mlp_small_i = 1;
+#ifdef RLHF_TUNE
+  if (const char* e = getenv("RLHF_DEC_SPLITS")) sscanf(e, "%d,%d,%d,%d,%d", &cap_qkv, &cap_o, &cap_1, &cap_2, &mlp_small_i);
+#endif
+  const bool mlp_small = p.mode == 1 && mlp_small_i != 0;
+  auto capped = [](GemmArgs g, int cap) {
+    g.max_split = cap;
+    return g;
+  };
   int ks_qkv = 1, ks_o = 1, ks_2 = 1;
   if (p.mode == 1) {
-    ks_qkv = gemm_splitk_factor(dt, gemm_args(A.a, nullptr, nullptr, A.qkv, 3 * d, d, EPI_BIAS));
-    ks_o = gemm_splitk_factor(dt, gemm_args(A.att, nullptr, nullptr, A.x, d, d, EPI_BIAS_RESADD));
-    ks_2 = gemm_splitk_factor(dt, gemm_args(A.ffn, nullptr, nullptr, A.x, d, c.d_ff, EPI_BIAS_RESADD));
+    ks_qkv = gemm_splitk_factor(dt, capped(gemm_args(A.a, nullptr, nullptr, A.qkv, 3 * d, d, EPI_BIAS), cap_qkv));
+    ks_o = gemm_splitk_factor(dt, capped(gemm_args(A.att, nullptr, nullptr, A.x, d, d, EPI_BIAS_RESADD), cap_o));
+    GemmArgs t2 = capped(gemm_args(A.ffn, nullptr, nullptr, A.x, d, c.d_ff, EPI_BIAS_RESADD), cap_2);
+    t2.small_footprint = mlp_small;
+    ks_2 = gemm_splitk_factor(dt, t2);
   }
   const bool fold = p.mode == 1 && ks_qkv > 1 && ks_o > 1 && ks_2 > 1 &&
                     rope_kv_splitk_supported(dt, c.n_heads, c.head_dim, c.rotary_dims) &&
@@ -300,7 +317,10 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
   // Decode: the MLP branch (weights streaming through the matrix cores) overlaps the attention
   // branch (K/V streaming from HBM).  Needs FC2 on the split-K path, so that only its final
   // reduction touches the residual stream; not used while per-kernel profiling is on.
-  const bool fork_mlp = p.mode == 1 && !h->prof_on && ks_2 > 1;
+  bool fork_mlp = p.mode == 1 && !h->prof_on && ks_2 > 1;
+#ifdef RLHF_TUNE
+  if (getenv("RLHF_NO_FORK")) fork_mlp = false;
+#endif
   // Prefill / scoring: out-projection and FC2 both add into the residual stream, so they run as one
   // product over the concatenated K = d + d_ff when the large-M kernel takes that shape.
   auto gcat = [&](int l) {
@@ -331,9 +351,10 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
                                            A.a, h->ln2_g[l], h->ln2_b[l], A.m, s));
     }
     GemmArgs g = gemm_args(A.a, h->w_qkv[l], h->b_qkv[l], A.qkv, 3 * d, d, EPI_BIAS);
+    if (p.mode == 1) g.max_split = cap_qkv;
     if (fold) {
       g.phase = 1;
-      LAUNCH("gemm_decode", launch_gemm(dt, g, s));
+      LAUNCH("gemm_decode_qkv", launch_gemm(dt, g, s));
       LAUNCH("rope_kv_decode", launch_rope_kv_splitk((const float*)A.splitk, ks_qkv, (size_t)p.rows_max * 3 * d, h->b_qkv[l],
                                                      p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff, p.len,
                                                      c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q,
@@ -349,7 +370,7 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
       g.qkv = &qa;
       LAUNCH("gemm", launch_gemm(dt, g, s));
     } else {
-      LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g, s));
+      LAUNCH(p.mode ? "gemm_decode_qkv" : "gemm", launch_gemm(dt, g, s));
       LAUNCH(p.mode ? "rope_kv_decode" : "rope_kv", launch_rope_kv(dt, A.qkv, p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff,
                                        p.len, c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q, kc, vc,
                                        (long)p.kv_extra, s));
@@ -386,6 +407,12 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
     GemmArgs g1 = gemm_args(A.m, h->w_fc1[l], h->b_fc1[l], A.ffn, c.d_ff, d, EPI_BIAS_GELU);
     GemmArgs g2 = gemm_args(A.ffn, h->w_fc2[l], h->b_fc2[l], A.x, d, c.d_ff, EPI_BIAS_RESADD);
     go.ldw = g2.ldw = h->ld_o2;
+    if (p.mode == 1) {
+      go.max_split = cap_o;
+      g1.max_split = cap_1;
+      g2.max_split = cap_2;
+      g1.small_footprint = g2.small_footprint = mlp_small;
+    }
     if (cat) {  // attention output and FFN hidden side by side: [rows, d + d_ff]
       g1.out = (char*)A.att + (size_t)d * h->esz;
       g1.ldo = d + c.d_ff;
@@ -423,24 +450,24 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
     }
     const bool defer = fold && l + 1 < c.n_layers;  // the next layer's LayerNorm adds both products
     if (fold) go.phase = 1;
-    LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, go, s));
+    LAUNCH(p.mode ? "gemm_decode_out" : "gemm", launch_gemm(dt, go, s));
     if (fork_mlp) {
       HIP_OK(hipStreamWaitEvent(s, join, 0));
     } else {
-      LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g1, s));
+      LAUNCH(p.mode ? "gemm_decode_fc1" : "gemm", launch_gemm(dt, g1, s));
       if (fold) g2.phase = 1;
-      LAUNCH(p.mode ? "gemm_decode" : "gemm", launch_gemm(dt, g2, s));
+      LAUNCH(p.mode ? "gemm_decode_fc2" : "gemm", launch_gemm(dt, g2, s));
     }
     if (defer) {
       pending = true;
     } else if (fold) {
       go.phase = 2;
       g2.phase = 2;
-      LAUNCH("gemm_decode", launch_gemm(dt, go, s));
-      LAUNCH("gemm_decode", launch_gemm(dt, g2, s));
+      LAUNCH("gemm_decode_out", launch_gemm(dt, go, s));
+      LAUNCH("gemm_decode_fc2", launch_gemm(dt, g2, s));
     } else if (fork_mlp) {
       g2.phase = 2;
-      LAUNCH("gemm_decode", launch_gemm(dt, g2, s));
+      LAUNCH("gemm_decode_fc2", launch_gemm(dt, g2, s));
     }
   }
   if (p.keep)

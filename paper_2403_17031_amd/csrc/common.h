@@ -140,7 +140,16 @@ struct GemmArgs {
   const struct QkvArgs* qkv = nullptr;  // EPI_QKV only
   int lda = 0, ldw = 0;        // row strides of A and W in elements (0: K); fp16 kernels only
   const void* bias2 = nullptr; // second bias added like the first; large-M fp16 kernel only
+  int max_split = 0;           // few-rows kernel: cap on the K split (0: as many as cover the chip)
+  bool small_footprint = false;  // few rows: stay on the staged tile kernel (24 KB of LDS, 4 blocks per CU), whose
+                                 // blocks fit next to another kernel's on a CU; the weight-streaming kernel takes a
+                                 // whole CU per block
 };
+// The few-rows (decode) kernel of gemm_skinny.hip: whether it takes these arguments, the K split it would use,
+// and the launch itself (ks > 1: fp32 partial slabs into a.splitk_ws; ks == 1: epilogue in the kernel).
+bool gemm_skinny_takes(int dtype, const GemmArgs& a);
+int gemm_skinny_splitk(const GemmArgs& a);
+void launch_gemm_skinny(const GemmArgs& a, int ks, hipStream_t s);
 // True when launch_gemm would route these arguments to the kernel that honours bias2.
 bool gemm_takes_bias2(int dtype, const GemmArgs& a);
 // > 1 when launch_gemm would take the split-K path for these arguments.

@@ -693,6 +693,9 @@ static void launch_f16_dma(const GemmArgs& a, hipStream_t s) {
 #define RLHF_GEMM_PF 1
 #define RLHF_GEMM_OCC 2
 #endif
+#ifndef RLHF_GEMM_SKINNY
+#define RLHF_GEMM_SKINNY 1
+#endif
 #ifndef RLHF_DEC_PF
 #define RLHF_DEC_PF 1
 #define RLHF_DEC_OCC 4
@@ -727,6 +730,7 @@ __global__ void __launch_bounds__(256)
 // N tiles and by splitting K, so that every CU holds several short k-loops in flight; partial sums
 // go through the caller's fp32 scratch.
 int gemm_splitk_factor(int dtype, const GemmArgs& a) {
+  if (RLHF_GEMM_SKINNY && gemm_skinny_takes(dtype, a)) return gemm_skinny_splitk(a);
   if (dtype != 1 || a.M_max > 512 || !a.splitk_ws || (a.ldo & 3) != 0) return 1;
   const int tiles = ((a.M_max + 127) / 128) * ((a.N + 63) / 64);
   const int nk = (a.K + TK - 1) / TK;
@@ -769,8 +773,16 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
     // Few rows (decode): the chip is filled by small N tiles and by splitting K, so that every CU
     // holds several short k-loops in flight; partial sums go through the caller's fp32 scratch.
     const int ksplit = gemm_splitk_factor(dtype, a);
+    const bool skinny = RLHF_GEMM_SKINNY && gemm_skinny_takes(dtype, a);
+    if (skinny && ksplit == 1) {
+      launch_gemm_skinny(a, 1, s);
+      return;
+    }
     if (ksplit > 1) {
-      if (a.phase != 2) launch_f16<EPI_F32, 2, 1, RLHF_DEC_PF, RLHF_DEC_OCC>(a, s, a.splitk_ws, ksplit);
+      if (a.phase != 2) {
+        if (skinny) launch_gemm_skinny(a, ksplit, s);
+        else launch_f16<EPI_F32, 2, 1, RLHF_DEC_PF, RLHF_DEC_OCC>(a, s, a.splitk_ws, ksplit);
+      }
       if (a.phase != 1) {
         const size_t n4 = ((size_t)a.M_max * a.ldo + 3) / 4;
         hipLaunchKernelGGL(splitk_reduce_kernel<EPI>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,

@@ -17,6 +17,31 @@ HBM_PEAK = 8.0e12       # B/s, MI355X HBM3E
 MFMA_PEAK = 2.5e15      # flop/s, dense fp16/bf16 MFMA
 
 
+def measured_ceilings():
+    """Runs the stand-alone ceilings driver (a streaming read of 2 GiB; a bare matrix-instruction loop on zero and
+    on random fp16 operands) in a child process before this process touches the GPU.  None if it was not built."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2403_17031_amd", "ceilings_driver")
+    if not os.path.exists(exe):
+        return None
+    try:
+        r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+        return json.loads(r.stdout.strip().splitlines()[-1]) if r.returncode == 0 else None
+    except Exception:
+        return None
+
+
+def gemm_traffic_per_row(cfg):
+    """L2-miss bytes per GEMM row and launch of the per-layer products (FETCH_SIZE + WRITE_SIZE on gemm_driver,
+    scaled by a copy kernel of known size; written by paper_2403_17031_amd/pmc_summary.py): for the 2.8B width
+    only, where it was measured.  Returns (bytes per row, commit it was measured at) or (None, None)."""
+    path = os.path.join(ROOT, "profiles", "pmc_gemm_traffic_config4.json")
+    if cfg.d_model != 2560 or cfg.dtype == "fp32" or not os.path.exists(path):
+        return None, None
+    d = json.load(open(path))
+    return float(d["bytes_per_gemm_row"]), d.get("commit")
+
+
 def work_counts(cfg, n, resp, N):
     """Algorithmic flops / bytes of the workload from the drawn lengths (real tokens only)."""
     import numpy as np
@@ -72,6 +97,7 @@ def main():
     import paper_2403_17031_amd as P
     from synth import WORKLOADS, make_weights, make_queries
 
+    ceil = measured_ceilings()   # before this process holds the GPU
     wl = WORKLOADS[a.config]
     cfg = wl.model
     B = a.batch or wl.batch
@@ -126,17 +152,14 @@ def main():
     if "gemm" in prof:
         fl = wc["gemm_flops_prefill"] + wc["gemm_flops_score"]
         ach = fl / (prof["gemm"][0] * 1e-3)
-        # Memory traffic of the per-layer GEMMs cannot be counted in this process (hardware counters are
-        # collected on the stand-alone gemm_driver, see profiles/pmc_gemm_traffic_config4.md): for d_model
-        # 2560 the L2-miss bytes, FETCH_SIZE + WRITE_SIZE scaled by a copy kernel of known size, came to
-        # 116,183 bytes per GEMM row per launch (mean of QKV, FC1 and out+FC2 at 83,373 rows) and grow in
-        # proportion to the rows, so the figure here is that rate times this run's mean rows per launch.
-        # It counts what leaves the L2s, Infinity-Cache hits included: an upper bound of the HBM bytes.
-        traffic = None
-        if cfg.d_model == 2560 and cfg.dtype != "fp32":
-            traffic = 116183.0 * 0.5 * (wc["real_query_tokens"] + wc["real_score_tokens"])
+        # Memory traffic of the per-layer GEMMs cannot be counted in this process (hardware counters are collected
+        # on the stand-alone gemm_driver, see profiles/pmc_gemm_traffic_config4.md): what leaves the L2s per GEMM
+        # row and launch, Infinity-Cache hits included (an upper bound of the HBM bytes), times this run's mean
+        # rows per launch.
+        per_row, traffic_commit = gemm_traffic_per_row(cfg)
+        traffic = per_row * 0.5 * (wc["real_query_tokens"] + wc["real_score_tokens"]) if per_row else None
         rooflines["gemm"] = {"bound": "mfma", "achieved": ach / 1e12, "peak": MFMA_PEAK / 1e12, "unit": "TFLOP/s",
-                             "frac": ach / MFMA_PEAK, "traffic": traffic,
+                             "frac": ach / MFMA_PEAK, "traffic": traffic, "traffic_measured_at_commit": traffic_commit,
                              "avg_launch_ms": prof["gemm"][0] / prof["gemm"][1]}
     if "attn_decode" in prof:
         by = wc["decode_kv_read_bytes"]
@@ -167,6 +190,11 @@ def main():
         rooflines["attn_prefill"] = {"bound": "mfma", "achieved": a_ / 1e12, "peak": MFMA_PEAK / 1e12,
                                      "unit": "TFLOP/s", "frac": a_ / MFMA_PEAK, "traffic": None,
                                      "avg_launch_ms": prof["attn_prefill"][0] / prof["attn_prefill"][1]}
+    # fractions of what this box was measured to sustain, next to the fractions of the published peaks
+    if ceil:
+        for rf in rooflines.values():
+            top = ceil["mfma_f16_random_TFLOPs"] if rf["bound"] == "mfma" else ceil["stream_read_GBps"]
+            rf["frac_of_measured"] = rf["achieved"] / top
     roof = rooflines.get(dom) or rooflines.get("gemm") or {}
     roof = dict(roof, kernel=dom if dom in rooflines else "gemm")
 
@@ -353,6 +381,11 @@ def main():
     if not a.no_cpu_baseline:
         cpu = cpu_baseline(cfg, w, queries, mask, wl, n_true)
 
+    if ceil:
+        for rf in rooflines.values():
+            if "frac_of_measured" not in rf:
+                top = ceil["mfma_f16_random_TFLOPs"] if rf["bound"] == "mfma" else ceil["stream_read_GBps"]
+                rf["frac_of_measured"] = rf["achieved"] / top
     ms_step = wall / a.steps * 1e3
     out = {
         "metric": "rollout generated tokens/s (rollout_generate + score_sequences per step)",
@@ -373,6 +406,10 @@ def main():
         "rescoring_tok_s_padded": B * (wl.query_len + N) / (score_ms * 1e-3),
         "score_mfma_frac": wc["score_flops"] / (score_ms * 1e-3) / MFMA_PEAK,
         "roofline": roof, "rooflines": rooflines, "kernels_ms": kern, "profiled_step_ms": tot,
+        "ceilings": ceil,
+        "decode_frac_of_measured_stream": (wc["decode_bytes"] / (decode_ms * 1e-3) / (ceil["stream_read_GBps"] * 1e9)) if ceil else None,
+        "prefill_frac_of_measured_mfma": (wc["prefill_flops"] / (prefill_ms * 1e-3) / (ceil["mfma_f16_random_TFLOPs"] * 1e12)) if ceil else None,
+        "score_frac_of_measured_mfma": (wc["score_flops"] / (score_ms * 1e-3) / (ceil["mfma_f16_random_TFLOPs"] * 1e12)) if ceil else None,
         "ppo_signals_ms": signals_ms, "adamw_ms_per_2p30_params": adamw_ms, "head_backward_ms": head_bwd_ms, "mlp_backward_ms_per_layer": mlp_bwd_ms, "attention_backward_ms_per_layer": attn_bwd_ms, "ppo_update": update, "extra_score_shapes": extra,
         "cpu_baseline": cpu, "setup_s": setup_s,
     }
@@ -380,8 +417,8 @@ def main():
 
 
 def cpu_baseline(cfg, w, queries, mask, wl, n_true):
-    """The oracle, as it stands, on a bounded sample of the same workload: the shortest row of the
-    batch, 4 new tokens (prefill + 3 cached decode passes), then rescoring of that row."""
+    """The oracle, as it stands, on a bounded sample of the same workload: rows 0 and B-1 of the batch (B-1 alone
+    when the batch has one row), 2 new tokens each (prefill + 1 cached decode pass), then rescoring of those rows."""
     import numpy as np
     from oracle import neox_oracle as O
     try:
@@ -389,20 +426,30 @@ def cpu_baseline(cfg, w, queries, mask, wl, n_true):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count()
-    b = int(np.argmin(np.where(n_true > 0, n_true, 1 << 30)))
-    n_new = min(4, wl.new_tokens)
+    B = queries.shape[0]
+    rows = sorted({0, B - 1})
+    n_new = min(2, wl.new_tokens)
     m = O.OracleModel(w, cfg, cache_f64=False)
-    t0 = time.time()
-    toks, lps, lens = O.rollout_generate(m, queries[b:b + 1], mask[b:b + 1], wl.sample_seed, wl.temperature, n_new,
-                                         seq_id_base=b)
-    t_roll = time.time() - t0
-    full = np.concatenate([mask[b:b + 1], (np.arange(n_new)[None, :] < lens[:, None]).astype(np.uint8)], axis=1)
-    t0 = time.time()
-    O.score_sequences(m, toks, full, wl.temperature)
-    t_score = time.time() - t0
-    return {"value": n_new / (t_roll + t_score), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"row {b} (query {int(n_true[b])} tokens), {n_new} new tokens, then rescoring of that row",
-            "generated_tok_s": n_new / t_roll, "rescoring_tok_s": float(full.sum()) / t_score,
+    t_roll = t_score = 0.0
+    n_scored = 0
+    for b in rows:
+        t0 = time.time()
+        toks, lps, lens = O.rollout_generate(m, queries[b:b + 1], mask[b:b + 1], wl.sample_seed, wl.temperature, n_new,
+                                             seq_id_base=b)
+        t_roll += time.time() - t0
+        full = np.concatenate([mask[b:b + 1], (np.arange(n_new)[None, :] < lens[:, None]).astype(np.uint8)], axis=1)
+        t0 = time.time()
+        O.score_sequences(m, toks, full, wl.temperature)
+        t_score += time.time() - t0
+        n_scored += int(full.sum())
+    n_gen = n_new * len(rows)
+    return {"value": n_gen / (t_roll + t_score), "unit": "tokens/s", "cores": int(cores),
+            "kind": "oracle",
+            "oracle_is": "oracle/neox_oracle.py: float64 numpy; its matrix products run on the BLAS that numpy links, "
+                         "everything else is plain numpy",
+            "sample": f"rows {rows} (queries of {[int(n_true[b]) for b in rows]} tokens), {n_new} new tokens each, "
+                      f"then rescoring of those rows",
+            "generated_tok_s": n_gen / t_roll, "rescoring_tok_s": n_scored / t_score,
             "rollout_s": t_roll, "score_s": t_score}
 
 

@@ -46,7 +46,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError(f"link failed:\n{r.stderr}")
     # stand-alone kernel drivers (hardware-counter runs): each links the library's own object
     for drv, obj in (("gemm_driver", "gemm.o gemm_skinny.o"), ("attn_driver", "attention.o"),
-                     ("dec_driver", "gemm.o gemm_skinny.o")):
+                     ("dec_driver", "gemm.o gemm_skinny.o"), ("ceilings_driver", "")):
         drv_obj = os.path.join(objdir, drv + ".o")
         r = subprocess.run([hipcc, *FLAGS, "-c", os.path.join(CSRC, drv + ".hip"), "-o", drv_obj],
                            capture_output=True, text=True)

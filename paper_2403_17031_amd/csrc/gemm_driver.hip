@@ -1,5 +1,6 @@
-// Stand-alone driver for the library's GEMM path at the per-layer shapes of a model: runs QKV, FC1 and
-// the fused out-projection + FC2 product on seeded random operands, checks sampled outputs against a
+// Stand-alone driver for the library's GEMM path at the per-layer shapes of a model: runs QKV (with the
+// epilogue the library runs it with: bias, rotary turn, q rows and K/V cache slots stored; sequences of 352
+// rows each), FC1 and the fused out-projection + FC2 product on seeded random operands, checks sampled outputs against a
 // double-precision dot product on the host, times them with HIP events, and runs a plain copy kernel of
 // known size next to them.  It exists because hardware counters (rocprofv3 --pmc) can be collected on a
 // small native process where they cannot on the Python benchmark; the copy kernel is the yardstick the
@@ -43,7 +44,7 @@ int main(int argc, char** argv) {
   const int d = argc > 3 ? atoi(argv[3]) : 2560, F = 4 * d;
   if (M <= 512 || d % 128 != 0) { printf("M must exceed 512 and d_model be a multiple of 128\n"); return 1; }
   struct Shape { const char* name; int N, K, epi; bool bias2; } shapes[] = {
-      {"qkv", 3 * d, d, EPI_BIAS, false}, {"fc1", F, d, EPI_BIAS_GELU, false}, {"out+fc2", d, d + F, EPI_BIAS_RESADD, true}};
+      {"qkv", 3 * d, d, EPI_QKV, false}, {"fc1", F, d, EPI_BIAS_GELU, false}, {"out+fc2", d, d + F, EPI_BIAS_RESADD, true}};
   const size_t maxA = (size_t)M * (d + F), maxW = (size_t)F * d * 3, maxO = (size_t)M * F;
   std::vector<uint16_t> hA(maxA), hW(maxW), hb(F), hb2(F);
   srand(1);
@@ -58,15 +59,62 @@ int main(int argc, char** argv) {
   CK(hipMemcpy(db, hb.data(), F * 2, hipMemcpyHostToDevice)); CK(hipMemcpy(db2, hb2.data(), F * 2, hipMemcpyHostToDevice));
   CK(hipMemcpy(dM, &M, 4, hipMemcpyHostToDevice));
   hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+  // packing for the QKV epilogue: sequences of Ls rows (the last one shorter), heads of 80 (2.8B shape) or 64
+  const int hd = d % 80 == 0 ? 80 : 64, H = d / hd, r = hd / 4, Ls = 352, nseq = (M + Ls - 1) / Ls, maxpos = 512;
+  std::vector<int> hpos(M + 1000, 0), hrow(M + 1000, 0), hkv(nseq + 1), hlen(nseq);
+  for (int t = 0; t < M; ++t) { hpos[t] = t % Ls; hrow[t] = t / Ls; }
+  for (int b = 0; b <= nseq; ++b) hkv[b] = std::min(b * Ls, M);
+  for (int b = 0; b < nseq; ++b) hlen[b] = hkv[b + 1] - hkv[b];
+  std::vector<float> hcs((size_t)maxpos * (r / 2)), hsn((size_t)maxpos * (r / 2));
+  for (int p = 0; p < maxpos; ++p)
+    for (int i = 0; i < r / 2; ++i) { const double a = p * pow(10000.0, -2.0 * i / r); hcs[(size_t)p * (r / 2) + i] = (float)cos(a); hsn[(size_t)p * (r / 2) + i] = (float)sin(a); }
+  int *dpos, *drow, *dkv, *dlen; float *dcs, *dsn; uint16_t *dq, *dkc, *dvc;
+  CK(hipMalloc(&dpos, hpos.size() * 4)); CK(hipMalloc(&drow, hrow.size() * 4)); CK(hipMalloc(&dkv, hkv.size() * 4)); CK(hipMalloc(&dlen, hlen.size() * 4));
+  CK(hipMalloc(&dcs, hcs.size() * 4)); CK(hipMalloc(&dsn, hsn.size() * 4));
+  CK(hipMalloc(&dq, (size_t)(M + 1000) * d * 2)); CK(hipMalloc(&dkc, (size_t)(M + 1000) * d * 2)); CK(hipMalloc(&dvc, (size_t)(M + 1000) * d * 2));
+  CK(hipMemcpy(dpos, hpos.data(), hpos.size() * 4, hipMemcpyHostToDevice)); CK(hipMemcpy(drow, hrow.data(), hrow.size() * 4, hipMemcpyHostToDevice));
+  CK(hipMemcpy(dkv, hkv.data(), hkv.size() * 4, hipMemcpyHostToDevice)); CK(hipMemcpy(dlen, hlen.data(), hlen.size() * 4, hipMemcpyHostToDevice));
+  CK(hipMemcpy(dcs, hcs.data(), hcs.size() * 4, hipMemcpyHostToDevice)); CK(hipMemcpy(dsn, hsn.data(), hsn.size() * 4, hipMemcpyHostToDevice));
+  QkvArgs qa;
+  qa.pos = dpos; qa.rowid = drow; qa.kvoff = dkv; qa.len = dlen; qa.cos_t = dcs; qa.sin_t = dsn; qa.q = dq; qa.kc = dkc; qa.vc = dvc;
+  qa.kv_extra = 0; qa.pos_add = 0; qa.H = H; qa.hd = hd; qa.r = r;
   int bad = 0;
   for (auto& s : shapes) {
     GemmArgs g;
     g.A = dA; g.W = dW; g.bias = db; g.bias2 = s.bias2 ? db2 : nullptr; g.out = dO;
     g.M_max = M + 1000; g.M_dev = dM; g.N = s.N; g.K = s.K; g.ldo = s.N; g.epilogue = s.epi;
+    if (s.epi == EPI_QKV) {
+      g.qkv = &qa;
+      if (!gemm_takes_qkv(1, g, H, hd, r)) { printf("the QKV epilogue does not take this shape\n"); return 1; }
+    }
     CK(hipMemset(dO, 0, maxO * 4));
     CK(launch_gemm(1, g, 0)); CK(hipDeviceSynchronize());
     const bool f32out = s.epi == EPI_BIAS_RESADD;
     std::vector<uint16_t> ho16; std::vector<float> ho32;
+    if (s.epi == EPI_QKV) {
+      // checked on the V section (no rotary turn): value (t, head h, e) sits at cache row kvoff[b]*H + h*len[b] + pos
+      std::vector<uint16_t> hv((size_t)M * d);
+      CK(hipMemcpy(hv.data(), dvc, hv.size() * 2, hipMemcpyDeviceToHost));
+      double maxerr = 0;
+      for (int t = 0; t < 400 && !bad; ++t) {
+        const int row = t < 4 ? (t % 2 ? M - 1 : 0) : rand() % M, c = 2 * d + (t < 4 ? (t < 2 ? 0 : d - 1) : rand() % d);
+        double acc = 0;
+        for (int k = 0; k < s.K; ++k) acc += (double)h2f(hA[(size_t)row * s.K + k]) * h2f(hW[(size_t)c * s.K + k]);
+        acc += bf2f(hb[c]);
+        const int b = hrow[row], hh = (c - 2 * d) / hd, e = (c - 2 * d) % hd;
+        const size_t slot = (size_t)hkv[b] * H + (size_t)hh * hlen[b] + hpos[row];
+        const double got = h2f(hv[slot * hd + e]), err = fabs(got - acc);
+        if (err > maxerr) maxerr = err;
+        if (err > 8e-3 * fmax(1.0, fabs(acc))) { printf("MISMATCH %s r=%d c=%d got %f want %f\n", s.name, row, c, got, acc); ++bad; }
+      }
+      CK(hipEventRecord(e0, 0));
+      for (int i = 0; i < reps; ++i) CK(launch_gemm(1, g, 0));
+      CK(hipEventRecord(e1, 0)); CK(hipEventSynchronize(e1));
+      float ms; CK(hipEventElapsedTime(&ms, e0, e1)); ms /= reps;
+      printf("%-8s M=%d N=%d K=%d: %.3f ms  %.1f TFLOP/s  algorithmic HBM bytes %.3f GB  max |err| %.2e\n", s.name, M, s.N,
+             s.K, ms, 2.0 * M * s.N * s.K / ms / 1e9, (2.0 * ((double)M * s.K + (double)s.N * s.K) + 2.0 * M * s.N) / 1e9, maxerr);
+      continue;
+    }
     if (f32out) { ho32.resize((size_t)M * s.N); CK(hipMemcpy(ho32.data(), dO, ho32.size() * 4, hipMemcpyDeviceToHost)); }
     else { ho16.resize((size_t)M * s.N); CK(hipMemcpy(ho16.data(), dO, ho16.size() * 2, hipMemcpyDeviceToHost)); }
     double maxerr = 0;

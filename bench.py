@@ -309,48 +309,32 @@ def main():
                                            "avg_launch_ms": attn_bwd_ms, "rows": T_ab}
         del qkvg, ab
 
-    # One PPO update pass over the rollout batch (outside the headline metric): the forward pass that keeps the
-    # layer inputs, the whole backward pass from synthetic loss gradients on the response positions, and AdamW over
-    # every weight.  Config 5 (6.9B) is skipped: weights, optimizer state and kept activations exceed one GPU.
+    # One iteration of the PPO update over the rollout batch through rlhf_ppo_update (outside the headline metric):
+    # forward pass keeping the layer inputs, the clipped objective, the whole backward pass, AdamW over every weight
+    # and the refresh of the fp16 weight image; the paper's update is K = 4 such iterations.  Advantages and returns
+    # are synthetic, the old log-probs and values are the rollout's own.  Config 5 (6.9B) is skipped: weights,
+    # optimizer state and kept activations exceed one GPU.
     update = None
     if not a.no_update_leg and cfg.n_layers > 0 and cfg.dtype != "fp32" and bwd_legs:
         toks_u, mask_u = r[0], r[3]
-        Lu = toks_u.shape[1]
-        mb = mask_u.bool()
-        bt = mb.nonzero()                                # packed order: by sequence, then position
-        bb, tt = bt[:, 0], bt[:, 1]
-        T_u = int(bt.shape[0])
-        t1 = torch.clamp(tt + 1, max=Lu - 1)
-        nxt = (tt + 1 < Lu) & mb[bb, t1] & (tt + 1 >= Lq)  # rows that predict a response token
-        tgt_u = torch.where(nxt, toks_u[bb, t1], torch.full_like(tt, -1, dtype=torch.int32)).to(torch.int32)
-        gl_u = torch.where(nxt, torch.randn(T_u, device="cuda", generator=g_hb) / (B * N), torch.zeros(T_u, device="cuda"))
-        gv_u = torch.where(nxt, torch.randn(T_u, device="cuda", generator=g_hb) / (B * N), torch.zeros(T_u, device="cuda"))
-        state = {}
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-        for it in range(2):                              # one untimed pass, one timed
-            ev[0].record()
-            x_keep, cu_u, ptok_u = pol.forward_keep(toks_u, mask_u)
-            ev[1].record()
-            grads = pol.policy_backward(x_keep, cu_u, ptok_u, tgt_u, gl_u, gv_u, wl.temperature, grad_scale=64.0 * B * N)
-            ev[2].record()
-            for name, gten in grads.items():
-                if name not in state:
-                    wt = pol._dev[name] if name in pol._dev else torch.zeros(1, device="cuda")
-                    state[name] = (wt.float().reshape(gten.shape).contiguous(), torch.zeros_like(gten),
-                                   torch.zeros_like(gten))
-                p32, m1, m2 = state[name]
-                P.adamw_step(p32, gten, m1, m2, it + 1, grad_scale=64.0 * B * N,
-                             param_bf16=pol._dev[name] if name in pol._dev and pol._dev[name].dtype == torch.bfloat16 else None)
-            pol.refresh_weights()                        # the matrix products read an fp16 image of the new weights
-            ev[3].record()
-            del x_keep, grads
+        adv_u = torch.randn(B, N, device="cuda", generator=g_hb)
+        ret_u = torch.randn(B, N, device="cuda", generator=g_hb)
+        oldv_u = val_d[:, Lq - 1:Lq - 1 + N].contiguous()
+        kept_u = r[2]
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        for it in range(2):                              # one untimed iteration, one timed
+            if it == 1:
+                ev[0].record()
+            st_u = pol.ppo_update(toks_u, mask_u, Lq, lps_d, adv_u, oldv_u, ret_u, kept_u, wl.temperature, epochs=1,
+                                  n_minibatches=1)
+        ev[1].record()
         torch.cuda.synchronize()
-        f_ms, b_ms, o_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), ev[2].elapsed_time(ev[3])
-        upd_ms = f_ms + b_ms + o_ms
-        update = {"forward_keep_ms": f_ms, "policy_backward_ms": b_ms, "adamw_ms": o_ms, "total_ms": upd_ms, "rows": T_u,
+        upd_ms = ev[0].elapsed_time(ev[1])
+        update = {"iteration_ms": upd_ms, "rows": int(mask_u.sum().item()), "loss": float(st_u[0, 0]),
                   "tflops": 3.0 * wc["score_flops"] / (upd_ms * 1e-3) / 1e12,
-                  "note": "3 x the scoring pass's flops (forward + twice that for the gradients) over the time of one pass"}
-        del state
+                  "note": "one of the K = 4 iterations of an update; 3 x the scoring pass's flops (forward + twice "
+                          "that for the gradients) over its time, AdamW and the weight-image refresh included"}
+        pol._train = None
 
     # The paper's other scoring shapes (reward-model batches of 638 tokens, long-context batches of 2021),
     # right-padded with true lengths uniform in [L/4, L]; outside the headline metric.

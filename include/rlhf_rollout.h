@@ -334,6 +334,49 @@ int rlhf_policy_backward(rlhf_handle *h, const float *x_keep, int64_t x_keep_lay
                          const float *d_logprobs, const float *d_values, float temperature, float grad_scale,
                          const rlhf_grads *grads, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- One PPO update on a rollout batch: K update iterations over mini-batches (paper: PPO hyperparameter table --
+ * "K (Number of PPO Update Iteration Per Epoch) 4", "N_mb Number of Mini-batches 1", AdamW (eps 1e-5, lr 3e-6),
+ * linear scheduler, clipping coefficients 0.2, c1 0.1, value function loss clipping; PPO Details for the model with
+ * its scalar head).  For iteration k < epochs and mini-batch j < n_minibatches (rows j*B/n_minibatches ... of the
+ * batch, in row order): the forward pass of the CURRENT weights over tokens / mask (as score_sequences, at
+ * `temperature`), keeping the layer inputs; rlhf_ppo_loss of the new log-probs of the N response tokens and the new
+ * values at the positions that emitted them (columns Lq-1 .. Lq+N-2) against the rollout's old_logprobs / old_values,
+ * advantages, returns and kept [B,N] / [B]; rlhf_policy_backward; rlhf_adamw_step on every tensor with step number
+ * first_step + (optimizer steps taken so far in this call) and the given lr (constant within the call: the linear
+ * schedule moves once per rollout batch); rlhf_refresh_weights.  The 8 loss statistics of every (k, j) go to
+ * out_stats dev float [epochs * n_minibatches, 8].
+ *
+ * rlhf_train_state: DEVICE float arrays shaped like the weights, in four rlhf_grads-style sets (per-layer members
+ * HOST arrays of n_layers device pointers): `grads` (scratch, overwritten), `exp_avg` / `exp_avg_sq` (the optimizer's
+ * moments, updated in place) and `master` (bf16 model: the fp32 master weights, updated in place, from which the
+ * caller's bf16 weight arrays -- the ones given to rlhf_create -- are rewritten; fp32 model: unused except value_b,
+ * the weight arrays themselves are updated).  THE CALL WRITES THE CALLER'S WEIGHT ARRAYS.  value_b: a device float in
+ * each set; master.value_b must hold the model's value bias on entry, and from the first call on the handle reads the
+ * bias from there (it must outlive the handle) instead of rlhf_weights.value_b.
+ * minibatch_tokens: HOST int32 [n_minibatches], the number of real tokens (mask == 1) of each mini-batch; max_len
+ * (host): at least the longest row.  grad_scale: see rlhf_head_backward (64 x the kept response tokens of a
+ * mini-batch is a good value in bf16 mode; 1 in fp32 mode).  Workspace size from rlhf_ppo_update_workspace_bytes
+ * (B_minibatch = B / n_minibatches, L = Lq + N, T_max = the largest entry of minibatch_tokens).  Everything is
+ * enqueued on `stream`; no host synchronisation. */
+typedef struct {
+  int32_t epochs, n_minibatches;            /* the paper: 4, 1 */
+  float cliprange, cliprange_value, vf_coef; /* 0.2, 0.2, 0.1 */
+  float temperature;                        /* 0.7: the sampling temperature */
+  double lr, beta1, beta2, eps, weight_decay;
+  int32_t first_step;                       /* >= 1 */
+  float grad_scale;
+} rlhf_ppo_update_config;
+typedef struct {
+  rlhf_grads grads, master, exp_avg, exp_avg_sq;
+} rlhf_train_state;
+int rlhf_ppo_update_workspace_bytes(const rlhf_handle *h, int32_t B_minibatch, int32_t L, int32_t N, int32_t T_max,
+                                    size_t *out);
+int rlhf_ppo_update(rlhf_handle *h, const rlhf_ppo_update_config *cfg, const rlhf_train_state *state,
+                    const int32_t *tokens, const uint8_t *mask, int32_t B, int32_t Lq, int32_t N,
+                    const float *old_logprobs, const float *advantages, const float *old_values, const float *returns,
+                    const int32_t *kept, const int32_t *minibatch_tokens, int32_t max_len, float *out_stats,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
 /* Debug / parity aid: raw (pre-temperature) fp32 logits of the same forward pass as
  * score_sequences at n (row, column) pairs.  rows_bt: HOST int32 [n, 2]; out_logits: dev float
  * [n, vocab].  Every pair must name a real position. */

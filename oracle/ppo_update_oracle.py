@@ -42,8 +42,12 @@ def ppo_update(weights: dict, cfg, tokens, mask, query_len: int, old_logprobs, a
                kept, temperature: float, epochs: int = 4, n_minibatches: int = 1, cliprange: float = 0.2,
                cliprange_value: float = 0.2, vf_coef: float = 0.1, lr: float = 3e-6, beta1: float = 0.9,
                beta2: float = 0.999, eps: float = 1e-5, weight_decay: float = 0.01, first_step: int = 1,
-               state: dict | None = None):
+               state: dict | None = None, storage_round=None):
     """tokens, mask: [B, Lq + N]; old_logprobs, advantages, old_values, returns: [B, N]; kept: [B].
+    storage_round: optional function array -> array.  Mixed-precision training as the paper runs it (bf16) keeps
+    exact master weights for the optimizer while the forward and backward passes read the weights rounded to their
+    storage type; with storage_round given, every pass reads storage_round(master) and the optimizer updates the
+    masters.  None: the passes read the masters themselves.
     Returns (new weights: name -> float64 array, with 'value_b' a float; optimizer state: name ->
     (exp_avg, exp_avg_sq); list of the K * N_mb loss statistics in order)."""
     tokens, mask = np.asarray(tokens), np.asarray(mask)
@@ -60,7 +64,12 @@ def ppo_update(weights: dict, cfg, tokens, mask, query_len: int, old_logprobs, a
     for _ in range(epochs):
         for j in range(n_minibatches):
             r = slice(j * mb, (j + 1) * mb)
-            lp, val = score_sequences(OracleModel(w, cfg, cache_f64=False), tokens[r], mask[r], temperature)
+            if storage_round is None:
+                wf = w
+            else:  # value_b stays a plain scalar: it has no reduced-precision storage copy
+                wf = {k: (np.asarray(storage_round(np.asarray(v, np.float32)), F64) if k != "value_b" else v)
+                      for k, v in w.items()}
+            lp, val = score_sequences(OracleModel(wf, cfg, cache_f64=False), tokens[r], mask[r], temperature)
             new_lp = lp[:, Lq:]
             new_v = val[:, Lq - 1:Lq - 1 + N]
             stats, d_lp, d_v = ppo_loss_oracle.ppo_loss(new_lp, old_logprobs[r], advantages[r], new_v, old_values[r],
@@ -69,7 +78,7 @@ def ppo_update(weights: dict, cfg, tokens, mask, query_len: int, old_logprobs, a
             GL, GV = np.zeros((mb, L), F64), np.zeros((mb, L), F64)
             GL[:, Lq:] = d_lp
             GV[:, Lq - 1:Lq - 1 + N] = d_v
-            grads = policy_backward(w, cfg, tokens[r], mask[r], GL, GV, temperature)
+            grads = policy_backward(wf, cfg, tokens[r], mask[r], GL, GV, temperature)
             for name, g in grads.items():
                 p = np.asarray(w[name], F64)
                 g = np.asarray(g, F64).reshape(p.shape)

@@ -18,6 +18,7 @@ EXPORTS = (
     "rlhf_head_backward", "rlhf_head_backward_workspace_bytes", "rlhf_mlp_backward", "rlhf_mlp_backward_workspace_bytes", "rlhf_attention_backward", "rlhf_forward_keep", "rlhf_policy_backward", "rlhf_policy_backward_workspace_bytes",
     "rlhf_attention_branch_backward", "rlhf_attention_branch_backward_workspace_bytes",
     "rlhf_attention_backward_noalloc", "rlhf_weight_image_bytes", "rlhf_refresh_weights",
+    "rlhf_ppo_update", "rlhf_ppo_update_workspace_bytes",
 )
 
 _PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -43,6 +44,17 @@ class _Grads(C.Structure):  # rlhf_grads: the mirror of rlhf_weights, float arra
     _fields_ = [("embed_in", C.c_void_p)] + [(n, C.POINTER(C.c_void_p)) for n in _PER_LAYER] + \
                [("lnf_g", C.c_void_p), ("lnf_b", C.c_void_p), ("embed_out", C.c_void_p), ("value_w", C.c_void_p),
                 ("value_b", C.c_void_p)]
+
+
+class _UpdateConfig(C.Structure):  # rlhf_ppo_update_config
+    _fields_ = [("epochs", C.c_int32), ("n_minibatches", C.c_int32), ("cliprange", C.c_float),
+                ("cliprange_value", C.c_float), ("vf_coef", C.c_float), ("temperature", C.c_float),
+                ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
+                ("weight_decay", C.c_double), ("first_step", C.c_int32), ("grad_scale", C.c_float)]
+
+
+class _TrainState(C.Structure):  # rlhf_train_state
+    _fields_ = [("grads", _Grads), ("master", _Grads), ("exp_avg", _Grads), ("exp_avg_sq", _Grads)]
 
 
 _lib = None
@@ -88,6 +100,9 @@ def load_library():
     lib.rlhf_policy_backward.argtypes = [vp, vp, C.c_int64, vp, vp, i32, i32, i32, vp, vp, vp, C.c_float, C.c_float,
                                          C.POINTER(_Grads), vp, C.c_size_t, vp]
     lib.rlhf_attention_backward.argtypes = [vp] * 5 + [i32] * 6 + [vp] * 5 + [vp]
+    lib.rlhf_ppo_update_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz)]
+    lib.rlhf_ppo_update.argtypes = [vp, C.POINTER(_UpdateConfig), C.POINTER(_TrainState), vp, vp, i32, i32, i32,
+                                    vp, vp, vp, vp, vp, C.POINTER(i32), i32, vp, vp, sz, vp]
     lib.rlhf_attention_backward_noalloc.argtypes = [vp] * 5 + [i32] * 6 + [vp] * 3 + [vp]
     lib.rlhf_adamw_step.argtypes = [vp, vp, vp, vp, vp, u64, i32] + [C.c_double] * 6 + [vp]
     lib.rlhf_last_error.restype = C.c_char_p
@@ -140,6 +155,8 @@ class Policy:
             setattr(w, n, self._dev[n].data_ptr())
         w.value_w = self._dev["value_w"].data_ptr() if "value_w" in self._dev else None
         w.value_b = float(weights.get("value_b", 0.0))
+        self._value_b = float(weights.get("value_b", 0.0))
+        self._train = None
         self._has_value = "value_w" in self._dev
         self._h = C.c_void_p()
         nimg = C.c_size_t()
@@ -365,6 +382,76 @@ class Policy:
                                                  gl.data_ptr(), gv.data_ptr() if gv is not None else None, temperature,
                                                  grad_scale, C.byref(g), ws.data_ptr(), ws.numel(), self._stream()))
         return res
+
+    # ------------------------------------------------------------------ training
+    def _grads_struct(self, tensors, keep):
+        """An rlhf_grads-shaped struct over {weight name: CUDA float32 tensor} (with a [1] tensor 'value_b')."""
+        g = _Grads()
+        for n in _PER_LAYER:
+            arr = (C.c_void_p * max(self.cfg.n_layers, 1))(*[tensors[f"layers.{l}.{n}"].data_ptr()
+                                                             for l in range(self.cfg.n_layers)])
+            keep.append(arr)
+            setattr(g, n, C.cast(arr, C.POINTER(C.c_void_p)))
+        for n in ("embed_in", "lnf_g", "lnf_b", "embed_out", "value_w", "value_b"):
+            setattr(g, n, tensors[n].data_ptr())
+        return g
+
+    def train_state(self):
+        """Allocates (once) what rlhf_ppo_update keeps between calls: fp32 master weights initialised from the
+        model's weights, zero moments and gradient buffers.  Returns the dict of dicts of CUDA tensors."""
+        torch = self.torch
+        if getattr(self, "_train", None) is None:
+            if not self._has_value:
+                raise RlhfError("the update needs a model with a value head")
+            names = [n for n in self._dev]
+            master = {n: self._dev[n].float().contiguous() for n in names}
+            master["value_b"] = torch.full((1,), self._value_b, dtype=torch.float32, device=self.device)
+            zeros = lambda: {n: torch.zeros_like(t) for n, t in master.items()}
+            self._train = dict(master=master, exp_avg=zeros(), exp_avg_sq=zeros(), grads=zeros(), steps=0)
+        return self._train
+
+    def ppo_update(self, tokens, mask, query_len, old_logprobs, advantages, old_values, returns, kept, temperature,
+                   epochs=4, n_minibatches=1, cliprange=0.2, cliprange_value=0.2, vf_coef=0.1, lr=3e-6, beta1=0.9,
+                   beta2=0.999, eps=1e-5, weight_decay=0.01, grad_scale=None):
+        """One PPO update (K iterations over mini-batches) through rlhf_ppo_update.  tokens int32 / mask uint8
+        [B, Lq+N]; old_logprobs, advantages, old_values, returns float32 [B, N]; kept int32 [B].  Updates this
+        policy's weights in place (and the optimizer state from train_state()).  Returns the loss statistics, a
+        CUDA float tensor [epochs * n_minibatches, 8] in the order of PPO_LOSS_STATS."""
+        torch = self.torch
+        t = self._to_dev(tokens, torch.int32)
+        m = self._to_dev(mask, torch.uint8)
+        B, L = t.shape
+        Lq = int(query_len)
+        N = L - Lq
+        arrs = [self._to_dev(a, torch.float32) for a in (old_logprobs, advantages, old_values, returns)]
+        if any(tuple(a.shape) != (B, N) for a in arrs):
+            raise RlhfError("ppo_update: old_logprobs, advantages, old_values and returns must be [B, L - query_len]")
+        k = self._to_dev(kept, torch.int32)
+        if B % n_minibatches:
+            raise RlhfError("ppo_update: n_minibatches must divide the batch")
+        Bm = B // n_minibatches
+        counts = m.view(n_minibatches, Bm * L).sum(1, dtype=torch.int32).cpu().numpy().astype(np.int32)
+        max_len = int(m.sum(1).max().item())
+        n_kept = int(k.clamp(min=0, max=N).view(n_minibatches, Bm).sum(1).max().item())
+        if grad_scale is None:
+            grad_scale = 1.0 if self.cfg.dtype == "fp32" else 64.0 * max(n_kept, 1)
+        st = self.train_state()
+        keep = []
+        ts = _TrainState(self._grads_struct(st["grads"], keep), self._grads_struct(st["master"], keep),
+                         self._grads_struct(st["exp_avg"], keep), self._grads_struct(st["exp_avg_sq"], keep))
+        uc = _UpdateConfig(epochs, n_minibatches, cliprange, cliprange_value, vf_coef, temperature, lr, beta1, beta2, eps,
+                           weight_decay, st["steps"] + 1, grad_scale)
+        need = C.c_size_t()
+        _check(self.lib.rlhf_ppo_update_workspace_bytes(self._h, Bm, L, N, int(counts.max()), C.byref(need)))
+        ws = self._workspace(need.value)
+        stats = torch.empty((epochs * n_minibatches, 8), dtype=torch.float32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(self.lib.rlhf_ppo_update(self._h, C.byref(uc), C.byref(ts), t.data_ptr(), m.data_ptr(), B, Lq, N,
+                                            *[a.data_ptr() for a in arrs], k.data_ptr(),
+                                            counts.ctypes.data_as(C.POINTER(C.c_int32)), max(max_len, 1),
+                                            stats.data_ptr(), ws.data_ptr(), ws.numel(), self._stream()))
+        st["steps"] += epochs * n_minibatches
+        return stats
 
     def debug_logits_rows(self, tokens, mask, rows_bt):
         torch = self.torch

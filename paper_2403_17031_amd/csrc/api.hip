@@ -81,6 +81,8 @@ struct rlhf_handle {
   // stride), so that prefill / scoring can run them as a single product over K = d + d_ff
   int ld_o2 = 0;
   size_t esz = 2;
+  // once an update has run, the value head's bias lives on the device (the optimizer updates it there)
+  const float* value_b_dev = nullptr;
   // profiling
   bool prof_on = false;
   std::vector<const char*> prof_names;
@@ -260,13 +262,14 @@ struct PassArgs {
   // keep + l * keep_stride (rows_max rows), and the stream after the last layer to slot n_layers.
   float* keep = nullptr;
   size_t keep_stride = 0;
+  size_t keep_rows = 0;
 };
 
 int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) {
   const rlhf_model_config& c = h->cfg;
   if (c.n_layers == 0) {  // nothing to run (and no layer 0 to take shapes from below)
     if (p.keep)
-      HIP_OK(hipMemcpyAsync(p.keep, A.x, (size_t)p.rows_max * c.d_model * sizeof(float), hipMemcpyDeviceToDevice, s));
+      HIP_OK(hipMemcpyAsync(p.keep, A.x, p.keep_rows * c.d_model * sizeof(float), hipMemcpyDeviceToDevice, s));
     return RLHF_OK;
   }
   const int d = c.d_model, dt = c.dtype;
@@ -334,7 +337,7 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
 
   for (int l = 0; l < c.n_layers; ++l) {
     if (p.keep)
-      HIP_OK(hipMemcpyAsync(p.keep + (size_t)l * p.keep_stride, A.x, (size_t)p.rows_max * d * sizeof(float),
+      HIP_OK(hipMemcpyAsync(p.keep + (size_t)l * p.keep_stride, A.x, p.keep_rows * d * sizeof(float),
                             hipMemcpyDeviceToDevice, s));
     char* kc = p.kv + (p.kv_per_layer ? (size_t)l * 2 * plane : 0);
     char* vc = kc + plane;
@@ -471,7 +474,7 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
     }
   }
   if (p.keep)
-    HIP_OK(hipMemcpyAsync(p.keep + (size_t)c.n_layers * p.keep_stride, A.x, (size_t)p.rows_max * d * sizeof(float),
+    HIP_OK(hipMemcpyAsync(p.keep + (size_t)c.n_layers * p.keep_stride, A.x, p.keep_rows * d * sizeof(float),
                           hipMemcpyDeviceToDevice, s));
   return RLHF_OK;
 }
@@ -1185,7 +1188,7 @@ int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_
 }
 
 static int score_forward(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, int B, int L, ScoreWs& ws,
-                         hipStream_t s, float* keep = nullptr) {
+                         hipStream_t s, float* keep = nullptr, size_t keep_rows = 0) {
   const rlhf_model_config& c = h->cfg;
   const Meta& m = ws.meta;
   LAUNCH("row_spans", launch_row_spans(mask, B, L, 0, m.start, m.len, m.cu, m.kvoff, m.total, s));
@@ -1210,32 +1213,24 @@ static int score_forward(rlhf_handle* h, const int32_t* tokens, const uint8_t* m
   p.kv_slots = ws.Tmax;
   p.kv_per_layer = false;
   p.keep = keep;
-  p.keep_stride = (size_t)B * L * c.d_model;
+  p.keep_rows = keep_rows ? keep_rows : (size_t)B * L;  // rows copied per layer = row stride of the kept slices
+  p.keep_stride = p.keep_rows * c.d_model;
   return run_layers(h, ws.acts, p, s);
 }
 
-int score_sequences(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, int32_t B, int32_t L,
-                    float temperature, float* out_logprobs, float* out_values, void* workspace,
-                    size_t workspace_bytes, void* stream) {
-  int rc = check_common(h, B, L);
-  if (rc) return rc;
-  if (!tokens || !mask || !out_logprobs || !workspace) return fail(RLHF_EINVAL, "null pointer argument");
-  if (!(temperature > 0.f) || !std::isfinite(temperature)) return fail(RLHF_EINVAL, "temperature must be > 0");
+// After score_forward: final LayerNorm + value head, LM head + log-softmax of the next token, and the packed ->
+// padded [B, L] outputs.
+static int score_tail(rlhf_handle* h, int B, int L, float temperature, ScoreWs& ws, float* out_logprobs,
+                      float* out_values, hipStream_t s) {
   const rlhf_model_config& c = h->cfg;
-  Carver cv((void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255));
-  ScoreWs ws = carve_score(cv, c, B, L, h->esz);
-  if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
-    return fail(RLHF_ENOMEM, "workspace too small for score_sequences");
-  hipStream_t s = (hipStream_t)stream;
-  rc = score_forward(h, tokens, mask, B, L, ws, s);
-  if (rc) return rc;
   const Meta& m = ws.meta;
   const int dt = c.dtype, d = c.d_model;
   const int Tmax = B * L;
+  const bool want_val = out_values && h->w.value_w;
   // final LayerNorm of every packed row (into the LN1 buffer, free by now) + value head
   LAUNCH("final_ln", launch_final_ln(dt, ws.acts.x, nullptr, 0, Tmax, m.total, d, c.ln_eps, h->w.lnf_g,
-                                     h->w.lnf_b, ws.acts.a, out_values ? h->w.value_w : nullptr, h->w.value_b,
-                                     ws.val, s));
+                                     h->w.lnf_b, ws.acts.a, want_val ? h->w.value_w : nullptr,
+                                     h->value_b_dev ? 0.f : h->w.value_b, ws.val, s));
   // LM head + log-softmax.  With enough rows for the large-M kernel the logits never leave the
   // accumulators: its epilogue reduces every part of a row (one wave's columns) to (max, sum of exp) and
   // picks out the target token's logit, and a small kernel combines the parts.  Otherwise the
@@ -1263,10 +1258,27 @@ int score_sequences(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, 
     LAUNCH("lse_gather", launch_lse_gather(ws.logits, rows, t0, m.total, c.vocab, temperature, m.tok, m.pos, ws.lp,
                                            s));
   }
-  LAUNCH("unpack_scores", launch_unpack_scores(ws.lp, (out_values && h->w.value_w) ? ws.val : nullptr, B, L, m.start,
-                                               m.len, m.cu, out_logprobs,
-                                               (out_values && h->w.value_w) ? out_values : nullptr, s));
+  LAUNCH("unpack_scores", launch_unpack_scores(ws.lp, want_val ? ws.val : nullptr, B, L, m.start, m.len, m.cu,
+                                               out_logprobs, want_val ? out_values : nullptr, s,
+                                               want_val ? h->value_b_dev : nullptr));
   return RLHF_OK;
+}
+
+int score_sequences(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, int32_t B, int32_t L,
+                    float temperature, float* out_logprobs, float* out_values, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+  int rc = check_common(h, B, L);
+  if (rc) return rc;
+  if (!tokens || !mask || !out_logprobs || !workspace) return fail(RLHF_EINVAL, "null pointer argument");
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return fail(RLHF_EINVAL, "temperature must be > 0");
+  Carver cv((void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255));
+  ScoreWs ws = carve_score(cv, h->cfg, B, L, h->esz);
+  if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
+    return fail(RLHF_ENOMEM, "workspace too small for score_sequences");
+  hipStream_t s = (hipStream_t)stream;
+  rc = score_forward(h, tokens, mask, B, L, ws, s);
+  if (rc) return rc;
+  return score_tail(h, B, L, temperature, ws, out_logprobs, out_values, s);
 }
 
 int rlhf_forward_keep(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, int32_t B, int32_t L, float* x_keep,
@@ -1353,6 +1365,152 @@ int rlhf_policy_backward(rlhf_handle* h, const float* x_keep, int64_t x_keep_lay
     std::swap(dx, dx_n);
   }
   LAUNCH("embed_backward", launch_embed_backward(packed_tokens, dx, T, c.d_model, c.vocab, g->embed_in, s));
+  return RLHF_OK;
+}
+
+namespace {
+struct UpdateWs {
+  ScoreWs score;
+  float *x_keep, *lp_full, *val_full, *new_lp, *new_v, *d_lp, *d_v, *gl, *gv;
+  int32_t* targets;
+  void* bwd;
+  size_t bwd_bytes;
+};
+UpdateWs carve_update(Carver& c, const rlhf_handle* h, int Bm, int L, int N, int T_max) {
+  UpdateWs w;
+  const rlhf_model_config& cfg = h->cfg;
+  w.score = carve_score(c, cfg, Bm, L, h->esz);
+  w.x_keep = c.take<float>((size_t)(cfg.n_layers + 1) * T_max * cfg.d_model);
+  w.lp_full = c.take<float>((size_t)Bm * L);
+  w.val_full = c.take<float>((size_t)Bm * L);
+  w.new_lp = c.take<float>((size_t)Bm * N);
+  w.new_v = c.take<float>((size_t)Bm * N);
+  w.d_lp = c.take<float>((size_t)Bm * N);
+  w.d_v = c.take<float>((size_t)Bm * N);
+  w.gl = c.take<float>((size_t)T_max);
+  w.gv = c.take<float>((size_t)T_max);
+  w.targets = c.take<int32_t>((size_t)T_max);
+  size_t b = 0;
+  (void)rlhf_policy_backward_workspace_bytes(h, T_max, &b);
+  w.bwd_bytes = b;
+  w.bwd = c.take_bytes(b);
+  return w;
+}
+}  // namespace
+
+int rlhf_ppo_update_workspace_bytes(const rlhf_handle* h, int32_t B_minibatch, int32_t L, int32_t N, int32_t T_max,
+                                    size_t* out) {
+  if (!h || !out) return fail(RLHF_EINVAL, "null argument");
+  if (B_minibatch <= 0 || L <= 0 || N <= 0 || N > L || T_max <= 0 || (size_t)T_max > (size_t)B_minibatch * L)
+    return fail(RLHF_EINVAL, "bad mini-batch shape");
+  Carver c(nullptr);
+  carve_update(c, h, B_minibatch, L, N, T_max);
+  *out = c.off + 256;
+  return RLHF_OK;
+}
+
+int rlhf_ppo_update(rlhf_handle* h, const rlhf_ppo_update_config* cfg, const rlhf_train_state* st,
+                    const int32_t* tokens, const uint8_t* mask, int32_t B, int32_t Lq, int32_t N,
+                    const float* old_logprobs, const float* advantages, const float* old_values, const float* returns,
+                    const int32_t* kept, const int32_t* minibatch_tokens, int32_t max_len, float* out_stats,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  if (!h || !cfg || !st) return fail(RLHF_EINVAL, "null argument");
+  const rlhf_model_config& c = h->cfg;
+  if (!tokens || !mask || !old_logprobs || !advantages || !old_values || !returns || !kept || !minibatch_tokens ||
+      !out_stats || !workspace)
+    return fail(RLHF_EINVAL, "null pointer argument");
+  if (B <= 0 || Lq <= 0 || N <= 0) return fail(RLHF_EINVAL, "batch, query length and response length must be positive");
+  if (cfg->epochs <= 0 || cfg->n_minibatches <= 0 || B % cfg->n_minibatches != 0)
+    return fail(RLHF_EINVAL, "epochs and n_minibatches must be positive and n_minibatches must divide the batch");
+  if (cfg->first_step < 1) return fail(RLHF_EINVAL, "first_step counts from 1");
+  if (!(cfg->temperature > 0.f) || !std::isfinite(cfg->temperature)) return fail(RLHF_EINVAL, "temperature must be > 0");
+  if (!(cfg->grad_scale > 0.f) || !std::isfinite(cfg->grad_scale)) return fail(RLHF_EINVAL, "grad_scale must be finite and > 0");
+  if (!h->w.value_w) return fail(RLHF_EUNSUPPORTED, "the update trains the value head as well: the model needs one");
+  const int L = Lq + N, Bm = B / cfg->n_minibatches;
+  int rc = check_common(h, Bm, L);
+  if (rc) return rc;
+  int T_max = 0;
+  for (int j = 0; j < cfg->n_minibatches; ++j) {
+    if (minibatch_tokens[j] <= 0 || (size_t)minibatch_tokens[j] > (size_t)Bm * L)
+      return fail(RLHF_EINVAL, "minibatch_tokens: every mini-batch needs between 1 and B_minibatch * L real tokens");
+    T_max = std::max(T_max, minibatch_tokens[j]);
+  }
+  const bool bf16 = c.dtype == RLHF_DTYPE_BF16;
+  // ---- every trainable tensor: the caller's weight array, its gradient buffer and optimizer state
+  struct Tensor { void* weight; float *grad, *master, *m, *v; size_t n; };
+  std::vector<Tensor> ts;
+  const size_t d = c.d_model, F = c.d_ff, V = c.vocab;
+  auto add = [&](const void* wt, float* g, float* ms, float* m, float* v, size_t n) {
+    ts.push_back(Tensor{(void*)wt, g, ms, m, v, n});
+  };
+  const rlhf_grads &G = st->grads, &P = st->master, &M1 = st->exp_avg, &M2 = st->exp_avg_sq;
+  add(h->w.embed_in, G.embed_in, P.embed_in, M1.embed_in, M2.embed_in, V * d);
+  add(h->w.embed_out, G.embed_out, P.embed_out, M1.embed_out, M2.embed_out, V * d);
+  add(h->w.lnf_g, G.lnf_g, P.lnf_g, M1.lnf_g, M2.lnf_g, d);
+  add(h->w.lnf_b, G.lnf_b, P.lnf_b, M1.lnf_b, M2.lnf_b, d);
+  add(h->w.value_w, G.value_w, P.value_w, M1.value_w, M2.value_w, d);
+  float* const* gl_[12] = {G.ln1_g, G.ln1_b, G.ln2_g, G.ln2_b, G.w_qkv, G.b_qkv, G.w_o, G.b_o, G.w_fc1, G.b_fc1, G.w_fc2, G.b_fc2};
+  float* const* pl_[12] = {P.ln1_g, P.ln1_b, P.ln2_g, P.ln2_b, P.w_qkv, P.b_qkv, P.w_o, P.b_o, P.w_fc1, P.b_fc1, P.w_fc2, P.b_fc2};
+  float* const* ml_[12] = {M1.ln1_g, M1.ln1_b, M1.ln2_g, M1.ln2_b, M1.w_qkv, M1.b_qkv, M1.w_o, M1.b_o, M1.w_fc1, M1.b_fc1, M1.w_fc2, M1.b_fc2};
+  float* const* vl_[12] = {M2.ln1_g, M2.ln1_b, M2.ln2_g, M2.ln2_b, M2.w_qkv, M2.b_qkv, M2.w_o, M2.b_o, M2.w_fc1, M2.b_fc1, M2.w_fc2, M2.b_fc2};
+  const std::vector<const void*>* wl_[12] = {&h->ln1_g, &h->ln1_b, &h->ln2_g, &h->ln2_b, &h->src_w_qkv, &h->src_b_qkv,
+                                            &h->src_w_o, &h->b_o, &h->src_w_fc1, &h->b_fc1, &h->src_w_fc2, &h->b_fc2};
+  const size_t nl_[12] = {d, d, d, d, 3 * d * d, 3 * d, d * d, d, F * d, F, d * F, d};
+  for (int i = 0; i < 12; ++i) {
+    if (c.n_layers > 0 && (!gl_[i] || !ml_[i] || !vl_[i] || (bf16 && !pl_[i])))
+      return fail(RLHF_EINVAL, "null per-layer array in the training state");
+    for (int l = 0; l < c.n_layers; ++l)
+      add((*wl_[i])[l], gl_[i][l], bf16 ? pl_[i][l] : nullptr, ml_[i][l], vl_[i][l], nl_[i]);
+  }
+  for (const Tensor& t : ts)
+    if (!t.weight || !t.grad || !t.m || !t.v || (bf16 && !t.master))
+      return fail(RLHF_EINVAL, "null tensor in the training state");
+  if (!G.value_b || !P.value_b || !M1.value_b || !M2.value_b)
+    return fail(RLHF_EINVAL, "the value bias needs a gradient, a master copy and both moments (device floats)");
+  Carver cv((void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255));
+  UpdateWs ws = carve_update(cv, h, Bm, L, N, T_max);
+  if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
+    return fail(RLHF_ENOMEM, "workspace too small for rlhf_ppo_update");
+  hipStream_t s = (hipStream_t)stream;
+  // from here on the value head's bias is the device scalar the optimizer updates
+  h->value_b_dev = P.value_b;
+  int step = cfg->first_step;
+  for (int ep = 0; ep < cfg->epochs; ++ep) {
+    for (int j = 0; j < cfg->n_minibatches; ++j, ++step) {
+      const size_t r0 = (size_t)j * Bm;
+      const int32_t* tok_j = tokens + r0 * L;
+      const uint8_t* mask_j = mask + r0 * L;
+      const int T = minibatch_tokens[j];
+      // forward with the current weights, keeping the layer inputs (packed rows: slices of T rows)
+      rc = score_forward(h, tok_j, mask_j, Bm, L, ws.score, s, ws.x_keep, (size_t)T);
+      if (rc) return rc;
+      rc = score_tail(h, Bm, L, cfg->temperature, ws.score, ws.lp_full, ws.val_full, s);
+      if (rc) return rc;
+      LAUNCH("ppo_glue", launch_ppo_slice(ws.lp_full, ws.val_full, Bm, L, Lq, N, ws.new_lp, ws.new_v, s));
+      float* stats = out_stats + ((size_t)ep * cfg->n_minibatches + j) * 8;
+      LAUNCH("ppo_loss", launch_ppo_loss(ws.new_lp, old_logprobs + r0 * N, advantages + r0 * N, ws.new_v,
+                                         old_values + r0 * N, returns + r0 * N, kept + r0, Bm, N, cfg->cliprange,
+                                         cfg->cliprange_value, cfg->vf_coef, ws.d_lp, ws.d_v, stats, s));
+      const Meta& m = ws.score.meta;
+      LAUNCH("ppo_glue", launch_ppo_pack_grads(tok_j, Bm, L, Lq, N, m.start, m.len, m.cu, ws.d_lp, ws.d_v, ws.targets,
+                                               ws.gl, ws.gv, s));
+      rc = rlhf_policy_backward(h, ws.x_keep, (int64_t)T * c.d_model, m.cu, m.tok, Bm, T, max_len, ws.targets, ws.gl,
+                                ws.gv, cfg->temperature, cfg->grad_scale, &G, ws.bwd, ws.bwd_bytes, stream);
+      if (rc) return rc;
+      // AdamW on every tensor; a bf16 model keeps fp32 masters and gets its storage arrays rewritten
+      const double inv_scale = 1.0 / (double)cfg->grad_scale;
+      for (const Tensor& t : ts) {
+        rc = rlhf_adamw_step(bf16 ? t.master : (float*)t.weight, t.grad, t.m, t.v, bf16 ? (uint16_t*)t.weight : nullptr,
+                             t.n, step, cfg->lr, cfg->beta1, cfg->beta2, cfg->eps, cfg->weight_decay, inv_scale, stream);
+        if (rc) return rc;
+      }
+      rc = rlhf_adamw_step(P.value_b, G.value_b, M1.value_b, M2.value_b, nullptr, 1, step, cfg->lr, cfg->beta1,
+                           cfg->beta2, cfg->eps, cfg->weight_decay, inv_scale, stream);
+      if (rc) return rc;
+      rc = rlhf_refresh_weights(h, stream);
+      if (rc) return rc;
+    }
+  }
   return RLHF_OK;
 }
 

@@ -251,8 +251,11 @@ hipError_t launch_lse_gather(const float* logits, int rows_max, int t0, const in
                              float temperature, const int* tok, const int* pos, float* lp_packed,
                              hipStream_t s);
 // Packed -> padded [B, L] outputs with zeros at masked slots; logprob of a row's first token is 0.
+// val_bias_dev: optional device scalar added to every real position's value (a value-head bias that lives on the
+// device because an optimizer updates it there).
 hipError_t launch_unpack_scores(const float* lp_packed, const float* val_packed, int B, int L, const int* start,
-                                const int* len, const int* cu, float* out_lp, float* out_val, hipStream_t s);
+                                const int* len, const int* cu, float* out_lp, float* out_val, hipStream_t s,
+                                const float* val_bias_dev = nullptr);
 // Gather helper for the debug entry point: idx[i] = cu[b_i] + (col_i - start[b_i]).
 hipError_t launch_rows_to_packed(const int32_t* rows_bt, int n, const int* start, const int* cu, int* idx,
                                  hipStream_t s);
@@ -268,6 +271,16 @@ hipError_t launch_ppo_whiten(const float* x, const int* kept, int B, int N, int 
 hipError_t launch_ppo_loss(const float* lp, const float* lp0, const float* adv, const float* v, const float* v0,
                            const float* ret, const int* kept, int B, int N, float eps, float eps_v, float c1,
                            float* d_lp, float* d_v, float* stats, hipStream_t s);
+// The PPO update's glue between the padded [B, L] outputs of a forward pass and the packed rows of the backward
+// pass.  Slices: new_lp[b, j] = lp_full[b, Lq + j], new_v[b, j] = val_full[b, Lq - 1 + j] (j < N).
+hipError_t launch_ppo_slice(const float* lp_full, const float* val_full, int B, int L, int Lq, int N, float* new_lp,
+                            float* new_v, hipStream_t s);
+// Packed row cu[b] + i holds token (b, c = start[b] + i); it predicts token (b, c + 1):
+//   targets = that token if it is real, else -1;  gl = d_lp[b, c + 1 - Lq] if that is a response position, else 0;
+//   gv = d_v[b, c - (Lq - 1)] if 0 <= c - (Lq - 1) < N, else 0.
+hipError_t launch_ppo_pack_grads(const int32_t* tokens, int B, int L, int Lq, int N, const int* start, const int* len,
+                                 const int* cu, const float* d_lp, const float* d_v, int32_t* targets, float* gl,
+                                 float* gv, hipStream_t s);
 // Optimizer step (optimizer.hip).
 hipError_t launch_adamw(float* p, const float* g, float* m, float* v, uint16_t* p_bf16, size_t n, float decay,
                         float beta1, float omb1, float beta2, float omb2, float step_size, float inv_sqrt_bias2,

@@ -1044,7 +1044,7 @@ hipError_t launch_lse_combine(const LseArgs& a, int rows_max, int nparts, float*
 __global__ void unpack_scores_kernel(const float* __restrict__ lp_packed, const float* __restrict__ val_packed,
                                      int L, const int* __restrict__ start, const int* __restrict__ len,
                                      const int* __restrict__ cu, float* __restrict__ out_lp,
-                                     float* __restrict__ out_val) {
+                                     float* __restrict__ out_val, const float* __restrict__ val_bias_dev) {
   const int b = blockIdx.y;
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= L) return;
@@ -1052,13 +1052,14 @@ __global__ void unpack_scores_kernel(const float* __restrict__ lp_packed, const 
   const bool real = i >= 0 && i < len[b];
   const size_t o = (size_t)b * L + c;
   out_lp[o] = (real && i >= 1) ? lp_packed[cu[b] + i] : 0.f;
-  if (out_val) out_val[o] = real ? val_packed[cu[b] + i] : 0.f;
+  if (out_val) out_val[o] = real ? val_packed[cu[b] + i] + (val_bias_dev ? *val_bias_dev : 0.f) : 0.f;
 }
 
 hipError_t launch_unpack_scores(const float* lp_packed, const float* val_packed, int B, int L, const int* start,
-                                const int* len, const int* cu, float* out_lp, float* out_val, hipStream_t s) {
+                                const int* len, const int* cu, float* out_lp, float* out_val, hipStream_t s,
+                                const float* val_bias_dev) {
   hipLaunchKernelGGL(unpack_scores_kernel, dim3((L + 255) / 256, B), dim3(256), 0, s, lp_packed, val_packed, L,
-                     start, len, cu, out_lp, out_val);
+                     start, len, cu, out_lp, out_val, val_bias_dev);
   return hipGetLastError();
 }
 

@@ -209,4 +209,46 @@ hipError_t launch_ppo_whiten(const float* x, const int* kept, int B, int N, int 
   return hipGetLastError();
 }
 
+// ---- glue of the update loop ------------------------------------------------------------------------------
+__global__ void ppo_slice_kernel(const float* __restrict__ lp_full, const float* __restrict__ val_full, int L, int Lq,
+                                 int N, float* __restrict__ new_lp, float* __restrict__ new_v) {
+  const int b = blockIdx.x;
+  for (int j = threadIdx.x; j < N; j += blockDim.x) {
+    new_lp[(size_t)b * N + j] = lp_full[(size_t)b * L + Lq + j];
+    new_v[(size_t)b * N + j] = (Lq - 1 + j >= 0) ? val_full[(size_t)b * L + Lq - 1 + j] : 0.f;
+  }
+}
+
+hipError_t launch_ppo_slice(const float* lp_full, const float* val_full, int B, int L, int Lq, int N, float* new_lp,
+                            float* new_v, hipStream_t s) {
+  hipLaunchKernelGGL(ppo_slice_kernel, dim3(B), dim3(64), 0, s, lp_full, val_full, L, Lq, N, new_lp, new_v);
+  return hipGetLastError();
+}
+
+__global__ void ppo_pack_grads_kernel(const int32_t* __restrict__ tokens, int L, int Lq, int N,
+                                      const int* __restrict__ start, const int* __restrict__ len,
+                                      const int* __restrict__ cu, const float* __restrict__ d_lp,
+                                      const float* __restrict__ d_v, int32_t* __restrict__ targets,
+                                      float* __restrict__ gl, float* __restrict__ gv) {
+  const int b = blockIdx.x;
+  const int st = start[b], n = len[b], base = cu[b];
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    const int c = st + i;
+    const bool nxt = i + 1 < n;  // the next token of the row is real
+    const int jr = c + 1 - Lq;   // response index of the token this row predicts
+    const int jv = c - (Lq - 1); // response index whose value is read at this position
+    targets[base + i] = nxt ? tokens[(size_t)b * L + c + 1] : -1;
+    gl[base + i] = (nxt && jr >= 0 && jr < N) ? d_lp[(size_t)b * N + jr] : 0.f;
+    gv[base + i] = (jv >= 0 && jv < N) ? d_v[(size_t)b * N + jv] : 0.f;
+  }
+}
+
+hipError_t launch_ppo_pack_grads(const int32_t* tokens, int B, int L, int Lq, int N, const int* start, const int* len,
+                                 const int* cu, const float* d_lp, const float* d_v, int32_t* targets, float* gl,
+                                 float* gv, hipStream_t s) {
+  hipLaunchKernelGGL(ppo_pack_grads_kernel, dim3(B), dim3(256), 0, s, tokens, L, Lq, N, start, len, cu, d_lp, d_v,
+                     targets, gl, gv);
+  return hipGetLastError();
+}
+
 }  // namespace rlhf

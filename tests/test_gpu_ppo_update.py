@@ -92,3 +92,90 @@ def test_one_update_matches_the_oracles_and_lowers_the_loss(gpu):
     stats2, _, _ = gpu.ppo_loss(lp2, old_lp, adv, v2, old_v, ret, kept)
     assert float(stats2[0]) < loss0
     pol2.close()
+
+
+def _loop_case(dtype):
+    cfg = ModelConfig(n_layers=2, d_model=64, n_heads=2, head_dim=32, rotary_dims=8, d_ff=128, vocab=200, dtype=dtype,
+                      pad_id=199, eos_id=1)
+    w = make_weights(cfg, 92, variant="test")
+    g = np.random.default_rng(6)
+    B, Lq, N = 6, 12, 7
+    L = Lq + N
+    tokens = g.integers(2, 190, (B, L)).astype(np.int32)
+    mask = np.ones((B, L), np.uint8)
+    mask[0, :4] = 0
+    mask[3, :9] = 0
+    mask[5, :1] = 0
+    kept = np.array([N, 3, N, 1, 5, N], np.int32)
+    for b in range(B):
+        mask[b, Lq + kept[b]:] = 0
+    tokens[mask == 0] = cfg.pad_id
+    adv = g.normal(0, 1, (B, N)).astype(np.float32)
+    ret = g.normal(0, 1, (B, N)).astype(np.float32)
+    return cfg, w, g, tokens, mask, kept, adv, ret, Lq, N
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_update_loop_matches_the_oracle_loop(gpu, dtype):
+    """rlhf_ppo_update (K = 2 iterations over 2 mini-batches, optimizer steps 1..4) against
+    oracle/ppo_update_oracle.py: the loss statistics of every step, every updated weight, and afterwards the same
+    handle scores with the updated weights.  fp32 check mode: weights to 2 % of one step's size (lr).  bf16 mode:
+    the oracle reads bf16-rounded copies of its exact masters in every pass, as the library does; what remains is
+    the fp16 rounding of operands inside the passes: each tensor's movement to 5 % (Frobenius), losses to 2e-2."""
+    import torch
+    from oracle.neox_oracle import OracleModel, score_sequences
+    from oracle.ppo_update_oracle import ppo_update
+    from synth import round_to_bf16
+    cfg, w, g, tokens, mask, kept, adv, ret, Lq, N = _loop_case(dtype)
+    T_, K, NMB = 0.7, 2, 2
+    hyp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-3, weight_decay=0.01)
+    pol = gpu.Policy(cfg, w)
+    lp0, v0 = (x.cpu().numpy() for x in pol.score_sequences(tokens, mask, T_))
+    old_lp = (lp0[:, Lq:] + g.normal(0, 0.15, lp0[:, Lq:].shape)).astype(np.float32)
+    old_v = (v0[:, Lq - 1:Lq - 1 + N] + g.normal(0, 0.15, (tokens.shape[0], N))).astype(np.float32)
+    stats = pol.ppo_update(tokens, mask, Lq, old_lp, adv, old_v, ret, kept, T_, epochs=K, n_minibatches=NMB, **hyp)
+    stats = stats.cpu().numpy()
+    st = pol.train_state()
+    assert st["steps"] == K * NMB
+    fp32 = dtype == "fp32"
+    o_w, _, o_stats = ppo_update(w, cfg, tokens, mask, Lq, old_lp, adv, old_v, ret, kept, T_, epochs=K, n_minibatches=NMB,
+                                 storage_round=None if fp32 else round_to_bf16, **hyp)
+    for i, s in enumerate(o_stats):
+        assert stats[i, 0] == pytest.approx(s["loss"], rel=1e-4, abs=1e-5 if fp32 else 2e-2), (i, stats[i], s)
+        assert stats[i, 7] == s["n_tokens"]
+    for name, want in o_w.items():
+        got = (st["master"][name] if (not fp32 or name == "value_b") else pol._dev[name]).double().cpu().numpy()
+        want = np.asarray(want, np.float64).reshape(got.shape)
+        start = np.asarray(w[name], np.float64).reshape(got.shape)
+        if fp32:
+            assert np.abs(got - want).max() <= 2e-2 * hyp["lr"], (name, np.abs(got - want).max())
+        else:
+            moved = np.linalg.norm(want - start)
+            assert np.linalg.norm(got - want) <= 5e-2 * moved + 1e-7, (name, np.linalg.norm(got - want), moved)
+            # the storage copy the forward passes read is the rounded master
+            if name != "value_b":
+                assert bool((pol._dev[name].float() == st["master"][name].bfloat16().float()).all()), name
+    # the handle now computes with the updated weights (value bias included: it lives on the device)
+    new_w = {k: (np.asarray(v, np.float64) if fp32 else round_to_bf16(np.asarray(v, np.float32))) for k, v in o_w.items()
+             if k != "value_b"}
+    new_w["value_b"] = np.float32(o_w["value_b"])
+    olp, oval = score_sequences(OracleModel(new_w, cfg), tokens, mask, T_)
+    lp1, v1 = (x.cpu().numpy() for x in pol.score_sequences(tokens, mask, T_))
+    tol = 1e-3 if fp32 else 2e-2
+    np.testing.assert_allclose(lp1, olp, atol=tol, rtol=0)
+    np.testing.assert_allclose(v1, oval, atol=tol * max(1.0, float(np.abs(oval).max())), rtol=0)
+    assert abs(float(st["master"]["value_b"][0]) - float(w["value_b"])) > 1e-4   # the bias moved, and v1 saw it
+    pol.close()
+
+
+def test_update_loop_rejects_bad_arguments(gpu):
+    cfg, w, g, tokens, mask, kept, adv, ret, Lq, N = _loop_case("fp32")
+    pol = gpu.Policy(cfg, w)
+    z = np.zeros((tokens.shape[0], N), np.float32)
+    with pytest.raises(gpu.RlhfError):
+        pol.ppo_update(tokens, mask, Lq, z, adv, z, ret, kept, 0.7, n_minibatches=4)      # 4 does not divide 6
+    with pytest.raises(gpu.RlhfError):
+        pol.ppo_update(tokens, mask, Lq, z, adv, z, ret, kept, 0.0)                       # temperature
+    with pytest.raises(gpu.RlhfError):
+        pol.ppo_update(tokens, mask, Lq, z, adv, z, ret, kept, 0.7, epochs=0)
+    pol.close()

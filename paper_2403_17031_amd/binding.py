@@ -28,6 +28,12 @@ class RlhfError(RuntimeError):
     pass
 
 
+# Debug aid (tests): when True, every Policy fills its workspace and every output it allocates with 0xFF bytes
+# (NaN as fp32 and fp16, -1 as an integer) before each call, so that a kernel reading a region that this call has
+# not written -- which on a reused workspace sees plausible values from the previous call -- shows up in the results.
+POISON = False
+
+
 class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "head_dim", "rotary_dims", "d_ff",
                                          "vocab", "dtype", "eos_id", "pad_id")] + \
@@ -196,7 +202,16 @@ class Policy:
         if self._ws is None or self._ws.numel() < nbytes:
             self._ws = None
             self._ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        if POISON:
+            self._ws.fill_(255)
         return self._ws
+
+    def _out(self, shape, dtype):
+        """An output buffer for a call (poisoned like the workspace when the debug switch is on)."""
+        t = self.torch.empty(shape, dtype=dtype, device=self.device)
+        if POISON:
+            t.view(self.torch.uint8).fill_(255)
+        return t
 
     def _stream(self):
         return C.c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
@@ -213,10 +228,10 @@ class Policy:
         B, Lq = q.shape
         N = int(max_new_tokens)
         ws = self._workspace(self.workspace_bytes(B, Lq, max(N, 1), 0))
-        toks = torch.empty((B, Lq + max(N, 0)), dtype=torch.int32, device=self.device)
-        lps = torch.empty((B, max(N, 0)), dtype=torch.float32, device=self.device)
-        lens = torch.empty((B,), dtype=torch.int32, device=self.device)
-        omask = torch.empty((B, Lq + max(N, 0)), dtype=torch.uint8, device=self.device) if return_mask else None
+        toks = self._out((B, Lq + max(N, 0)), torch.int32)
+        lps = self._out((B, max(N, 0)), torch.float32)
+        lens = self._out((B,), torch.int32)
+        omask = self._out((B, Lq + max(N, 0)), torch.uint8) if return_mask else None
         with torch.cuda.device(self.device):
             _check(self.lib.rollout_generate(self._h, q.data_ptr(), m.data_ptr(), B, Lq, C.c_uint64(seed),
                                              C.c_uint64(seq_id_base), temperature, N, toks.data_ptr(),
@@ -232,8 +247,8 @@ class Policy:
         m = self._to_dev(mask, torch.uint8)
         B, L = t.shape
         ws = self._workspace(self.workspace_bytes(B, 0, 0, L))
-        lp = torch.empty((B, L), dtype=torch.float32, device=self.device)
-        val = torch.empty((B, L), dtype=torch.float32, device=self.device) if want_values else None
+        lp = self._out((B, L), torch.float32)
+        val = self._out((B, L), torch.float32) if want_values else None
         with torch.cuda.device(self.device):
             _check(self.lib.score_sequences(self._h, t.data_ptr(), m.data_ptr(), B, L, temperature, lp.data_ptr(),
                                             val.data_ptr() if want_values else None, ws.data_ptr(), ws.numel(),
@@ -258,7 +273,7 @@ class Policy:
         out = C.c_size_t()
         _check(self.lib.rlhf_head_backward_workspace_bytes(self._h, T, C.byref(out)))
         ws = self._workspace(out.value)
-        new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=self.device)
+        new = lambda *shape: self._out(shape, torch.float32)
         res = dict(d_x=new(T, d), d_lnf_g=new(d), d_lnf_b=new(d), d_embed_out=new(self.cfg.vocab, d))
         if has_v:
             res.update(d_value_w=new(d), d_value_b=new(1))
@@ -283,7 +298,7 @@ class Policy:
         out = C.c_size_t()
         _check(self.lib.rlhf_mlp_backward_workspace_bytes(self._h, T, C.byref(out)))
         ws = self._workspace(out.value)
-        new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=self.device)
+        new = lambda *shape: self._out(shape, torch.float32)
         res = dict(d_x=new(T, d), d_ln2_g=new(d), d_ln2_b=new(d), d_w_fc1=new(F, d), d_b_fc1=new(F),
                    d_w_fc2=new(d, F), d_b_fc2=new(d))
         with torch.cuda.device(self.device):
@@ -310,7 +325,7 @@ class Policy:
         out = C.c_size_t()
         _check(self.lib.rlhf_attention_branch_backward_workspace_bytes(self._h, T, C.byref(out)))
         ws = self._workspace(out.value)
-        new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=self.device)
+        new = lambda *shape: self._out(shape, torch.float32)
         names = ("d_x", "d_ln1_g", "d_ln1_b", "d_w_qkv", "d_b_qkv", "d_w_o", "d_b_o")
         res = dict(d_x=new(T, d), d_ln1_g=new(d), d_ln1_b=new(d), d_w_qkv=new(3 * d, d), d_b_qkv=new(3 * d),
                    d_w_o=new(d, d), d_b_o=new(d))
@@ -329,9 +344,9 @@ class Policy:
         m = self._to_dev(mask, torch.uint8)
         B, L = t.shape
         ws = self._workspace(self.workspace_bytes(B, 0, 0, L))
-        x_keep = torch.empty((self.cfg.n_layers + 1, B * L, self.cfg.d_model), dtype=torch.float32, device=self.device)
-        cu = torch.empty(B + 1, dtype=torch.int32, device=self.device)
-        ptok = torch.empty(B * L, dtype=torch.int32, device=self.device)
+        x_keep = self._out((self.cfg.n_layers + 1, B * L, self.cfg.d_model), torch.float32)
+        cu = self._out((B + 1,), torch.int32)
+        ptok = self._out((B * L,), torch.int32)
         with torch.cuda.device(self.device):
             _check(self.lib.rlhf_forward_keep(self._h, t.data_ptr(), m.data_ptr(), B, L, x_keep.data_ptr(), cu.data_ptr(),
                                               ptok.data_ptr(), ws.data_ptr(), ws.numel(), self._stream()))
@@ -354,7 +369,7 @@ class Policy:
         if y.numel() != T or gl.numel() != T or (gv is not None and gv.numel() != T):
             raise RlhfError("policy_backward: targets, d_logprobs and d_values must have one entry per packed row")
         d, F, V = cfg.d_model, cfg.d_ff, cfg.vocab
-        new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=self.device)
+        new = lambda *shape: self._out(shape, torch.float32)
         shapes = dict(ln1_g=(d,), ln1_b=(d,), ln2_g=(d,), ln2_b=(d,), w_qkv=(3 * d, d), b_qkv=(3 * d,), w_o=(d, d),
                       b_o=(d,), w_fc1=(F, d), b_fc1=(F,), w_fc2=(d, F), b_fc2=(d,))
         res = dict(embed_in=new(V, d), lnf_g=new(d), lnf_b=new(d), embed_out=new(V, d))
@@ -444,7 +459,7 @@ class Policy:
         need = C.c_size_t()
         _check(self.lib.rlhf_ppo_update_workspace_bytes(self._h, Bm, L, N, int(counts.max()), C.byref(need)))
         ws = self._workspace(need.value)
-        stats = torch.empty((epochs * n_minibatches, 8), dtype=torch.float32, device=self.device)
+        stats = self._out((epochs * n_minibatches, 8), torch.float32)
         with torch.cuda.device(self.device):
             _check(self.lib.rlhf_ppo_update(self._h, C.byref(uc), C.byref(ts), t.data_ptr(), m.data_ptr(), B, Lq, N,
                                             *[a.data_ptr() for a in arrs], k.data_ptr(),
@@ -461,7 +476,7 @@ class Policy:
         rows = np.ascontiguousarray(np.asarray(rows_bt, dtype=np.int32).reshape(-1, 2))
         n = rows.shape[0]
         ws = self._workspace(self.workspace_bytes(B, 0, 0, L))
-        out = torch.empty((n, self.cfg.vocab), dtype=torch.float32, device=self.device)
+        out = self._out((n, self.cfg.vocab), torch.float32)
         with torch.cuda.device(self.device):
             _check(self.lib.rlhf_debug_logits_rows(self._h, t.data_ptr(), m.data_ptr(), B, L,
                                                    rows.ctypes.data_as(C.POINTER(C.c_int32)), n, out.data_ptr(),

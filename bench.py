@@ -1,8 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the rollout + rescoring hot path on one MI355X.
 
-One "step" = rollout_generate on a synthetic left-padded query batch, then score_sequences on the
-rollout's own (tokens, mask) output.  Inputs are resident in HBM before the timed region.  Prints
+One "step" = rollout_generate on a synthetic left-padded query batch, then score_responses (the teacher-forced
+forward pass that yields the response positions' log-probabilities and values; --score-all-columns runs
+score_sequences, which also produces the query positions' that PPO never reads) on the rollout's own (tokens,
+mask) output.  Inputs are resident in HBM before the timed region.  Prints
 ONE JSON line (see README for the fields)."""
 import argparse
 import json
@@ -42,8 +44,11 @@ def gemm_traffic_per_row(cfg):
     return float(d["bytes_per_gemm_row"]), d.get("commit")
 
 
-def work_counts(cfg, n, resp, N):
-    """Algorithmic flops / bytes of the workload from the drawn lengths (real tokens only)."""
+def work_counts(cfg, n, resp, N, score_all=False):
+    """Algorithmic flops / bytes of the workload from the drawn lengths (real tokens only).  Unless score_all, the
+    rescoring pass is counted as score_responses needs it: every row through all layers but the last and through
+    the last layer's QKV product; the rows from the last query column on (resp + 1 per sequence) through the last
+    layer's attention, out-projection and MLP; the LM head on the resp rows that predict a response token."""
     import numpy as np
     L, d, F, V = cfg.n_layers, cfg.d_model, cfg.d_ff, cfg.vocab
     es = 4 if cfg.dtype == "fp32" else 2
@@ -62,16 +67,32 @@ def work_counts(cfg, n, resp, N):
     mm_pre = 2 * ((L - 1) * P_l + 3 * d * d) if L > 0 else 0
     last_rows = 2 * (d * d + 2 * d * F) if L > 0 else 0
     attn_pre = lambda k: (L - 1) * 4 * d * k * (k + 1) / 2 + 4 * d * k if L > 0 else 0 * k
+    if score_all or L == 0:
+        gemm_sc = float(m.sum() * mm)
+        lm_sc = float(m.sum() * lm)
+        attn_sc = float(attn(m).sum())
+        gemm_rows = m.sum() * 3 * L
+    else:
+        r = np.where(n > 0, resp + 1, 0).astype(np.float64)   # rows of a sequence from the last query column on
+        gemm_sc = float(m.sum() * 2 * ((L - 1) * P_l + 3 * d * d) + r.sum() * 2 * (d * d + 2 * d * F))
+        lm_sc = float(resp.sum() * lm)
+        tri = lambda k: k * (k + 1) / 2
+        attn_sc = float(((L - 1) * 4 * d * tri(m) + 4 * d * (tri(m) - tri(m - r))).sum())
+        gemm_rows = m.sum() * (3 * (L - 1) + 1) + r.sum() * 2
+    # launches of the large per-layer products (QKV, FC1, out-projection + FC2 as one) and the rows they cover
+    gemm_launches = 3 * L + (3 * (L - 1) + 1 if L > 0 else 0)
+    gemm_rows += n.sum() * (3 * (L - 1) + 1 if L > 0 else 0)
     return dict(
         prefill_flops=float((n * mm_pre + attn_pre(n)).sum() + B * (last_rows + lm)),
-        score_flops=float((m * (mm + lm) + attn(m)).sum()),
+        score_flops=gemm_sc + lm_sc + attn_sc,
+        gemm_rows_per_launch=float(gemm_rows / gemm_launches) if gemm_launches else 0.0,
         decode_bytes=float((N - 1) * W + kv_read + (N - 1) * B * kv_tok),
         decode_kv_read_bytes=float(kv_read),
         decode_flops=float((N - 1) * B * (mm + lm)),
-        gemm_flops_prefill=float(n.sum() * mm_pre), gemm_flops_score=float(m.sum() * mm),
-        lm_flops_score=float(m.sum() * lm), weights_bytes=float(W), real_score_tokens=float(m.sum()),
+        gemm_flops_prefill=float(n.sum() * mm_pre), gemm_flops_score=gemm_sc,
+        lm_flops_score=lm_sc, weights_bytes=float(W), real_score_tokens=float(m.sum()),
         # the packed causal attention kernel: every layer of scoring, all but the final layer of prefill
-        attn_flops=float(attn(m).sum() + (attn(n).sum() * (L - 1) / L if L > 0 else 0.0)),
+        attn_flops=float(attn(m).sum() + (attn(n).sum() * (L - 1) / L if L > 0 else 0.0)),  # as run: all queries
         real_query_tokens=float(n.sum()))
 
 
@@ -85,6 +106,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-update-leg", action="store_true",
                     help="skip the PPO-update leg (forward keeping activations, backward, AdamW; ~10 s at config 4)")
+    ap.add_argument("--score-all-columns", action="store_true",
+                    help="rescoring with score_sequences (log-probs and values of the query columns too) instead of "
+                         "score_responses")
     ap.add_argument("--extra-score-shapes", action="store_true",
                     help="also time score_sequences on the paper's other batch shapes: right-padded (B,638) and (B,2021)")
     a = ap.parse_args()
@@ -111,9 +135,14 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
+    def score(toks, omask):
+        if a.score_all_columns:
+            return pol.score_sequences(toks, omask, wl.temperature)
+        return pol.score_responses(toks, omask, wl.query_len, wl.temperature)
+
     def step():
         toks, lps, lens, omask = pol.rollout_generate(q_d, m_d, wl.sample_seed, wl.temperature, N, return_mask=True)
-        lp, val = pol.score_sequences(toks, omask, wl.temperature)
+        lp, val = score(toks, omask)
         return toks, lps, lens, omask, lp, val
 
     for _ in range(a.warmup):
@@ -125,7 +154,7 @@ def main():
         ev[3 * i].record()
         r = pol.rollout_generate(q_d, m_d, wl.sample_seed, wl.temperature, N, return_mask=True)
         ev[3 * i + 1].record()
-        s = pol.score_sequences(r[0], r[3], wl.temperature)
+        s = score(r[0], r[3])
         ev[3 * i + 2].record()
     torch.cuda.synchronize()
     wall = time.time() - t1
@@ -134,7 +163,7 @@ def main():
     prefill_ms, decode_ms = pol.last_rollout_phases()
     lens = r[2].cpu().numpy()
     n_true = mask.sum(1)
-    wc = work_counts(cfg, n_true, lens, N)
+    wc = work_counts(cfg, n_true, lens, N, score_all=a.score_all_columns)
 
     # one more step with per-kernel HIP events (outside the timed region) for the roofline object
     pol.profile_enable(True)
@@ -157,7 +186,7 @@ def main():
         # row and launch, Infinity-Cache hits included (an upper bound of the HBM bytes), times this run's mean
         # rows per launch.
         per_row, traffic_commit = gemm_traffic_per_row(cfg)
-        traffic = per_row * 0.5 * (wc["real_query_tokens"] + wc["real_score_tokens"]) if per_row else None
+        traffic = per_row * wc["gemm_rows_per_launch"] if per_row else None
         rooflines["gemm"] = {"bound": "mfma", "achieved": ach / 1e12, "peak": MFMA_PEAK / 1e12, "unit": "TFLOP/s",
                              "frac": ach / MFMA_PEAK, "traffic": traffic, "traffic_measured_at_commit": traffic_commit,
                              "avg_launch_ms": prof["gemm"][0] / prof["gemm"][1]}
@@ -372,7 +401,8 @@ def main():
                 rf["frac_of_measured"] = rf["achieved"] / top
     ms_step = wall / a.steps * 1e3
     out = {
-        "metric": "rollout generated tokens/s (rollout_generate + score_sequences per step)",
+        "metric": "rollout generated tokens/s (rollout_generate + %s per step)" % (
+            "score_sequences" if a.score_all_columns else "score_responses"),
         "value": B * N / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if cfg.dtype == "fp32" else "f16 operands / f32 accumulate (bf16 weights)",

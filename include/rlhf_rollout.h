@@ -133,6 +133,21 @@ int score_sequences(rlhf_handle *h, const int32_t *tokens, const uint8_t *mask, 
                     float temperature, float *out_logprobs, float *out_values,
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/* Rescoring of the response only (paper: PPO Details -- the log-probabilities PPO, the KL penalty and the
+ * advantages use are those of the response tokens, sliced from the forward pass at the columns from the query
+ * length on; values and the reward-model score likewise start at the last query column).  Same inputs and
+ * outputs as score_sequences, except that out_logprobs[b,t] is 0 for t < first_col and out_values[b,t] is 0 for
+ * t < first_col - 1; the other entries equal score_sequences' up to the rounding order of the kernel variants
+ * that the smaller row count selects.  What it saves: the LM head and the
+ * final layer's attention output, out-projection and MLP run only on the rows from column first_col - 1 on
+ * (every layer still computes K and V for every row).  first_col in [0, L]; 0 or 1 = score_sequences.  The
+ * workspace size depends on first_col: rlhf_score_responses_workspace_bytes. */
+int rlhf_score_responses_workspace_bytes(const rlhf_handle *h, int32_t B, int32_t L, int32_t first_col,
+                                         size_t *out);
+int score_responses(rlhf_handle *h, const int32_t *tokens, const uint8_t *mask, int32_t B, int32_t L,
+                    int32_t first_col, float temperature, float *out_logprobs, float *out_values,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- What PPO consumes after the rollout (stateless: no handle, no workspace). ------------------
  *
  * Reward assembly (paper: Preliminaries, Eq. (RL); Reward Model Details, "Extract reward from the EOS

@@ -18,7 +18,7 @@ EXPORTS = (
     "rlhf_head_backward", "rlhf_head_backward_workspace_bytes", "rlhf_mlp_backward", "rlhf_mlp_backward_workspace_bytes", "rlhf_attention_backward", "rlhf_forward_keep", "rlhf_policy_backward", "rlhf_policy_backward_workspace_bytes",
     "rlhf_attention_branch_backward", "rlhf_attention_branch_backward_workspace_bytes",
     "rlhf_attention_backward_noalloc", "rlhf_weight_image_bytes", "rlhf_refresh_weights",
-    "rlhf_ppo_update", "rlhf_ppo_update_workspace_bytes",
+    "rlhf_ppo_update", "rlhf_ppo_update_workspace_bytes", "score_responses", "rlhf_score_responses_workspace_bytes",
 )
 
 _PER_LAYER = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -86,6 +86,8 @@ def load_library():
     lib.rlhf_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz)]
     lib.rollout_generate.argtypes = [vp, vp, vp, i32, i32, u64, u64, f32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.score_sequences.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.score_responses.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.rlhf_score_responses_workspace_bytes.argtypes = [vp, i32, i32, i32, C.POINTER(sz)]
     lib.rlhf_debug_logits_rows.argtypes = [vp, vp, vp, i32, i32, C.POINTER(i32), i32, vp, vp, sz, vp]
     lib.rlhf_profile_enable.argtypes = [vp, i32]
     lib.rlhf_profile_read.argtypes = [vp, i32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
@@ -253,6 +255,24 @@ class Policy:
             _check(self.lib.score_sequences(self._h, t.data_ptr(), m.data_ptr(), B, L, temperature, lp.data_ptr(),
                                             val.data_ptr() if want_values else None, ws.data_ptr(), ws.numel(),
                                             self._stream()))
+        return lp, val
+
+    def score_responses(self, tokens, mask, first_col, temperature, want_values=True):
+        """score_sequences restricted to the response: logprobs of the columns from first_col on, values from
+        column first_col - 1 on, zeros before.  Returns (logprobs, values) float32 [B, L] CUDA tensors."""
+        torch = self.torch
+        t = self._to_dev(tokens, torch.int32)
+        m = self._to_dev(mask, torch.uint8)
+        B, L = t.shape
+        out = C.c_size_t()
+        _check(self.lib.rlhf_score_responses_workspace_bytes(self._h, B, L, int(first_col), C.byref(out)))
+        ws = self._workspace(out.value)
+        lp = self._out((B, L), torch.float32)
+        val = self._out((B, L), torch.float32) if want_values else None
+        with torch.cuda.device(self.device):
+            _check(self.lib.score_responses(self._h, t.data_ptr(), m.data_ptr(), B, L, int(first_col), temperature,
+                                            lp.data_ptr(), val.data_ptr() if want_values else None, ws.data_ptr(),
+                                            ws.numel(), self._stream()))
         return lp, val
 
     def head_backward(self, x_final, targets, d_logprobs, d_values, temperature, grad_scale=1.0):

@@ -206,8 +206,17 @@ struct ScoreWs {
   int32_t* rows_dev;
   size_t Tmax;
   int chunk;
+  // Scoring from a first column on (score_responses): only the rows from column first_col - 1 on go through the
+  // LM head (and, outside the training forward, through the final layer's attention output, out-projection and MLP).
+  // sel_rows = 0: no selection, every row is computed and the outputs before first_col are just written as 0.
+  int first_col = 0;
+  int sel_rows = 0;            // host bound of the selected rows, B * (L - first_col + 1)
+  int *sel = nullptr, *tgt = nullptr, *n_sel = nullptr, *sel_off = nullptr;
+  Acts z;                      // [sel_rows, .] activations of the selected rows
+  float* val_sel = nullptr;
+  bool sel_layers = false;     // set by score_forward: the final layer ran on the selected rows, z.x holds its output
 };
-ScoreWs carve_score(Carver& c, const rlhf_model_config& cfg, int B, int L, size_t esz) {
+ScoreWs carve_score(Carver& c, const rlhf_model_config& cfg, int B, int L, size_t esz, int first_col = 0) {
   ScoreWs w;
   w.Tmax = (size_t)B * L;
   w.meta = carve_meta(c, B, w.Tmax);
@@ -222,13 +231,27 @@ ScoreWs carve_score(Carver& c, const rlhf_model_config& cfg, int B, int L, size_
   lf.M_max = (int)w.Tmax; lf.M_dev = nullptr;
   lf.N = cfg.vocab; lf.K = cfg.d_model; lf.ldo = cfg.vocab; lf.epilogue = EPI_LSE;
   w.fused_lm = gemm_takes_lse(cfg.dtype, lf);
+  w.first_col = std::max(first_col, 0);
+  if (w.first_col > 1 && w.first_col <= L && w.fused_lm) {
+    lf.M_max = B * (L - w.first_col + 1);
+    if (gemm_takes_lse(cfg.dtype, lf)) w.sel_rows = lf.M_max;
+  }
+  const size_t lm_rows = w.sel_rows ? (size_t)w.sel_rows : w.Tmax;
   w.chunk = (int)std::min<size_t>(w.Tmax, kLogitChunk);
   w.logits = w.fused_lm ? nullptr : c.take<float>((size_t)w.chunk * cfg.vocab);
   w.nparts = gemm_lse_parts(cfg.vocab);
   if (w.fused_lm) {
-    w.pmax = c.take<float>((size_t)w.nparts * w.Tmax);
-    w.psum = c.take<float>((size_t)w.nparts * w.Tmax);
-    w.ztgt = c.take<float>(w.Tmax);
+    w.pmax = c.take<float>((size_t)w.nparts * lm_rows);
+    w.psum = c.take<float>((size_t)w.nparts * lm_rows);
+    w.ztgt = c.take<float>(lm_rows);
+  }
+  if (w.sel_rows) {
+    w.sel = c.take<int>(w.sel_rows);
+    w.tgt = c.take<int>(w.sel_rows);
+    w.n_sel = c.take<int>(1);
+    w.sel_off = c.take<int>(B + 1);
+    w.z = carve_acts(c, cfg, (size_t)w.sel_rows, esz);
+    w.val_sel = c.take<float>(w.sel_rows);
   }
   w.idx = c.take<int>(w.Tmax);
   w.rows_dev = c.take<int32_t>(2 * w.Tmax);
@@ -263,6 +286,13 @@ struct PassArgs {
   float* keep = nullptr;
   size_t keep_stride = 0;
   size_t keep_rows = 0;
+  // Scoring from a first column on: when `sel` is set, the final layer computes K and V for every row as usual
+  // and attention for every query, but the out-projection and the MLP run on the sel_rows selected rows only
+  // (sel[j] = packed row, *n_sel of them), into selz->x.
+  const int* sel = nullptr;
+  const int* n_sel = nullptr;
+  int sel_rows = 0;
+  const Acts* selz = nullptr;
 };
 
 int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) {
@@ -404,6 +434,43 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
       LAUNCH("gemm_decode", launch_gemm(dt, zo, s));
       LAUNCH("gemm_decode", launch_gemm(dt, z1, s));
       LAUNCH("gemm_decode", launch_gemm(dt, z2, s));
+      break;
+    }
+    if (p.mode == 0 && p.sel && l + 1 == c.n_layers) {
+      const Acts& Z = *p.selz;
+      const size_t esz = h->esz, ld_att = (size_t)(cat ? d + c.d_ff : d);
+      LAUNCH("attn_prefill", launch_attn_prefill(dt, A.q, kc, vc, (long)p.kv_extra, p.B, p.Lmax, p.len, p.cu, p.kvoff,
+                                                 c.n_heads, c.head_dim, A.att, (int)ld_att, s));
+      LAUNCH("gather_sel", launch_gather_rows_strided(A.att, ld_att * esz, p.sel, p.sel_rows, (size_t)d * esz, Z.att,
+                                                      ld_att * esz, s));
+      LAUNCH("gather_sel", launch_gather_rows_strided(A.m, (size_t)d * esz, p.sel, p.sel_rows, (size_t)d * esz, Z.m,
+                                                      (size_t)d * esz, s));
+      LAUNCH("gather_sel", launch_gather_rows_strided(A.x, (size_t)d * 4, p.sel, p.sel_rows, (size_t)d * 4, Z.x,
+                                                      (size_t)d * 4, s));
+      GemmArgs zb;
+      zb.M_max = p.sel_rows;
+      zb.M_dev = p.n_sel;
+      auto zg = [&](const void* in, const void* w, const void* bias, void* out, int N, int K, int epi) {
+        GemmArgs g = zb;
+        g.A = in; g.W = w; g.bias = bias; g.out = out; g.N = N; g.K = K; g.ldo = N; g.epilogue = epi;
+        return g;
+      };
+      GemmArgs z1 = zg(Z.m, h->w_fc1[l], h->b_fc1[l], Z.ffn, c.d_ff, d, EPI_BIAS_GELU);
+      if (cat) {
+        z1.out = (char*)Z.att + (size_t)d * esz;
+        z1.ldo = d + c.d_ff;
+        GemmArgs zc = zg(Z.att, h->w_o[l], h->b_o[l], Z.x, d, d + c.d_ff, EPI_BIAS_RESADD);
+        zc.bias2 = h->b_fc2[l];
+        LAUNCH("gemm", launch_gemm(dt, z1, s));
+        LAUNCH("gemm", launch_gemm(dt, zc, s));
+      } else {
+        GemmArgs zo = zg(Z.att, h->w_o[l], h->b_o[l], Z.x, d, d, EPI_BIAS_RESADD);
+        GemmArgs z2 = zg(Z.ffn, h->w_fc2[l], h->b_fc2[l], Z.x, d, c.d_ff, EPI_BIAS_RESADD);
+        zo.ldw = z2.ldw = h->ld_o2;
+        LAUNCH("gemm", launch_gemm(dt, zo, s));
+        LAUNCH("gemm", launch_gemm(dt, z1, s));
+        LAUNCH("gemm", launch_gemm(dt, z2, s));
+      }
       break;
     }
     GemmArgs go = gemm_args(A.att, h->w_o[l], h->b_o[l], A.x, d, d, EPI_BIAS_RESADD);
@@ -1215,6 +1282,18 @@ static int score_forward(rlhf_handle* h, const int32_t* tokens, const uint8_t* m
   p.keep = keep;
   p.keep_rows = keep_rows ? keep_rows : (size_t)B * L;  // rows copied per layer = row stride of the kept slices
   p.keep_stride = p.keep_rows * c.d_model;
+  ws.sel_layers = false;
+  if (ws.sel_rows) {
+    LAUNCH("select_rows", launch_select_rows(ws.first_col, B, m.start, m.len, m.cu, m.tok, ws.sel_rows, ws.sel, ws.tgt,
+                                             ws.n_sel, ws.sel_off, s));
+    if (!keep && c.n_layers > 0) {  // a training forward keeps the final layer's output for every row
+      p.sel = ws.sel;
+      p.n_sel = ws.n_sel;
+      p.sel_rows = ws.sel_rows;
+      p.selz = &ws.z;
+      ws.sel_layers = true;
+    }
+  }
   return run_layers(h, ws.acts, p, s);
 }
 
@@ -1227,6 +1306,36 @@ static int score_tail(rlhf_handle* h, int B, int L, float temperature, ScoreWs& 
   const int dt = c.dtype, d = c.d_model;
   const int Tmax = B * L;
   const bool want_val = out_values && h->w.value_w;
+  LseArgs la;
+  la.inv_temperature = 1.0f / temperature;
+  la.pmax = ws.pmax; la.psum = ws.psum; la.ztgt = ws.ztgt; la.vocab = c.vocab;
+  GemmArgs lf;
+  lf.W = h->embed_out_mm; lf.bias = nullptr; lf.out = nullptr; lf.M_sub = 0;
+  lf.N = c.vocab; lf.K = d; lf.ldo = c.vocab; lf.epilogue = EPI_LSE; lf.lse = &la;
+  if (ws.sel_rows) {
+    // Scoring from a first column on: the LM head runs on the selected rows only.  Their final LayerNorm (and
+    // value head) reads the final layer's output where it is: the selected rows' own buffer, or, after a forward
+    // that ran every row through the final layer, the packed rows through the selection.
+    if (ws.sel_layers) {
+      LAUNCH("final_ln", launch_final_ln(dt, ws.z.x, nullptr, 0, ws.sel_rows, ws.n_sel, d, c.ln_eps, h->w.lnf_g,
+                                         h->w.lnf_b, ws.z.a, want_val ? h->w.value_w : nullptr,
+                                         h->value_b_dev ? 0.f : h->w.value_b, ws.val_sel, s));
+    } else {
+      LAUNCH("final_ln", launch_final_ln(dt, ws.acts.x, ws.sel, 0, ws.sel_rows, ws.n_sel, d, c.ln_eps, h->w.lnf_g,
+                                         h->w.lnf_b, ws.z.a, want_val ? h->w.value_w : nullptr,
+                                         h->value_b_dev ? 0.f : h->w.value_b, ws.val_sel, s));
+    }
+    la.tok = nullptr; la.pos = nullptr; la.T_dev = ws.n_sel; la.stride = ws.sel_rows;
+    la.tgt = ws.tgt; la.dst = ws.sel;
+    if (want_val) { la.val_in = ws.val_sel; la.val_out = ws.val; }
+    lf.A = ws.z.a; lf.M_max = ws.sel_rows; lf.M_dev = ws.n_sel;
+    LAUNCH("gemm_lm_head", launch_gemm(dt, lf, s));
+    LAUNCH("lse_gather", launch_lse_combine(la, ws.sel_rows, ws.nparts, ws.lp, s));
+    LAUNCH("unpack_scores", launch_unpack_scores(ws.lp, want_val ? ws.val : nullptr, B, L, m.start, m.len, m.cu,
+                                                 out_logprobs, want_val ? out_values : nullptr, s,
+                                                 want_val ? h->value_b_dev : nullptr, ws.first_col));
+    return RLHF_OK;
+  }
   // final LayerNorm of every packed row (into the LN1 buffer, free by now) + value head
   LAUNCH("final_ln", launch_final_ln(dt, ws.acts.x, nullptr, 0, Tmax, m.total, d, c.ln_eps, h->w.lnf_g,
                                      h->w.lnf_b, ws.acts.a, want_val ? h->w.value_w : nullptr,
@@ -1235,13 +1344,8 @@ static int score_tail(rlhf_handle* h, int B, int L, float temperature, ScoreWs& 
   // accumulators: its epilogue reduces every part of a row (one wave's columns) to (max, sum of exp) and
   // picks out the target token's logit, and a small kernel combines the parts.  Otherwise the
   // logits of a chunk of rows are materialised and reduced by a second kernel.
-  LseArgs la;
-  la.tok = m.tok; la.pos = m.pos; la.T_dev = m.total; la.inv_temperature = 1.0f / temperature;
-  la.pmax = ws.pmax; la.psum = ws.psum; la.ztgt = ws.ztgt; la.stride = Tmax; la.vocab = c.vocab;
-  GemmArgs lf;
-  lf.A = ws.acts.a; lf.W = h->embed_out_mm; lf.bias = nullptr; lf.out = nullptr;
-  lf.M_max = Tmax; lf.M_dev = m.total; lf.M_sub = 0;
-  lf.N = c.vocab; lf.K = d; lf.ldo = c.vocab; lf.epilogue = EPI_LSE; lf.lse = &la;
+  la.tok = m.tok; la.pos = m.pos; la.T_dev = m.total; la.stride = Tmax;
+  lf.A = ws.acts.a; lf.M_max = Tmax; lf.M_dev = m.total;
   const bool fused_lm = ws.fused_lm;
   if (fused_lm) {
     LAUNCH("gemm_lm_head", launch_gemm(dt, lf, s));
@@ -1260,7 +1364,7 @@ static int score_tail(rlhf_handle* h, int B, int L, float temperature, ScoreWs& 
   }
   LAUNCH("unpack_scores", launch_unpack_scores(ws.lp, want_val ? ws.val : nullptr, B, L, m.start, m.len, m.cu,
                                                out_logprobs, want_val ? out_values : nullptr, s,
-                                               want_val ? h->value_b_dev : nullptr));
+                                               want_val ? h->value_b_dev : nullptr, ws.first_col));
   return RLHF_OK;
 }
 
@@ -1275,6 +1379,34 @@ int score_sequences(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, 
   ScoreWs ws = carve_score(cv, h->cfg, B, L, h->esz);
   if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
     return fail(RLHF_ENOMEM, "workspace too small for score_sequences");
+  hipStream_t s = (hipStream_t)stream;
+  rc = score_forward(h, tokens, mask, B, L, ws, s);
+  if (rc) return rc;
+  return score_tail(h, B, L, temperature, ws, out_logprobs, out_values, s);
+}
+
+int rlhf_score_responses_workspace_bytes(const rlhf_handle* h, int32_t B, int32_t L, int32_t first_col, size_t* out) {
+  if (!h || !out) return fail(RLHF_EINVAL, "null argument");
+  int rc = check_common(h, B, L);
+  if (rc) return rc;
+  Carver c(nullptr);
+  carve_score(c, h->cfg, B, L, h->esz, first_col);
+  *out = c.off + 256;
+  return RLHF_OK;
+}
+
+int score_responses(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, int32_t B, int32_t L, int32_t first_col,
+                    float temperature, float* out_logprobs, float* out_values, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+  int rc = check_common(h, B, L);
+  if (rc) return rc;
+  if (!tokens || !mask || !out_logprobs || !workspace) return fail(RLHF_EINVAL, "null pointer argument");
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return fail(RLHF_EINVAL, "temperature must be > 0");
+  if (first_col < 0 || first_col > L) return fail(RLHF_EINVAL, "first_col must be in [0, L]");
+  Carver cv((void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255));
+  ScoreWs ws = carve_score(cv, h->cfg, B, L, h->esz, first_col);
+  if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
+    return fail(RLHF_ENOMEM, "workspace too small for score_responses");
   hipStream_t s = (hipStream_t)stream;
   rc = score_forward(h, tokens, mask, B, L, ws, s);
   if (rc) return rc;
@@ -1317,10 +1449,28 @@ int rlhf_policy_backward_workspace_bytes(const rlhf_handle* h, int32_t T, size_t
   return RLHF_OK;
 }
 
+// sel (optional): the sel_rows packed rows (*n_sel of them real) outside which targets, d_logprobs and d_values
+// carry nothing: the output heads' backward pass then runs on those rows only.
+static int policy_backward_impl(rlhf_handle* h, const float* x_keep, int64_t x_keep_layer_stride,
+                                const int32_t* cu_seqlens, const int32_t* packed_tokens, int32_t B, int32_t T,
+                                int32_t max_len, const int32_t* targets, const float* d_logprobs, const float* d_values,
+                                float temperature, float grad_scale, const rlhf_grads* g, void* workspace,
+                                size_t workspace_bytes, void* stream, const int* sel, int sel_rows, const int* n_sel);
+
 int rlhf_policy_backward(rlhf_handle* h, const float* x_keep, int64_t x_keep_layer_stride, const int32_t* cu_seqlens,
                          const int32_t* packed_tokens, int32_t B, int32_t T, int32_t max_len, const int32_t* targets,
                          const float* d_logprobs, const float* d_values, float temperature, float grad_scale,
                          const rlhf_grads* g, void* workspace, size_t workspace_bytes, void* stream) {
+  return policy_backward_impl(h, x_keep, x_keep_layer_stride, cu_seqlens, packed_tokens, B, T, max_len, targets,
+                              d_logprobs, d_values, temperature, grad_scale, g, workspace, workspace_bytes, stream,
+                              nullptr, 0, nullptr);
+}
+
+static int policy_backward_impl(rlhf_handle* h, const float* x_keep, int64_t x_keep_layer_stride,
+                                const int32_t* cu_seqlens, const int32_t* packed_tokens, int32_t B, int32_t T,
+                                int32_t max_len, const int32_t* targets, const float* d_logprobs, const float* d_values,
+                                float temperature, float grad_scale, const rlhf_grads* g, void* workspace,
+                                size_t workspace_bytes, void* stream, const int* sel, int sel_rows, const int* n_sel) {
   if (!h || !g) return fail(RLHF_EINVAL, "null argument");
   const rlhf_model_config& c = h->cfg;
   if (T <= 0 || B <= 0) return fail(RLHF_EINVAL, "rows and batch must be positive");
@@ -1349,10 +1499,27 @@ int rlhf_policy_backward(rlhf_handle* h, const float* x_keep, int64_t x_keep_lay
   float* dx_n = (float*)(base + 3 * buf);   // their sum with dx: the gradient one layer down
   char* sub = base + 4 * buf;
   const size_t sub_bytes = workspace_bytes - (size_t)(sub - (char*)workspace);
-  rc = rlhf_head_backward(h, x_keep + (size_t)c.n_layers * x_keep_layer_stride, targets, d_logprobs, d_values, T,
-                          temperature, grad_scale, dx, g->lnf_g, g->lnf_b, g->embed_out, g->value_w, g->value_b, sub,
-                          sub_bytes, stream);
-  if (rc) return rc;
+  const float* x_final = x_keep + (size_t)c.n_layers * x_keep_layer_stride;
+  if (sel && sel_rows > 0 && sel_rows < T) {
+    // the heads on the selected rows: their inputs gathered into the (still free) branch buffers, the input
+    // gradient scattered back into a zeroed dx
+    const size_t rb = (size_t)c.d_model * sizeof(float);
+    float *x_sel = dx_m, *dx_sel = dx_a;
+    int* t_sel = (int*)dx_n;
+    float *gl_sel = dx_n + sel_rows, *gv_sel = dx_n + 2 * (size_t)sel_rows;
+    LAUNCH("gather_sel", launch_gather_rows_strided(x_final, rb, sel, sel_rows, rb, x_sel, rb, s));
+    LAUNCH("gather_sel", launch_gather_row_scalars(sel, n_sel, sel_rows, targets, d_logprobs, d_values, t_sel, gl_sel,
+                                                   gv_sel, s));
+    rc = rlhf_head_backward(h, x_sel, t_sel, gl_sel, gv_sel, sel_rows, temperature, grad_scale, dx_sel, g->lnf_g,
+                            g->lnf_b, g->embed_out, g->value_w, g->value_b, sub, sub_bytes, stream);
+    if (rc) return rc;
+    LAUNCH("gather_sel", launch_fill_zero(dx, n * sizeof(float), s));
+    LAUNCH("gather_sel", launch_scatter_rows(dx_sel, sel, n_sel, sel_rows, rb, dx, s));
+  } else {
+    rc = rlhf_head_backward(h, x_final, targets, d_logprobs, d_values, T, temperature, grad_scale, dx, g->lnf_g,
+                            g->lnf_b, g->embed_out, g->value_w, g->value_b, sub, sub_bytes, stream);
+    if (rc) return rc;
+  }
   for (int l = c.n_layers - 1; l >= 0; --l) {
     const float* xl = x_keep + (size_t)l * x_keep_layer_stride;
     rc = rlhf_mlp_backward(h, l, xl, dx, T, dx_m, g->ln2_g[l], g->ln2_b[l], g->w_fc1[l], g->b_fc1[l], g->w_fc2[l],
@@ -1379,7 +1546,7 @@ struct UpdateWs {
 UpdateWs carve_update(Carver& c, const rlhf_handle* h, int Bm, int L, int N, int T_max) {
   UpdateWs w;
   const rlhf_model_config& cfg = h->cfg;
-  w.score = carve_score(c, cfg, Bm, L, h->esz);
+  w.score = carve_score(c, cfg, Bm, L, h->esz, L - N);  // log-probs and values are read from column L - N - 1 on
   w.x_keep = c.take<float>((size_t)(cfg.n_layers + 1) * T_max * cfg.d_model);
   w.lp_full = c.take<float>((size_t)Bm * L);
   w.val_full = c.take<float>((size_t)Bm * L);
@@ -1494,8 +1661,9 @@ int rlhf_ppo_update(rlhf_handle* h, const rlhf_ppo_update_config* cfg, const rlh
       const Meta& m = ws.score.meta;
       LAUNCH("ppo_glue", launch_ppo_pack_grads(tok_j, Bm, L, Lq, N, m.start, m.len, m.cu, ws.d_lp, ws.d_v, ws.targets,
                                                ws.gl, ws.gv, s));
-      rc = rlhf_policy_backward(h, ws.x_keep, (int64_t)T * c.d_model, m.cu, m.tok, Bm, T, max_len, ws.targets, ws.gl,
-                                ws.gv, cfg->temperature, cfg->grad_scale, &G, ws.bwd, ws.bwd_bytes, stream);
+      rc = policy_backward_impl(h, ws.x_keep, (int64_t)T * c.d_model, m.cu, m.tok, Bm, T, max_len, ws.targets, ws.gl,
+                                ws.gv, cfg->temperature, cfg->grad_scale, &G, ws.bwd, ws.bwd_bytes, stream,
+                                ws.score.sel_rows ? ws.score.sel : nullptr, ws.score.sel_rows, ws.score.n_sel);
       if (rc) return rc;
       // AdamW on every tensor; a bf16 model keeps fp32 masters and gets its storage arrays rewritten
       const double inv_scale = 1.0 / (double)cfg->grad_scale;

@@ -94,10 +94,32 @@ struct LseArgs {
   float* ztgt;
   int stride;         // rows_max
   int vocab;
+  // Rows that are a selection of the packed rows (launch_select_rows): tgt[j] is row j's target token (-1: none)
+  // and replaces the tok / pos test; dst[j] is the packed row it stands for.
+  const int* tgt = nullptr;
+  const int* dst = nullptr;
+  const float* val_in = nullptr;  // with dst: per-row values to scatter, val_out[dst[j]] = val_in[j]
+  float* val_out = nullptr;
 };
 // lp_packed[t + 1] = ztgt[t] - logsumexp over the nparts parts, for every t whose successor is in
-// the same sequence.
+// the same sequence (with a selection: lp_packed[dst[j] + 1] for every row j with a target).
 hipError_t launch_lse_combine(const LseArgs& a, int rows_max, int nparts, float* lp_packed, hipStream_t s);
+// The rows of a packed batch from padded column first_col - 1 on (what predicts the tokens at columns >=
+// first_col): sel[j] = their packed row, sequence by sequence, j < *n_sel; tgt[j] = the token the row predicts
+// (-1 for a sequence's last row).  Entries n_sel .. rows_max-1 are filled with row 0 / -1, so that a gather over
+// rows_max entries stays in bounds.  off [B + 1] is scratch (the selection's offsets per sequence).  One block.
+hipError_t launch_select_rows(int first_col, int B, const int* start, const int* len, const int* cu, const int* tok,
+                              int rows_max, int* sel, int* tgt, int* n_sel, int* off, hipStream_t s);
+// Per-row scalars of the selected rows: tgt_out[j] = tgt[sel[j]], a_out[j] = a[sel[j]], b_out[j] = b[sel[j]]
+// for j < *n_sel; (-1, 0, 0) for the entries up to rows.  b / b_out may be null.
+hipError_t launch_gather_row_scalars(const int* sel, const int* n_sel, int rows, const int* tgt, const float* a,
+                                     const float* b, int* tgt_out, float* a_out, float* b_out, hipStream_t s);
+// out row sel[j] = in row j for j < *n_sel (distinct rows of row_bytes, a multiple of 16).
+hipError_t launch_scatter_rows(const void* in, const int* sel, const int* n_sel, int rows, size_t row_bytes, void* out,
+                               hipStream_t s);
+// out row r (out_stride bytes apart) = the first row_bytes of in row src[r] (in_stride bytes apart).
+hipError_t launch_gather_rows_strided(const void* in, size_t in_stride, const int* src, int rows, size_t row_bytes,
+                                      void* out, size_t out_stride, hipStream_t s);
 // True when launch_gemm would take EPI_LSE for these arguments (large-M fp16 kernel only).
 // EPI_QKV: the product is the [rows, 3*d] QKV matrix in sections q | k | v with the rotary pairs of a
 // head in neighbouring columns.  The epilogue adds the bias, turns the pairs by the row's position,
@@ -253,9 +275,10 @@ hipError_t launch_lse_gather(const float* logits, int rows_max, int t0, const in
 // Packed -> padded [B, L] outputs with zeros at masked slots; logprob of a row's first token is 0.
 // val_bias_dev: optional device scalar added to every real position's value (a value-head bias that lives on the
 // device because an optimizer updates it there).
+// first_col: log-probs of columns before it and values of columns before first_col - 1 are written as 0.
 hipError_t launch_unpack_scores(const float* lp_packed, const float* val_packed, int B, int L, const int* start,
                                 const int* len, const int* cu, float* out_lp, float* out_val, hipStream_t s,
-                                const float* val_bias_dev = nullptr);
+                                const float* val_bias_dev = nullptr, int first_col = 0);
 // Gather helper for the debug entry point: idx[i] = cu[b_i] + (col_i - start[b_i]).
 hipError_t launch_rows_to_packed(const int32_t* rows_bt, int n, const int* start, const int* cu, int* idx,
                                  hipStream_t s);

@@ -1023,8 +1023,14 @@ __global__ void __launch_bounds__(256)
     lse_combine_kernel(LseArgs a, int nparts, float* __restrict__ lp_packed) {
   const int t = blockIdx.x * 256 + threadIdx.x;
   const int T = *a.T_dev;
-  if (t + 1 >= T) return;
-  if (a.pos[t + 1] != a.pos[t] + 1) return;  // t is the last token of its sequence: nothing to predict
+  if (a.tgt) {
+    if (t >= T) return;
+    if (a.val_out) a.val_out[a.dst[t]] = a.val_in[t];
+    if (a.tgt[t] < 0) return;
+  } else {
+    if (t + 1 >= T) return;
+    if (a.pos[t + 1] != a.pos[t] + 1) return;  // t is the last token of its sequence: nothing to predict
+  }
   float m = -INFINITY;
   for (int p = 0; p < nparts; ++p) m = fmaxf(m, a.pmax[(size_t)p * a.stride + t]);
   float s = 0.f;
@@ -1032,7 +1038,7 @@ __global__ void __launch_bounds__(256)
     const float pm = a.pmax[(size_t)p * a.stride + t];
     if (pm > -INFINITY) s += a.psum[(size_t)p * a.stride + t] * expf(pm - m);
   }
-  lp_packed[t + 1] = a.ztgt[t] - (m + logf(s));
+  lp_packed[(a.tgt ? a.dst[t] : t) + 1] = a.ztgt[t] - (m + logf(s));
 }
 
 hipError_t launch_lse_combine(const LseArgs& a, int rows_max, int nparts, float* lp_packed, hipStream_t s) {
@@ -1044,22 +1050,137 @@ hipError_t launch_lse_combine(const LseArgs& a, int rows_max, int nparts, float*
 __global__ void unpack_scores_kernel(const float* __restrict__ lp_packed, const float* __restrict__ val_packed,
                                      int L, const int* __restrict__ start, const int* __restrict__ len,
                                      const int* __restrict__ cu, float* __restrict__ out_lp,
-                                     float* __restrict__ out_val, const float* __restrict__ val_bias_dev) {
+                                     float* __restrict__ out_val, const float* __restrict__ val_bias_dev,
+                                     int first_col) {
   const int b = blockIdx.y;
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= L) return;
   const int i = c - start[b];
   const bool real = i >= 0 && i < len[b];
   const size_t o = (size_t)b * L + c;
-  out_lp[o] = (real && i >= 1) ? lp_packed[cu[b] + i] : 0.f;
-  if (out_val) out_val[o] = real ? val_packed[cu[b] + i] + (val_bias_dev ? *val_bias_dev : 0.f) : 0.f;
+  out_lp[o] = (real && i >= 1 && c >= first_col) ? lp_packed[cu[b] + i] : 0.f;
+  if (out_val)
+    out_val[o] = (real && c >= first_col - 1) ? val_packed[cu[b] + i] + (val_bias_dev ? *val_bias_dev : 0.f) : 0.f;
 }
 
 hipError_t launch_unpack_scores(const float* lp_packed, const float* val_packed, int B, int L, const int* start,
                                 const int* len, const int* cu, float* out_lp, float* out_val, hipStream_t s,
-                                const float* val_bias_dev) {
+                                const float* val_bias_dev, int first_col) {
   hipLaunchKernelGGL(unpack_scores_kernel, dim3((L + 255) / 256, B), dim3(256), 0, s, lp_packed, val_packed, L,
-                     start, len, cu, out_lp, out_val, val_bias_dev);
+                     start, len, cu, out_lp, out_val, val_bias_dev, first_col);
+  return hipGetLastError();
+}
+
+// The packed rows from padded column first_col - 1 on, sequence by sequence (see common.h).  One block: a
+// block-wide prefix sum over the sequences' counts (1024 sequences at a time) gives the offsets, then each wave
+// fills the entries of every 16th sequence.
+__global__ void __launch_bounds__(1024)
+    select_rows_kernel(int first_col, int B, const int* __restrict__ start, const int* __restrict__ len,
+                       const int* __restrict__ cu, const int* __restrict__ tok, int rows_max, int* __restrict__ sel,
+                       int* __restrict__ tgt, int* __restrict__ n_sel, int* __restrict__ off) {
+  __shared__ int sc[1024];
+  __shared__ int carry;
+  const int tid = threadIdx.x;
+  if (tid == 0) carry = 0;
+  __syncthreads();
+  for (int base = 0; base < B; base += 1024) {
+    const int b = base + tid;
+    int cnt = 0;
+    if (b < B) cnt = len[b] - min(max(first_col - 1 - start[b], 0), len[b]);
+    sc[tid] = cnt;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      const int v = tid >= o ? sc[tid - o] : 0;
+      __syncthreads();
+      sc[tid] += v;
+      __syncthreads();
+    }
+    if (b < B) off[b] = carry + sc[tid] - cnt;
+    __syncthreads();
+    if (tid == 1023) carry += sc[1023];
+    __syncthreads();
+  }
+  const int total = min(carry, rows_max);
+  if (tid == 0) {
+    off[B] = carry;
+    *n_sel = total;
+  }
+  const int wave = tid >> 6, lane = tid & 63;
+  for (int b = wave; b < B; b += 16) {
+    const int i0 = min(max(first_col - 1 - start[b], 0), len[b]);
+    const int cnt = len[b] - i0, o = off[b];
+    for (int k = lane; k < cnt && o + k < rows_max; k += 64) {
+      const int t = cu[b] + i0 + k;
+      sel[o + k] = t;
+      tgt[o + k] = k + 1 < cnt ? tok[t + 1] : -1;
+    }
+  }
+  for (int j = total + tid; j < rows_max; j += 1024) {
+    sel[j] = 0;
+    tgt[j] = -1;
+  }
+}
+
+hipError_t launch_select_rows(int first_col, int B, const int* start, const int* len, const int* cu, const int* tok,
+                              int rows_max, int* sel, int* tgt, int* n_sel, int* off, hipStream_t s) {
+  hipLaunchKernelGGL(select_rows_kernel, dim3(1), dim3(1024), 0, s, first_col, B, start, len, cu, tok, rows_max, sel,
+                     tgt, n_sel, off);
+  return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256)
+    gather_rows_strided_kernel(const u32x4_t* __restrict__ in, size_t in_chunks, const int* __restrict__ src,
+                               int chunks, u32x4_t* __restrict__ out, size_t out_chunks) {
+  const size_t sr = (size_t)max(src[blockIdx.x], 0);
+  for (int c = threadIdx.x; c < chunks; c += 256) out[(size_t)blockIdx.x * out_chunks + c] = in[sr * in_chunks + c];
+}
+
+hipError_t launch_gather_rows_strided(const void* in, size_t in_stride, const int* src, int rows, size_t row_bytes,
+                                      void* out, size_t out_stride, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (((row_bytes | in_stride | out_stride) & 15) != 0 || row_bytes / 16 > 0x7fffffff) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gather_rows_strided_kernel, dim3(rows), dim3(256), 0, s, (const u32x4_t*)in, in_stride / 16, src,
+                     (int)(row_bytes / 16), (u32x4_t*)out, out_stride / 16);
+  return hipGetLastError();
+}
+
+// Per-row scalars of the selected rows (a target id and two gradients); entries past *n_sel get (-1, 0, 0).
+__global__ void gather_row_scalars_kernel(const int* __restrict__ sel, const int* __restrict__ n_sel, int rows,
+                                          const int* __restrict__ tgt, const float* __restrict__ a,
+                                          const float* __restrict__ b, int* __restrict__ tgt_out,
+                                          float* __restrict__ a_out, float* __restrict__ b_out) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= rows) return;
+  const bool ok = j < *n_sel;
+  const int t = ok ? sel[j] : 0;
+  tgt_out[j] = ok ? tgt[t] : -1;
+  a_out[j] = ok ? a[t] : 0.f;
+  if (b_out) b_out[j] = ok && b ? b[t] : 0.f;
+}
+
+hipError_t launch_gather_row_scalars(const int* sel, const int* n_sel, int rows, const int* tgt, const float* a,
+                                     const float* b, int* tgt_out, float* a_out, float* b_out, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(gather_row_scalars_kernel, dim3((rows + 255) / 256), dim3(256), 0, s, sel, n_sel, rows, tgt, a, b,
+                     tgt_out, a_out, b_out);
+  return hipGetLastError();
+}
+
+// out row sel[j] = in row j for j < *n_sel (rows of `chunks` 16-byte pieces); the selected rows are distinct.
+__global__ void __launch_bounds__(256)
+    scatter_rows_kernel(const u32x4_t* __restrict__ in, const int* __restrict__ sel, const int* __restrict__ n_sel,
+                        int chunks, u32x4_t* __restrict__ out) {
+  if ((int)blockIdx.x >= *n_sel) return;
+  const size_t dr = (size_t)max(sel[blockIdx.x], 0);
+  for (int c = threadIdx.x; c < chunks; c += 256) out[dr * chunks + c] = in[(size_t)blockIdx.x * chunks + c];
+}
+
+hipError_t launch_scatter_rows(const void* in, const int* sel, const int* n_sel, int rows, size_t row_bytes, void* out,
+                               hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if ((row_bytes & 15) != 0 || row_bytes / 16 > 0x7fffffff) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(scatter_rows_kernel, dim3(rows), dim3(256), 0, s, (const u32x4_t*)in, sel, n_sel,
+                     (int)(row_bytes / 16), (u32x4_t*)out);
   return hipGetLastError();
 }
 

@@ -450,7 +450,12 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
       const int tr = M_sub + m0 + wm + 32 * i + l32;  // packed row
       const bool row_ok = m0 + wm + 32 * i + l32 < M;
       int tcol = -1;  // target column relative to this wave's first column, or out of range
-      if (row_ok && tr + 1 < T && lse.pos[tr + 1] == lse.pos[tr] + 1) tcol = lse.tok[tr + 1] - (n0 + wn);
+      if (lse.tgt) {
+        const int tg = row_ok && tr < T ? lse.tgt[tr] : -1;
+        if (tg >= 0) tcol = tg - (n0 + wn);
+      } else if (row_ok && tr + 1 < T && lse.pos[tr + 1] == lse.pos[tr] + 1) {
+        tcol = lse.tok[tr + 1] - (n0 + wn);
+      }
       float m = -INFINITY, zt = 0.f;
       bool has_t = false;
       float z[NT][16];

@@ -168,6 +168,49 @@ def test_update_loop_matches_the_oracle_loop(gpu, dtype):
     pol.close()
 
 
+def test_update_loop_with_the_heads_on_the_response_rows_only(gpu):
+    """A batch with enough response rows (40 sequences x 14 columns) for the loop to run the LM head, and the output
+    heads' backward pass, on the rows from the last query column on only (the log-probs and values of the other rows
+    are never read): one iteration over the whole batch against the oracle loop, every tensor."""
+    from oracle.ppo_update_oracle import ppo_update
+    from synth import round_to_bf16
+    cfg = ModelConfig(n_layers=2, d_model=128, n_heads=4, head_dim=32, rotary_dims=8, d_ff=256, vocab=200, dtype="bf16",
+                      pad_id=199, eos_id=1)
+    w = make_weights(cfg, 93, variant="test")
+    g = np.random.default_rng(16)
+    B, Lq, N = 40, 24, 13
+    L = Lq + N
+    tokens = g.integers(2, 190, (B, L)).astype(np.int32)
+    qlen = g.integers(5, Lq + 1, B)
+    kept = g.integers(1, N + 1, B).astype(np.int32)
+    kept[:4] = N
+    col = np.arange(L)[None, :]
+    mask = ((col >= (Lq - qlen)[:, None]) & (col < (Lq + kept)[:, None])).astype(np.uint8)
+    tokens[mask == 0] = cfg.pad_id
+    adv = g.normal(0, 1, (B, N)).astype(np.float32)
+    ret = g.normal(0, 1, (B, N)).astype(np.float32)
+    T_ = 0.7
+    hyp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-3, weight_decay=0.01)
+    pol = gpu.Policy(cfg, w)
+    lp0, v0 = (x.cpu().numpy() for x in pol.score_sequences(tokens, mask, T_))
+    old_lp = (lp0[:, Lq:] + g.normal(0, 0.15, (B, N))).astype(np.float32)
+    old_v = (v0[:, Lq - 1:Lq - 1 + N] + g.normal(0, 0.15, (B, N))).astype(np.float32)
+    stats = pol.ppo_update(tokens, mask, Lq, old_lp, adv, old_v, ret, kept, T_, epochs=1, n_minibatches=1, **hyp)
+    stats = stats.cpu().numpy()
+    st = pol.train_state()
+    o_w, _, o_stats = ppo_update(w, cfg, tokens, mask, Lq, old_lp, adv, old_v, ret, kept, T_, epochs=1, n_minibatches=1,
+                                 storage_round=round_to_bf16, **hyp)
+    assert stats[0, 0] == pytest.approx(o_stats[0]["loss"], abs=2e-2)
+    assert stats[0, 7] == o_stats[0]["n_tokens"] == int(kept.sum())
+    for name, want in o_w.items():
+        got = st["master"][name].double().cpu().numpy()
+        want = np.asarray(want, np.float64).reshape(got.shape)
+        start = np.asarray(w[name], np.float64).reshape(got.shape)
+        moved = np.linalg.norm(want - start)
+        assert np.linalg.norm(got - want) <= 5e-2 * moved + 1e-7, (name, np.linalg.norm(got - want), moved)
+    pol.close()
+
+
 def test_update_loop_rejects_bad_arguments(gpu):
     cfg, w, g, tokens, mask, kept, adv, ret, Lq, N = _loop_case("fp32")
     pol = gpu.Policy(cfg, w)

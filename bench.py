@@ -93,7 +93,10 @@ def work_counts(cfg, n, resp, N, score_all=False):
         lm_flops_score=lm_sc, weights_bytes=float(W), real_score_tokens=float(m.sum()),
         # the packed causal attention kernel: every layer of scoring, all but the final layer of prefill
         attn_flops=float(attn(m).sum() + (attn(n).sum() * (L - 1) / L if L > 0 else 0.0)),  # as run: all queries
-        real_query_tokens=float(n.sum()))
+        real_query_tokens=float(n.sum()),
+        # one update iteration: a forward pass over every row (LM head on the response rows) and twice its flops
+        # for the gradients
+        update_flops=3.0 * float((m * mm + attn(m)).sum() + resp.sum() * lm))
 
 
 def main():
@@ -106,6 +109,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-update-leg", action="store_true",
                     help="skip the PPO-update leg (forward keeping activations, backward, AdamW; ~10 s at config 4)")
+    ap.add_argument("--profile-update", action="store_true",
+                    help="add per-kernel times of one more update iteration to the ppo_update object")
     ap.add_argument("--score-all-columns", action="store_true",
                     help="rescoring with score_sequences (log-probs and values of the query columns too) instead of "
                          "score_responses")
@@ -360,9 +365,18 @@ def main():
         torch.cuda.synchronize()
         upd_ms = ev[0].elapsed_time(ev[1])
         update = {"iteration_ms": upd_ms, "rows": int(mask_u.sum().item()), "loss": float(st_u[0, 0]),
-                  "tflops": 3.0 * wc["score_flops"] / (upd_ms * 1e-3) / 1e12,
-                  "note": "one of the K = 4 iterations of an update; 3 x the scoring pass's flops (forward + twice "
-                          "that for the gradients) over its time, AdamW and the weight-image refresh included"}
+                  "tflops": wc["update_flops"] / (upd_ms * 1e-3) / 1e12,
+                  "note": "one of the K = 4 iterations of an update; 3 x the forward pass's flops (every row through "
+                          "the layers, the LM head on the response rows; twice that for the gradients) over its time, "
+                          "AdamW and the weight-image refresh included"}
+        if a.profile_update:   # one more iteration with per-kernel HIP events
+            pol.profile_enable(True)
+            pol.ppo_update(toks_u, mask_u, Lq, lps_d, adv_u, oldv_u, ret_u, kept_u, wl.temperature, epochs=1,
+                           n_minibatches=1)
+            up = pol.profile_read()
+            pol.profile_enable(False)
+            update["kernels_ms"] = {k: {"ms": round(v[0], 3), "launches": v[1]}
+                                    for k, v in sorted(up.items(), key=lambda kv: -kv[1][0])}
         pol._train = None
 
     # The paper's other scoring shapes (reward-model batches of 638 tokens, long-context batches of 2021),

@@ -947,6 +947,9 @@ namespace {
 struct MlpBwdWs {
   void *m, *u, *f, *go, *df, *goT, *fT, *mT, *w1T, *w2T;
   float *dm, *stats, *part;
+  void* slabs;         // fp32 partial results of the K-sliced weight-gradient products
+  size_t slabs_bytes;
+  float* lnpart;       // per-wave column sums of the one-pass LayerNorm backward
   int T_pad, splits;
 };
 MlpBwdWs carve_mlp_bwd(Carver& c, const rlhf_model_config& cfg, int T, size_t esz) {
@@ -968,6 +971,9 @@ MlpBwdWs carve_mlp_bwd(Carver& c, const rlhf_model_config& cfg, int T, size_t es
   w.dm = c.take<float>((size_t)T * d);
   w.stats = c.take<float>((size_t)2 * T);
   w.part = c.take<float>((size_t)w.splits * std::max(3 * d, F));
+  w.slabs_bytes = 8 * d * F * sizeof(float);
+  w.slabs = c.take_bytes(w.slabs_bytes);
+  w.lnpart = c.take<float>(ln_backward_rows_scratch_floats(T, (int)d));
   return w;
 }
 }  // namespace
@@ -1016,7 +1022,14 @@ int rlhf_mlp_backward(rlhf_handle* h, int32_t layer, const float* x_in, const fl
   LAUNCH("convert", launch_convert_from_f32(dt, d_out, ws.go, (size_t)T * d, s));
   LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.go, (size_t)d, ws.goT, (size_t)Tp, T, d, Tp, s));
   LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.f, (size_t)F, ws.fT, (size_t)Tp, T, F, Tp, s));
-  LAUNCH("gemm_mlp_dw", launch_gemm(dt, gemm(ws.goT, ws.fT, nullptr, d_w_fc2, d, F, Tp, EPI_F32), s));
+  auto dw_gemm = [&](const void* A, const void* W, void* out, int M, int N) {  // K = the rows: sliced
+    GemmArgs g = gemm(A, W, nullptr, out, M, N, Tp, EPI_F32);
+    g.long_k = true;
+    g.splitk_ws = ws.slabs;
+    g.splitk_ws_bytes = ws.slabs_bytes;
+    return g;
+  };
+  LAUNCH("gemm_mlp_dw", launch_gemm(dt, dw_gemm(ws.goT, ws.fT, d_w_fc2, d, F), s));
   LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, h->w_fc2[l], ld_w2, ws.w2T, (size_t)d, d, F, d, s));
   LAUNCH("gemm_mlp_dx", launch_gemm(dt, gemm(ws.go, ws.w2T, nullptr, ws.df, T, F, d, EPI_BIAS), s));
   // ---- GELU, then FC1: du = df * gelu'(u) (in place), db1 = sum_t du, dW1 = du^T m, dm = du W1
@@ -1024,13 +1037,17 @@ int rlhf_mlp_backward(rlhf_handle* h, int32_t layer, const float* x_in, const fl
   LAUNCH("colsum", launch_colsum(dt, ws.df, T, F, ws.part, ws.splits, d_b_fc1, s));
   LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.df, (size_t)F, ws.fT, (size_t)Tp, T, F, Tp, s));
   LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.m, (size_t)d, ws.mT, (size_t)Tp, T, d, Tp, s));
-  LAUNCH("gemm_mlp_dw", launch_gemm(dt, gemm(ws.fT, ws.mT, nullptr, d_w_fc1, F, d, Tp, EPI_F32), s));
+  LAUNCH("gemm_mlp_dw", launch_gemm(dt, dw_gemm(ws.fT, ws.mT, d_w_fc1, F, d), s));
   LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, h->w_fc1[l], (size_t)d, ws.w1T, (size_t)F, F, d, F, s));
   LAUNCH("gemm_mlp_dx", launch_gemm(dt, gemm(ws.df, ws.w1T, nullptr, ws.dm, T, d, F, EPI_F32), s));
   // ---- LN2: the branch's term of dL/dx, and the gradients of its gain and bias
-  LAUNCH("head_ln_backward", launch_head_ln_backward(dt, x_in, ws.dm, nullptr, 1.0f, nullptr, h->ln2_g[l], h->ln2_b[l], T,
-                                                     d, c.ln_eps, d_x, ws.stats, ws.part, ws.splits, d_ln2_g, d_ln2_b,
-                                                     nullptr, nullptr, s));
+  if (ln_backward_rows_supported(dt, d) && (((uintptr_t)x_in | (uintptr_t)d_x) & 15) == 0)
+    LAUNCH("ln_backward", launch_ln_backward_rows(x_in, ws.dm, h->ln2_g[l], T, d, c.ln_eps, d_x, ws.lnpart, d_ln2_g,
+                                                  d_ln2_b, s));
+  else
+    LAUNCH("head_ln_backward", launch_head_ln_backward(dt, x_in, ws.dm, nullptr, 1.0f, nullptr, h->ln2_g[l], h->ln2_b[l],
+                                                       T, d, c.ln_eps, d_x, ws.stats, ws.part, ws.splits, d_ln2_g,
+                                                       d_ln2_b, nullptr, nullptr, s));
   return RLHF_OK;
 }
 
@@ -1038,6 +1055,9 @@ namespace {
 struct AttnBwdWs {
   void *a, *qkv, *go, *dO, *att, *dqkv, *goT, *attT, *dqkvT, *aT, *woT, *wqkvT;
   float *da, *dwq, *dbq, *stats, *part, *lse, *delta;
+  void* slabs;         // fp32 partial results of the K-sliced weight-gradient products
+  size_t slabs_bytes;
+  float* lnpart;       // per-wave column sums of the one-pass LayerNorm backward
   int T_pad, splits;
 };
 AttnBwdWs carve_attn_bwd(Carver& c, const rlhf_model_config& cfg, int T, size_t esz) {
@@ -1065,6 +1085,9 @@ AttnBwdWs carve_attn_bwd(Carver& c, const rlhf_model_config& cfg, int T, size_t 
   w.part = c.take<float>((size_t)w.splits * 3 * d);
   w.lse = c.take<float>((size_t)T * cfg.n_heads);
   w.delta = c.take<float>((size_t)T * cfg.n_heads);
+  w.slabs_bytes = 8 * 3 * d * d * sizeof(float);
+  w.slabs = c.take_bytes(w.slabs_bytes);
+  w.lnpart = c.take<float>(ln_backward_rows_scratch_floats(T, (int)d));
   return w;
 }
 }  // namespace
@@ -1133,14 +1156,21 @@ int rlhf_attention_branch_backward(rlhf_handle* h, int32_t layer, const float* x
   // ---- dWo = G^T o
   LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.go, (size_t)d, ws.goT, (size_t)Tp, T, d, Tp, s));
   LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.att, (size_t)d, ws.attT, (size_t)Tp, T, d, Tp, s));
-  LAUNCH("gemm_attn_dw", launch_gemm(dt, gemm(ws.goT, ws.attT, nullptr, d_w_o, d, d, Tp, EPI_F32), s));
+  auto dw_gemm = [&](const void* A, const void* W, void* out, int M, int N) {  // K = the rows: sliced
+    GemmArgs g = gemm(A, W, nullptr, out, M, N, Tp, EPI_F32);
+    g.long_k = true;
+    g.splitk_ws = ws.slabs;
+    g.splitk_ws_bytes = ws.slabs_bytes;
+    return g;
+  };
+  LAUNCH("gemm_attn_dw", launch_gemm(dt, dw_gemm(ws.goT, ws.attT, d_w_o, d, d), s));
   // ---- back through the rotary turn, then the QKV product: dbqkv, dWqkv, da
   LAUNCH("rope_inplace", launch_rope_inplace(dt, ws.dqkv, (size_t)3 * d, cu_seqlens, B, T, H, hd, c.rotary_dims,
                                              h->rope_cos, h->rope_sin, 1, s));
   LAUNCH("colsum", launch_colsum(dt, ws.dqkv, T, 3 * d, ws.part, ws.splits, reordered ? ws.dbq : d_b_qkv, s));
   LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.dqkv, (size_t)3 * d, ws.dqkvT, (size_t)Tp, T, 3 * d, Tp, s));
   LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.a, (size_t)d, ws.aT, (size_t)Tp, T, d, Tp, s));
-  LAUNCH("gemm_attn_dw", launch_gemm(dt, gemm(ws.dqkvT, ws.aT, nullptr, reordered ? ws.dwq : d_w_qkv, 3 * d, d, Tp, EPI_F32), s));
+  LAUNCH("gemm_attn_dw", launch_gemm(dt, dw_gemm(ws.dqkvT, ws.aT, reordered ? ws.dwq : d_w_qkv, 3 * d, d), s));
   if (reordered) {
     LAUNCH("qkv_rows", launch_qkv_rows_to_caller_order(ws.dwq, d_w_qkv, d, hd, c.rotary_dims, d, s));
     LAUNCH("qkv_rows", launch_qkv_rows_to_caller_order(ws.dbq, d_b_qkv, d, hd, c.rotary_dims, 1, s));
@@ -1148,9 +1178,13 @@ int rlhf_attention_branch_backward(rlhf_handle* h, int32_t layer, const float* x
   LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, h->w_qkv[l], (size_t)d, ws.wqkvT, (size_t)3 * d, 3 * d, d, 3 * d, s));
   LAUNCH("gemm_attn_dx", launch_gemm(dt, gemm(ws.dqkv, ws.wqkvT, nullptr, ws.da, T, d, 3 * d, EPI_F32), s));
   // ---- LN1: the branch's term of dL/dx, and the gradients of its gain and bias
-  LAUNCH("head_ln_backward", launch_head_ln_backward(dt, x_in, ws.da, nullptr, 1.0f, nullptr, h->ln1_g[l], h->ln1_b[l], T,
-                                                     d, c.ln_eps, d_x, ws.stats, ws.part, ws.splits, d_ln1_g, d_ln1_b,
-                                                     nullptr, nullptr, s));
+  if (ln_backward_rows_supported(dt, d) && (((uintptr_t)x_in | (uintptr_t)d_x) & 15) == 0)
+    LAUNCH("ln_backward", launch_ln_backward_rows(x_in, ws.da, h->ln1_g[l], T, d, c.ln_eps, d_x, ws.lnpart, d_ln1_g,
+                                                  d_ln1_b, s));
+  else
+    LAUNCH("head_ln_backward", launch_head_ln_backward(dt, x_in, ws.da, nullptr, 1.0f, nullptr, h->ln1_g[l], h->ln1_b[l],
+                                                       T, d, c.ln_eps, d_x, ws.stats, ws.part, ws.splits, d_ln1_g,
+                                                       d_ln1_b, nullptr, nullptr, s));
   return RLHF_OK;
 }
 

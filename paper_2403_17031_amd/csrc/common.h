@@ -163,6 +163,9 @@ struct GemmArgs {
   int lda = 0, ldw = 0;        // row strides of A and W in elements (0: K); fp16 kernels only
   const void* bias2 = nullptr; // second bias added like the first; large-M fp16 kernel only
   int max_split = 0;           // few-rows kernel: cap on the K split (0: as many as cover the chip)
+  bool long_k = false;         // large-M kernel, fp32 output, no bias: K may be cut into slices whose fp32 slabs (in
+                               // splitk_ws) are then summed in slice order -- for products with few output tiles and
+                               // a very long K (weight gradients)
   bool small_footprint = false;  // few rows: stay on the staged tile kernel (24 KB of LDS, 4 blocks per CU), whose
                                  // blocks fit next to another kernel's on a CU; the weight-streaming kernel takes a
                                  // whole CU per block
@@ -321,6 +324,12 @@ hipError_t launch_softmax_grad(int dtype, const float* logits, int V, int V_pad,
                                int rows, int rows_pad, float inv_temp, float scale, void* dz, hipStream_t s);
 // dy = dhl + gv * scale * value_w; dx = LayerNorm input gradient of dy; d_g = sum_t dy * xhat, d_b = sum_t dy,
 // d_wv = sum_t gv * scale * h, d_bv = scale * sum_t gv.  stats [T, 2] and part [splits, 3, d] are scratch.
+// LayerNorm backward of a layer (no value-head term) in one pass: dx, d_g = sum_t dy * xhat, d_b = sum_t dy.
+// bf16 parameters, d a multiple of 256 up to 4096; part: ln_backward_rows_scratch_floats(T, d) floats of scratch.
+bool ln_backward_rows_supported(int dtype, int d);
+size_t ln_backward_rows_scratch_floats(int T, int d);
+hipError_t launch_ln_backward_rows(const float* x, const float* dy, const void* g, int T, int d, float eps, float* dx,
+                                   float* part, float* d_g, float* d_b, hipStream_t s);
 hipError_t launch_head_ln_backward(int dtype, const float* x, const float* dhl, const float* gv, float scale,
                                    const void* value_w, const void* g, const void* b, int T, int d, float eps,
                                    float* dx, float* stats, float* part, int splits, float* d_g, float* d_b,

@@ -317,7 +317,7 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
     gemm_f16_dma_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
                         void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
                         int ldo, int nb_m, int nb_n, int lda, int ldw, const bf16_t* __restrict__ bias2,
-                        LseArgs lse, QkvArgs qk) {
+                        LseArgs lse, QkvArgs qk, int k_slice, size_t slab) {
   // WAVES = 4: one wave per SIMD, each 128 x 128 of the tile (256 accumulator registers).
   // WAVES = 8: two waves per SIMD, each 128 x 64 (128 accumulator registers): what one wave cannot
   // overlap (waits, epilogue arithmetic against stores) the SIMD's other wave fills.
@@ -341,6 +341,15 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
   const int tm = grp * GROUP_M + rem % gm, tn = rem / gm;
   const int m0 = tm * TM, n0 = tn * TN;
 
+  // K split over blockIdx.y (weight-gradient products: few tiles, a very long K): slice z covers
+  // [z * k_slice, min(K, (z + 1) * k_slice)) and writes its fp32 result to slab z of `out`
+  if (k_slice > 0) {
+    const int kb = blockIdx.y * k_slice;
+    A += kb;
+    W += kb;
+    K = min(k_slice, K - kb);
+    out = (float*)out + (size_t)blockIdx.y * slab;
+  }
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps LDS bases in SGPRs
   const int wm = (wave / NWN) * 128, wn = (wave % NWN) * WN;
@@ -678,15 +687,17 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
 }
 
 template <int EPI>
-static void launch_f16_dma(const GemmArgs& a, hipStream_t s) {
+static void launch_f16_dma(const GemmArgs& a, hipStream_t s, int k_slices = 1, int k_slice = 0) {
   const int nb_m = (a.M_max + 255) / 256, nb_n = (a.N + 255) / 256;
   const int per_xcd = (nb_m * nb_n + 7) / 8;
   // Eight waves measure 8-10 % faster than four on the layer shapes.
   constexpr int WV = kDmaWaves;
-  hipLaunchKernelGGL((gemm_f16_dma_kernel<EPI, WV>), dim3(per_xcd * 8), dim3(64 * WV), 0, s, (const half_t*)a.A,
-                     (const half_t*)a.W, (const bf16_t*)a.bias, a.out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, a.ldo,
-                     nb_m, nb_n, a.lda ? a.lda : a.K, a.ldw ? a.ldw : a.K, (const bf16_t*)a.bias2,
-                     a.lse ? *a.lse : LseArgs{}, a.qkv ? *a.qkv : QkvArgs{});
+  const bool split = k_slices > 1;
+  hipLaunchKernelGGL((gemm_f16_dma_kernel<EPI, WV>), dim3(per_xcd * 8, split ? k_slices : 1), dim3(64 * WV), 0, s,
+                     (const half_t*)a.A, (const half_t*)a.W, (const bf16_t*)a.bias, split ? a.splitk_ws : a.out, a.M_max,
+                     a.M_dev, a.M_sub, a.N, a.K, split ? a.N : a.ldo, nb_m, nb_n, a.lda ? a.lda : a.K,
+                     a.ldw ? a.ldw : a.K, (const bf16_t*)a.bias2, a.lse ? *a.lse : LseArgs{},
+                     a.qkv ? *a.qkv : QkvArgs{}, split ? k_slice : 0, split ? (size_t)a.M_max * a.N : (size_t)0);
 }
 
 #ifndef RLHF_GEMM_DMA
@@ -756,6 +767,26 @@ static bool takes_dma(const GemmArgs& a) {
   return RLHF_GEMM_DMA && a.M_max > 512 && (a.K % (2 * DK)) == 0 && (a.N % 8) == 0 && (a.ldo % 8) == 0 &&
          (lda % 8) == 0 && (ldw % 8) == 0 && std::max((size_t)a.M_max * lda, (size_t)a.N * ldw) < (1ull << 32);
 }
+// K slices of a large-M product with few output tiles and a long K (GemmArgs::long_k: the weight-gradient
+// products of a backward pass, K = the batch's rows): the slice count (at most 8, each slice a whole number of
+// stage pairs, the fp32 slabs fitting the caller's scratch) that minimises rounds of 256 tiles times slice length.
+static int dma_k_slices(const GemmArgs& a, int* k_slice) {
+  *k_slice = 0;
+  if (!a.long_k || !a.splitk_ws || a.M_dev || a.bias || a.ldo != a.N ||
+      (a.epilogue != EPI_F32 && a.epilogue != EPI_BIAS_RESADD))
+    return 1;
+  const int tiles = ((a.M_max + 255) / 256) * ((a.N + 255) / 256), pairs = a.K / (2 * DK);
+  int best = 1, best_q = pairs;
+  double best_t = (double)((tiles + 255) / 256) * pairs;
+  for (int sp = 2; sp <= 8; ++sp) {
+    const int q = (pairs + sp - 1) / sp, n = (pairs + q - 1) / q;  // n non-empty slices of q stage pairs
+    if (q < 8 || (size_t)n * a.M_max * a.N * sizeof(float) > a.splitk_ws_bytes) continue;
+    const double t = (double)((tiles * n + 255) / 256) * q;
+    if (t < best_t * 0.97) { best_t = t; best = n; best_q = q; }
+  }
+  *k_slice = best_q * 2 * DK;
+  return best;
+}
 bool gemm_takes_bias2(int dtype, const GemmArgs& a) { return dtype == 1 && takes_dma(a); }
 bool gemm_takes_lse(int dtype, const GemmArgs& a) { return dtype == 1 && takes_dma(a); }
 // EPI_QKV: 16-byte chunks must not straddle heads, a lane's 4-column group must be whole pairs, and the
@@ -798,8 +829,21 @@ static void launch_epi(int dtype, const GemmArgs& a, hipStream_t s) {
     }
     if (a.M_max <= 512)
       launch_f16<EPI, 2, 1, RLHF_DEC_PF, RLHF_DEC_OCC>(a, s, a.out, 1);
-    else if (takes_dma(a))
+    else if (takes_dma(a)) {
+      int k_slice = 0;
+      const int n = dma_k_slices(a, &k_slice);
+      if constexpr (EPI == EPI_F32 || EPI == EPI_BIAS_RESADD) {
+        if (n > 1) {  // fp32 slabs, then their sum in slab order into (or, residual form, onto) the output
+          launch_f16_dma<EPI_F32>(a, s, n, k_slice);
+          const size_t quads = ((size_t)a.M_max * a.ldo + 3) / 4;
+          hipLaunchKernelGGL((splitk_reduce_kernel<EPI>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
+                             (const float*)a.splitk_ws, n, (size_t)a.M_max * a.N, (const bf16_t*)nullptr, a.out,
+                             a.M_max, a.N, a.ldo);
+          return;
+        }
+      }
       launch_f16_dma<EPI>(a, s);
+    }
     else
       launch_f16<EPI, RLHF_GEMM_MT, RLHF_GEMM_NT, RLHF_GEMM_PF, RLHF_GEMM_OCC>(a, s, a.out, 1);
   }

@@ -12,6 +12,7 @@ namespace {
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
 __device__ __forceinline__ float block_sum(float v, float* sh) {  // 256 threads; sh: 4 floats
   v = wave_sum(v);
@@ -259,6 +260,100 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+// The layers' LayerNorm backward in one pass over the data: a wave owns a run of consecutive rows, holds a row of x
+// and of dy in registers (NV float4 per lane, d = 256 * NV), forms the row's statistics and dx, and keeps the column
+// sums sum dy * xh and sum dy of its rows in registers; they go to part [waves][2][d], which
+// ln_backward_rows_final_kernel adds in wave order.  x, dy read once, dx written once.
+template <int NV>
+__global__ void __launch_bounds__(256)
+    ln_backward_rows_kernel(const float* __restrict__ x, const float* __restrict__ dyp, const bf16_t* __restrict__ g,
+                            int T, float eps, float* __restrict__ dx, float* __restrict__ part, int rows_per_wave) {
+  constexpr int d = 256 * NV;
+  const int lane = threadIdx.x & 63;
+  const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int t0 = gw * rows_per_wave, t1 = min(T, t0 + rows_per_wave);
+  f32x4_t sg[NV], sb[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    sg[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    sb[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
+  for (int t = t0; t < t1; ++t) {
+    const f32x4_t* xr = (const f32x4_t*)(x + (size_t)t * d);
+    const f32x4_t* dr = (const f32x4_t*)(dyp + (size_t)t * d);
+    f32x4_t xv[NV], dv[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      xv[j] = xr[lane + 64 * j];
+      dv[j] = dr[lane + 64 * j];
+    }
+    float a = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) a += (xv[j][0] + xv[j][1]) + (xv[j][2] + xv[j][3]);
+    const float mean = wave_sum(a) / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        xv[j][e] -= mean;
+        q += xv[j][e] * xv[j][e];
+      }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+    float su = 0.f, sux = 0.f;
+    f32x4_t u[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const u32x2_t gb = *(const u32x2_t*)(g + 4 * (lane + 64 * j));
+      const float gf[4] = {__uint_as_float(gb[0] << 16), __uint_as_float(gb[0] & 0xFFFF0000u),
+                           __uint_as_float(gb[1] << 16), __uint_as_float(gb[1] & 0xFFFF0000u)};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        xv[j][e] *= rstd;  // xh
+        u[j][e] = dv[j][e] * gf[e];
+        su += u[j][e];
+        sux += u[j][e] * xv[j][e];
+        sg[j][e] += dv[j][e] * xv[j][e];
+        sb[j][e] += dv[j][e];
+      }
+    }
+    const float mu = wave_sum(su) / (float)d, mux = wave_sum(sux) / (float)d;
+    f32x4_t* o = (f32x4_t*)(dx + (size_t)t * d);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      f32x4_t r;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r[e] = rstd * (u[j][e] - mu - xv[j][e] * mux);
+      o[lane + 64 * j] = r;
+    }
+  }
+  f32x4_t* p = (f32x4_t*)(part + (size_t)gw * 2 * d);
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    p[lane + 64 * j] = sg[j];
+    p[d / 4 + lane + 64 * j] = sb[j];
+  }
+}
+
+__global__ void __launch_bounds__(256)
+    ln_backward_rows_final_kernel(const float* __restrict__ part, int waves, int d, float* __restrict__ d_g,
+                                  float* __restrict__ d_b) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= 2 * d) return;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;  // four interleaved chains, added at the end: a fixed order
+  int w = 0;
+  for (; w + 4 <= waves; w += 4) {
+    s0 += part[(size_t)w * 2 * d + c];
+    s1 += part[(size_t)(w + 1) * 2 * d + c];
+    s2 += part[(size_t)(w + 2) * 2 * d + c];
+    s3 += part[(size_t)(w + 3) * 2 * d + c];
+  }
+  for (; w < waves; ++w) s0 += part[(size_t)w * 2 * d + c];
+  const float r = (s0 + s1) + (s2 + s3);
+  if (c < d) d_g[c] = r;
+  else d_b[c - d] = r;
+}
+
 // Column sums over a range of rows: block (column block, row split) leaves, for each of its 256
 // columns, sum dy * xh, sum dy and sum gv * h over its rows (h = the final LayerNorm's output in the
 // activation type A, as the forward pass produces it).  part: [splits][3][d].
@@ -394,6 +489,33 @@ __global__ void __launch_bounds__(256)
   for (int r = r0; r < r1; ++r) s += to_f32(a[(size_t)r * C + c]);
   part[(size_t)blockIdx.y * C + c] = s;
 }
+// The same with 16-byte accesses: a thread owns 16 bytes' worth of neighbouring columns (4 floats or 8 halfs) and
+// keeps four rows' loads in flight; rows are still added in increasing order.
+template <typename T>
+__global__ void __launch_bounds__(256)
+    colsum_part_vec_kernel(const T* __restrict__ a, int R, int C, int rows_per_split, float* __restrict__ part) {
+  constexpr int V = 16 / sizeof(T);
+  const int c0 = (blockIdx.x * 256 + threadIdx.x) * V;
+  if (c0 >= C) return;
+  const int r0 = blockIdx.y * rows_per_split, r1 = min(R, r0 + rows_per_split);
+  float s[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) s[i] = 0.f;
+  const u32x4_t zero = {0u, 0u, 0u, 0u};
+  for (int r = r0; r < r1; r += 4) {
+    u32x4_t v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = r + k < r1 ? *(const u32x4_t*)(a + (size_t)(r + k) * C + c0) : zero;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const T* e = (const T*)&v[k];
+#pragma unroll
+      for (int i = 0; i < V; ++i) s[i] += to_f32(e[i]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < V; ++i) part[(size_t)blockIdx.y * C + c0 + i] = s[i];
+}
 __global__ void __launch_bounds__(256)
     colsum_final_kernel(const float* __restrict__ part, int splits, int C, float* __restrict__ out) {
   const int c = blockIdx.x * 256 + threadIdx.x;
@@ -496,7 +618,15 @@ hipError_t launch_colsum(int elem, const void* a, int R, int C, float* part, int
   if (C <= 0) return hipSuccess;
   const int rps = (std::max(R, 1) + splits - 1) / splits;
   dim3 grid((C + 255) / 256, splits);
-  if (elem == 0) hipLaunchKernelGGL(colsum_part_kernel<float>, grid, dim3(256), 0, s, (const float*)a, R, C, rps, part);
+  const int V = elem == 0 ? 4 : 8;
+  if (C % V == 0 && ((uintptr_t)a & 15) == 0) {
+    dim3 vgrid((C / V + 255) / 256, splits);
+    if (elem == 0)
+      hipLaunchKernelGGL(colsum_part_vec_kernel<float>, vgrid, dim3(256), 0, s, (const float*)a, R, C, rps, part);
+    else
+      hipLaunchKernelGGL(colsum_part_vec_kernel<half_t>, vgrid, dim3(256), 0, s, (const half_t*)a, R, C, rps, part);
+  } else if (elem == 0)
+    hipLaunchKernelGGL(colsum_part_kernel<float>, grid, dim3(256), 0, s, (const float*)a, R, C, rps, part);
   else hipLaunchKernelGGL(colsum_part_kernel<half_t>, grid, dim3(256), 0, s, (const half_t*)a, R, C, rps, part);
   hipLaunchKernelGGL(colsum_final_kernel, dim3((C + 255) / 256), dim3(256), 0, s, part, splits, C, out);
   return hipGetLastError();
@@ -544,6 +674,30 @@ hipError_t launch_softmax_grad(int dtype, const float* logits, int V, int V_pad,
     if (mode) RLHF_SG(half_t, 1); else RLHF_SG(half_t, 0);
   }
 #undef RLHF_SG
+  return hipGetLastError();
+}
+
+bool ln_backward_rows_supported(int dtype, int d) { return dtype == 1 && d % 256 == 0 && d / 256 >= 1 && d / 256 <= 16; }
+size_t ln_backward_rows_scratch_floats(int T, int d) {
+  const int rpw = std::max(1, (T + 2047) / 2048), waves = ((T + rpw - 1) / rpw + 3) & ~3;
+  return (size_t)waves * 2 * d;
+}
+hipError_t launch_ln_backward_rows(const float* x, const float* dy, const void* g, int T, int d, float eps, float* dx,
+                                   float* part, float* d_g, float* d_b, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  const int rpw = std::max(1, (T + 2047) / 2048), waves = ((T + rpw - 1) / rpw + 3) & ~3;
+#define RLHF_LNB(NV)                                                                                             \
+  case NV:                                                                                                       \
+    hipLaunchKernelGGL(ln_backward_rows_kernel<NV>, dim3(waves / 4), dim3(256), 0, s, x, dy, (const bf16_t*)g, T, \
+                       eps, dx, part, rpw);                                                                      \
+    break;
+  switch (d / 256) {
+    RLHF_LNB(1) RLHF_LNB(2) RLHF_LNB(3) RLHF_LNB(4) RLHF_LNB(5) RLHF_LNB(6) RLHF_LNB(7) RLHF_LNB(8)
+    RLHF_LNB(9) RLHF_LNB(10) RLHF_LNB(11) RLHF_LNB(12) RLHF_LNB(13) RLHF_LNB(14) RLHF_LNB(15) RLHF_LNB(16)
+    default: return hipErrorInvalidValue;
+  }
+#undef RLHF_LNB
+  hipLaunchKernelGGL(ln_backward_rows_final_kernel, dim3((2 * d + 255) / 256), dim3(256), 0, s, part, waves, d, d_g, d_b);
   return hipGetLastError();
 }
 

@@ -107,6 +107,8 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="BASELINE config index 1..5 (default: the 2.8B target)")
     ap.add_argument("--batch", type=int, default=None, help="override the config's batch (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="do not run the ceilings driver first (e.g. under a profiler, which should see this process only)")
     ap.add_argument("--no-update-leg", action="store_true",
                     help="skip the PPO-update leg (forward keeping activations, backward, AdamW; ~10 s at config 4)")
     ap.add_argument("--profile-update", action="store_true",
@@ -126,7 +128,7 @@ def main():
     import paper_2403_17031_amd as P
     from synth import WORKLOADS, make_weights, make_queries
 
-    ceil = measured_ceilings()   # before this process holds the GPU
+    ceil = None if a.no_ceilings else measured_ceilings()   # before this process holds the GPU
     wl = WORKLOADS[a.config]
     cfg = wl.model
     B = a.batch or wl.batch

@@ -135,7 +135,8 @@ __global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
   const int b = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * FA_BQ;
   const int n = len[b];
   if (q0 >= n) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: the per-tile branches below are scalar
   const int half = lane >> 5, l32 = lane & 31;
   const int d = H * HD;
   const half_t* kb = kc + ((size_t)kvoff[b] * H + (size_t)h * (len[b] + kv_extra)) * HD;
@@ -216,6 +217,10 @@ __global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
     }
   };
   load_tile(0);
+  // Everything loaded so far (the Q fragments, tile 0) is waited for here, once: otherwise the compiler's wait
+  // bookkeeping carries the Q loads as possibly pending around the loop and, since loads retire in order, makes
+  // every iteration wait for the tile it has just prefetched before the first matrix instruction that reads Q.
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   for (int k0 = 0; k0 <= q_hi; k0 += FA_BK) {
     __syncthreads();  // every wave is done with the previous tile
     store_tile();
@@ -223,33 +228,49 @@ __global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
     if (k0 + FA_BK <= q_hi) load_tile(k0 + FA_BK);
     if (k0 > wq_lo + 31) continue;  // every key of this tile is in the future of this wave's queries
 
-    // ---- S^T = K Q^T for the two 32-key fragments
+    // ---- S^T = K Q^T for the two 32-key fragments.  The two accumulation chains alternate, and the fragment
+    //      reads run four ahead of the matrix instructions (scheduling groups: left to itself the compiler
+    //      waits for every read right before the instruction that uses it)
     f32x16_t st[2];
-#pragma unroll
-    for (int kf = 0; kf < 2; ++kf) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) st[kf][e] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        const f16x8_t kfrag = *(const f16x8_t*)(Ks + (kf * 32 + l32) * K_STRIDE + 16 * ks + 8 * half);
-        st[kf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kfrag, qf[ks], st[kf], 0, 0, 0);
-      }
-    }
-    // ---- mask (only tiles that touch the diagonal or the end of the sequence), scale, running max
-    const bool need_mask = (k0 + FA_BK - 1 > wq_lo) || (k0 + FA_BK > n);
-    float mx = -INFINITY;
 #pragma unroll
     for (int kf = 0; kf < 2; ++kf)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float v = st[kf][e];  // raw dot products: the (positive) scale is applied inside the exponent's FMA
-        if (need_mask) {
-          const int kj = k0 + kf * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-          if (kj > qi || kj >= n) v = -INFINITY;
-        }
-        st[kf][e] = v;
-        mx = fmaxf(mx, v);
+      for (int e = 0; e < 16; ++e) st[kf][e] = 0.f;
+    {
+      f16x8_t kfr[2 * NKS];
+#pragma unroll
+      for (int i = 0; i < 2 * NKS; ++i)
+        kfr[i] = *(const f16x8_t*)(Ks + ((i & 1) * 32 + l32) * K_STRIDE + 16 * (i >> 1) + 8 * half);
+#pragma unroll
+      for (int i = 0; i < 2 * NKS; ++i)
+        st[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kfr[i], qf[i >> 1], st[i & 1], 0, 0, 0);
+      constexpr int AHEAD = 2 * NKS < 4 ? 2 * NKS : 4;
+      __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
+#pragma unroll
+      for (int i = 0; i < 2 * NKS - AHEAD; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x008, AHEAD, 0);
+    }
+    // ---- mask (only tiles that touch the diagonal or the end of the sequence), scale, running max
+    //      Key kj = k0 + 4*half + c of element (kf, e), c = 32*kf + 8*(e/4) + e%4 a constant, is visible iff
+    //      kj <= min(qi, n - 1), i.e. c <= lim with lim formed once per tile: a compare and a select per element
+    //      (the branch is wave-uniform).
+    const bool need_mask = (k0 + FA_BK - 1 > wq_lo) || (k0 + FA_BK > n);
+    if (need_mask) {
+      const int lim = min(qi, n - 1) - k0 - 4 * half;
+#pragma unroll
+      for (int kf = 0; kf < 2; ++kf)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (kf * 32 + 8 * (e >> 2) + (e & 3) > lim) st[kf][e] = -INFINITY;
+    }
+    float mx = -INFINITY;  // raw dot products: the (positive) scale is applied inside the exponent's FMA
+#pragma unroll
+    for (int kf = 0; kf < 2; ++kf)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[kf][e]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx * scale_log2e);  // finite: key 0 is visible to every query
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // arguments <= 0: the bare instruction will do
@@ -274,13 +295,22 @@ __global__ void __launch_bounds__(256, (HD <= 128 ? 2 : 1))
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
     }
+    //      (the NDT accumulation chains alternate; fragment reads four ahead as above)
+    {
+      f16x8_t vfr[4 * NDT];
 #pragma unroll
-    for (int t = 0; t < NDT; ++t) {
+      for (int i = 0; i < 4 * NDT; ++i)
+        vfr[i] = *(const f16x8_t*)(Vt + ((i % NDT) * 32 + l32) * FA_VT_STRIDE + 16 * (i / NDT) + 8 * half);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const f16x8_t vfrag = *(const f16x8_t*)(Vt + (t * 32 + l32) * FA_VT_STRIDE + 16 * c + 8 * half);
-        o[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vfrag, pf[c], o[t], 0, 0, 0);
+      for (int i = 0; i < 4 * NDT; ++i)
+        o[i % NDT] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vfr[i], pf[i / NDT], o[i % NDT], 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int i = 0; i < 4 * NDT - 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
     }
   }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);

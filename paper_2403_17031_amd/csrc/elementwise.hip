@@ -1018,32 +1018,50 @@ hipError_t launch_lse_gather(const float* logits, int rows_max, int t0, const in
   return hipGetLastError();
 }
 
-// Scoring with the fused LM head: one thread per packed row combines the per-part statistics.
+// Scoring with the fused LM head: the per-part statistics of a row are combined by four threads (one per wave of
+// the block, each taking every fourth part; rows along the lanes so that the reads coalesce) and then across the
+// waves through LDS, in a fixed order.
 __global__ void __launch_bounds__(256)
     lse_combine_kernel(LseArgs a, int nparts, float* __restrict__ lp_packed) {
-  const int t = blockIdx.x * 256 + threadIdx.x;
+  __shared__ float sm[4][64], ss[4][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int t = blockIdx.x * 64 + lane;
   const int T = *a.T_dev;
+  const bool row = t < T;
+  float m = -INFINITY, s = 0.f;
+  if (row) {
+    for (int p = w; p < nparts; p += 4) {  // online: rescale the running sum when the maximum moves
+      const float pm = a.pmax[(size_t)p * a.stride + t];
+      if (pm > -INFINITY) {
+        const float ps = a.psum[(size_t)p * a.stride + t];
+        const float mn = fmaxf(m, pm);
+        s = s * expf(m - mn) + ps * expf(pm - mn);
+        m = mn;
+      }
+    }
+  }
+  sm[w][lane] = m;
+  ss[w][lane] = s;
+  __syncthreads();
+  if (w != 0 || !row) return;
+  m = fmaxf(fmaxf(sm[0][lane], sm[1][lane]), fmaxf(sm[2][lane], sm[3][lane]));
+  s = 0.f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    if (sm[k][lane] > -INFINITY) s += ss[k][lane] * expf(sm[k][lane] - m);
   if (a.tgt) {
-    if (t >= T) return;
     if (a.val_out) a.val_out[a.dst[t]] = a.val_in[t];
     if (a.tgt[t] < 0) return;
   } else {
     if (t + 1 >= T) return;
     if (a.pos[t + 1] != a.pos[t] + 1) return;  // t is the last token of its sequence: nothing to predict
   }
-  float m = -INFINITY;
-  for (int p = 0; p < nparts; ++p) m = fmaxf(m, a.pmax[(size_t)p * a.stride + t]);
-  float s = 0.f;
-  for (int p = 0; p < nparts; ++p) {
-    const float pm = a.pmax[(size_t)p * a.stride + t];
-    if (pm > -INFINITY) s += a.psum[(size_t)p * a.stride + t] * expf(pm - m);
-  }
   lp_packed[(a.tgt ? a.dst[t] : t) + 1] = a.ztgt[t] - (m + logf(s));
 }
 
 hipError_t launch_lse_combine(const LseArgs& a, int rows_max, int nparts, float* lp_packed, hipStream_t s) {
   if (rows_max <= 0) return hipSuccess;
-  hipLaunchKernelGGL(lse_combine_kernel, dim3((rows_max + 255) / 256), dim3(256), 0, s, a, nparts, lp_packed);
+  hipLaunchKernelGGL(lse_combine_kernel, dim3((rows_max + 63) / 64), dim3(256), 0, s, a, nparts, lp_packed);
   return hipGetLastError();
 }
 

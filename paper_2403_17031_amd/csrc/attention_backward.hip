@@ -289,11 +289,12 @@ __global__ void __launch_bounds__(256, 1)
   __shared__ __attribute__((aligned(16))) uint16_t Gs[64 * RS];
   __shared__ __attribute__((aligned(16))) uint16_t Qt[NDT * 32 * TS];
   __shared__ __attribute__((aligned(16))) uint16_t Gt[NDT * 32 * TS];
-  __shared__ float lse_s[64], del_s[64];
+  __shared__ __attribute__((aligned(16))) float lse_s[64], del_s[64];
   const int b = blockIdx.z, h = blockIdx.y, k0 = blockIdx.x * 128;
   const int s0 = min(max(cu[b], 0), Tn), n = min(cu[b + 1], Tn) - s0;  // clamped: a malformed cu must not lead out of bounds
   if (k0 >= n) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: the per-tile tests become scalar branches
   const size_t col = (size_t)h * HD;
   const int kj = k0 + wave * 32 + l32;  // this lane's key
   const int kjc = min(kj, n - 1);
@@ -318,75 +319,128 @@ __global__ void __launch_bounds__(256, 1)
   const float scale_log2e = scale * 1.4426950408889634f;
   const int kw0 = k0 + wave * 32;  // first key of the wave
   constexpr int CPR = HD / 8;
-  for (int i0 = k0 & ~63; i0 < n; i0 += 64) {
-    __syncthreads();  // every wave is done with the previous tile
-    for (int c = tid; c < 64 * CPR; c += 256) {  // row-major images
-      const int r = c / CPR, ch = c - r * CPR;
-      const size_t row = (size_t)(s0 + min(i0 + r, n - 1));
-      *(u32x4_t*)(Qs + r * RS + ch * 8) = *(const u32x4_t*)(q + row * ldq + col + ch * 8);
-      *(u32x4_t*)(Gs + r * RS + ch * 8) = *(const u32x4_t*)(g + row * ldg + col + ch * 8);
+  // A tile travels global -> registers one iteration ahead of its use, once: a thread's item is 4 queries x 8 dims
+  // of Q and of dO, which it writes to LDS both row-major (4 x 16 bytes) and transposed (8 x 8 bytes, the 4 queries
+  // adjacent under the column permutation of the accumulator layout).  Threads past the tile's 16 * CPR items
+  // re-read the last item instead of branching around the loads (the wait counting stays static).
+  constexpr int ITEMS = 16 * CPR;
+  static_assert(ITEMS <= 256, "one item per thread");
+  const int item = min(tid, ITEMS - 1), ich = item / 16, ig4 = item - ich * 16;
+  f16x8_t qv[4], gv[4];
+  float lse_r = 0.f, del_r = 0.f;
+  auto load_tile = [&](int i0) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t row = (size_t)(s0 + min(i0 + 4 * ig4 + u, n - 1));
+      qv[u] = *(const f16x8_t*)(q + row * ldq + col + ich * 8);
+      gv[u] = *(const f16x8_t*)(g + row * ldg + col + ich * 8);
     }
-    for (int c = tid; c < 16 * CPR; c += 256) {  // transposed images: 4 queries x 8 dims per item
-      const int ch = c / 16, g4 = c - ch * 16;
-      const int kk = (4 * g4) & 15;
-      const int colp = ((4 * g4) & ~15) + 8 * ((kk >> 2) & 1) + 4 * (kk >> 3);
-      f16x8_t qv[4], gv[4];
+    const size_t row = (size_t)(s0 + min(i0 + (tid & 63), n - 1));
+    lse_r = lse[row * H + h];
+    del_r = delta[row * H + h];
+  };
+  auto store_tile = [&]() {
+    if (tid < ITEMS) {
+      const int kk = (4 * ig4) & 15;
+      const int colp = ((4 * ig4) & ~15) + 8 * ((kk >> 2) & 1) + 4 * (kk >> 3);
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const size_t row = (size_t)(s0 + min(i0 + 4 * g4 + u, n - 1));
-        qv[u] = *(const f16x8_t*)(q + row * ldq + col + ch * 8);
-        gv[u] = *(const f16x8_t*)(g + row * ldg + col + ch * 8);
+        *(f16x8_t*)((half_t*)Qs + (4 * ig4 + u) * RS + ich * 8) = qv[u];
+        *(f16x8_t*)((half_t*)Gs + (4 * ig4 + u) * RS + ich * 8) = gv[u];
       }
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const f16x4_t wq = {qv[0][e], qv[1][e], qv[2][e], qv[3][e]};
         const f16x4_t wg = {gv[0][e], gv[1][e], gv[2][e], gv[3][e]};
-        *(f16x4_t*)((half_t*)Qt + (ch * 8 + e) * TS + colp) = wq;
-        *(f16x4_t*)((half_t*)Gt + (ch * 8 + e) * TS + colp) = wg;
+        *(f16x4_t*)((half_t*)Qt + (ich * 8 + e) * TS + colp) = wq;
+        *(f16x4_t*)((half_t*)Gt + (ich * 8 + e) * TS + colp) = wg;
       }
     }
     if (tid < 64) {
-      const size_t row = (size_t)(s0 + min(i0 + tid, n - 1));
-      lse_s[tid] = lse[row * H + h] * 1.4426950408889634f;
-      del_s[tid] = delta[row * H + h];
+      lse_s[tid] = lse_r * 1.4426950408889634f;
+      del_s[tid] = del_r;
     }
+  };
+  const int i_first = k0 & ~63;
+  const int i_last = ((n - 1) / 64) * 64;  // first query of the sequence's last tile
+  load_tile(i_first);
+  // (the loads issued so far are waited for here, once: see the note in attn_prefill_mfma)
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  for (int i0 = i_first; i0 < n; i0 += 64) {
+    __syncthreads();  // every wave is done with the previous tile
+    store_tile();
     __syncthreads();
+    load_tile(min(i0 + 64, i_last));
     if (i0 + 63 < kw0) continue;  // every query of this tile comes before every key of this wave
+    // lse and delta of this lane's 32 queries of the tile: rows 32*qf2 + 8*g + 4*half + (0..3), as 4-vectors
     f16x8_t pf[4], df[4];  // P and dS of the tile for this lane's key, as second operands of the 16-query steps
+    // a query i sees key kj iff i >= kj; rows past the sequence's end and keys past it contribute nothing
+    const bool need_mask = (i0 < kw0 + 31) || (i0 + 64 > n) || (kw0 + 32 > n);
+    const int lo = kj - i0 - 4 * half, hi = (kj < n ? n : 0) - i0 - 4 * half;  // visible iff lo <= c < hi
 #pragma unroll
     for (int qf2 = 0; qf2 < 2; ++qf2) {
       f32x16_t st, dp;
+      {
+        f16x8_t qa[NKS], ga[NKS];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        st[e] = 0.f;
-        dp[e] = 0.f;
+        for (int ks = 0; ks < NKS; ++ks) {
+          qa[ks] = *(const f16x8_t*)(Qs + (qf2 * 32 + l32) * RS + 16 * ks + 8 * half);
+          ga[ks] = *(const f16x8_t*)(Gs + (qf2 * 32 + l32) * RS + 16 * ks + 8 * half);
+        }
+        const f32x16_t z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        st = z;
+        dp = z;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+          st = __builtin_amdgcn_mfma_f32_32x32x16_f16(qa[ks], kf[ks], st, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_f16(ga[ks], vf[ks], dp, 0, 0, 0);
+        }
+        // fragment reads four ahead of the matrix instructions
+        constexpr int AH = 2 * NKS < 4 ? 2 * NKS : 4;
+        __builtin_amdgcn_sched_group_barrier(0x100, AH, 0);
+#pragma unroll
+        for (int i = 0; i < 2 * NKS - AH; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, AH, 0);
+      }
+      f32x4_t ls[4], dl[4];
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        ls[g4] = *(const f32x4_t*)(lse_s + qf2 * 32 + 8 * g4 + 4 * half);
+        dl[g4] = *(const f32x4_t*)(del_s + qf2 * 32 + 8 * g4 + 4 * half);
       }
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        const f16x8_t qa = *(const f16x8_t*)(Qs + (qf2 * 32 + l32) * RS + 16 * ks + 8 * half);
-        const f16x8_t ga = *(const f16x8_t*)(Gs + (qf2 * 32 + l32) * RS + 16 * ks + 8 * half);
-        st = __builtin_amdgcn_mfma_f32_32x32x16_f16(qa, kf[ks], st, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_f16(ga, vf[ks], dp, 0, 0, 0);
-      }
-#pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int row = qf2 * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-        const int i = i0 + row;
-        const bool ok = i >= kj && i < n && kj < n;
-        const float pr = ok ? __builtin_amdgcn_exp2f(fmaf(st[e], scale_log2e, -lse_s[row])) : 0.f;
+        float pr = __builtin_amdgcn_exp2f(fmaf(st[e], scale_log2e, -ls[e >> 2][e & 3]));
+        if (need_mask) {
+          const int c = qf2 * 32 + 8 * (e >> 2) + (e & 3);
+          if (c < lo || c >= hi) pr = 0.f;
+        }
         pf[qf2 * 2 + (e >> 3)][e & 7] = (half_t)pr;
-        df[qf2 * 2 + (e >> 3)][e & 7] = (half_t)(pr * (dp[e] - del_s[row]));
+        df[qf2 * 2 + (e >> 3)][e & 7] = (half_t)(pr * (dp[e] - dl[e >> 2][e & 3]));
       }
     }
+    {
+      f16x8_t ga[4 * NDT], qa[4 * NDT];
 #pragma unroll
-    for (int t = 0; t < NDT; ++t) {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const f16x8_t ga = *(const f16x8_t*)(Gt + (t * 32 + l32) * TS + 16 * c + 8 * half);
-        const f16x8_t qa = *(const f16x8_t*)(Qt + (t * 32 + l32) * TS + 16 * c + 8 * half);
-        dvT[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ga, pf[c], dvT[t], 0, 0, 0);
-        dkT[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(qa, df[c], dkT[t], 0, 0, 0);
+      for (int i = 0; i < 4 * NDT; ++i) {
+        ga[i] = *(const f16x8_t*)(Gt + ((i % NDT) * 32 + l32) * TS + 16 * (i / NDT) + 8 * half);
+        qa[i] = *(const f16x8_t*)(Qt + ((i % NDT) * 32 + l32) * TS + 16 * (i / NDT) + 8 * half);
       }
+#pragma unroll
+      for (int i = 0; i < 4 * NDT; ++i) {
+        dvT[i % NDT] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ga[i], pf[i / NDT], dvT[i % NDT], 0, 0, 0);
+        dkT[i % NDT] = __builtin_amdgcn_mfma_f32_32x32x16_f16(qa[i], df[i / NDT], dkT[i % NDT], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int i = 0; i < 8 * NDT - 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
     }
   }
   if (kj < n) {
@@ -430,7 +484,8 @@ __global__ void __launch_bounds__(256, 1)
   const int b = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * 128;
   const int s0 = min(max(cu[b], 0), Tn), n = min(cu[b + 1], Tn) - s0;
   if (q0 >= n) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: the per-tile tests become scalar branches
   const size_t col = (size_t)h * HD;
   const int qi = q0 + wave * 32 + l32;  // this lane's query (two lanes per query: half 0 / 1)
   const int qic = min(qi, n - 1);
@@ -445,48 +500,81 @@ __global__ void __launch_bounds__(256, 1)
     Vt[HD * TS + c] = 0;
   }
   const int q_hi = min(q0 + 128, n) - 1, wq_lo = q0 + wave * 32;
+  const int k_last = (q_hi / 64) * 64;  // first key of the block's last tile
   const float scale_log2e = scale * 1.4426950408889634f;
-  auto load_tiles = [&](int k0) {
-    __syncthreads();  // every wave is done with the previous tile
-    for (int c = tid; c < 64 * CPR; c += 256) {
-      const int r = c / CPR, ch = c - r * CPR;
-      const size_t row = (size_t)(s0 + min(k0 + r, n - 1));
-      *(u32x4_t*)(Ks + r * RS + ch * 8) = *(const u32x4_t*)(k + row * ldq + col + ch * 8);
-      *(u32x4_t*)(Vs + r * RS + ch * 8) = *(const u32x4_t*)(v + row * ldq + col + ch * 8);
+  // A tile travels global -> registers one iteration ahead of its use, once: a thread's item is 4 keys x 8 dims of K
+  // and of V, which it writes to LDS row-major (4 x 16 bytes) and / or transposed (8 x 8 bytes, the 4 keys adjacent
+  // under the column permutation of the accumulator layout), whichever images the pass reads.  Threads past the
+  // tile's 16 * CPR items re-read the last item instead of branching around the loads (static wait counts).
+  constexpr int ITEMS = 16 * CPR;
+  static_assert(ITEMS <= 256, "one item per thread");
+  const int item = min(tid, ITEMS - 1), ich = item / 16, ig4 = item - ich * 16;
+  f16x8_t kv[4], vv[4];
+  auto load_tile = [&](int k0) {
+    k0 = min(k0, k_last);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t row = (size_t)(s0 + min(k0 + 4 * ig4 + u, n - 1));
+      kv[u] = *(const f16x8_t*)(k + row * ldq + col + ich * 8);
+      vv[u] = *(const f16x8_t*)(v + row * ldq + col + ich * 8);
     }
-    for (int c = tid; c < 16 * CPR; c += 256) {
-      const int ch = c / 16, g4 = c - ch * 16;
-      const int kk = (4 * g4) & 15;
-      const int colp = ((4 * g4) & ~15) + 8 * ((kk >> 2) & 1) + 4 * (kk >> 3);
-      f16x8_t kv[4], vv[4];
+  };
+  auto store_tile = [&](bool second_pass) {
+    if (tid < ITEMS) {
+      const int kk = (4 * ig4) & 15;
+      const int colp = ((4 * ig4) & ~15) + 8 * ((kk >> 2) & 1) + 4 * (kk >> 3);
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const size_t row = (size_t)(s0 + min(k0 + 4 * g4 + u, n - 1));
-        kv[u] = *(const f16x8_t*)(k + row * ldq + col + ch * 8);
-        vv[u] = *(const f16x8_t*)(v + row * ldq + col + ch * 8);
+        *(f16x8_t*)((half_t*)Ks + (4 * ig4 + u) * RS + ich * 8) = kv[u];
+        if (second_pass) *(f16x8_t*)((half_t*)Vs + (4 * ig4 + u) * RS + ich * 8) = vv[u];
       }
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const f16x4_t wk = {kv[0][e], kv[1][e], kv[2][e], kv[3][e]};
-        const f16x4_t wv = {vv[0][e], vv[1][e], vv[2][e], vv[3][e]};
-        *(f16x4_t*)((half_t*)Kt + (ch * 8 + e) * TS + colp) = wk;
-        *(f16x4_t*)((half_t*)Vt + (ch * 8 + e) * TS + colp) = wv;
-      }
-    }
-    __syncthreads();
-  };
-  auto scores = [&](f32x16_t* st) {  // S^T of the tile for this lane's query: two fragments of 32 keys
-#pragma unroll
-    for (int kf = 0; kf < 2; ++kf) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) st[kf][e] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        const f16x8_t ka = *(const f16x8_t*)(Ks + (kf * 32 + l32) * RS + 16 * ks + 8 * half);
-        st[kf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka, qf[ks], st[kf], 0, 0, 0);
+        if (second_pass) {
+          const f16x4_t wk = {kv[0][e], kv[1][e], kv[2][e], kv[3][e]};
+          *(f16x4_t*)((half_t*)Kt + (ich * 8 + e) * TS + colp) = wk;
+        } else {
+          const f16x4_t wv = {vv[0][e], vv[1][e], vv[2][e], vv[3][e]};
+          *(f16x4_t*)((half_t*)Vt + (ich * 8 + e) * TS + colp) = wv;
+        }
       }
     }
   };
+  // S^T of the tile for this lane's query: two fragments of 32 keys, their accumulation chains alternating, the
+  // fragment reads four ahead of the matrix instructions
+#define BWD_SCORES(ST)                                                                                      \
+  {                                                                                                         \
+    f16x8_t kfr[2 * NKS];                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < 2 * NKS; ++i)                                                     \
+        kfr[i] = *(const f16x8_t*)(Ks + ((i & 1) * 32 + l32) * RS + 16 * (i >> 1) + 8 * half);            \
+    const f32x16_t z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};    \
+    ST[0] = z;                                                                                              \
+    ST[1] = z;                                                                                              \
+    _Pragma("unroll") for (int i = 0; i < 2 * NKS; ++i)                                                     \
+        ST[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kfr[i], qf[i >> 1], ST[i & 1], 0, 0, 0);       \
+    constexpr int AH = 2 * NKS < 4 ? 2 * NKS : 4;                                                           \
+    __builtin_amdgcn_sched_group_barrier(0x100, AH, 0);                                                     \
+    _Pragma("unroll") for (int i = 0; i < 2 * NKS - AH; ++i) {                                              \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                    \
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                    \
+    }                                                                                                       \
+    __builtin_amdgcn_sched_group_barrier(0x008, AH, 0);                                                     \
+  }
+  // NDT accumulation chains over the four 16-key steps of a transposed image, reads four ahead
+#define BWD_OUT(IMG, OPS, ACC)                                                                              \
+  {                                                                                                         \
+    f16x8_t fr[4 * NDT];                                                                                    \
+    _Pragma("unroll") for (int i = 0; i < 4 * NDT; ++i)                                                     \
+        fr[i] = *(const f16x8_t*)(IMG + ((i % NDT) * 32 + l32) * TS + 16 * (i / NDT) + 8 * half);         \
+    _Pragma("unroll") for (int i = 0; i < 4 * NDT; ++i)                                                     \
+        ACC[i % NDT] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[i], OPS[i / NDT], ACC[i % NDT], 0, 0, 0); \
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);                                                      \
+    _Pragma("unroll") for (int i = 0; i < 4 * NDT - 4; ++i) {                                               \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                    \
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                    \
+    }                                                                                                       \
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);                                                      \
+  }
   // ---- pass 1: the forward pass
   f32x16_t acc[NDT];
 #pragma unroll
@@ -494,20 +582,31 @@ __global__ void __launch_bounds__(256, 1)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
+  load_tile(0);
+  // (the loads issued so far are waited for here, once: see the note in attn_prefill_mfma)
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   for (int k0 = 0; k0 <= q_hi; k0 += 64) {
-    load_tiles(k0);
+    __syncthreads();  // every wave is done with the previous tile
+    store_tile(false);
+    __syncthreads();
+    load_tile(k0 + 64 <= q_hi ? k0 + 64 : 0);  // after the last tile: tile 0, which the second pass starts with
     if (k0 > wq_lo + 31) continue;  // every key of this tile is in the future of this wave's queries
     f32x16_t st[2];
-    scores(st);
+    BWD_SCORES(st)
+    // key kj = k0 + 4*half + c of element (kf, e), c = 32*kf + 8*(e/4) + e%4, is visible iff kj <= min(qi, n - 1)
+    if ((k0 + 63 > wq_lo) || (k0 + 64 > n)) {
+      const int lim = min(qi, n - 1) - k0 - 4 * half;
+#pragma unroll
+      for (int kf = 0; kf < 2; ++kf)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (kf * 32 + 8 * (e >> 2) + (e & 3) > lim) st[kf][e] = -INFINITY;
+    }
     float mx = -INFINITY;
 #pragma unroll
     for (int kf = 0; kf < 2; ++kf)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int kj = k0 + kf * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-        if (kj > qi || kj >= n) st[kf][e] = -INFINITY;
-        mx = fmaxf(mx, st[kf][e]);
-      }
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[kf][e]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx * scale_log2e);  // finite: key 0 is visible to every query
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
@@ -523,17 +622,13 @@ __global__ void __launch_bounds__(256, 1)
         pf[kf * 2 + (e >> 3)][e & 7] = (half_t)p;
       }
     l_run = l_run * alpha + psum;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-    for (int t = 0; t < NDT; ++t)
+      for (int t = 0; t < NDT; ++t)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[t][e] *= alpha;
-#pragma unroll
-    for (int t = 0; t < NDT; ++t)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const f16x8_t va = *(const f16x8_t*)(Vt + (t * 32 + l32) * TS + 16 * c + 8 * half);
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pf[c], acc[t], 0, 0, 0);
-      }
+        for (int e = 0; e < 16; ++e) acc[t][e] *= alpha;
+    }
+    BWD_OUT(Vt, pf, acc)
   }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = 1.0f / l_tot;
@@ -570,38 +665,40 @@ __global__ void __launch_bounds__(256, 1)
   for (int t = 0; t < NDT; ++t)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
-  for (int k0 = 0; k0 <= q_hi; k0 += 64) {
-    load_tiles(k0);
+  for (int k0 = 0; k0 <= q_hi; k0 += 64) {  // (tile 0 is in the registers: the first pass's last load)
+    __syncthreads();
+    store_tile(true);
+    __syncthreads();
+    load_tile(k0 + 64);
     if (k0 > wq_lo + 31) continue;
     f32x16_t st[2];
-    scores(st);
+    BWD_SCORES(st)
     f16x8_t df[4];
+    const bool need_mask = (k0 + 63 > wq_lo) || (k0 + 64 > n);
+    const int lim = min(qi, n - 1) - k0 - 4 * half;
 #pragma unroll
     for (int kf = 0; kf < 2; ++kf) {
       f32x16_t dp;
+      {
+        f16x8_t va[NKS];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) dp[e] = 0.f;
+        for (int ks = 0; ks < NKS; ++ks) va[ks] = *(const f16x8_t*)(Vs + (kf * 32 + l32) * RS + 16 * ks + 8 * half);
+        const f32x16_t z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        dp = z;
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        const f16x8_t va = *(const f16x8_t*)(Vs + (kf * 32 + l32) * RS + 16 * ks + 8 * half);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, gf[ks], dp, 0, 0, 0);
+        for (int ks = 0; ks < NKS; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[ks], gf[ks], dp, 0, 0, 0);
       }
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int kj = k0 + kf * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-        const bool ok = kj <= qi && kj < n;
-        const float pr = ok ? __builtin_amdgcn_exp2f(fmaf(st[kf][e], scale_log2e, -lse2)) : 0.f;
+        float pr = __builtin_amdgcn_exp2f(fmaf(st[kf][e], scale_log2e, -lse2));
+        if (need_mask && kf * 32 + 8 * (e >> 2) + (e & 3) > lim) pr = 0.f;
         df[kf * 2 + (e >> 3)][e & 7] = (half_t)(pr * (dp[e] - dl));
       }
     }
-#pragma unroll
-    for (int t = 0; t < NDT; ++t)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const f16x8_t ka = *(const f16x8_t*)(Kt + (t * 32 + l32) * TS + 16 * c + 8 * half);
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka, df[c], acc[t], 0, 0, 0);
-      }
+    BWD_OUT(Kt, df, acc)
   }
+#undef BWD_SCORES
+#undef BWD_OUT
   if (qi < n) {
     half_t* drow = dq + (size_t)(s0 + qi) * ldo + col;
 #pragma unroll

@@ -958,11 +958,11 @@ MlpBwdWs carve_mlp_bwd(Carver& c, const rlhf_model_config& cfg, int T, size_t es
   w.T_pad = (T + 127) & ~127;  // the row count is the K of the weight-gradient products
   w.splits = std::max(1, std::min(256, (T + 255) / 256));
   const size_t Tp = (size_t)w.T_pad;
-  w.m = c.take_bytes((size_t)T * d * esz);
+  w.m = c.take_bytes(Tp * d * esz);  // (Tp rows: operands of the weight-gradient products, whose K is padded)
   w.u = c.take_bytes((size_t)T * F * esz);
-  w.f = c.take_bytes((size_t)T * F * esz);
-  w.go = c.take_bytes((size_t)T * d * esz);
-  w.df = c.take_bytes((size_t)T * F * esz);
+  w.f = c.take_bytes(Tp * F * esz);
+  w.go = c.take_bytes(Tp * d * esz);
+  w.df = c.take_bytes(Tp * F * esz);
   w.goT = c.take_bytes(d * Tp * esz);
   w.fT = c.take_bytes(F * Tp * esz);
   w.mT = c.take_bytes(d * Tp * esz);
@@ -1020,8 +1020,6 @@ int rlhf_mlp_backward(rlhf_handle* h, int32_t layer, const float* x_in, const fl
   // ---- FC2: db2 = sum_t G, dW2 = G^T f, df = G W2
   LAUNCH("colsum", launch_colsum(0, d_out, T, d, ws.part, ws.splits, d_b_fc2, s));
   LAUNCH("convert", launch_convert_from_f32(dt, d_out, ws.go, (size_t)T * d, s));
-  LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.go, (size_t)d, ws.goT, (size_t)Tp, T, d, Tp, s));
-  LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.f, (size_t)F, ws.fT, (size_t)Tp, T, F, Tp, s));
   auto dw_gemm = [&](const void* A, const void* W, void* out, int M, int N) {  // K = the rows: sliced
     GemmArgs g = gemm(A, W, nullptr, out, M, N, Tp, EPI_F32);
     g.long_k = true;
@@ -1029,15 +1027,42 @@ int rlhf_mlp_backward(rlhf_handle* h, int32_t layer, const float* x_in, const fl
     g.splitk_ws_bytes = ws.slabs_bytes;
     return g;
   };
-  LAUNCH("gemm_mlp_dw", launch_gemm(dt, dw_gemm(ws.goT, ws.fT, d_w_fc2, d, F), s));
+  // Weight gradients straight from the row-major activations (K-major operands) where the kernel takes the shape;
+  // the rows T .. Tp-1 of those operands are zeroed first.  Otherwise from transposed, zero-padded copies.
+  auto dw_kmajor = [&](const void* A, const void* W, void* out, int M, int N) {
+    GemmArgs g = dw_gemm(A, W, out, M, N);
+    g.k_major = true;
+    return g;
+  };
+  const bool kmaj = gemm_takes_k_major(dt, dw_kmajor(ws.go, ws.f, d_w_fc2, d, F)) &&
+                    gemm_takes_k_major(dt, dw_kmajor(ws.df, ws.m, d_w_fc1, F, d));
+  auto zero_tail = [&](void* buf, int width) {
+    return Tp > T ? launch_fill_zero((char*)buf + (size_t)T * width * h->esz, (size_t)(Tp - T) * width * h->esz, s)
+                  : hipSuccess;
+  };
+  if (kmaj) {
+    LAUNCH("mlp_bwd_zero", zero_tail(ws.go, d));
+    LAUNCH("mlp_bwd_zero", zero_tail(ws.f, F));
+    LAUNCH("gemm_mlp_dw", launch_gemm(dt, dw_kmajor(ws.go, ws.f, d_w_fc2, d, F), s));
+  } else {
+    LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.go, (size_t)d, ws.goT, (size_t)Tp, T, d, Tp, s));
+    LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.f, (size_t)F, ws.fT, (size_t)Tp, T, F, Tp, s));
+    LAUNCH("gemm_mlp_dw", launch_gemm(dt, dw_gemm(ws.goT, ws.fT, d_w_fc2, d, F), s));
+  }
   LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, h->w_fc2[l], ld_w2, ws.w2T, (size_t)d, d, F, d, s));
   LAUNCH("gemm_mlp_dx", launch_gemm(dt, gemm(ws.go, ws.w2T, nullptr, ws.df, T, F, d, EPI_BIAS), s));
   // ---- GELU, then FC1: du = df * gelu'(u) (in place), db1 = sum_t du, dW1 = du^T m, dm = du W1
   LAUNCH("gelu", launch_gelu_backward(dt, ws.u, ws.df, (size_t)T * F, s));
   LAUNCH("colsum", launch_colsum(dt, ws.df, T, F, ws.part, ws.splits, d_b_fc1, s));
-  LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.df, (size_t)F, ws.fT, (size_t)Tp, T, F, Tp, s));
-  LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.m, (size_t)d, ws.mT, (size_t)Tp, T, d, Tp, s));
-  LAUNCH("gemm_mlp_dw", launch_gemm(dt, dw_gemm(ws.fT, ws.mT, d_w_fc1, F, d), s));
+  if (kmaj) {
+    LAUNCH("mlp_bwd_zero", zero_tail(ws.df, F));
+    LAUNCH("mlp_bwd_zero", zero_tail(ws.m, d));
+    LAUNCH("gemm_mlp_dw", launch_gemm(dt, dw_kmajor(ws.df, ws.m, d_w_fc1, F, d), s));
+  } else {
+    LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.df, (size_t)F, ws.fT, (size_t)Tp, T, F, Tp, s));
+    LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.m, (size_t)d, ws.mT, (size_t)Tp, T, d, Tp, s));
+    LAUNCH("gemm_mlp_dw", launch_gemm(dt, dw_gemm(ws.fT, ws.mT, d_w_fc1, F, d), s));
+  }
   LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, h->w_fc1[l], (size_t)d, ws.w1T, (size_t)F, F, d, F, s));
   LAUNCH("gemm_mlp_dx", launch_gemm(dt, gemm(ws.df, ws.w1T, nullptr, ws.dm, T, d, F, EPI_F32), s));
   // ---- LN2: the branch's term of dL/dx, and the gradients of its gain and bias
@@ -1066,12 +1091,12 @@ AttnBwdWs carve_attn_bwd(Carver& c, const rlhf_model_config& cfg, int T, size_t 
   w.T_pad = (T + 127) & ~127;
   w.splits = std::max(1, std::min(256, (T + 255) / 256));
   const size_t Tp = (size_t)w.T_pad;
-  w.a = c.take_bytes((size_t)T * d * esz);
+  w.a = c.take_bytes(Tp * d * esz);  // (Tp rows: operands of the weight-gradient products, whose K is padded)
   w.qkv = c.take_bytes((size_t)T * 3 * d * esz);
-  w.go = c.take_bytes((size_t)T * d * esz);
+  w.go = c.take_bytes(Tp * d * esz);
   w.dO = c.take_bytes((size_t)T * d * esz);
-  w.att = c.take_bytes((size_t)T * d * esz);
-  w.dqkv = c.take_bytes((size_t)T * 3 * d * esz);
+  w.att = c.take_bytes(Tp * d * esz);
+  w.dqkv = c.take_bytes(Tp * 3 * d * esz);
   w.goT = c.take_bytes(d * Tp * esz);
   w.attT = c.take_bytes(d * Tp * esz);
   w.dqkvT = c.take_bytes(3 * d * Tp * esz);
@@ -1154,8 +1179,6 @@ int rlhf_attention_branch_backward(rlhf_handle* h, int32_t layer, const float* x
                                    max_len, ws.lse, ws.delta, dqkv, dqkv + (size_t)d * esz, dqkv + (size_t)2 * d * esz, s,
                                    (size_t)3 * d, (size_t)d, (size_t)3 * d, ws.att, (size_t)d));
   // ---- dWo = G^T o
-  LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.go, (size_t)d, ws.goT, (size_t)Tp, T, d, Tp, s));
-  LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.att, (size_t)d, ws.attT, (size_t)Tp, T, d, Tp, s));
   auto dw_gemm = [&](const void* A, const void* W, void* out, int M, int N) {  // K = the rows: sliced
     GemmArgs g = gemm(A, W, nullptr, out, M, N, Tp, EPI_F32);
     g.long_k = true;
@@ -1163,14 +1186,41 @@ int rlhf_attention_branch_backward(rlhf_handle* h, int32_t layer, const float* x
     g.splitk_ws_bytes = ws.slabs_bytes;
     return g;
   };
-  LAUNCH("gemm_attn_dw", launch_gemm(dt, dw_gemm(ws.goT, ws.attT, d_w_o, d, d), s));
+  // Weight gradients straight from the row-major activations (K-major operands) where the kernel takes the shape;
+  // the rows T .. Tp-1 of those operands are zeroed first.  Otherwise from transposed, zero-padded copies.
+  auto dw_kmajor = [&](const void* A, const void* W, void* out, int M, int N) {
+    GemmArgs g = dw_gemm(A, W, out, M, N);
+    g.k_major = true;
+    return g;
+  };
+  const bool kmaj = gemm_takes_k_major(dt, dw_kmajor(ws.go, ws.att, d_w_o, d, d)) &&
+                    gemm_takes_k_major(dt, dw_kmajor(ws.dqkv, ws.a, d_w_qkv, 3 * d, d));
+  auto zero_tail = [&](void* buf, int width) {
+    return Tp > T ? launch_fill_zero((char*)buf + (size_t)T * width * esz, (size_t)(Tp - T) * width * esz, s)
+                  : hipSuccess;
+  };
+  if (kmaj) {
+    LAUNCH("attn_bwd_zero", zero_tail(ws.go, d));
+    LAUNCH("attn_bwd_zero", zero_tail(ws.att, d));
+    LAUNCH("gemm_attn_dw", launch_gemm(dt, dw_kmajor(ws.go, ws.att, d_w_o, d, d), s));
+  } else {
+    LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.go, (size_t)d, ws.goT, (size_t)Tp, T, d, Tp, s));
+    LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.att, (size_t)d, ws.attT, (size_t)Tp, T, d, Tp, s));
+    LAUNCH("gemm_attn_dw", launch_gemm(dt, dw_gemm(ws.goT, ws.attT, d_w_o, d, d), s));
+  }
   // ---- back through the rotary turn, then the QKV product: dbqkv, dWqkv, da
   LAUNCH("rope_inplace", launch_rope_inplace(dt, ws.dqkv, (size_t)3 * d, cu_seqlens, B, T, H, hd, c.rotary_dims,
                                              h->rope_cos, h->rope_sin, 1, s));
   LAUNCH("colsum", launch_colsum(dt, ws.dqkv, T, 3 * d, ws.part, ws.splits, reordered ? ws.dbq : d_b_qkv, s));
-  LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.dqkv, (size_t)3 * d, ws.dqkvT, (size_t)Tp, T, 3 * d, Tp, s));
-  LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.a, (size_t)d, ws.aT, (size_t)Tp, T, d, Tp, s));
-  LAUNCH("gemm_attn_dw", launch_gemm(dt, dw_gemm(ws.dqkvT, ws.aT, reordered ? ws.dwq : d_w_qkv, 3 * d, d), s));
+  if (kmaj) {
+    LAUNCH("attn_bwd_zero", zero_tail(ws.dqkv, 3 * d));
+    LAUNCH("attn_bwd_zero", zero_tail(ws.a, d));
+    LAUNCH("gemm_attn_dw", launch_gemm(dt, dw_kmajor(ws.dqkv, ws.a, reordered ? ws.dwq : d_w_qkv, 3 * d, d), s));
+  } else {
+    LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.dqkv, (size_t)3 * d, ws.dqkvT, (size_t)Tp, T, 3 * d, Tp, s));
+    LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.a, (size_t)d, ws.aT, (size_t)Tp, T, d, Tp, s));
+    LAUNCH("gemm_attn_dw", launch_gemm(dt, dw_gemm(ws.dqkvT, ws.aT, reordered ? ws.dwq : d_w_qkv, 3 * d, d), s));
+  }
   if (reordered) {
     LAUNCH("qkv_rows", launch_qkv_rows_to_caller_order(ws.dwq, d_w_qkv, d, hd, c.rotary_dims, d, s));
     LAUNCH("qkv_rows", launch_qkv_rows_to_caller_order(ws.dbq, d_b_qkv, d, hd, c.rotary_dims, 1, s));

@@ -143,6 +143,7 @@ struct QkvArgs {
 struct GemmArgs;
 bool gemm_takes_qkv(int dtype, const GemmArgs& a, int H, int hd, int r);
 bool gemm_takes_lse(int dtype, const GemmArgs& a);
+bool gemm_takes_k_major(int dtype, const GemmArgs& a);
 int gemm_lse_parts(int n_cols);
 
 struct GemmArgs {
@@ -163,6 +164,9 @@ struct GemmArgs {
   int lda = 0, ldw = 0;        // row strides of A and W in elements (0: K); fp16 kernels only
   const void* bias2 = nullptr; // second bias added like the first; large-M fp16 kernel only
   int max_split = 0;           // few-rows kernel: cap on the K split (0: as many as cover the chip)
+  bool k_major = false;        // operands given K-major: A is [K, M_max], W is [K, N], row-major, lda / ldw their row
+                               // strides (0: M_max / N); out = A^T W, fp32 (EPI_F32), large-M fp16 kernel only: ask
+                               // gemm_takes_k_major first
   bool long_k = false;         // large-M kernel, fp32 output, no bias: K may be cut into slices whose fp32 slabs (in
                                // splitk_ws) are then summed in slice order -- for products with few output tiles and
                                // a very long K (weight gradients)

@@ -312,7 +312,14 @@ constexpr int kDmaWaves = 8;                // waves per block of the large-M ke
 constexpr int DK = 64;                      // K depth of one stage: 128 bytes per tile row
 constexpr int DSTAGE = (256 + 256) * DK;    // halfs per stage (64 KB)
 
-template <int EPI, int WAVES>
+// KMAJ: both operands are given K-major -- A as [K, M] and W as [K, N], row-major, lda / ldw their row strides
+// (the weight-gradient products of a backward pass: out = A^T W over the batch's rows, no transposed copies).  A stage
+// then holds 64 k-rows of 512 bytes per operand, and a matrix-instruction operand slice (8 consecutive k of one
+// column) comes from two transposing LDS reads (ds_read_b64_tr_b16: within a group of 16 lanes, lane i receives the
+// (i mod 4)-th element of the 8-byte items addressed by lanes i/4, i/4+4, i/4+8, i/4+12; with lane r pointing at row
+// k + r/4, columns 4(r mod 4).. of the tile, lane i gets column i of rows k .. k+3).  16-byte chunk c of k-row k sits at
+// chunk c ^ 2(k mod 4) of the row, so that the four rows one group reads fall into four different 32-byte bank groups.
+template <int EPI, int WAVES, bool KMAJ = false>
 __global__ void __launch_bounds__(64 * WAVES, 1)
     gemm_f16_dma_kernel(const half_t* __restrict__ A, const half_t* __restrict__ W, const bf16_t* __restrict__ bias,
                         void* __restrict__ out, int M_max, const int* __restrict__ M_dev, int M_sub, int N, int K,
@@ -345,8 +352,8 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
   // [z * k_slice, min(K, (z + 1) * k_slice)) and writes its fp32 result to slab z of `out`
   if (k_slice > 0) {
     const int kb = blockIdx.y * k_slice;
-    A += kb;
-    W += kb;
+    A += KMAJ ? (size_t)kb * lda : (size_t)kb;
+    W += KMAJ ? (size_t)kb * ldw : (size_t)kb;
     K = min(k_slice, K - kb);
     out = (float*)out + (size_t)blockIdx.y * slab;
   }
@@ -358,15 +365,26 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
   //      rows 8j .. 8j+7 (rows < 256: A, else W); lane l lands at row 8j + l/8, physical chunk l%8,
   //      and therefore fetches logical chunk (l%8) ^ ((row>>1)&7)
   uint32_t goff[NLD];
+  const int gld = wave < WAVES / 2 ? lda : ldw;  // row stride of the operand this wave loads
 #pragma unroll
   for (int i = 0; i < NLD; ++i) {
-    const int row = 8 * (NLD * wave + i) + (lane >> 3);
-    const int c = (lane & 7) ^ ((row >> 1) & 7);
-    goff[i] = (uint32_t)((row < TM ? min(m0 + row, M - 1) * lda : min(n0 + row - TM, N - 1) * ldw) + c * 8);
+    if (KMAJ) {
+      // wave-load j covers k-rows 2j', 2j'+1 (j' = j mod 32) of its operand; lane l lands at k-row 2j' + l/32,
+      // physical chunk l%32, and fetches logical chunk (l%32) ^ 2(k-row mod 4); columns past the operand's width
+      // re-read its last chunk (those output columns are never stored)
+      const int krow = 2 * ((NLD * wave + i) & 31) + (lane >> 5);
+      const int c = (lane & 31) ^ (2 * (krow & 3));
+      const int colb = wave < WAVES / 2 ? min(m0 + c * 8, M - 8) : min(n0 + c * 8, N - 8);
+      goff[i] = (uint32_t)(krow * gld + colb);
+    } else {
+      const int row = 8 * (NLD * wave + i) + (lane >> 3);
+      const int c = (lane & 7) ^ ((row >> 1) & 7);
+      goff[i] = (uint32_t)((row < TM ? min(m0 + row, M - 1) * lda : min(n0 + row - TM, N - 1) * ldw) + c * 8);
+    }
   }
   const half_t* gbase = wave < WAVES / 2 ? A : W;  // the first half of the waves loads A rows, the second W rows
   auto load_one = [&](uint16_t* stage, int k0, int i) {
-    __builtin_amdgcn_global_load_lds(RLHF_GLOBAL_PTR(gbase + goff[i] + k0),
+    __builtin_amdgcn_global_load_lds(RLHF_GLOBAL_PTR(gbase + goff[i] + (KMAJ ? (size_t)k0 * gld : (size_t)k0)),
                                      RLHF_LDS_PTR(stage + (8 * (NLD * wave + i)) * DK), 16, 0, 0);
   };
 
@@ -374,8 +392,20 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
   const int key = (l32 >> 1) & 7;
   const int a_off = (wm + l32) * DK, w_off = (TM + wn + l32) * DK;
   // sub-step s (16 of the 64 k of a stage) reads logical chunks 2s and 2s+1: one per half-wave
-  const int ch0 = ((0 + hf) ^ key) << 3, ch1 = ((2 + hf) ^ key) << 3, ch2 = ((4 + hf) ^ key) << 3,
-            ch3 = ((6 + hf) ^ key) << 3;
+  // KMAJ: sub-step s reads k-rows 16s + 8hf .. +7 (256 halfs per row); the column part of a lane's address, with
+  // the row swizzle, is fixed per fragment
+  const int ch0 = KMAJ ? (0 + 8 * hf) * 256 : ((0 + hf) ^ key) << 3, ch1 = KMAJ ? (16 + 8 * hf) * 256 : ((2 + hf) ^ key) << 3,
+            ch2 = KMAJ ? (32 + 8 * hf) * 256 : ((4 + hf) ^ key) << 3, ch3 = KMAJ ? (48 + 8 * hf) * 256 : ((6 + hf) ^ key) << 3;
+  int koff[MT + NT];
+  if (KMAJ) {
+    const int r = lane & 15, gsel = (lane >> 4) & 1;
+#pragma unroll
+    for (int q = 0; q < MT + NT; ++q) {
+      const int colb = (q < MT ? wm + 32 * q : wn + 32 * (q - MT)) + 16 * gsel;  // first column of the group's 16
+      const int chunk = ((colb >> 3) + ((r & 3) >> 1)) ^ (2 * ((r >> 2) & 3));
+      koff[q] = (q < MT ? 0 : 64 * 256) + (r >> 2) * 256 + chunk * 8 + (r & 1) * 4;
+    }
+  }
 
   f32x16_t acc[NT][MT];
 #pragma unroll
@@ -390,8 +420,21 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
   // m = lane%32), i.e. 4 consecutive output columns per lane
   f16x8_t fa0[MT], fw0[NT], fa1[MT], fw1[NT];
   auto frag_one = [&](const uint16_t* ls, int ch, int q, f16x8_t* fa, f16x8_t* fw) {
-    if (q < MT) fa[q] = *(const f16x8_t*)(ls + a_off + q * 32 * DK + ch);
-    else fw[q - MT] = *(const f16x8_t*)(ls + w_off + (q - MT) * 32 * DK + ch);
+    if (KMAJ) {
+      typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+      typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+      typedef __attribute__((address_space(3))) s16x4_t* lds4_t;
+      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(ls + koff[q] + ch));
+      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(ls + koff[q] + ch + 4 * 256));
+      const s16x8_t b = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      const f16x8_t v = __builtin_bit_cast(f16x8_t, b);
+      if (q < MT) fa[q] = v;
+      else fw[q - MT] = v;
+    } else if (q < MT) {
+      fa[q] = *(const f16x8_t*)(ls + a_off + q * 32 * DK + ch);
+    } else {
+      fw[q - MT] = *(const f16x8_t*)(ls + w_off + (q - MT) * 32 * DK + ch);
+    }
   };
   // NMF matrix instructions on (FA, FW); after the n-th, fragment read n (n < MT + NT) of the next
   // sub-step from (LS, CH) into (GA, GW) and, if LOAD, tile load n of the stage at K offset KL
@@ -693,11 +736,23 @@ static void launch_f16_dma(const GemmArgs& a, hipStream_t s, int k_slices = 1, i
   // Eight waves measure 8-10 % faster than four on the layer shapes.
   constexpr int WV = kDmaWaves;
   const bool split = k_slices > 1;
-  hipLaunchKernelGGL((gemm_f16_dma_kernel<EPI, WV>), dim3(per_xcd * 8, split ? k_slices : 1), dim3(64 * WV), 0, s,
-                     (const half_t*)a.A, (const half_t*)a.W, (const bf16_t*)a.bias, split ? a.splitk_ws : a.out, a.M_max,
-                     a.M_dev, a.M_sub, a.N, a.K, split ? a.N : a.ldo, nb_m, nb_n, a.lda ? a.lda : a.K,
-                     a.ldw ? a.ldw : a.K, (const bf16_t*)a.bias2, a.lse ? *a.lse : LseArgs{},
-                     a.qkv ? *a.qkv : QkvArgs{}, split ? k_slice : 0, split ? (size_t)a.M_max * a.N : (size_t)0);
+  const dim3 grid(per_xcd * 8, split ? k_slices : 1), block(64 * WV);
+  void* out = split ? a.splitk_ws : a.out;
+  const int ldo = split ? a.N : a.ldo, ks = split ? k_slice : 0;
+  const size_t slab = split ? (size_t)a.M_max * a.N : (size_t)0;
+  if constexpr (EPI == EPI_F32) {
+    if (a.k_major) {
+      hipLaunchKernelGGL((gemm_f16_dma_kernel<EPI_F32, WV, true>), grid, block, 0, s, (const half_t*)a.A,
+                         (const half_t*)a.W, (const bf16_t*)nullptr, out, a.M_max, (const int*)nullptr, 0, a.N, a.K, ldo,
+                         nb_m, nb_n, a.lda ? a.lda : a.M_max, a.ldw ? a.ldw : a.N, (const bf16_t*)nullptr, LseArgs{},
+                         QkvArgs{}, ks, slab);
+      return;
+    }
+  }
+  hipLaunchKernelGGL((gemm_f16_dma_kernel<EPI, WV>), grid, block, 0, s, (const half_t*)a.A, (const half_t*)a.W,
+                     (const bf16_t*)a.bias, out, a.M_max, a.M_dev, a.M_sub, a.N, a.K, ldo, nb_m, nb_n,
+                     a.lda ? a.lda : a.K, a.ldw ? a.ldw : a.K, (const bf16_t*)a.bias2, a.lse ? *a.lse : LseArgs{},
+                     a.qkv ? *a.qkv : QkvArgs{}, ks, slab);
 }
 
 #ifndef RLHF_GEMM_DMA
@@ -763,6 +818,12 @@ int gemm_splitk_factor(int dtype, const GemmArgs& a) {
 
 // Shapes the large-M kernel takes: K a multiple of two stages, 16-byte aligned rows, 32-bit offsets.
 static bool takes_dma(const GemmArgs& a) {
+  if (a.k_major) {  // [K, M] and [K, N] operands, fp32 output: whole 16-byte chunks per operand row, 32-bit offsets
+    const size_t lda = a.lda ? a.lda : a.M_max, ldw = a.ldw ? a.ldw : a.N;
+    return RLHF_GEMM_DMA && a.epilogue == EPI_F32 && !a.M_dev && !a.bias && !a.bias2 && a.M_max > 512 && a.N >= 8 &&
+           (a.M_max % 8) == 0 && (a.N % 8) == 0 && (a.K % (2 * DK)) == 0 && (a.ldo % 8) == 0 && (lda % 8) == 0 &&
+           (ldw % 8) == 0 && (size_t)a.K * std::max(lda, ldw) < (1ull << 32);
+  }
   const size_t lda = a.lda ? a.lda : a.K, ldw = a.ldw ? a.ldw : a.K;
   return RLHF_GEMM_DMA && a.M_max > 512 && (a.K % (2 * DK)) == 0 && (a.N % 8) == 0 && (a.ldo % 8) == 0 &&
          (lda % 8) == 0 && (ldw % 8) == 0 && std::max((size_t)a.M_max * lda, (size_t)a.N * ldw) < (1ull << 32);
@@ -788,6 +849,7 @@ static int dma_k_slices(const GemmArgs& a, int* k_slice) {
   return best;
 }
 bool gemm_takes_bias2(int dtype, const GemmArgs& a) { return dtype == 1 && takes_dma(a); }
+bool gemm_takes_k_major(int dtype, const GemmArgs& a) { return dtype == 1 && a.k_major && takes_dma(a); }
 bool gemm_takes_lse(int dtype, const GemmArgs& a) { return dtype == 1 && takes_dma(a); }
 // EPI_QKV: 16-byte chunks must not straddle heads, a lane's 4-column group must be whole pairs, and the
 // cos / sin pairs are read as aligned 8-byte words.
@@ -854,6 +916,7 @@ hipError_t launch_gemm(int dtype, const GemmArgs& a, hipStream_t s) {
   if (dtype == 1 && (a.K % 8) != 0) return hipErrorInvalidValue;
   if (dtype != 1 && (a.lda || a.ldw || a.bias2)) return hipErrorInvalidValue;
   if (a.bias2 && !gemm_takes_bias2(dtype, a)) return hipErrorInvalidValue;
+  if (a.k_major && !gemm_takes_k_major(dtype, a)) return hipErrorInvalidValue;
   switch (a.epilogue) {
     case EPI_BIAS: launch_epi<EPI_BIAS>(dtype, a, s); break;
     case EPI_BIAS_GELU: launch_epi<EPI_BIAS_GELU>(dtype, a, s); break;

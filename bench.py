@@ -366,7 +366,9 @@ def main():
         ev[1].record()
         torch.cuda.synchronize()
         upd_ms = ev[0].elapsed_time(ev[1])
+        free_b, total_b = torch.cuda.mem_get_info()
         update = {"iteration_ms": upd_ms, "rows": int(mask_u.sum().item()), "loss": float(st_u[0, 0]),
+                  "hbm_in_use_gb": (total_b - free_b) / 1e9,   # whole process: rollout workspace, weights, optimizer state, kept activations
                   "tflops": wc["update_flops"] / (upd_ms * 1e-3) / 1e12,
                   "note": "one of the K = 4 iterations of an update; 3 x the forward pass's flops (every row through "
                           "the layers, the LM head on the response rows; twice that for the gradients) over its time, "

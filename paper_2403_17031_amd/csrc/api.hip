@@ -293,6 +293,10 @@ struct PassArgs {
   const int* n_sel = nullptr;
   int sel_rows = 0;
   const Acts* selz = nullptr;
+  // Training forward that also keeps every layer's QKV product: layer l's rotated q rows go to q_keep + l *
+  // q_keep_stride bytes instead of the pass's own q buffer (its K / V are kept through kv_per_layer).
+  char* q_keep = nullptr;
+  size_t q_keep_stride = 0;
 };
 
 int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) {
@@ -371,6 +375,7 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
                             hipMemcpyDeviceToDevice, s));
     char* kc = p.kv + (p.kv_per_layer ? (size_t)l * 2 * plane : 0);
     char* vc = kc + plane;
+    void* const q_l = p.q_keep ? (void*)(p.q_keep + (size_t)l * p.q_keep_stride) : A.q;  // this layer's rotated q rows
     if (pending) {
       PendingResidual pr;
       pr.part_a = (const float*)A.splitk; pr.ks_a = ks_o; pr.bias_a = h->b_o[l - 1];
@@ -390,14 +395,14 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
       LAUNCH("gemm_decode_qkv", launch_gemm(dt, g, s));
       LAUNCH("rope_kv_decode", launch_rope_kv_splitk((const float*)A.splitk, ks_qkv, (size_t)p.rows_max * 3 * d, h->b_qkv[l],
                                                      p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff, p.len,
-                                                     c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q,
+                                                     c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, q_l,
                                                      kc, vc, (long)p.kv_extra, s));
     } else if (p.mode == 0 && gemm_takes_qkv(dt, g, c.n_heads, c.head_dim, c.rotary_dims)) {
       // prefill / scoring: the rotary turn and the K/V store are the epilogue of the QKV product
       QkvArgs qa;
       qa.pos = p.pos; qa.rowid = p.rowid; qa.kvoff = p.kvoff; qa.len = p.len;
       qa.cos_t = h->rope_cos; qa.sin_t = h->rope_sin;
-      qa.q = A.q; qa.kc = kc; qa.vc = vc; qa.kv_extra = (long)p.kv_extra;
+      qa.q = q_l; qa.kc = kc; qa.vc = vc; qa.kv_extra = (long)p.kv_extra;
       qa.pos_add = p.pos_add; qa.H = c.n_heads; qa.hd = c.head_dim; qa.r = c.rotary_dims;
       g.epilogue = EPI_QKV;
       g.qkv = &qa;
@@ -405,13 +410,13 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
     } else {
       LAUNCH(p.mode ? "gemm_decode_qkv" : "gemm", launch_gemm(dt, g, s));
       LAUNCH(p.mode ? "rope_kv_decode" : "rope_kv", launch_rope_kv(dt, A.qkv, p.rows_max, p.rows_dev, p.pos, p.pos_add, p.rowid, p.kvoff,
-                                       p.len, c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, A.q, kc, vc,
+                                       p.len, c.n_heads, c.head_dim, c.rotary_dims, h->rope_cos, h->rope_sin, q_l, kc, vc,
                                        (long)p.kv_extra, s));
     }
     if (p.mode == 0 && p.last && l + 1 == c.n_layers) {
       const Acts& Z = *p.last;
       const size_t rb = (size_t)d * h->esz;
-      LAUNCH("gather_last", launch_gather_rows(A.q, p.cu + 1, -1, p.B, rb, Z.q, s));
+      LAUNCH("gather_last", launch_gather_rows(q_l, p.cu + 1, -1, p.B, rb, Z.q, s));
       LAUNCH("gather_last", launch_gather_rows(A.m, p.cu + 1, -1, p.B, rb, Z.m, s));
       LAUNCH("gather_last", launch_gather_rows(A.x, p.cu + 1, -1, p.B, (size_t)d * sizeof(float), Z.x, s));
       // the last query of a sequence attends over all of its rows: the single-row kernel with ctx = len
@@ -439,7 +444,7 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
     if (p.mode == 0 && p.sel && l + 1 == c.n_layers) {
       const Acts& Z = *p.selz;
       const size_t esz = h->esz, ld_att = (size_t)(cat ? d + c.d_ff : d);
-      LAUNCH("attn_prefill", launch_attn_prefill(dt, A.q, kc, vc, (long)p.kv_extra, p.B, p.Lmax, p.len, p.cu, p.kvoff,
+      LAUNCH("attn_prefill", launch_attn_prefill(dt, q_l, kc, vc, (long)p.kv_extra, p.B, p.Lmax, p.len, p.cu, p.kvoff,
                                                  c.n_heads, c.head_dim, A.att, (int)ld_att, s));
       LAUNCH("gather_sel", launch_gather_rows_strided(A.att, ld_att * esz, p.sel, p.sel_rows, (size_t)d * esz, Z.att,
                                                       ld_att * esz, s));
@@ -506,10 +511,10 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
       HIP_OK(hipEventRecord(join, h->side));
     }
     if (p.mode == 0)
-      LAUNCH("attn_prefill", launch_attn_prefill(dt, A.q, kc, vc, (long)p.kv_extra, p.B, p.Lmax, p.len, p.cu, p.kvoff,
+      LAUNCH("attn_prefill", launch_attn_prefill(dt, q_l, kc, vc, (long)p.kv_extra, p.B, p.Lmax, p.len, p.cu, p.kvoff,
                                                  c.n_heads, c.head_dim, A.att, cat ? d + c.d_ff : d, s));
     else
-      LAUNCH("attn_decode", launch_attn_decode(dt, A.q, kc, vc, (long)p.kv_extra, p.B, p.len, p.ctx_add, p.ctx_max,
+      LAUNCH("attn_decode", launch_attn_decode(dt, q_l, kc, vc, (long)p.kv_extra, p.B, p.len, p.ctx_add, p.ctx_max,
                                                p.kvoff, c.n_heads, c.head_dim, A.att, s));
     // From here on the order of the additions into x is the serial one: x = (x + attn) + mlp.
     if (cat) {
@@ -1126,10 +1131,28 @@ int rlhf_attention_branch_backward_workspace_bytes(const rlhf_handle* h, int32_t
   return RLHF_OK;
 }
 
+// kept_q / kept_k / kept_v (optional, all or none): what the forward pass left of this layer's QKV product -- the
+// rotated q rows [T, d] and the layer's K / V cache -- so that the product and the rotary turn are not recomputed.
+static int attention_branch_backward_impl(rlhf_handle* h, int32_t layer, const float* x_in, const float* d_out,
+                                          const int32_t* cu_seqlens, int32_t B, int32_t T, int32_t max_len, float* d_x,
+                                          float* d_ln1_g, float* d_ln1_b, float* d_w_qkv, float* d_b_qkv, float* d_w_o,
+                                          float* d_b_o, void* workspace, size_t workspace_bytes, void* stream,
+                                          const void* kept_q, const void* kept_k, const void* kept_v);
+
 int rlhf_attention_branch_backward(rlhf_handle* h, int32_t layer, const float* x_in, const float* d_out,
                                    const int32_t* cu_seqlens, int32_t B, int32_t T, int32_t max_len, float* d_x,
                                    float* d_ln1_g, float* d_ln1_b, float* d_w_qkv, float* d_b_qkv, float* d_w_o,
                                    float* d_b_o, void* workspace, size_t workspace_bytes, void* stream) {
+  return attention_branch_backward_impl(h, layer, x_in, d_out, cu_seqlens, B, T, max_len, d_x, d_ln1_g, d_ln1_b, d_w_qkv,
+                                        d_b_qkv, d_w_o, d_b_o, workspace, workspace_bytes, stream, nullptr, nullptr,
+                                        nullptr);
+}
+
+static int attention_branch_backward_impl(rlhf_handle* h, int32_t layer, const float* x_in, const float* d_out,
+                                          const int32_t* cu_seqlens, int32_t B, int32_t T, int32_t max_len, float* d_x,
+                                          float* d_ln1_g, float* d_ln1_b, float* d_w_qkv, float* d_b_qkv, float* d_w_o,
+                                          float* d_b_o, void* workspace, size_t workspace_bytes, void* stream,
+                                          const void* kept_q, const void* kept_k, const void* kept_v) {
   if (!h) return fail(RLHF_EINVAL, "null handle");
   const rlhf_model_config& c = h->cfg;
   if (layer < 0 || layer >= c.n_layers) return fail(RLHF_EINVAL, "layer index out of range");
@@ -1163,9 +1186,13 @@ int rlhf_attention_branch_backward(rlhf_handle* h, int32_t layer, const float* x
   // ---- the branch's forward, recomputed from the layer input: a = LN1(x), qkv = a Wqkv^T + b, rotary turn
   LAUNCH("final_ln", launch_final_ln(dt, x_in, nullptr, 0, T, nullptr, d, c.ln_eps, h->ln1_g[l], h->ln1_b[l], ws.a,
                                      nullptr, 0.f, nullptr, s));
-  LAUNCH("gemm_attn_fwd", launch_gemm(dt, gemm(ws.a, h->w_qkv[l], h->b_qkv[l], ws.qkv, T, 3 * d, d, EPI_BIAS), s));
-  LAUNCH("rope_inplace", launch_rope_inplace(dt, ws.qkv, (size_t)3 * d, cu_seqlens, B, T, H, hd, c.rotary_dims,
-                                             h->rope_cos, h->rope_sin, 0, s));
+  const bool kept = kept_q && kept_k && kept_v;
+  if (kept && !attention_backward_takes_cache(dt, hd)) return fail(RLHF_EUNSUPPORTED, "kept K/V cache: head size");
+  if (!kept) {
+    LAUNCH("gemm_attn_fwd", launch_gemm(dt, gemm(ws.a, h->w_qkv[l], h->b_qkv[l], ws.qkv, T, 3 * d, d, EPI_BIAS), s));
+    LAUNCH("rope_inplace", launch_rope_inplace(dt, ws.qkv, (size_t)3 * d, cu_seqlens, B, T, H, hd, c.rotary_dims,
+                                               h->rope_cos, h->rope_sin, 0, s));
+  }
   // ---- out-projection: dbo = sum_t G, do = G Wo
   LAUNCH("colsum", launch_colsum(0, d_out, T, d, ws.part, ws.splits, d_b_o, s));
   LAUNCH("convert", launch_convert_from_f32(dt, d_out, ws.go, (size_t)T * d, s));
@@ -1174,10 +1201,17 @@ int rlhf_attention_branch_backward(rlhf_handle* h, int32_t layer, const float* x
   // ---- attention core: (dq | dk | dv) into the sections of dqkv, and the forward output o
   char* qkv = (char*)ws.qkv;
   char* dqkv = (char*)ws.dqkv;
-  LAUNCH("attention_backward",
-         launch_attention_backward(dt, qkv, qkv + (size_t)d * esz, qkv + (size_t)2 * d * esz, ws.dO, cu_seqlens, B, T, H, hd,
-                                   max_len, ws.lse, ws.delta, dqkv, dqkv + (size_t)d * esz, dqkv + (size_t)2 * d * esz, s,
-                                   (size_t)3 * d, (size_t)d, (size_t)3 * d, ws.att, (size_t)d));
+  if (kept)
+    LAUNCH("attention_backward",
+           launch_attention_backward(dt, kept_q, kept_k, kept_v, ws.dO, cu_seqlens, B, T, H, hd, max_len, ws.lse, ws.delta,
+                                     dqkv, dqkv + (size_t)d * esz, dqkv + (size_t)2 * d * esz, s, (size_t)d, (size_t)d,
+                                     (size_t)3 * d, ws.att, (size_t)d, true));
+  else
+    LAUNCH("attention_backward",
+           launch_attention_backward(dt, qkv, qkv + (size_t)d * esz, qkv + (size_t)2 * d * esz, ws.dO, cu_seqlens, B, T, H,
+                                     hd, max_len, ws.lse, ws.delta, dqkv, dqkv + (size_t)d * esz,
+                                     dqkv + (size_t)2 * d * esz, s, (size_t)3 * d, (size_t)d, (size_t)3 * d, ws.att,
+                                     (size_t)d));
   // ---- dWo = G^T o
   auto dw_gemm = [&](const void* A, const void* W, void* out, int M, int N) {  // K = the rows: sliced
     GemmArgs g = gemm(A, W, nullptr, out, M, N, Tp, EPI_F32);
@@ -1338,8 +1372,11 @@ int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_
   return RLHF_OK;
 }
 
+// keep_q / keep_kv (training forward, with keep): buffers of [layers][keep_rows][d] and [layers][2][keep_rows * d]
+// elements that receive every layer's rotated q rows and its K / V cache.
 static int score_forward(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, int B, int L, ScoreWs& ws,
-                         hipStream_t s, float* keep = nullptr, size_t keep_rows = 0) {
+                         hipStream_t s, float* keep = nullptr, size_t keep_rows = 0, char* keep_q = nullptr,
+                         char* keep_kv = nullptr) {
   const rlhf_model_config& c = h->cfg;
   const Meta& m = ws.meta;
   LAUNCH("row_spans", launch_row_spans(mask, B, L, 0, m.start, m.len, m.cu, m.kvoff, m.total, s));
@@ -1366,6 +1403,13 @@ static int score_forward(rlhf_handle* h, const int32_t* tokens, const uint8_t* m
   p.keep = keep;
   p.keep_rows = keep_rows ? keep_rows : (size_t)B * L;  // rows copied per layer = row stride of the kept slices
   p.keep_stride = p.keep_rows * c.d_model;
+  if (keep && keep_q && keep_kv) {
+    p.kv = keep_kv;
+    p.kv_slots = p.keep_rows;
+    p.kv_per_layer = true;
+    p.q_keep = keep_q;
+    p.q_keep_stride = p.keep_rows * c.d_model * h->esz;
+  }
   ws.sel_layers = false;
   if (ws.sel_rows) {
     LAUNCH("select_rows", launch_select_rows(ws.first_col, B, m.start, m.len, m.cu, m.tok, ws.sel_rows, ws.sel, ws.tgt,
@@ -1539,7 +1583,8 @@ static int policy_backward_impl(rlhf_handle* h, const float* x_keep, int64_t x_k
                                 const int32_t* cu_seqlens, const int32_t* packed_tokens, int32_t B, int32_t T,
                                 int32_t max_len, const int32_t* targets, const float* d_logprobs, const float* d_values,
                                 float temperature, float grad_scale, const rlhf_grads* g, void* workspace,
-                                size_t workspace_bytes, void* stream, const int* sel, int sel_rows, const int* n_sel);
+                                size_t workspace_bytes, void* stream, const int* sel, int sel_rows, const int* n_sel,
+                                const char* kept_q = nullptr, const char* kept_kv = nullptr);
 
 int rlhf_policy_backward(rlhf_handle* h, const float* x_keep, int64_t x_keep_layer_stride, const int32_t* cu_seqlens,
                          const int32_t* packed_tokens, int32_t B, int32_t T, int32_t max_len, const int32_t* targets,
@@ -1554,7 +1599,9 @@ static int policy_backward_impl(rlhf_handle* h, const float* x_keep, int64_t x_k
                                 const int32_t* cu_seqlens, const int32_t* packed_tokens, int32_t B, int32_t T,
                                 int32_t max_len, const int32_t* targets, const float* d_logprobs, const float* d_values,
                                 float temperature, float grad_scale, const rlhf_grads* g, void* workspace,
-                                size_t workspace_bytes, void* stream, const int* sel, int sel_rows, const int* n_sel) {
+                                size_t workspace_bytes, void* stream, const int* sel, int sel_rows, const int* n_sel,
+                                const char* kept_q, const char* kept_kv) {
+  // kept_q / kept_kv: what score_forward's keep_q / keep_kv received, with keep_rows = x_keep_layer_stride / d_model
   if (!h || !g) return fail(RLHF_EINVAL, "null argument");
   const rlhf_model_config& c = h->cfg;
   if (T <= 0 || B <= 0) return fail(RLHF_EINVAL, "rows and batch must be positive");
@@ -1609,8 +1656,12 @@ static int policy_backward_impl(rlhf_handle* h, const float* x_keep, int64_t x_k
     rc = rlhf_mlp_backward(h, l, xl, dx, T, dx_m, g->ln2_g[l], g->ln2_b[l], g->w_fc1[l], g->b_fc1[l], g->w_fc2[l],
                            g->b_fc2[l], sub, sub_bytes, stream);
     if (rc) return rc;
-    rc = rlhf_attention_branch_backward(h, l, xl, dx, cu_seqlens, B, T, max_len, dx_a, g->ln1_g[l], g->ln1_b[l],
-                                        g->w_qkv[l], g->b_qkv[l], g->w_o[l], g->b_o[l], sub, sub_bytes, stream);
+    const size_t plane = (size_t)x_keep_layer_stride * h->esz;  // bytes of one layer's q rows, K plane or V plane
+    const char* kq = kept_q && kept_kv ? kept_q + (size_t)l * plane : nullptr;
+    const char* kk = kq ? kept_kv + (size_t)l * 2 * plane : nullptr;
+    rc = attention_branch_backward_impl(h, l, xl, dx, cu_seqlens, B, T, max_len, dx_a, g->ln1_g[l], g->ln1_b[l],
+                                        g->w_qkv[l], g->b_qkv[l], g->w_o[l], g->b_o[l], sub, sub_bytes, stream, kq, kk,
+                                        kk ? kk + plane : nullptr);
     if (rc) return rc;
     LAUNCH("add3", launch_add3(dx, dx_a, dx_m, dx_n, n, s));
     std::swap(dx, dx_n);
@@ -1622,6 +1673,8 @@ static int policy_backward_impl(rlhf_handle* h, const float* x_keep, int64_t x_k
 namespace {
 struct UpdateWs {
   ScoreWs score;
+  char *q_keep = nullptr, *kv_keep = nullptr;  // every layer's rotated q rows and K / V cache (where the backward
+                                               // pass's attention kernels read that layout), else null
   float *x_keep, *lp_full, *val_full, *new_lp, *new_v, *d_lp, *d_v, *gl, *gv;
   int32_t* targets;
   void* bwd;
@@ -1632,6 +1685,10 @@ UpdateWs carve_update(Carver& c, const rlhf_handle* h, int Bm, int L, int N, int
   const rlhf_model_config& cfg = h->cfg;
   w.score = carve_score(c, cfg, Bm, L, h->esz, L - N);  // log-probs and values are read from column L - N - 1 on
   w.x_keep = c.take<float>((size_t)(cfg.n_layers + 1) * T_max * cfg.d_model);
+  if (cfg.n_layers > 0 && attention_backward_takes_cache(cfg.dtype, cfg.head_dim)) {
+    w.q_keep = (char*)c.take_bytes((size_t)cfg.n_layers * T_max * cfg.d_model * h->esz);
+    w.kv_keep = (char*)c.take_bytes((size_t)cfg.n_layers * 2 * T_max * cfg.d_model * h->esz);
+  }
   w.lp_full = c.take<float>((size_t)Bm * L);
   w.val_full = c.take<float>((size_t)Bm * L);
   w.new_lp = c.take<float>((size_t)Bm * N);
@@ -1733,7 +1790,7 @@ int rlhf_ppo_update(rlhf_handle* h, const rlhf_ppo_update_config* cfg, const rlh
       const uint8_t* mask_j = mask + r0 * L;
       const int T = minibatch_tokens[j];
       // forward with the current weights, keeping the layer inputs (packed rows: slices of T rows)
-      rc = score_forward(h, tok_j, mask_j, Bm, L, ws.score, s, ws.x_keep, (size_t)T);
+      rc = score_forward(h, tok_j, mask_j, Bm, L, ws.score, s, ws.x_keep, (size_t)T, ws.q_keep, ws.kv_keep);
       if (rc) return rc;
       rc = score_tail(h, Bm, L, cfg->temperature, ws.score, ws.lp_full, ws.val_full, s);
       if (rc) return rc;
@@ -1747,7 +1804,8 @@ int rlhf_ppo_update(rlhf_handle* h, const rlhf_ppo_update_config* cfg, const rlh
                                                ws.gl, ws.gv, s));
       rc = policy_backward_impl(h, ws.x_keep, (int64_t)T * c.d_model, m.cu, m.tok, Bm, T, max_len, ws.targets, ws.gl,
                                 ws.gv, cfg->temperature, cfg->grad_scale, &G, ws.bwd, ws.bwd_bytes, stream,
-                                ws.score.sel_rows ? ws.score.sel : nullptr, ws.score.sel_rows, ws.score.n_sel);
+                                ws.score.sel_rows ? ws.score.sel : nullptr, ws.score.sel_rows, ws.score.n_sel,
+                                ws.q_keep, ws.kv_keep);
       if (rc) return rc;
       // AdamW on every tensor; a bf16 model keeps fp32 masters and gets its storage arrays rewritten
       const double inv_scale = 1.0 / (double)cfg->grad_scale;

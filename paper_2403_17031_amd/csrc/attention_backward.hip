@@ -283,7 +283,9 @@ __global__ void __launch_bounds__(256, 1)
     attn_bwd_kv_mfma(const half_t* __restrict__ q, const half_t* __restrict__ k, const half_t* __restrict__ v,
                      const half_t* __restrict__ g, const int* __restrict__ cu, int Tn, int H, float scale,
                      const float* __restrict__ lse, const float* __restrict__ delta, half_t* __restrict__ dk,
-                     half_t* __restrict__ dv, size_t ldq, size_t ldg, size_t ldo) {
+                     half_t* __restrict__ dv, size_t ldq, size_t ldg, size_t ldo, int kv_cache) {
+  // kv_cache: k and v are the forward pass's K / V cache of the layer (sequence b owns the slots from cu[b] * H on,
+  // head h of it len_b consecutive rows of HD) instead of [T, .] matrices with row stride ldq
   constexpr int NKS = HD / 16, NDT = (HD + 31) / 32, RS = HD + 8, TS = 64 + 8;
   __shared__ __attribute__((aligned(16))) uint16_t Qs[64 * RS];
   __shared__ __attribute__((aligned(16))) uint16_t Gs[64 * RS];
@@ -299,10 +301,14 @@ __global__ void __launch_bounds__(256, 1)
   const int kj = k0 + wave * 32 + l32;  // this lane's key
   const int kjc = min(kj, n - 1);
   f16x8_t kf[NKS], vf[NKS];
+  {
+    const size_t kvb = kv_cache ? ((size_t)s0 * H + (size_t)h * (cu[b + 1] - cu[b]) + kjc) * HD
+                                : (size_t)(s0 + kjc) * ldq + col;
 #pragma unroll
-  for (int ks = 0; ks < NKS; ++ks) {
-    kf[ks] = *(const f16x8_t*)(k + (size_t)(s0 + kjc) * ldq + col + 16 * ks + 8 * half);
-    vf[ks] = *(const f16x8_t*)(v + (size_t)(s0 + kjc) * ldq + col + 16 * ks + 8 * half);
+    for (int ks = 0; ks < NKS; ++ks) {
+      kf[ks] = *(const f16x8_t*)(k + kvb + 16 * ks + 8 * half);
+      vf[ks] = *(const f16x8_t*)(v + kvb + 16 * ks + 8 * half);
+    }
   }
   for (int c = tid; c < (NDT * 32 - HD) * TS; c += 256) {  // rows of the transposed tiles past HD stay zero
     Qt[HD * TS + c] = 0;
@@ -475,7 +481,8 @@ __global__ void __launch_bounds__(256, 1)
     attn_bwd_q_mfma(const half_t* __restrict__ q, const half_t* __restrict__ k, const half_t* __restrict__ v,
                     const half_t* __restrict__ g, const int* __restrict__ cu, int Tn, int H, float scale,
                     float* __restrict__ lse, float* __restrict__ delta, half_t* __restrict__ dq, size_t ldq, size_t ldg,
-                    size_t ldo, half_t* __restrict__ o_out, size_t ldoo) {
+                    size_t ldo, half_t* __restrict__ o_out, size_t ldoo, int kv_cache) {
+  // kv_cache: k and v are the forward pass's K / V cache of the layer (see attn_bwd_kv_mfma); q stays [T, .]
   constexpr int NKS = HD / 16, NDT = (HD + 31) / 32, RS = HD + 8, TS = 64 + 8, CPR = HD / 8;
   __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * RS];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[64 * RS];
@@ -510,13 +517,15 @@ __global__ void __launch_bounds__(256, 1)
   static_assert(ITEMS <= 256, "one item per thread");
   const int item = min(tid, ITEMS - 1), ich = item / 16, ig4 = item - ich * 16;
   f16x8_t kv[4], vv[4];
+  const size_t kvb = kv_cache ? ((size_t)s0 * H + (size_t)h * (cu[b + 1] - cu[b])) * HD : (size_t)s0 * ldq + col;
+  const size_t kvld = kv_cache ? (size_t)HD : ldq;
   auto load_tile = [&](int k0) {
     k0 = min(k0, k_last);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const size_t row = (size_t)(s0 + min(k0 + 4 * ig4 + u, n - 1));
-      kv[u] = *(const f16x8_t*)(k + row * ldq + col + ich * 8);
-      vv[u] = *(const f16x8_t*)(v + row * ldq + col + ich * 8);
+      const size_t off = kvb + (size_t)min(k0 + 4 * ig4 + u, n - 1) * kvld + ich * 8;
+      kv[u] = *(const f16x8_t*)(k + off);
+      vv[u] = *(const f16x8_t*)(v + off);
     }
   };
   auto store_tile = [&](bool second_pass) {
@@ -773,11 +782,14 @@ hipError_t launch_qkv_rows_to_caller_order(const float* in, float* out, int d, i
 
 // dtype 0: float, 1: fp16.  head_dim a multiple of 4 (float) or 8 (fp16); the longest sequence at
 // most max_len rows (longer ones are cut off at max_len: wrong results, but no access out of bounds).
+bool attention_backward_takes_cache(int dtype, int hd) { return dtype == 1 && (hd == 64 || hd == 80 || hd == 128); }
+
 hipError_t launch_attention_backward(int dtype, const void* q, const void* k, const void* v, const void* g,
                                      const int* cu, int B, int Tn, int H, int hd, int max_len, float* lse,
                                      float* delta, void* dq, void* dk, void* dv, hipStream_t s, size_t ld_qkv,
-                                     size_t ld_g, size_t ld_out, void* o, size_t ld_o) {
+                                     size_t ld_g, size_t ld_out, void* o, size_t ld_o, bool kv_cache) {
   const size_t dm = (size_t)H * hd;
+  if (kv_cache && !attention_backward_takes_cache(dtype, hd)) return hipErrorInvalidValue;
   if (!ld_qkv) ld_qkv = dm;
   if (!ld_g) ld_g = dm;
   if (!ld_out) ld_out = dm;
@@ -809,10 +821,10 @@ hipError_t launch_attention_backward(int dtype, const void* q, const void* k, co
 #define RLHF_BWD_MFMA(HD_)                                                                                      \
   hipLaunchKernelGGL(attn_bwd_q_mfma<HD_>, mgrid, dim3(256), 0, s, (const half_t*)q, (const half_t*)k,          \
                      (const half_t*)v, (const half_t*)g, cu, Tn, H, scale, lse, delta, (half_t*)dq, ld_qkv,     \
-                     ld_g, ld_out, (half_t*)o, ld_o);                                                           \
+                     ld_g, ld_out, (half_t*)o, ld_o, kv_cache ? 1 : 0);                                         \
   hipLaunchKernelGGL(attn_bwd_kv_mfma<HD_>, mgrid, dim3(256), 0, s, (const half_t*)q, (const half_t*)k,         \
                      (const half_t*)v, (const half_t*)g, cu, Tn, H, scale, lse, delta, (half_t*)dk, (half_t*)dv, \
-                     ld_qkv, ld_g, ld_out)
+                     ld_qkv, ld_g, ld_out, kv_cache ? 1 : 0)
       if (hd == 64) { RLHF_BWD_MFMA(64); }
       else if (hd == 80) { RLHF_BWD_MFMA(80); }
       else { RLHF_BWD_MFMA(128); }

@@ -352,9 +352,13 @@ hipError_t launch_colsum(int elem, const void* a, int R, int C, float* part, int
 hipError_t launch_attention_backward(int dtype, const void* q, const void* k, const void* v, const void* g,
                                      const int* cu, int B, int Tn, int H, int hd, int max_len, float* lse,
                                      float* delta, void* dq, void* dk, void* dv, hipStream_t s, size_t ld_qkv = 0,
-                                     size_t ld_g = 0, size_t ld_out = 0, void* o = nullptr, size_t ld_o = 0);
+                                     size_t ld_g = 0, size_t ld_out = 0, void* o = nullptr, size_t ld_o = 0,
+                                     bool kv_cache = false);
 // (row strides in elements: ld_qkv of q, k, v; ld_g of g; ld_out of dq, dk, dv; 0 = H*hd.  o: optional forward
-// output O = P V, [T, ld_o].)
+// output O = P V, [T, ld_o].  kv_cache: k and v are a layer's K / V cache as the forward pass of a packed batch
+// leaves it -- sequence b's slab starts at slot cu[b] * H, head h of it holds the sequence's rows consecutively --
+// and ld_qkv is q's stride alone; only where attention_backward_takes_cache says so.)
+bool attention_backward_takes_cache(int dtype, int hd);
 
 // Rotary turn, in place, of the q and k sections of a [T, 3*d] matrix (row stride ld) by each row's position in
 // its sequence; backward != 0 applies the transpose (turn by the negative angle).  dtype 1 uses the reordered

@@ -171,11 +171,13 @@ def test_update_loop_matches_the_oracle_loop(gpu, dtype):
 def test_update_loop_with_the_heads_on_the_response_rows_only(gpu):
     """A batch with enough response rows (40 sequences x 14 columns) for the loop to run the LM head, and the output
     heads' backward pass, on the rows from the last query column on only (the log-probs and values of the other rows
-    are never read): one iteration over the whole batch against the oracle loop, every tensor."""
+    are never read), at a head size for which the loop keeps every layer's rotated q rows and K / V cache from the
+    forward pass instead of recomputing the QKV product in the backward pass: one iteration over the whole batch
+    against the oracle loop, every tensor."""
     from oracle.ppo_update_oracle import ppo_update
     from synth import round_to_bf16
-    cfg = ModelConfig(n_layers=2, d_model=128, n_heads=4, head_dim=32, rotary_dims=8, d_ff=256, vocab=200, dtype="bf16",
-                      pad_id=199, eos_id=1)
+    cfg = ModelConfig(n_layers=2, d_model=128, n_heads=2, head_dim=64, rotary_dims=16, d_ff=256, vocab=200, dtype="bf16",
+                      pad_id=199, eos_id=1)   # head size 64: the loop also keeps q and the K / V cache of every layer
     w = make_weights(cfg, 93, variant="test")
     g = np.random.default_rng(16)
     B, Lq, N = 40, 24, 13

@@ -992,9 +992,27 @@ int rlhf_mlp_backward_workspace_bytes(const rlhf_handle* h, int32_t T, size_t* o
   return RLHF_OK;
 }
 
+// Shared work of a layer's two branches inside a whole backward pass (all optional): go16 = the fp16 copy of d_out,
+// [T padded to 128 rows, d] with zero padding rows, made once for both branches together with the column sums that
+// are d_b_fc2 and d_b_o (then neither is computed here); base = what d_x is added to (d_x = base + the branch's term).
+struct BranchShare {
+  const void* go16 = nullptr;
+  const float* base = nullptr;
+};
+static int mlp_backward_impl(rlhf_handle* h, int32_t layer, const float* x_in, const float* d_out, int32_t T, float* d_x,
+                             float* d_ln2_g, float* d_ln2_b, float* d_w_fc1, float* d_b_fc1, float* d_w_fc2,
+                             float* d_b_fc2, void* workspace, size_t workspace_bytes, void* stream, BranchShare sh);
+
 int rlhf_mlp_backward(rlhf_handle* h, int32_t layer, const float* x_in, const float* d_out, int32_t T, float* d_x,
                       float* d_ln2_g, float* d_ln2_b, float* d_w_fc1, float* d_b_fc1, float* d_w_fc2, float* d_b_fc2,
                       void* workspace, size_t workspace_bytes, void* stream) {
+  return mlp_backward_impl(h, layer, x_in, d_out, T, d_x, d_ln2_g, d_ln2_b, d_w_fc1, d_b_fc1, d_w_fc2, d_b_fc2, workspace,
+                           workspace_bytes, stream, BranchShare{});
+}
+
+static int mlp_backward_impl(rlhf_handle* h, int32_t layer, const float* x_in, const float* d_out, int32_t T, float* d_x,
+                             float* d_ln2_g, float* d_ln2_b, float* d_w_fc1, float* d_b_fc1, float* d_w_fc2,
+                             float* d_b_fc2, void* workspace, size_t workspace_bytes, void* stream, BranchShare sh) {
   if (!h) return fail(RLHF_EINVAL, "null handle");
   const rlhf_model_config& c = h->cfg;
   if (layer < 0 || layer >= c.n_layers) return fail(RLHF_EINVAL, "layer index out of range");
@@ -1023,8 +1041,11 @@ int rlhf_mlp_backward(rlhf_handle* h, int32_t layer, const float* x_in, const fl
   LAUNCH("gemm_mlp_fwd", launch_gemm(dt, gemm(ws.m, h->w_fc1[l], h->b_fc1[l], ws.u, T, F, d, EPI_BIAS), s));
   LAUNCH("gelu", launch_gelu(dt, ws.u, ws.f, (size_t)T * F, s));
   // ---- FC2: db2 = sum_t G, dW2 = G^T f, df = G W2
-  LAUNCH("colsum", launch_colsum(0, d_out, T, d, ws.part, ws.splits, d_b_fc2, s));
-  LAUNCH("convert", launch_convert_from_f32(dt, d_out, ws.go, (size_t)T * d, s));
+  const void* go = sh.go16 ? sh.go16 : ws.go;
+  if (!sh.go16) {
+    LAUNCH("colsum", launch_colsum(0, d_out, T, d, ws.part, ws.splits, d_b_fc2, s));
+    LAUNCH("convert", launch_convert_from_f32(dt, d_out, ws.go, (size_t)T * d, s));
+  }
   auto dw_gemm = [&](const void* A, const void* W, void* out, int M, int N) {  // K = the rows: sliced
     GemmArgs g = gemm(A, W, nullptr, out, M, N, Tp, EPI_F32);
     g.long_k = true;
@@ -1039,23 +1060,23 @@ int rlhf_mlp_backward(rlhf_handle* h, int32_t layer, const float* x_in, const fl
     g.k_major = true;
     return g;
   };
-  const bool kmaj = gemm_takes_k_major(dt, dw_kmajor(ws.go, ws.f, d_w_fc2, d, F)) &&
+  const bool kmaj = gemm_takes_k_major(dt, dw_kmajor(go, ws.f, d_w_fc2, d, F)) &&
                     gemm_takes_k_major(dt, dw_kmajor(ws.df, ws.m, d_w_fc1, F, d));
   auto zero_tail = [&](void* buf, int width) {
     return Tp > T ? launch_fill_zero((char*)buf + (size_t)T * width * h->esz, (size_t)(Tp - T) * width * h->esz, s)
                   : hipSuccess;
   };
   if (kmaj) {
-    LAUNCH("mlp_bwd_zero", zero_tail(ws.go, d));
+    if (!sh.go16) LAUNCH("mlp_bwd_zero", zero_tail(ws.go, d));
     LAUNCH("mlp_bwd_zero", zero_tail(ws.f, F));
-    LAUNCH("gemm_mlp_dw", launch_gemm(dt, dw_kmajor(ws.go, ws.f, d_w_fc2, d, F), s));
+    LAUNCH("gemm_mlp_dw", launch_gemm(dt, dw_kmajor(go, ws.f, d_w_fc2, d, F), s));
   } else {
-    LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.go, (size_t)d, ws.goT, (size_t)Tp, T, d, Tp, s));
+    LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, go, (size_t)d, ws.goT, (size_t)Tp, T, d, Tp, s));
     LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, ws.f, (size_t)F, ws.fT, (size_t)Tp, T, F, Tp, s));
     LAUNCH("gemm_mlp_dw", launch_gemm(dt, dw_gemm(ws.goT, ws.fT, d_w_fc2, d, F), s));
   }
   LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, h->w_fc2[l], ld_w2, ws.w2T, (size_t)d, d, F, d, s));
-  LAUNCH("gemm_mlp_dx", launch_gemm(dt, gemm(ws.go, ws.w2T, nullptr, ws.df, T, F, d, EPI_BIAS), s));
+  LAUNCH("gemm_mlp_dx", launch_gemm(dt, gemm(go, ws.w2T, nullptr, ws.df, T, F, d, EPI_BIAS), s));
   // ---- GELU, then FC1: du = df * gelu'(u) (in place), db1 = sum_t du, dW1 = du^T m, dm = du W1
   LAUNCH("gelu", launch_gelu_backward(dt, ws.u, ws.df, (size_t)T * F, s));
   LAUNCH("colsum", launch_colsum(dt, ws.df, T, F, ws.part, ws.splits, d_b_fc1, s));
@@ -1071,9 +1092,11 @@ int rlhf_mlp_backward(rlhf_handle* h, int32_t layer, const float* x_in, const fl
   LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, h->w_fc1[l], (size_t)d, ws.w1T, (size_t)F, F, d, F, s));
   LAUNCH("gemm_mlp_dx", launch_gemm(dt, gemm(ws.df, ws.w1T, nullptr, ws.dm, T, d, F, EPI_F32), s));
   // ---- LN2: the branch's term of dL/dx, and the gradients of its gain and bias
+  if (sh.base && !(ln_backward_rows_supported(dt, d) && (((uintptr_t)x_in | (uintptr_t)d_x | (uintptr_t)sh.base) & 15) == 0))
+    return fail(RLHF_EUNSUPPORTED, "accumulating LayerNorm backward: shape");
   if (ln_backward_rows_supported(dt, d) && (((uintptr_t)x_in | (uintptr_t)d_x) & 15) == 0)
     LAUNCH("ln_backward", launch_ln_backward_rows(x_in, ws.dm, h->ln2_g[l], T, d, c.ln_eps, d_x, ws.lnpart, d_ln2_g,
-                                                  d_ln2_b, s));
+                                                  d_ln2_b, s, sh.base));
   else
     LAUNCH("head_ln_backward", launch_head_ln_backward(dt, x_in, ws.dm, nullptr, 1.0f, nullptr, h->ln2_g[l], h->ln2_b[l],
                                                        T, d, c.ln_eps, d_x, ws.stats, ws.part, ws.splits, d_ln2_g,
@@ -1137,7 +1160,8 @@ static int attention_branch_backward_impl(rlhf_handle* h, int32_t layer, const f
                                           const int32_t* cu_seqlens, int32_t B, int32_t T, int32_t max_len, float* d_x,
                                           float* d_ln1_g, float* d_ln1_b, float* d_w_qkv, float* d_b_qkv, float* d_w_o,
                                           float* d_b_o, void* workspace, size_t workspace_bytes, void* stream,
-                                          const void* kept_q, const void* kept_k, const void* kept_v);
+                                          const void* kept_q, const void* kept_k, const void* kept_v,
+                                          BranchShare sh = BranchShare{});
 
 int rlhf_attention_branch_backward(rlhf_handle* h, int32_t layer, const float* x_in, const float* d_out,
                                    const int32_t* cu_seqlens, int32_t B, int32_t T, int32_t max_len, float* d_x,
@@ -1152,7 +1176,7 @@ static int attention_branch_backward_impl(rlhf_handle* h, int32_t layer, const f
                                           const int32_t* cu_seqlens, int32_t B, int32_t T, int32_t max_len, float* d_x,
                                           float* d_ln1_g, float* d_ln1_b, float* d_w_qkv, float* d_b_qkv, float* d_w_o,
                                           float* d_b_o, void* workspace, size_t workspace_bytes, void* stream,
-                                          const void* kept_q, const void* kept_k, const void* kept_v) {
+                                          const void* kept_q, const void* kept_k, const void* kept_v, BranchShare sh) {
   if (!h) return fail(RLHF_EINVAL, "null handle");
   const rlhf_model_config& c = h->cfg;
   if (layer < 0 || layer >= c.n_layers) return fail(RLHF_EINVAL, "layer index out of range");
@@ -1194,10 +1218,13 @@ static int attention_branch_backward_impl(rlhf_handle* h, int32_t layer, const f
                                                h->rope_cos, h->rope_sin, 0, s));
   }
   // ---- out-projection: dbo = sum_t G, do = G Wo
-  LAUNCH("colsum", launch_colsum(0, d_out, T, d, ws.part, ws.splits, d_b_o, s));
-  LAUNCH("convert", launch_convert_from_f32(dt, d_out, ws.go, (size_t)T * d, s));
+  const void* go = sh.go16 ? sh.go16 : ws.go;
+  if (!sh.go16) {
+    LAUNCH("colsum", launch_colsum(0, d_out, T, d, ws.part, ws.splits, d_b_o, s));
+    LAUNCH("convert", launch_convert_from_f32(dt, d_out, ws.go, (size_t)T * d, s));
+  }
   LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, h->w_o[l], ld_wo, ws.woT, (size_t)d, d, d, d, s));
-  LAUNCH("gemm_attn_dx", launch_gemm(dt, gemm(ws.go, ws.woT, nullptr, ws.dO, T, d, d, EPI_BIAS), s));
+  LAUNCH("gemm_attn_dx", launch_gemm(dt, gemm(go, ws.woT, nullptr, ws.dO, T, d, d, EPI_BIAS), s));
   // ---- attention core: (dq | dk | dv) into the sections of dqkv, and the forward output o
   char* qkv = (char*)ws.qkv;
   char* dqkv = (char*)ws.dqkv;
@@ -1227,18 +1254,18 @@ static int attention_branch_backward_impl(rlhf_handle* h, int32_t layer, const f
     g.k_major = true;
     return g;
   };
-  const bool kmaj = gemm_takes_k_major(dt, dw_kmajor(ws.go, ws.att, d_w_o, d, d)) &&
+  const bool kmaj = gemm_takes_k_major(dt, dw_kmajor(go, ws.att, d_w_o, d, d)) &&
                     gemm_takes_k_major(dt, dw_kmajor(ws.dqkv, ws.a, d_w_qkv, 3 * d, d));
   auto zero_tail = [&](void* buf, int width) {
     return Tp > T ? launch_fill_zero((char*)buf + (size_t)T * width * esz, (size_t)(Tp - T) * width * esz, s)
                   : hipSuccess;
   };
   if (kmaj) {
-    LAUNCH("attn_bwd_zero", zero_tail(ws.go, d));
+    if (!sh.go16) LAUNCH("attn_bwd_zero", zero_tail(ws.go, d));
     LAUNCH("attn_bwd_zero", zero_tail(ws.att, d));
-    LAUNCH("gemm_attn_dw", launch_gemm(dt, dw_kmajor(ws.go, ws.att, d_w_o, d, d), s));
+    LAUNCH("gemm_attn_dw", launch_gemm(dt, dw_kmajor(go, ws.att, d_w_o, d, d), s));
   } else {
-    LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.go, (size_t)d, ws.goT, (size_t)Tp, T, d, Tp, s));
+    LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, go, (size_t)d, ws.goT, (size_t)Tp, T, d, Tp, s));
     LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, ws.att, (size_t)d, ws.attT, (size_t)Tp, T, d, Tp, s));
     LAUNCH("gemm_attn_dw", launch_gemm(dt, dw_gemm(ws.goT, ws.attT, d_w_o, d, d), s));
   }
@@ -1262,9 +1289,11 @@ static int attention_branch_backward_impl(rlhf_handle* h, int32_t layer, const f
   LAUNCH("attn_bwd_transpose", launch_transpose_pad(dt, h->w_qkv[l], (size_t)d, ws.wqkvT, (size_t)3 * d, 3 * d, d, 3 * d, s));
   LAUNCH("gemm_attn_dx", launch_gemm(dt, gemm(ws.dqkv, ws.wqkvT, nullptr, ws.da, T, d, 3 * d, EPI_F32), s));
   // ---- LN1: the branch's term of dL/dx, and the gradients of its gain and bias
+  if (sh.base && !(ln_backward_rows_supported(dt, d) && (((uintptr_t)x_in | (uintptr_t)d_x | (uintptr_t)sh.base) & 15) == 0))
+    return fail(RLHF_EUNSUPPORTED, "accumulating LayerNorm backward: shape");
   if (ln_backward_rows_supported(dt, d) && (((uintptr_t)x_in | (uintptr_t)d_x) & 15) == 0)
     LAUNCH("ln_backward", launch_ln_backward_rows(x_in, ws.da, h->ln1_g[l], T, d, c.ln_eps, d_x, ws.lnpart, d_ln1_g,
-                                                  d_ln1_b, s));
+                                                  d_ln1_b, s, sh.base));
   else
     LAUNCH("head_ln_backward", launch_head_ln_backward(dt, x_in, ws.da, nullptr, 1.0f, nullptr, h->ln1_g[l], h->ln1_b[l],
                                                        T, d, c.ln_eps, d_x, ws.stats, ws.part, ws.splits, d_ln1_g,
@@ -1573,7 +1602,10 @@ int rlhf_policy_backward_workspace_bytes(const rlhf_handle* h, int32_t T, size_t
     rc = rlhf_attention_branch_backward_workspace_bytes(h, T, &c);
     if (rc) return rc;
   }
-  *out = std::max(a, std::max(b, c)) + (size_t)4 * T * h->cfg.d_model * sizeof(float) + 2048;
+  // four [T, d] float buffers, the shared fp16 copy of the stream's gradient (rows padded to 128) and its column-sum scratch
+  const size_t Tp = ((size_t)T + 127) & ~(size_t)127;
+  *out = std::max(a, std::max(b, c)) + (size_t)4 * T * h->cfg.d_model * sizeof(float) + Tp * h->cfg.d_model * h->esz +
+         (size_t)256 * h->cfg.d_model * sizeof(float) + 4096;
   return RLHF_OK;
 }
 
@@ -1628,8 +1660,20 @@ static int policy_backward_impl(rlhf_handle* h, const float* x_keep, int64_t x_k
   float* dx_m = (float*)(base + buf);       // MLP branch term
   float* dx_a = (float*)(base + 2 * buf);   // attention branch term
   float* dx_n = (float*)(base + 3 * buf);   // their sum with dx: the gradient one layer down
-  char* sub = base + 4 * buf;
+  // shared by a layer's two branches: the fp16 copy of dx (zero padding rows) and the scratch of its column sums
+  const size_t Tp = ((size_t)T + 127) & ~(size_t)127;
+  const size_t go_bytes = (Tp * c.d_model * h->esz + 255) & ~(size_t)255;
+  const size_t part_bytes = ((size_t)256 * c.d_model * sizeof(float) + 255) & ~(size_t)255;
+  char* go16 = base + 4 * buf;
+  float* go_part = (float*)(go16 + go_bytes);
+  char* sub = go16 + go_bytes + part_bytes;
   const size_t sub_bytes = workspace_bytes - (size_t)(sub - (char*)workspace);
+  // one conversion and one set of column sums of dx per layer for both branches, and each branch's LayerNorm
+  // backward adding onto the running sum (dx + MLP term, then + attention term) -- where the one-pass kernel runs
+  const bool share = c.dtype == 1 && c.n_layers > 0 && ln_backward_rows_supported(c.dtype, c.d_model) && (c.d_model & 3) == 0;
+  const int go_splits = std::max(1, std::min(256, (T + 255) / 256));
+  if (share && Tp > (size_t)T)
+    LAUNCH("convert", launch_fill_zero(go16 + (size_t)T * c.d_model * h->esz, (Tp - T) * c.d_model * h->esz, s));
   const float* x_final = x_keep + (size_t)c.n_layers * x_keep_layer_stride;
   if (sel && sel_rows > 0 && sel_rows < T) {
     // the heads on the selected rows: their inputs gathered into the (still free) branch buffers, the input
@@ -1653,17 +1697,27 @@ static int policy_backward_impl(rlhf_handle* h, const float* x_keep, int64_t x_k
   }
   for (int l = c.n_layers - 1; l >= 0; --l) {
     const float* xl = x_keep + (size_t)l * x_keep_layer_stride;
-    rc = rlhf_mlp_backward(h, l, xl, dx, T, dx_m, g->ln2_g[l], g->ln2_b[l], g->w_fc1[l], g->b_fc1[l], g->w_fc2[l],
-                           g->b_fc2[l], sub, sub_bytes, stream);
+    if (share) {
+      LAUNCH("convert", launch_convert_colsum(dx, T, c.d_model, go_part, go_splits, g->b_fc2[l], go16, s));
+      HIP_OK(hipMemcpyAsync(g->b_o[l], g->b_fc2[l], (size_t)c.d_model * sizeof(float), hipMemcpyDeviceToDevice, s));
+    }
+    BranchShare sm, sa;
+    if (share) {
+      sm.go16 = sa.go16 = go16;
+      sm.base = dx;    // dx_m = dx + MLP term
+      sa.base = dx_m;  // dx_n = dx_m + attention term
+    }
+    rc = mlp_backward_impl(h, l, xl, dx, T, dx_m, g->ln2_g[l], g->ln2_b[l], g->w_fc1[l], g->b_fc1[l], g->w_fc2[l],
+                           g->b_fc2[l], sub, sub_bytes, stream, sm);
     if (rc) return rc;
     const size_t plane = (size_t)x_keep_layer_stride * h->esz;  // bytes of one layer's q rows, K plane or V plane
     const char* kq = kept_q && kept_kv ? kept_q + (size_t)l * plane : nullptr;
     const char* kk = kq ? kept_kv + (size_t)l * 2 * plane : nullptr;
-    rc = attention_branch_backward_impl(h, l, xl, dx, cu_seqlens, B, T, max_len, dx_a, g->ln1_g[l], g->ln1_b[l],
-                                        g->w_qkv[l], g->b_qkv[l], g->w_o[l], g->b_o[l], sub, sub_bytes, stream, kq, kk,
-                                        kk ? kk + plane : nullptr);
+    rc = attention_branch_backward_impl(h, l, xl, dx, cu_seqlens, B, T, max_len, share ? dx_n : dx_a, g->ln1_g[l],
+                                        g->ln1_b[l], g->w_qkv[l], g->b_qkv[l], g->w_o[l], g->b_o[l], sub, sub_bytes, stream,
+                                        kq, kk, kk ? kk + plane : nullptr, sa);
     if (rc) return rc;
-    LAUNCH("add3", launch_add3(dx, dx_a, dx_m, dx_n, n, s));
+    if (!share) LAUNCH("add3", launch_add3(dx, dx_a, dx_m, dx_n, n, s));
     std::swap(dx, dx_n);
   }
   LAUNCH("embed_backward", launch_embed_backward(packed_tokens, dx, T, c.d_model, c.vocab, g->embed_in, s));

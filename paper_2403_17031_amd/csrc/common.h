@@ -332,8 +332,13 @@ hipError_t launch_softmax_grad(int dtype, const float* logits, int V, int V_pad,
 // bf16 parameters, d a multiple of 256 up to 4096; part: ln_backward_rows_scratch_floats(T, d) floats of scratch.
 bool ln_backward_rows_supported(int dtype, int d);
 size_t ln_backward_rows_scratch_floats(int T, int d);
+// base (optional): dx = base + the LayerNorm input gradient (rows of d floats like dx).
 hipError_t launch_ln_backward_rows(const float* x, const float* dy, const void* g, int T, int d, float eps, float* dx,
-                                   float* part, float* d_g, float* d_b, hipStream_t s);
+                                   float* part, float* d_g, float* d_b, hipStream_t s, const float* base = nullptr);
+// sums[c] = sum_r a[r][c] of a float [R, C] matrix (C a multiple of 4) and out_f16 = its fp16 copy, in one pass;
+// part: [splits][C] floats of scratch.
+hipError_t launch_convert_colsum(const float* a, int R, int C, float* part, int splits, float* sums, void* out_f16,
+                                 hipStream_t s);
 hipError_t launch_head_ln_backward(int dtype, const float* x, const float* dhl, const float* gv, float scale,
                                    const void* value_w, const void* g, const void* b, int T, int d, float eps,
                                    float* dx, float* stats, float* part, int splits, float* d_g, float* d_b,

@@ -267,7 +267,8 @@ __global__ void __launch_bounds__(256)
 template <int NV>
 __global__ void __launch_bounds__(256)
     ln_backward_rows_kernel(const float* __restrict__ x, const float* __restrict__ dyp, const bf16_t* __restrict__ g,
-                            int T, float eps, float* __restrict__ dx, float* __restrict__ part, int rows_per_wave) {
+                            int T, float eps, float* __restrict__ dx, float* __restrict__ part, int rows_per_wave,
+                            const float* __restrict__ base) {
   constexpr int d = 256 * NV;
   const int lane = threadIdx.x & 63;
   const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -319,11 +320,13 @@ __global__ void __launch_bounds__(256)
     }
     const float mu = wave_sum(su) / (float)d, mux = wave_sum(sux) / (float)d;
     f32x4_t* o = (f32x4_t*)(dx + (size_t)t * d);
+    const f32x4_t* bs = base ? (const f32x4_t*)(base + (size_t)t * d) : nullptr;  // dx = base + this term
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       f32x4_t r;
 #pragma unroll
       for (int e = 0; e < 4; ++e) r[e] = rstd * (u[j][e] - mu - xv[j][e] * mux);
+      if (bs) r += bs[lane + 64 * j];
       o[lane + 64 * j] = r;
     }
   }
@@ -516,6 +519,32 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
   for (int i = 0; i < V; ++i) part[(size_t)blockIdx.y * C + c0 + i] = s[i];
 }
+// Column sums of a float [R, C] matrix as above and, in the same pass, its fp16 copy.
+__global__ void __launch_bounds__(256)
+    convert_colsum_part_kernel(const float* __restrict__ a, int R, int C, int rows_per_split, float* __restrict__ part,
+                               half_t* __restrict__ out) {
+  const int c0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (c0 >= C) return;
+  const int r0 = blockIdx.y * rows_per_split, r1 = min(R, r0 + rows_per_split);
+  f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+  for (int r = r0; r < r1; r += 4) {
+    f32x4_t v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      v[k] = r + k < r1 ? *(const f32x4_t*)(a + (size_t)(r + k) * C + c0) : f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      s += v[k];
+      if (r + k < r1) {
+        const f16x4_t hv = {from_f32<half_t>(v[k][0]), from_f32<half_t>(v[k][1]), from_f32<half_t>(v[k][2]),
+                            from_f32<half_t>(v[k][3])};
+        *(f16x4_t*)(out + (size_t)(r + k) * C + c0) = hv;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) part[(size_t)blockIdx.y * C + c0 + i] = s[i];
+}
 __global__ void __launch_bounds__(256)
     colsum_final_kernel(const float* __restrict__ part, int splits, int C, float* __restrict__ out) {
   const int c = blockIdx.x * 256 + threadIdx.x;
@@ -613,6 +642,16 @@ hipError_t launch_convert_from_f32(int dtype, const float* src, void* dst, size_
   else hipLaunchKernelGGL(convert_kernel<half_t>, dim3(blocks), dim3(256), 0, s, src, (half_t*)dst, n);
   return hipGetLastError();
 }
+hipError_t launch_convert_colsum(const float* a, int R, int C, float* part, int splits, float* sums, void* out_f16,
+                                 hipStream_t s) {
+  if (C <= 0 || R <= 0) return hipSuccess;
+  if ((C & 3) != 0 || (((uintptr_t)a | (uintptr_t)out_f16) & 15) != 0) return hipErrorInvalidValue;
+  const int rps = (R + splits - 1) / splits;
+  hipLaunchKernelGGL(convert_colsum_part_kernel, dim3((C / 4 + 255) / 256, splits), dim3(256), 0, s, a, R, C, rps, part,
+                     (half_t*)out_f16);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((C + 255) / 256), dim3(256), 0, s, part, splits, C, sums);
+  return hipGetLastError();
+}
 // elem: 0 = float matrix, 1 = fp16 matrix.  part: [splits][C] floats of scratch.
 hipError_t launch_colsum(int elem, const void* a, int R, int C, float* part, int splits, float* out, hipStream_t s) {
   if (C <= 0) return hipSuccess;
@@ -683,13 +722,13 @@ size_t ln_backward_rows_scratch_floats(int T, int d) {
   return (size_t)waves * 2 * d;
 }
 hipError_t launch_ln_backward_rows(const float* x, const float* dy, const void* g, int T, int d, float eps, float* dx,
-                                   float* part, float* d_g, float* d_b, hipStream_t s) {
+                                   float* part, float* d_g, float* d_b, hipStream_t s, const float* base) {
   if (T <= 0) return hipSuccess;
   const int rpw = std::max(1, (T + 2047) / 2048), waves = ((T + rpw - 1) / rpw + 3) & ~3;
 #define RLHF_LNB(NV)                                                                                             \
   case NV:                                                                                                       \
     hipLaunchKernelGGL(ln_backward_rows_kernel<NV>, dim3(waves / 4), dim3(256), 0, s, x, dy, (const bf16_t*)g, T, \
-                       eps, dx, part, rpw);                                                                      \
+                       eps, dx, part, rpw, base);                                                                \
     break;
   switch (d / 256) {
     RLHF_LNB(1) RLHF_LNB(2) RLHF_LNB(3) RLHF_LNB(4) RLHF_LNB(5) RLHF_LNB(6) RLHF_LNB(7) RLHF_LNB(8)

@@ -329,37 +329,43 @@ __global__ void __launch_bounds__(256, 1)
   // of Q and of dO, which it writes to LDS both row-major (4 x 16 bytes) and transposed (8 x 8 bytes, the 4 queries
   // adjacent under the column permutation of the accumulator layout).  Threads past the tile's 16 * CPR items
   // re-read the last item instead of branching around the loads (the wait counting stays static).
-  constexpr int ITEMS = 16 * CPR;
-  static_assert(ITEMS <= 256, "one item per thread");
-  const int item = min(tid, ITEMS - 1), ich = item / 16, ig4 = item - ich * 16;
-  f16x8_t qv[4], gv[4];
+  constexpr int ITEMS = 16 * CPR, NIT = (ITEMS + 255) / 256;  // items of the tile, items per thread
+  f16x8_t qv[NIT][4], gv[NIT][4];
   float lse_r = 0.f, del_r = 0.f;
   auto load_tile = [&](int i0) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const size_t row = (size_t)(s0 + min(i0 + 4 * ig4 + u, n - 1));
-      qv[u] = *(const f16x8_t*)(q + row * ldq + col + ich * 8);
-      gv[u] = *(const f16x8_t*)(g + row * ldg + col + ich * 8);
+    for (int it = 0; it < NIT; ++it) {
+      const int item = min(tid + 256 * it, ITEMS - 1), ich = item / 16, ig4 = item - ich * 16;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const size_t row = (size_t)(s0 + min(i0 + 4 * ig4 + u, n - 1));
+        qv[it][u] = *(const f16x8_t*)(q + row * ldq + col + ich * 8);
+        gv[it][u] = *(const f16x8_t*)(g + row * ldg + col + ich * 8);
+      }
     }
     const size_t row = (size_t)(s0 + min(i0 + (tid & 63), n - 1));
     lse_r = lse[row * H + h];
     del_r = delta[row * H + h];
   };
   auto store_tile = [&]() {
-    if (tid < ITEMS) {
-      const int kk = (4 * ig4) & 15;
-      const int colp = ((4 * ig4) & ~15) + 8 * ((kk >> 2) & 1) + 4 * (kk >> 3);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        *(f16x8_t*)((half_t*)Qs + (4 * ig4 + u) * RS + ich * 8) = qv[u];
-        *(f16x8_t*)((half_t*)Gs + (4 * ig4 + u) * RS + ich * 8) = gv[u];
-      }
+    for (int it = 0; it < NIT; ++it) {
+      const int item = tid + 256 * it, ich = item / 16, ig4 = item - ich * 16;
+      if (item < ITEMS) {
+        const int kk = (4 * ig4) & 15;
+        const int colp = ((4 * ig4) & ~15) + 8 * ((kk >> 2) & 1) + 4 * (kk >> 3);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const f16x4_t wq = {qv[0][e], qv[1][e], qv[2][e], qv[3][e]};
-        const f16x4_t wg = {gv[0][e], gv[1][e], gv[2][e], gv[3][e]};
-        *(f16x4_t*)((half_t*)Qt + (ich * 8 + e) * TS + colp) = wq;
-        *(f16x4_t*)((half_t*)Gt + (ich * 8 + e) * TS + colp) = wg;
+        for (int u = 0; u < 4; ++u) {
+          *(f16x8_t*)((half_t*)Qs + (4 * ig4 + u) * RS + ich * 8) = qv[it][u];
+          *(f16x8_t*)((half_t*)Gs + (4 * ig4 + u) * RS + ich * 8) = gv[it][u];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const f16x4_t wq = {qv[it][0][e], qv[it][1][e], qv[it][2][e], qv[it][3][e]};
+          const f16x4_t wg = {gv[it][0][e], gv[it][1][e], gv[it][2][e], gv[it][3][e]};
+          *(f16x4_t*)((half_t*)Qt + (ich * 8 + e) * TS + colp) = wq;
+          *(f16x4_t*)((half_t*)Gt + (ich * 8 + e) * TS + colp) = wg;
+        }
       }
     }
     if (tid < 64) {
@@ -513,38 +519,44 @@ __global__ void __launch_bounds__(256, 1)
   // and of V, which it writes to LDS row-major (4 x 16 bytes) and / or transposed (8 x 8 bytes, the 4 keys adjacent
   // under the column permutation of the accumulator layout), whichever images the pass reads.  Threads past the
   // tile's 16 * CPR items re-read the last item instead of branching around the loads (static wait counts).
-  constexpr int ITEMS = 16 * CPR;
-  static_assert(ITEMS <= 256, "one item per thread");
-  const int item = min(tid, ITEMS - 1), ich = item / 16, ig4 = item - ich * 16;
-  f16x8_t kv[4], vv[4];
+  constexpr int ITEMS = 16 * CPR, NIT = (ITEMS + 255) / 256;  // items of the tile, items per thread
+  f16x8_t kv[NIT][4], vv[NIT][4];
   const size_t kvb = kv_cache ? ((size_t)s0 * H + (size_t)h * (cu[b + 1] - cu[b])) * HD : (size_t)s0 * ldq + col;
   const size_t kvld = kv_cache ? (size_t)HD : ldq;
   auto load_tile = [&](int k0) {
     k0 = min(k0, k_last);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const size_t off = kvb + (size_t)min(k0 + 4 * ig4 + u, n - 1) * kvld + ich * 8;
-      kv[u] = *(const f16x8_t*)(k + off);
-      vv[u] = *(const f16x8_t*)(v + off);
+    for (int it = 0; it < NIT; ++it) {
+      const int item = min(tid + 256 * it, ITEMS - 1), ich = item / 16, ig4 = item - ich * 16;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const size_t off = kvb + (size_t)min(k0 + 4 * ig4 + u, n - 1) * kvld + ich * 8;
+        kv[it][u] = *(const f16x8_t*)(k + off);
+        vv[it][u] = *(const f16x8_t*)(v + off);
+      }
     }
   };
   auto store_tile = [&](bool second_pass) {
-    if (tid < ITEMS) {
-      const int kk = (4 * ig4) & 15;
-      const int colp = ((4 * ig4) & ~15) + 8 * ((kk >> 2) & 1) + 4 * (kk >> 3);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        *(f16x8_t*)((half_t*)Ks + (4 * ig4 + u) * RS + ich * 8) = kv[u];
-        if (second_pass) *(f16x8_t*)((half_t*)Vs + (4 * ig4 + u) * RS + ich * 8) = vv[u];
-      }
+    for (int it = 0; it < NIT; ++it) {
+      const int item = tid + 256 * it, ich = item / 16, ig4 = item - ich * 16;
+      if (item < ITEMS) {
+        const int kk = (4 * ig4) & 15;
+        const int colp = ((4 * ig4) & ~15) + 8 * ((kk >> 2) & 1) + 4 * (kk >> 3);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        if (second_pass) {
-          const f16x4_t wk = {kv[0][e], kv[1][e], kv[2][e], kv[3][e]};
-          *(f16x4_t*)((half_t*)Kt + (ich * 8 + e) * TS + colp) = wk;
-        } else {
-          const f16x4_t wv = {vv[0][e], vv[1][e], vv[2][e], vv[3][e]};
-          *(f16x4_t*)((half_t*)Vt + (ich * 8 + e) * TS + colp) = wv;
+        for (int u = 0; u < 4; ++u) {
+          *(f16x8_t*)((half_t*)Ks + (4 * ig4 + u) * RS + ich * 8) = kv[it][u];
+          if (second_pass) *(f16x8_t*)((half_t*)Vs + (4 * ig4 + u) * RS + ich * 8) = vv[it][u];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (second_pass) {
+            const f16x4_t wk = {kv[it][0][e], kv[it][1][e], kv[it][2][e], kv[it][3][e]};
+            *(f16x4_t*)((half_t*)Kt + (ich * 8 + e) * TS + colp) = wk;
+          } else {
+            const f16x4_t wv = {vv[it][0][e], vv[it][1][e], vv[it][2][e], vv[it][3][e]};
+            *(f16x4_t*)((half_t*)Vt + (ich * 8 + e) * TS + colp) = wv;
+          }
         }
       }
     }
@@ -782,7 +794,7 @@ hipError_t launch_qkv_rows_to_caller_order(const float* in, float* out, int d, i
 
 // dtype 0: float, 1: fp16.  head_dim a multiple of 4 (float) or 8 (fp16); the longest sequence at
 // most max_len rows (longer ones are cut off at max_len: wrong results, but no access out of bounds).
-bool attention_backward_takes_cache(int dtype, int hd) { return dtype == 1 && (hd == 64 || hd == 80 || hd == 128); }
+bool attention_backward_takes_cache(int dtype, int hd) { return dtype == 1 && (hd == 64 || hd == 80 || hd == 128 || hd == 256); }
 
 hipError_t launch_attention_backward(int dtype, const void* q, const void* k, const void* v, const void* g,
                                      const int* cu, int B, int Tn, int H, int hd, int max_len, float* lse,
@@ -816,7 +828,7 @@ hipError_t launch_attention_backward(int dtype, const void* q, const void* k, co
       (void)hipFuncSetAttribute((const void*)attn_bwd_q_kernel<half_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
       (void)hipFuncSetAttribute((const void*)attn_bwd_kv_kernel<half_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
     }
-    if (hd == 64 || hd == 80 || hd == 128) {  // the model family's head sizes: matrix-core forms of both kernels
+    if (hd == 64 || hd == 80 || hd == 128 || hd == 256) {  // the model family's head sizes: matrix-core forms of both kernels
       dim3 mgrid((max_len + 127) / 128, H, B);
 #define RLHF_BWD_MFMA(HD_)                                                                                      \
   hipLaunchKernelGGL(attn_bwd_q_mfma<HD_>, mgrid, dim3(256), 0, s, (const half_t*)q, (const half_t*)k,          \
@@ -827,7 +839,8 @@ hipError_t launch_attention_backward(int dtype, const void* q, const void* k, co
                      ld_qkv, ld_g, ld_out, kv_cache ? 1 : 0)
       if (hd == 64) { RLHF_BWD_MFMA(64); }
       else if (hd == 80) { RLHF_BWD_MFMA(80); }
-      else { RLHF_BWD_MFMA(128); }
+      else if (hd == 128) { RLHF_BWD_MFMA(128); }
+      else { RLHF_BWD_MFMA(256); }
 #undef RLHF_BWD_MFMA
       return hipGetLastError();
     }

@@ -48,7 +48,7 @@ def test_fp32(gpu, lens, H, hd):
 
 
 @pytest.mark.parametrize("lens,H,hd", [((3,), 1, 8), ((5, 1, 7, 2), 2, 16), ((64, 65, 1, 130, 63), 3, 64),
-                                        ((352, 565, 96, 211), 4, 80), ((129, 40), 2, 128), ((70,), 1, 256)])
+                                        ((352, 565, 96, 211), 4, 80), ((129, 40), 2, 128), ((70,), 1, 256), ((300, 70, 129, 565), 2, 256)])
 def test_fp16(gpu, lens, H, hd):
     """Sequence lengths around the 64-lane wave width and the benchmark's range, every head size of the model
     family."""

@@ -330,12 +330,8 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
   // LayerNorm / rotary kernel as much again in partial sums to add up).  FC1 and FC2 run in the shadow of the
   // attention kernel on a second stream: there the staged tile kernel's small blocks, which fit on a CU next to
   // attention blocks, do better than blocks that each take a whole CU (measured: decode 476 against 525-580 ms).
-  int cap_qkv = 4, cap_o = 4, cap_1 = 0, cap_2 = 0;
-  int mlp_small_i = 1;
-#ifdef RLHF_TUNE
-  if (const char* e = getenv("RLHF_DEC_SPLITS")) sscanf(e, "%d,%d,%d,%d,%d", &cap_qkv, &cap_o, &cap_1, &cap_2, &mlp_small_i);
-#endif
-  const bool mlp_small = p.mode == 1 && mlp_small_i != 0;
+  const int cap_qkv = 4, cap_o = 4, cap_1 = 0, cap_2 = 0;
+  const bool mlp_small = p.mode == 1;
   auto capped = [](GemmArgs g, int cap) {
     g.max_split = cap;
     return g;
@@ -354,10 +350,7 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
   // Decode: the MLP branch (weights streaming through the matrix cores) overlaps the attention
   // branch (K/V streaming from HBM).  Needs FC2 on the split-K path, so that only its final
   // reduction touches the residual stream; not used while per-kernel profiling is on.
-  bool fork_mlp = p.mode == 1 && !h->prof_on && ks_2 > 1;
-#ifdef RLHF_TUNE
-  if (getenv("RLHF_NO_FORK")) fork_mlp = false;
-#endif
+  const bool fork_mlp = p.mode == 1 && !h->prof_on && ks_2 > 1;
   // Prefill / scoring: out-projection and FC2 both add into the residual stream, so they run as one
   // product over the concatenated K = d + d_ff when the large-M kernel takes that shape.
   auto gcat = [&](int l) {

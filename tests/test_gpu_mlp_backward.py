@@ -65,10 +65,11 @@ def test_fp32_check_mode(gpu, T, d, F):
     _check(gpu, _cfg(d, F, "fp32"), T, seed=T, layer=1)
 
 
-@pytest.mark.parametrize("T,d,F", [(5, 64, 256), (300, 128, 512), (700, 128, 328), (1500, 256, 1024), (2100, 384, 768)])
+@pytest.mark.parametrize("T,d,F", [(5, 64, 256), (300, 128, 512), (700, 128, 328), (1500, 256, 1024), (2100, 384, 768), (1333, 640, 1544)])
 def test_bf16_mode(gpu, T, d, F):
     """Few rows and many (the weight-gradient products' K is the row count, padded to 128), widths the large-tile
-    GEMM takes and widths it does not, a row count that is not a multiple of 4 (scalar transposes)."""
+    GEMM takes and widths it does not, a row count that is not a multiple of 4 (scalar transposes), widths beyond 512
+    that are no multiple of the 256-wide tile (the weight-gradient products then read K-major operands)."""
     _check(gpu, _cfg(d, F, "bf16"), T, seed=T, layer=0, scale=8.0)
 
 

@@ -371,7 +371,10 @@ int rlhf_policy_backward(rlhf_handle *h, const float *x_keep, int64_t x_keep_lay
  * minibatch_tokens: HOST int32 [n_minibatches], the number of real tokens (mask == 1) of each mini-batch; max_len
  * (host): at least the longest row.  grad_scale: see rlhf_head_backward (64 x the kept response tokens of a
  * mini-batch is a good value in bf16 mode; 1 in fp32 mode).  Workspace size from rlhf_ppo_update_workspace_bytes
- * (B_minibatch = B / n_minibatches, L = Lq + N, T_max = the largest entry of minibatch_tokens).  Everything is
+ * (B_minibatch = B / n_minibatches, L = Lq + N, T_max = the largest entry of minibatch_tokens): that is the minimum.
+ * A bf16 model uses whatever the caller passes beyond it to keep FC1's output (before the GELU) of the forward pass
+ * instead of recomputing it in the backward pass: T_max * d_ff * 2 bytes (rounded up to 256) per layer, for as many
+ * of the first layers as fit; results are the same up to the rounding of the GELU's two forms.  Everything is
  * enqueued on `stream`; no host synchronisation. */
 typedef struct {
   int32_t epochs, n_minibatches;            /* the paper: 4, 1 */

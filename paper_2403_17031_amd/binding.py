@@ -447,7 +447,7 @@ class Policy:
 
     def ppo_update(self, tokens, mask, query_len, old_logprobs, advantages, old_values, returns, kept, temperature,
                    epochs=4, n_minibatches=1, cliprange=0.2, cliprange_value=0.2, vf_coef=0.1, lr=3e-6, beta1=0.9,
-                   beta2=0.999, eps=1e-5, weight_decay=0.01, grad_scale=None):
+                   beta2=0.999, eps=1e-5, weight_decay=0.01, grad_scale=None, keep_preactivations=True):
         """One PPO update (K iterations over mini-batches) through rlhf_ppo_update.  tokens int32 / mask uint8
         [B, Lq+N]; old_logprobs, advantages, old_values, returns float32 [B, N]; kept int32 [B].  Updates this
         policy's weights in place (and the optimizer state from train_state()).  Returns the loss statistics, a
@@ -478,7 +478,16 @@ class Policy:
                            weight_decay, st["steps"] + 1, grad_scale)
         need = C.c_size_t()
         _check(self.lib.rlhf_ppo_update_workspace_bytes(self._h, Bm, L, N, int(counts.max()), C.byref(need)))
-        ws = self._workspace(need.value)
+        # Workspace beyond the minimum lets the loop keep FC1's pre-activations instead of recomputing them (one
+        # [T_max, d_ff] fp16 slice per layer): as many layers as leave 16 GB of the device free.
+        want = need.value
+        if keep_preactivations and self.cfg.dtype != "fp32":
+            per_layer = (int(counts.max()) * self.cfg.d_ff * 2 + 255) // 256 * 256
+            free_b, _ = torch.cuda.mem_get_info()
+            have = self._ws.numel() if self._ws is not None else 0
+            room = free_b + have - need.value - (16 << 30)
+            want += max(0, min(self.cfg.n_layers, room // per_layer)) * per_layer + 256
+        ws = self._workspace(want)
         stats = self._out((epochs * n_minibatches, 8), torch.float32)
         with torch.cuda.device(self.device):
             _check(self.lib.rlhf_ppo_update(self._h, C.byref(uc), C.byref(ts), t.data_ptr(), m.data_ptr(), B, Lq, N,

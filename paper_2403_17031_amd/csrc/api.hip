@@ -297,6 +297,11 @@ struct PassArgs {
   // q_keep_stride bytes instead of the pass's own q buffer (its K / V are kept through kv_per_layer).
   char* q_keep = nullptr;
   size_t q_keep_stride = 0;
+  // ... and, for the first u_keep_layers layers, FC1's output before the GELU (keep_rows rows of d_ff each, layer l at
+  // u_keep + l * u_keep_stride bytes): those layers run FC1 with the plain bias epilogue and the GELU as a pass of its own.
+  char* u_keep = nullptr;
+  size_t u_keep_stride = 0;
+  int u_keep_layers = 0;
 };
 
 int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) {
@@ -510,9 +515,18 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
       LAUNCH("attn_decode", launch_attn_decode(dt, q_l, kc, vc, (long)p.kv_extra, p.B, p.len, p.ctx_add, p.ctx_max,
                                                p.kvoff, c.n_heads, c.head_dim, A.att, s));
     // From here on the order of the additions into x is the serial one: x = (x + attn) + mlp.
+    const bool keep_u = p.mode == 0 && p.u_keep && l < p.u_keep_layers && dt == 1;
+    if (keep_u) {  // FC1 into the kept buffer, GELU from there into where FC2 reads its operand
+      GemmArgs gu = g1;
+      gu.epilogue = EPI_BIAS;
+      gu.out = p.u_keep + (size_t)l * p.u_keep_stride;
+      gu.ldo = c.d_ff;
+      LAUNCH("gemm", launch_gemm(dt, gu, s));
+      LAUNCH("gelu", launch_gelu_rows_f16(gu.out, (size_t)c.d_ff, g1.out, (size_t)g1.ldo, (int)p.keep_rows, c.d_ff, s));
+    }
     if (cat) {
       // x += [att | ffn] [W_o | W_fc2]^T + b_o + b_fc2: one product, one pass over the residual stream
-      LAUNCH("gemm", launch_gemm(dt, g1, s));
+      if (!keep_u) LAUNCH("gemm", launch_gemm(dt, g1, s));
       LAUNCH("gemm", launch_gemm(dt, gcat(l), s));
       continue;
     }
@@ -522,7 +536,7 @@ int run_layers(rlhf_handle* h, const Acts& A, const PassArgs& p, hipStream_t s) 
     if (fork_mlp) {
       HIP_OK(hipStreamWaitEvent(s, join, 0));
     } else {
-      LAUNCH(p.mode ? "gemm_decode_fc1" : "gemm", launch_gemm(dt, g1, s));
+      if (!keep_u) LAUNCH(p.mode ? "gemm_decode_fc1" : "gemm", launch_gemm(dt, g1, s));
       if (fold) g2.phase = 1;
       LAUNCH(p.mode ? "gemm_decode_fc2" : "gemm", launch_gemm(dt, g2, s));
     }
@@ -987,10 +1001,12 @@ int rlhf_mlp_backward_workspace_bytes(const rlhf_handle* h, int32_t T, size_t* o
 
 // Shared work of a layer's two branches inside a whole backward pass (all optional): go16 = the fp16 copy of d_out,
 // [T padded to 128 rows, d] with zero padding rows, made once for both branches together with the column sums that
-// are d_b_fc2 and d_b_o (then neither is computed here); base = what d_x is added to (d_x = base + the branch's term).
+// are d_b_fc2 and d_b_o (then neither is computed here); base = what d_x is added to (d_x = base + the branch's term);
+// kept_u = the MLP branch's pre-activations kept by the forward pass (then FC1 is not recomputed).
 struct BranchShare {
   const void* go16 = nullptr;
   const float* base = nullptr;
+  const void* kept_u = nullptr;  // MLP branch: FC1's output before the GELU as the forward pass left it, [T, d_ff]
 };
 static int mlp_backward_impl(rlhf_handle* h, int32_t layer, const float* x_in, const float* d_out, int32_t T, float* d_x,
                              float* d_ln2_g, float* d_ln2_b, float* d_w_fc1, float* d_b_fc1, float* d_w_fc2,
@@ -1031,8 +1047,10 @@ static int mlp_backward_impl(rlhf_handle* h, int32_t layer, const float* x_in, c
   // ---- the branch's forward, recomputed from the layer input: m = LN2(x), u = m W1^T + b1, f = gelu(u)
   LAUNCH("final_ln", launch_final_ln(dt, x_in, nullptr, 0, T, nullptr, d, c.ln_eps, h->ln2_g[l], h->ln2_b[l], ws.m,
                                      nullptr, 0.f, nullptr, s));
-  LAUNCH("gemm_mlp_fwd", launch_gemm(dt, gemm(ws.m, h->w_fc1[l], h->b_fc1[l], ws.u, T, F, d, EPI_BIAS), s));
-  LAUNCH("gelu", launch_gelu(dt, ws.u, ws.f, (size_t)T * F, s));
+  const void* u = sh.kept_u ? sh.kept_u : ws.u;
+  if (!sh.kept_u)
+    LAUNCH("gemm_mlp_fwd", launch_gemm(dt, gemm(ws.m, h->w_fc1[l], h->b_fc1[l], ws.u, T, F, d, EPI_BIAS), s));
+  LAUNCH("gelu", launch_gelu(dt, u, ws.f, (size_t)T * F, s));
   // ---- FC2: db2 = sum_t G, dW2 = G^T f, df = G W2
   const void* go = sh.go16 ? sh.go16 : ws.go;
   if (!sh.go16) {
@@ -1071,7 +1089,7 @@ static int mlp_backward_impl(rlhf_handle* h, int32_t layer, const float* x_in, c
   LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, h->w_fc2[l], ld_w2, ws.w2T, (size_t)d, d, F, d, s));
   LAUNCH("gemm_mlp_dx", launch_gemm(dt, gemm(go, ws.w2T, nullptr, ws.df, T, F, d, EPI_BIAS), s));
   // ---- GELU, then FC1: du = df * gelu'(u) (in place), db1 = sum_t du, dW1 = du^T m, dm = du W1
-  LAUNCH("gelu", launch_gelu_backward(dt, ws.u, ws.df, (size_t)T * F, s));
+  LAUNCH("gelu", launch_gelu_backward(dt, u, ws.df, (size_t)T * F, s));
   LAUNCH("colsum", launch_colsum(dt, ws.df, T, F, ws.part, ws.splits, d_b_fc1, s));
   if (kmaj) {
     LAUNCH("mlp_bwd_zero", zero_tail(ws.df, F));
@@ -1398,7 +1416,8 @@ int rollout_generate(rlhf_handle* h, const int32_t* queries, const uint8_t* pad_
 // elements that receive every layer's rotated q rows and its K / V cache.
 static int score_forward(rlhf_handle* h, const int32_t* tokens, const uint8_t* mask, int B, int L, ScoreWs& ws,
                          hipStream_t s, float* keep = nullptr, size_t keep_rows = 0, char* keep_q = nullptr,
-                         char* keep_kv = nullptr) {
+                         char* keep_kv = nullptr, char* keep_u = nullptr, size_t keep_u_stride = 0,
+                         int keep_u_layers = 0) {
   const rlhf_model_config& c = h->cfg;
   const Meta& m = ws.meta;
   LAUNCH("row_spans", launch_row_spans(mask, B, L, 0, m.start, m.len, m.cu, m.kvoff, m.total, s));
@@ -1431,6 +1450,11 @@ static int score_forward(rlhf_handle* h, const int32_t* tokens, const uint8_t* m
     p.kv_per_layer = true;
     p.q_keep = keep_q;
     p.q_keep_stride = p.keep_rows * c.d_model * h->esz;
+  }
+  if (keep && keep_u && keep_u_layers > 0) {
+    p.u_keep = keep_u;
+    p.u_keep_stride = keep_u_stride;
+    p.u_keep_layers = keep_u_layers;
   }
   ws.sel_layers = false;
   if (ws.sel_rows) {
@@ -1609,7 +1633,8 @@ static int policy_backward_impl(rlhf_handle* h, const float* x_keep, int64_t x_k
                                 int32_t max_len, const int32_t* targets, const float* d_logprobs, const float* d_values,
                                 float temperature, float grad_scale, const rlhf_grads* g, void* workspace,
                                 size_t workspace_bytes, void* stream, const int* sel, int sel_rows, const int* n_sel,
-                                const char* kept_q = nullptr, const char* kept_kv = nullptr);
+                                const char* kept_q = nullptr, const char* kept_kv = nullptr,
+                                const char* kept_u = nullptr, size_t kept_u_stride = 0, int kept_u_layers = 0);
 
 int rlhf_policy_backward(rlhf_handle* h, const float* x_keep, int64_t x_keep_layer_stride, const int32_t* cu_seqlens,
                          const int32_t* packed_tokens, int32_t B, int32_t T, int32_t max_len, const int32_t* targets,
@@ -1625,7 +1650,8 @@ static int policy_backward_impl(rlhf_handle* h, const float* x_keep, int64_t x_k
                                 int32_t max_len, const int32_t* targets, const float* d_logprobs, const float* d_values,
                                 float temperature, float grad_scale, const rlhf_grads* g, void* workspace,
                                 size_t workspace_bytes, void* stream, const int* sel, int sel_rows, const int* n_sel,
-                                const char* kept_q, const char* kept_kv) {
+                                const char* kept_q, const char* kept_kv, const char* kept_u, size_t kept_u_stride,
+                                int kept_u_layers) {
   // kept_q / kept_kv: what score_forward's keep_q / keep_kv received, with keep_rows = x_keep_layer_stride / d_model
   if (!h || !g) return fail(RLHF_EINVAL, "null argument");
   const rlhf_model_config& c = h->cfg;
@@ -1700,6 +1726,7 @@ static int policy_backward_impl(rlhf_handle* h, const float* x_keep, int64_t x_k
       sm.base = dx;    // dx_m = dx + MLP term
       sa.base = dx_m;  // dx_n = dx_m + attention term
     }
+    if (kept_u && l < kept_u_layers) sm.kept_u = kept_u + (size_t)l * kept_u_stride;
     rc = mlp_backward_impl(h, l, xl, dx, T, dx_m, g->ln2_g[l], g->ln2_b[l], g->w_fc1[l], g->b_fc1[l], g->w_fc2[l],
                            g->b_fc2[l], sub, sub_bytes, stream, sm);
     if (rc) return rc;
@@ -1722,6 +1749,9 @@ struct UpdateWs {
   ScoreWs score;
   char *q_keep = nullptr, *kv_keep = nullptr;  // every layer's rotated q rows and K / V cache (where the backward
                                                // pass's attention kernels read that layout), else null
+  char* u_keep = nullptr;      // FC1 pre-activations of the first u_layers layers: whatever workspace the caller
+  size_t u_stride = 0;         // gave beyond the minimum
+  int u_layers = 0;
   float *x_keep, *lp_full, *val_full, *new_lp, *new_v, *d_lp, *d_v, *gl, *gv;
   int32_t* targets;
   void* bwd;
@@ -1826,6 +1856,12 @@ int rlhf_ppo_update(rlhf_handle* h, const rlhf_ppo_update_config* cfg, const rlh
   UpdateWs ws = carve_update(cv, h, Bm, L, N, T_max);
   if (cv.off + ((char*)cv.base - (char*)workspace) > workspace_bytes)
     return fail(RLHF_ENOMEM, "workspace too small for rlhf_ppo_update");
+  if (bf16 && c.n_layers > 0) {  // what the caller gave beyond the minimum keeps FC1 pre-activations, layer by layer
+    const size_t used = ((cv.off + 255) & ~(size_t)255) + (size_t)((char*)cv.base - (char*)workspace);
+    ws.u_stride = (((size_t)T_max * c.d_ff * h->esz) + 255) & ~(size_t)255;
+    ws.u_layers = (int)std::min<size_t>((size_t)c.n_layers, (workspace_bytes - used) / ws.u_stride);
+    ws.u_keep = ws.u_layers > 0 ? (char*)workspace + used : nullptr;
+  }
   hipStream_t s = (hipStream_t)stream;
   // from here on the value head's bias is the device scalar the optimizer updates
   h->value_b_dev = P.value_b;
@@ -1837,7 +1873,8 @@ int rlhf_ppo_update(rlhf_handle* h, const rlhf_ppo_update_config* cfg, const rlh
       const uint8_t* mask_j = mask + r0 * L;
       const int T = minibatch_tokens[j];
       // forward with the current weights, keeping the layer inputs (packed rows: slices of T rows)
-      rc = score_forward(h, tok_j, mask_j, Bm, L, ws.score, s, ws.x_keep, (size_t)T, ws.q_keep, ws.kv_keep);
+      rc = score_forward(h, tok_j, mask_j, Bm, L, ws.score, s, ws.x_keep, (size_t)T, ws.q_keep, ws.kv_keep, ws.u_keep,
+                         ws.u_stride, ws.u_layers);
       if (rc) return rc;
       rc = score_tail(h, Bm, L, cfg->temperature, ws.score, ws.lp_full, ws.val_full, s);
       if (rc) return rc;
@@ -1852,7 +1889,7 @@ int rlhf_ppo_update(rlhf_handle* h, const rlhf_ppo_update_config* cfg, const rlh
       rc = policy_backward_impl(h, ws.x_keep, (int64_t)T * c.d_model, m.cu, m.tok, Bm, T, max_len, ws.targets, ws.gl,
                                 ws.gv, cfg->temperature, cfg->grad_scale, &G, ws.bwd, ws.bwd_bytes, stream,
                                 ws.score.sel_rows ? ws.score.sel : nullptr, ws.score.sel_rows, ws.score.n_sel,
-                                ws.q_keep, ws.kv_keep);
+                                ws.q_keep, ws.kv_keep, ws.u_keep, ws.u_stride, ws.u_layers);
       if (rc) return rc;
       // AdamW on every tensor; a bf16 model keeps fp32 masters and gets its storage arrays rewritten
       const double inv_scale = 1.0 / (double)cfg->grad_scale;

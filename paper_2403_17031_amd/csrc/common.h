@@ -346,6 +346,8 @@ hipError_t launch_head_ln_backward(int dtype, const float* x, const float* dhl, 
 
 // Element-wise pieces of a layer's backward pass (dtype 0: float activations, 1: fp16).
 hipError_t launch_gelu(int dtype, const void* u, void* f, size_t n, hipStream_t s);            // f = gelu(u)
+// the same on fp16 rows with strides (elements; cols and strides multiples of 8, 16-byte aligned bases)
+hipError_t launch_gelu_rows_f16(const void* u, size_t ld_u, void* f, size_t ld_f, int rows, int cols, hipStream_t s);
 hipError_t launch_gelu_backward(int dtype, const void* u, void* df, size_t n, hipStream_t s);  // df *= gelu'(u)
 hipError_t launch_convert_from_f32(int dtype, const float* src, void* dst, size_t n, hipStream_t s);
 // out[c] = sum_r a[r][c] over a contiguous [R, C] matrix (elem 0: float, 1: fp16); part: [splits][C] scratch.

@@ -613,6 +613,31 @@ hipError_t launch_add3(const float* a, const float* b, const float* c, float* ou
   return hipGetLastError();
 }
 
+// f[r][0..cols) = gelu(u[r][0..cols)) for r < rows, fp16, row strides ld_u / ld_f in elements (all multiples of 8).
+__global__ void __launch_bounds__(256)
+    gelu_rows_f16x8_kernel(const half_t* __restrict__ u, size_t ld_u, half_t* __restrict__ f, size_t ld_f, int rows,
+                           int cols8) {
+  const size_t n = (size_t)rows * cols8, stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    const size_t r = i / cols8, c = i - r * cols8;
+    const f16x8_t v = *(const f16x8_t*)(u + r * ld_u + c * 8);
+    f16x8_t o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float x = (float)v[e];
+      o[e] = from_f32<half_t>(x * phi_cdf_fast(x));
+    }
+    *(f16x8_t*)(f + r * ld_f + c * 8) = o;
+  }
+}
+hipError_t launch_gelu_rows_f16(const void* u, size_t ld_u, void* f, size_t ld_f, int rows, int cols, hipStream_t s) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  if (((cols | ld_u | ld_f) & 7) != 0 || (((uintptr_t)u | (uintptr_t)f) & 15) != 0) return hipErrorInvalidValue;
+  const size_t n = (size_t)rows * (cols / 8);
+  hipLaunchKernelGGL(gelu_rows_f16x8_kernel, dim3((int)std::min<size_t>((n + 255) / 256, 65536)), dim3(256), 0, s,
+                     (const half_t*)u, ld_u, (half_t*)f, ld_f, rows, cols / 8);
+  return hipGetLastError();
+}
 hipError_t launch_gelu(int dtype, const void* u, void* f, size_t n, hipStream_t s) {
   if (n == 0) return hipSuccess;
   const int blocks = (int)std::min<size_t>((n + 255) / 256, 65536);

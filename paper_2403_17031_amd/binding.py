@@ -493,7 +493,7 @@ class Policy:
             _check(self.lib.rlhf_ppo_update(self._h, C.byref(uc), C.byref(ts), t.data_ptr(), m.data_ptr(), B, Lq, N,
                                             *[a.data_ptr() for a in arrs], k.data_ptr(),
                                             counts.ctypes.data_as(C.POINTER(C.c_int32)), max(max_len, 1),
-                                            stats.data_ptr(), ws.data_ptr(), ws.numel(), self._stream()))
+                                            stats.data_ptr(), ws.data_ptr(), want, self._stream()))
         st["steps"] += epochs * n_minibatches
         return stats
 

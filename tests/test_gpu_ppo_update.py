@@ -168,12 +168,14 @@ def test_update_loop_matches_the_oracle_loop(gpu, dtype):
     pol.close()
 
 
-def test_update_loop_with_the_heads_on_the_response_rows_only(gpu):
+@pytest.mark.parametrize("keep", [True, False])
+def test_update_loop_with_the_heads_on_the_response_rows_only(gpu, keep):
     """A batch with enough response rows (40 sequences x 14 columns) for the loop to run the LM head, and the output
     heads' backward pass, on the rows from the last query column on only (the log-probs and values of the other rows
     are never read), at a head size for which the loop keeps every layer's rotated q rows and K / V cache from the
     forward pass instead of recomputing the QKV product in the backward pass: one iteration over the whole batch
-    against the oracle loop, every tensor."""
+    against the oracle loop, every tensor; with workspace for the kept FC1 pre-activations and with the minimum
+    (FC1 recomputed in the backward pass)."""
     from oracle.ppo_update_oracle import ppo_update
     from synth import round_to_bf16
     cfg = ModelConfig(n_layers=2, d_model=128, n_heads=2, head_dim=64, rotary_dims=16, d_ff=256, vocab=200, dtype="bf16",
@@ -197,7 +199,8 @@ def test_update_loop_with_the_heads_on_the_response_rows_only(gpu):
     lp0, v0 = (x.cpu().numpy() for x in pol.score_sequences(tokens, mask, T_))
     old_lp = (lp0[:, Lq:] + g.normal(0, 0.15, (B, N))).astype(np.float32)
     old_v = (v0[:, Lq - 1:Lq - 1 + N] + g.normal(0, 0.15, (B, N))).astype(np.float32)
-    stats = pol.ppo_update(tokens, mask, Lq, old_lp, adv, old_v, ret, kept, T_, epochs=1, n_minibatches=1, **hyp)
+    stats = pol.ppo_update(tokens, mask, Lq, old_lp, adv, old_v, ret, kept, T_, epochs=1, n_minibatches=1,
+                           keep_preactivations=keep, **hyp)
     stats = stats.cpu().numpy()
     st = pol.train_state()
     o_w, _, o_stats = ppo_update(w, cfg, tokens, mask, Lq, old_lp, adv, old_v, ret, kept, T_, epochs=1, n_minibatches=1,

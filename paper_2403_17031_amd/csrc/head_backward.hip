@@ -302,7 +302,6 @@ __global__ void __launch_bounds__(256)
       }
     const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
     float su = 0.f, sux = 0.f;
-    f32x4_t u[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const u32x2_t gb = *(const u32x2_t*)(g + 4 * (lane + 64 * j));
@@ -311,11 +310,11 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         xv[j][e] *= rstd;  // xh
-        u[j][e] = dv[j][e] * gf[e];
-        su += u[j][e];
-        sux += u[j][e] * xv[j][e];
         sg[j][e] += dv[j][e] * xv[j][e];
         sb[j][e] += dv[j][e];
+        dv[j][e] *= gf[e];  // u = dy * g, in place: dy itself is not needed again
+        su += dv[j][e];
+        sux += dv[j][e] * xv[j][e];
       }
     }
     const float mu = wave_sum(su) / (float)d, mux = wave_sum(sux) / (float)d;
@@ -325,7 +324,7 @@ __global__ void __launch_bounds__(256)
     for (int j = 0; j < NV; ++j) {
       f32x4_t r;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) r[e] = rstd * (u[j][e] - mu - xv[j][e] * mux);
+      for (int e = 0; e < 4; ++e) r[e] = rstd * (dv[j][e] - mu - xv[j][e] * mux);
       if (bs) r += bs[lane + 64 * j];
       o[lane + 64 * j] = r;
     }

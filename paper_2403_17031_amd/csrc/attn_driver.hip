@@ -4,7 +4,8 @@
 // plain copy kernel of known size next to it; it also runs and checks the packed causal (prefill /
 // scoring) attention kernel on the same cache.  Like gemm_driver it exists for hardware-counter runs
 // (rocprofv3 --pmc), which work on a small native process but not on the Python benchmark.
-//   usage: attn_driver [batch=256] [reps=5]
+//   usage: attn_driver [batch=256] [reps=5] [layers=1]
+//   (layers > 1: the decode kernel is also timed rotating over that many layers' caches, as a decode pass does)
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -46,6 +47,8 @@ __global__ void __launch_bounds__(256) copy_yardstick_kernel(const u4_t* __restr
 int main(int argc, char** argv) {
   const int B = argc > 1 ? atoi(argv[1]) : 256;
   const int reps = argc > 2 ? atoi(argv[2]) : 5;
+  const int layers = argc > 3 ? atoi(argv[3]) : 1;
+  if (layers < 1 || layers > 64) { printf("layers out of range\n"); return 1; }
   const int H = 32, HD = 80, d = H * HD, N = 53, step = 26;  // mid-rollout decode step
   if (B <= 0 || B > 4096) { printf("batch out of range\n"); return 1; }
   std::vector<int> len(B), kvoff(B + 1);
@@ -114,6 +117,29 @@ int main(int argc, char** argv) {
   const double bytes = ctx_sum * 2.0 * d * 2.0;  // K and V rows of every sequence's context, fp16
   printf("attn_decode B=%d H=%d hd=%d mean context %.1f: %.1f us  algorithmic K/V bytes %.3f GB  %.2f TB/s  max |err| %.2e\n",
          B, H, HD, ctx_sum / B, ms * 1e3, bytes / 1e9, bytes / ms / 1e9, maxerr);
+  if (layers > 1) {  // one cache per layer, visited in turn: every launch finds its K / V cold in the caches and TLBs
+    _Float16* dKV;
+    CK(hipMalloc(&dKV, (size_t)layers * 2 * plane * 2));
+    for (int l = 0; l < layers; ++l) {
+      CK(hipMemcpy(dKV + (size_t)l * 2 * plane, dK, plane * 2, hipMemcpyDeviceToDevice));
+      CK(hipMemcpy(dKV + (size_t)l * 2 * plane + plane, dV, plane * 2, hipMemcpyDeviceToDevice));
+    }
+    CK(hipDeviceSynchronize());
+    const int n = reps * layers;
+    for (int i = 0; i < layers; ++i)
+      CK(launch_attn_decode(1, dq, dKV + (size_t)i * 2 * plane, dKV + (size_t)i * 2 * plane + plane, N - 1, B, dlen, step + 1,
+                            ctx_max, dkvoff, H, HD, dout, 0));
+    CK(hipEventRecord(e0, 0));
+    for (int i = 0; i < n; ++i) {
+      const size_t o = (size_t)(i % layers) * 2 * plane;
+      CK(launch_attn_decode(1, dq, dKV + o, dKV + o + plane, N - 1, B, dlen, step + 1, ctx_max, dkvoff, H, HD, dout, 0));
+    }
+    CK(hipEventRecord(e1, 0)); CK(hipEventSynchronize(e1));
+    float msl; CK(hipEventElapsedTime(&msl, e0, e1)); msl /= n;
+    printf("attn_decode rotating over %d layers' caches (%.1f GB): %.1f us  %.2f TB/s\n", layers,
+           (double)layers * 2 * plane * 2 / 1e9, msl * 1e3, bytes / msl / 1e9);
+    CK(hipFree(dKV));
+  }
   // ---- the packed causal (prefill / scoring) kernel on the same cache: every sequence attends over
   //      all len + 52 rows of its slab, queries packed back to back as the library packs them
   {

@@ -1089,8 +1089,12 @@ static int mlp_backward_impl(rlhf_handle* h, int32_t layer, const float* x_in, c
   LAUNCH("mlp_bwd_transpose", launch_transpose_pad(dt, h->w_fc2[l], ld_w2, ws.w2T, (size_t)d, d, F, d, s));
   LAUNCH("gemm_mlp_dx", launch_gemm(dt, gemm(go, ws.w2T, nullptr, ws.df, T, F, d, EPI_BIAS), s));
   // ---- GELU, then FC1: du = df * gelu'(u) (in place), db1 = sum_t du, dW1 = du^T m, dm = du W1
-  LAUNCH("gelu", launch_gelu_backward(dt, u, ws.df, (size_t)T * F, s));
-  LAUNCH("colsum", launch_colsum(dt, ws.df, T, F, ws.part, ws.splits, d_b_fc1, s));
+  if (gelu_backward_colsum_supported(dt, u, ws.df, F)) {
+    LAUNCH("gelu", launch_gelu_backward_colsum(u, ws.df, T, F, ws.part, ws.splits, d_b_fc1, s));
+  } else {
+    LAUNCH("gelu", launch_gelu_backward(dt, u, ws.df, (size_t)T * F, s));
+    LAUNCH("colsum", launch_colsum(dt, ws.df, T, F, ws.part, ws.splits, d_b_fc1, s));
+  }
   if (kmaj) {
     LAUNCH("mlp_bwd_zero", zero_tail(ws.df, F));
     LAUNCH("mlp_bwd_zero", zero_tail(ws.m, d));

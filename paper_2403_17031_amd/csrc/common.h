@@ -349,6 +349,10 @@ hipError_t launch_gelu(int dtype, const void* u, void* f, size_t n, hipStream_t 
 // the same on fp16 rows with strides (elements; cols and strides multiples of 8, 16-byte aligned bases)
 hipError_t launch_gelu_rows_f16(const void* u, size_t ld_u, void* f, size_t ld_f, int rows, int cols, hipStream_t s);
 hipError_t launch_gelu_backward(int dtype, const void* u, void* df, size_t n, hipStream_t s);  // df *= gelu'(u)
+// the same on an fp16 [R, C] matrix together with the column sums of the result (sums[c]; part: [splits][C] scratch)
+bool gelu_backward_colsum_supported(int dtype, const void* u, const void* df, int C);
+hipError_t launch_gelu_backward_colsum(const void* u, void* df, int R, int C, float* part, int splits, float* sums,
+                                       hipStream_t s);
 hipError_t launch_convert_from_f32(int dtype, const float* src, void* dst, size_t n, hipStream_t s);
 // out[c] = sum_r a[r][c] over a contiguous [R, C] matrix (elem 0: float, 1: fp16); part: [splits][C] scratch.
 hipError_t launch_colsum(int elem, const void* a, int R, int C, float* part, int splits, float* out, hipStream_t s);

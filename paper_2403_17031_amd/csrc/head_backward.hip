@@ -473,6 +473,42 @@ __global__ void __launch_bounds__(256)
     ((f16x8_t*)df)[i] = g;
   }
 }
+// df *= gelu'(u) on a [R, C] fp16 matrix and, in the same pass, the column sums of the result (of the rounded values,
+// as a separate pass over the stored matrix would see them): part [splits][C], rows added in increasing order.
+__global__ void __launch_bounds__(256)
+    gelu_backward_colsum_kernel(const half_t* __restrict__ u, half_t* __restrict__ df, int R, int C, int rows_per_split,
+                                float* __restrict__ part) {
+  const int c0 = (blockIdx.x * 256 + threadIdx.x) * 8;
+  if (c0 >= C) return;
+  const int r0 = blockIdx.y * rows_per_split, r1 = min(R, r0 + rows_per_split);
+  float s[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s[i] = 0.f;
+  for (int r = r0; r < r1; r += 2) {
+    f16x8_t v[2], g[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const size_t o = (size_t)min(r + k, r1 - 1) * C + c0;
+      v[k] = *(const f16x8_t*)(u + o);
+      g[k] = *(const f16x8_t*)(df + o);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      if (r + k < r1) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float x = (float)v[k][e];
+          const float phi = 0.3989422804014327f * __builtin_amdgcn_exp2f(-0.72134752044448170f * x * x);
+          g[k][e] = from_f32<half_t>((float)g[k][e] * (phi_cdf_fast(x) + x * phi));
+          s[e] += (float)g[k][e];
+        }
+        *(f16x8_t*)(df + (size_t)(r + k) * C + c0) = g[k];
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) part[(size_t)blockIdx.y * C + c0 + i] = s[i];
+}
 template <typename T>
 __global__ void __launch_bounds__(256) convert_kernel(const float* __restrict__ src, T* __restrict__ dst, size_t n) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -657,6 +693,18 @@ hipError_t launch_gelu_backward(int dtype, const void* u, void* df, size_t n, hi
                        0, s, (const half_t*)u, (half_t*)df, n / 8);
   else
     hipLaunchKernelGGL(gelu_backward_kernel<half_t>, dim3(blocks), dim3(256), 0, s, (const half_t*)u, (half_t*)df, n);
+  return hipGetLastError();
+}
+bool gelu_backward_colsum_supported(int dtype, const void* u, const void* df, int C) {
+  return dtype == 1 && (C & 7) == 0 && (((uintptr_t)u | (uintptr_t)df) & 15) == 0;
+}
+hipError_t launch_gelu_backward_colsum(const void* u, void* df, int R, int C, float* part, int splits, float* sums,
+                                       hipStream_t s) {
+  if (R <= 0 || C <= 0) return hipSuccess;
+  const int rps = (R + splits - 1) / splits;
+  hipLaunchKernelGGL(gelu_backward_colsum_kernel, dim3((C / 8 + 255) / 256, splits), dim3(256), 0, s, (const half_t*)u,
+                     (half_t*)df, R, C, rps, part);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((C + 255) / 256), dim3(256), 0, s, part, splits, C, sums);
   return hipGetLastError();
 }
 hipError_t launch_convert_from_f32(int dtype, const float* src, void* dst, size_t n, hipStream_t s) {

@@ -140,6 +140,40 @@ int main(int argc, char** argv) {
            s.K, ms, fl / ms / 1e9, bytes / 1e9, maxerr);
   }
   {
+    // the weight-gradient form: out [d, F] = A^T W with both operands K-major ([K, d] and [K, F] row-major, K = the
+    // rows rounded down to 128), K cut into slices whose fp32 slabs are summed -- as the backward pass runs dW_fc2
+    const int Kk = (M / 128) * 128;
+    const uint16_t *hAt = hA.data(), *hWt = hA.data() + (size_t)Kk * d;  // the same host data, read as [Kk, d] | [Kk, F]
+    void* dslab;
+    const size_t slab_bytes = (size_t)8 * d * F * 4;
+    CK(hipMalloc(&dslab, slab_bytes));
+    GemmArgs g;
+    g.A = dA; g.W = dA + (size_t)Kk * d; g.bias = nullptr; g.out = dO;
+    g.M_max = d; g.M_dev = nullptr; g.N = F; g.K = Kk; g.ldo = F; g.epilogue = EPI_F32;
+    g.k_major = true; g.long_k = true; g.splitk_ws = dslab; g.splitk_ws_bytes = slab_bytes;
+    if (!gemm_takes_k_major(1, g)) { printf("the K-major form does not take this shape\n"); return 1; }
+    CK(launch_gemm(1, g, 0)); CK(hipDeviceSynchronize());
+    std::vector<float> ho((size_t)d * F);
+    CK(hipMemcpy(ho.data(), dO, ho.size() * 4, hipMemcpyDeviceToHost));
+    double maxerr = 0, maxabs = 0;
+    for (int t = 0; t < 200; ++t) {
+      const int m = t < 4 ? (t % 2 ? d - 1 : 0) : rand() % d, n = t < 4 ? (t < 2 ? 0 : F - 1) : rand() % F;
+      double acc = 0;
+      for (int k = 0; k < Kk; ++k) acc += (double)h2f(hAt[(size_t)k * d + m]) * h2f(hWt[(size_t)k * F + n]);
+      const double err = fabs(ho[(size_t)m * F + n] - acc);
+      if (err > maxerr) maxerr = err;
+      if (fabs(acc) > maxabs) maxabs = fabs(acc);
+      if (err > 2e-3 * fmax(1.0, fabs(acc)) + 2e-2) { printf("MISMATCH k-major m=%d n=%d got %f want %f\n", m, n, ho[(size_t)m * F + n], acc); ++bad; break; }
+    }
+    CK(hipEventRecord(e0, 0));
+    for (int i = 0; i < reps; ++i) CK(launch_gemm(1, g, 0));
+    CK(hipEventRecord(e1, 0)); CK(hipEventSynchronize(e1));
+    float ms; CK(hipEventElapsedTime(&ms, e0, e1)); ms /= reps;
+    printf("dW k-major M=%d N=%d K=%d: %.3f ms  %.1f TFLOP/s  max |err| %.2e (largest |value| %.1f)\n", d, F, Kk, ms,
+           2.0 * d * F * (double)Kk / ms / 1e9, maxerr, maxabs);
+    CK(hipFree(dslab));
+  }
+  {
     const size_t n = (size_t)1 << 26;  // 1 GiB read + 1 GiB written
     u4_t *src = (u4_t*)dA, *dst = (u4_t*)dO;
     if (maxA * 2 < n * 16 || maxO * 4 < n * 16) { printf("copy yardstick skipped: buffers smaller than 1 GiB\n"); }

@@ -1,10 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the rollout + rescoring hot path on one MI355X.
 
-One "step" = rollout_generate on a synthetic left-padded query batch, then score_responses (the teacher-forced
-forward pass that yields the response positions' log-probabilities and values; --score-all-columns runs
-score_sequences, which also produces the query positions' that PPO never reads) on the rollout's own (tokens,
-mask) output.  Inputs are resident in HBM before the timed region.  Prints
+One "step" = rollout_generate on a synthetic left-padded query batch, then score_sequences (the teacher-forced
+forward pass that yields every position's log-probability and value) on the rollout's own (tokens, mask) output.
+score_responses, the same pass restricted to the response positions PPO reads, is timed beside it (outside the
+timed region) and reported as `score_responses`; --score-responses makes it the step's rescoring call.  Inputs are resident in HBM before the timed region.  Prints
 ONE JSON line (see README for the fields)."""
 import argparse
 import json
@@ -113,9 +113,9 @@ def main():
                     help="skip the PPO-update leg (forward keeping activations, backward, AdamW; ~10 s at config 4)")
     ap.add_argument("--profile-update", action="store_true",
                     help="add per-kernel times of one more update iteration to the ppo_update object")
-    ap.add_argument("--score-all-columns", action="store_true",
-                    help="rescoring with score_sequences (log-probs and values of the query columns too) instead of "
-                         "score_responses")
+    ap.add_argument("--score-responses", action="store_true",
+                    help="rescoring with score_responses (log-probs and values of the response columns only) instead of "
+                         "score_sequences")
     ap.add_argument("--extra-score-shapes", action="store_true",
                     help="also time score_sequences on the paper's other batch shapes: right-padded (B,638) and (B,2021)")
     a = ap.parse_args()
@@ -143,9 +143,9 @@ def main():
     setup_s = time.time() - t0
 
     def score(toks, omask):
-        if a.score_all_columns:
-            return pol.score_sequences(toks, omask, wl.temperature)
-        return pol.score_responses(toks, omask, wl.query_len, wl.temperature)
+        if a.score_responses:
+            return pol.score_responses(toks, omask, wl.query_len, wl.temperature)
+        return pol.score_sequences(toks, omask, wl.temperature)
 
     def step():
         toks, lps, lens, omask = pol.rollout_generate(q_d, m_d, wl.sample_seed, wl.temperature, N, return_mask=True)
@@ -170,7 +170,20 @@ def main():
     prefill_ms, decode_ms = pol.last_rollout_phases()
     lens = r[2].cpu().numpy()
     n_true = mask.sum(1)
-    wc = work_counts(cfg, n_true, lens, N, score_all=a.score_all_columns)
+    wc = work_counts(cfg, n_true, lens, N, score_all=not a.score_responses)
+    # the restricted rescoring call beside the full one (outside the timed region): what a PPO step would run
+    wc_r = work_counts(cfg, n_true, lens, N, score_all=False)
+    er = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    pol.score_responses(r[0], r[3], wl.query_len, wl.temperature)
+    er[0].record()
+    pol.score_responses(r[0], r[3], wl.query_len, wl.temperature)
+    er[1].record()
+    torch.cuda.synchronize()
+    sr_ms = er[0].elapsed_time(er[1])
+    score_resp = {"ms": sr_ms, "mfma_frac": wc_r["score_flops"] / (sr_ms * 1e-3) / MFMA_PEAK,
+                  "step_ms_with_it": roll_ms + sr_ms, "step_tok_s_with_it": B * N / ((roll_ms + sr_ms) * 1e-3),
+                  "note": "score_responses(first_col = query length): log-probs of the response columns and values "
+                          "from the last query column on; flops counted as that pass needs them"}
 
     # one more step with per-kernel HIP events (outside the timed region) for the roofline object
     pol.profile_enable(True)
@@ -420,7 +433,7 @@ def main():
     ms_step = wall / a.steps * 1e3
     out = {
         "metric": "rollout generated tokens/s (rollout_generate + %s per step)" % (
-            "score_sequences" if a.score_all_columns else "score_responses"),
+            "score_responses" if a.score_responses else "score_sequences"),
         "value": B * N / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if cfg.dtype == "fp32" else "f16 operands / f32 accumulate (bf16 weights)",
@@ -437,6 +450,7 @@ def main():
         "rescoring_tok_s": wc["real_score_tokens"] / (score_ms * 1e-3), "score_ms": score_ms,
         "rescoring_tok_s_padded": B * (wl.query_len + N) / (score_ms * 1e-3),
         "score_mfma_frac": wc["score_flops"] / (score_ms * 1e-3) / MFMA_PEAK,
+        "score_responses": score_resp,
         "roofline": roof, "rooflines": rooflines, "kernels_ms": kern, "profiled_step_ms": tot,
         "ceilings": ceil,
         "decode_frac_of_measured_stream": (wc["decode_bytes"] / (decode_ms * 1e-3) / (ceil["stream_read_GBps"] * 1e9)) if ceil else None,

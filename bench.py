@@ -4,8 +4,8 @@
 One "step" = rollout_generate on a synthetic left-padded query batch, then score_sequences (the teacher-forced
 forward pass that yields every position's log-probability and value) on the rollout's own (tokens, mask) output.
 score_responses, the same pass restricted to the response positions PPO reads, is timed beside it (outside the
-timed region) and reported as `score_responses`; --score-responses makes it the step's rescoring call.  Inputs are resident in HBM before the timed region.  Prints
-ONE JSON line (see README for the fields)."""
+timed region) and reported as `score_responses`; --score-responses makes it the step's rescoring call.  Inputs are
+resident in HBM before the timed region.  Prints ONE JSON line."""
 import argparse
 import json
 import os
@@ -120,8 +120,8 @@ def main():
                     help="also time score_sequences on the paper's other batch shapes: right-padded (B,638) and (B,2021)")
     a = ap.parse_args()
     if a.gpus != 1:
-        sys.exit("bench.py: this build is single-GPU (sequences are independent; see DESIGN.md on sharding); "
-                 "--gpus must be 1")
+        sys.exit("bench.py: this build runs on one GPU (sequences are independent, so a batch would shard by "
+                 "sequence with no communication inside a pass; that is not built here): --gpus must be 1")
 
     import numpy as np
     import torch

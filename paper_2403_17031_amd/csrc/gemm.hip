@@ -440,8 +440,9 @@ __global__ void __launch_bounds__(64 * WAVES, 1)
   // sub-step from (LS, CH) into (GA, GW) and, if LOAD, tile load n of the stage at K offset KL
 #define RLHF_SUB(FA, FW, LS, CH, GA, GW, LOAD, LSTAGE, KL)                                        \
   _Pragma("unroll") for (int n = 0; n < NMF; ++n) {                                               \
-    acc[n >> 2][n & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(FW[n >> 2], FA[n & 3],            \
-                                                                acc[n >> 2][n & 3], 0, 0, 0);     \
+    const int mi = ((n >> 2) & 1) ? 3 - (n & 3) : (n & 3); /* serpentine: one operand changes at a time */ \
+    acc[n >> 2][mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(FW[n >> 2], FA[mi],                  \
+                                                             acc[n >> 2][mi], 0, 0, 0);           \
     __builtin_amdgcn_sched_barrier(0);                                                            \
     if (n < MT + NT) frag_one(LS, CH, n, GA, GW);                                                 \
     if (LOAD && n < NLD) load_one(LSTAGE, KL, n);                                                 \

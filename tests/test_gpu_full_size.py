@@ -20,13 +20,14 @@ def _run_full(P, idx):
     toks, lps, lens, omask = pol.rollout_generate(queries, mask, wl.sample_seed, wl.temperature, wl.new_tokens,
                                                   return_mask=True)
     glp, gval = pol.score_sequences(toks, omask, wl.temperature)
-    out = [x.cpu().numpy() for x in (toks, lps, lens, omask, glp, gval)]
+    rlp, rval = pol.score_responses(toks, omask, queries.shape[1], wl.temperature)
+    out = [x.cpu().numpy() for x in (toks, lps, lens, omask, glp, gval, rlp, rval)]
     pol.close()
     return wl, w, queries, mask, out
 
 
 def _check_any_size_properties(wl, queries, mask, out):
-    toks, lps, lens, omask, glp, gval = out
+    toks, lps, lens, omask, glp, gval, rlp, rval = out
     B, Lq = queries.shape
     N = wl.new_tokens
     cfg = wl.model
@@ -46,11 +47,17 @@ def _check_any_size_properties(wl, queries, mask, out):
     first = np.argmax(omask, axis=1)
     assert (glp[np.arange(B), first] == 0).all()
     assert np.isfinite(glp).all() and np.isfinite(gval).all() and (glp <= 0).all()
+    # the pass restricted to the response columns (PPO Details: what the losses read): zeros before the first response
+    # column (values: before the last query column), elsewhere the full pass's outputs up to the rounding order of the
+    # kernel variants its smaller row count selects -- a tenth of the parity bar
+    assert (rlp[:, :Lq] == 0).all() and (rval[:, :Lq - 1] == 0).all()
+    assert np.abs(rlp[:, Lq:] - glp[:, Lq:]).max() <= TOL / 10
+    assert np.abs(rval[:, Lq - 1:] - gval[:, Lq - 1:]).max() <= TOL / 10 * max(1.0, float(np.abs(gval).max()))
 
 
 def _grade_rows(wl, w, queries, mask, out, rows):
     from oracle import neox_oracle as O
-    toks, lps, lens, omask, glp, gval = out
+    toks, lps, lens, omask, glp, gval = out[:6]
     Lq = queries.shape[1]
     m = O.OracleModel(w, wl.model, cache_f64=False)
     rep = O.verify_rollout(m, toks, mask, wl.sample_seed, wl.temperature, wl.new_tokens, rows=rows)

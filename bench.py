@@ -116,8 +116,8 @@ def main():
     ap.add_argument("--score-responses", action="store_true",
                     help="rescoring with score_responses (log-probs and values of the response columns only) instead of "
                          "score_sequences")
-    ap.add_argument("--extra-score-shapes", action="store_true",
-                    help="also time score_sequences on the paper's other batch shapes: right-padded (B,638) and (B,2021)")
+    ap.add_argument("--no-extra-score-shapes", action="store_true",
+                    help="skip timing score_sequences on the paper's other batch shapes: right-padded (B,638) and (B/4,2021)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (sequences are independent, so a batch would shard by "
@@ -358,6 +358,31 @@ def main():
                                            "avg_launch_ms": attn_bwd_ms, "rows": T_ab}
         del qkvg, ab
 
+    # The paper's other scoring shapes (reward-model batches of 638 tokens, long-context batches of 2021),
+    # right-padded with true lengths uniform in [L/4, L]; outside the headline metric.
+    extra = None
+    if not a.no_extra_score_shapes:
+        extra = {}
+        for L, Bx in ((638, B), (2021, max(1, B // 4))):
+            g = np.random.default_rng(wl.data_seed + L)
+            xl = g.integers(L // 4, L + 1, Bx)
+            xt = g.integers(1, cfg.pad_id, (Bx, L)).astype(np.int32)
+            xm = (np.arange(L)[None, :] < xl[:, None]).astype(np.uint8)
+            xt[xm == 0] = cfg.pad_id
+            xt_d, xm_d = torch.from_numpy(xt).cuda(), torch.from_numpy(xm).cuda()
+            pol.score_sequences(xt_d, xm_d, 1.0)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            pol.score_sequences(xt_d, xm_d, 1.0)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            n_ = xl.astype(np.float64)
+            Lc, d_, F_, V_ = cfg.n_layers, cfg.d_model, cfg.d_ff, cfg.vocab
+            fl = float((n_ * (2 * Lc * (4 * d_ * d_ + 2 * d_ * F_) + 2 * V_ * d_) + Lc * 4 * d_ * n_ * (n_ + 1) / 2).sum())
+            extra[f"B{Bx}xL{L}"] = {"ms": ms, "real_tok_s": float(xl.sum()) / (ms * 1e-3),
+                                    "mfma_frac": fl / (ms * 1e-3) / MFMA_PEAK}
+
     # One iteration of the PPO update over the rollout batch through rlhf_ppo_update (outside the headline metric):
     # forward pass keeping the layer inputs, the clipped objective, the whole backward pass, AdamW over every weight
     # and the refresh of the fp16 weight image; the paper's update is K = 4 such iterations.  Advantages and returns
@@ -395,31 +420,6 @@ def main():
             update["kernels_ms"] = {k: {"ms": round(v[0], 3), "launches": v[1]}
                                     for k, v in sorted(up.items(), key=lambda kv: -kv[1][0])}
         pol._train = None
-
-    # The paper's other scoring shapes (reward-model batches of 638 tokens, long-context batches of 2021),
-    # right-padded with true lengths uniform in [L/4, L]; outside the headline metric.
-    extra = None
-    if a.extra_score_shapes:
-        extra = {}
-        for L, Bx in ((638, B), (2021, max(1, B // 4))):
-            g = np.random.default_rng(wl.data_seed + L)
-            xl = g.integers(L // 4, L + 1, Bx)
-            xt = g.integers(1, cfg.pad_id, (Bx, L)).astype(np.int32)
-            xm = (np.arange(L)[None, :] < xl[:, None]).astype(np.uint8)
-            xt[xm == 0] = cfg.pad_id
-            xt_d, xm_d = torch.from_numpy(xt).cuda(), torch.from_numpy(xm).cuda()
-            pol.score_sequences(xt_d, xm_d, 1.0)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            pol.score_sequences(xt_d, xm_d, 1.0)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1)
-            n_ = xl.astype(np.float64)
-            Lc, d_, F_, V_ = cfg.n_layers, cfg.d_model, cfg.d_ff, cfg.vocab
-            fl = float((n_ * (2 * Lc * (4 * d_ * d_ + 2 * d_ * F_) + 2 * V_ * d_) + Lc * 4 * d_ * n_ * (n_ + 1) / 2).sum())
-            extra[f"B{Bx}xL{L}"] = {"ms": ms, "real_tok_s": float(xl.sum()) / (ms * 1e-3),
-                                    "mfma_frac": fl / (ms * 1e-3) / MFMA_PEAK}
 
     cpu = None
     if not a.no_cpu_baseline:
